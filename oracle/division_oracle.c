@@ -1,0 +1,369 @@
+/*
+ * DIVISION activation codec -- CPU ORACLE.
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is a plain, slow, obviously-correct
+ * scalar implementation of what the codec computes, used only by the tests,
+ * by the smoke check and by the benchmark's CPU-baseline leg.  The product
+ * (the HIP library) shares no code, header, table or constant generator with
+ * it, and never calls it.
+ *
+ * What is computed (paper: "DIVISION: Memory Efficient Training via Dual
+ * Activation Precision", Sec. 4.1 compression, Sec. 4.2 decompression,
+ * Eq. (quantization), the reconstruction equation, Algorithm 1 steps
+ * "AveragePooling / UpSampling / Quant / Cache" and "Dequant / UpSampling+add";
+ * Appendix D for the pooled shapes):
+ *
+ *   for every (sample, channel) plane of an NCHW tensor
+ *     H^L   = average pooling of the plane, window = stride = B      (Sec. 4.1)
+ *     H^H   = H - UpSampling(H^L)          (nearest, block replicate) (Sec. 4.1)
+ *     delta = min H^H, h_max = max H^H, Delta = (h_max-delta)/(2^Q-1) (Eq. quantization)
+ *     V     = stochastic_round( Delta^-1 (H^H - delta) )              (Eq. quantization)
+ *     cache (H^L, V packed Q bits per element, Delta, delta)          (Sec. 4.1, last paragraph)
+ *   and back
+ *     H^H~  = Delta * V + delta                                       (Sec. 4.2)
+ *     H~    = UpSampling(H^L) + H^H~                                  (reconstruction equation)
+ *
+ * Readings taken where the paper is silent or at odds with itself (each is
+ * listed with its reason in the design document of this repository):
+ *   - pooled size is ceil(H/B) x ceil(W/B); edge windows average only their
+ *     valid elements.  Identical to the paper whenever B divides the map size
+ *     and whenever the map is smaller than B (one window covering the map).
+ *   - one (delta, Delta) pair per (sample, channel) plane, stored as fp32.
+ *   - stochastic rounding rounds UP with probability frac(x) (the unbiased
+ *     rule the paper's second footnote on Eq. (quantization) requires).
+ *   - a plane whose residual range is below 2^-90 is degenerate: Delta = 0,
+ *     all codes 0.
+ *   - the scale factor is inv = fl((2^Q-1)/range), bumped by one ulp when
+ *     fl(range*inv) would fall short of 2^Q-1, so that the plane's maximum
+ *     always receives the top code.
+ *   - the random numbers are 16 bits per element from a counter-based hash of
+ *     (seed, plane, element-pair index); the paper names no generator.
+ *   - the residual is taken against the LFC as stored (after rounding to the
+ *     storage type), so that decompression sees exactly what compression used.
+ *
+ * Arithmetic: every "fp32 op" below is one IEEE-754 binary32 operation,
+ * round-to-nearest-even, never fused.  Compile with -ffp-contract=off and
+ * without -ffast-math.  Block means are accumulated in binary64.
+ *
+ * Parity pins: tests/test_oracle_pins.py checks this file against worked
+ * examples, closed forms, library pooling/upsampling, a brute-force
+ * exact-rational re-derivation and statistical properties.  The random
+ * generator has no counterpart in the paper: its pins are this build's own
+ * known-answer vectors (an independent big-integer evaluation) and
+ * statistical tests.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#include <math.h>
+#include <stdlib.h>
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+
+/* ---------- storage types ------------------------------------------------ */
+
+static float bf16_to_float(uint16_t v)
+{
+    uint32_t u = (uint32_t)v << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* round-to-nearest-even fp32 -> bfloat16 (NaN kept quiet) */
+static uint16_t float_to_bf16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7fffu + lsb;
+    return (uint16_t)(u >> 16);
+}
+
+static float load_elem(const void *x, int dt, size_t idx)
+{
+    if (dt == ORACLE_BF16)
+        return bf16_to_float(((const uint16_t *)x)[idx]);
+    return ((const float *)x)[idx];
+}
+
+static size_t elem_size(int dt) { return dt == ORACLE_BF16 ? 2u : 4u; }
+
+static size_t align16(size_t v) { return (v + 15u) & ~(size_t)15u; }
+
+/* ---------- random source (paper silent; defined by this build) ---------- */
+
+/* 32-bit xorshift-multiply integer finaliser (shifts 16/15/16). */
+static uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x ^= x >> 15;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+/* the two per-plane keys derived from the 64-bit seed and the plane index */
+void oracle_plane_keys(uint64_t seed, uint32_t plane, uint32_t *k1, uint32_t *k2)
+{
+    uint32_t a = mix32((uint32_t)(seed & 0xffffffffu) ^ 0x243F6A88u);
+    uint32_t c = mix32((uint32_t)(seed >> 32) ^ 0x85A308D3u);
+    *k1 = mix32(plane ^ a);
+    *k2 = mix32(*k1 + c);
+}
+
+/* one 32-bit random word per PAIR of elements: j = (index in plane) >> 1 */
+uint32_t oracle_hash32(uint64_t seed, uint32_t plane, uint32_t j)
+{
+    uint32_t k1, k2;
+    oracle_plane_keys(seed, plane, &k1, &k2);
+    uint32_t x = k1 + j * 0x9E3779B9u;
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x = x ^ (x >> 15) ^ k2;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+/* n consecutive words of one plane's stream (test aid for statistical checks) */
+void oracle_hash32_fill(uint64_t seed, uint32_t plane, uint32_t j0, size_t n, uint32_t *out)
+{
+    for (size_t k = 0; k < n; ++k)
+        out[k] = oracle_hash32(seed, plane, j0 + (uint32_t)k);
+}
+
+/* the 16 random bits of element i of a plane */
+uint32_t oracle_rand16(uint64_t seed, uint32_t plane, uint32_t i)
+{
+    uint32_t w = oracle_hash32(seed, plane, i >> 1);
+    return (i & 1u) ? (w >> 16) : (w & 0xffffu);
+}
+
+/* ---------- packed layout ------------------------------------------------ */
+
+typedef struct {
+    size_t P, HW, LH, LW, WPP;
+    size_t codes_off, codes_bytes, meta_off, meta_bytes, lfc_off, lfc_bytes, total;
+} layout_t;
+
+static int make_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt, layout_t *L)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4))
+        return 1;
+    if (dt != ORACLE_F32 && dt != ORACLE_BF16)
+        return 1;
+    L->P = (size_t)N * (size_t)C;
+    L->HW = (size_t)H * (size_t)W;
+    L->LH = ((size_t)H + (size_t)B - 1) / (size_t)B;
+    L->LW = ((size_t)W + (size_t)B - 1) / (size_t)B;
+    size_t cpw = 32u / (unsigned)b;
+    L->WPP = (L->HW + cpw - 1) / cpw;
+    L->codes_off = 0;
+    L->codes_bytes = 4u * L->P * L->WPP;
+    L->meta_off = align16(L->codes_bytes);
+    L->meta_bytes = 8u * L->P;
+    L->lfc_off = align16(L->meta_off + L->meta_bytes);
+    L->lfc_bytes = elem_size(dt) * L->P * L->LH * L->LW;
+    L->total = align16(L->lfc_off + L->lfc_bytes);
+    return 0;
+}
+
+size_t oracle_packed_bytes(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt)
+{
+    layout_t L;
+    if (make_layout(N, C, H, W, B, b, dt, &L))
+        return 0;
+    return L.total;
+}
+
+int oracle_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt,
+                         size_t *codes_off, size_t *codes_bytes, size_t *meta_off,
+                         size_t *meta_bytes, size_t *lfc_off, size_t *lfc_bytes)
+{
+    layout_t L;
+    if (make_layout(N, C, H, W, B, b, dt, &L))
+        return 1;
+    *codes_off = L.codes_off; *codes_bytes = L.codes_bytes;
+    *meta_off = L.meta_off;   *meta_bytes = L.meta_bytes;
+    *lfc_off = L.lfc_off;     *lfc_bytes = L.lfc_bytes;
+    return 0;
+}
+
+/* ---------- one plane, step by step -------------------------------------- */
+
+/* Sec. 4.1: H^L = AveragePooling(H), window = stride = B, clipped at the
+ * border.  The mean is the exact sum (binary64 accumulation, row-major)
+ * divided by the element count, rounded once to fp32, then rounded to the
+ * storage type.  lfc_f receives the stored value widened back to fp32. */
+static void plane_lfc(const void *x, int dt, size_t base, size_t H, size_t W, size_t B,
+                      size_t LH, size_t LW, float *lfc_f)
+{
+    for (size_t bi = 0; bi < LH; ++bi) {
+        for (size_t bj = 0; bj < LW; ++bj) {
+            size_t r1 = (bi + 1) * B < H ? (bi + 1) * B : H;
+            size_t c1 = (bj + 1) * B < W ? (bj + 1) * B : W;
+            double S = 0.0;
+            size_t cnt = 0;
+            for (size_t r = bi * B; r < r1; ++r)
+                for (size_t c = bj * B; c < c1; ++c) {
+                    S += (double)load_elem(x, dt, base + r * W + c);
+                    ++cnt;
+                }
+            float m = (float)(S / (double)cnt);
+            if (dt == ORACLE_BF16)
+                m = bf16_to_float(float_to_bf16(m));
+            lfc_f[bi * LW + bj] = m;
+        }
+    }
+}
+
+/* Eq. (quantization): per-plane scale.  Returns delta, Delta and the scale inv. */
+static void plane_scale(const float *h, size_t HW, int b, float *delta, float *Delta, float *inv)
+{
+    float lo = h[0], hi = h[0];
+    for (size_t i = 1; i < HW; ++i) {
+        if (h[i] < lo) lo = h[i];
+        if (h[i] > hi) hi = h[i];
+    }
+    const float Lf = (float)((1 << b) - 1);
+    volatile float range = hi - lo;                 /* fp32 sub */
+    *delta = lo;
+    if (range >= 0x1p-90f && range <= 3.4028234663852886e38f) {
+        volatile float D = range / Lf;              /* fp32 div */
+        volatile float s = Lf / range;              /* fp32 div */
+        volatile float top = range * s;             /* fp32 mul */
+        if (top < Lf)
+            s = nextafterf(s, INFINITY);
+        *Delta = D;
+        *inv = s;
+    } else {
+        *Delta = 0.0f;
+        *inv = 0.0f;
+    }
+}
+
+/*
+ * Compress.  x: N*C*H*W elements of type dt (host memory, NCHW contiguous).
+ * packed: oracle_packed_bytes(...) bytes, fully written (pad bytes zero).
+ * Optional debug outputs (may be NULL), each N*C*H*W long:
+ *   t_out   the fp32 pre-round value t = fl(fl(h - delta) * inv)
+ *   r_out   the 16 random bits used for the element
+ *   h_out   the fp32 residual h
+ * Planes are independent; `threads` > 1 distributes them over OpenMP threads
+ * (no arithmetic is reordered by that).  Returns 0, or 1 on invalid arguments.
+ */
+int oracle_compress(const void *x, int64_t N, int64_t C, int64_t H, int64_t W, int dt,
+                    int B, int b, uint64_t seed, void *packed,
+                    float *t_out, uint16_t *r_out, float *h_out, int threads)
+{
+    layout_t L;
+    if (!x || !packed || make_layout(N, C, H, W, B, b, dt, &L))
+        return 1;
+    if (L.P > 0x7fffffffu || L.HW > 0x7fffffffu)
+        return 1;
+    memset(packed, 0, L.total);
+    uint8_t *pk = (uint8_t *)packed;
+    const uint32_t Lq = (1u << b) - 1u;
+    const size_t cpw = 32u / (unsigned)b;
+    if (threads < 1) threads = 1;
+
+    #pragma omp parallel for schedule(static) num_threads(threads)
+    for (int64_t pp = 0; pp < (int64_t)L.P; ++pp) {
+        size_t p = (size_t)pp;
+        size_t base = p * L.HW;
+        float *lfc_f = (float *)malloc(sizeof(float) * L.LH * L.LW);
+        float *h = (float *)malloc(sizeof(float) * L.HW);
+
+        plane_lfc(x, dt, base, (size_t)H, (size_t)W, (size_t)B, L.LH, L.LW, lfc_f);
+
+        /* store H^L in the storage type */
+        for (size_t k = 0; k < L.LH * L.LW; ++k) {
+            if (dt == ORACLE_BF16)
+                ((uint16_t *)(pk + L.lfc_off))[p * L.LH * L.LW + k] = float_to_bf16(lfc_f[k]);
+            else
+                ((float *)(pk + L.lfc_off))[p * L.LH * L.LW + k] = lfc_f[k];
+        }
+
+        /* Sec. 4.1: H^H = H - UpSampling(H^L), nearest = block replicate */
+        for (size_t r = 0; r < (size_t)H; ++r)
+            for (size_t c = 0; c < (size_t)W; ++c) {
+                volatile float d = load_elem(x, dt, base + r * W + c)
+                                   - lfc_f[(r / B) * L.LW + (c / B)];
+                h[r * W + c] = d;
+            }
+
+        float delta, Delta, inv;
+        plane_scale(h, L.HW, b, &delta, &Delta, &inv);
+        ((float *)(pk + L.meta_off))[2 * p + 0] = delta;
+        ((float *)(pk + L.meta_off))[2 * p + 1] = Delta;
+
+        uint32_t *codes = (uint32_t *)(pk + L.codes_off) + p * L.WPP;
+        for (size_t i = 0; i < L.HW; ++i) {
+            uint32_t r16 = oracle_rand16(seed, (uint32_t)p, (uint32_t)i);
+            volatile float d = h[i] - delta;        /* fp32 sub */
+            volatile float t = d * inv;             /* fp32 mul */
+            /* floor(t + u), u = r16 / 2^16, evaluated exactly in binary64:
+             * t has <= 24 significant bits and lies in [0, 16], u has 16
+             * fraction bits, so the sum needs < 53 bits. */
+            double s = floor((double)t + (double)r16 / 65536.0);
+            uint32_t q = s < 0.0 ? 0u : (uint32_t)s;
+            if (q > Lq) q = Lq;
+            codes[i / cpw] |= q << ((i % cpw) * (unsigned)b);
+            if (t_out) t_out[base + i] = t;
+            if (r_out) r_out[base + i] = (uint16_t)r16;
+            if (h_out) h_out[base + i] = h[i];
+        }
+        free(h);
+        free(lfc_f);
+    }
+    return 0;
+}
+
+/*
+ * Decompress (Sec. 4.2 and the reconstruction equation):
+ *   hh = fl(q * Delta); hh = fl(hh + delta); v = fl(lfc + hh); xhat = (T)v.
+ */
+int oracle_decompress(const void *packed, int64_t N, int64_t C, int64_t H, int64_t W, int dt,
+                      int B, int b, void *xhat, int threads)
+{
+    layout_t L;
+    if (!xhat || !packed || make_layout(N, C, H, W, B, b, dt, &L))
+        return 1;
+    const uint8_t *pk = (const uint8_t *)packed;
+    const uint32_t Lq = (1u << b) - 1u;
+    const size_t cpw = 32u / (unsigned)b;
+    if (threads < 1) threads = 1;
+
+    #pragma omp parallel for schedule(static) num_threads(threads)
+    for (int64_t pp = 0; pp < (int64_t)L.P; ++pp) {
+        size_t p = (size_t)pp;
+        const uint32_t *codes = (const uint32_t *)(pk + L.codes_off) + p * L.WPP;
+        float delta = ((const float *)(pk + L.meta_off))[2 * p + 0];
+        float Delta = ((const float *)(pk + L.meta_off))[2 * p + 1];
+        for (size_t r = 0; r < (size_t)H; ++r)
+            for (size_t c = 0; c < (size_t)W; ++c) {
+                size_t i = r * (size_t)W + c;
+                uint32_t q = (codes[i / cpw] >> ((i % cpw) * (unsigned)b)) & Lq;
+                size_t k = p * L.LH * L.LW + (r / (size_t)B) * L.LW + (c / (size_t)B);
+                float lfc = (dt == ORACLE_BF16)
+                                ? bf16_to_float(((const uint16_t *)(pk + L.lfc_off))[k])
+                                : ((const float *)(pk + L.lfc_off))[k];
+                volatile float hh = (float)q * Delta;   /* Sec. 4.2: Delta * V   */
+                hh = hh + delta;                        /*           ... + delta */
+                volatile float v = lfc + hh;            /* reconstruction eq.    */
+                if (dt == ORACLE_BF16)
+                    ((uint16_t *)xhat)[p * L.HW + i] = float_to_bf16(v);
+                else
+                    ((float *)xhat)[p * L.HW + i] = v;
+            }
+    }
+    return 0;
+}
+
+/* bf16 helpers exported so tests can build bf16 inputs without torch */
+uint16_t oracle_float_to_bf16(float f) { return float_to_bf16(f); }
+float oracle_bf16_to_float(uint16_t v) { return bf16_to_float(v); }
