@@ -1,0 +1,119 @@
+/*
+ * division.h -- C ABI of the DIVISION activation codec for AMD MI355X (gfx950).
+ *
+ * The codec is the per-layer hot path of "DIVISION: Memory Efficient Training
+ * via Dual Activation Precision": in the forward pass every cached activation
+ * map H (NCHW) is replaced by the tuple (H^L, V^H, Delta, delta) of Sec. 4.1,
+ * in the backward pass the map is rebuilt from that tuple as in Sec. 4.2.
+ *
+ * All tensor pointers are DEVICE pointers (HIP global memory) unless a
+ * comment says "host".  The library allocates nothing, keeps no state between
+ * calls, and never synchronises: every kernel is enqueued on the caller's
+ * stream and the call returns at once.  Buffers stay owned by the caller and
+ * must remain valid until the stream has passed the call.
+ *
+ * Packed buffer layout (little endian; P = N*C planes, one plane = one
+ * (sample, channel) map of H*W elements; LH = ceil(H/B), LW = ceil(W/B);
+ * CPW = 32/b codes per word; WPP = ceil(H*W/CPW) words per plane):
+ *
+ *   codes  at byte 0                      uint32 [P][WPP]
+ *          element i = r*W + c of a plane sits in word i / CPW at bit
+ *          (i % CPW) * b; pad bits are zero.
+ *   meta   at align16(end of codes)       float  [P][2] = (delta_p, Delta_p)
+ *   lfc    at align16(end of meta)        T      [P][LH][LW], T = element type
+ *   total  = align16(end of lfc)          == division_packed_bytes(...)
+ */
+#ifndef DIVISION_H
+#define DIVISION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element type of x, of the reconstructed map and of the stored LFC. */
+typedef enum { DIVISION_F32 = 0, DIVISION_BF16 = 1 } division_dtype;
+
+/* Return codes of every int-returning entry point. */
+enum {
+    DIVISION_OK     = 0,
+    DIVISION_EINVAL = 1,  /* null pointer, N/C/H/W <= 0, B < 1, b not in {2,4}, unknown dtype */
+    DIVISION_ESIZE  = 2,  /* packed buffer smaller than division_packed_bytes(...)             */
+    DIVISION_EALIGN = 3,  /* x / xhat not aligned to the element size, packed not to 16 bytes  */
+    DIVISION_ERANGE = 4,  /* N*C or H*W above 2^31-1, or N*C*H*W above 2^40                    */
+    DIVISION_EHIP   = 5   /* a kernel launch failed; hipGetLastError() holds the detail        */
+};
+
+/*
+ * Size in bytes of the cached tuple (H^L, V^H, Delta, delta) of one NCHW map
+ * (Sec. 4.1, last paragraph; the paper's per-channel accounting N^2 Q/8 + 4
+ * bytes plus the pooled map, here with fp32 (delta, Delta) and word-padded
+ * codes).  Host-only arithmetic; returns 0 for invalid arguments.
+ */
+size_t division_packed_bytes(int64_t N, int64_t C, int64_t H, int64_t W,
+                             int B, int b, division_dtype dt);
+
+/*
+ * Byte offset and size of the three regions of the packed buffer (host-only;
+ * out pointers are host pointers, none may be null).  Returns DIVISION_OK or
+ * DIVISION_EINVAL.
+ */
+int division_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W,
+                           int B, int b, division_dtype dt,
+                           size_t *codes_off, size_t *codes_bytes,
+                           size_t *meta_off, size_t *meta_bytes,
+                           size_t *lfc_off, size_t *lfc_bytes);
+
+/*
+ * Forward-pass compression (Sec. 4.1; Algorithm 1, the four steps after the
+ * layer's forward: AveragePooling, residual against UpSampling, Quant, Cache).
+ *
+ *   x       device, read only, N*C*H*W elements of type dt, dense NCHW.
+ *   B       pooling window = stride (the paper's block size B), >= 1.  Maps
+ *           smaller than B are pooled to 1x1 (footnote of Sec. 4.1); when B
+ *           does not divide H or W the border windows average their valid
+ *           elements only.
+ *   b       bits per HFC code (the paper's Q), 2 or 4.
+ *   seed    selects the stochastic-rounding stream of Eq. (quantization); the
+ *           output is a pure function of (x, shape, dt, B, b, seed) and does
+ *           not depend on the launch geometry or the device.
+ *   packed  device, written in full (pad bits and pad bytes zero), at least
+ *           division_packed_bytes(...) bytes, 16-byte aligned; must not
+ *           overlap x.
+ *   hip_stream  a hipStream_t passed as void* (NULL = the default stream).
+ *
+ * Per plane: H^L = block means (stored in type dt); H^H = x - nearest
+ * up-sampling of the stored H^L; delta = min H^H, Delta = (max H^H - delta) /
+ * (2^b - 1); code = floor(t + u) with t = (H^H - delta) * (2^b - 1)/(max-delta)
+ * and u uniform in [0,1) with 16 random bits per element.  A plane whose
+ * residual range is below 2^-90 gets Delta = 0 and all-zero codes.
+ * NaN or infinite inputs give unspecified codes (no error is raised).
+ */
+int division_compress(const void *x, int64_t N, int64_t C, int64_t H, int64_t W,
+                      division_dtype dt, int B, int b, uint64_t seed,
+                      void *packed, size_t packed_capacity, void *hip_stream);
+
+/*
+ * Backward-pass decompression (Sec. 4.2 and the reconstruction equation;
+ * Algorithm 1, the Dequant and UpSampling+add steps):
+ *   xhat = UpSampling(H^L) + (Delta * V^H + delta), rounded to type dt.
+ *
+ *   packed  device, read only, as written by division_compress with the same
+ *           (N, C, H, W, dt, B, b); packed_bytes is the size of that buffer.
+ *   xhat    device, N*C*H*W elements of type dt, written in full; must not
+ *           overlap packed.
+ */
+int division_decompress(const void *packed, size_t packed_bytes,
+                        int64_t N, int64_t C, int64_t H, int64_t W,
+                        division_dtype dt, int B, int b,
+                        void *xhat, void *hip_stream);
+
+/* Version of this ABI (host-only). */
+int division_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DIVISION_H */

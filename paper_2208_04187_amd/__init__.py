@@ -1,0 +1,7 @@
+"""DIVISION activation codec for AMD MI355X: HIP kernels behind a C ABI.
+
+compress / decompress of cached activation maps as in "DIVISION: Memory
+Efficient Training via Dual Activation Precision" (Sec. 4.1 and Sec. 4.2).
+"""
+from .binding import (DIVISION_BF16, DIVISION_F32, DivisionError, division_compress,  # noqa: F401
+                      division_decompress, division_packed_bytes, division_packed_layout, lib)

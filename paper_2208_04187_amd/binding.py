@@ -1,0 +1,107 @@
+"""Python binding of the C ABI declared in include/division.h.
+
+Argument marshalling only: every step of the codec runs in the HIP library.
+PyTorch supplies device memory and streams.  There is no CPU fallback: if
+libdivision.so is missing, importing a function from here raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+DIVISION_F32 = 0
+DIVISION_BF16 = 1
+
+ERRORS = {1: "DIVISION_EINVAL", 2: "DIVISION_ESIZE", 3: "DIVISION_EALIGN",
+          4: "DIVISION_ERANGE", 5: "DIVISION_EHIP"}
+
+_LIB_PATH = Path(__file__).resolve().parent / "libdivision.so"
+_lib = None
+
+
+class DivisionError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what} failed: {ERRORS.get(code, code)}")
+        self.code = code
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the built library; builds it first only if no build exists."""
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            from . import _build
+            _build.build()
+        L = ctypes.CDLL(str(_LIB_PATH))
+        i64, sz, u64, vp, ci = ctypes.c_int64, ctypes.c_size_t, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_int
+        L.division_abi_version.restype = ci
+        L.division_abi_version.argtypes = []
+        L.division_packed_bytes.restype = sz
+        L.division_packed_bytes.argtypes = [i64, i64, i64, i64, ci, ci, ci]
+        L.division_packed_layout.restype = ci
+        L.division_packed_layout.argtypes = [i64, i64, i64, i64, ci, ci, ci] + [ctypes.POINTER(sz)] * 6
+        L.division_compress.restype = ci
+        L.division_compress.argtypes = [vp, i64, i64, i64, i64, ci, ci, ci, u64, vp, sz, vp]
+        L.division_decompress.restype = ci
+        L.division_decompress.argtypes = [vp, sz, i64, i64, i64, i64, ci, ci, ci, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _dt(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return DIVISION_F32
+    if t == torch.bfloat16:
+        return DIVISION_BF16
+    raise TypeError(f"unsupported dtype {t}")
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def division_packed_bytes(N: int, C: int, H: int, W: int, B: int, b: int, dtype=torch.float32) -> int:
+    return int(lib().division_packed_bytes(N, C, H, W, B, b, _dt(dtype)))
+
+
+def division_packed_layout(N: int, C: int, H: int, W: int, B: int, b: int, dtype=torch.float32) -> dict:
+    vals = [ctypes.c_size_t() for _ in range(6)]
+    rc = lib().division_packed_layout(N, C, H, W, B, b, _dt(dtype), *[ctypes.byref(v) for v in vals])
+    if rc:
+        raise DivisionError(rc, "division_packed_layout")
+    names = ["codes_off", "codes_bytes", "meta_off", "meta_bytes", "lfc_off", "lfc_bytes"]
+    return {n: int(v.value) for n, v in zip(names, vals)}
+
+
+def division_compress(x: torch.Tensor, B: int, b: int, seed: int, packed: torch.Tensor | None = None,
+                      stream=None) -> torch.Tensor:
+    """x: contiguous NCHW device tensor (float32 or bfloat16).  Returns the packed uint8 buffer."""
+    if x.dim() != 4 or not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous 4-d device tensor")
+    N, C, H, W = x.shape
+    need = division_packed_bytes(N, C, H, W, B, b, x.dtype)
+    if need == 0:
+        raise DivisionError(1, "division_packed_bytes")
+    if packed is None:
+        packed = torch.empty(need, dtype=torch.uint8, device=x.device)
+    rc = lib().division_compress(x.data_ptr(), N, C, H, W, _dt(x.dtype), B, b, seed & (2 ** 64 - 1),
+                                 packed.data_ptr(), packed.numel() * packed.element_size(), _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_compress")
+    return packed
+
+
+def division_decompress(packed: torch.Tensor, shape, B: int, b: int, dtype=torch.float32,
+                        out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    N, C, H, W = shape
+    if out is None:
+        out = torch.empty(shape, dtype=dtype, device=packed.device)
+    rc = lib().division_decompress(packed.data_ptr(), packed.numel() * packed.element_size(),
+                                   N, C, H, W, _dt(dtype), B, b, out.data_ptr(), _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_decompress")
+    return out

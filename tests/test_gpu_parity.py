@@ -1,0 +1,204 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle,
+element by element on the same seeded inputs.  Needs a real MI355X."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2208_04187_amd as pkg
+from synthetic_inputs import codec_seed, config, draw, draw_config
+from tests.parity import check_against_oracle, gpu_roundtrip, to_host_array
+
+pytestmark = pytest.mark.gpu
+
+
+def _relu_normal(shape, seed, dtype=torch.float32):
+    g = torch.Generator().manual_seed(seed)
+    return torch.relu(torch.randn(shape, generator=g)).to(dtype)
+
+
+# ---------------------------------------------------------------- small and medium shapes
+
+TILE_CASES = [
+    # shape, B, b                     what it exercises
+    ((3, 5, 56, 56), 8, 2),           # 7x7 full blocks, float4 rows, several planes per workgroup
+    ((2, 3, 112, 112), 8, 2),         # one plane per workgroup, > 48 KB of LDS
+    ((4, 7, 28, 28), 8, 2),           # ragged 8/8/8/4 blocks, padded item slots
+    ((5, 9, 14, 14), 8, 2),           # 8+6 blocks, float2 rows
+    ((8, 33, 7, 7), 8, 2),            # map smaller than the block: 1x1 LFC, scalar rows, odd plane size
+    ((2, 3, 55, 55), 4, 4),           # 13 full blocks + one of 3, odd plane size, 4-bit codes
+    ((3, 4, 32, 32), 4, 2),
+    ((6, 10, 16, 16), 4, 2),
+    ((9, 5, 8, 8), 4, 2),
+    ((40, 13, 4, 4), 4, 2),           # one block per plane, one word per plane
+    ((2, 16, 32, 32), 8, 4),
+    ((1, 1, 190, 190), 8, 2),         # a single large plane in LDS (144 KB)
+    ((3, 2, 24, 40), 8, 4),           # H != W
+    ((2, 2, 9, 6), 4, 2),             # H*W not a multiple of 4 with even W
+    ((1, 3, 5, 3), 8, 2),
+    ((1, 1, 1, 1), 4, 2),
+    ((300, 7, 7, 7), 8, 4),           # last workgroup holds a partial chunk
+]
+
+ANY_CASES = [
+    ((2, 3, 20, 24), 1, 2),           # B = 1: LFC is x itself
+    ((2, 3, 20, 24), 2, 4),
+    ((2, 3, 20, 24), 3, 2),
+    ((2, 3, 36, 36), 12, 2),          # block sizes of the paper's sweep
+    ((2, 2, 36, 36), 18, 2),
+    ((2, 3, 56, 56), 64, 2),          # block larger than the map
+    ((1, 2, 300, 300), 8, 2),         # plane too large for LDS
+    ((2, 2, 33, 17), 16, 4),
+]
+
+
+@pytest.mark.parametrize("shape,B,b", TILE_CASES + ANY_CASES)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_matches_oracle_small(shape, B, b, dtype):
+    x = _relu_normal(shape, 1000 + sum(shape) + B + b, dtype)
+    st = check_against_oracle(x, B, b, seed=0x1234_5678_9ABC_DEF0 ^ B, require_exact=True)
+    assert st["exact"]
+
+
+def test_unaligned_input_pointer_takes_scalar_loads():
+    base = torch.relu(torch.randn(1 + 3 * 5 * 56 * 56, generator=torch.Generator().manual_seed(5)))
+    xd = base.to("cuda:0")[1:].view(3, 5, 56, 56)
+    assert xd.data_ptr() % 16 == 4
+    packed = pkg.division_compress(xd, 8, 2, 77)
+    torch.cuda.synchronize()
+    ref = oracle.compress(base[1:].view(3, 5, 56, 56).contiguous().numpy(), 8, 2, 77)
+    assert np.array_equal(packed.cpu().numpy(), ref)
+
+
+def test_signed_and_heavy_tailed_values():
+    g = torch.Generator().manual_seed(9)
+    x = torch.randn((4, 6, 28, 28), generator=g) * torch.exp(3 * torch.randn((4, 6, 1, 1), generator=g))
+    x[0, 0] = 0.0                       # an all-zero plane: degenerate range
+    x[0, 1] = 3.25                      # a constant plane
+    x[1, 2, 5, 5] = 1e30                # one huge outlier
+    for b in (2, 4):
+        assert check_against_oracle(x, 8, b, seed=3, require_exact=True)["exact"]
+
+
+# ---------------------------------------------------------------- invariants on the GPU path
+
+def test_B1_roundtrip_is_identity():
+    x = torch.randn((2, 3, 12, 20), generator=torch.Generator().manual_seed(2))
+    gp, gx = gpu_roundtrip(x, 1, 2, 5)
+    s = oracle.split_packed(gp, tuple(x.shape), 1, 2)
+    assert np.array_equal(s["lfc"].reshape(x.shape), x.numpy())
+    assert not s["codes"].any() and not s["meta"][:, 1].any()
+    assert torch.equal(gx, x)
+
+
+@pytest.mark.parametrize("shape,B", [((3, 4, 56, 56), 8), ((2, 5, 14, 14), 8), ((2, 3, 55, 55), 4)])
+def test_block_constant_input_has_zero_hfc(shape, B):
+    N, C, H, W = shape
+    LH, LW = -(-H // B), -(-W // B)
+    g = torch.Generator().manual_seed(4)
+    vals = torch.randint(-64, 64, (N, C, LH, LW), generator=g).float() / 8       # exactly summable
+    x = vals.repeat_interleave(B, 2).repeat_interleave(B, 3)[:, :, :H, :W].contiguous()
+    gp, gx = gpu_roundtrip(x, B, 2, 1)
+    s = oracle.split_packed(gp, shape, B, 2)
+    assert np.array_equal(s["lfc"].reshape(N, C, LH, LW), vals.numpy())
+    assert not s["codes"].any() and not s["meta"][:, 1].any()
+    assert torch.equal(gx, x)
+
+
+def test_error_bound_and_extreme_codes():
+    x = _relu_normal((6, 8, 28, 28), 6)
+    for b in (2, 4):
+        L = (1 << b) - 1
+        gp, gx = gpu_roundtrip(x, 8, b, 21)
+        s = oracle.split_packed(gp, tuple(x.shape), 8, b)
+        Delta = torch.from_numpy(s["meta"][:, 1].copy()).view(6, 8, 1, 1)
+        assert torch.all((gx - x).abs() <= Delta * (1 + 1e-5) + 1e-6)
+        q = oracle.unpack_codes(s["codes"], 784, b)
+        assert np.all(q.min(1) == 0) and np.all(q.max(1) == L)
+
+
+def test_deterministic_and_independent_of_neighbours():
+    x = _relu_normal((16, 16, 14, 14), 8)
+    a, _ = gpu_roundtrip(x, 8, 2, 9)
+    bb, _ = gpu_roundtrip(x, 8, 2, 9, prefill=0x00)
+    assert np.array_equal(a, bb)
+    # the first planes of a larger batch compress to the same bytes as on their own:
+    # results do not depend on how planes are grouped into workgroups
+    sub = x[:3].contiguous()
+    c, _ = gpu_roundtrip(sub, 8, 2, 9)
+    sa, sc = oracle.split_packed(a, tuple(x.shape), 8, 2), oracle.split_packed(c, tuple(sub.shape), 8, 2)
+    for k in ("codes", "meta", "lfc"):
+        assert np.array_equal(sa[k][:48], sc[k])
+
+
+def test_unbiased_over_seeds_on_gpu():
+    K = 512
+    x = _relu_normal((1, 4, 16, 16), 10)
+    xd = x.to("cuda:0")
+    acc = torch.zeros_like(xd, dtype=torch.float64)
+    for seed in range(K):
+        p = pkg.division_compress(xd, 8, 2, seed)
+        acc += pkg.division_decompress(p, tuple(x.shape), 8, 2).double()
+    mean = (acc / K).cpu()
+    s = oracle.split_packed(p.cpu().numpy(), tuple(x.shape), 8, 2)
+    Delta = torch.from_numpy(s["meta"][:, 1].copy()).view(1, 4, 1, 1).double()
+    err = (mean - x.double()).abs()
+    assert torch.all(err <= 4.5 * Delta * 0.5 / K ** 0.5 + 1e-6)
+    assert err.mean() < 0.5 * (Delta * 0.5 / K ** 0.5).mean() * 2
+
+
+def test_runs_on_a_side_stream():
+    x = _relu_normal((4, 8, 56, 56), 11).to("cuda:0")
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        p = pkg.division_compress(x, 8, 2, 4, stream=st)
+        y = pkg.division_decompress(p, tuple(x.shape), 8, 2, stream=st)
+    st.synchronize()
+    ref = oracle.compress(x.cpu().numpy(), 8, 2, 4)
+    assert np.array_equal(p.cpu().numpy(), ref)
+    assert np.array_equal(y.cpu().numpy(), oracle.decompress(ref, tuple(x.shape), 8, 2))
+
+
+def test_error_codes_on_device_buffers():
+    x = torch.zeros((1, 1, 8, 8), device="cuda:0")
+    need = pkg.division_packed_bytes(1, 1, 8, 8, 4, 2)
+    small = torch.empty(need - 16, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(pkg.DivisionError) as e:
+        pkg.division_compress(x, 4, 2, 0, packed=small)
+    assert e.value.code == 2
+    big = torch.empty(need + 16, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(pkg.DivisionError) as e:
+        pkg.division_compress(x, 4, 2, 0, packed=big[1:])
+    assert e.value.code == 3
+    with pytest.raises(pkg.DivisionError) as e:
+        pkg.division_compress(x, 4, 3, 0)
+    assert e.value.code == 1
+
+
+# ---------------------------------------------------------------- the benchmark configurations
+
+def test_config0_small_tensor_exact():
+    for k, spec, x in draw_config(0):
+        st = check_against_oracle(x, spec.B, spec.b, codec_seed(0, k), require_exact=True)
+        assert st["exact"]
+
+
+@pytest.mark.parametrize("idx", [1, 2, 4])
+def test_full_size_fp32_configs(idx):
+    total = flips = 0
+    for k, spec, x in draw_config(idx):
+        st = check_against_oracle(x, spec.B, spec.b, codec_seed(idx, k), threads=16)
+        total += st["elements"]
+        flips += st["flips"]
+        print(f"config {idx} tensor {k} {spec.name}: exact={st['exact']} flips={st['flips']}", flush=True)
+    assert flips <= 1e-6 * total
+
+
+def test_full_size_bf16_config3():
+    for k, spec, x in draw_config(3):
+        xb = x.to(torch.bfloat16)
+        del x
+        st = check_against_oracle(xb, spec.B, spec.b, codec_seed(3, k), threads=16)
+        print(f"config 3 {spec.name}: exact={st['exact']} flips={st['flips']}", flush=True)
+        assert st["flips"] <= 1e-6 * st["elements"]

@@ -1,0 +1,75 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and its host-only entry points agree with
+the oracle's byte accounting and reject bad arguments."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+import paper_2208_04187_amd as pkg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "division.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(division_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert {"division_packed_bytes", "division_compress", "division_decompress",
+            "division_packed_layout", "division_abi_version"} <= set(names)
+    L = pkg.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert L.division_abi_version() == 1
+
+
+SHAPES = [(2, 16, 32, 32, 8, 2), (64, 256, 56, 56, 8, 2), (64, 2048, 7, 7, 8, 2), (32, 96, 55, 55, 4, 4),
+          (128, 512, 4, 4, 4, 2), (1, 1, 1, 1, 1, 2), (3, 5, 13, 29, 5, 4), (2, 2, 300, 300, 64, 2)]
+
+
+@pytest.mark.parametrize("dt", [0, 1])
+def test_packed_bytes_and_layout_match_oracle(dt):
+    import torch
+    tdt = torch.float32 if dt == 0 else torch.bfloat16
+    for s in SHAPES:
+        assert pkg.division_packed_bytes(*s, dtype=tdt) == oracle.packed_bytes(*s, dt)
+        assert pkg.division_packed_layout(*s, dtype=tdt) == oracle.packed_layout(*s, dt)
+
+
+def test_config_sizes_and_ratios():
+    # sizes of the benchmark configurations (fp32 LFC, 8-byte meta)
+    assert pkg.division_packed_bytes(2, 16, 32, 32, 8, 2) == 10496
+    from synthetic_inputs import config
+    _, specs = config(2)
+    inp = sum(4 * s.shape[0] * s.shape[1] * s.shape[2] * s.shape[3] for s in specs)
+    out = sum(pkg.division_packed_bytes(*s.shape, s.B, s.b) for s in specs)
+    assert inp == 1618477056
+    assert 11.4 < inp / out < 11.6          # >= 10x activation compression at B=8, b=2
+
+
+def test_invalid_arguments_are_rejected_on_the_host():
+    L = pkg.lib()
+    assert L.division_packed_bytes(0, 1, 4, 4, 2, 2, 0) == 0
+    assert L.division_packed_bytes(1, 1, 4, 4, 0, 2, 0) == 0
+    assert L.division_packed_bytes(1, 1, 4, 4, 2, 3, 0) == 0
+    assert L.division_packed_bytes(1, 1, 4, 4, 2, 2, 7) == 0
+    assert L.division_packed_bytes(2 ** 20, 2 ** 20, 4, 4, 2, 2, 0) == 0        # too many planes
+    buf = ctypes.create_string_buffer(4096)
+    addr = ctypes.addressof(buf)
+    addr16 = (addr + 15) & ~15
+    # all of these return before any HIP call is made
+    assert L.division_compress(None, 1, 1, 4, 4, 0, 2, 2, 0, addr16, 4096, None) == 1
+    assert L.division_compress(addr16, 1, 1, 4, 4, 0, 2, 5, 0, addr16, 4096, None) == 1
+    assert L.division_compress(addr16, 1, 1, 4, 4, 0, 2, 2, 0, addr16 + 1024, 8, None) == 2
+    assert L.division_compress(addr16, 1, 1, 4, 4, 0, 2, 2, 0, addr16 + 1025, 2048, None) == 3
+    assert L.division_compress(addr16 + 2, 1, 1, 4, 4, 0, 2, 2, 0, addr16 + 1024, 2048, None) == 3
+    assert L.division_compress(addr16, 2 ** 20, 2 ** 20, 4, 4, 0, 2, 2, 0, addr16 + 1024, 2048, None) == 4
+    assert L.division_decompress(None, 64, 1, 1, 4, 4, 0, 2, 2, addr16, None) == 1
+    assert L.division_decompress(addr16, 8, 1, 1, 4, 4, 0, 2, 2, addr16 + 1024, None) == 2
+    assert L.division_decompress(addr16 + 4, 2048, 1, 1, 4, 4, 0, 2, 2, addr16 + 1024, None) == 3
