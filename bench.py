@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the DIVISION activation codec on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic
+activations: every tensor of the workload is compressed (forward order), then
+every tensor is decompressed (reverse order, as the backward pass of
+Algorithm 1 does).  Inputs are resident in HBM before the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config IDX]
+
+Prints ONE JSON line.  `value` is the algorithmic throughput
+2 * (input_bytes + packed_bytes) / step_time in GB/s (bytes the method must
+move: one read of x and one write of the packed tuple in compress, the reverse
+in decompress); `activation_GB_s` counts the activation bytes alone.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs (see profiles/); None until measured for the current kernels.
+MEASURED_TRAFFIC_BYTES = None
+
+WORKLOAD_NAMES = {
+    0: "single 2x16x32x32 fp32 tensor, B=8 b=2 (configs[0])",
+    1: "ResNet-18/CIFAR activation set, batch 128, fp32, B=4 b=2 (configs[1])",
+    2: "ResNet-50/ImageNet activation set, batch 64, fp32, B=8 b=2 (configs[2])",
+    3: "single 256x256x56x56 bf16 tensor, B=8 b=2 (configs[3])",
+    4: "edge-shape heavy-tail fp32 set, batch 32, b=4 (configs[4])",
+}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload index 0..4 (default: ResNet-50 set)")
+    ap.add_argument("--sets", type=int, default=3, help="rotating buffer sets (defeats last-level-cache reuse)")
+    ap.add_argument("--batch", type=int, default=None, help="override the batch size (not a valid headline run)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; planes are independent so data-parallel ranks would run "
+              "the same kernels with no collective, but no multi-GPU figure is produced. Use --gpus 1.",
+              file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2208_04187_amd as pkg
+    from synthetic_inputs import codec_seed, config, draw_config
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---- synthetic workload on the host, then resident in HBM (several rotating sets)
+    _, specs = config(args.config)
+    host = []
+    for k, spec, x in draw_config(args.config, args.batch):
+        if spec.dtype == "bf16":
+            x = x.to(torch.bfloat16)
+        host.append((k, spec, x))
+    nsets = max(1, args.sets)
+    xs, packs, outs = [], [], []
+    for s in range(nsets):
+        xs.append([(x.to(dev) if s == 0 else torch.roll(x.to(dev), s, 0).contiguous()) for _, _, x in host])
+        packs.append([torch.empty(pkg.division_packed_bytes(*x.shape, sp.B, sp.b, x.dtype), dtype=torch.uint8, device=dev)
+                      for _, sp, x in host])
+        outs.append([torch.empty(x.shape, dtype=x.dtype, device=dev) for _, _, x in host])
+    shapes = [tuple(x.shape) for _, _, x in host]
+    dtypes = [x.dtype for _, _, x in host]
+    seeds = [codec_seed(args.config, k) for k, _, _ in host]
+    in_bytes = [x.numel() * x.element_size() for _, _, x in host]
+    pk_bytes = [p.numel() for p in packs[0]]
+    elements = sum(x.numel() for _, _, x in host)
+    input_bytes, packed_bytes = sum(in_bytes), sum(pk_bytes)
+    algo_bytes_step = 2 * (input_bytes + packed_bytes)
+
+    # every launch of a step: (direction, tensor index, kernel name)
+    launches = [(0, i) for i in range(len(host))] + [(1, i) for i in reversed(range(len(host)))]
+    names = {(d, i): pkg.division_kernel_name(d, shapes[i], host[i][1].B, host[i][1].b, dtypes[i]) for d, i in launches}
+
+    def run_step(s: int, timed_group=None, events=None):
+        for d, i in launches:
+            sp = host[i][1]
+            rec = events is not None and (timed_group is None or names[(d, i)] == timed_group)
+            if rec:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+            if d == 0:
+                pkg.division_compress(xs[s][i], sp.B, sp.b, seeds[i], packed=packs[s][i])
+            else:
+                pkg.division_decompress(packs[s][i], shapes[i], sp.B, sp.b, dtypes[i], out=outs[s][i])
+            if rec:
+                e1.record()
+                events.append(((d, i), e0, e1))
+
+    # ---- warm-up; its last step times every launch to find the dominant kernel
+    for w in range(max(1, args.warmup) - 1):
+        run_step(w % nsets)
+    probe = []
+    run_step((max(1, args.warmup) - 1) % nsets, None, probe)
+    torch.cuda.synchronize()
+    per_kernel = {}
+    for key, e0, e1 in probe:
+        per_kernel[names[key]] = per_kernel.get(names[key], 0.0) + e0.elapsed_time(e1)
+    dominant = max(per_kernel, key=per_kernel.get)
+
+    # ---- timed region: exactly K steps; events only around the dominant kernel's launches
+    events = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        run_step(k % nsets, dominant, events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    dom_ms = [e0.elapsed_time(e1) for _, e0, e1 in events]
+    dom_bytes = [in_bytes[i] + pk_bytes[i] for (d, i), _, _ in events]
+    avg_ms = sum(dom_ms) / len(dom_ms)
+    avg_bytes = sum(dom_bytes) / len(dom_bytes)
+    achieved = avg_bytes / (avg_ms * 1e-3) / 1e9
+    value = algo_bytes_step / (ms_per_step * 1e-3) / 1e9
+
+    out = {
+        "metric": "compress+decompress GB/s of activations and % of HBM peak; compression ratio",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if dtypes[0] == torch.bfloat16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[args.config], "tensors": len(host), "elements": elements,
+                   "input_bytes": input_bytes, "packed_bytes": packed_bytes,
+                   "B": host[0][1].B, "b": host[0][1].b, "buffer_sets": nsets,
+                   "batch_override": args.batch},
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "activation_GB_s": round(2 * input_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "compression_ratio": round(input_bytes / packed_bytes, 3),
+        "kernel_ms_last_warmup_step": {k: round(v, 4) for k, v in sorted(per_kernel.items())},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES,
+                     "algorithmic_bytes_per_launch": round(avg_bytes), "avg_launch_ms": round(avg_ms, 5),
+                     "launches_timed": len(dom_ms)},
+    }
+
+    # ---- CPU baseline: the oracle as it stands, on the host cores, same workload
+    if not args.no_cpu_baseline:
+        import numpy as np
+
+        import oracle
+        threads = min(16, os.cpu_count() or 1)
+        tc = 0.0
+        for (k, sp, x), seed in zip(host, seeds):
+            if x.dtype == torch.bfloat16:
+                arr, dt = x.view(torch.int16).numpy().view(np.uint16), oracle.BF16
+            else:
+                arr, dt = x.numpy(), oracle.F32
+            a0 = time.perf_counter()
+            p = oracle.compress(arr, sp.B, sp.b, seed, dt, threads=threads)
+            oracle.decompress(p, tuple(x.shape), sp.B, sp.b, dt, threads=threads)
+            tc += time.perf_counter() - a0
+        out["cpu_baseline"] = {"value": round(algo_bytes_step / tc / 1e9, 3), "unit": "GB/s", "cores": threads,
+                               "kind": "oracle",
+                               "sample": f"one full step ({len(host)} tensors, {elements} elements) through the C oracle, "
+                                         f"{threads} OpenMP threads over planes, {tc:.1f} s wall"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -110,6 +110,19 @@ int division_decompress(const void *packed, size_t packed_bytes,
                         division_dtype dt, int B, int b,
                         void *xhat, void *hip_stream);
 
+/*
+ * Profiling aid (host-only): writes the name of the kernel template instance
+ * that division_compress (direction 0, data = x) or division_decompress
+ * (direction 1, data = xhat) would launch for these arguments, as it appears
+ * in a kernel trace, e.g. "compress_tile<float, 2, 8, 4>".  The choice depends
+ * on the shape, the block size and the 16-byte alignment of `data` (which may
+ * be null: treated as aligned).  out is a host buffer of cap bytes.
+ * Returns DIVISION_OK, or DIVISION_ESIZE when cap is too small.
+ */
+int division_kernel_name(int direction, const void *data,
+                         int64_t N, int64_t C, int64_t H, int64_t W,
+                         division_dtype dt, int B, int b, char *out, size_t cap);
+
 /* Version of this ABI (host-only). */
 int division_abi_version(void);
 

@@ -14,6 +14,7 @@ HIPCC_FLAGS = [
     "-ffp-contract=off",                       # fp32 steps of the codec are never fused
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-fPIC", "-shared",
+    "-Rpass-analysis=kernel-resource-usage",   # parsed below: no kernel may spill to scratch
 ]
 
 
@@ -25,7 +26,12 @@ def build(verbose: bool = False) -> Path:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stderr)
+    spills = [ln for ln in res.stderr.splitlines()
+              if "ScratchSize [bytes/lane]:" in ln and not ln.split("ScratchSize [bytes/lane]:")[1].strip().startswith("0")]
+    if spills:
+        tmp.unlink(missing_ok=True)
+        raise RuntimeError("a kernel spills registers to scratch memory (performance guard):\n" + "\n".join(spills[:5]))
     if verbose and res.stderr:
-        print(res.stderr)
+        print("\n".join(ln for ln in res.stderr.splitlines() if "remark:" not in ln))
     os.replace(tmp, LIB)
     return LIB

@@ -46,6 +46,8 @@ def lib() -> ctypes.CDLL:
         L.division_compress.argtypes = [vp, i64, i64, i64, i64, ci, ci, ci, u64, vp, sz, vp]
         L.division_decompress.restype = ci
         L.division_decompress.argtypes = [vp, sz, i64, i64, i64, i64, ci, ci, ci, vp, vp]
+        L.division_kernel_name.restype = ci
+        L.division_kernel_name.argtypes = [ci, vp, i64, i64, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
         _lib = L
     return _lib
 
@@ -105,3 +107,13 @@ def division_decompress(packed: torch.Tensor, shape, B: int, b: int, dtype=torch
     if rc:
         raise DivisionError(rc, "division_decompress")
     return out
+
+
+def division_kernel_name(direction: int, shape, B: int, b: int, dtype=torch.float32, data_ptr: int = 0) -> str:
+    """Name of the kernel instance a call would launch (direction 0 = compress, 1 = decompress)."""
+    buf = ctypes.create_string_buffer(128)
+    N, C, H, W = shape
+    rc = lib().division_kernel_name(direction, data_ptr or None, N, C, H, W, _dt(dtype), B, b, buf, 128)
+    if rc:
+        raise DivisionError(rc, "division_kernel_name")
+    return buf.value.decode()

@@ -21,6 +21,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <stdio.h>
+#include <stdlib.h>
 #include "../../include/division.h"
 
 namespace {
@@ -135,14 +137,112 @@ struct TileArgs {
     FastDiv d_ipp, d_ipr, d_wpp;
 };
 
+// ------------------------------------------------------------------ synchronisation
+
+// Orders LDS traffic between the lanes of ONE wavefront.  The LDS unit serves
+// a wavefront's instructions in issue order, so no wait is needed; the fence
+// only stops the compiler from moving LDS accesses across this point.  Unlike
+// __syncthreads() it does not wait for outstanding global loads and stores.
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Workgroup barrier that publishes LDS writes only: waits for this wave's LDS
+// operations (lgkmcnt), not for its global loads and stores (vmcnt), then
+// joins the barrier.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_s_waitcnt(0xc07f);      // lgkmcnt(0), vmcnt and expcnt untouched
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ------------------------------------------------------------------ cross-lane helpers (DPP)
+
+// value of another lane of the same 16-lane row; all lanes must be active
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+    const uint64_t u = __double_as_longlong(v);
+    const uint32_t lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, CTRL, 0xf, 0xf, false);
+    const uint32_t hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), CTRL, 0xf, 0xf, false);
+    return __longlong_as_double(((uint64_t)hi << 32) | lo);
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8 lanes
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each 16 lanes
+
+// sum over aligned groups of N lanes (N = 1, 2, 4, 8), result in every lane of the group
+template <int N>
+__device__ __forceinline__ double group_sum(double v) {
+    if constexpr (N >= 2) v += dpp_f64<kDppXor1>(v);
+    if constexpr (N >= 4) v += dpp_f64<kDppXor2>(v);
+    if constexpr (N >= 8) v += dpp_f64<kDppHalfMirror>(v);
+    return v;
+}
+
+// min / max over aligned groups of S lanes (S a power of two <= 64, uniform
+// in the wave), result in every lane of the group
+__device__ __forceinline__ void group_minmax(uint32_t S, float& mn, float& mx) {
+    if (S >= 2)  { mn = fminf(mn, dpp_f32<kDppXor1>(mn)); mx = fmaxf(mx, dpp_f32<kDppXor1>(mx)); }
+    if (S >= 4)  { mn = fminf(mn, dpp_f32<kDppXor2>(mn)); mx = fmaxf(mx, dpp_f32<kDppXor2>(mx)); }
+    if (S >= 8)  { mn = fminf(mn, dpp_f32<kDppHalfMirror>(mn)); mx = fmaxf(mx, dpp_f32<kDppHalfMirror>(mx)); }
+    if (S >= 16) { mn = fminf(mn, dpp_f32<kDppMirror>(mn)); mx = fmaxf(mx, dpp_f32<kDppMirror>(mx)); }
+    if (S >= 32) {
+        const int imn = __float_as_int(mn), imx = __float_as_int(mx);
+        const float n0 = __int_as_float(__builtin_amdgcn_readlane(imn, 0)), n1 = __int_as_float(__builtin_amdgcn_readlane(imn, 16));
+        const float n2 = __int_as_float(__builtin_amdgcn_readlane(imn, 32)), n3 = __int_as_float(__builtin_amdgcn_readlane(imn, 48));
+        const float x0 = __int_as_float(__builtin_amdgcn_readlane(imx, 0)), x1 = __int_as_float(__builtin_amdgcn_readlane(imx, 16));
+        const float x2 = __int_as_float(__builtin_amdgcn_readlane(imx, 32)), x3 = __int_as_float(__builtin_amdgcn_readlane(imx, 48));
+        if (S == 64) {
+            mn = fminf(fminf(n0, n1), fminf(n2, n3));
+            mx = fmaxf(fmaxf(x0, x1), fmaxf(x2, x3));
+        } else {
+            const bool upper = (threadIdx.x & 32u) != 0;
+            mn = upper ? fminf(n2, n3) : fminf(n0, n1);
+            mx = upper ? fmaxf(x2, x3) : fmaxf(x0, x1);
+        }
+    }
+}
+
 // ------------------------------------------------------------------ compress, LDS tile
 
+// One pair of elements -> two codes pushed into the packed word (element
+// 2j+1 first, then 2j: words are built from the last element down, so that
+// element 0 ends in the low bits).  Exact integer evaluation of
+// floor(t + r/2^16): T = trunc(t * 2^(32-BITS)), sum = T + (r << (16-BITS)),
+// code = top BITS bits of sum.  t <= L(1 + 3 ulp) and r < 2^16 keep the sum
+// below 2^32, so no clamp is needed.
+template <int BITS>
+__device__ __forceinline__ uint32_t push_pair(uint32_t acc, float h0, float h1, float delta, float invs,
+                                              uint32_t xw, uint32_t k2, uint32_t rscale) {
+    uint32_t x = xw;
+    x ^= x >> 16; x *= 0x7feb352du;
+    x = x ^ (x >> 15) ^ k2; x *= 0x846ca68bu;
+    // final x ^= x >> 16: the high half is unchanged, the low half becomes lo ^ hi
+    const uint32_t xl = x ^ (x >> 16);
+    const uint32_t T1 = (uint32_t)((h1 - delta) * invs);
+    const uint32_t T0 = (uint32_t)((h0 - delta) * invs);
+    uint32_t s1, s0;
+    asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(s1) : "v"(x), "s"(rscale), "v"(T1));
+    asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[0,0,0,0]" : "=v"(s0) : "v"(xl), "s"(rscale), "v"(T0));
+    acc = __builtin_amdgcn_alignbit(acc, s1, 32 - BITS);
+    acc = __builtin_amdgcn_alignbit(acc, s0, 32 - BITS);
+    return acc;
+}
+
 // T: element type; BITS: code width; B: block size (4 or 8); VEC: elements per
-// LDS vector access in the pooling phase (W % VEC == 0, B % VEC == 0).
-template <typename T, int BITS, int B, int VEC>
-__global__ void __launch_bounds__(kThreads) compress_tile(TileArgs a) {
+// LDS vector access in the pooling phase (W % VEC == 0, B % VEC == 0);
+// NT: threads per workgroup (64 or 256).
+template <typename T, int BITS, int B, int VEC, int NT>
+__global__ void __launch_bounds__(NT) compress_tile(TileArgs a) {
     extern __shared__ float4 smem4[];
-    float4* params = smem4;                                   // [G] (delta, inv16, k1, k2)
+    float4* params = smem4;                                   // [G] (delta, inv scaled, k1, k2)
     float* xs = reinterpret_cast<float*>(smem4 + a.G);        // [G*HW] x, later the residual h
     float* item_min = xs + a.xs_floats;                       // [items_cap]
     float* item_max = item_min + a.items_cap;                 // [items_cap]
@@ -156,22 +256,23 @@ __global__ void __launch_bounds__(kThreads) compress_tile(TileArgs a) {
     const uint32_t n = Gc * a.HW;
     if (blockIdx.x == 0) zero_pads(a.pads, tid);
 
-    // ---- phase 0: chunk -> LDS (fp32), coalesced 16-byte loads
+    // ---- phase 0: chunk -> LDS (fp32); coalesced 16-byte loads, up to 8 in flight per lane
     {
         const T* src = static_cast<const T*>(a.x) + (size_t)p0 * a.HW;
         constexpr uint32_t EPV = 16 / sizeof(T);
-        uint32_t nv = a.vec_load ? n / EPV : 0;
+        constexpr int U = 8;
+        const uint32_t nv = a.vec_load ? n / EPV : 0;
         const u32x4* src4 = reinterpret_cast<const u32x4*>(src);
-        for (uint32_t v0 = 0; v0 < nv; v0 += 4 * kThreads) {
-            u32x4 q[4];
+        for (uint32_t v0 = 0; v0 < nv; v0 += U * NT) {
+            u32x4 q[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                uint32_t v = v0 + u * kThreads + tid;
+            for (int u = 0; u < U; ++u) {
+                const uint32_t v = v0 + u * NT + tid;
                 if (v < nv) q[u] = __builtin_nontemporal_load(src4 + v);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                uint32_t v = v0 + u * kThreads + tid;
+            for (int u = 0; u < U; ++u) {
+                const uint32_t v = v0 + u * NT + tid;
                 if (v < nv) {
                     if constexpr (sizeof(T) == 4) {
                         reinterpret_cast<u32x4*>(xs)[v] = q[u];
@@ -187,14 +288,15 @@ __global__ void __launch_bounds__(kThreads) compress_tile(TileArgs a) {
                 }
             }
         }
-        for (uint32_t e = nv * EPV + tid; e < n; e += kThreads) xs[e] = Elem<T>::load(src, e);
+        for (uint32_t e = nv * EPV + tid; e < n; e += NT) xs[e] = Elem<T>::load(src, e);
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- phase 1: block means (Sec. 4.1 AveragePooling), residual in place
-    // item = (plane g, block row bi, slot s): B rows x VEC columns of one block
+    // item = (plane g, block row bi, slot s): B rows x VEC columns of one block;
+    // the IPB items of a block sit in adjacent lanes
     const uint32_t nitems = Gc * a.ipp;
-    for (uint32_t it0 = 0; it0 < nitems; it0 += kThreads) {
+    for (uint32_t it0 = 0; it0 < nitems; it0 += NT) {
         const uint32_t it = it0 + tid;
         const uint32_t g = fdiv(it, a.d_ipp);
         const uint32_t rem = it - g * a.ipp;
@@ -227,8 +329,7 @@ __global__ void __launch_bounds__(kThreads) compress_tile(TileArgs a) {
 #pragma unroll
             for (int c = 0; c < VEC; ++c) S += (double)v[rr][c];
         }
-#pragma unroll
-        for (int off = 1; off < IPB; off <<= 1) S += __shfl_xor(S, off);
+        S = group_sum<IPB>(S);
 
         const uint32_t bj = s / IPB;
         const uint32_t rows = min((uint32_t)B, a.H - min(a.H, r0));
@@ -263,12 +364,12 @@ __global__ void __launch_bounds__(kThreads) compress_tile(TileArgs a) {
         }
         if (it < nitems) { item_min[it] = hmin; item_max[it] = hmax; }
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- phase 2: per-plane min / max, scale of Eq. (quantization), keys
     {
         const uint32_t S = a.S;
-        const uint32_t groups = kThreads / S;
+        const uint32_t groups = NT / S;
         const uint32_t sub = tid & (S - 1);
         for (uint32_t g0 = 0; g0 < Gc; g0 += groups) {
             const uint32_t g = g0 + tid / S;
@@ -281,10 +382,7 @@ __global__ void __launch_bounds__(kThreads) compress_tile(TileArgs a) {
                     mx = fmaxf(mx, item_max[b0 + k]);
                 }
             }
-            for (uint32_t off = S >> 1; off > 0; off >>= 1) {
-                mn = fminf(mn, __shfl_xor(mn, off));
-                mx = fmaxf(mx, __shfl_xor(mx, off));
-            }
+            group_minmax(S, mn, mx);
             if (live && sub == 0) {
                 float Delta, inv;
                 plane_scale(mn, mx, Lf, Delta, inv);
@@ -292,21 +390,22 @@ __global__ void __launch_bounds__(kThreads) compress_tile(TileArgs a) {
                 reinterpret_cast<float2*>(a.meta)[p] = make_float2(mn, Delta);
                 const uint32_t k1 = mix32(p ^ a.seed_a);
                 const uint32_t k2 = mix32(k1 + a.seed_c);
-                params[g] = make_float4(mn, inv * 65536.0f, __uint_as_float(k1), __uint_as_float(k2));
+                params[g] = make_float4(mn, inv * (float)(1u << (32 - BITS)), __uint_as_float(k1), __uint_as_float(k2));
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- phase 3: Quant of Eq. (quantization) + packing, one word per lane
     {
         const uint32_t nwords = Gc * a.WPP;
         const bool hw4 = (a.HW & 3u) == 0;
-        for (uint32_t wi = tid; wi < nwords; wi += kThreads) {
+        const uint32_t rscale = 1u << (16 - BITS);
+        for (uint32_t wi = tid; wi < nwords; wi += NT) {
             const uint32_t g = fdiv(wi, a.d_wpp);
             const uint32_t k = wi - g * a.WPP;
             const float4 pr = params[g];
-            const float delta = pr.x, inv16 = pr.y;
+            const float delta = pr.x, invs = pr.y;
             const uint32_t k1 = __float_as_uint(pr.z), k2 = __float_as_uint(pr.w);
             const uint32_t e0 = k * CPW;
             const uint32_t left = a.HW - e0;
@@ -323,17 +422,334 @@ __global__ void __launch_bounds__(kThreads) compress_tile(TileArgs a) {
 #pragma unroll
                 for (int e = 0; e < CPW; ++e) h[e] = (uint32_t)e < left ? hp[e] : delta;
             }
-            uint32_t xw = k1 + (k * (CPW / 2)) * kWeyl;
+            const uint32_t xw0 = k1 + (k * (CPW / 2)) * kWeyl;
             uint32_t word = 0;
 #pragma unroll
-            for (int j = 0; j < CPW / 2; ++j) {
-                const uint32_t w = pair_word(xw, k2);
-                xw += kWeyl;
-                word |= quant<0>(h[2 * j], delta, inv16, w) << (2 * j * BITS);
-                word |= quant<1>(h[2 * j + 1], delta, inv16, w) << ((2 * j + 1) * BITS);
-            }
+            for (int j = CPW / 2 - 1; j >= 0; --j)
+                word = push_pair<BITS>(word, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
             a.codes[(size_t)(p0 + g) * a.WPP + k] = word;
         }
+    }
+}
+
+// ------------------------------------------------------------------ compress, one wavefront per chunk
+
+struct WaveArgs {
+    Pads pads;
+    const void* x;
+    uint32_t* codes;
+    float* meta;
+    void* lfc;
+    uint32_t P, H, W, HW, LH, LW, nb, WPP;
+    uint32_t G;          // planes per wavefront (one workgroup = one wavefront)
+    uint32_t ipr;        // item slots per block row (padded to the items-per-block count)
+    uint32_t ipp;        // item slots per plane = LH * ipr
+    uint32_t ippp;       // ipp padded: next power of two if <= 64, else next multiple of 64
+    uint32_t ippp_log2;  // log2(ippp) when ippp <= 64
+    uint32_t vec_load;   // chunk starts are 16-byte aligned
+    uint32_t seed_a, seed_c;
+    FastDiv d_ipr, d_wpp;
+#ifdef DIVISION_EXPERIMENT
+    uint32_t skip;       // timing experiments only: bit 0 skips pooling, bit 1 skips quantisation
+#endif
+};
+
+// Sec. 4.1 for one pooling item: B rows x VEC columns of one block, read from
+// LDS; the IPB items of a block sit in adjacent lanes.  Writes the block's LFC,
+// overwrites x by the residual, folds the item's residual min / max into
+// (hmin, hmax).  FULLROWS: H is a multiple of B, so every row of every block
+// exists and the body needs no per-row predicate; lanes without an item work
+// on item 0 of the chunk and have their effects masked.
+template <typename T, int B, int VEC, bool FULLROWS>
+__device__ __forceinline__ void pool_item(float* xs, const WaveArgs& a, T* lfc_plane, uint32_t g, uint32_t rem,
+                                          bool live, float& hmin, float& hmax) {
+    constexpr int IPB = B / VEC;
+    const uint32_t bi = fdiv(rem, a.d_ipr);
+    const uint32_t s = rem - bi * a.ipr;
+    const uint32_t col0 = s * VEC;
+    const uint32_t r0 = bi * B;
+    const bool valid = live && rem < a.ipp && col0 < a.W;
+    const uint32_t base = valid ? g * a.HW + r0 * a.W + col0 : 0u;
+    const uint32_t nrows = FULLROWS ? (uint32_t)B : (valid ? min((uint32_t)B, a.H - r0) : 0u);
+
+    float v[B][VEC];
+    double acc[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) acc[c] = 0.0;
+#pragma unroll
+    for (int rr = 0; rr < B; ++rr) {
+        // rows past the map re-read row 0 of the item (always present) and count as zero
+        const bool ok = FULLROWS || (uint32_t)rr < nrows;
+        const float* src = xs + base + (ok ? rr : 0) * a.W;
+        if constexpr (VEC == 4) {
+            float4 q = *reinterpret_cast<const float4*>(src);
+            v[rr][0] = q.x; v[rr][1] = q.y; v[rr][2] = q.z; v[rr][3] = q.w;
+        } else if constexpr (VEC == 2) {
+            float2 q = *reinterpret_cast<const float2*>(src);
+            v[rr][0] = q.x; v[rr][1] = q.y;
+        } else {
+            v[rr][0] = src[0];
+        }
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc[c] += ok ? (double)v[rr][c] : 0.0;
+    }
+    double S = acc[0];
+#pragma unroll
+    for (int c = 1; c < VEC; ++c) S += acc[c];
+    S = valid ? S : 0.0;
+    S = group_sum<IPB>(S);
+
+    const uint32_t bj = s / IPB;
+    const uint32_t rows = FULLROWS ? (uint32_t)B : min((uint32_t)B, a.H - min(a.H, r0));
+    const uint32_t cols = min((uint32_t)B, a.W - min(a.W, bj * B));
+    const uint32_t cnt = max(rows * cols, 1u);
+    // exact sum / count, one rounding to fp32, then to the storage type
+    float m;
+    if ((cnt & (cnt - 1)) == 0) m = (float)(S * (1.0 / (double)cnt));   // power of two: exact scaling
+    else m = (float)(S / (double)cnt);
+    const float lfc = Elem<T>::round(m);
+    if (valid && (s % IPB) == 0) Elem<T>::store(lfc_plane, bi * a.LW + bj, lfc);
+
+    // H^H = H - UpSampling(H^L), written back over x
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+    float h[B][VEC];
+#pragma unroll
+    for (int rr = 0; rr < B; ++rr) {
+        const bool ok = FULLROWS || (uint32_t)rr < nrows;
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            h[rr][c] = v[rr][c] - lfc;
+            mn = fminf(mn, ok ? h[rr][c] : __builtin_inff());
+            mx = fmaxf(mx, ok ? h[rr][c] : -__builtin_inff());
+        }
+    }
+    if (valid) {
+#pragma unroll
+        for (int rr = 0; rr < B; ++rr) {
+            if (FULLROWS || (uint32_t)rr < nrows) {
+                float* dst = xs + base + rr * a.W;
+                if constexpr (VEC == 4) *reinterpret_cast<float4*>(dst) = make_float4(h[rr][0], h[rr][1], h[rr][2], h[rr][3]);
+                else if constexpr (VEC == 2) *reinterpret_cast<float2*>(dst) = make_float2(h[rr][0], h[rr][1]);
+                else dst[0] = h[rr][0];
+            }
+        }
+        hmin = fminf(hmin, mn);
+        hmax = fmaxf(hmax, mx);
+    }
+}
+
+// staging registers of one chunk: up to 16 coalesced 16-byte loads per lane
+struct ChunkRegs { u32x4 q[16]; };
+
+// Issues the chunk's loads NOW.  They are marked volatile so that the compiler
+// keeps them where they are written: ahead of the arithmetic whose time is to
+// cover their latency (it would otherwise sink them next to their first use).
+// Buffer addressing: lane*16 plus a scalar offset, reads past the chunk return
+// zero, so there is no per-lane address arithmetic and no bounds branch.
+template <typename T>
+__device__ __forceinline__ void chunk_load(ChunkRegs& r, const WaveArgs& a, uint32_t chunk, uint32_t lane) {
+    const uint32_t p0 = chunk * a.G;
+    const uint32_t Gc = min(a.G, a.P - p0);
+    constexpr uint32_t EPV = 16 / sizeof(T);
+    const uint32_t nv = Gc * a.HW / EPV;
+    const T* src = static_cast<const T*>(a.x) + (size_t)p0 * a.HW;
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(nv * 16u), 0x00020000);
+    const uint32_t voff = lane * 16u;
+    constexpr int kVolatile = (int)0x80000000u;
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+        if ((uint32_t)u * 64u < nv) r.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, u * 1024u, kVolatile);
+}
+
+template <typename T>
+__device__ __forceinline__ void chunk_to_lds(const ChunkRegs& r, float* xs, uint32_t nv, uint32_t lane) {
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const uint32_t v = u * 64 + lane;
+        if (v < nv) {
+            if constexpr (sizeof(T) == 4) {
+                reinterpret_cast<u32x4*>(xs)[v] = r.q[u];
+            } else {
+                const u32x4 q = r.q[u];
+                float4 lo, hi;
+                lo.x = __uint_as_float(q.x << 16); lo.y = __uint_as_float(q.x & 0xffff0000u);
+                lo.z = __uint_as_float(q.y << 16); lo.w = __uint_as_float(q.y & 0xffff0000u);
+                hi.x = __uint_as_float(q.z << 16); hi.y = __uint_as_float(q.z & 0xffff0000u);
+                hi.z = __uint_as_float(q.w << 16); hi.w = __uint_as_float(q.w & 0xffff0000u);
+                reinterpret_cast<float4*>(xs)[2 * v] = lo;
+                reinterpret_cast<float4*>(xs)[2 * v + 1] = hi;
+            }
+        }
+    }
+}
+
+// A workgroup is ONE wavefront.  It walks over chunks of G whole planes
+// (chunk = blockIdx.x, += gridDim.x): no phase needs a cross-wave barrier, a CU
+// keeps many independent wavefronts in flight, and the HBM loads of the next
+// chunk are issued into registers before the current chunk is processed, so
+// their latency is covered by arithmetic.
+#ifndef DIVISION_WAVE_ATTR
+#define DIVISION_WAVE_ATTR
+#endif
+template <typename T, int BITS, int B, int VEC>
+__global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs a) {
+    extern __shared__ float4 smem4[];
+    float4* params = smem4;                                   // [G] (delta, inv scaled, k1, k2)
+    float* xs = reinterpret_cast<float*>(smem4 + a.G);        // [G*HW] x, later the residual h
+
+    constexpr int CPW = 32 / BITS;        // codes per word
+    constexpr int PPW = CPW / 2;          // element pairs per word
+    constexpr float Lf = float((1 << BITS) - 1);
+    constexpr uint32_t EPV = 16 / sizeof(T);
+    const uint32_t lane = threadIdx.x;
+    const uint32_t nchunks = (a.P + a.G - 1) / a.G;
+    if (blockIdx.x == 0) zero_pads(a.pads, lane);
+
+    ChunkRegs regs;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) regs.q[u] = u32x4{0u, 0u, 0u, 0u};
+    if (a.vec_load) chunk_load<T>(regs, a, blockIdx.x, lane);
+
+    for (uint32_t chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
+        const uint32_t p0 = chunk * a.G;
+        const uint32_t Gc = min(a.G, a.P - p0);
+        const uint32_t n = Gc * a.HW;
+
+        // ---- phase 0: staged chunk -> LDS (fp32); then start fetching the next chunk
+        {
+            const uint32_t nv = a.vec_load ? n / EPV : 0;
+            if (a.vec_load) {
+#ifdef DIVISION_EXPERIMENT
+                if (!(a.skip & 16u))
+#endif
+                chunk_to_lds<T>(regs, xs, nv, lane);
+            }
+            const T* src = static_cast<const T*>(a.x) + (size_t)p0 * a.HW;
+            for (uint32_t e = nv * EPV + lane; e < n; e += 64) xs[e] = Elem<T>::load(src, e);
+            if (a.vec_load && chunk + gridDim.x < nchunks) chunk_load<T>(regs, a, chunk + gridDim.x, lane);
+        }
+        wave_sync();
+
+        // ---- phases 1+2: pooling items, then the plane's min / max and scale.
+        // ippp <= 64: a round covers 64/ippp whole planes; else a plane takes ippp/64 rounds.
+        {
+            const bool small = a.ippp <= 64;
+            const uint32_t ppr = small ? 64u >> a.ippp_log2 : 1u;       // planes per round
+            const uint32_t rpp = small ? 1u : a.ippp >> 6;               // rounds per plane
+            const uint32_t S = small ? a.ippp : 64u;
+            const uint32_t gsub = small ? lane >> a.ippp_log2 : 0u;
+            const uint32_t sub = lane & (S - 1);
+            const bool fullrows = (a.H % B) == 0;
+#if !defined(DIVISION_STRIP1)
+#ifdef DIVISION_EXPERIMENT
+            if (!(a.skip & 8u))
+#endif
+            for (uint32_t g0 = 0; g0 < Gc; g0 += ppr) {
+                const uint32_t g = g0 + gsub;
+                const bool live = g < Gc;
+                T* lfc_plane = static_cast<T*>(a.lfc) + (size_t)(p0 + g) * a.nb;
+                float mn = __builtin_inff(), mx = -__builtin_inff();
+#ifdef DIVISION_EXPERIMENT
+                if (a.skip & 1u) { mn = 0.f; mx = 1.f; } else
+#endif
+                if (fullrows)
+                    for (uint32_t t = 0; t < rpp; ++t) pool_item<T, B, VEC, true>(xs, a, lfc_plane, g, t * 64 + sub, live, mn, mx);
+                else
+                    for (uint32_t t = 0; t < rpp; ++t) pool_item<T, B, VEC, false>(xs, a, lfc_plane, g, t * 64 + sub, live, mn, mx);
+                group_minmax(S, mn, mx);
+                float Delta, inv;
+                plane_scale(mn, mx, Lf, Delta, inv);
+                const uint32_t p = p0 + g;
+                const uint32_t k1 = mix32(p ^ a.seed_a);
+                const uint32_t k2 = mix32(k1 + a.seed_c);
+                if (live && sub == 0) {
+                    reinterpret_cast<float2*>(a.meta)[p] = make_float2(mn, Delta);
+                    params[g] = make_float4(mn, inv * (float)(1u << (32 - BITS)), __uint_as_float(k1), __uint_as_float(k2));
+                }
+            }
+#endif
+        }
+        wave_sync();
+
+        // ---- phase 3: Quant of Eq. (quantization) + packing
+        {
+            const uint32_t nwords = Gc * a.WPP;
+            const bool hw4 = (a.HW & 3u) == 0;
+            const uint32_t rscale = 1u << (16 - BITS);
+            // a short last round is done pair-per-lane instead of word-per-lane
+            const uint32_t tailw = nwords & 63u;
+            const bool pair_tail = tailw != 0 && tailw * PPW <= 64;
+            const uint32_t nfull = pair_tail ? nwords - tailw : nwords;
+#ifdef DIVISION_EXPERIMENT
+            if (a.skip & 2u) {
+                for (uint32_t wi = lane; wi < nwords; wi += 64) {
+                    const uint32_t g = fdiv(wi, a.d_wpp);
+                    const uint32_t k = wi - g * a.WPP;
+                    if (!(a.skip & 32u) || k == 0)
+                        a.codes[(size_t)(p0 + g) * a.WPP + k] = (a.skip & 4u) ? 0u : __float_as_uint(xs[g * a.HW + k * CPW]);
+                }
+                wave_sync();
+                continue;
+            }
+#endif
+#if !defined(DIVISION_STRIP3)
+            for (uint32_t wi = lane; wi < nfull; wi += 64) {
+                const uint32_t g = fdiv(wi, a.d_wpp);
+                const uint32_t k = wi - g * a.WPP;
+                const float4 pr = params[g];
+                const float delta = pr.x, invs = pr.y;
+                const uint32_t k1 = __float_as_uint(pr.z), k2 = __float_as_uint(pr.w);
+                const uint32_t e0 = k * CPW;
+                const uint32_t left = a.HW - e0;
+                const float* hp = xs + g * a.HW + e0;
+                float h[CPW];
+                if (hw4 && left >= (uint32_t)CPW) {
+#pragma unroll
+                    for (int q = 0; q < CPW / 4; ++q) {
+                        float4 f = reinterpret_cast<const float4*>(hp)[q];
+                        h[4 * q] = f.x; h[4 * q + 1] = f.y; h[4 * q + 2] = f.z; h[4 * q + 3] = f.w;
+                    }
+                } else {
+                    // ragged tail: elements past the plane take h = delta -> t = 0 -> code 0
+#pragma unroll
+                    for (int e = 0; e < CPW; ++e) h[e] = (uint32_t)e < left ? hp[e] : delta;
+                }
+                const uint32_t xw0 = k1 + (k * PPW) * kWeyl;
+                uint32_t word = 0;
+#pragma unroll
+                for (int j = PPW - 1; j >= 0; --j)
+                    word = push_pair<BITS>(word, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+                a.codes[(size_t)(p0 + g) * a.WPP + k] = word;
+            }
+            if (pair_tail) {
+                // lane = one element pair of the last words; PPW adjacent lanes build one word
+                const uint32_t wi = nfull + lane / PPW;
+                const uint32_t pw = lane % PPW;
+                const bool act = wi < nwords;
+                uint32_t part = 0;
+                uint32_t g = 0, k = 0;
+                if (act) {
+                    g = fdiv(wi, a.d_wpp);
+                    k = wi - g * a.WPP;
+                    const float4 pr = params[g];
+                    const float delta = pr.x, invs = pr.y;
+                    const uint32_t k1 = __float_as_uint(pr.z), k2 = __float_as_uint(pr.w);
+                    const uint32_t e0 = k * CPW + 2 * pw;
+                    const float* hp = xs + g * a.HW;
+                    const float h0 = e0 < a.HW ? hp[e0] : delta;
+                    const float h1 = e0 + 1 < a.HW ? hp[e0 + 1] : delta;
+                    const uint32_t two = push_pair<BITS>(0u, h0, h1, delta, invs, k1 + (k * PPW + pw) * kWeyl, k2, rscale);
+                    part = two << (pw * 2 * BITS);
+                }
+                part |= __builtin_amdgcn_update_dpp(0, (int)part, kDppXor1, 0xf, 0xf, false);
+                part |= __builtin_amdgcn_update_dpp(0, (int)part, kDppXor2, 0xf, 0xf, false);
+                if constexpr (PPW == 8) part |= __builtin_amdgcn_update_dpp(0, (int)part, kDppHalfMirror, 0xf, 0xf, false);
+                if (act && pw == 0) a.codes[(size_t)(p0 + g) * a.WPP + k] = part;
+            }
+#endif
+        }
+        wave_sync();      // the next chunk overwrites xs and params
     }
 }
 
@@ -589,6 +1005,35 @@ Pads make_pads(char* pk, const Layout& L) {
     return pd;
 }
 
+// tuning of the tiled compress kernel: threads per workgroup and preferred LDS
+// bytes per workgroup; DIVISION_TUNE="nt=64,lds=16384" overrides for experiments
+// tuning: nt = 64 enables the one-wavefront kernel for planes whose LDS
+// footprint is at most `lds` bytes; DIVISION_TUNE="nt=256,lds=16384" overrides
+// the defaults for experiments
+struct Tune { int nt; uint32_t lds; };
+Tune tile_tune() {
+    static Tune t = [] {
+        Tune v{64, 17u << 10};
+        if (const char* e = getenv("DIVISION_TUNE")) {
+            int nt = 0; unsigned lds = 0;
+            if (sscanf(e, "nt=%d,lds=%u", &nt, &lds) == 2 && (nt == 64 || nt == 256) && lds >= 1024) { v.nt = nt; v.lds = lds; }
+        }
+        return v;
+    }();
+    return t;
+}
+
+int num_cus() {
+    static int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+            v = 256;
+        return v;
+    }();
+    return n;
+}
+
 // dynamic LDS above the default limit needs a one-time opt-in per kernel
 hipError_t allow_large_lds(void (*kern)(TileArgs), size_t lds) {
     if (lds <= 48u * 1024u) return hipSuccess;
@@ -598,12 +1043,12 @@ hipError_t allow_large_lds(void (*kern)(TileArgs), size_t lds) {
 
 template <typename T, int BITS, int B>
 hipError_t launch_tile_vec(int vec, const TileArgs& a, uint32_t grid, size_t lds, hipStream_t st) {
-    void (*kern)(TileArgs) = vec == 4 ? compress_tile<T, BITS, B, 4>
-                           : vec == 2 ? compress_tile<T, BITS, B, 2>
-                                      : compress_tile<T, BITS, B, 1>;
+    void (*kern)(TileArgs) = vec == 4 ? compress_tile<T, BITS, B, 4, 256>
+                           : vec == 2 ? compress_tile<T, BITS, B, 2, 256>
+                                      : compress_tile<T, BITS, B, 1, 256>;
     hipError_t e = allow_large_lds(kern, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a);
     return hipGetLastError();
 }
 
@@ -613,9 +1058,82 @@ hipError_t launch_tile(int B, int vec, const TileArgs& a, uint32_t grid, size_t 
                   : launch_tile_vec<T, BITS, 4>(vec, a, grid, lds, st);
 }
 
+template <typename T, int BITS, int B>
+hipError_t launch_wave_vec(int vec, const WaveArgs& a, uint32_t grid, size_t lds, hipStream_t st) {
+    void (*kern)(WaveArgs) = vec == 4 ? compress_wave<T, BITS, B, 4>
+                           : vec == 2 ? compress_wave<T, BITS, B, 2>
+                                      : compress_wave<T, BITS, B, 1>;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64), lds, st, a);
+    return hipGetLastError();
+}
+
+template <typename T, int BITS>
+hipError_t launch_wave(int B, int vec, const WaveArgs& a, uint32_t grid, size_t lds, hipStream_t st) {
+    return B == 8 ? launch_wave_vec<T, BITS, 8>(vec, a, grid, lds, st)
+                  : launch_wave_vec<T, BITS, 4>(vec, a, grid, lds, st);
+}
+
+// Fills the one-wavefront compress plan; false when the shape is not covered.
+bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, const void* x,
+               WaveArgs* a, uint32_t* grid, size_t* lds, int* vec_out) {
+    const Tune tune = tile_tune();
+    if ((B != 4 && B != 8) || tune.nt != 64) return false;
+    const uint64_t per_plane = 4ull * L.HW + 16ull;
+    if (per_plane > tune.lds || tune.lds > 48u * 1024u) return false;
+    const int vec = (W % 4 == 0) ? 4 : (W % 2 == 0) ? 2 : 1;
+    const uint32_t ipb = (uint32_t)B / (uint32_t)vec;
+    const uint64_t slots = ((uint64_t)W + vec - 1) / vec;
+    const uint64_t ipr = (slots + ipb - 1) / ipb * ipb;
+    const uint64_t ipp = L.LH * ipr;
+    uint64_t ippp = 1, lg = 0;
+    if (ipp <= 64) { while (ippp < ipp) { ippp *= 2; ++lg; } }
+    else ippp = (ipp + 63) / 64 * 64;
+    uint64_t Gmax = tune.lds / per_plane;
+    if (Gmax > L.P) Gmax = L.P;
+    const uint64_t unit = 16 / gcd_u64(16, L.HW * es);
+    uint32_t vec_load = ((uintptr_t)x % 16) == 0;
+    if (vec_load && unit > 1 && Gmax < unit && Gmax < L.P) vec_load = 0;
+    const uint64_t step = vec_load ? unit : 1;
+    // pick the G that wastes the fewest lanes in partly filled rounds
+    const uint64_t cpw = 32 / b, ppw = cpw / 2;
+    const double c1 = 4.5 * B * vec, c3 = 8.5 * (double)cpw;
+    uint64_t G = 0;
+    double best = 0;
+    for (uint64_t g = step; g <= Gmax; g += step) {
+        const double r1 = ipp <= 64 ? (double)((g + 64 / ippp - 1) / (64 / ippp)) : (double)(g * (ippp / 64));
+        const uint64_t nw = g * L.WPP, tw = nw % 64;
+        const double r3 = (double)(nw / 64) + (tw == 0 ? 0.0 : tw * ppw <= 64 ? 0.25 : 1.0);
+        const double per_elt = (r1 * c1 + r3 * c3 + 2.0) / (double)(g * L.HW);
+        if (G == 0 || per_elt < best * 0.97) { G = g; best = per_elt; }
+    }
+    if (G == 0) G = Gmax;          // Gmax == P < unit: a single chunk, aligned at its start
+    if (!fastdiv_ok(ippp, ipr) || !fastdiv_ok(G * L.WPP + 64, L.WPP)) return false;
+    a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
+    a->LH = (uint32_t)L.LH; a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP;
+    a->G = (uint32_t)G; a->ipr = (uint32_t)ipr; a->ipp = (uint32_t)ipp;
+    a->ippp = (uint32_t)ippp; a->ippp_log2 = (uint32_t)lg;
+    a->vec_load = vec_load;
+    a->d_ipr = make_fastdiv((uint32_t)ipr);
+    a->d_wpp = make_fastdiv((uint32_t)L.WPP);
+    *lds = 16ull * G + 4ull * ((G * L.HW + 3) / 4 * 4);
+    // the staging registers hold 16 x 64 vectors of 16 bytes
+    if (vec_load && G * L.HW * es > 16ull * 1024ull) return false;
+    // persistent wavefronts: as many as the CUs hold at once, each walking an
+    // equal number of chunks
+    const uint64_t nchunks = (L.P + G - 1) / G;
+    uint64_t per_cu = (160ull * 1024ull) / (*lds + 256);
+    if (per_cu > 12) per_cu = 12;
+    if (per_cu < 1) per_cu = 1;
+    const uint64_t resident = per_cu * (uint64_t)num_cus();
+    const uint64_t iters = (nchunks + resident - 1) / resident;
+    *grid = (uint32_t)((nchunks + iters - 1) / iters);
+    *vec_out = vec;
+    return true;
+}
+
 // Fills the tiled-compress launch plan; false when the shape is not covered.
-bool plan_tile(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* x,
-               TileArgs* a, uint32_t* grid, size_t* lds, int* vec_out) {
+bool plan_tile(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, const void* x,
+               TileArgs* a, uint32_t* grid, size_t* lds, int* vec_out, int* nt_out) {
     if (B != 4 && B != 8) return false;
     const int vec = (W % 4 == 0) ? 4 : (W % 2 == 0) ? 2 : 1;
     const uint32_t ipb = (uint32_t)B / (uint32_t)vec;
@@ -624,18 +1142,29 @@ bool plan_tile(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
     const uint64_t ipp = L.LH * ipr;
     const uint64_t per_plane = 4ull * L.HW + 8ull * ipp + 16ull;
     if (per_plane + 64 > kLdsMax) return false;
-    uint64_t G = kLdsTarget / per_plane;
-    if (G < 1) G = 1;
+    const int nt = 256;
+    uint64_t Gmax = kLdsTarget / per_plane;
+    if (Gmax < 1) Gmax = 1;
+    if (Gmax > L.P) Gmax = L.P;
     // chunk starts stay 16-byte aligned when G * (bytes per plane) is a multiple of 16
     const uint64_t unit = 16 / gcd_u64(16, L.HW * es);
     uint32_t vec_load = ((uintptr_t)x % 16) == 0;
-    if (vec_load && unit > 1) {
-        const uint64_t Gr = (G + unit - 1) / unit * unit;
-        if (Gr * per_plane + 64 <= kLdsMax) G = Gr; else vec_load = 0;
+    if (vec_load && unit > 1 && Gmax < unit && Gmax < L.P) {
+        if (unit * per_plane + 64 <= kLdsMax) Gmax = unit; else vec_load = 0;
     }
-    if (G > L.P) G = L.P;
+    const uint64_t step = vec_load ? unit : 1;
+    // pick the G whose last, partly filled wavefront pass wastes the fewest lanes
+    const double c1 = 4.0 * B * vec, c3 = 7.5 * (32 / b);
+    uint64_t G = 0;
+    double best = 0;
+    for (uint64_t g = step; g <= Gmax; g += step) {
+        const double cost = (double)((g * ipp + 63) / 64) * c1 + (double)((g * L.WPP + 63) / 64) * c3;
+        const double per_elt = cost / (double)(g * L.HW);
+        if (G == 0 || per_elt < best * 0.98) { G = g; best = per_elt; }
+    }
+    if (G == 0) G = Gmax;          // Gmax == P < unit: a single chunk, aligned at its start
     const uint64_t nitems = G * ipp, nwords = G * L.WPP;
-    if (!fastdiv_ok(nitems + kThreads, ipp) || !fastdiv_ok(ipp, ipr) || !fastdiv_ok(nwords + kThreads, L.WPP))
+    if (!fastdiv_ok(nitems + 256, ipp) || !fastdiv_ok(ipp, ipr) || !fastdiv_ok(nwords + 256, L.WPP))
         return false;
     a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
     a->LH = (uint32_t)L.LH; a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP;
@@ -652,7 +1181,51 @@ bool plan_tile(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
     *lds = 16ull * G + 4ull * a->xs_floats + 8ull * a->items_cap;
     *grid = (uint32_t)((L.P + G - 1) / G);
     *vec_out = vec;
+    *nt_out = nt;
     return *lds <= kLdsMax;
+}
+
+// Fills the decompress launch plan; returns 0 (row vectors), 1 (flat) or 2 (scalar).
+int plan_decompress(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* xhat,
+                    DecArgs* a, uint32_t* grid) {
+    a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
+    a->LH = (uint32_t)L.LH; a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP; a->B = (uint32_t)B;
+    a->d_B = make_fastdiv((uint32_t)B);
+    a->d_W = make_fastdiv((uint32_t)W);
+    a->d_HW = make_fastdiv((uint32_t)L.HW);
+    const bool small_idx = fastdiv_ok((uint64_t)H, (uint64_t)B) && fastdiv_ok((uint64_t)W, (uint64_t)B);
+    const bool out_vec_aligned = ((uintptr_t)xhat % (4 * es)) == 0;
+    const uint64_t target = 16ull * 4 * kThreads;      // elements per workgroup
+    // fast path: rows are whole vectors that sit inside one block
+    if (W % 4 == 0 && B % 4 == 0 && small_idx && out_vec_aligned) {
+        a->q4 = (uint32_t)(L.HW / 4);
+        a->w4 = (uint32_t)(W / 4);
+        uint64_t G = (target / 4 + a->q4 - 1) / a->q4;
+        if (G > L.P) G = L.P;
+        while (G > 1 && !fastdiv_ok(G * a->q4 + kThreads, a->q4)) --G;
+        if (fastdiv_ok(G * a->q4 + kThreads, a->q4) && fastdiv_ok(a->q4, a->w4)) {
+            a->G = (uint32_t)G;
+            a->d_q4 = make_fastdiv(a->q4);
+            a->d_w4 = make_fastdiv(a->w4);
+            *grid = (uint32_t)((L.P + G - 1) / G);
+            return 0;
+        }
+    }
+    // general path: flat run of G planes, G*HW a multiple of 4
+    if (small_idx && out_vec_aligned && fastdiv_ok(L.HW, (uint64_t)W)) {
+        const uint64_t unit = 4 / gcd_u64(4, L.HW);
+        uint64_t G = (target + L.HW - 1) / L.HW;
+        G = (G + unit - 1) / unit * unit;
+        if (G > L.P) G = L.P;
+        if (fastdiv_ok(G * L.HW + 4ull * kThreads, L.HW)) {
+            a->G = (uint32_t)G;
+            *grid = (uint32_t)((L.P + G - 1) / G);
+            return 1;
+        }
+    }
+    a->G = 1;
+    *grid = (uint32_t)L.P;
+    return 2;
 }
 
 }  // namespace
@@ -698,9 +1271,25 @@ int division_compress(const void* x, int64_t N, int64_t C, int64_t H, int64_t W,
     TileArgs a{};
     size_t lds = 0;
     uint32_t grid = 0;
-    int vec = 1;
+    int vec = 1, nt = 64;
     hipError_t err;
-    if (plan_tile(L, H, W, B, es, x, &a, &grid, &lds, &vec)) {
+    WaveArgs wa{};
+    if (plan_wave(L, H, W, B, b, es, x, &wa, &grid, &lds, &vec)) {
+        wa.pads = make_pads(pk, L);
+        wa.x = x;
+        wa.codes = reinterpret_cast<uint32_t*>(pk + L.codes_off);
+        wa.meta = reinterpret_cast<float*>(pk + L.meta_off);
+        wa.lfc = pk + L.lfc_off;
+        wa.seed_a = seed_a; wa.seed_c = seed_c;
+#ifdef DIVISION_EXPERIMENT
+        wa.skip = getenv("DIVISION_SKIP") ? (uint32_t)atoi(getenv("DIVISION_SKIP")) : 0u;
+        if (getenv("DIVISION_GRID")) grid = (uint32_t)atoi(getenv("DIVISION_GRID"));
+#endif
+        if (dt == DIVISION_F32)
+            err = b == 2 ? launch_wave<float, 2>(B, vec, wa, grid, lds, st) : launch_wave<float, 4>(B, vec, wa, grid, lds, st);
+        else
+            err = b == 2 ? launch_wave<bf16_t, 2>(B, vec, wa, grid, lds, st) : launch_wave<bf16_t, 4>(B, vec, wa, grid, lds, st);
+    } else if (plan_tile(L, H, W, B, b, es, x, &a, &grid, &lds, &vec, &nt)) {
         a.pads = make_pads(pk, L);
         a.x = x;
         a.codes = reinterpret_cast<uint32_t*>(pk + L.codes_off);
@@ -747,58 +1336,50 @@ int division_decompress(const void* packed, size_t packed_bytes, int64_t N, int6
     const char* pk = static_cast<const char*>(packed);
 
     DecArgs a{};
+    uint32_t grid = 0;
+    const int kind = plan_decompress(L, H, W, B, es, xhat, &a, &grid);
     a.codes = reinterpret_cast<const uint32_t*>(pk + L.codes_off);
     a.meta = reinterpret_cast<const float*>(pk + L.meta_off);
     a.lfc = pk + L.lfc_off;
     a.xhat = xhat;
-    a.P = (uint32_t)L.P; a.H = (uint32_t)H; a.W = (uint32_t)W; a.HW = (uint32_t)L.HW;
-    a.LH = (uint32_t)L.LH; a.LW = (uint32_t)L.LW; a.nb = (uint32_t)L.nb; a.WPP = (uint32_t)L.WPP; a.B = (uint32_t)B;
-    a.d_B = make_fastdiv((uint32_t)B);
-    a.d_W = make_fastdiv((uint32_t)W);
-    a.d_HW = make_fastdiv((uint32_t)L.HW);
-    const bool small_idx = fastdiv_ok((uint64_t)H, (uint64_t)B) && fastdiv_ok((uint64_t)W, (uint64_t)B);
-    const bool out_vec_aligned = ((uintptr_t)xhat % (4 * es)) == 0;
-    const uint64_t target = 16ull * 4 * kThreads;      // elements per workgroup
-
-    void (*kern)(DecArgs) = nullptr;
-    uint32_t grid = 0;
-    // fast path: rows are whole vectors that sit inside one block
-    if (W % 4 == 0 && B % 4 == 0 && small_idx && out_vec_aligned) {
-        a.q4 = (uint32_t)(L.HW / 4);
-        a.w4 = (uint32_t)(W / 4);
-        uint64_t G = (target / 4 + a.q4 - 1) / a.q4;
-        if (G > L.P) G = L.P;
-        while (G > 1 && !fastdiv_ok(G * a.q4 + kThreads, a.q4)) --G;
-        if (fastdiv_ok(G * a.q4 + kThreads, a.q4) && fastdiv_ok(a.q4, a.w4)) {
-            a.G = (uint32_t)G;
-            a.d_q4 = make_fastdiv(a.q4);
-            a.d_w4 = make_fastdiv(a.w4);
-            grid = (uint32_t)((L.P + G - 1) / G);
-            if (dt == DIVISION_F32) kern = b == 2 ? decompress_rowvec<float, 2> : decompress_rowvec<float, 4>;
-            else kern = b == 2 ? decompress_rowvec<bf16_t, 2> : decompress_rowvec<bf16_t, 4>;
-        }
-    }
-    // general path: flat run of G planes, G*HW a multiple of 4
-    if (!kern && small_idx && out_vec_aligned && fastdiv_ok(L.HW, (uint64_t)W)) {
-        const uint64_t unit = 4 / gcd_u64(4, L.HW);
-        uint64_t G = (target + L.HW - 1) / L.HW;
-        G = (G + unit - 1) / unit * unit;
-        if (G > L.P) G = L.P;
-        if (fastdiv_ok(G * L.HW + 4ull * kThreads, L.HW)) {
-            a.G = (uint32_t)G;
-            grid = (uint32_t)((L.P + G - 1) / G);
-            if (dt == DIVISION_F32) kern = b == 2 ? decompress_flat<float, 2> : decompress_flat<float, 4>;
-            else kern = b == 2 ? decompress_flat<bf16_t, 2> : decompress_flat<bf16_t, 4>;
-        }
-    }
-    if (!kern) {
-        a.G = 1;
-        grid = (uint32_t)L.P;
+    void (*kern)(DecArgs);
+    if (kind == 0) {
+        if (dt == DIVISION_F32) kern = b == 2 ? decompress_rowvec<float, 2> : decompress_rowvec<float, 4>;
+        else kern = b == 2 ? decompress_rowvec<bf16_t, 2> : decompress_rowvec<bf16_t, 4>;
+    } else if (kind == 1) {
+        if (dt == DIVISION_F32) kern = b == 2 ? decompress_flat<float, 2> : decompress_flat<float, 4>;
+        else kern = b == 2 ? decompress_flat<bf16_t, 2> : decompress_flat<bf16_t, 4>;
+    } else {
         if (dt == DIVISION_F32) kern = b == 2 ? decompress_scalar<float, 2> : decompress_scalar<float, 4>;
         else kern = b == 2 ? decompress_scalar<bf16_t, 2> : decompress_scalar<bf16_t, 4>;
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), 0, st, a);
     return hipGetLastError() == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
+}
+
+int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, int64_t H, int64_t W,
+                         division_dtype dt, int B, int b, char* out, size_t cap) {
+    if (!out || cap == 0) return DIVISION_EINVAL;
+    Layout L;
+    const int rc = make_layout(N, C, H, W, B, b, (int)dt, &L);
+    if (rc != DIVISION_OK) return rc;
+    const size_t es = dt == DIVISION_BF16 ? 2 : 4;
+    const char* tn = dt == DIVISION_BF16 ? "bf16_t" : "float";
+    int n;
+    if (direction == 0) {
+        TileArgs a{}; WaveArgs wa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64;
+        if (plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))
+            n = snprintf(out, cap, "compress_wave<%s, %d, %d, %d>", tn, b, B, vec);
+        else if (plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
+            n = snprintf(out, cap, "compress_tile<%s, %d, %d, %d, %d>", tn, b, B, vec, nt);
+        else
+            n = snprintf(out, cap, "compress_any<%s, %d>", tn, b);
+    } else {
+        DecArgs a{}; uint32_t grid = 0;
+        const int kind = plan_decompress(L, H, W, B, es, data, &a, &grid);
+        n = snprintf(out, cap, "%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 1 ? "decompress_flat" : "decompress_scalar", tn, b);
+    }
+    return (n < 0 || (size_t)n >= cap) ? DIVISION_ESIZE : DIVISION_OK;
 }
 
 }  // extern "C"

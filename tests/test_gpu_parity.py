@@ -38,6 +38,13 @@ TILE_CASES = [
     ((1, 3, 5, 3), 8, 2),
     ((1, 1, 1, 1), 4, 2),
     ((300, 7, 7, 7), 8, 4),           # last workgroup holds a partial chunk
+    ((3, 5, 56, 56), 8, 4),           # 4-bit codes with a short last round (pair-per-lane tail)
+    ((4, 7, 28, 28), 8, 4),
+    ((5, 9, 14, 14), 8, 4),
+    ((7, 11, 12, 12), 4, 2),
+    ((2, 3, 64, 64), 8, 2),           # 16 KB plane
+    ((2, 3, 72, 72), 8, 2),           # above the one-wavefront budget: four-wavefront tile kernel
+    ((3, 3, 40, 40), 4, 4),
 ]
 
 ANY_CASES = [
