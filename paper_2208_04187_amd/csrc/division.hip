@@ -609,7 +609,11 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
     ChunkRegs regs;
 #pragma unroll
     for (int u = 0; u < 16; ++u) regs.q[u] = u32x4{0u, 0u, 0u, 0u};
-    if (a.vec_load) chunk_load<T>(regs, a, blockIdx.x, lane);
+    uint32_t vec_load = a.vec_load;
+#ifdef DIVISION_EXPERIMENT
+    if (a.skip & 64u) vec_load = 0;        // timing only: no global loads at all (LDS holds garbage)
+#endif
+    if (vec_load) chunk_load<T>(regs, a, blockIdx.x, lane);
 
     for (uint32_t chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
         const uint32_t p0 = chunk * a.G;
@@ -618,16 +622,19 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
 
         // ---- phase 0: staged chunk -> LDS (fp32); then start fetching the next chunk
         {
-            const uint32_t nv = a.vec_load ? n / EPV : 0;
-            if (a.vec_load) {
+            const uint32_t nv = vec_load ? n / EPV : 0;
+            if (vec_load) {
 #ifdef DIVISION_EXPERIMENT
                 if (!(a.skip & 16u))
 #endif
                 chunk_to_lds<T>(regs, xs, nv, lane);
             }
             const T* src = static_cast<const T*>(a.x) + (size_t)p0 * a.HW;
+#ifdef DIVISION_EXPERIMENT
+            if (!(a.skip & 64u))
+#endif
             for (uint32_t e = nv * EPV + lane; e < n; e += 64) xs[e] = Elem<T>::load(src, e);
-            if (a.vec_load && chunk + gridDim.x < nchunks) chunk_load<T>(regs, a, chunk + gridDim.x, lane);
+            if (vec_load && chunk + gridDim.x < nchunks) chunk_load<T>(regs, a, chunk + gridDim.x, lane);
         }
         wave_sync();
 
@@ -869,31 +876,66 @@ __device__ __forceinline__ void store4(T* dst, size_t i, float a, float b, float
     }
 }
 
+// Copies this workgroup's slices of the three packed regions (codes, meta, LFC
+// of planes p0 .. p0+Gc-1: about 8 % of the output volume) into LDS with
+// coalesced loads, so that the streaming loop below depends on LDS latency
+// only and its 16-byte stores go out back to back.
+template <typename T>
+__device__ __forceinline__ void stage_packed(const DecArgs& a, uint32_t p0, uint32_t Gc, uint32_t* s_codes,
+                                             float2* s_meta, T* s_lfc, uint32_t tid) {
+    const uint32_t nw = Gc * a.WPP;
+    const uint32_t* src = a.codes + (size_t)p0 * a.WPP;
+    if ((((size_t)p0 * a.WPP) & 3u) == 0) {
+        const uint32_t nq = nw >> 2;
+        for (uint32_t i = tid; i < nq; i += kThreads)
+            reinterpret_cast<u32x4*>(s_codes)[i] = reinterpret_cast<const u32x4*>(src)[i];
+        for (uint32_t i = (nq << 2) + tid; i < nw; i += kThreads) s_codes[i] = src[i];
+    } else {
+        for (uint32_t i = tid; i < nw; i += kThreads) s_codes[i] = src[i];
+    }
+    for (uint32_t i = tid; i < Gc; i += kThreads) s_meta[i] = reinterpret_cast<const float2*>(a.meta)[p0 + i];
+    const uint32_t nl = Gc * a.nb;
+    const T* lsrc = static_cast<const T*>(a.lfc) + (size_t)p0 * a.nb;
+    for (uint32_t i = tid; i < nl; i += kThreads) s_lfc[i] = lsrc[i];
+    lds_barrier();
+}
+
+// LDS carve-up shared by the two streaming kernels (the host sizes it the same way)
+template <typename T>
+__device__ __forceinline__ void dec_lds(const DecArgs& a, uint32_t*& s_codes, float2*& s_meta, T*& s_lfc) {
+    extern __shared__ float4 smem4[];
+    s_codes = reinterpret_cast<uint32_t*>(smem4);
+    s_meta = reinterpret_cast<float2*>(s_codes + ((a.G * a.WPP + 3u) & ~3u));
+    s_lfc = reinterpret_cast<T*>(s_meta + a.G);
+}
+
 // W % 4 == 0 and B % 4 == 0: the four elements of a vector lie in one row and
 // share one LFC value.  A workgroup streams G whole planes.
 template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) decompress_rowvec(DecArgs a) {
+    uint32_t* s_codes; float2* s_meta; T* s_lfc;
+    dec_lds<T>(a, s_codes, s_meta, s_lfc);
     const uint32_t tid = threadIdx.x;
     const uint32_t p0 = blockIdx.x * a.G;
     const uint32_t Gc = min(a.G, a.P - p0);
+    stage_packed<T>(a, p0, Gc, s_codes, s_meta, s_lfc, tid);
     const uint32_t nvec = Gc * a.q4;
     constexpr uint32_t Lq = (1u << BITS) - 1u;
+    T* out = static_cast<T*>(a.xhat) + (size_t)p0 * a.HW;
     for (uint32_t vi = tid; vi < nvec; vi += kThreads) {
         const uint32_t g = fdiv(vi, a.d_q4);
         const uint32_t fi = vi - g * a.q4;        // vector index inside the plane
-        const uint32_t p = p0 + g;
-        const float2 dd = reinterpret_cast<const float2*>(a.meta)[p];
+        const float2 dd = s_meta[g];
         uint32_t c4;                               // the four codes, BITS apart from bit 0
-        if constexpr (BITS == 2) c4 = reinterpret_cast<const uint8_t*>(a.codes)[(size_t)p * a.WPP * 4 + fi];
-        else c4 = reinterpret_cast<const uint16_t*>(a.codes)[(size_t)p * a.WPP * 2 + fi];
+        if constexpr (BITS == 2) c4 = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + fi];
+        else c4 = reinterpret_cast<const uint16_t*>(s_codes)[g * a.WPP * 2 + fi];
         const uint32_t r = fdiv(fi, a.d_w4);
         const uint32_t c = (fi - r * a.w4) * 4;
-        const T* lfcp = static_cast<const T*>(a.lfc) + (size_t)p * a.nb;
-        const float lfc = Elem<T>::load(lfcp, fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B));
+        const float lfc = Elem<T>::load(s_lfc, g * a.nb + fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B));
         float o[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = dequant((c4 >> (e * BITS)) & Lq, dd.y, dd.x, lfc);
-        store4(static_cast<T*>(a.xhat), (size_t)p * a.HW + (size_t)fi * 4, o[0], o[1], o[2], o[3]);
+        store4(out, (size_t)vi * 4, o[0], o[1], o[2], o[3]);
     }
 }
 
@@ -903,11 +945,14 @@ __global__ void __launch_bounds__(kThreads) decompress_rowvec(DecArgs a) {
 // vector stores stay aligned; the ragged end of the last chunk is scalar.
 template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) {
+    uint32_t* s_codes; float2* s_meta; T* s_lfc;
+    dec_lds<T>(a, s_codes, s_meta, s_lfc);
     constexpr uint32_t CPW = 32 / BITS;
     constexpr uint32_t Lq = (1u << BITS) - 1u;
     const uint32_t tid = threadIdx.x;
     const uint32_t p0 = blockIdx.x * a.G;
     const uint32_t Gc = min(a.G, a.P - p0);
+    stage_packed<T>(a, p0, Gc, s_codes, s_meta, s_lfc, tid);
     const uint32_t n = Gc * a.HW;
     T* out = static_cast<T*>(a.xhat) + (size_t)p0 * a.HW;
     for (uint32_t e0 = tid * 4; e0 < n; e0 += kThreads * 4) {
@@ -920,11 +965,9 @@ __global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) {
         for (int e = 0; e < 4; ++e) {
             o[e] = 0.0f;
             if (e0 + e < n) {
-                const uint32_t p = p0 + g;
-                const float2 dd = reinterpret_cast<const float2*>(a.meta)[p];
-                const uint32_t q = (a.codes[(size_t)p * a.WPP + i / CPW] >> ((i % CPW) * BITS)) & Lq;
-                const T* lfcp = static_cast<const T*>(a.lfc) + (size_t)p * a.nb;
-                const float lfc = Elem<T>::load(lfcp, fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B));
+                const float2 dd = s_meta[g];
+                const uint32_t q = (s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS)) & Lq;
+                const float lfc = Elem<T>::load(s_lfc, g * a.nb + fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B));
                 o[e] = dequant(q, dd.y, dd.x, lfc);
                 ++i;
                 if (++c == a.W) { c = 0; ++r; }
@@ -1186,6 +1229,12 @@ bool plan_tile(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
 }
 
 // Fills the decompress launch plan; returns 0 (row vectors), 1 (flat) or 2 (scalar).
+// LDS bytes of the streaming decompress kernels for G planes per workgroup
+size_t dec_lds_bytes(const Layout& L, size_t es, uint64_t G) {
+    return 4ull * ((G * L.WPP + 3) & ~(uint64_t)3) + 8ull * G + es * G * L.nb + 16;
+}
+constexpr size_t kDecLdsMax = 60u << 10;
+
 int plan_decompress(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* xhat,
                     DecArgs* a, uint32_t* grid) {
     a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
@@ -1203,7 +1252,7 @@ int plan_decompress(const Layout& L, int64_t H, int64_t W, int B, size_t es, con
         uint64_t G = (target / 4 + a->q4 - 1) / a->q4;
         if (G > L.P) G = L.P;
         while (G > 1 && !fastdiv_ok(G * a->q4 + kThreads, a->q4)) --G;
-        if (fastdiv_ok(G * a->q4 + kThreads, a->q4) && fastdiv_ok(a->q4, a->w4)) {
+        if (fastdiv_ok(G * a->q4 + kThreads, a->q4) && fastdiv_ok(a->q4, a->w4) && dec_lds_bytes(L, es, G) <= kDecLdsMax) {
             a->G = (uint32_t)G;
             a->d_q4 = make_fastdiv(a->q4);
             a->d_w4 = make_fastdiv(a->w4);
@@ -1217,7 +1266,7 @@ int plan_decompress(const Layout& L, int64_t H, int64_t W, int B, size_t es, con
         uint64_t G = (target + L.HW - 1) / L.HW;
         G = (G + unit - 1) / unit * unit;
         if (G > L.P) G = L.P;
-        if (fastdiv_ok(G * L.HW + 4ull * kThreads, L.HW)) {
+        if (fastdiv_ok(G * L.HW + 4ull * kThreads, L.HW) && dec_lds_bytes(L, es, G) <= kDecLdsMax) {
             a->G = (uint32_t)G;
             *grid = (uint32_t)((L.P + G - 1) / G);
             return 1;
@@ -1353,7 +1402,10 @@ int division_decompress(const void* packed, size_t packed_bytes, int64_t N, int6
         if (dt == DIVISION_F32) kern = b == 2 ? decompress_scalar<float, 2> : decompress_scalar<float, 4>;
         else kern = b == 2 ? decompress_scalar<bf16_t, 2> : decompress_scalar<bf16_t, 4>;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), 0, st, a);
+    // LDS of the streaming kernels: staged codes, meta and LFC of G planes
+    size_t lds = 0;
+    if (kind != 2) lds = dec_lds_bytes(L, es, a.G);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, st, a);
     return hipGetLastError() == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
 }
 
