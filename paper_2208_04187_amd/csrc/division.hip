@@ -454,12 +454,30 @@ struct WaveArgs {
 #endif
 };
 
+// (float)(S / cnt) for a small positive integer cnt, the way the reference
+// definition rounds it (binary64 quotient, then one rounding to binary32),
+// without a binary64 division in the common case: q = S * (1/cnt) is within
+// 2 ulp of the binary64 quotient, so both round to the same binary32 value
+// unless q lies within a few ulp of a binary32 rounding midpoint (the 29
+// mantissa bits a binary32 drops close to 1000...0); only then, for the whole
+// wavefront, the true division runs.
+__device__ __forceinline__ float mean_of(double S, uint32_t cnt) {
+    if ((cnt & (cnt - 1)) == 0) return (float)(S * (1.0 / (double)cnt));     // power of two: exact scaling
+    const double q = S * (1.0 / (double)cnt);
+    const uint32_t low = (uint32_t)__double_as_longlong(q) & 0x1fffffffu;
+    const uint32_t dist = low > 0x10000000u ? low - 0x10000000u : 0x10000000u - low;
+    if (__builtin_expect(__any(dist < 16u), 0)) return (float)(S / (double)cnt);
+    return (float)q;
+}
+
 // Sec. 4.1 for one pooling item: B rows x VEC columns of one block, read from
 // LDS; the IPB items of a block sit in adjacent lanes.  Writes the block's LFC,
 // overwrites x by the residual, folds the item's residual min / max into
-// (hmin, hmax).  FULLROWS: H is a multiple of B, so every row of every block
-// exists and the body needs no per-row predicate; lanes without an item work
-// on item 0 of the chunk and have their effects masked.
+// (hmin, hmax).  Lanes without an item work on item 0 of the chunk and have
+// their effects masked.  Rows past the map (ragged last block row, FULLROWS
+// false) re-read row 0 of the item: a duplicate changes neither min nor max,
+// its residual is written back to the very value row 0 gets, and its row sum
+// is left out of the block sum.
 template <typename T, int B, int VEC, bool FULLROWS>
 __device__ __forceinline__ void pool_item(float* xs, const WaveArgs& a, T* lfc_plane, uint32_t g, uint32_t rem,
                                           bool live, float& hmin, float& hmax) {
@@ -470,17 +488,16 @@ __device__ __forceinline__ void pool_item(float* xs, const WaveArgs& a, T* lfc_p
     const uint32_t r0 = bi * B;
     const bool valid = live && rem < a.ipp && col0 < a.W;
     const uint32_t base = valid ? g * a.HW + r0 * a.W + col0 : 0u;
-    const uint32_t nrows = FULLROWS ? (uint32_t)B : (valid ? min((uint32_t)B, a.H - r0) : 0u);
+    const uint32_t nrows = FULLROWS ? (uint32_t)B : (valid ? min((uint32_t)B, a.H - r0) : 1u);
 
     float v[B][VEC];
-    double acc[VEC];
-#pragma unroll
-    for (int c = 0; c < VEC; ++c) acc[c] = 0.0;
+    uint32_t off[B];
+    double S = 0.0;
 #pragma unroll
     for (int rr = 0; rr < B; ++rr) {
-        // rows past the map re-read row 0 of the item (always present) and count as zero
         const bool ok = FULLROWS || (uint32_t)rr < nrows;
-        const float* src = xs + base + (ok ? rr : 0) * a.W;
+        off[rr] = base + (ok ? rr : 0) * a.W;
+        const float* src = xs + off[rr];
         if constexpr (VEC == 4) {
             float4 q = *reinterpret_cast<const float4*>(src);
             v[rr][0] = q.x; v[rr][1] = q.y; v[rr][2] = q.z; v[rr][3] = q.w;
@@ -490,12 +507,11 @@ __device__ __forceinline__ void pool_item(float* xs, const WaveArgs& a, T* lfc_p
         } else {
             v[rr][0] = src[0];
         }
+        double rs = (double)v[rr][0];
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) acc[c] += ok ? (double)v[rr][c] : 0.0;
+        for (int c = 1; c < VEC; ++c) rs += (double)v[rr][c];
+        S += ok ? rs : 0.0;
     }
-    double S = acc[0];
-#pragma unroll
-    for (int c = 1; c < VEC; ++c) S += acc[c];
     S = valid ? S : 0.0;
     S = group_sum<IPB>(S);
 
@@ -504,34 +520,27 @@ __device__ __forceinline__ void pool_item(float* xs, const WaveArgs& a, T* lfc_p
     const uint32_t cols = min((uint32_t)B, a.W - min(a.W, bj * B));
     const uint32_t cnt = max(rows * cols, 1u);
     // exact sum / count, one rounding to fp32, then to the storage type
-    float m;
-    if ((cnt & (cnt - 1)) == 0) m = (float)(S * (1.0 / (double)cnt));   // power of two: exact scaling
-    else m = (float)(S / (double)cnt);
-    const float lfc = Elem<T>::round(m);
+    const float lfc = Elem<T>::round(mean_of(S, cnt));
     if (valid && (s % IPB) == 0) Elem<T>::store(lfc_plane, bi * a.LW + bj, lfc);
 
     // H^H = H - UpSampling(H^L), written back over x
     float mn = __builtin_inff(), mx = -__builtin_inff();
     float h[B][VEC];
 #pragma unroll
-    for (int rr = 0; rr < B; ++rr) {
-        const bool ok = FULLROWS || (uint32_t)rr < nrows;
+    for (int rr = 0; rr < B; ++rr)
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
             h[rr][c] = v[rr][c] - lfc;
-            mn = fminf(mn, ok ? h[rr][c] : __builtin_inff());
-            mx = fmaxf(mx, ok ? h[rr][c] : -__builtin_inff());
+            mn = fminf(mn, h[rr][c]);
+            mx = fmaxf(mx, h[rr][c]);
         }
-    }
     if (valid) {
 #pragma unroll
         for (int rr = 0; rr < B; ++rr) {
-            if (FULLROWS || (uint32_t)rr < nrows) {
-                float* dst = xs + base + rr * a.W;
-                if constexpr (VEC == 4) *reinterpret_cast<float4*>(dst) = make_float4(h[rr][0], h[rr][1], h[rr][2], h[rr][3]);
-                else if constexpr (VEC == 2) *reinterpret_cast<float2*>(dst) = make_float2(h[rr][0], h[rr][1]);
-                else dst[0] = h[rr][0];
-            }
+            float* dst = xs + off[rr];
+            if constexpr (VEC == 4) *reinterpret_cast<float4*>(dst) = make_float4(h[rr][0], h[rr][1], h[rr][2], h[rr][3]);
+            else if constexpr (VEC == 2) *reinterpret_cast<float2*>(dst) = make_float2(h[rr][0], h[rr][1]);
+            else dst[0] = h[rr][0];
         }
         hmin = fminf(hmin, mn);
         hmax = fmaxf(hmax, mx);
@@ -665,17 +674,22 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
                 else
                     for (uint32_t t = 0; t < rpp; ++t) pool_item<T, B, VEC, false>(xs, a, lfc_plane, g, t * 64 + sub, live, mn, mx);
                 group_minmax(S, mn, mx);
-                float Delta, inv;
-                plane_scale(mn, mx, Lf, Delta, inv);
-                const uint32_t p = p0 + g;
-                const uint32_t k1 = mix32(p ^ a.seed_a);
-                const uint32_t k2 = mix32(k1 + a.seed_c);
-                if (live && sub == 0) {
-                    reinterpret_cast<float2*>(a.meta)[p] = make_float2(mn, Delta);
-                    params[g] = make_float4(mn, inv * (float)(1u << (32 - BITS)), __uint_as_float(k1), __uint_as_float(k2));
-                }
+                if (live && sub == 0) params[g] = make_float4(mn, mx, 0.0f, 0.0f);
             }
 #endif
+        }
+        wave_sync();
+
+        // ---- phase 2: one lane per plane: scale of Eq. (quantization) and the plane's keys
+        for (uint32_t g = lane; g < Gc; g += 64) {
+            const float4 mm = params[g];
+            float Delta, inv;
+            plane_scale(mm.x, mm.y, Lf, Delta, inv);
+            const uint32_t p = p0 + g;
+            const uint32_t k1 = mix32(p ^ a.seed_a);
+            const uint32_t k2 = mix32(k1 + a.seed_c);
+            reinterpret_cast<float2*>(a.meta)[p] = make_float2(mm.x, Delta);
+            params[g] = make_float4(mm.x, inv * (float)(1u << (32 - BITS)), __uint_as_float(k1), __uint_as_float(k2));
         }
         wave_sync();
 
@@ -955,23 +969,61 @@ __global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) {
     stage_packed<T>(a, p0, Gc, s_codes, s_meta, s_lfc, tid);
     const uint32_t n = Gc * a.HW;
     T* out = static_cast<T*>(a.xhat) + (size_t)p0 * a.HW;
+    const bool one_block = a.nb == 1;             // map smaller than the block: LFC is one value per plane
     for (uint32_t e0 = tid * 4; e0 < n; e0 += kThreads * 4) {
         uint32_t g = fdiv(e0, a.d_HW);
         uint32_t i = e0 - g * a.HW;
-        uint32_t r = fdiv(i, a.d_W);
-        uint32_t c = i - r * a.W;
         float o[4];
+        if (i + 4 <= a.HW && (i % CPW) + 4 <= CPW) {
+            // the four elements share plane, scale and code word
+            const float2 dd = s_meta[g];
+            const uint32_t w = s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS);
+            const T* lp = s_lfc + g * a.nb;
+            if (one_block) {
+                const float lfc = Elem<T>::load(lp, 0);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            o[e] = 0.0f;
-            if (e0 + e < n) {
-                const float2 dd = s_meta[g];
-                const uint32_t q = (s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS)) & Lq;
-                const float lfc = Elem<T>::load(s_lfc, g * a.nb + fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B));
-                o[e] = dequant(q, dd.y, dd.x, lfc);
-                ++i;
-                if (++c == a.W) { c = 0; ++r; }
-                if (i == a.HW) { i = 0; r = 0; ++g; }
+                for (int e = 0; e < 4; ++e) o[e] = dequant((w >> (e * BITS)) & Lq, dd.y, dd.x, lfc);
+            } else {
+                uint32_t r = fdiv(i, a.d_W);
+                uint32_t c = i - r * a.W;
+                uint32_t rowoff = fdiv(r, a.d_B) * a.LW;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float lfc = Elem<T>::load(lp, rowoff + fdiv(c, a.d_B));
+                    o[e] = dequant((w >> (e * BITS)) & Lq, dd.y, dd.x, lfc);
+                    if (++c == a.W) { c = 0; ++r; rowoff = fdiv(r, a.d_B) * a.LW; }
+                }
+            }
+            store4(out, e0, o[0], o[1], o[2], o[3]);
+            continue;
+        }
+        if (one_block) {
+            // at most one plane boundary inside the vector when HW >= 4; handled per element
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                o[e] = 0.0f;
+                if (e0 + e < n) {
+                    const float2 dd = s_meta[g];
+                    const uint32_t q = (s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS)) & Lq;
+                    o[e] = dequant(q, dd.y, dd.x, Elem<T>::load(s_lfc, g));
+                    if (++i == a.HW) { i = 0; ++g; }
+                }
+            }
+        } else {
+            uint32_t r = fdiv(i, a.d_W);
+            uint32_t c = i - r * a.W;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                o[e] = 0.0f;
+                if (e0 + e < n) {
+                    const float2 dd = s_meta[g];
+                    const uint32_t q = (s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS)) & Lq;
+                    const float lfc = Elem<T>::load(s_lfc, g * a.nb + fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B));
+                    o[e] = dequant(q, dd.y, dd.x, lfc);
+                    ++i;
+                    if (++c == a.W) { c = 0; ++r; }
+                    if (i == a.HW) { i = 0; r = 0; c = 0; ++g; }
+                }
             }
         }
         if (e0 + 4 <= n) {
