@@ -550,10 +550,7 @@ __device__ __forceinline__ void pool_item(float* xs, const WaveArgs& a, T* lfc_p
 // staging registers of one chunk: up to 16 coalesced 16-byte loads per lane
 struct ChunkRegs { u32x4 q[16]; };
 
-// Issues the chunk's loads NOW.  They are marked volatile so that the compiler
-// keeps them where they are written: ahead of the arithmetic whose time is to
-// cover their latency (it would otherwise sink them next to their first use).
-// Buffer addressing: lane*16 plus a scalar offset, reads past the chunk return
+// Issues all loads of the chunk.  Buffer addressing: lane*16 plus a scalar offset, reads past the chunk return
 // zero, so there is no per-lane address arithmetic and no bounds branch.
 template <typename T>
 __device__ __forceinline__ void chunk_load(ChunkRegs& r, const WaveArgs& a, uint32_t chunk, uint32_t lane) {
@@ -565,10 +562,9 @@ __device__ __forceinline__ void chunk_load(ChunkRegs& r, const WaveArgs& a, uint
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(nv * 16u), 0x00020000);
     const uint32_t voff = lane * 16u;
-    constexpr int kVolatile = (int)0x80000000u;
 #pragma unroll
     for (int u = 0; u < 16; ++u)
-        if ((uint32_t)u * 64u < nv) r.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, u * 1024u, kVolatile);
+        if ((uint32_t)u * 64u < nv) r.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, u * 1024u, 0);
 }
 
 template <typename T>
@@ -593,11 +589,11 @@ __device__ __forceinline__ void chunk_to_lds(const ChunkRegs& r, float* xs, uint
     }
 }
 
-// A workgroup is ONE wavefront.  It walks over chunks of G whole planes
-// (chunk = blockIdx.x, += gridDim.x): no phase needs a cross-wave barrier, a CU
-// keeps many independent wavefronts in flight, and the HBM loads of the next
-// chunk are issued into registers before the current chunk is processed, so
-// their latency is covered by arithmetic.
+// A workgroup is ONE wavefront and owns one chunk of G whole planes: no phase
+// needs a cross-wave barrier, and a CU keeps a dozen independent wavefronts in
+// different phases in flight, so that the HBM loads of some overlap the
+// arithmetic of others (measured faster than persistent wavefronts that
+// prefetch their next chunk, which ran in lock step).
 #ifndef DIVISION_WAVE_ATTR
 #define DIVISION_WAVE_ATTR
 #endif
@@ -612,39 +608,22 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
     constexpr float Lf = float((1 << BITS) - 1);
     constexpr uint32_t EPV = 16 / sizeof(T);
     const uint32_t lane = threadIdx.x;
-    const uint32_t nchunks = (a.P + a.G - 1) / a.G;
     if (blockIdx.x == 0) zero_pads(a.pads, lane);
 
-    ChunkRegs regs;
-#pragma unroll
-    for (int u = 0; u < 16; ++u) regs.q[u] = u32x4{0u, 0u, 0u, 0u};
-    uint32_t vec_load = a.vec_load;
-#ifdef DIVISION_EXPERIMENT
-    if (a.skip & 64u) vec_load = 0;        // timing only: no global loads at all (LDS holds garbage)
-#endif
-    if (vec_load) chunk_load<T>(regs, a, blockIdx.x, lane);
-
-    for (uint32_t chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
-        const uint32_t p0 = chunk * a.G;
-        const uint32_t Gc = min(a.G, a.P - p0);
-        const uint32_t n = Gc * a.HW;
-
-        // ---- phase 0: staged chunk -> LDS (fp32); then start fetching the next chunk
-        {
-            const uint32_t nv = vec_load ? n / EPV : 0;
-            if (vec_load) {
-#ifdef DIVISION_EXPERIMENT
-                if (!(a.skip & 16u))
-#endif
-                chunk_to_lds<T>(regs, xs, nv, lane);
-            }
-            const T* src = static_cast<const T*>(a.x) + (size_t)p0 * a.HW;
-#ifdef DIVISION_EXPERIMENT
-            if (!(a.skip & 64u))
-#endif
-            for (uint32_t e = nv * EPV + lane; e < n; e += 64) xs[e] = Elem<T>::load(src, e);
-            if (vec_load && chunk + gridDim.x < nchunks) chunk_load<T>(regs, a, chunk + gridDim.x, lane);
+    const uint32_t chunk = blockIdx.x;
+    const uint32_t p0 = chunk * a.G;
+    const uint32_t Gc = min(a.G, a.P - p0);
+    const uint32_t n = Gc * a.HW;
+    {
+        // ---- phase 0: chunk -> LDS (fp32): every load is issued before the first LDS write
+        const uint32_t nv = a.vec_load ? n / EPV : 0;
+        if (a.vec_load) {
+            ChunkRegs regs;
+            chunk_load<T>(regs, a, chunk, lane);
+            chunk_to_lds<T>(regs, xs, nv, lane);
         }
+        const T* src = static_cast<const T*>(a.x) + (size_t)p0 * a.HW;
+        for (uint32_t e = nv * EPV + lane; e < n; e += 64) xs[e] = Elem<T>::load(src, e);
         wave_sync();
 
         // ---- phases 1+2: pooling items, then the plane's min / max and scale.
@@ -710,8 +689,7 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
                     if (!(a.skip & 32u) || k == 0)
                         a.codes[(size_t)(p0 + g) * a.WPP + k] = (a.skip & 4u) ? 0u : __float_as_uint(xs[g * a.HW + k * CPW]);
                 }
-                wave_sync();
-                continue;
+                return;
             }
 #endif
 #if !defined(DIVISION_STRIP3)
@@ -724,23 +702,25 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
                 const uint32_t e0 = k * CPW;
                 const uint32_t left = a.HW - e0;
                 const float* hp = xs + g * a.HW + e0;
+                // A ragged last word reads past its plane (into the next plane or the
+                // LDS slack behind the chunk); those codes are cleared below.
                 float h[CPW];
-                if (hw4 && left >= (uint32_t)CPW) {
+                if (hw4) {
 #pragma unroll
                     for (int q = 0; q < CPW / 4; ++q) {
                         float4 f = reinterpret_cast<const float4*>(hp)[q];
                         h[4 * q] = f.x; h[4 * q + 1] = f.y; h[4 * q + 2] = f.z; h[4 * q + 3] = f.w;
                     }
                 } else {
-                    // ragged tail: elements past the plane take h = delta -> t = 0 -> code 0
 #pragma unroll
-                    for (int e = 0; e < CPW; ++e) h[e] = (uint32_t)e < left ? hp[e] : delta;
+                    for (int e = 0; e < CPW; ++e) h[e] = hp[e];
                 }
                 const uint32_t xw0 = k1 + (k * PPW) * kWeyl;
                 uint32_t word = 0;
 #pragma unroll
                 for (int j = PPW - 1; j >= 0; --j)
                     word = push_pair<BITS>(word, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+                if (left < (uint32_t)CPW) word &= (1u << (left * BITS)) - 1u;      // pad bits are zero
                 a.codes[(size_t)(p0 + g) * a.WPP + k] = word;
             }
             if (pair_tail) {
@@ -770,7 +750,6 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
             }
 #endif
         }
-        wave_sync();      // the next chunk overwrites xs and params
     }
 }
 
@@ -1102,13 +1081,15 @@ Pads make_pads(char* pk, const Layout& L) {
 
 // tuning of the tiled compress kernel: threads per workgroup and preferred LDS
 // bytes per workgroup; DIVISION_TUNE="nt=64,lds=16384" overrides for experiments
-// tuning: nt = 64 enables the one-wavefront kernel for planes whose LDS
-// footprint is at most `lds` bytes; DIVISION_TUNE="nt=256,lds=16384" overrides
-// the defaults for experiments
+// tuning: nt = 64 enables the one-wavefront kernel; `lds` is the preferred LDS
+// footprint of one wavefront's chunk (small chunks = many wavefronts per CU),
+// a single plane of up to kWavePlaneMax bytes is taken whatever `lds` says.
+// DIVISION_TUNE="nt=256,lds=16384" overrides the defaults for experiments.
+constexpr uint32_t kWavePlaneMax = 17u << 10;
 struct Tune { int nt; uint32_t lds; };
 Tune tile_tune() {
     static Tune t = [] {
-        Tune v{64, 17u << 10};
+        Tune v{64, 8704u};
         if (const char* e = getenv("DIVISION_TUNE")) {
             int nt = 0; unsigned lds = 0;
             if (sscanf(e, "nt=%d,lds=%u", &nt, &lds) == 2 && (nt == 64 || nt == 256) && lds >= 1024) { v.nt = nt; v.lds = lds; }
@@ -1174,7 +1155,7 @@ bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
     const Tune tune = tile_tune();
     if ((B != 4 && B != 8) || tune.nt != 64) return false;
     const uint64_t per_plane = 4ull * L.HW + 16ull;
-    if (per_plane > tune.lds || tune.lds > 48u * 1024u) return false;
+    if (per_plane > kWavePlaneMax || tune.lds > 48u * 1024u) return false;
     const int vec = (W % 4 == 0) ? 4 : (W % 2 == 0) ? 2 : 1;
     const uint32_t ipb = (uint32_t)B / (uint32_t)vec;
     const uint64_t slots = ((uint64_t)W + vec - 1) / vec;
@@ -1184,10 +1165,13 @@ bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
     if (ipp <= 64) { while (ippp < ipp) { ippp *= 2; ++lg; } }
     else ippp = (ipp + 63) / 64 * 64;
     uint64_t Gmax = tune.lds / per_plane;
+    if (Gmax < 1) Gmax = 1;
     if (Gmax > L.P) Gmax = L.P;
     const uint64_t unit = 16 / gcd_u64(16, L.HW * es);
     uint32_t vec_load = ((uintptr_t)x % 16) == 0;
-    if (vec_load && unit > 1 && Gmax < unit && Gmax < L.P) vec_load = 0;
+    if (vec_load && unit > 1 && Gmax < unit && Gmax < L.P) {
+        if (unit * per_plane <= kWavePlaneMax) Gmax = unit; else vec_load = 0;
+    }
     const uint64_t step = vec_load ? unit : 1;
     // pick the G that wastes the fewest lanes in partly filled rounds
     const uint64_t cpw = 32 / b, ppw = cpw / 2;
@@ -1210,18 +1194,10 @@ bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
     a->vec_load = vec_load;
     a->d_ipr = make_fastdiv((uint32_t)ipr);
     a->d_wpp = make_fastdiv((uint32_t)L.WPP);
-    *lds = 16ull * G + 4ull * ((G * L.HW + 3) / 4 * 4);
+    *lds = 16ull * G + 4ull * ((G * L.HW + 3) / 4 * 4) + 64;      // 16 floats of slack for ragged last words
     // the staging registers hold 16 x 64 vectors of 16 bytes
     if (vec_load && G * L.HW * es > 16ull * 1024ull) return false;
-    // persistent wavefronts: as many as the CUs hold at once, each walking an
-    // equal number of chunks
-    const uint64_t nchunks = (L.P + G - 1) / G;
-    uint64_t per_cu = (160ull * 1024ull) / (*lds + 256);
-    if (per_cu > 12) per_cu = 12;
-    if (per_cu < 1) per_cu = 1;
-    const uint64_t resident = per_cu * (uint64_t)num_cus();
-    const uint64_t iters = (nchunks + resident - 1) / resident;
-    *grid = (uint32_t)((nchunks + iters - 1) / iters);
+    *grid = (uint32_t)((L.P + G - 1) / G);
     *vec_out = vec;
     return true;
 }

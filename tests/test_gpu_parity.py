@@ -209,3 +209,39 @@ def test_full_size_bf16_config3():
         st = check_against_oracle(xb, spec.B, spec.b, codec_seed(3, k), threads=16)
         print(f"config 3 {spec.name}: exact={st['exact']} flips={st['flips']}", flush=True)
         assert st["flips"] <= 1e-6 * st["elements"]
+
+
+# ---------------------------------------------------------------- block means at binary32 rounding midpoints
+
+def _midpoint_plane(rng, cnt_side=7):
+    """A cnt_side x cnt_side plane (one block when B=8) whose exact mean is a binary32
+    rounding midpoint, plus neighbours a hair above and below it."""
+    from fractions import Fraction
+    n = cnt_side * cnt_side
+    k = int(rng.integers(1 << 23, 1 << 24))
+    M = Fraction(2 * k + 1, 1 << 26)                      # odd multiple of 2^-26 in [0.25, 0.5): a midpoint
+    vals = [Fraction(int(v), 1 << 25) for v in rng.integers(1 << 23, 1 << 24, n - 3)]
+    R = n * M - sum(vals)
+    u = Fraction(float(np.float32(float(R / 2))))
+    w = Fraction(float(np.float32(float(R - u))))
+    t = R - u - w
+    assert Fraction(float(np.float32(float(t)))) == t    # the remainder is itself a binary32 value
+    planes = []
+    for eps in (Fraction(0), Fraction(1, 1 << 44), -Fraction(1, 1 << 44)):
+        tt = t + eps
+        if Fraction(float(np.float32(float(tt)))) != tt:
+            continue
+        p = np.array([float(v) for v in vals] + [float(u), float(w), float(tt)], np.float32)
+        assert sum(Fraction(float(v)) for v in p) == n * M + eps
+        planes.append(rng.permutation(p).reshape(cnt_side, cnt_side))
+    return planes
+
+
+def test_block_mean_on_rounding_midpoints():
+    rng = np.random.default_rng(77)
+    planes = []
+    while len(planes) < 96:
+        planes += _midpoint_plane(rng)
+    x = torch.from_numpy(np.stack(planes[:96]).reshape(4, 24, 7, 7))
+    st = check_against_oracle(x, 8, 2, seed=5, require_exact=True)
+    assert st["exact"]
