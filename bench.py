@@ -49,6 +49,8 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=3, help="rotating buffer sets (defeats last-level-cache reuse)")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size (not a valid headline run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run only a plain 1 GiB device copy 10 times (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -67,6 +69,16 @@ def main() -> int:
         return 3
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4,
+                          "launches": 10}))
+        return 0
 
     # ---- synthetic workload on the host, then resident in HBM (several rotating sets)
     _, specs = config(args.config)

@@ -478,17 +478,44 @@ __device__ __forceinline__ float mean_of(double S, uint32_t cnt) {
 // false) re-read row 0 of the item: a duplicate changes neither min nor max,
 // its residual is written back to the very value row 0 gets, and its row sum
 // is left out of the block sum.
-template <typename T, int B, int VEC, bool FULLROWS>
-__device__ __forceinline__ void pool_item(float* xs, const WaveArgs& a, T* lfc_plane, uint32_t g, uint32_t rem,
-                                          bool live, float& hmin, float& hmax) {
+// What a lane needs to know about its pooling item apart from the plane: the
+// same in every round, so it is worked out once per wavefront.
+struct ItemGeom {
+    uint32_t off;      // element offset of the item's first row inside its plane
+    uint32_t lfc_idx;  // index of the item's block in the plane's LFC
+    uint32_t nrows;    // rows of the block that exist (1..B)
+    uint32_t cnt;      // elements of the block (rows * columns)
+    bool in_plane;     // the slot holds an item (not padding)
+    bool writes_lfc;   // first item of its block
+};
+
+template <int B, int VEC>
+__device__ __forceinline__ ItemGeom item_geom(const WaveArgs& a, uint32_t rem) {
     constexpr int IPB = B / VEC;
+    ItemGeom gm;
     const uint32_t bi = fdiv(rem, a.d_ipr);
     const uint32_t s = rem - bi * a.ipr;
     const uint32_t col0 = s * VEC;
     const uint32_t r0 = bi * B;
-    const bool valid = live && rem < a.ipp && col0 < a.W;
-    const uint32_t base = valid ? g * a.HW + r0 * a.W + col0 : 0u;
-    const uint32_t nrows = FULLROWS ? (uint32_t)B : (valid ? min((uint32_t)B, a.H - r0) : 1u);
+    const uint32_t bj = s / IPB;
+    gm.in_plane = rem < a.ipp && col0 < a.W;
+    gm.off = gm.in_plane ? r0 * a.W + col0 : 0u;
+    gm.nrows = gm.in_plane ? min((uint32_t)B, a.H - r0) : 1u;
+    const uint32_t rows = min((uint32_t)B, a.H - min(a.H, r0));
+    const uint32_t cols = min((uint32_t)B, a.W - min(a.W, bj * B));
+    gm.cnt = max(rows * cols, 1u);
+    gm.lfc_idx = bi * a.LW + bj;
+    gm.writes_lfc = gm.in_plane && (s % IPB) == 0;
+    return gm;
+}
+
+template <typename T, int B, int VEC, bool FULLROWS>
+__device__ __forceinline__ void pool_item(float* xs, const WaveArgs& a, T* lfc_plane, uint32_t g, const ItemGeom& gm,
+                                          bool live, float& hmin, float& hmax) {
+    constexpr int IPB = B / VEC;
+    const bool valid = live && gm.in_plane;
+    const uint32_t base = valid ? g * a.HW + gm.off : 0u;
+    const uint32_t nrows = FULLROWS ? (uint32_t)B : (valid ? gm.nrows : 1u);
 
     float v[B][VEC];
     uint32_t off[B];
@@ -515,13 +542,9 @@ __device__ __forceinline__ void pool_item(float* xs, const WaveArgs& a, T* lfc_p
     S = valid ? S : 0.0;
     S = group_sum<IPB>(S);
 
-    const uint32_t bj = s / IPB;
-    const uint32_t rows = FULLROWS ? (uint32_t)B : min((uint32_t)B, a.H - min(a.H, r0));
-    const uint32_t cols = min((uint32_t)B, a.W - min(a.W, bj * B));
-    const uint32_t cnt = max(rows * cols, 1u);
     // exact sum / count, one rounding to fp32, then to the storage type
-    const float lfc = Elem<T>::round(mean_of(S, cnt));
-    if (valid && (s % IPB) == 0) Elem<T>::store(lfc_plane, bi * a.LW + bj, lfc);
+    const float lfc = Elem<T>::round(mean_of(S, gm.cnt));
+    if (live && gm.writes_lfc) Elem<T>::store(lfc_plane, gm.lfc_idx, lfc);
 
     // H^H = H - UpSampling(H^L), written back over x
     float mn = __builtin_inff(), mx = -__builtin_inff();
@@ -636,6 +659,7 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
             const uint32_t gsub = small ? lane >> a.ippp_log2 : 0u;
             const uint32_t sub = lane & (S - 1);
             const bool fullrows = (a.H % B) == 0;
+            const ItemGeom geom0 = item_geom<B, VEC>(a, sub);      // the lane's item when a plane fits one round
 #if !defined(DIVISION_STRIP1)
 #ifdef DIVISION_EXPERIMENT
             if (!(a.skip & 8u))
@@ -648,10 +672,16 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
 #ifdef DIVISION_EXPERIMENT
                 if (a.skip & 1u) { mn = 0.f; mx = 1.f; } else
 #endif
-                if (fullrows)
-                    for (uint32_t t = 0; t < rpp; ++t) pool_item<T, B, VEC, true>(xs, a, lfc_plane, g, t * 64 + sub, live, mn, mx);
-                else
-                    for (uint32_t t = 0; t < rpp; ++t) pool_item<T, B, VEC, false>(xs, a, lfc_plane, g, t * 64 + sub, live, mn, mx);
+                if (small) {
+                    if (fullrows) pool_item<T, B, VEC, true>(xs, a, lfc_plane, g, geom0, live, mn, mx);
+                    else pool_item<T, B, VEC, false>(xs, a, lfc_plane, g, geom0, live, mn, mx);
+                } else {
+                    for (uint32_t t = 0; t < rpp; ++t) {
+                        const ItemGeom gm = item_geom<B, VEC>(a, t * 64 + sub);
+                        if (fullrows) pool_item<T, B, VEC, true>(xs, a, lfc_plane, g, gm, live, mn, mx);
+                        else pool_item<T, B, VEC, false>(xs, a, lfc_plane, g, gm, live, mn, mx);
+                    }
+                }
                 group_minmax(S, mn, mx);
                 if (live && sub == 0) params[g] = make_float4(mn, mx, 0.0f, 0.0f);
             }
