@@ -27,9 +27,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs (see profiles/); None until measured for the current kernels.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# benchmark (each counter scaled by what it reads for a plain 1 GiB copy: x2.000
+# and x1.000), averaged over the kernel's launches in one step of the default
+# workload; profiles/bench_resnet50_set_hbm_traffic.md has the figures.
+MEASURED_TRAFFIC_BYTES = {"compress_wave<float, 2, 8, 4>": 159.78e6}
 
 WORKLOAD_NAMES = {
     0: "single 2x16x32x32 fp32 tensor, B=8 b=2 (configs[0])",
@@ -174,7 +176,7 @@ def main() -> int:
         "kernel_ms_last_warmup_step": {k: round(v, 4) for k, v in sorted(per_kernel.items())},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(dominant) if args.config == 2 and args.batch is None else None,
                      "algorithmic_bytes_per_launch": round(avg_bytes), "avg_launch_ms": round(avg_ms, 5),
                      "launches_timed": len(dom_ms)},
     }
