@@ -962,6 +962,50 @@ __global__ void __launch_bounds__(kThreads) decompress_rowvec(DecArgs a) {
     }
 }
 
+// H*W a multiple of 4 and at most 255 blocks per plane: the LFC index of every
+// element of a plane is looked up in a table (one byte per element, four per
+// vector) that the workgroup builds once in LDS, so the streaming loop has no
+// row / column arithmetic.  A workgroup streams G whole planes.
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_table(DecArgs a) {
+    uint32_t* s_codes; float2* s_meta; T* s_lfc;
+    dec_lds<T>(a, s_codes, s_meta, s_lfc);
+    uint32_t* s_tab = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(s_lfc) + ((a.G * a.nb * sizeof(T) + 15u) & ~15u));
+    constexpr uint32_t Lq = (1u << BITS) - 1u;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t p0 = blockIdx.x * a.G;
+    const uint32_t Gc = min(a.G, a.P - p0);
+    for (uint32_t fi = tid; fi < a.q4; fi += kThreads) {
+        uint32_t r = fdiv(fi * 4, a.d_W);
+        uint32_t c = fi * 4 - r * a.W;
+        uint32_t t = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            t |= (fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B)) << (8 * e);
+            if (++c == a.W) { c = 0; ++r; }
+        }
+        s_tab[fi] = t;
+    }
+    stage_packed<T>(a, p0, Gc, s_codes, s_meta, s_lfc, tid);      // ends with a barrier
+    const uint32_t nvec = Gc * a.q4;
+    T* out = static_cast<T*>(a.xhat) + (size_t)p0 * a.HW;
+    for (uint32_t vi = tid; vi < nvec; vi += kThreads) {
+        const uint32_t g = fdiv(vi, a.d_q4);
+        const uint32_t fi = vi - g * a.q4;
+        const float2 dd = s_meta[g];
+        uint32_t c4;
+        if constexpr (BITS == 2) c4 = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + fi];
+        else c4 = reinterpret_cast<const uint16_t*>(s_codes)[g * a.WPP * 2 + fi];
+        const uint32_t t = s_tab[fi];
+        const T* lp = s_lfc + g * a.nb;
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            o[e] = dequant((c4 >> (e * BITS)) & Lq, dd.y, dd.x, Elem<T>::load(lp, (t >> (8 * e)) & 0xffu));
+        store4(out, (size_t)vi * 4, o[0], o[1], o[2], o[3]);
+    }
+}
+
 // Any W, H, B: a workgroup streams G whole planes as one flat run of elements,
 // four consecutive elements per lane step; every element finds its own plane,
 // row, column and block.  G*HW is a multiple of 4 whenever G < P remains, so
@@ -983,56 +1027,54 @@ __global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) {
         uint32_t g = fdiv(e0, a.d_HW);
         uint32_t i = e0 - g * a.HW;
         float o[4];
-        if (i + 4 <= a.HW && (i % CPW) + 4 <= CPW) {
-            // the four elements share plane, scale and code word
-            const float2 dd = s_meta[g];
-            const uint32_t w = s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS);
-            const T* lp = s_lfc + g * a.nb;
-            if (one_block) {
-                const float lfc = Elem<T>::load(lp, 0);
+        if (one_block && e0 + 4 <= n && a.HW >= 4) {
+            // at most one plane boundary inside the vector: elements before it use
+            // plane g, the others plane g+1 (which exists because e0+4 <= n)
+            const uint32_t n0 = min(4u, a.HW - i);
+            const uint32_t g1 = n0 < 4 ? g + 1 : g;
+            const float2 da = s_meta[g], db = s_meta[g1];
+            const float la = Elem<T>::load(s_lfc, g), lb = Elem<T>::load(s_lfc, g1);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = dequant((w >> (e * BITS)) & Lq, dd.y, dd.x, lfc);
-            } else {
-                uint32_t r = fdiv(i, a.d_W);
-                uint32_t c = i - r * a.W;
-                uint32_t rowoff = fdiv(r, a.d_B) * a.LW;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float lfc = Elem<T>::load(lp, rowoff + fdiv(c, a.d_B));
-                    o[e] = dequant((w >> (e * BITS)) & Lq, dd.y, dd.x, lfc);
-                    if (++c == a.W) { c = 0; ++r; rowoff = fdiv(r, a.d_B) * a.LW; }
-                }
+            for (int e = 0; e < 4; ++e) {
+                const bool first = (uint32_t)e < n0;
+                const uint32_t idx = first ? i + e : (uint32_t)e - n0;
+                const uint32_t w = s_codes[(first ? g : g1) * a.WPP + idx / CPW];
+                const uint32_t q = (w >> ((idx % CPW) * BITS)) & Lq;
+                o[e] = dequant(q, first ? da.y : db.y, first ? da.x : db.x, first ? la : lb);
             }
             store4(out, e0, o[0], o[1], o[2], o[3]);
             continue;
         }
-        if (one_block) {
-            // at most one plane boundary inside the vector when HW >= 4; handled per element
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                o[e] = 0.0f;
-                if (e0 + e < n) {
-                    const float2 dd = s_meta[g];
-                    const uint32_t q = (s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS)) & Lq;
-                    o[e] = dequant(q, dd.y, dd.x, Elem<T>::load(s_lfc, g));
-                    if (++i == a.HW) { i = 0; ++g; }
-                }
-            }
-        } else {
+        if (!one_block && i + 4 <= a.HW && (i % CPW) + 4 <= CPW) {
+            // the four elements share plane, scale and code word
+            const float2 dd = s_meta[g];
+            const uint32_t w = s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS);
+            const T* lp = s_lfc + g * a.nb;
             uint32_t r = fdiv(i, a.d_W);
             uint32_t c = i - r * a.W;
+            uint32_t rowoff = fdiv(r, a.d_B) * a.LW;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                o[e] = 0.0f;
-                if (e0 + e < n) {
-                    const float2 dd = s_meta[g];
-                    const uint32_t q = (s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS)) & Lq;
-                    const float lfc = Elem<T>::load(s_lfc, g * a.nb + fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B));
-                    o[e] = dequant(q, dd.y, dd.x, lfc);
-                    ++i;
-                    if (++c == a.W) { c = 0; ++r; }
-                    if (i == a.HW) { i = 0; r = 0; c = 0; ++g; }
-                }
+                const float lfc = Elem<T>::load(lp, rowoff + fdiv(c, a.d_B));
+                o[e] = dequant((w >> (e * BITS)) & Lq, dd.y, dd.x, lfc);
+                if (++c == a.W) { c = 0; ++r; rowoff = fdiv(r, a.d_B) * a.LW; }
+            }
+            store4(out, e0, o[0], o[1], o[2], o[3]);
+            continue;
+        }
+        uint32_t r = fdiv(i, a.d_W);
+        uint32_t c = i - r * a.W;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            o[e] = 0.0f;
+            if (e0 + e < n) {
+                const float2 dd = s_meta[g];
+                const uint32_t q = (s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS)) & Lq;
+                const float lfc = Elem<T>::load(s_lfc, g * a.nb + fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B));
+                o[e] = dequant(q, dd.y, dd.x, lfc);
+                ++i;
+                if (++c == a.W) { c = 0; ++r; }
+                if (i == a.HW) { i = 0; r = 0; c = 0; ++g; }
             }
         }
         if (e0 + 4 <= n) {
@@ -1286,7 +1328,7 @@ bool plan_tile(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
     return *lds <= kLdsMax;
 }
 
-// Fills the decompress launch plan; returns 0 (row vectors), 1 (flat) or 2 (scalar).
+// Fills the decompress launch plan; returns 0 (row vectors), 3 (block table), 1 (flat) or 2 (scalar).
 // LDS bytes of the streaming decompress kernels for G planes per workgroup
 size_t dec_lds_bytes(const Layout& L, size_t es, uint64_t G) {
     return 4ull * ((G * L.WPP + 3) & ~(uint64_t)3) + 8ull * G + es * G * L.nb + 16;
@@ -1316,6 +1358,19 @@ int plan_decompress(const Layout& L, int64_t H, int64_t W, int B, size_t es, con
             a->d_w4 = make_fastdiv(a->w4);
             *grid = (uint32_t)((L.P + G - 1) / G);
             return 0;
+        }
+    }
+    // planes of whole vectors with few blocks: LFC indices from a table in LDS
+    if (L.HW % 4 == 0 && L.nb > 1 && L.nb <= 255 && small_idx && out_vec_aligned && fastdiv_ok(L.HW, (uint64_t)W)) {
+        a->q4 = (uint32_t)(L.HW / 4);
+        uint64_t G = (target / 4 + a->q4 - 1) / a->q4;
+        if (G > L.P) G = L.P;
+        while (G > 1 && !fastdiv_ok(G * a->q4 + kThreads, a->q4)) --G;
+        if (fastdiv_ok(G * a->q4 + kThreads, a->q4) && dec_lds_bytes(L, es, G) + 4ull * a->q4 + 16 <= kDecLdsMax) {
+            a->G = (uint32_t)G;
+            a->d_q4 = make_fastdiv(a->q4);
+            *grid = (uint32_t)((L.P + G - 1) / G);
+            return 3;
         }
     }
     // general path: flat run of G planes, G*HW a multiple of 4
@@ -1453,6 +1508,9 @@ int division_decompress(const void* packed, size_t packed_bytes, int64_t N, int6
     if (kind == 0) {
         if (dt == DIVISION_F32) kern = b == 2 ? decompress_rowvec<float, 2> : decompress_rowvec<float, 4>;
         else kern = b == 2 ? decompress_rowvec<bf16_t, 2> : decompress_rowvec<bf16_t, 4>;
+    } else if (kind == 3) {
+        if (dt == DIVISION_F32) kern = b == 2 ? decompress_table<float, 2> : decompress_table<float, 4>;
+        else kern = b == 2 ? decompress_table<bf16_t, 2> : decompress_table<bf16_t, 4>;
     } else if (kind == 1) {
         if (dt == DIVISION_F32) kern = b == 2 ? decompress_flat<float, 2> : decompress_flat<float, 4>;
         else kern = b == 2 ? decompress_flat<bf16_t, 2> : decompress_flat<bf16_t, 4>;
@@ -1462,7 +1520,7 @@ int division_decompress(const void* packed, size_t packed_bytes, int64_t N, int6
     }
     // LDS of the streaming kernels: staged codes, meta and LFC of G planes
     size_t lds = 0;
-    if (kind != 2) lds = dec_lds_bytes(L, es, a.G);
+    if (kind != 2) lds = dec_lds_bytes(L, es, a.G) + (kind == 3 ? 4ull * a.q4 + 16 : 0);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, st, a);
     return hipGetLastError() == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
 }
@@ -1487,7 +1545,7 @@ int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, 
     } else {
         DecArgs a{}; uint32_t grid = 0;
         const int kind = plan_decompress(L, H, W, B, es, data, &a, &grid);
-        n = snprintf(out, cap, "%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 1 ? "decompress_flat" : "decompress_scalar", tn, b);
+        n = snprintf(out, cap, "%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 3 ? "decompress_table" : kind == 1 ? "decompress_flat" : "decompress_scalar", tn, b);
     }
     return (n < 0 || (size_t)n >= cap) ? DIVISION_ESIZE : DIVISION_OK;
 }
