@@ -783,6 +783,174 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
     }
 }
 
+// ------------------------------------------------------------------ compress, plane held in registers
+
+struct RegsArgs {
+    Pads pads;
+    const void* x;
+    uint32_t* codes;
+    float* meta;
+    void* lfc;
+    uint32_t P, H, W, HW, LH, LW, nb, WPP;
+    uint32_t q4;         // units (4 consecutive elements) per plane = H*W/4
+    uint32_t w4;         // units per row = W/4
+    uint32_t ppw;        // planes a workgroup handles one after the other
+    uint32_t seed_a, seed_c;
+    FastDiv d_w4, d_LW;
+};
+
+constexpr int kRegUnits = 13;     // units per lane: planes of up to 13 * (threads per workgroup) units
+
+// Large planes (56x56 with one wavefront, 112x112 with four): the plane never
+// goes through LDS.  Lane `tid` keeps units tid, tid+NT, tid+2NT, ... (the
+// layout of the coalesced 16-byte loads) in registers from the load to the
+// packed codes; LDS carries only one binary64 sum per unit and one LFC value
+// per block (~7 KB per wavefront), so occupancy is set by registers, not LDS.
+// A unit lies inside one block (W % 4 == 0, B % 4 == 0), which block is the
+// same for every plane and is worked out once per workgroup.
+template <typename T, int BITS, int B, int NW>
+__global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
+    constexpr int NT = 64 * NW;
+    constexpr int K = kRegUnits;
+    constexpr int UPB = B / 4;            // units per block row
+    constexpr float Lf = float((1 << BITS) - 1);
+    extern __shared__ float4 smem4[];
+    double* usum = reinterpret_cast<double*>(smem4);                  // [K*NT] per-unit sums
+    float* lfcs = reinterpret_cast<float*>(usum + K * NT);            // [nb + 1], last = NaN sentinel
+    float* red = lfcs + ((a.nb + 1 + 3) & ~3u);                        // [2*NW] cross-wave min / max
+
+    const uint32_t tid = threadIdx.x;
+    if (blockIdx.x == 0) zero_pads(a.pads, tid);
+
+    // which block each of the lane's units belongs to (nb = sentinel for units past the plane)
+    uint32_t blk[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t f = tid + NT * k;
+        const uint32_t row = fdiv(f, a.d_w4);
+        const uint32_t c4 = f - row * a.w4;
+        blk[k] = f < a.q4 ? (row / B) * a.LW + c4 / UPB : a.nb;
+    }
+    if (tid == 0) lfcs[a.nb] = __builtin_nanf("");
+    const bool full_blocks = (a.H % B) == 0 && (a.W % B) == 0;
+
+    const uint32_t pbeg = blockIdx.x * a.ppw;
+    const uint32_t pend = min(a.P, pbeg + a.ppw);
+    for (uint32_t p = pbeg; p < pend; ++p) {
+        // ---- load the plane: coalesced, bounds-checked (units past the plane read as zero)
+        float x[K][4];
+        {
+            const T* src = static_cast<const T*>(a.x) + (size_t)p * a.HW;
+            const __amdgpu_buffer_rsrc_t rsrc =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(a.HW * sizeof(T)), 0x00020000);
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                if constexpr (sizeof(T) == 4) {
+                    const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, tid * 16u, k * NT * 16, 0);
+                    x[k][0] = __uint_as_float(q.x); x[k][1] = __uint_as_float(q.y);
+                    x[k][2] = __uint_as_float(q.z); x[k][3] = __uint_as_float(q.w);
+                } else {
+                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                    const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, tid * 8u, k * NT * 8, 0);
+                    x[k][0] = __uint_as_float(q.x << 16); x[k][1] = __uint_as_float(q.x & 0xffff0000u);
+                    x[k][2] = __uint_as_float(q.y << 16); x[k][3] = __uint_as_float(q.y & 0xffff0000u);
+                }
+            }
+        }
+        // ---- Sec. 4.1 AveragePooling, step 1: one binary64 sum per unit
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            usum[tid + NT * k] = ((double)x[k][0] + (double)x[k][1]) + ((double)x[k][2] + (double)x[k][3]);
+        if constexpr (NW == 1) wave_sync(); else lds_barrier();
+
+        // ---- step 2: a lane per block adds the block's unit sums in a fixed order
+        for (uint32_t t = tid; t < a.nb; t += NT) {
+            const uint32_t bi = fdiv(t, a.d_LW);
+            const uint32_t bj = t - bi * a.LW;
+            const uint32_t u0 = bi * B * a.w4 + bj * UPB;
+            double S = 0.0;
+            uint32_t cnt;
+            if (full_blocks) {
+#pragma unroll
+                for (int rr = 0; rr < B; ++rr)
+#pragma unroll
+                    for (int u = 0; u < UPB; ++u) S += usum[u0 + rr * a.w4 + u];
+                cnt = B * B;
+            } else {
+                const uint32_t rows = min((uint32_t)B, a.H - bi * B);
+                const uint32_t units = min((uint32_t)UPB, a.w4 - bj * UPB);
+#pragma unroll
+                for (int rr = 0; rr < B; ++rr)
+#pragma unroll
+                    for (int u = 0; u < UPB; ++u) {
+                        const bool ok = (uint32_t)rr < rows && (uint32_t)u < units;
+                        const double v = usum[ok ? u0 + rr * a.w4 + u : u0];
+                        S += ok ? v : 0.0;
+                    }
+                cnt = rows * units * 4;
+            }
+            const float lfc = Elem<T>::round(mean_of(S, cnt));
+            lfcs[t] = lfc;
+            Elem<T>::store(static_cast<T*>(a.lfc), (size_t)p * a.nb + t, lfc);
+        }
+        if constexpr (NW == 1) wave_sync(); else lds_barrier();
+
+        // ---- residual H^H = H - UpSampling(H^L) in place, plane min / max.
+        // Units past the plane take the NaN sentinel: their residual is NaN,
+        // which min / max skip.
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const float lfc = lfcs[blk[k]];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x[k][e] = x[k][e] - lfc;
+                mn = fminf(mn, x[k][e]);
+                mx = fmaxf(mx, x[k][e]);
+            }
+        }
+        group_minmax(64, mn, mx);
+        if constexpr (NW > 1) {
+            if ((tid & 63u) == 0) { red[2 * (tid >> 6)] = mn; red[2 * (tid >> 6) + 1] = mx; }
+            lds_barrier();
+#pragma unroll
+            for (int w = 0; w < NW; ++w) { mn = fminf(mn, red[2 * w]); mx = fmaxf(mx, red[2 * w + 1]); }
+        }
+
+        // ---- scale of Eq. (quantization), keys, meta
+        float Delta, inv;
+        plane_scale(mn, mx, Lf, Delta, inv);
+        const float delta = mn;
+        const float invs = inv * (float)(1u << (32 - BITS));
+        const uint32_t k1 = mix32(p ^ a.seed_a);
+        const uint32_t k2 = mix32(k1 + a.seed_c);
+        if (tid == 0) reinterpret_cast<float2*>(a.meta)[p] = make_float2(delta, Delta);
+
+        // ---- Quant + packing: a unit is two element pairs = 4 codes (one byte for b = 2)
+        {
+            const uint32_t rscale = 1u << (16 - BITS);
+            constexpr uint32_t CB = BITS / 2;                         // code bytes per unit (1 or 2)
+            uint8_t* cbase = reinterpret_cast<uint8_t*>(a.codes) + (size_t)p * a.WPP * 4;
+            const __amdgpu_buffer_rsrc_t crs =
+                __builtin_amdgcn_make_buffer_rsrc(cbase, 0, (int)(a.q4 * CB), 0x00020000);
+            const uint32_t xw0 = k1 + (2u * tid) * kWeyl;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const uint32_t xw = xw0 + (uint32_t)(2 * NT * k) * kWeyl;
+                uint32_t c = push_pair<BITS>(0u, x[k][2], x[k][3], delta, invs, xw + kWeyl, k2, rscale);
+                c = push_pair<BITS>(c, x[k][0], x[k][1], delta, invs, xw, k2, rscale);
+                // stores past the plane's code bytes are dropped by the buffer bound
+                if constexpr (CB == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, tid, k * NT, 0);
+                else __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c, crs, tid * 2u, k * NT * 2, 0);
+            }
+            // pad bytes of the plane's last word are zero
+            const uint32_t padb = a.WPP * 4 - a.q4 * CB;
+            if (tid < padb) cbase[a.q4 * CB + tid] = 0;
+        }
+        if constexpr (NW == 1) wave_sync(); else lds_barrier();      // usum, lfcs and red are reused
+    }
+}
+
 // ------------------------------------------------------------------ compress, any shape (slow)
 
 struct AnyArgs {
@@ -1221,6 +1389,40 @@ hipError_t launch_wave(int B, int vec, const WaveArgs& a, uint32_t grid, size_t 
                   : launch_wave_vec<T, BITS, 4>(vec, a, grid, lds, st);
 }
 
+// Fills the plane-in-registers compress plan; false when the shape is not covered.
+bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* x,
+               RegsArgs* a, uint32_t* grid, size_t* lds, int* nw_out) {
+    static const bool disabled = getenv("DIVISION_NO_REGS") != nullptr;      // experiments only
+    if (disabled || (B != 4 && B != 8) || W % 4 != 0) return false;
+    if (((uintptr_t)x % (4 * es)) != 0) return false;
+    const uint64_t q4 = L.HW / 4;
+    int nw;
+    if (q4 >= 512 && q4 <= (uint64_t)kRegUnits * 64) nw = 1;
+    else if (q4 >= 2048 && q4 <= (uint64_t)kRegUnits * 256) nw = 4;
+    else return false;
+    const uint64_t nt = 64ull * nw, w4 = (uint64_t)W / 4;
+    if (!fastdiv_ok(kRegUnits * nt, w4) || !fastdiv_ok(L.nb + nt, L.LW) || L.HW * es >= (1ull << 31)) return false;
+    a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
+    a->LH = (uint32_t)L.LH; a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP;
+    a->q4 = (uint32_t)q4; a->w4 = (uint32_t)w4;
+    a->ppw = 4;
+    a->d_w4 = make_fastdiv((uint32_t)w4);
+    a->d_LW = make_fastdiv((uint32_t)L.LW);
+    *lds = 8ull * kRegUnits * nt + 4ull * ((L.nb + 1 + 3) & ~3ull) + 8ull * nw + 16;
+    *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
+    *nw_out = nw;
+    return *lds <= 60u * 1024u;
+}
+
+template <typename T, int BITS>
+hipError_t launch_regs(int B, int nw, const RegsArgs& a, uint32_t grid, size_t lds, hipStream_t st) {
+    void (*kern)(RegsArgs);
+    if (nw == 1) kern = B == 8 ? compress_regs<T, BITS, 8, 1> : compress_regs<T, BITS, 4, 1>;
+    else kern = B == 8 ? compress_regs<T, BITS, 8, 4> : compress_regs<T, BITS, 4, 4>;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * nw), lds, st, a);
+    return hipGetLastError();
+}
+
 // Fills the one-wavefront compress plan; false when the shape is not covered.
 bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, const void* x,
                WaveArgs* a, uint32_t* grid, size_t* lds, int* vec_out) {
@@ -1436,7 +1638,20 @@ int division_compress(const void* x, int64_t N, int64_t C, int64_t H, int64_t W,
     int vec = 1, nt = 64;
     hipError_t err;
     WaveArgs wa{};
-    if (plan_wave(L, H, W, B, b, es, x, &wa, &grid, &lds, &vec)) {
+    RegsArgs ra{};
+    int nw = 1;
+    if (plan_regs(L, H, W, B, es, x, &ra, &grid, &lds, &nw)) {
+        ra.pads = make_pads(pk, L);
+        ra.x = x;
+        ra.codes = reinterpret_cast<uint32_t*>(pk + L.codes_off);
+        ra.meta = reinterpret_cast<float*>(pk + L.meta_off);
+        ra.lfc = pk + L.lfc_off;
+        ra.seed_a = seed_a; ra.seed_c = seed_c;
+        if (dt == DIVISION_F32)
+            err = b == 2 ? launch_regs<float, 2>(B, nw, ra, grid, lds, st) : launch_regs<float, 4>(B, nw, ra, grid, lds, st);
+        else
+            err = b == 2 ? launch_regs<bf16_t, 2>(B, nw, ra, grid, lds, st) : launch_regs<bf16_t, 4>(B, nw, ra, grid, lds, st);
+    } else if (plan_wave(L, H, W, B, b, es, x, &wa, &grid, &lds, &vec)) {
         wa.pads = make_pads(pk, L);
         wa.x = x;
         wa.codes = reinterpret_cast<uint32_t*>(pk + L.codes_off);
@@ -1535,8 +1750,10 @@ int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, 
     const char* tn = dt == DIVISION_BF16 ? "bf16_t" : "float";
     int n;
     if (direction == 0) {
-        TileArgs a{}; WaveArgs wa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64;
-        if (plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))
+        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
+        if (plan_regs(L, H, W, B, es, data, &ra, &grid, &lds, &nw))
+            n = snprintf(out, cap, "compress_regs<%s, %d, %d, %d>", tn, b, B, nw);
+        else if (plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_wave<%s, %d, %d, %d>", tn, b, B, vec);
         else if (plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
             n = snprintf(out, cap, "compress_tile<%s, %d, %d, %d, %d>", tn, b, B, vec, nt);

@@ -45,6 +45,12 @@ TILE_CASES = [
     ((2, 3, 64, 64), 8, 2),           # 16 KB plane
     ((2, 3, 72, 72), 8, 2),           # above the one-wavefront budget: four-wavefront tile kernel
     ((3, 3, 40, 40), 4, 4),
+    ((3, 4, 48, 48), 4, 2),           # plane kept in registers, one wavefront, B = 4
+    ((2, 3, 50, 44), 8, 2),           # same kernel, ragged blocks both ways, ragged last code word
+    ((2, 3, 50, 44), 8, 4),
+    ((2, 2, 96, 96), 8, 2),           # plane kept in registers, four wavefronts
+    ((1, 3, 100, 92), 8, 4),          # four wavefronts, ragged blocks
+    ((9, 1, 56, 56), 8, 2),           # 9 planes: the last workgroup handles one plane only
 ]
 
 ANY_CASES = [
