@@ -50,6 +50,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload index 0..4 (default: ResNet-50 set)")
     ap.add_argument("--sets", type=int, default=3, help="rotating buffer sets (defeats last-level-cache reuse)")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size (not a valid headline run)")
+    ap.add_argument("--mode", choices=["batch", "layer"], default="batch",
+                    help="batch: consecutive same-shape maps share a launch (<= 8 per call); layer: one call per map")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy 10 times (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -105,49 +107,78 @@ def main() -> int:
     input_bytes, packed_bytes = sum(in_bytes), sum(pk_bytes)
     algo_bytes_step = 2 * (input_bytes + packed_bytes)
 
-    # every launch of a step: (direction, tensor index, kernel name)
-    launches = [(0, i) for i in range(len(host))] + [(1, i) for i in reversed(range(len(host)))]
-    names = {(d, i): pkg.division_kernel_name(d, shapes[i], host[i][1].B, host[i][1].b, dtypes[i]) for d, i in launches}
-
-    def run_step(s: int, timed_group=None, events=None):
-        for d, i in launches:
+    # every launch of a step: (direction, tensor indices).  "batch": consecutive maps of one
+    # shape (one stage of the network) go through the batch entry points, at most 8 per call,
+    # so one call is one kernel launch; "layer": one call per map, as a layer-by-layer
+    # integration issues them.
+    def launch_list(mode):
+        groups = []
+        for i in range(len(host)):
             sp = host[i][1]
-            rec = events is not None and (timed_group is None or names[(d, i)] == timed_group)
+            key = (shapes[i], dtypes[i], sp.B, sp.b)
+            if mode == "batch" and groups and groups[-1][0] == key and len(groups[-1][1]) < 8:
+                groups[-1][1].append(i)
+            else:
+                groups.append((key, [i]))
+        idx = [tuple(g[1]) for g in groups]
+        return [(0, g) for g in idx] + [(1, g) for g in reversed(idx)]
+
+    def kname(d, g):
+        i = g[0]
+        return pkg.division_kernel_name(d, shapes[i], host[i][1].B, host[i][1].b, dtypes[i])
+
+    def run_step(launches, s: int, timed_group=None, events=None):
+        for d, g in launches:
+            sp = host[g[0]][1]
+            rec = events is not None and (timed_group is None or kname(d, g) == timed_group)
             if rec:
                 e0 = torch.cuda.Event(enable_timing=True)
                 e1 = torch.cuda.Event(enable_timing=True)
                 e0.record()
-            if d == 0:
-                pkg.division_compress(xs[s][i], sp.B, sp.b, seeds[i], packed=packs[s][i])
+            if len(g) == 1:
+                i = g[0]
+                if d == 0:
+                    pkg.division_compress(xs[s][i], sp.B, sp.b, seeds[i], packed=packs[s][i])
+                else:
+                    pkg.division_decompress(packs[s][i], shapes[i], sp.B, sp.b, dtypes[i], out=outs[s][i])
+            elif d == 0:
+                pkg.division_compress_batch([xs[s][i] for i in g], sp.B, sp.b, [seeds[i] for i in g],
+                                            packed=[packs[s][i] for i in g])
             else:
-                pkg.division_decompress(packs[s][i], shapes[i], sp.B, sp.b, dtypes[i], out=outs[s][i])
+                pkg.division_decompress_batch([packs[s][i] for i in g], shapes[g[0]], sp.B, sp.b, dtypes[g[0]],
+                                              out=[outs[s][i] for i in g])
             if rec:
                 e1.record()
-                events.append(((d, i), e0, e1))
+                events.append(((d, g), e0, e1))
 
-    # ---- warm-up; its last step times every launch to find the dominant kernel
-    for w in range(max(1, args.warmup) - 1):
-        run_step(w % nsets)
-    probe = []
-    run_step((max(1, args.warmup) - 1) % nsets, None, probe)
-    torch.cuda.synchronize()
-    per_kernel = {}
-    for key, e0, e1 in probe:
-        per_kernel[names[key]] = per_kernel.get(names[key], 0.0) + e0.elapsed_time(e1)
-    dominant = max(per_kernel, key=per_kernel.get)
+    def timed(mode):
+        launches = launch_list(mode)
+        # warm-up; its last step times every launch to find the dominant kernel
+        for w in range(max(1, args.warmup) - 1):
+            run_step(launches, w % nsets)
+        probe = []
+        run_step(launches, (max(1, args.warmup) - 1) % nsets, None, probe)
+        torch.cuda.synchronize()
+        per_kernel = {}
+        for (d, g), e0, e1 in probe:
+            per_kernel[kname(d, g)] = per_kernel.get(kname(d, g), 0.0) + e0.elapsed_time(e1)
+        dominant = max(per_kernel, key=per_kernel.get)
+        # timed region: exactly K steps; events only around the dominant kernel's launches
+        events = []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            run_step(launches, k % nsets, dominant, events)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / args.steps, per_kernel, dominant, events, len(launches)
 
-    # ---- timed region: exactly K steps; events only around the dominant kernel's launches
-    events = []
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        run_step(k % nsets, dominant, events)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    other_mode = "layer" if args.mode == "batch" else "batch"
+    other_ms = timed(other_mode)[0]
+    ms_per_step, per_kernel, dominant, events, n_launches = timed(args.mode)
 
     dom_ms = [e0.elapsed_time(e1) for _, e0, e1 in events]
-    dom_bytes = [in_bytes[i] + pk_bytes[i] for (d, i), _, _ in events]
+    dom_bytes = [sum(in_bytes[i] + pk_bytes[i] for i in g) for (d, g), _, _ in events]
     avg_ms = sum(dom_ms) / len(dom_ms)
     avg_bytes = sum(dom_bytes) / len(dom_bytes)
     achieved = avg_bytes / (avg_ms * 1e-3) / 1e9
@@ -169,10 +200,13 @@ def main() -> int:
         "config": {"workload": WORKLOAD_NAMES[args.config], "tensors": len(host), "elements": elements,
                    "input_bytes": input_bytes, "packed_bytes": packed_bytes,
                    "B": host[0][1].B, "b": host[0][1].b, "buffer_sets": nsets,
+                   "launch_mode": args.mode, "launches_per_step": n_launches,
                    "batch_override": args.batch},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "activation_GB_s": round(2 * input_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "compression_ratio": round(input_bytes / packed_bytes, 3),
+        f"{other_mode}_mode_GB_s": round(algo_bytes_step / (other_ms * 1e-3) / 1e9, 1),
+        f"{other_mode}_mode_ms_per_step": round(other_ms, 4),
         "kernel_ms_last_warmup_step": {k: round(v, 4) for k, v in sorted(per_kernel.items())},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),

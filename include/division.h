@@ -111,6 +111,36 @@ int division_decompress(const void *packed, size_t packed_bytes,
                         void *xhat, void *hip_stream);
 
 /*
+ * The same two operations over `count` maps of ONE shape (Algorithm 1 runs the
+ * forward-pass compression once per layer and the backward-pass decompression
+ * once per layer; layers whose maps share (N, C, H, W, dt, B, b) can be served
+ * together).  Tensor i gives exactly the bytes that the single-map call with
+ * (x[i], seeds[i], packed[i]) resp. (packed[i], xhat[i]) gives; up to 8 maps
+ * share one kernel launch, so the machine is filled and drained once for all
+ * of them.
+ *
+ *   x, packed, xhat   HOST arrays of `count` DEVICE pointers, read during the
+ *                     call only; the same requirements as above hold for every
+ *                     pointed-to buffer, and no two output buffers may overlap.
+ *   seeds             HOST array of `count` seeds.
+ *   packed_capacity / packed_bytes   size of EACH packed buffer.
+ *
+ * count == 0 is a no-op (DIVISION_OK); count < 0 or a null array or a null
+ * entry is DIVISION_EINVAL.  Arguments are checked for the whole batch before
+ * anything is launched.
+ */
+int division_compress_batch(int count, const void *const *x, void *const *packed,
+                            const uint64_t *seeds,
+                            int64_t N, int64_t C, int64_t H, int64_t W,
+                            division_dtype dt, int B, int b,
+                            size_t packed_capacity, void *hip_stream);
+
+int division_decompress_batch(int count, const void *const *packed, void *const *xhat,
+                              size_t packed_bytes,
+                              int64_t N, int64_t C, int64_t H, int64_t W,
+                              division_dtype dt, int B, int b, void *hip_stream);
+
+/*
  * Profiling aid (host-only): writes the name of the kernel template instance
  * that division_compress (direction 0, data = x) or division_decompress
  * (direction 1, data = xhat) would launch for these arguments, as it appears

@@ -4,4 +4,4 @@ compress / decompress of cached activation maps as in "DIVISION: Memory
 Efficient Training via Dual Activation Precision" (Sec. 4.1 and Sec. 4.2).
 """
 from .binding import (DIVISION_BF16, DIVISION_F32, DivisionError, division_compress,  # noqa: F401
-                      division_decompress, division_kernel_name, division_packed_bytes, division_packed_layout, lib)
+                      division_compress_batch, division_decompress, division_decompress_batch, division_kernel_name, division_packed_bytes, division_packed_layout, lib)

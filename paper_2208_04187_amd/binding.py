@@ -46,6 +46,11 @@ def lib() -> ctypes.CDLL:
         L.division_compress.argtypes = [vp, i64, i64, i64, i64, ci, ci, ci, u64, vp, sz, vp]
         L.division_decompress.restype = ci
         L.division_decompress.argtypes = [vp, sz, i64, i64, i64, i64, ci, ci, ci, vp, vp]
+        pp = ctypes.POINTER(vp)
+        L.division_compress_batch.restype = ci
+        L.division_compress_batch.argtypes = [ci, pp, pp, ctypes.POINTER(u64), i64, i64, i64, i64, ci, ci, ci, sz, vp]
+        L.division_decompress_batch.restype = ci
+        L.division_decompress_batch.argtypes = [ci, pp, pp, sz, i64, i64, i64, i64, ci, ci, ci, vp]
         L.division_kernel_name.restype = ci
         L.division_kernel_name.argtypes = [ci, vp, i64, i64, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
         _lib = L
@@ -106,6 +111,60 @@ def division_decompress(packed: torch.Tensor, shape, B: int, b: int, dtype=torch
                                    N, C, H, W, _dt(dtype), B, b, out.data_ptr(), _stream(stream))
     if rc:
         raise DivisionError(rc, "division_decompress")
+    return out
+
+
+def _ptr_array(tensors):
+    return (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+
+
+def division_compress_batch(xs, B: int, b: int, seeds, packed=None, stream=None):
+    """xs: contiguous NCHW device tensors of ONE shape and dtype; seeds: one per tensor.
+    Returns the list of packed uint8 buffers (those given in `packed`, else new ones)."""
+    xs = list(xs)
+    seeds = list(seeds)
+    if len(seeds) != len(xs):
+        raise ValueError("one seed per tensor")
+    if not xs:
+        return []
+    x0 = xs[0]
+    for x in xs:
+        if x.dim() != 4 or not x.is_cuda or not x.is_contiguous() or x.shape != x0.shape or x.dtype != x0.dtype:
+            raise ValueError("xs must be contiguous 4-d device tensors of one shape and dtype")
+    N, C, H, W = x0.shape
+    need = division_packed_bytes(N, C, H, W, B, b, x0.dtype)
+    if need == 0:
+        raise DivisionError(1, "division_packed_bytes")
+    if packed is None:
+        packed = [torch.empty(need, dtype=torch.uint8, device=x0.device) for _ in xs]
+    packed = list(packed)
+    if len(packed) != len(xs):
+        raise ValueError("one packed buffer per tensor")
+    cap = min(p.numel() * p.element_size() for p in packed)
+    sd = (ctypes.c_uint64 * len(xs))(*[s & (2 ** 64 - 1) for s in seeds])
+    rc = lib().division_compress_batch(len(xs), _ptr_array(xs), _ptr_array(packed), sd, N, C, H, W,
+                                       _dt(x0.dtype), B, b, cap, _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_compress_batch")
+    return packed
+
+
+def division_decompress_batch(packed, shape, B: int, b: int, dtype=torch.float32, out=None, stream=None):
+    """packed: buffers written by division_compress(_batch) for maps of `shape`.  Returns the list of maps."""
+    packed = list(packed)
+    if not packed:
+        return []
+    N, C, H, W = shape
+    if out is None:
+        out = [torch.empty(shape, dtype=dtype, device=packed[0].device) for _ in packed]
+    out = list(out)
+    if len(out) != len(packed):
+        raise ValueError("one output per packed buffer")
+    nbytes = min(p.numel() * p.element_size() for p in packed)
+    rc = lib().division_decompress_batch(len(packed), _ptr_array(packed), _ptr_array(out), nbytes,
+                                         N, C, H, W, _dt(dtype), B, b, _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_decompress_batch")
     return out
 
 

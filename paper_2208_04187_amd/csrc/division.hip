@@ -108,23 +108,50 @@ __device__ __forceinline__ uint32_t quant(float h, float delta, float inv16, uin
     return (T + r) >> 16;
 }
 
-// byte ranges between / after the three regions of the packed buffer that
-// must read as zero (each shorter than 16 bytes)
-struct Pads { uint8_t* base; size_t off[3]; uint32_t len[3]; };
+// One launch serves up to kMaxBatch tensors of one shape (blockIdx.y picks the
+// tensor): fewer, longer kernels, so less of a step is spent filling and
+// draining the machine.
+constexpr int kMaxBatch = 8;
+struct CompTab { const void* x[kMaxBatch]; void* pk[kMaxBatch]; uint32_t seed_a[kMaxBatch], seed_c[kMaxBatch]; };
+struct DecTab { const void* pk[kMaxBatch]; void* xhat[kMaxBatch]; };
 
-__device__ __forceinline__ void zero_pads(const Pads& pd, uint32_t tid) {
-    if (tid < 48) {
+// Offsets of the regions inside a packed buffer, and the byte ranges between /
+// after them that must read as zero (each shorter than 16 bytes).
+struct Regions { size_t meta_off, lfc_off; size_t pad_off[3]; uint32_t pad_len[3]; };
+
+// this workgroup's tensor
+struct CompPtrs { const void* x; uint32_t* codes; float* meta; void* lfc; uint32_t seed_a, seed_c; };
+__device__ __forceinline__ CompPtrs comp_ptrs(const CompTab& tab, const Regions& rg, uint32_t tid) {
+    const uint32_t ti = blockIdx.y;
+    char* pk = static_cast<char*>(tab.pk[ti]);
+    if (blockIdx.x == 0 && tid < 48) {
         const uint32_t k = tid >> 4, j = tid & 15u;
-        if (j < pd.len[k]) pd.base[pd.off[k] + j] = 0;
+        if (j < rg.pad_len[k]) pk[rg.pad_off[k] + j] = 0;
     }
+    CompPtrs pt;
+    pt.x = tab.x[ti];
+    pt.codes = reinterpret_cast<uint32_t*>(pk);
+    pt.meta = reinterpret_cast<float*>(pk + rg.meta_off);
+    pt.lfc = pk + rg.lfc_off;
+    pt.seed_a = tab.seed_a[ti];
+    pt.seed_c = tab.seed_c[ti];
+    return pt;
+}
+struct DecPtrs { const uint32_t* codes; const float* meta; const void* lfc; void* xhat; };
+__device__ __forceinline__ DecPtrs dec_ptrs(const DecTab& tab, const Regions& rg) {
+    const uint32_t ti = blockIdx.y;
+    const char* pk = static_cast<const char*>(tab.pk[ti]);
+    DecPtrs pt;
+    pt.codes = reinterpret_cast<const uint32_t*>(pk);
+    pt.meta = reinterpret_cast<const float*>(pk + rg.meta_off);
+    pt.lfc = pk + rg.lfc_off;
+    pt.xhat = tab.xhat[ti];
+    return pt;
 }
 
 struct TileArgs {
-    Pads pads;
-    const void* x;
-    uint32_t* codes;
-    float* meta;
-    void* lfc;
+    CompTab tab;
+    Regions rg;
     uint32_t P, H, W, HW, LH, LW, nb, WPP;
     uint32_t G;          // planes per workgroup
     uint32_t ipr;        // item slots per block row (padded to the items-per-block count)
@@ -133,7 +160,6 @@ struct TileArgs {
     uint32_t xs_floats;  // LDS floats reserved for the chunk (multiple of 4)
     uint32_t items_cap;  // LDS floats reserved per item array
     uint32_t vec_load;   // chunk starts are 16-byte aligned
-    uint32_t seed_a, seed_c;
     FastDiv d_ipp, d_ipr, d_wpp;
 };
 
@@ -254,11 +280,11 @@ __global__ void __launch_bounds__(NT) compress_tile(TileArgs a) {
     const uint32_t p0 = blockIdx.x * a.G;
     const uint32_t Gc = min(a.G, a.P - p0);
     const uint32_t n = Gc * a.HW;
-    if (blockIdx.x == 0) zero_pads(a.pads, tid);
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
 
     // ---- phase 0: chunk -> LDS (fp32); coalesced 16-byte loads, up to 8 in flight per lane
     {
-        const T* src = static_cast<const T*>(a.x) + (size_t)p0 * a.HW;
+        const T* src = static_cast<const T*>(pt.x) + (size_t)p0 * a.HW;
         constexpr uint32_t EPV = 16 / sizeof(T);
         constexpr int U = 8;
         const uint32_t nv = a.vec_load ? n / EPV : 0;
@@ -341,7 +367,7 @@ __global__ void __launch_bounds__(NT) compress_tile(TileArgs a) {
         else m = (float)(S / (double)cnt);
         const float lfc = Elem<T>::round(m);
         if (valid && (s % IPB) == 0)
-            Elem<T>::store(static_cast<T*>(a.lfc), (size_t)(p0 + g) * a.nb + bi * a.LW + bj, lfc);
+            Elem<T>::store(static_cast<T*>(pt.lfc), (size_t)(p0 + g) * a.nb + bi * a.LW + bj, lfc);
 
         // Sec. 4.1: H^H = H - UpSampling(H^L); written back over x
         float hmin = __builtin_inff(), hmax = -__builtin_inff();
@@ -387,9 +413,9 @@ __global__ void __launch_bounds__(NT) compress_tile(TileArgs a) {
                 float Delta, inv;
                 plane_scale(mn, mx, Lf, Delta, inv);
                 const uint32_t p = p0 + g;
-                reinterpret_cast<float2*>(a.meta)[p] = make_float2(mn, Delta);
-                const uint32_t k1 = mix32(p ^ a.seed_a);
-                const uint32_t k2 = mix32(k1 + a.seed_c);
+                reinterpret_cast<float2*>(pt.meta)[p] = make_float2(mn, Delta);
+                const uint32_t k1 = mix32(p ^ pt.seed_a);
+                const uint32_t k2 = mix32(k1 + pt.seed_c);
                 params[g] = make_float4(mn, inv * (float)(1u << (32 - BITS)), __uint_as_float(k1), __uint_as_float(k2));
             }
         }
@@ -427,7 +453,7 @@ __global__ void __launch_bounds__(NT) compress_tile(TileArgs a) {
 #pragma unroll
             for (int j = CPW / 2 - 1; j >= 0; --j)
                 word = push_pair<BITS>(word, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
-            a.codes[(size_t)(p0 + g) * a.WPP + k] = word;
+            pt.codes[(size_t)(p0 + g) * a.WPP + k] = word;
         }
     }
 }
@@ -435,11 +461,8 @@ __global__ void __launch_bounds__(NT) compress_tile(TileArgs a) {
 // ------------------------------------------------------------------ compress, one wavefront per chunk
 
 struct WaveArgs {
-    Pads pads;
-    const void* x;
-    uint32_t* codes;
-    float* meta;
-    void* lfc;
+    CompTab tab;
+    Regions rg;
     uint32_t P, H, W, HW, LH, LW, nb, WPP;
     uint32_t G;          // planes per wavefront (one workgroup = one wavefront)
     uint32_t ipr;        // item slots per block row (padded to the items-per-block count)
@@ -447,7 +470,6 @@ struct WaveArgs {
     uint32_t ippp;       // ipp padded: next power of two if <= 64, else next multiple of 64
     uint32_t ippp_log2;  // log2(ippp) when ippp <= 64
     uint32_t vec_load;   // chunk starts are 16-byte aligned
-    uint32_t seed_a, seed_c;
     FastDiv d_ipr, d_wpp;
 #ifdef DIVISION_EXPERIMENT
     uint32_t skip;       // timing experiments only: bit 0 skips pooling, bit 1 skips quantisation
@@ -576,12 +598,12 @@ struct ChunkRegs { u32x4 q[16]; };
 // Issues all loads of the chunk.  Buffer addressing: lane*16 plus a scalar offset, reads past the chunk return
 // zero, so there is no per-lane address arithmetic and no bounds branch.
 template <typename T>
-__device__ __forceinline__ void chunk_load(ChunkRegs& r, const WaveArgs& a, uint32_t chunk, uint32_t lane) {
+__device__ __forceinline__ void chunk_load(ChunkRegs& r, const WaveArgs& a, const void* x, uint32_t chunk, uint32_t lane) {
     const uint32_t p0 = chunk * a.G;
     const uint32_t Gc = min(a.G, a.P - p0);
     constexpr uint32_t EPV = 16 / sizeof(T);
     const uint32_t nv = Gc * a.HW / EPV;
-    const T* src = static_cast<const T*>(a.x) + (size_t)p0 * a.HW;
+    const T* src = static_cast<const T*>(x) + (size_t)p0 * a.HW;
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(nv * 16u), 0x00020000);
     const uint32_t voff = lane * 16u;
@@ -631,7 +653,7 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
     constexpr float Lf = float((1 << BITS) - 1);
     constexpr uint32_t EPV = 16 / sizeof(T);
     const uint32_t lane = threadIdx.x;
-    if (blockIdx.x == 0) zero_pads(a.pads, lane);
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, lane);
 
     const uint32_t chunk = blockIdx.x;
     const uint32_t p0 = chunk * a.G;
@@ -642,10 +664,10 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
         const uint32_t nv = a.vec_load ? n / EPV : 0;
         if (a.vec_load) {
             ChunkRegs regs;
-            chunk_load<T>(regs, a, chunk, lane);
+            chunk_load<T>(regs, a, pt.x, chunk, lane);
             chunk_to_lds<T>(regs, xs, nv, lane);
         }
-        const T* src = static_cast<const T*>(a.x) + (size_t)p0 * a.HW;
+        const T* src = static_cast<const T*>(pt.x) + (size_t)p0 * a.HW;
         for (uint32_t e = nv * EPV + lane; e < n; e += 64) xs[e] = Elem<T>::load(src, e);
         wave_sync();
 
@@ -667,7 +689,7 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
             for (uint32_t g0 = 0; g0 < Gc; g0 += ppr) {
                 const uint32_t g = g0 + gsub;
                 const bool live = g < Gc;
-                T* lfc_plane = static_cast<T*>(a.lfc) + (size_t)(p0 + g) * a.nb;
+                T* lfc_plane = static_cast<T*>(pt.lfc) + (size_t)(p0 + g) * a.nb;
                 float mn = __builtin_inff(), mx = -__builtin_inff();
 #ifdef DIVISION_EXPERIMENT
                 if (a.skip & 1u) { mn = 0.f; mx = 1.f; } else
@@ -695,9 +717,9 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
             float Delta, inv;
             plane_scale(mm.x, mm.y, Lf, Delta, inv);
             const uint32_t p = p0 + g;
-            const uint32_t k1 = mix32(p ^ a.seed_a);
-            const uint32_t k2 = mix32(k1 + a.seed_c);
-            reinterpret_cast<float2*>(a.meta)[p] = make_float2(mm.x, Delta);
+            const uint32_t k1 = mix32(p ^ pt.seed_a);
+            const uint32_t k2 = mix32(k1 + pt.seed_c);
+            reinterpret_cast<float2*>(pt.meta)[p] = make_float2(mm.x, Delta);
             params[g] = make_float4(mm.x, inv * (float)(1u << (32 - BITS)), __uint_as_float(k1), __uint_as_float(k2));
         }
         wave_sync();
@@ -717,7 +739,7 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
                     const uint32_t g = fdiv(wi, a.d_wpp);
                     const uint32_t k = wi - g * a.WPP;
                     if (!(a.skip & 32u) || k == 0)
-                        a.codes[(size_t)(p0 + g) * a.WPP + k] = (a.skip & 4u) ? 0u : __float_as_uint(xs[g * a.HW + k * CPW]);
+                        pt.codes[(size_t)(p0 + g) * a.WPP + k] = (a.skip & 4u) ? 0u : __float_as_uint(xs[g * a.HW + k * CPW]);
                 }
                 return;
             }
@@ -751,7 +773,7 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
                 for (int j = PPW - 1; j >= 0; --j)
                     word = push_pair<BITS>(word, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
                 if (left < (uint32_t)CPW) word &= (1u << (left * BITS)) - 1u;      // pad bits are zero
-                a.codes[(size_t)(p0 + g) * a.WPP + k] = word;
+                pt.codes[(size_t)(p0 + g) * a.WPP + k] = word;
             }
             if (pair_tail) {
                 // lane = one element pair of the last words; PPW adjacent lanes build one word
@@ -776,7 +798,7 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
                 part |= __builtin_amdgcn_update_dpp(0, (int)part, kDppXor1, 0xf, 0xf, false);
                 part |= __builtin_amdgcn_update_dpp(0, (int)part, kDppXor2, 0xf, 0xf, false);
                 if constexpr (PPW == 8) part |= __builtin_amdgcn_update_dpp(0, (int)part, kDppHalfMirror, 0xf, 0xf, false);
-                if (act && pw == 0) a.codes[(size_t)(p0 + g) * a.WPP + k] = part;
+                if (act && pw == 0) pt.codes[(size_t)(p0 + g) * a.WPP + k] = part;
             }
 #endif
         }
@@ -786,16 +808,12 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
 // ------------------------------------------------------------------ compress, plane held in registers
 
 struct RegsArgs {
-    Pads pads;
-    const void* x;
-    uint32_t* codes;
-    float* meta;
-    void* lfc;
+    CompTab tab;
+    Regions rg;
     uint32_t P, H, W, HW, LH, LW, nb, WPP;
     uint32_t q4;         // units (4 consecutive elements) per plane = H*W/4
     uint32_t w4;         // units per row = W/4
     uint32_t ppw;        // planes a workgroup handles one after the other
-    uint32_t seed_a, seed_c;
     FastDiv d_w4, d_LW;
 };
 
@@ -820,7 +838,7 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
     float* red = lfcs + ((a.nb + 1 + 3) & ~3u);                        // [2*NW] cross-wave min / max
 
     const uint32_t tid = threadIdx.x;
-    if (blockIdx.x == 0) zero_pads(a.pads, tid);
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
 
     // which block each of the lane's units belongs to (nb = sentinel for units past the plane)
     uint32_t blk[K];
@@ -840,7 +858,7 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
         // ---- load the plane: coalesced, bounds-checked (units past the plane read as zero)
         float x[K][4];
         {
-            const T* src = static_cast<const T*>(a.x) + (size_t)p * a.HW;
+            const T* src = static_cast<const T*>(pt.x) + (size_t)p * a.HW;
             const __amdgpu_buffer_rsrc_t rsrc =
                 __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(a.HW * sizeof(T)), 0x00020000);
 #pragma unroll
@@ -891,7 +909,7 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
             }
             const float lfc = Elem<T>::round(mean_of(S, cnt));
             lfcs[t] = lfc;
-            Elem<T>::store(static_cast<T*>(a.lfc), (size_t)p * a.nb + t, lfc);
+            Elem<T>::store(static_cast<T*>(pt.lfc), (size_t)p * a.nb + t, lfc);
         }
         if constexpr (NW == 1) wave_sync(); else lds_barrier();
 
@@ -922,15 +940,15 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
         plane_scale(mn, mx, Lf, Delta, inv);
         const float delta = mn;
         const float invs = inv * (float)(1u << (32 - BITS));
-        const uint32_t k1 = mix32(p ^ a.seed_a);
-        const uint32_t k2 = mix32(k1 + a.seed_c);
-        if (tid == 0) reinterpret_cast<float2*>(a.meta)[p] = make_float2(delta, Delta);
+        const uint32_t k1 = mix32(p ^ pt.seed_a);
+        const uint32_t k2 = mix32(k1 + pt.seed_c);
+        if (tid == 0) reinterpret_cast<float2*>(pt.meta)[p] = make_float2(delta, Delta);
 
         // ---- Quant + packing: a unit is two element pairs = 4 codes (one byte for b = 2)
         {
             const uint32_t rscale = 1u << (16 - BITS);
             constexpr uint32_t CB = BITS / 2;                         // code bytes per unit (1 or 2)
-            uint8_t* cbase = reinterpret_cast<uint8_t*>(a.codes) + (size_t)p * a.WPP * 4;
+            uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)p * a.WPP * 4;
             const __amdgpu_buffer_rsrc_t crs =
                 __builtin_amdgcn_make_buffer_rsrc(cbase, 0, (int)(a.q4 * CB), 0x00020000);
             const uint32_t xw0 = k1 + (2u * tid) * kWeyl;
@@ -954,13 +972,9 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
 // ------------------------------------------------------------------ compress, any shape (slow)
 
 struct AnyArgs {
-    Pads pads;
-    const void* x;
-    uint32_t* codes;
-    float* meta;
-    void* lfc;
+    CompTab tab;
+    Regions rg;
     uint32_t P, H, W, HW, LH, LW, nb, WPP, B;
-    uint32_t seed_a, seed_c;
 };
 
 // One workgroup per plane; x is re-read from global memory in each pass.
@@ -972,9 +986,9 @@ __global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) {
     constexpr float Lf = float((1 << BITS) - 1);
     const uint32_t tid = threadIdx.x;
     const uint32_t p = blockIdx.x;
-    const T* xp = static_cast<const T*>(a.x) + (size_t)p * a.HW;
-    T* lfcp = static_cast<T*>(a.lfc) + (size_t)p * a.nb;
-    if (p == 0) zero_pads(a.pads, tid);
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
+    const T* xp = static_cast<const T*>(pt.x) + (size_t)p * a.HW;
+    T* lfcp = static_cast<T*>(pt.lfc) + (size_t)p * a.nb;
 
     // pass A: block means; block min/max of the residual follow from the
     // block min/max of x because x -> fl(x - m) is monotone
@@ -1007,9 +1021,9 @@ __global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) {
     if (tid == 0) {
         float Delta, inv;
         plane_scale(red_min[0], red_max[0], Lf, Delta, inv);
-        reinterpret_cast<float2*>(a.meta)[p] = make_float2(red_min[0], Delta);
-        const uint32_t k1 = mix32(p ^ a.seed_a);
-        const uint32_t k2 = mix32(k1 + a.seed_c);
+        reinterpret_cast<float2*>(pt.meta)[p] = make_float2(red_min[0], Delta);
+        const uint32_t k1 = mix32(p ^ pt.seed_a);
+        const uint32_t k2 = mix32(k1 + pt.seed_c);
         sh_params = make_float4(red_min[0], inv * 65536.0f, __uint_as_float(k1), __uint_as_float(k2));
     }
     __syncthreads();
@@ -1030,17 +1044,15 @@ __global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) {
             const uint32_t q = (i & 1u) ? quant<1>(h, delta, inv16, w) : quant<0>(h, delta, inv16, w);
             word |= q << (e * BITS);
         }
-        a.codes[(size_t)p * a.WPP + k] = word;
+        pt.codes[(size_t)p * a.WPP + k] = word;
     }
 }
 
 // ------------------------------------------------------------------ decompress
 
 struct DecArgs {
-    const uint32_t* codes;
-    const float* meta;
-    const void* lfc;
-    void* xhat;
+    DecTab tab;
+    Regions rg;
     uint32_t P, H, W, HW, LH, LW, nb, WPP, B;
     uint32_t G;          // planes per workgroup
     uint32_t q4;         // HW / 4
@@ -1072,10 +1084,10 @@ __device__ __forceinline__ void store4(T* dst, size_t i, float a, float b, float
 // coalesced loads, so that the streaming loop below depends on LDS latency
 // only and its 16-byte stores go out back to back.
 template <typename T>
-__device__ __forceinline__ void stage_packed(const DecArgs& a, uint32_t p0, uint32_t Gc, uint32_t* s_codes,
+__device__ __forceinline__ void stage_packed(const DecArgs& a, const DecPtrs& pt, uint32_t p0, uint32_t Gc, uint32_t* s_codes,
                                              float2* s_meta, T* s_lfc, uint32_t tid) {
     const uint32_t nw = Gc * a.WPP;
-    const uint32_t* src = a.codes + (size_t)p0 * a.WPP;
+    const uint32_t* src = pt.codes + (size_t)p0 * a.WPP;
     if ((((size_t)p0 * a.WPP) & 3u) == 0) {
         const uint32_t nq = nw >> 2;
         for (uint32_t i = tid; i < nq; i += kThreads)
@@ -1084,9 +1096,9 @@ __device__ __forceinline__ void stage_packed(const DecArgs& a, uint32_t p0, uint
     } else {
         for (uint32_t i = tid; i < nw; i += kThreads) s_codes[i] = src[i];
     }
-    for (uint32_t i = tid; i < Gc; i += kThreads) s_meta[i] = reinterpret_cast<const float2*>(a.meta)[p0 + i];
+    for (uint32_t i = tid; i < Gc; i += kThreads) s_meta[i] = reinterpret_cast<const float2*>(pt.meta)[p0 + i];
     const uint32_t nl = Gc * a.nb;
-    const T* lsrc = static_cast<const T*>(a.lfc) + (size_t)p0 * a.nb;
+    const T* lsrc = static_cast<const T*>(pt.lfc) + (size_t)p0 * a.nb;
     for (uint32_t i = tid; i < nl; i += kThreads) s_lfc[i] = lsrc[i];
     lds_barrier();
 }
@@ -1104,15 +1116,16 @@ __device__ __forceinline__ void dec_lds(const DecArgs& a, uint32_t*& s_codes, fl
 // share one LFC value.  A workgroup streams G whole planes.
 template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) decompress_rowvec(DecArgs a) {
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
     uint32_t* s_codes; float2* s_meta; T* s_lfc;
     dec_lds<T>(a, s_codes, s_meta, s_lfc);
     const uint32_t tid = threadIdx.x;
     const uint32_t p0 = blockIdx.x * a.G;
     const uint32_t Gc = min(a.G, a.P - p0);
-    stage_packed<T>(a, p0, Gc, s_codes, s_meta, s_lfc, tid);
+    stage_packed<T>(a, pt, p0, Gc, s_codes, s_meta, s_lfc, tid);
     const uint32_t nvec = Gc * a.q4;
     constexpr uint32_t Lq = (1u << BITS) - 1u;
-    T* out = static_cast<T*>(a.xhat) + (size_t)p0 * a.HW;
+    T* out = static_cast<T*>(pt.xhat) + (size_t)p0 * a.HW;
     for (uint32_t vi = tid; vi < nvec; vi += kThreads) {
         const uint32_t g = fdiv(vi, a.d_q4);
         const uint32_t fi = vi - g * a.q4;        // vector index inside the plane
@@ -1136,6 +1149,7 @@ __global__ void __launch_bounds__(kThreads) decompress_rowvec(DecArgs a) {
 // row / column arithmetic.  A workgroup streams G whole planes.
 template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) decompress_table(DecArgs a) {
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
     uint32_t* s_codes; float2* s_meta; T* s_lfc;
     dec_lds<T>(a, s_codes, s_meta, s_lfc);
     uint32_t* s_tab = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(s_lfc) + ((a.G * a.nb * sizeof(T) + 15u) & ~15u));
@@ -1154,9 +1168,9 @@ __global__ void __launch_bounds__(kThreads) decompress_table(DecArgs a) {
         }
         s_tab[fi] = t;
     }
-    stage_packed<T>(a, p0, Gc, s_codes, s_meta, s_lfc, tid);      // ends with a barrier
+    stage_packed<T>(a, pt, p0, Gc, s_codes, s_meta, s_lfc, tid);      // ends with a barrier
     const uint32_t nvec = Gc * a.q4;
-    T* out = static_cast<T*>(a.xhat) + (size_t)p0 * a.HW;
+    T* out = static_cast<T*>(pt.xhat) + (size_t)p0 * a.HW;
     for (uint32_t vi = tid; vi < nvec; vi += kThreads) {
         const uint32_t g = fdiv(vi, a.d_q4);
         const uint32_t fi = vi - g * a.q4;
@@ -1180,6 +1194,7 @@ __global__ void __launch_bounds__(kThreads) decompress_table(DecArgs a) {
 // vector stores stay aligned; the ragged end of the last chunk is scalar.
 template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) {
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
     uint32_t* s_codes; float2* s_meta; T* s_lfc;
     dec_lds<T>(a, s_codes, s_meta, s_lfc);
     constexpr uint32_t CPW = 32 / BITS;
@@ -1187,9 +1202,9 @@ __global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) {
     const uint32_t tid = threadIdx.x;
     const uint32_t p0 = blockIdx.x * a.G;
     const uint32_t Gc = min(a.G, a.P - p0);
-    stage_packed<T>(a, p0, Gc, s_codes, s_meta, s_lfc, tid);
+    stage_packed<T>(a, pt, p0, Gc, s_codes, s_meta, s_lfc, tid);
     const uint32_t n = Gc * a.HW;
-    T* out = static_cast<T*>(a.xhat) + (size_t)p0 * a.HW;
+    T* out = static_cast<T*>(pt.xhat) + (size_t)p0 * a.HW;
     const bool one_block = a.nb == 1;             // map smaller than the block: LFC is one value per plane
     for (uint32_t e0 = tid * 4; e0 < n; e0 += kThreads * 4) {
         uint32_t g = fdiv(e0, a.d_HW);
@@ -1257,13 +1272,14 @@ __global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) {
 // planes too large for the 32-bit index tricks above: one element per thread step
 template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) decompress_scalar(DecArgs a) {
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
     constexpr uint32_t CPW = 32 / BITS;
     constexpr uint32_t Lq = (1u << BITS) - 1u;
     const uint32_t p = blockIdx.x;
-    const float2 dd = reinterpret_cast<const float2*>(a.meta)[p];
-    const T* lfcp = static_cast<const T*>(a.lfc) + (size_t)p * a.nb;
-    const uint32_t* cp = a.codes + (size_t)p * a.WPP;
-    T* out = static_cast<T*>(a.xhat) + (size_t)p * a.HW;
+    const float2 dd = reinterpret_cast<const float2*>(pt.meta)[p];
+    const T* lfcp = static_cast<const T*>(pt.lfc) + (size_t)p * a.nb;
+    const uint32_t* cp = pt.codes + (size_t)p * a.WPP;
+    T* out = static_cast<T*>(pt.xhat) + (size_t)p * a.HW;
     for (uint32_t i = threadIdx.x; i < a.HW; i += kThreads) {
         const uint32_t r = i / a.W, c = i - r * a.W;
         const uint32_t q = (cp[i / CPW] >> ((i % CPW) * BITS)) & Lq;
@@ -1310,21 +1326,21 @@ uint64_t gcd_u64(uint64_t a, uint64_t b) { while (b) { uint64_t t = a % b; a = b
 // fdiv(n, d) is exact while n*d < 2^32
 bool fastdiv_ok(uint64_t n_max, uint64_t d) { return n_max * d < (1ull << 32); }
 
-Pads make_pads(char* pk, const Layout& L) {
-    Pads pd;
-    pd.base = reinterpret_cast<uint8_t*>(pk);
-    pd.off[0] = L.codes_off + L.codes_bytes; pd.len[0] = (uint32_t)(L.meta_off - pd.off[0]);
-    pd.off[1] = L.meta_off + L.meta_bytes;   pd.len[1] = (uint32_t)(L.lfc_off - pd.off[1]);
-    pd.off[2] = L.lfc_off + L.lfc_bytes;     pd.len[2] = (uint32_t)(L.total - pd.off[2]);
-    return pd;
+Regions make_regions(const Layout& L) {
+    Regions rg;
+    rg.meta_off = L.meta_off;
+    rg.lfc_off = L.lfc_off;
+    rg.pad_off[0] = L.codes_off + L.codes_bytes; rg.pad_len[0] = (uint32_t)(L.meta_off - rg.pad_off[0]);
+    rg.pad_off[1] = L.meta_off + L.meta_bytes;   rg.pad_len[1] = (uint32_t)(L.lfc_off - rg.pad_off[1]);
+    rg.pad_off[2] = L.lfc_off + L.lfc_bytes;     rg.pad_len[2] = (uint32_t)(L.total - rg.pad_off[2]);
+    return rg;
 }
 
-// tuning of the tiled compress kernel: threads per workgroup and preferred LDS
-// bytes per workgroup; DIVISION_TUNE="nt=64,lds=16384" overrides for experiments
-// tuning: nt = 64 enables the one-wavefront kernel; `lds` is the preferred LDS
-// footprint of one wavefront's chunk (small chunks = many wavefronts per CU),
-// a single plane of up to kWavePlaneMax bytes is taken whatever `lds` says.
-// DIVISION_TUNE="nt=256,lds=16384" overrides the defaults for experiments.
+// tuning of the compress kernels: nt = 64 enables the one-wavefront kernel; `lds`
+// is the preferred LDS footprint of one wavefront's chunk (small chunks = many
+// wavefronts per CU), a single plane of up to kWavePlaneMax bytes is taken
+// whatever `lds` says.  DIVISION_TUNE="nt=256,lds=16384" overrides the defaults
+// for experiments.
 constexpr uint32_t kWavePlaneMax = 17u << 10;
 struct Tune { int nt; uint32_t lds; };
 Tune tile_tune() {
@@ -1358,33 +1374,33 @@ hipError_t allow_large_lds(void (*kern)(TileArgs), size_t lds) {
 }
 
 template <typename T, int BITS, int B>
-hipError_t launch_tile_vec(int vec, const TileArgs& a, uint32_t grid, size_t lds, hipStream_t st) {
+hipError_t launch_tile_vec(int vec, const TileArgs& a, dim3 grid, size_t lds, hipStream_t st) {
     void (*kern)(TileArgs) = vec == 4 ? compress_tile<T, BITS, B, 4, 256>
                            : vec == 2 ? compress_tile<T, BITS, B, 2, 256>
                                       : compress_tile<T, BITS, B, 1, 256>;
     hipError_t e = allow_large_lds(kern, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a);
     return hipGetLastError();
 }
 
 template <typename T, int BITS>
-hipError_t launch_tile(int B, int vec, const TileArgs& a, uint32_t grid, size_t lds, hipStream_t st) {
+hipError_t launch_tile(int B, int vec, const TileArgs& a, dim3 grid, size_t lds, hipStream_t st) {
     return B == 8 ? launch_tile_vec<T, BITS, 8>(vec, a, grid, lds, st)
                   : launch_tile_vec<T, BITS, 4>(vec, a, grid, lds, st);
 }
 
 template <typename T, int BITS, int B>
-hipError_t launch_wave_vec(int vec, const WaveArgs& a, uint32_t grid, size_t lds, hipStream_t st) {
+hipError_t launch_wave_vec(int vec, const WaveArgs& a, dim3 grid, size_t lds, hipStream_t st) {
     void (*kern)(WaveArgs) = vec == 4 ? compress_wave<T, BITS, B, 4>
                            : vec == 2 ? compress_wave<T, BITS, B, 2>
                                       : compress_wave<T, BITS, B, 1>;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64), lds, st, a);
+    hipLaunchKernelGGL(kern, grid, dim3(64), lds, st, a);
     return hipGetLastError();
 }
 
 template <typename T, int BITS>
-hipError_t launch_wave(int B, int vec, const WaveArgs& a, uint32_t grid, size_t lds, hipStream_t st) {
+hipError_t launch_wave(int B, int vec, const WaveArgs& a, dim3 grid, size_t lds, hipStream_t st) {
     return B == 8 ? launch_wave_vec<T, BITS, 8>(vec, a, grid, lds, st)
                   : launch_wave_vec<T, BITS, 4>(vec, a, grid, lds, st);
 }
@@ -1405,7 +1421,8 @@ bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
     a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
     a->LH = (uint32_t)L.LH; a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP;
     a->q4 = (uint32_t)q4; a->w4 = (uint32_t)w4;
-    a->ppw = 4;
+    static const int ppw_env = getenv("DIVISION_PPW") ? atoi(getenv("DIVISION_PPW")) : 0;      // experiments only
+    a->ppw = ppw_env > 0 ? (uint32_t)ppw_env : 1u;
     a->d_w4 = make_fastdiv((uint32_t)w4);
     a->d_LW = make_fastdiv((uint32_t)L.LW);
     *lds = 8ull * kRegUnits * nt + 4ull * ((L.nb + 1 + 3) & ~3ull) + 8ull * nw + 16;
@@ -1415,11 +1432,11 @@ bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
 }
 
 template <typename T, int BITS>
-hipError_t launch_regs(int B, int nw, const RegsArgs& a, uint32_t grid, size_t lds, hipStream_t st) {
+hipError_t launch_regs(int B, int nw, const RegsArgs& a, dim3 grid, size_t lds, hipStream_t st) {
     void (*kern)(RegsArgs);
     if (nw == 1) kern = B == 8 ? compress_regs<T, BITS, 8, 1> : compress_regs<T, BITS, 4, 1>;
     else kern = B == 8 ? compress_regs<T, BITS, 8, 4> : compress_regs<T, BITS, 4, 4>;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * nw), lds, st, a);
+    hipLaunchKernelGGL(kern, grid, dim3(64 * nw), lds, st, a);
     return hipGetLastError();
 }
 
@@ -1618,126 +1635,140 @@ int division_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, in
     return DIVISION_OK;
 }
 
-int division_compress(const void* x, int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
-                      int B, int b, uint64_t seed, void* packed, size_t packed_capacity, void* hip_stream) {
-    if (!x || !packed) return DIVISION_EINVAL;
+int division_compress_batch(int count, const void* const* x, void* const* packed, const uint64_t* seeds,
+                            int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
+                            int B, int b, size_t packed_capacity, void* hip_stream) {
+    if (count < 0 || (count > 0 && (!x || !packed || !seeds))) return DIVISION_EINVAL;
     Layout L;
     const int rc = make_layout(N, C, H, W, B, b, (int)dt, &L);
     if (rc != DIVISION_OK) return rc;
     if (packed_capacity < L.total) return DIVISION_ESIZE;
     const size_t es = dt == DIVISION_BF16 ? 2 : 4;
-    if (((uintptr_t)x % es) != 0 || ((uintptr_t)packed % 16) != 0) return DIVISION_EALIGN;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    char* pk = static_cast<char*>(packed);
-    const uint32_t seed_a = mix32((uint32_t)(seed & 0xffffffffu) ^ 0x243F6A88u);
-    const uint32_t seed_c = mix32((uint32_t)(seed >> 32) ^ 0x85A308D3u);
-
-    TileArgs a{};
-    size_t lds = 0;
-    uint32_t grid = 0;
-    int vec = 1, nt = 64;
-    hipError_t err;
-    WaveArgs wa{};
-    RegsArgs ra{};
-    int nw = 1;
-    if (plan_regs(L, H, W, B, es, x, &ra, &grid, &lds, &nw)) {
-        ra.pads = make_pads(pk, L);
-        ra.x = x;
-        ra.codes = reinterpret_cast<uint32_t*>(pk + L.codes_off);
-        ra.meta = reinterpret_cast<float*>(pk + L.meta_off);
-        ra.lfc = pk + L.lfc_off;
-        ra.seed_a = seed_a; ra.seed_c = seed_c;
-        if (dt == DIVISION_F32)
-            err = b == 2 ? launch_regs<float, 2>(B, nw, ra, grid, lds, st) : launch_regs<float, 4>(B, nw, ra, grid, lds, st);
-        else
-            err = b == 2 ? launch_regs<bf16_t, 2>(B, nw, ra, grid, lds, st) : launch_regs<bf16_t, 4>(B, nw, ra, grid, lds, st);
-    } else if (plan_wave(L, H, W, B, b, es, x, &wa, &grid, &lds, &vec)) {
-        wa.pads = make_pads(pk, L);
-        wa.x = x;
-        wa.codes = reinterpret_cast<uint32_t*>(pk + L.codes_off);
-        wa.meta = reinterpret_cast<float*>(pk + L.meta_off);
-        wa.lfc = pk + L.lfc_off;
-        wa.seed_a = seed_a; wa.seed_c = seed_c;
-#ifdef DIVISION_EXPERIMENT
-        wa.skip = getenv("DIVISION_SKIP") ? (uint32_t)atoi(getenv("DIVISION_SKIP")) : 0u;
-        if (getenv("DIVISION_GRID")) grid = (uint32_t)atoi(getenv("DIVISION_GRID"));
-#endif
-        if (dt == DIVISION_F32)
-            err = b == 2 ? launch_wave<float, 2>(B, vec, wa, grid, lds, st) : launch_wave<float, 4>(B, vec, wa, grid, lds, st);
-        else
-            err = b == 2 ? launch_wave<bf16_t, 2>(B, vec, wa, grid, lds, st) : launch_wave<bf16_t, 4>(B, vec, wa, grid, lds, st);
-    } else if (plan_tile(L, H, W, B, b, es, x, &a, &grid, &lds, &vec, &nt)) {
-        a.pads = make_pads(pk, L);
-        a.x = x;
-        a.codes = reinterpret_cast<uint32_t*>(pk + L.codes_off);
-        a.meta = reinterpret_cast<float*>(pk + L.meta_off);
-        a.lfc = pk + L.lfc_off;
-        a.seed_a = seed_a; a.seed_c = seed_c;
-        if (dt == DIVISION_F32)
-            err = b == 2 ? launch_tile<float, 2>(B, vec, a, grid, lds, st) : launch_tile<float, 4>(B, vec, a, grid, lds, st);
-        else
-            err = b == 2 ? launch_tile<bf16_t, 2>(B, vec, a, grid, lds, st) : launch_tile<bf16_t, 4>(B, vec, a, grid, lds, st);
-    } else {
-        AnyArgs g{};
-        g.pads = make_pads(pk, L);
-        g.x = x;
-        g.codes = reinterpret_cast<uint32_t*>(pk + L.codes_off);
-        g.meta = reinterpret_cast<float*>(pk + L.meta_off);
-        g.lfc = pk + L.lfc_off;
-        g.P = (uint32_t)L.P; g.H = (uint32_t)H; g.W = (uint32_t)W; g.HW = (uint32_t)L.HW;
-        g.LH = (uint32_t)L.LH; g.LW = (uint32_t)L.LW; g.nb = (uint32_t)L.nb; g.WPP = (uint32_t)L.WPP; g.B = (uint32_t)B;
-        g.seed_a = seed_a; g.seed_c = seed_c;
-        const dim3 gr((uint32_t)L.P), bl(kThreads);
-        if (dt == DIVISION_F32) {
-            if (b == 2) hipLaunchKernelGGL((compress_any<float, 2>), gr, bl, 0, st, g);
-            else hipLaunchKernelGGL((compress_any<float, 4>), gr, bl, 0, st, g);
-        } else {
-            if (b == 2) hipLaunchKernelGGL((compress_any<bf16_t, 2>), gr, bl, 0, st, g);
-            else hipLaunchKernelGGL((compress_any<bf16_t, 4>), gr, bl, 0, st, g);
-        }
-        err = hipGetLastError();
+    uintptr_t all_x = 0;            // alignment of the batch = alignment of the OR of its pointers
+    for (int i = 0; i < count; ++i) {
+        if (!x[i] || !packed[i]) return DIVISION_EINVAL;
+        if (((uintptr_t)x[i] % es) != 0 || ((uintptr_t)packed[i] % 16) != 0) return DIVISION_EALIGN;
+        all_x |= (uintptr_t)x[i];
     }
-    return err == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const void* xa = reinterpret_cast<const void*>(all_x ? all_x : 16);
+    const Regions rg = make_regions(L);
+
+    for (int i0 = 0; i0 < count; i0 += kMaxBatch) {
+        const int cnt = count - i0 < kMaxBatch ? count - i0 : kMaxBatch;
+        CompTab tab{};
+        for (int i = 0; i < cnt; ++i) {
+            tab.x[i] = x[i0 + i];
+            tab.pk[i] = packed[i0 + i];
+            tab.seed_a[i] = mix32((uint32_t)(seeds[i0 + i] & 0xffffffffu) ^ 0x243F6A88u);
+            tab.seed_c[i] = mix32((uint32_t)(seeds[i0 + i] >> 32) ^ 0x85A308D3u);
+        }
+        TileArgs a{};
+        WaveArgs wa{};
+        RegsArgs ra{};
+        size_t lds = 0;
+        uint32_t grid = 0;
+        int vec = 1, nt = 64, nw = 1;
+        hipError_t err;
+        if (plan_regs(L, H, W, B, es, xa, &ra, &grid, &lds, &nw)) {
+            ra.tab = tab; ra.rg = rg;
+            if (dt == DIVISION_F32)
+                err = b == 2 ? launch_regs<float, 2>(B, nw, ra, dim3(grid, cnt), lds, st) : launch_regs<float, 4>(B, nw, ra, dim3(grid, cnt), lds, st);
+            else
+                err = b == 2 ? launch_regs<bf16_t, 2>(B, nw, ra, dim3(grid, cnt), lds, st) : launch_regs<bf16_t, 4>(B, nw, ra, dim3(grid, cnt), lds, st);
+        } else if (plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
+            wa.tab = tab; wa.rg = rg;
+#ifdef DIVISION_EXPERIMENT
+            wa.skip = getenv("DIVISION_SKIP") ? (uint32_t)atoi(getenv("DIVISION_SKIP")) : 0u;
+#endif
+            if (dt == DIVISION_F32)
+                err = b == 2 ? launch_wave<float, 2>(B, vec, wa, dim3(grid, cnt), lds, st) : launch_wave<float, 4>(B, vec, wa, dim3(grid, cnt), lds, st);
+            else
+                err = b == 2 ? launch_wave<bf16_t, 2>(B, vec, wa, dim3(grid, cnt), lds, st) : launch_wave<bf16_t, 4>(B, vec, wa, dim3(grid, cnt), lds, st);
+        } else if (plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) {
+            a.tab = tab; a.rg = rg;
+            if (dt == DIVISION_F32)
+                err = b == 2 ? launch_tile<float, 2>(B, vec, a, dim3(grid, cnt), lds, st) : launch_tile<float, 4>(B, vec, a, dim3(grid, cnt), lds, st);
+            else
+                err = b == 2 ? launch_tile<bf16_t, 2>(B, vec, a, dim3(grid, cnt), lds, st) : launch_tile<bf16_t, 4>(B, vec, a, dim3(grid, cnt), lds, st);
+        } else {
+            AnyArgs g{};
+            g.tab = tab; g.rg = rg;
+            g.P = (uint32_t)L.P; g.H = (uint32_t)H; g.W = (uint32_t)W; g.HW = (uint32_t)L.HW;
+            g.LH = (uint32_t)L.LH; g.LW = (uint32_t)L.LW; g.nb = (uint32_t)L.nb; g.WPP = (uint32_t)L.WPP; g.B = (uint32_t)B;
+            const dim3 gr((uint32_t)L.P, cnt), bl(kThreads);
+            if (dt == DIVISION_F32) {
+                if (b == 2) hipLaunchKernelGGL((compress_any<float, 2>), gr, bl, 0, st, g);
+                else hipLaunchKernelGGL((compress_any<float, 4>), gr, bl, 0, st, g);
+            } else {
+                if (b == 2) hipLaunchKernelGGL((compress_any<bf16_t, 2>), gr, bl, 0, st, g);
+                else hipLaunchKernelGGL((compress_any<bf16_t, 4>), gr, bl, 0, st, g);
+            }
+            err = hipGetLastError();
+        }
+        if (err != hipSuccess) return DIVISION_EHIP;
+    }
+    return DIVISION_OK;
 }
 
-int division_decompress(const void* packed, size_t packed_bytes, int64_t N, int64_t C, int64_t H, int64_t W,
-                        division_dtype dt, int B, int b, void* xhat, void* hip_stream) {
-    if (!xhat || !packed) return DIVISION_EINVAL;
+int division_compress(const void* x, int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
+                      int B, int b, uint64_t seed, void* packed, size_t packed_capacity, void* hip_stream) {
+    if (!x || !packed) return DIVISION_EINVAL;
+    return division_compress_batch(1, &x, &packed, &seed, N, C, H, W, dt, B, b, packed_capacity, hip_stream);
+}
+
+int division_decompress_batch(int count, const void* const* packed, void* const* xhat, size_t packed_bytes,
+                              int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
+                              int B, int b, void* hip_stream) {
+    if (count < 0 || (count > 0 && (!packed || !xhat))) return DIVISION_EINVAL;
     Layout L;
     const int rc = make_layout(N, C, H, W, B, b, (int)dt, &L);
     if (rc != DIVISION_OK) return rc;
     if (packed_bytes < L.total) return DIVISION_ESIZE;
     const size_t es = dt == DIVISION_BF16 ? 2 : 4;
-    if (((uintptr_t)xhat % es) != 0 || ((uintptr_t)packed % 16) != 0) return DIVISION_EALIGN;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const char* pk = static_cast<const char*>(packed);
-
-    DecArgs a{};
-    uint32_t grid = 0;
-    const int kind = plan_decompress(L, H, W, B, es, xhat, &a, &grid);
-    a.codes = reinterpret_cast<const uint32_t*>(pk + L.codes_off);
-    a.meta = reinterpret_cast<const float*>(pk + L.meta_off);
-    a.lfc = pk + L.lfc_off;
-    a.xhat = xhat;
-    void (*kern)(DecArgs);
-    if (kind == 0) {
-        if (dt == DIVISION_F32) kern = b == 2 ? decompress_rowvec<float, 2> : decompress_rowvec<float, 4>;
-        else kern = b == 2 ? decompress_rowvec<bf16_t, 2> : decompress_rowvec<bf16_t, 4>;
-    } else if (kind == 3) {
-        if (dt == DIVISION_F32) kern = b == 2 ? decompress_table<float, 2> : decompress_table<float, 4>;
-        else kern = b == 2 ? decompress_table<bf16_t, 2> : decompress_table<bf16_t, 4>;
-    } else if (kind == 1) {
-        if (dt == DIVISION_F32) kern = b == 2 ? decompress_flat<float, 2> : decompress_flat<float, 4>;
-        else kern = b == 2 ? decompress_flat<bf16_t, 2> : decompress_flat<bf16_t, 4>;
-    } else {
-        if (dt == DIVISION_F32) kern = b == 2 ? decompress_scalar<float, 2> : decompress_scalar<float, 4>;
-        else kern = b == 2 ? decompress_scalar<bf16_t, 2> : decompress_scalar<bf16_t, 4>;
+    uintptr_t all_out = 0;
+    for (int i = 0; i < count; ++i) {
+        if (!xhat[i] || !packed[i]) return DIVISION_EINVAL;
+        if (((uintptr_t)xhat[i] % es) != 0 || ((uintptr_t)packed[i] % 16) != 0) return DIVISION_EALIGN;
+        all_out |= (uintptr_t)xhat[i];
     }
-    // LDS of the streaming kernels: staged codes, meta and LFC of G planes
-    size_t lds = 0;
-    if (kind != 2) lds = dec_lds_bytes(L, es, a.G) + (kind == 3 ? 4ull * a.q4 + 16 : 0);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, st, a);
-    return hipGetLastError() == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const Regions rg = make_regions(L);
+
+    for (int i0 = 0; i0 < count; i0 += kMaxBatch) {
+        const int cnt = count - i0 < kMaxBatch ? count - i0 : kMaxBatch;
+        DecArgs a{};
+        uint32_t grid = 0;
+        const int kind = plan_decompress(L, H, W, B, es, reinterpret_cast<const void*>(all_out ? all_out : 16), &a, &grid);
+        for (int i = 0; i < cnt; ++i) { a.tab.pk[i] = packed[i0 + i]; a.tab.xhat[i] = xhat[i0 + i]; }
+        a.rg = rg;
+        void (*kern)(DecArgs);
+        if (kind == 0) {
+            if (dt == DIVISION_F32) kern = b == 2 ? decompress_rowvec<float, 2> : decompress_rowvec<float, 4>;
+            else kern = b == 2 ? decompress_rowvec<bf16_t, 2> : decompress_rowvec<bf16_t, 4>;
+        } else if (kind == 3) {
+            if (dt == DIVISION_F32) kern = b == 2 ? decompress_table<float, 2> : decompress_table<float, 4>;
+            else kern = b == 2 ? decompress_table<bf16_t, 2> : decompress_table<bf16_t, 4>;
+        } else if (kind == 1) {
+            if (dt == DIVISION_F32) kern = b == 2 ? decompress_flat<float, 2> : decompress_flat<float, 4>;
+            else kern = b == 2 ? decompress_flat<bf16_t, 2> : decompress_flat<bf16_t, 4>;
+        } else {
+            if (dt == DIVISION_F32) kern = b == 2 ? decompress_scalar<float, 2> : decompress_scalar<float, 4>;
+            else kern = b == 2 ? decompress_scalar<bf16_t, 2> : decompress_scalar<bf16_t, 4>;
+        }
+        // LDS of the streaming kernels: staged codes, meta and LFC of G planes (+ the block table)
+        size_t lds = 0;
+        if (kind != 2) lds = dec_lds_bytes(L, es, a.G) + (kind == 3 ? 4ull * a.q4 + 16 : 0);
+        hipLaunchKernelGGL(kern, dim3(grid, cnt), dim3(kThreads), lds, st, a);
+        if (hipGetLastError() != hipSuccess) return DIVISION_EHIP;
+    }
+    return DIVISION_OK;
+}
+
+int division_decompress(const void* packed, size_t packed_bytes, int64_t N, int64_t C, int64_t H, int64_t W,
+                        division_dtype dt, int B, int b, void* xhat, void* hip_stream) {
+    if (!xhat || !packed) return DIVISION_EINVAL;
+    return division_decompress_batch(1, &packed, &xhat, packed_bytes, N, C, H, W, dt, B, b, hip_stream);
 }
 
 int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, int64_t H, int64_t W,

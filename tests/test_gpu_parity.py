@@ -189,6 +189,74 @@ def test_error_codes_on_device_buffers():
     assert e.value.code == 1
 
 
+# ---------------------------------------------------------------- several maps of one shape per launch
+
+BATCH_CASES = [
+    # shape, B, b, count                one shape per kernel family; 11 maps = one full launch of 8 + one of 3
+    ((3, 5, 56, 56), 8, 2, 11),       # plane in registers
+    ((2, 2, 96, 96), 8, 4, 3),        # plane in registers, four wavefronts
+    ((4, 7, 28, 28), 8, 2, 11),       # one wavefront per chunk
+    ((37, 9, 7, 7), 8, 2, 9),         # one-block planes, two-plane decompress path
+    ((2, 3, 72, 72), 8, 2, 2),        # four-wavefront tile
+    ((2, 3, 36, 36), 12, 2, 5),       # generic kernels
+    ((2, 3, 55, 55), 4, 4, 4),
+]
+
+
+@pytest.mark.parametrize("shape,B,b,count", BATCH_CASES)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_batch_matches_oracle_per_tensor(shape, B, b, count, dtype):
+    xs = [_relu_normal(shape, 7000 + 13 * i + sum(shape), dtype) for i in range(count)]
+    seeds = [(0xC0FFEE << 20) + 0x1_0000_0001 * i for i in range(count)]
+    xd = [x.to("cuda:0") for x in xs]
+    need = pkg.division_packed_bytes(*shape, B, b, dtype)
+    packed = [torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda:0") for _ in xs]
+    pkg.division_compress_batch(xd, B, b, seeds, packed=packed)
+    outs = pkg.division_decompress_batch(packed, shape, B, b, dtype)
+    torch.cuda.synchronize()
+    for x, seed, p, y in zip(xs, seeds, packed, outs):
+        xh, dt = to_host_array(x)
+        ref = oracle.compress(xh, B, b, seed, dt)
+        assert np.array_equal(p.cpu().numpy(), ref)
+        yh, _ = to_host_array(y.cpu())
+        assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt))
+
+
+def test_batch_equals_single_calls_and_empty_batch():
+    shape, B, b = (6, 10, 14, 14), 8, 2
+    xs = [_relu_normal(shape, 7100 + i).to("cuda:0") for i in range(3)]
+    seeds = [5, 6, 7]
+    pb = pkg.division_compress_batch(xs, B, b, seeds)
+    ps = [pkg.division_compress(x, B, b, s) for x, s in zip(xs, seeds)]
+    for u, v in zip(pb, ps):
+        assert torch.equal(u, v)
+    yb = pkg.division_decompress_batch(pb, shape, B, b)
+    for p, y in zip(ps, yb):
+        assert torch.equal(y, pkg.division_decompress(p, shape, B, b))
+    assert pkg.division_compress_batch([], B, b, []) == []
+    assert pkg.division_decompress_batch([], shape, B, b) == []
+    # one misaligned member rejects the whole batch before any launch
+    need = pkg.division_packed_bytes(*shape, B, b)
+    big = torch.empty(need + 16, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(pkg.DivisionError) as e:
+        pkg.division_compress_batch(xs[:2], B, b, seeds[:2], packed=[pb[0], big[1:]])
+    assert e.value.code == 3
+
+
+def test_batch_with_one_unaligned_input_takes_scalar_loads():
+    shape, B, b = (2, 3, 28, 28), 8, 2
+    base = torch.zeros(2 * 3 * 28 * 28 + 1, device="cuda:0")
+    x0 = _relu_normal(shape, 7200)
+    x1 = _relu_normal(shape, 7201)
+    base[1:].copy_(x1.flatten())
+    xs = [x0.to("cuda:0"), base[1:].view(shape)]
+    assert xs[1].data_ptr() % 16 == 4
+    pb = pkg.division_compress_batch(xs, B, b, [1, 2])
+    torch.cuda.synchronize()
+    assert np.array_equal(pb[0].cpu().numpy(), oracle.compress(x0.numpy(), B, b, 1))
+    assert np.array_equal(pb[1].cpu().numpy(), oracle.compress(x1.numpy(), B, b, 2))
+
+
 # ---------------------------------------------------------------- the benchmark configurations
 
 def test_config0_small_tensor_exact():

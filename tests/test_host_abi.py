@@ -22,7 +22,8 @@ def _declared_symbols():
 def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
     assert {"division_packed_bytes", "division_compress", "division_decompress",
-            "division_packed_layout", "division_abi_version"} <= set(names)
+            "division_packed_layout", "division_abi_version",
+            "division_compress_batch", "division_decompress_batch"} <= set(names)
     L = pkg.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -73,3 +74,17 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.division_decompress(None, 64, 1, 1, 4, 4, 0, 2, 2, addr16, None) == 1
     assert L.division_decompress(addr16, 8, 1, 1, 4, 4, 0, 2, 2, addr16 + 1024, None) == 2
     assert L.division_decompress(addr16 + 4, 2048, 1, 1, 4, 4, 0, 2, 2, addr16 + 1024, None) == 3
+    # the batch forms check every item before anything is launched
+    vp2 = ctypes.c_void_p * 2
+    xs, pk = vp2(addr16, addr16 + 512), vp2(addr16 + 1024, addr16 + 2048)
+    sd = (ctypes.c_uint64 * 2)(1, 2)
+    assert L.division_compress_batch(0, None, None, None, 1, 1, 4, 4, 0, 2, 2, 2048, None) == 0
+    assert L.division_compress_batch(-1, xs, pk, sd, 1, 1, 4, 4, 0, 2, 2, 2048, None) == 1
+    assert L.division_compress_batch(2, xs, None, sd, 1, 1, 4, 4, 0, 2, 2, 2048, None) == 1
+    assert L.division_compress_batch(2, vp2(addr16, None), pk, sd, 1, 1, 4, 4, 0, 2, 2, 2048, None) == 1
+    assert L.division_compress_batch(2, xs, pk, sd, 1, 1, 4, 4, 0, 2, 2, 8, None) == 2
+    assert L.division_compress_batch(2, xs, vp2(addr16 + 1024, addr16 + 2049), sd, 1, 1, 4, 4, 0, 2, 2, 1024, None) == 3
+    assert L.division_decompress_batch(0, None, None, 64, 1, 1, 4, 4, 0, 2, 2, None) == 0
+    assert L.division_decompress_batch(2, pk, None, 64, 1, 1, 4, 4, 0, 2, 2, None) == 1
+    assert L.division_decompress_batch(2, pk, xs, 8, 1, 1, 4, 4, 0, 2, 2, None) == 2
+    assert L.division_decompress_batch(2, pk, vp2(addr16, addr16 + 2), 1024, 1, 1, 4, 4, 0, 2, 2, None) == 3
