@@ -814,6 +814,7 @@ struct RegsArgs {
     uint32_t q4;         // units (4 consecutive elements) per plane = H*W/4
     uint32_t w4;         // units per row = W/4
     uint32_t ppw;        // planes a workgroup handles one after the other
+    uint32_t stag_n, stag_shift, stag_iters;   // start-up stagger (see compress_regs)
     FastDiv d_w4, d_LW;
 };
 
@@ -851,6 +852,13 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
     }
     if (tid == 0) lfcs[a.nb] = __builtin_nanf("");
     const bool full_blocks = (a.H % B) == 0 && (a.W % B) == 0;
+
+    // Start-up stagger: the workgroups resident first all load at once, are
+    // served evenly and so finish loading together, then all compute while the
+    // memory idles.  Half of that first wave of workgroups starts late, which
+    // puts the two halves in opposite phases.
+    if (blockIdx.y == 0 && blockIdx.x < a.stag_n && ((blockIdx.x >> a.stag_shift) & 1u))
+        for (uint32_t i = 0; i < a.stag_iters; ++i) __builtin_amdgcn_s_sleep(127);
 
     const uint32_t pbeg = blockIdx.x * a.ppw;
     const uint32_t pend = min(a.P, pbeg + a.ppw);
@@ -1425,6 +1433,11 @@ bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
     a->ppw = ppw_env > 0 ? (uint32_t)ppw_env : 1u;
     a->d_w4 = make_fastdiv((uint32_t)w4);
     a->d_LW = make_fastdiv((uint32_t)L.LW);
+    a->stag_n = 0; a->stag_shift = 0; a->stag_iters = 0;
+    if (const char* e = getenv("DIVISION_STAGGER")) {      // experiments only: "n,shift,iters"
+        unsigned n = 0, sh = 0, it = 0;
+        if (sscanf(e, "%u,%u,%u", &n, &sh, &it) == 3 && sh < 32 && it <= 64) { a->stag_n = n; a->stag_shift = sh; a->stag_iters = it; }
+    }
     *lds = 8ull * kRegUnits * nt + 4ull * ((L.nb + 1 + 3) & ~3ull) + 8ull * nw + 16;
     *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
     *nw_out = nw;
