@@ -42,6 +42,76 @@ WORKLOAD_NAMES = {
 }
 
 
+def per_shape(args, torch, pkg, dev) -> int:
+    """Compress-only and decompress-only rates of every distinct shape of the workload, single calls
+    and batch calls, each against a plain device copy of the map's size timed the same way."""
+    from synthetic_inputs import codec_seed, draw_config
+
+    def timed_us(fn, reps):
+        """median and min over `reps` launches, each bracketed by events on the current stream"""
+        for i in range(5):
+            fn(i)
+        ev = []
+        for i in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn(i)
+            e1.record()
+            ev.append((e0, e1))
+        torch.cuda.synchronize()
+        t = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in ev)
+        return t[len(t) // 2], t[0]
+
+    groups = {}
+    for k, spec, x in draw_config(args.config, args.batch):
+        if spec.dtype == "bf16":
+            x = x.to(torch.bfloat16)
+        groups.setdefault((tuple(x.shape), x.dtype, spec.B, spec.b), []).append((k, x))
+    reps = max(20, args.steps)
+    rows = []
+    for (shape, dtype, B, b), members in groups.items():
+        n = min(len(members), 8)
+        nsets = max(3, args.sets)
+        in_b = members[0][1].numel() * members[0][1].element_size()
+        pk_b = pkg.division_packed_bytes(*shape, B, b, dtype)
+        # rotating sets of n maps each, so that the last-level cache cannot hold the working set
+        xs = [[torch.roll(members[j][1].to(dev), s, 0).contiguous() for j in range(n)] for s in range(nsets)]
+        pk = [[torch.empty(pk_b, dtype=torch.uint8, device=dev) for _ in range(n)] for _ in range(nsets)]
+        out = [[torch.empty(shape, dtype=dtype, device=dev) for _ in range(n)] for _ in range(nsets)]
+        seeds = [codec_seed(args.config, members[j][0]) for j in range(n)]
+        for s in range(nsets):
+            pkg.division_compress_batch(xs[s], B, b, seeds, packed=pk[s])
+        row = {"shape": list(shape), "dtype": "bf16" if dtype == torch.bfloat16 else "f32", "B": B, "b": b,
+               "maps_in_workload": len(members), "input_bytes": in_b, "packed_bytes": pk_b,
+               "compress_kernel": pkg.division_kernel_name(0, shape, B, b, dtype),
+               "decompress_kernel": pkg.division_kernel_name(1, shape, B, b, dtype)}
+        modes = [("single", 1)] + ([("batch", n)] if n > 1 else [])
+        for name, m in modes:
+            tc = timed_us(lambda i: pkg.division_compress_batch(xs[i % nsets][:m], B, b, seeds[:m], packed=pk[i % nsets][:m]), reps)
+            td = timed_us(lambda i: pkg.division_decompress_batch(pk[i % nsets][:m], shape, B, b, dtype, out=out[i % nsets][:m]), reps)
+            tcopy = timed_us(lambda i: [out[i % nsets][j].copy_(xs[i % nsets][j]) for j in range(m)], reps)
+            alg = m * (in_b + pk_b)
+            copy_gbs = 2 * m * in_b / tcopy[0] / 1e3
+            row[name] = {"maps": m,
+                         "compress_us_median": round(tc[0], 2), "compress_us_min": round(tc[1], 2),
+                         "decompress_us_median": round(td[0], 2), "decompress_us_min": round(td[1], 2),
+                         "compress_GB_s": round(alg / tc[0] / 1e3, 1), "decompress_GB_s": round(alg / td[0] / 1e3, 1),
+                         "roundtrip_GB_s": round(2 * alg / (tc[0] + td[0]) / 1e3, 1),
+                         "activation_GB_s": round(2 * m * in_b / (tc[0] + td[0]) / 1e3, 1),
+                         "pct_hbm_peak": round(100 * 2 * alg / (tc[0] + td[0]) / 1e3 / HBM_PEAK_GBS, 1),
+                         "device_copy_GB_s": round(copy_gbs, 1),
+                         "roundtrip_vs_copy": round(2 * alg / (tc[0] + td[0]) / 1e3 / copy_gbs, 3)}
+        row["compression_ratio"] = round(in_b / pk_b, 3)
+        rows.append(row)
+        del xs, pk, out
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "per-shape compress / decompress GB/s (algorithmic bytes), median of %d launches" % reps,
+                      "unit": "GB/s", "n_gpus": 1, "data": "synthetic",
+                      "config": {"workload": WORKLOAD_NAMES[args.config], "batch_override": args.batch},
+                      "shapes": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -55,6 +125,9 @@ def main() -> int:
     ap.add_argument("--compare-modes", action="store_true",
                     help="also time the other launch mode (before the reported one) and add its figures to the line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-shape", action="store_true",
+                    help="time compress and decompress of every distinct tensor shape of the workload on their own, "
+                         "beside a plain device copy of the same size; prints one JSON line with a 'shapes' list")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy 10 times (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -85,6 +158,9 @@ def main() -> int:
         print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4,
                           "launches": 10}))
         return 0
+
+    if args.per_shape:
+        return per_shape(args, torch, pkg, dev)
 
     # ---- synthetic workload on the host, then resident in HBM (several rotating sets)
     _, specs = config(args.config)

@@ -51,6 +51,17 @@ TILE_CASES = [
     ((2, 2, 96, 96), 8, 2),           # plane kept in registers, four wavefronts
     ((1, 3, 100, 92), 8, 4),          # four wavefronts, ragged blocks
     ((9, 1, 56, 56), 8, 2),           # 9 planes: the last workgroup handles one plane only
+    ((3, 7, 24, 40), 8, 2),           # chunk of small planes, 15 blocks per plane (not a power of two)
+    ((5, 5, 20, 12), 4, 2),           # chunk kernel, 15 blocks, ragged last chunk
+    ((2, 3, 22, 18), 8, 4),           # chunk kernel, float2 halves in different blocks, ragged blocks both ways
+    ((3, 67, 6, 6), 4, 2),            # chunk kernel, 92 planes per chunk, pad bytes after every plane
+    ((1, 2, 44, 44), 4, 4),           # chunk kernel, one plane per chunk, 121 blocks (two rounds of block slots)
+]
+
+# enough planes that a workgroup takes several chunks one after the other
+MANY_PLANE_CASES = [
+    ((2048, 64, 14, 14), 8, 2),
+    ((512, 129, 28, 28), 8, 4),
 ]
 
 ANY_CASES = [
@@ -63,6 +74,13 @@ ANY_CASES = [
     ((1, 2, 300, 300), 8, 2),         # plane too large for LDS
     ((2, 2, 33, 17), 16, 4),
 ]
+
+
+@pytest.mark.parametrize("shape,B,b", MANY_PLANE_CASES)
+def test_matches_oracle_many_planes(shape, B, b):
+    x = _relu_normal(shape, 2000 + sum(shape))
+    st = check_against_oracle(x, B, b, seed=0xABCDEF ^ B, threads=16, require_exact=True)
+    assert st["exact"]
 
 
 @pytest.mark.parametrize("shape,B,b", TILE_CASES + ANY_CASES)
