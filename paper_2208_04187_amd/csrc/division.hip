@@ -805,6 +805,170 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
     }
 }
 
+// ------------------------------------------------------------------ compress, items straight from global memory
+
+struct ItemsArgs {
+    CompTab tab;
+    Regions rg;
+    uint32_t P, H, W, HW, LW, nb, WPP;
+    uint32_t ipr;        // item slots per block row (padded to the items-per-block count)
+    uint32_t ipp;        // item slots per plane = LH * ipr (<= 64)
+    uint32_t S;          // lanes per plane: ipp rounded up to a power of two
+    uint32_t S_log2;
+    uint32_t ppr;        // planes per round = 64 / S
+    uint32_t rpw;        // rounds a workgroup handles one after the other
+    uint32_t nrounds;    // ceil(P / ppr)
+    FastDiv d_ipr;
+};
+
+// Small planes (at most 64 pooling items, e.g. 28x28 and 14x14 with B = 8): one
+// wavefront per round of 64/S whole planes, and x never goes through LDS.  A
+// lane owns one pooling item (B rows x VEC columns of one block) and loads it
+// straight from global memory, one VEC-wide load per row; the items of a block
+// and of a plane sit in adjacent lanes, so the block sum (binary64) and the
+// plane's min / max are DPP reductions and every lane ends up with its plane's
+// scale.  The item is quantised out of the registers; its VEC codes per row are
+// OR-ed into the round's packed words in LDS (cleared first, so pad bits stay
+// zero), which then leave as whole coalesced words.
+template <typename T, int BITS, int B, int VEC>
+__global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
+    constexpr int IPB = B / VEC;          // items per block (power of two)
+    constexpr int CPW = 32 / BITS;        // codes per word
+    constexpr float Lf = float((1 << BITS) - 1);
+    extern __shared__ float4 smem4[];
+    uint32_t* cw = reinterpret_cast<uint32_t*>(smem4);        // [ppr * WPP] packed words of the round
+
+    const uint32_t lane = threadIdx.x;
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, lane);
+
+    // the lane's item: the same in every round
+    const uint32_t g = lane >> a.S_log2;                      // plane of the round
+    const uint32_t sub = lane & (a.S - 1);
+    const uint32_t bi = fdiv(sub, a.d_ipr);
+    const uint32_t sl = sub - bi * a.ipr;
+    const uint32_t col0 = sl * VEC, r0 = bi * B, bj = sl / IPB;
+    const bool in_plane = sub < a.ipp && col0 < a.W;
+    const uint32_t off = in_plane ? r0 * a.W + col0 : 0u;     // first element of the item inside its plane
+    const uint32_t nrows = in_plane ? min((uint32_t)B, a.H - r0) : 1u;
+    const uint32_t cnt = max(min((uint32_t)B, a.H - min(a.H, r0)) * min((uint32_t)B, a.W - min(a.W, bj * B)), 1u);
+    const uint32_t lfc_idx = bi * a.LW + bj;
+    const bool writes_lfc = in_plane && (sl % IPB) == 0;
+    const bool fullrows = (a.H % B) == 0;
+    const uint32_t rscale = 1u << (16 - BITS);
+    const uint32_t xoff = (off / 2u) * kWeyl;                 // pair counter of the item's first row
+    const uint32_t rowW = (a.W / 2u) * kWeyl;                 // pair counter distance between rows
+    const uint32_t rwords = a.ppr * a.WPP;
+
+    const uint32_t rend = min(a.nrounds, (blockIdx.x + 1) * a.rpw);
+    for (uint32_t round = blockIdx.x * a.rpw; round < rend; ++round) {
+        const uint32_t p0 = round * a.ppr;
+        const uint32_t Gc = min(a.ppr, a.P - p0);
+        const bool live = g < Gc;
+        const bool valid = live && in_plane;
+
+        // ---- load the item: rows past the map re-read row 0 (no effect on min / max, left out of the sum);
+        // lanes without an item read item 0 of the round and have their effects masked
+        float v[B][VEC];
+        {
+            const T* src = static_cast<const T*>(pt.x) + (size_t)p0 * a.HW;
+            const __amdgpu_buffer_rsrc_t rsrc =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(Gc * a.HW * sizeof(T)), 0x00020000);
+            const uint32_t base = (valid ? g * a.HW + off : 0u) * (uint32_t)sizeof(T);
+            const uint32_t rowb = a.W * (uint32_t)sizeof(T);
+#pragma unroll
+            for (int rr = 0; rr < B; ++rr) {
+                const uint32_t vo = fullrows ? base : base + ((uint32_t)rr < nrows ? rr * rowb : 0u);
+                const uint32_t so = fullrows ? rr * rowb : 0u;
+                if constexpr (sizeof(T) == 4 && VEC == 4) {
+                    const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, vo, so, 0);
+                    v[rr][0] = __uint_as_float(q.x); v[rr][1] = __uint_as_float(q.y);
+                    v[rr][2] = __uint_as_float(q.z); v[rr][3] = __uint_as_float(q.w);
+                } else if constexpr (sizeof(T) == 4 && VEC == 2) {
+                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                    const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, vo, so, 0);
+                    v[rr][0] = __uint_as_float(q.x); v[rr][1] = __uint_as_float(q.y);
+                } else if constexpr (VEC == 4) {
+                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                    const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, vo, so, 0);
+                    v[rr][0] = __uint_as_float(q.x << 16); v[rr][1] = __uint_as_float(q.x & 0xffff0000u);
+                    v[rr][2] = __uint_as_float(q.y << 16); v[rr][3] = __uint_as_float(q.y & 0xffff0000u);
+                } else {
+                    const uint32_t q = __builtin_amdgcn_raw_buffer_load_b32(rsrc, vo, so, 0);
+                    v[rr][0] = __uint_as_float(q << 16); v[rr][1] = __uint_as_float(q & 0xffff0000u);
+                }
+            }
+        }
+        // the round's packed words start at zero
+        for (uint32_t w = lane; w < rwords; w += 64) cw[w] = 0u;
+
+        // ---- Sec. 4.1 AveragePooling: block sum in binary64 over the block's adjacent lanes
+        double Sm = 0.0;
+#pragma unroll
+        for (int rr = 0; rr < B; ++rr) {
+            double rs = (double)v[rr][0];
+#pragma unroll
+            for (int c = 1; c < VEC; ++c) rs += (double)v[rr][c];
+            Sm += (fullrows || (uint32_t)rr < nrows) ? rs : 0.0;
+        }
+        Sm = valid ? Sm : 0.0;
+        Sm = group_sum<IPB>(Sm);
+        const float lfc = Elem<T>::round(mean_of(Sm, cnt));
+        if (valid && writes_lfc) Elem<T>::store(static_cast<T*>(pt.lfc), (size_t)(p0 + g) * a.nb + lfc_idx, lfc);
+
+        // ---- residual H^H = H - UpSampling(H^L) in place, plane min / max
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+#pragma unroll
+        for (int rr = 0; rr < B; ++rr)
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) {
+                v[rr][c] = v[rr][c] - lfc;
+                mn = fminf(mn, v[rr][c]);
+                mx = fmaxf(mx, v[rr][c]);
+            }
+        mn = valid ? mn : __builtin_inff();
+        mx = valid ? mx : -__builtin_inff();
+        group_minmax(a.S, mn, mx);
+
+        // ---- scale of Eq. (quantization), keys, meta: every lane of the plane computes the same values
+        float Delta, inv;
+        plane_scale(mn, mx, Lf, Delta, inv);
+        const float delta = mn;
+        const float invs = inv * (float)(1u << (32 - BITS));
+        const uint32_t p = p0 + g;
+        const uint32_t k1 = mix32(p ^ pt.seed_a);
+        const uint32_t k2 = mix32(k1 + pt.seed_c);
+        if (live && sub == 0) reinterpret_cast<float2*>(pt.meta)[p] = make_float2(delta, Delta);
+        wave_sync();                                           // the zeroed words precede the ORs below
+
+        // ---- Quant + packing: the VEC codes of a row are OR-ed into their word (a row part never straddles words)
+        {
+            const uint32_t xw0 = k1 + xoff;
+            uint32_t* const pw = cw + g * a.WPP;
+#pragma unroll
+            for (int rr = 0; rr < B; ++rr) {
+                const uint32_t xw = xw0 + (uint32_t)rr * rowW;
+                uint32_t c;
+                if constexpr (VEC == 4) {
+                    c = push_pair<BITS>(0u, v[rr][2], v[rr][3], delta, invs, xw + kWeyl, k2, rscale);
+                    c = push_pair<BITS>(c, v[rr][0], v[rr][1], delta, invs, xw, k2, rscale);
+                } else {
+                    c = push_pair<BITS>(0u, v[rr][0], v[rr][1], delta, invs, xw, k2, rscale);
+                }
+                const uint32_t i = off + (uint32_t)rr * a.W;              // element index inside the plane
+                if (valid && (fullrows || (uint32_t)rr < nrows))
+                    __hip_atomic_fetch_or(pw + i / CPW, c << ((i % CPW) * BITS), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
+        wave_sync();
+        {
+            uint32_t* dst = pt.codes + (size_t)p0 * a.WPP;
+            const uint32_t nw = Gc * a.WPP;
+            for (uint32_t w = lane; w < nw; w += 64) dst[w] = cw[w];
+        }
+        wave_sync();                                           // the words are cleared again by the next round
+    }
+}
+
 // ------------------------------------------------------------------ compress, plane held in registers
 
 struct RegsArgs {
@@ -1454,6 +1618,47 @@ hipError_t launch_regs(int B, int nw, const RegsArgs& a, dim3 grid, size_t lds, 
 }
 
 // Fills the one-wavefront compress plan; false when the shape is not covered.
+// Fills the items-from-global compress plan (small planes); false when the shape is not covered.
+bool plan_items(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* x,
+                ItemsArgs* a, uint32_t* grid, size_t* lds, int* vec_out) {
+    static const bool disabled = getenv("DIVISION_NO_ITEMS") != nullptr;      // experiments only
+    if (disabled || (B != 4 && B != 8) || W % 2 != 0) return false;
+    const int vec = W % 4 == 0 ? 4 : 2;
+    if (((uintptr_t)x % (vec * es)) != 0) return false;
+    const uint64_t ipb = (uint64_t)B / vec;
+    const uint64_t slots = (uint64_t)W / vec;
+    const uint64_t ipr = (slots + ipb - 1) / ipb * ipb;
+    const uint64_t ipp = L.LH * ipr;
+    if (ipp > 64) return false;
+    uint64_t S = 1, lg = 0;
+    while (S < ipp) { S *= 2; ++lg; }
+    const uint64_t ppr = 64 / S;
+    if (ppr * L.WPP * 4 > 32u * 1024u || ppr * L.HW * es >= (1ull << 31)) return false;
+    a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
+    a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP;
+    a->ipr = (uint32_t)ipr; a->ipp = (uint32_t)ipp; a->S = (uint32_t)S; a->S_log2 = (uint32_t)lg;
+    a->ppr = (uint32_t)ppr;
+    a->nrounds = (uint32_t)((L.P + ppr - 1) / ppr);
+    a->d_ipr = make_fastdiv((uint32_t)ipr);
+    static const int rpw_env = getenv("DIVISION_RPW") ? atoi(getenv("DIVISION_RPW")) : 0;      // experiments only
+    uint32_t rpw = rpw_env > 0 ? (uint32_t)rpw_env : 2u;
+    while (rpw > 1 && a->nrounds / rpw < 32u * (uint32_t)num_cus()) --rpw;
+    a->rpw = rpw;
+    *lds = 4ull * ppr * L.WPP + 16;
+    *grid = (a->nrounds + rpw - 1) / rpw;
+    *vec_out = vec;
+    return true;
+}
+
+template <typename T, int BITS>
+hipError_t launch_items(int B, int vec, const ItemsArgs& a, dim3 grid, size_t lds, hipStream_t st) {
+    void (*kern)(ItemsArgs);
+    if (B == 8) kern = vec == 4 ? compress_items<T, BITS, 8, 4> : compress_items<T, BITS, 8, 2>;
+    else kern = vec == 4 ? compress_items<T, BITS, 4, 4> : compress_items<T, BITS, 4, 2>;
+    hipLaunchKernelGGL(kern, grid, dim3(64), lds, st, a);
+    return hipGetLastError();
+}
+
 bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, const void* x,
                WaveArgs* a, uint32_t* grid, size_t* lds, int* vec_out) {
     const Tune tune = tile_tune();
@@ -1679,6 +1884,7 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
         TileArgs a{};
         WaveArgs wa{};
         RegsArgs ra{};
+        ItemsArgs ia{};
         size_t lds = 0;
         uint32_t grid = 0;
         int vec = 1, nt = 64, nw = 1;
@@ -1689,6 +1895,12 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
                 err = b == 2 ? launch_regs<float, 2>(B, nw, ra, dim3(grid, cnt), lds, st) : launch_regs<float, 4>(B, nw, ra, dim3(grid, cnt), lds, st);
             else
                 err = b == 2 ? launch_regs<bf16_t, 2>(B, nw, ra, dim3(grid, cnt), lds, st) : launch_regs<bf16_t, 4>(B, nw, ra, dim3(grid, cnt), lds, st);
+        } else if (plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) {
+            ia.tab = tab; ia.rg = rg;
+            if (dt == DIVISION_F32)
+                err = b == 2 ? launch_items<float, 2>(B, vec, ia, dim3(grid, cnt), lds, st) : launch_items<float, 4>(B, vec, ia, dim3(grid, cnt), lds, st);
+            else
+                err = b == 2 ? launch_items<bf16_t, 2>(B, vec, ia, dim3(grid, cnt), lds, st) : launch_items<bf16_t, 4>(B, vec, ia, dim3(grid, cnt), lds, st);
         } else if (plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
             wa.tab = tab; wa.rg = rg;
 #ifdef DIVISION_EXPERIMENT
@@ -1794,9 +2006,11 @@ int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, 
     const char* tn = dt == DIVISION_BF16 ? "bf16_t" : "float";
     int n;
     if (direction == 0) {
-        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
+        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (plan_regs(L, H, W, B, es, data, &ra, &grid, &lds, &nw))
             n = snprintf(out, cap, "compress_regs<%s, %d, %d, %d>", tn, b, B, nw);
+        else if (plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
+            n = snprintf(out, cap, "compress_items<%s, %d, %d, %d>", tn, b, B, vec);
         else if (plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_wave<%s, %d, %d, %d>", tn, b, B, vec);
         else if (plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
