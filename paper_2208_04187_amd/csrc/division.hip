@@ -972,6 +972,131 @@ __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
     }
 }
 
+// ------------------------------------------------------------------ one-block planes, a lane per plane
+
+struct LaneArgs {
+    CompTab tab;
+    Regions rg;
+    uint32_t P, HW, WPP;
+    uint32_t nrounds;    // ceil(P / 64): a round is 64 planes, one per lane
+    uint32_t rpw;        // rounds a workgroup handles one after the other
+    uint32_t vec_load;   // x is 16-byte aligned (a round starts on a 16-byte boundary)
+};
+
+// Planes that are a single block (H <= B and W <= B, e.g. 7x7 with B = 8) with
+// an odd number of elements: one wavefront per round of 64 planes.  The round
+// (64*HW contiguous elements) is loaded with coalesced 16-byte loads and parked
+// in LDS; then lane g owns plane g outright: it reads its HW elements with a
+// stride of HW words (odd, so the 64 lanes hit 64 different banks), sums them in
+// binary64 in index order, takes min / max, and in a second pass quantises its
+// plane pair by pair into its WPP words.  No cross-lane step at all.
+template <typename T, int BITS>
+__global__ void __launch_bounds__(64) compress_lane(LaneArgs a) {
+    constexpr int CPW = 32 / BITS;        // codes per word
+    constexpr int PPW = CPW / 2;          // element pairs per word
+    constexpr uint32_t EPV = 16 / sizeof(T);
+    constexpr float Lf = float((1 << BITS) - 1);
+    extern __shared__ float4 smem4[];
+    float* xs = reinterpret_cast<float*>(smem4);              // [64 * HW (+3)]
+
+    const uint32_t lane = threadIdx.x;
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, lane);
+    const uint32_t rscale = 1u << (16 - BITS);
+    const float* mine = xs + lane * a.HW;
+
+    const uint32_t rend = min(a.nrounds, (blockIdx.x + 1) * a.rpw);
+    for (uint32_t round = blockIdx.x * a.rpw; round < rend; ++round) {
+        const uint32_t p0 = round * 64u;
+        const uint32_t Gc = min(64u, a.P - p0);
+        const uint32_t n = Gc * a.HW;
+        const bool live = lane < Gc;
+        const T* src = static_cast<const T*>(pt.x) + (size_t)p0 * a.HW;
+
+        // ---- the round -> LDS as fp32; vectors past its end read as zero
+        const uint32_t nv = a.vec_load ? n / EPV : 0u;
+        if (a.vec_load) {
+            const __amdgpu_buffer_rsrc_t rsrc =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(nv * 16u), 0x00020000);
+            u32x4 q[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if ((uint32_t)u * 64u < nv) q[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane * 16u, u * 1024, kLoadAux);
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const uint32_t vi = lane + 64u * u;
+                if ((uint32_t)u * 64u < nv && vi < nv) {
+                    if constexpr (sizeof(T) == 4) {
+                        reinterpret_cast<u32x4*>(xs)[vi] = q[u];
+                    } else {
+                        float4* d = reinterpret_cast<float4*>(xs) + 2 * vi;
+                        d[0] = make_float4(__uint_as_float(q[u].x << 16), __uint_as_float(q[u].x & 0xffff0000u),
+                                           __uint_as_float(q[u].y << 16), __uint_as_float(q[u].y & 0xffff0000u));
+                        d[1] = make_float4(__uint_as_float(q[u].z << 16), __uint_as_float(q[u].z & 0xffff0000u),
+                                           __uint_as_float(q[u].w << 16), __uint_as_float(q[u].w & 0xffff0000u));
+                    }
+                }
+            }
+        }
+        for (uint32_t e = nv * EPV + lane; e < n; e += 64) xs[e] = Elem<T>::load(src, e);
+        wave_sync();
+
+        // ---- Sec. 4.1 AveragePooling over the whole plane, min / max of x.  x -> fl(x - m) is
+        // monotone, so the residual's extremes are fl(min x - m) and fl(max x - m).
+        // Lanes past the last plane work on plane 0 of the round and store nothing.
+        const float* pl = live ? mine : xs;
+        double S = 0.0;
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+#pragma unroll 7
+        for (uint32_t e = 0; e < a.HW; ++e) {
+            const float v = pl[e];
+            S += (double)v;
+            mn = fminf(mn, v);
+            mx = fmaxf(mx, v);
+        }
+        const float lfc = Elem<T>::round(mean_of(S, a.HW));
+        const float hmn = mn - lfc, hmx = mx - lfc;
+        float Delta, inv;
+        plane_scale(hmn, hmx, Lf, Delta, inv);
+        const float delta = hmn;
+        const float invs = inv * (float)(1u << (32 - BITS));
+        const uint32_t p = p0 + lane;
+        const uint32_t k1 = mix32(p ^ pt.seed_a);
+        const uint32_t k2 = mix32(k1 + pt.seed_c);
+        if (live) {
+            Elem<T>::store(static_cast<T*>(pt.lfc), p, lfc);
+            reinterpret_cast<float2*>(pt.meta)[p] = make_float2(delta, Delta);
+        }
+
+        // ---- residual, Quant of Eq. (quantization), packing: whole words, then the ragged last one
+        uint32_t* cdst = pt.codes + (size_t)p * a.WPP;
+        const uint32_t wfull = a.HW / CPW;
+        for (uint32_t w = 0; w < wfull; ++w) {
+            const float* hp = pl + w * CPW;
+            const uint32_t xw0 = k1 + (w * PPW) * kWeyl;
+            uint32_t word = 0;
+#pragma unroll
+            for (int j = PPW - 1; j >= 0; --j)
+                word = push_pair<BITS>(word, hp[2 * j] - lfc, hp[2 * j + 1] - lfc, delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+            if (live) cdst[w] = word;
+        }
+        const uint32_t left = a.HW - wfull * CPW;              // 0 .. CPW-1 elements in the last word
+        if (left) {
+            const float* hp = pl + wfull * CPW;
+            const uint32_t xw0 = k1 + (wfull * PPW) * kWeyl;
+            uint32_t word = 0;
+            // pairs from the last one down; an odd `left` pairs its last element with a repeat of itself
+            for (int j = (int)((left - 1) / 2); j >= 0; --j) {
+                const float h0 = hp[2 * j] - lfc;
+                const float h1 = hp[min((uint32_t)(2 * j + 1), left - 1)] - lfc;
+                word = push_pair<BITS>(word, h0, h1, delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+            }
+            word &= (1u << (left * BITS)) - 1u;                 // pad bits are zero
+            if (live) cdst[wfull] = word;
+        }
+        wave_sync();      // LDS is reused by the next round
+    }
+}
+
 // ------------------------------------------------------------------ compress, plane held in registers
 
 struct RegsArgs {
@@ -1484,6 +1609,55 @@ __global__ void __launch_bounds__(kThreads) decompress_scalar(DecArgs a) {
 
 // ------------------------------------------------------------------ host side
 
+// One-block planes with an odd number of elements (the shapes compress_lane
+// takes): one wavefront per round of 64 planes, lane g reconstructs plane g from
+// its WPP code words into LDS (stride HW words, odd: no bank conflicts), then the
+// round leaves with coalesced 16-byte stores.  a.G = rounds per workgroup.
+template <typename T, int BITS>
+__global__ void __launch_bounds__(64) decompress_lane(DecArgs a) {
+    constexpr int CPW = 32 / BITS;
+    constexpr uint32_t Lmask = (1u << BITS) - 1u;
+    extern __shared__ float4 smem4[];
+    float* xs = reinterpret_cast<float*>(smem4);              // [64 * HW (+3)]
+    const uint32_t lane = threadIdx.x;
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
+    const uint32_t nrounds = (a.P + 63u) / 64u;
+    float* mine = xs + lane * a.HW;
+    const bool out_vec = (reinterpret_cast<uintptr_t>(pt.xhat) % (4 * sizeof(T))) == 0;
+
+    const uint32_t rend = min(nrounds, (blockIdx.x + 1) * a.G);
+    for (uint32_t round = blockIdx.x * a.G; round < rend; ++round) {
+        const uint32_t p0 = round * 64u;
+        const uint32_t Gc = min(64u, a.P - p0);
+        const uint32_t p = lane < Gc ? p0 + lane : p0;        // lanes past the last plane redo plane p0 (never stored)
+        const float2 dd = reinterpret_cast<const float2*>(pt.meta)[p];
+        const float lfc = Elem<T>::load(static_cast<const T*>(pt.lfc), p);
+        const uint32_t* cp = pt.codes + (size_t)p * a.WPP;
+        const uint32_t wfull = a.HW / CPW;
+        for (uint32_t w = 0; w < wfull; ++w) {
+            const uint32_t word = cp[w];
+#pragma unroll
+            for (int j = 0; j < CPW; ++j) mine[w * CPW + j] = dequant((word >> (j * BITS)) & Lmask, dd.y, dd.x, lfc);
+        }
+        const uint32_t left = a.HW - wfull * CPW;
+        if (left) {
+            const uint32_t word = cp[wfull];
+            for (uint32_t j = 0; j < left; ++j) mine[wfull * CPW + j] = dequant((word >> (j * BITS)) & Lmask, dd.y, dd.x, lfc);
+        }
+        wave_sync();
+
+        const uint32_t n = Gc * a.HW;
+        T* out = static_cast<T*>(pt.xhat) + (size_t)p0 * a.HW;
+        const uint32_t nv = out_vec ? n / 4u : 0u;
+        for (uint32_t vi = lane; vi < nv; vi += 64) {
+            const float4 f = reinterpret_cast<const float4*>(xs)[vi];
+            store4(out, (size_t)vi * 4, f.x, f.y, f.z, f.w);
+        }
+        for (uint32_t e = nv * 4u + lane; e < n; e += 64) Elem<T>::store(out, e, xs[e]);
+        wave_sync();      // LDS is reused by the next round
+    }
+}
+
 struct Layout {
     uint64_t P, HW, LH, LW, nb, WPP;
     size_t codes_off, codes_bytes, meta_off, meta_bytes, lfc_off, lfc_bytes, total;
@@ -1640,6 +1814,25 @@ hipError_t launch_regs(int B, int nw, const RegsArgs& a, dim3 grid, size_t lds, 
 }
 
 // Fills the one-wavefront compress plan; false when the shape is not covered.
+// one-block planes with an odd element count: the shapes the lane-per-plane kernels take
+bool lane_shape(const Layout& L) { return L.nb == 1 && (L.HW & 1) == 1 && L.HW <= 64; }
+
+// Fills the lane-per-plane compress plan; false when the shape is not covered.
+bool plan_lane(const Layout& L, size_t es, const void* x, LaneArgs* a, uint32_t* grid, size_t* lds) {
+    static const bool disabled = getenv("DIVISION_NO_LANE") != nullptr;      // experiments only
+    if (disabled || !lane_shape(L)) return false;
+    a->P = (uint32_t)L.P; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP;
+    a->nrounds = (uint32_t)((L.P + 63) / 64);
+    a->vec_load = ((uintptr_t)x % 16) == 0;
+    static const int rpw_env = getenv("DIVISION_RPW") ? atoi(getenv("DIVISION_RPW")) : 0;      // experiments only
+    uint32_t rpw = rpw_env > 0 ? (uint32_t)rpw_env : 2u;
+    while (rpw > 1 && a->nrounds / rpw < 32u * (uint32_t)num_cus()) --rpw;
+    a->rpw = rpw;
+    *lds = 4ull * (64ull * L.HW + 4) + 16 * (es == 2 ? 1 : 0);
+    *grid = (a->nrounds + rpw - 1) / rpw;
+    return true;
+}
+
 // Fills the items-from-global compress plan (small planes); false when the shape is not covered.
 bool plan_items(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* x,
                 ItemsArgs* a, uint32_t* grid, size_t* lds, int* vec_out) {
@@ -1804,6 +1997,16 @@ int plan_decompress(const Layout& L, int64_t H, int64_t W, int B, size_t es, con
     const bool small_idx = fastdiv_ok((uint64_t)H, (uint64_t)B) && fastdiv_ok((uint64_t)W, (uint64_t)B);
     const bool out_vec_aligned = ((uintptr_t)xhat % (4 * es)) == 0;
     const uint64_t target = 16ull * 4 * kThreads;      // elements per workgroup
+    // one-block planes with an odd element count: a lane per plane, 64 planes per round
+    static const bool no_lane = getenv("DIVISION_NO_LANE") != nullptr;      // experiments only
+    if (!no_lane && lane_shape(L)) {
+        const uint32_t nrounds = (uint32_t)((L.P + 63) / 64);
+        uint32_t rpw = 2;
+        while (rpw > 1 && nrounds / rpw < 32u * (uint32_t)num_cus()) --rpw;
+        a->G = rpw;
+        *grid = (nrounds + rpw - 1) / rpw;
+        return 4;
+    }
     // fast path: rows are whole vectors that sit inside one block
     if (W % 4 == 0 && B % 4 == 0 && small_idx && out_vec_aligned) {
         a->q4 = (uint32_t)(L.HW / 4);
@@ -1907,6 +2110,7 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
         WaveArgs wa{};
         RegsArgs ra{};
         ItemsArgs ia{};
+        LaneArgs la{};
         size_t lds = 0;
         uint32_t grid = 0;
         int vec = 1, nt = 64, nw = 1;
@@ -1917,6 +2121,13 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
                 err = b == 2 ? launch_regs<float, 2>(B, nw, ra, dim3(grid, cnt), lds, st) : launch_regs<float, 4>(B, nw, ra, dim3(grid, cnt), lds, st);
             else
                 err = b == 2 ? launch_regs<bf16_t, 2>(B, nw, ra, dim3(grid, cnt), lds, st) : launch_regs<bf16_t, 4>(B, nw, ra, dim3(grid, cnt), lds, st);
+        } else if (plan_lane(L, es, xa, &la, &grid, &lds)) {
+            la.tab = tab; la.rg = rg;
+            void (*kern)(LaneArgs);
+            if (dt == DIVISION_F32) kern = b == 2 ? compress_lane<float, 2> : compress_lane<float, 4>;
+            else kern = b == 2 ? compress_lane<bf16_t, 2> : compress_lane<bf16_t, 4>;
+            hipLaunchKernelGGL(kern, dim3(grid, cnt), dim3(64), lds, st, la);
+            err = hipGetLastError();
         } else if (plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) {
             ia.tab = tab; ia.rg = rg;
             if (dt == DIVISION_F32)
@@ -1999,14 +2210,18 @@ int division_decompress_batch(int count, const void* const* packed, void* const*
         } else if (kind == 1) {
             if (dt == DIVISION_F32) kern = b == 2 ? decompress_flat<float, 2> : decompress_flat<float, 4>;
             else kern = b == 2 ? decompress_flat<bf16_t, 2> : decompress_flat<bf16_t, 4>;
+        } else if (kind == 4) {
+            if (dt == DIVISION_F32) kern = b == 2 ? decompress_lane<float, 2> : decompress_lane<float, 4>;
+            else kern = b == 2 ? decompress_lane<bf16_t, 2> : decompress_lane<bf16_t, 4>;
         } else {
             if (dt == DIVISION_F32) kern = b == 2 ? decompress_scalar<float, 2> : decompress_scalar<float, 4>;
             else kern = b == 2 ? decompress_scalar<bf16_t, 2> : decompress_scalar<bf16_t, 4>;
         }
         // LDS of the streaming kernels: staged codes, meta and LFC of G planes (+ the block table)
         size_t lds = 0;
-        if (kind != 2) lds = dec_lds_bytes(L, es, a.G) + (kind == 3 ? 4ull * a.q4 + 16 : 0);
-        hipLaunchKernelGGL(kern, dim3(grid, cnt), dim3(kThreads), lds, st, a);
+        if (kind == 4) lds = 4ull * (64ull * L.HW + 4);
+        else if (kind != 2) lds = dec_lds_bytes(L, es, a.G) + (kind == 3 ? 4ull * a.q4 + 16 : 0);
+        hipLaunchKernelGGL(kern, dim3(grid, cnt), dim3(kind == 4 ? 64 : kThreads), lds, st, a);
         if (hipGetLastError() != hipSuccess) return DIVISION_EHIP;
     }
     return DIVISION_OK;
@@ -2028,9 +2243,11 @@ int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, 
     const char* tn = dt == DIVISION_BF16 ? "bf16_t" : "float";
     int n;
     if (direction == 0) {
-        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
+        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (plan_regs(L, H, W, B, es, data, &ra, &grid, &lds, &nw))
             n = snprintf(out, cap, "compress_regs<%s, %d, %d, %d>", tn, b, B, nw);
+        else if (plan_lane(L, es, data, &la, &grid, &lds))
+            n = snprintf(out, cap, "compress_lane<%s, %d>", tn, b);
         else if (plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_items<%s, %d, %d, %d>", tn, b, B, vec);
         else if (plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))
@@ -2042,7 +2259,7 @@ int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, 
     } else {
         DecArgs a{}; uint32_t grid = 0;
         const int kind = plan_decompress(L, H, W, B, es, data, &a, &grid);
-        n = snprintf(out, cap, "%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 3 ? "decompress_table" : kind == 1 ? "decompress_flat" : "decompress_scalar", tn, b);
+        n = snprintf(out, cap, "%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 3 ? "decompress_table" : kind == 1 ? "decompress_flat" : kind == 4 ? "decompress_lane" : "decompress_scalar", tn, b);
     }
     return (n < 0 || (size_t)n >= cap) ? DIVISION_ESIZE : DIVISION_OK;
 }

@@ -73,6 +73,8 @@ ANY_CASES = [
     ((2, 3, 56, 56), 64, 2),          # block larger than the map
     ((1, 2, 300, 300), 8, 2),         # plane too large for LDS
     ((2, 2, 33, 17), 16, 4),
+    ((5, 13, 7, 5), 16, 4),           # one-block planes under a block size the tiled kernels do not cover
+    ((70, 3, 7, 7), 64, 2),           # 210 planes: three full rounds of 64 and a ragged one
 ]
 
 
