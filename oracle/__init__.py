@@ -62,6 +62,16 @@ def lib() -> ctypes.CDLL:
         L.oracle_float_to_bf16.argtypes = [ctypes.c_float]
         L.oracle_bf16_to_float.restype = ctypes.c_float
         L.oracle_bf16_to_float.argtypes = [ctypes.c_uint16]
+        L.oracle_mask_bytes.restype = sz
+        L.oracle_mask_bytes.argtypes = [i64]
+        L.oracle_relu_forward.restype = ci
+        L.oracle_relu_forward.argtypes = [vp, i64, ci, vp, vp]
+        L.oracle_dropout_threshold.restype = u32
+        L.oracle_dropout_threshold.argtypes = [ctypes.c_float]
+        L.oracle_dropout_forward.restype = ci
+        L.oracle_dropout_forward.argtypes = [vp, i64, ci, ctypes.c_float, u64, vp, vp]
+        L.oracle_mask_backward.restype = ci
+        L.oracle_mask_backward.argtypes = [vp, vp, i64, ci, vp]
         _lib = L
     return _lib
 
@@ -165,3 +175,45 @@ def bf16_bits(a: np.ndarray) -> np.ndarray:
 
 def bf16_to_f32(a: np.ndarray) -> np.ndarray:
     return (a.astype(np.uint32) << 16).view(np.float32)
+
+
+# ---------------------------------------------------------------- 1-bit masks (Relu / Dropout operators)
+
+def mask_bytes(n: int) -> int:
+    return int(lib().oracle_mask_bytes(n))
+
+
+def relu_forward(x: np.ndarray, dt: int = F32):
+    """x: flat or n-d array (float32, or uint16 bf16 bit patterns).  Returns (out, mask words)."""
+    x = np.ascontiguousarray(x, dtype=_np_dtype(dt))
+    y = np.empty_like(x)
+    mask = np.empty(mask_bytes(x.size) // 4, dtype=np.uint32)
+    rc = lib().oracle_relu_forward(x.ctypes.data, x.size, dt, y.ctypes.data, mask.ctypes.data)
+    if rc:
+        raise ValueError("oracle_relu_forward failed")
+    return y, mask
+
+
+def dropout_threshold(p: float) -> int:
+    return int(lib().oracle_dropout_threshold(p))
+
+
+def dropout_forward(x: np.ndarray, p: float, seed: int, dt: int = F32):
+    x = np.ascontiguousarray(x, dtype=_np_dtype(dt))
+    y = np.empty_like(x)
+    mask = np.empty(mask_bytes(x.size) // 4, dtype=np.uint32)
+    rc = lib().oracle_dropout_forward(x.ctypes.data, x.size, dt, p, seed & (2 ** 64 - 1), y.ctypes.data, mask.ctypes.data)
+    if rc:
+        raise ValueError("oracle_dropout_forward failed")
+    return y, mask
+
+
+def mask_backward(mask: np.ndarray, grad_out: np.ndarray, dt: int = F32) -> np.ndarray:
+    g = np.ascontiguousarray(grad_out, dtype=_np_dtype(dt))
+    mask = np.ascontiguousarray(mask, dtype=np.uint32)
+    assert mask.size * 4 == mask_bytes(g.size)
+    out = np.empty_like(g)
+    rc = lib().oracle_mask_backward(mask.ctypes.data, g.ctypes.data, g.size, dt, out.ctypes.data)
+    if rc:
+        raise ValueError("oracle_mask_backward failed")
+    return out

@@ -367,3 +367,88 @@ int oracle_decompress(const void *packed, int64_t N, int64_t C, int64_t H, int64
 /* bf16 helpers exported so tests can build bf16 inputs without torch */
 uint16_t oracle_float_to_bf16(float f) { return float_to_bf16(f); }
 float oracle_bf16_to_float(uint16_t v) { return bf16_to_float(v); }
+
+/* ====================================================================== *
+ * 1-bit masks of the Relu and Dropout operators (the paper's appendix on
+ * operator compression: Algorithms "Relu operator" and "Dropout operator").
+ *
+ *   Relu forward:     V = sgn(H) (1 where H > 0, else 0),  out = V (.) H,
+ *                     V packed one bit per element and cached.
+ *   Dropout forward:  V ~ Bernoulli(1 - p) element-wise,   out = V (.) H.
+ *   Backward (both):  grad_in = V (.) grad_out.
+ *
+ * Readings: the products V (.) H and V (.) grad select: where V = 0 the result
+ * is +0 whatever the operand (also for NaN and -x).  Dropout does not rescale
+ * by 1/(1-p), as in the paper's listing.  The paper names no generator for V;
+ * element i keeps its value iff its 16 random bits r satisfy r >= T with
+ * T = floor(p * 65536 + 0.5) clipped to [0, 65536] (p is widened to binary64
+ * first), the 16 bits being those of element (i mod 2^32) of "plane" i >> 32
+ * of the stream above under the seed XOR 0xD509A5B3C2E1F047.
+ * Mask layout: bit i%32 of 32-bit word i/32 (little endian), pad bits zero.
+ * ====================================================================== */
+
+size_t oracle_mask_bytes(int64_t n) { return n < 0 ? 0 : (size_t)((n + 31) / 32) * 4u; }
+
+static void store_elem(void *y, int dt, size_t idx, float v)
+{
+    if (dt == ORACLE_BF16) ((uint16_t *)y)[idx] = float_to_bf16(v);
+    else ((float *)y)[idx] = v;
+}
+
+/* copies element idx bit for bit (no rounding: the value already has type dt) */
+static void copy_elem(void *y, const void *x, int dt, size_t idx)
+{
+    if (dt == ORACLE_BF16) ((uint16_t *)y)[idx] = ((const uint16_t *)x)[idx];
+    else memcpy((char *)y + 4 * idx, (const char *)x + 4 * idx, 4);
+}
+
+int oracle_relu_forward(const void *x, int64_t n, int dt, void *y, uint32_t *mask)
+{
+    if (!x || !y || !mask || n < 0 || (dt != ORACLE_F32 && dt != ORACLE_BF16)) return 1;
+    memset(mask, 0, oracle_mask_bytes(n));
+    for (int64_t i = 0; i < n; ++i) {
+        if (load_elem(x, dt, (size_t)i) > 0.0f) {
+            mask[i / 32] |= 1u << (i % 32);
+            copy_elem(y, x, dt, (size_t)i);
+        } else {
+            store_elem(y, dt, (size_t)i, 0.0f);
+        }
+    }
+    return 0;
+}
+
+uint32_t oracle_dropout_threshold(float p)
+{
+    double t = floor((double)p * 65536.0 + 0.5);
+    if (!(t > 0.0)) return 0u;          /* also NaN */
+    if (t > 65536.0) return 65536u;
+    return (uint32_t)t;
+}
+
+int oracle_dropout_forward(const void *x, int64_t n, int dt, float p, uint64_t seed, void *y, uint32_t *mask)
+{
+    if (!x || !y || !mask || n < 0 || (dt != ORACLE_F32 && dt != ORACLE_BF16)) return 1;
+    const uint32_t T = oracle_dropout_threshold(p);
+    const uint64_t s = seed ^ 0xD509A5B3C2E1F047ull;
+    memset(mask, 0, oracle_mask_bytes(n));
+    for (int64_t i = 0; i < n; ++i) {
+        uint32_t r = oracle_rand16(s, (uint32_t)((uint64_t)i >> 32), (uint32_t)((uint64_t)i & 0xffffffffu));
+        if (r >= T) {
+            mask[i / 32] |= 1u << (i % 32);
+            copy_elem(y, x, dt, (size_t)i);
+        } else {
+            store_elem(y, dt, (size_t)i, 0.0f);
+        }
+    }
+    return 0;
+}
+
+int oracle_mask_backward(const uint32_t *mask, const void *grad_out, int64_t n, int dt, void *grad_in)
+{
+    if (!mask || !grad_out || !grad_in || n < 0 || (dt != ORACLE_F32 && dt != ORACLE_BF16)) return 1;
+    for (int64_t i = 0; i < n; ++i) {
+        if ((mask[i / 32] >> (i % 32)) & 1u) copy_elem(grad_in, grad_out, dt, (size_t)i);
+        else store_elem(grad_in, dt, (size_t)i, 0.0f);
+    }
+    return 0;
+}

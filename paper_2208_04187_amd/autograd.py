@@ -1,0 +1,52 @@
+"""Algorithm 1 as a saved-tensor hook for torch.autograd.
+
+Inside `with division_saved_tensors(B, b, seed):` every 4-d activation map that
+autograd saves for the backward pass is replaced by its cached tuple (Algorithm
+1, forward loop: AveragePooling, residual, Quant, Cache) and rebuilt when the
+backward pass asks for it (backward loop: Dequant, UpSampling + add), so each
+layer's gradients are estimated from the reconstructed map as in Sec. 4.2.
+Parameters, small tensors and tensors that are not contiguous NCHW float32 /
+bfloat16 device tensors are saved as they are.  Only calls the binding: all
+arithmetic runs in the HIP library.
+"""
+from __future__ import annotations
+
+import torch
+
+from .binding import division_compress, division_decompress
+
+
+class _Cached:
+    __slots__ = ("packed", "shape", "dtype", "B", "b")
+
+    def __init__(self, packed, shape, dtype, B, b):
+        self.packed, self.shape, self.dtype, self.B, self.b = packed, shape, dtype, B, b
+
+
+class division_saved_tensors(torch.autograd.graph.saved_tensors_hooks):
+    """Context manager.  `seed` selects the stochastic-rounding streams: the k-th map cached inside
+    the context uses seed + k, so a training step is reproducible and no two maps share a stream."""
+
+    def __init__(self, B: int = 8, b: int = 2, seed: int = 0, min_elements: int = 1024):
+        self.cached_maps = 0        # maps cached so far
+        self.cached_bytes = 0       # bytes of their packed buffers
+        self.original_bytes = 0     # bytes the maps themselves would have held
+
+        def pack(t: torch.Tensor):
+            eligible = (t.is_cuda and t.dim() == 4 and t.dtype in (torch.float32, torch.bfloat16)
+                        and t.is_contiguous() and t.numel() >= min_elements
+                        and not isinstance(t, torch.nn.Parameter) and not (t.is_leaf and t.requires_grad))
+            if not eligible:
+                return t
+            packed = division_compress(t.detach(), B, b, seed + self.cached_maps)
+            self.cached_maps += 1
+            self.cached_bytes += packed.numel()
+            self.original_bytes += t.numel() * t.element_size()
+            return _Cached(packed, tuple(t.shape), t.dtype, B, b)
+
+        def unpack(obj):
+            if isinstance(obj, _Cached):
+                return division_decompress(obj.packed, obj.shape, obj.B, obj.b, obj.dtype)
+            return obj
+
+        super().__init__(pack, unpack)

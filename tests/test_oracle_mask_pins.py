@@ -1,0 +1,130 @@
+"""Pins of the oracle's 1-bit mask operators (Relu / Dropout, the paper's appendix on operator
+compression) against things other than the oracle: numpy's own elementwise routines and bit
+packing, the algebra of the listings, an independent big-integer evaluation of the random stream,
+and binomial statistics."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from tests import pyref
+
+
+def _bits(mask_words: np.ndarray, n: int) -> np.ndarray:
+    return np.unpackbits(mask_words.view(np.uint8), bitorder="little")[:n].astype(bool)
+
+
+def _values(rng, n):
+    x = rng.standard_normal(n).astype(np.float32)
+    x[::7] = 0.0
+    x[3::11] = -0.0
+    x[5::13] = np.float32(1e-45)          # smallest subnormal: positive, kept
+    return x
+
+
+@pytest.mark.parametrize("n", [0, 1, 31, 32, 33, 64, 1000, 4097])
+def test_relu_forward_is_numpy_maximum_and_packbits(n):
+    rng = np.random.default_rng(n)
+    x = _values(rng, n)
+    y, mask = oracle.relu_forward(x)
+    assert mask.size == (n + 31) // 32
+    keep = x > 0
+    # Algorithm "Relu operator": V = sgn(H), out = V (.) H
+    assert np.array_equal(y, np.where(keep, x, np.float32(0.0)))
+    assert np.array_equal(y, np.maximum(x, np.float32(0.0)))                   # the textbook ReLU
+    assert not np.signbit(y[~keep]).any()                                      # dropped values are +0
+    ref = np.packbits(keep, bitorder="little")
+    assert np.array_equal(mask.view(np.uint8)[:ref.size], ref)
+    assert not mask.view(np.uint8)[ref.size:].any()                            # pad bits zero
+    assert mask.size * 4 == oracle.mask_bytes(n)
+
+
+def test_relu_nan_and_infinities():
+    x = np.array([np.nan, np.inf, -np.inf, -1.0, 2.0], dtype=np.float32)
+    y, mask = oracle.relu_forward(x)
+    assert np.array_equal(_bits(mask, 5), [False, True, False, False, True])
+    assert np.array_equal(y, np.array([0.0, np.inf, 0.0, 0.0, 2.0], dtype=np.float32))
+
+
+def test_mask_backward_is_elementwise_product_with_the_indicator():
+    rng = np.random.default_rng(7)
+    n = 2500
+    x = _values(rng, n)
+    g = rng.standard_normal(n).astype(np.float32)
+    _, mask = oracle.relu_forward(x)
+    gin = oracle.mask_backward(mask, g)
+    # Algorithm "Relu operator", backward: grad_in = V (.) grad_out
+    assert np.array_equal(gin, np.where(x > 0, g, np.float32(0.0)))
+    assert np.array_equal(gin, g * (x > 0).astype(np.float32) + np.float32(0.0))   # -0 * 0 folded to +0
+    # all-ones and all-zero masks: identity and annihilation
+    ones = np.full((n + 31) // 32, 0xFFFFFFFF, dtype=np.uint32)
+    assert np.array_equal(oracle.mask_backward(ones, g), g)
+    assert not oracle.mask_backward(np.zeros_like(ones), g).any()
+
+
+def test_bf16_values_pass_through_bit_for_bit():
+    rng = np.random.default_rng(9)
+    xf = rng.standard_normal(777).astype(np.float32)
+    xb = oracle.bf16_bits(xf)
+    y, mask = oracle.relu_forward(xb, oracle.BF16)
+    keep = oracle.bf16_to_f32(xb) > 0
+    assert np.array_equal(y, np.where(keep, xb, np.uint16(0)))
+    assert np.array_equal(_bits(mask, 777), keep)
+    g = oracle.bf16_bits(rng.standard_normal(777).astype(np.float32))
+    assert np.array_equal(oracle.mask_backward(mask, g, oracle.BF16), np.where(keep, g, np.uint16(0)))
+
+
+def test_dropout_threshold_closed_form():
+    for p, T in [(0.0, 0), (1.0, 65536), (0.5, 32768), (0.25, 16384), (1.0 / 65536, 1), (0.1, 6554),
+                 (-0.3, 0), (2.0, 65536), (float("nan"), 0), (0.999999, 65536)]:
+        assert oracle.dropout_threshold(p) == T, p
+    for p in np.linspace(0, 1, 97):
+        p32 = float(np.float32(p))
+        assert oracle.dropout_threshold(p32) == int(Fraction(p32) * 65536 + Fraction(1, 2))   # exact rational floor
+
+
+@pytest.mark.parametrize("p", [0.0, 0.1, 0.5, 0.9, 1.0])
+def test_dropout_mask_follows_the_independent_stream_evaluation(p):
+    n, seed = 515, 0x1234_5678_9ABC_DEF0
+    x = np.arange(1, n + 1, dtype=np.float32)
+    y, mask = oracle.dropout_forward(x, p, seed)
+    T = oracle.dropout_threshold(p)
+    s = seed ^ 0xD509A5B3C2E1F047
+    keep = np.array([pyref.rand16(s, 0, i) >= T for i in range(n)])
+    assert np.array_equal(_bits(mask, n), keep)
+    # Algorithm "Dropout operator": out = V (.) H, no rescaling
+    assert np.array_equal(y, np.where(keep, x, np.float32(0.0)))
+    if p == 0.0:
+        assert keep.all()
+    if p == 1.0:
+        assert not keep.any()
+
+
+def test_dropout_keep_rate_and_independence():
+    n = 1 << 18
+    x = np.ones(n, dtype=np.float32)
+    for p in (0.1, 0.5, 0.8):
+        _, m1 = oracle.dropout_forward(x, p, 11)
+        _, m2 = oracle.dropout_forward(x, p, 12)
+        k1, k2 = _bits(m1, n), _bits(m2, n)
+        q = 1.0 - oracle.dropout_threshold(p) / 65536.0
+        sd = (n * q * (1 - q)) ** 0.5
+        assert abs(k1.sum() - n * q) < 5 * sd
+        assert abs(k2.sum() - n * q) < 5 * sd
+        # two seeds agree on about q^2 + (1-q)^2 of the positions, neighbours are uncorrelated
+        agree = (k1 == k2).mean()
+        assert abs(agree - (q * q + (1 - q) * (1 - q))) < 0.01
+        c = np.corrcoef(k1[:-1], k1[1:])[0, 1]
+        assert abs(c) < 0.01
+        # same seed: same mask
+        _, m3 = oracle.dropout_forward(x, p, 11)
+        assert np.array_equal(m1, m3)
+
+
+def test_dropout_stream_differs_from_the_codec_stream_of_the_same_seed():
+    n, seed = 4096, 5
+    x = np.ones(n, dtype=np.float32)
+    _, m = oracle.dropout_forward(x, 0.5, seed)
+    codec_bits = np.array([oracle.rand16(seed, 0, i) >= 32768 for i in range(n)])
+    assert abs((_bits(m, n) == codec_bits).mean() - 0.5) < 0.05
