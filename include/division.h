@@ -141,6 +141,44 @@ int division_decompress_batch(int count, const void *const *packed, void *const 
                               division_dtype dt, int B, int b, void *hip_stream);
 
 /*
+ * 1-bit masks of the Relu and Dropout operators (appendix on operator
+ * compression; Algorithms "Relu operator" and "Dropout operator"): the forward
+ * pass caches V, one bit per element (N^2/8 bytes per channel), instead of the
+ * activation; the backward pass needs nothing else.
+ *
+ * Mask layout: bit i%32 of the 32-bit word i/32 holds V of element i (flat
+ * index, any tensor shape); pad bits of the last word are zero.
+ * division_mask_bytes(n) = 4*ceil(n/32) (host-only; 0 for n < 0).
+ *
+ *   x, y, grad_out, grad_in   device, n elements of type dt, aligned to the
+ *           element size (16-byte alignment of both buffers of a call enables
+ *           the fast path).  y may be x itself and grad_in may be grad_out
+ *           itself (in place); other overlaps are not allowed.
+ *   mask    device, 4-byte aligned, at least division_mask_bytes(n) bytes;
+ *           written in full by the forward calls, read by the backward call.
+ *
+ * division_relu_forward:    V = sgn(x) (1 where x > 0), y = V (.) x.
+ * division_dropout_forward: V ~ Bernoulli(1 - p) element-wise, y = V (.) x, no
+ *           rescaling (as in the listing; fold 1/(1-p) into a neighbouring
+ *           layer).  V is a pure function of (n, p, seed): element i is kept
+ *           iff its 16 random bits are >= floor(p*65536 + 0.5).
+ * division_mask_backward:   grad_in = V (.) grad_out (both operators).
+ * Where V = 0 the result is +0 whatever the operand.  Values pass through bit
+ * for bit.  n == 0 is a no-op (the pointers may then be null).  Errors as above (EINVAL, ESIZE, EALIGN,
+ * ERANGE for n > 2^40, EHIP).
+ */
+size_t division_mask_bytes(int64_t n);
+
+int division_relu_forward(const void *x, int64_t n, division_dtype dt,
+                          void *y, void *mask, size_t mask_capacity, void *hip_stream);
+
+int division_dropout_forward(const void *x, int64_t n, division_dtype dt, float p, uint64_t seed,
+                             void *y, void *mask, size_t mask_capacity, void *hip_stream);
+
+int division_mask_backward(const void *mask, size_t mask_bytes, const void *grad_out, int64_t n,
+                           division_dtype dt, void *grad_in, void *hip_stream);
+
+/*
  * Profiling aid (host-only): writes the name of the kernel template instance
  * that division_compress (direction 0, data = x) or division_decompress
  * (direction 1, data = xhat) would launch for these arguments, as it appears

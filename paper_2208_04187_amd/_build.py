@@ -6,7 +6,7 @@ import subprocess
 from pathlib import Path
 
 PKG = Path(__file__).resolve().parent
-SRC = PKG / "csrc" / "division.hip"
+SRCS = [PKG / "csrc" / "division.hip", PKG / "csrc" / "masks.hip"]
 LIB = PKG / "libdivision.so"
 
 HIPCC_FLAGS = [
@@ -22,7 +22,7 @@ def build(verbose: bool = False) -> Path:
     """Compile unconditionally; returns the path of the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB.with_name(LIB.name + ".tmp%d" % os.getpid())
-    cmd = [hipcc, *HIPCC_FLAGS, "-o", str(tmp), str(SRC)]
+    cmd = [hipcc, *HIPCC_FLAGS, "-o", str(tmp), *map(str, SRCS)]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stderr)

@@ -51,6 +51,14 @@ def lib() -> ctypes.CDLL:
         L.division_compress_batch.argtypes = [ci, pp, pp, ctypes.POINTER(u64), i64, i64, i64, i64, ci, ci, ci, sz, vp]
         L.division_decompress_batch.restype = ci
         L.division_decompress_batch.argtypes = [ci, pp, pp, sz, i64, i64, i64, i64, ci, ci, ci, vp]
+        L.division_mask_bytes.restype = sz
+        L.division_mask_bytes.argtypes = [i64]
+        L.division_relu_forward.restype = ci
+        L.division_relu_forward.argtypes = [vp, i64, ci, vp, vp, sz, vp]
+        L.division_dropout_forward.restype = ci
+        L.division_dropout_forward.argtypes = [vp, i64, ci, ctypes.c_float, u64, vp, vp, sz, vp]
+        L.division_mask_backward.restype = ci
+        L.division_mask_backward.argtypes = [vp, sz, vp, i64, ci, vp, vp]
         L.division_kernel_name.restype = ci
         L.division_kernel_name.argtypes = [ci, vp, i64, i64, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
         _lib = L
@@ -176,3 +184,57 @@ def division_kernel_name(direction: int, shape, B: int, b: int, dtype=torch.floa
     if rc:
         raise DivisionError(rc, "division_kernel_name")
     return buf.value.decode()
+
+
+# ---------------------------------------------------------------- 1-bit masks (Relu / Dropout operators)
+
+def division_mask_bytes(n: int) -> int:
+    return int(lib().division_mask_bytes(n))
+
+
+def _flat_ok(t: torch.Tensor, what: str):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{what} must be a contiguous device tensor")
+
+
+def division_relu_forward(x: torch.Tensor, out: torch.Tensor | None = None, mask: torch.Tensor | None = None, stream=None):
+    """Returns (y, mask): y = x where x > 0 else +0; mask = one bit per element (int32 words)."""
+    _flat_ok(x, "x")
+    n = x.numel()
+    if out is None:
+        out = torch.empty_like(x)
+    if mask is None:
+        mask = torch.empty(division_mask_bytes(n) // 4, dtype=torch.int32, device=x.device)
+    rc = lib().division_relu_forward(x.data_ptr(), n, _dt(x.dtype), out.data_ptr(), mask.data_ptr(),
+                                     mask.numel() * mask.element_size(), _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_relu_forward")
+    return out, mask
+
+
+def division_dropout_forward(x: torch.Tensor, p: float, seed: int, out: torch.Tensor | None = None,
+                             mask: torch.Tensor | None = None, stream=None):
+    """Returns (y, mask): y = x where the element is kept else +0 (no rescaling)."""
+    _flat_ok(x, "x")
+    n = x.numel()
+    if out is None:
+        out = torch.empty_like(x)
+    if mask is None:
+        mask = torch.empty(division_mask_bytes(n) // 4, dtype=torch.int32, device=x.device)
+    rc = lib().division_dropout_forward(x.data_ptr(), n, _dt(x.dtype), p, seed & (2 ** 64 - 1), out.data_ptr(),
+                                        mask.data_ptr(), mask.numel() * mask.element_size(), _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_dropout_forward")
+    return out, mask
+
+
+def division_mask_backward(mask: torch.Tensor, grad_out: torch.Tensor, out: torch.Tensor | None = None, stream=None):
+    """grad_in = grad_out where the mask bit is set else +0."""
+    _flat_ok(grad_out, "grad_out")
+    if out is None:
+        out = torch.empty_like(grad_out)
+    rc = lib().division_mask_backward(mask.data_ptr(), mask.numel() * mask.element_size(), grad_out.data_ptr(),
+                                      grad_out.numel(), _dt(grad_out.dtype), out.data_ptr(), _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_mask_backward")
+    return out

@@ -1,0 +1,255 @@
+// 1-bit mask operators for AMD MI355X (gfx950): the Relu and Dropout operators of
+// "DIVISION: Memory Efficient Training via Dual Activation Precision" (appendix on
+// operator compression, Algorithms "Relu operator" and "Dropout operator").
+//
+//   forward:   V = sgn(H) (Relu) or V ~ Bernoulli(1 - p) (Dropout); out = V (.) H;
+//              V is cached one bit per element (N^2/8 bytes per channel).
+//   backward:  grad_in = V (.) grad_out.
+//
+// Pure streaming kernels: one 16-byte vector per lane and step, the lane's 4 (fp32) or
+// 8 (bf16) mask bits are merged over 8 or 4 adjacent lanes with DPP and leave as whole
+// 32-bit words.  Mask layout: bit i%32 of word i/32, pad bits zero.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/division.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kVecPerThread = 4;                  // 16-byte vectors a thread handles, kThreads apart
+constexpr uint32_t kWeyl = 0x9E3779B9u;
+constexpr uint64_t kDropoutStream = 0xD509A5B3C2E1F047ull;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 32-bit xorshift-multiply finaliser (shifts 16/15/16): the codec's random source
+__host__ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
+    x ^= x >> 16; x *= 0x7feb352du;
+    x ^= x >> 15; x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+// random word of element pair j of a stream segment with keys (k1, k2)
+__device__ __forceinline__ uint32_t pair_word(uint32_t k1, uint32_t k2, uint32_t j) {
+    uint32_t x = k1 + j * kWeyl;
+    x ^= x >> 16; x *= 0x7feb352du;
+    x = x ^ (x >> 15) ^ k2; x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8 lanes
+
+// element helpers: T = float or uint16_t (bf16 bit pattern); values pass through bit for bit
+template <typename T> struct Tr;
+template <> struct Tr<float> {
+    static constexpr int EPV = 4;
+    static __device__ __forceinline__ bool positive(uint32_t bits) { return __uint_as_float(bits) > 0.0f; }
+};
+template <> struct Tr<uint16_t> {
+    static constexpr int EPV = 8;
+    static __device__ __forceinline__ bool positive(uint32_t bits) { return __uint_as_float(bits << 16) > 0.0f; }
+};
+
+// the EPV "is positive" bits of one vector (bit e = element e)
+template <typename T>
+__device__ __forceinline__ uint32_t positive_bits(u32x4 q) {
+    uint32_t m = 0;
+    if constexpr (sizeof(T) == 4) {
+        m |= Tr<T>::positive(q.x) ? 1u : 0u; m |= Tr<T>::positive(q.y) ? 2u : 0u;
+        m |= Tr<T>::positive(q.z) ? 4u : 0u; m |= Tr<T>::positive(q.w) ? 8u : 0u;
+    } else {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            m |= Tr<T>::positive(w[k] & 0xffffu) ? (1u << (2 * k)) : 0u;
+            m |= Tr<T>::positive(w[k] >> 16) ? (2u << (2 * k)) : 0u;
+        }
+    }
+    return m;
+}
+
+// keeps the elements of a vector whose bit is set, +0 elsewhere
+template <typename T>
+__device__ __forceinline__ u32x4 select_bits(u32x4 q, uint32_t m) {
+    u32x4 o;
+    if constexpr (sizeof(T) == 4) {
+        o.x = (m & 1u) ? q.x : 0u; o.y = (m & 2u) ? q.y : 0u;
+        o.z = (m & 4u) ? q.z : 0u; o.w = (m & 8u) ? q.w : 0u;
+    } else {
+        uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t keep = ((m >> (2 * k)) & 1u ? 0x0000ffffu : 0u) | ((m >> (2 * k + 1)) & 1u ? 0xffff0000u : 0u);
+            w[k] &= keep;
+        }
+        o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
+    }
+    return o;
+}
+
+// Dropout's keep bits of the EPV elements starting at element e0 (a multiple of EPV):
+// element i keeps its value iff the 16 random bits of element (i mod 2^32) of stream
+// segment i >> 32 are >= T.
+template <typename T>
+__device__ __forceinline__ uint32_t keep_bits(uint64_t e0, uint32_t seed_a, uint32_t seed_c, uint32_t thr) {
+    constexpr int EPV = Tr<T>::EPV;
+    const uint32_t seg = (uint32_t)(e0 >> 32);
+    const uint32_t k1 = mix32(seg ^ seed_a);
+    const uint32_t k2 = mix32(k1 + seed_c);
+    const uint32_t j0 = (uint32_t)e0 >> 1;
+    uint32_t m = 0;
+#pragma unroll
+    for (int k = 0; k < EPV / 2; ++k) {
+        const uint32_t w = pair_word(k1, k2, j0 + (uint32_t)k);
+        m |= ((w & 0xffffu) >= thr ? 1u : 0u) << (2 * k);
+        m |= ((w >> 16) >= thr ? 2u : 0u) << (2 * k);
+    }
+    return m;
+}
+
+// merges the per-lane bit groups of 32/EPV adjacent lanes into the 32-bit mask word they
+// share (every lane of the group ends up with the whole word); all lanes must be active
+template <typename T>
+__device__ __forceinline__ uint32_t merge_word(uint32_t m, uint32_t lane) {
+    constexpr int EPV = Tr<T>::EPV;
+    constexpr uint32_t LPW = 32 / EPV;               // lanes per word: 8 (fp32) or 4 (bf16)
+    uint32_t v = m << (EPV * (lane & (LPW - 1)));
+    v |= dpp_u32<kDppXor1>(v);
+    v |= dpp_u32<kDppXor2>(v);
+    if constexpr (LPW == 8) v |= dpp_u32<kDppHalfMirror>(v);
+    return v;
+}
+
+struct MaskArgs {
+    const void* in;        // x (forward) or grad_out (backward)
+    void* out;             // y or grad_in
+    uint32_t* mask;
+    uint64_t n;            // elements
+    uint64_t nwords;       // mask words = ceil(n / 32)
+    uint32_t vec;          // in and out are 16-byte aligned: whole vectors move with 16-byte accesses
+    uint32_t seed_a, seed_c, thr;      // dropout only
+};
+
+// MODE 0: Relu forward, 1: Dropout forward, 2: backward (mask is read)
+template <typename T, int MODE>
+__global__ void __launch_bounds__(kThreads) mask_kernel(MaskArgs a) {
+    constexpr int EPV = Tr<T>::EPV;
+    constexpr uint32_t LPW = 32 / EPV;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const T* in = static_cast<const T*>(a.in);
+    T* out = static_cast<T*>(a.out);
+    const uint64_t v0 = (uint64_t)blockIdx.x * (kThreads * kVecPerThread) + tid;
+#pragma unroll
+    for (int u = 0; u < kVecPerThread; ++u) {
+        const uint64_t vi = v0 + (uint64_t)u * kThreads;       // the lane's vector
+        const uint64_t e0 = vi * EPV;
+        const bool whole = e0 + EPV <= a.n;
+        const bool fast = whole && a.vec;
+        u32x4 q = {0u, 0u, 0u, 0u};
+        if (fast) {
+            q = *reinterpret_cast<const u32x4*>(in + e0);
+        } else if (e0 < a.n) {
+            // ragged last vector, or unaligned buffers: element by element
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int e = 0; e < EPV; ++e)
+                if (e0 + e < a.n) {
+                    if constexpr (sizeof(T) == 4) w[e] = __float_as_uint(in[e0 + e]);
+                    else w[e / 2] |= (uint32_t)in[e0 + e] << (16 * (e & 1));
+                }
+            q.x = w[0]; q.y = w[1]; q.z = w[2]; q.w = w[3];
+        }
+        uint32_t m;
+        if constexpr (MODE == 0) m = positive_bits<T>(q);
+        else if constexpr (MODE == 1) m = keep_bits<T>(e0, a.seed_a, a.seed_c, a.thr);
+        else {
+            const uint64_t wi = vi / LPW;
+            const uint32_t word = wi < a.nwords ? a.mask[wi] : 0u;
+            m = (word >> (EPV * (uint32_t)(vi & (LPW - 1)))) & ((1u << EPV) - 1u);
+        }
+        // bits of elements past the end are zero
+        if (!whole) m &= e0 < a.n ? (1u << (uint32_t)(a.n - e0)) - 1u : 0u;
+        const u32x4 o = select_bits<T>(q, m);
+        if (fast) {
+            *reinterpret_cast<u32x4*>(out + e0) = o;
+        } else if (e0 < a.n) {
+            const uint32_t w[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+            for (int e = 0; e < EPV; ++e)
+                if (e0 + e < a.n) {
+                    if constexpr (sizeof(T) == 4) out[e0 + e] = __uint_as_float(w[e]);
+                    else out[e0 + e] = (uint16_t)(w[e / 2] >> (16 * (e & 1)));
+                }
+        }
+        if constexpr (MODE != 2) {
+            const uint32_t word = merge_word<T>(m, lane);
+            const uint64_t wi = vi / LPW;
+            if ((lane & (LPW - 1)) == 0 && wi < a.nwords) a.mask[wi] = word;
+        }
+    }
+}
+
+int launch(int mode, const void* in, int64_t n, division_dtype dt, void* out, void* mask, size_t mask_bytes,
+           float p, uint64_t seed, void* hip_stream) {
+    if (n < 0 || (dt != DIVISION_F32 && dt != DIVISION_BF16)) return DIVISION_EINVAL;
+    if (n == 0) return DIVISION_OK;                 // nothing to do; the pointers may be null
+    if (!in || !out || !mask) return DIVISION_EINVAL;
+    if (n > (int64_t)1 << 40) return DIVISION_ERANGE;
+    if (mask_bytes < division_mask_bytes(n)) return DIVISION_ESIZE;
+    const size_t es = dt == DIVISION_BF16 ? 2 : 4;
+    if (((uintptr_t)in % es) != 0 || ((uintptr_t)out % es) != 0 || ((uintptr_t)mask % 4) != 0) return DIVISION_EALIGN;
+    MaskArgs a{};
+    a.in = in; a.out = out; a.mask = static_cast<uint32_t*>(mask);
+    a.n = (uint64_t)n; a.nwords = ((uint64_t)n + 31) / 32;
+    a.vec = ((uintptr_t)in % 16) == 0 && ((uintptr_t)out % 16) == 0;
+    if (mode == 1) {
+        const uint64_t s = seed ^ kDropoutStream;
+        a.seed_a = mix32((uint32_t)(s & 0xffffffffu) ^ 0x243F6A88u);
+        a.seed_c = mix32((uint32_t)(s >> 32) ^ 0x85A308D3u);
+        // T = floor(p * 65536 + 0.5) in binary64, clipped to [0, 65536]; NaN drops nothing
+        const double t = (double)p * 65536.0 + 0.5;
+        a.thr = !(t >= 1.0) ? 0u : t >= 65537.0 ? 65536u : (uint32_t)t;
+    }
+    const uint64_t epv = 16 / es;
+    const uint64_t nvec = ((uint64_t)n + epv - 1) / epv;
+    const uint64_t per_block = (uint64_t)kThreads * kVecPerThread;
+    const uint32_t grid = (uint32_t)((nvec + per_block - 1) / per_block);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    void (*kern)(MaskArgs);
+    if (dt == DIVISION_F32) kern = mode == 0 ? mask_kernel<float, 0> : mode == 1 ? mask_kernel<float, 1> : mask_kernel<float, 2>;
+    else kern = mode == 0 ? mask_kernel<uint16_t, 0> : mode == 1 ? mask_kernel<uint16_t, 1> : mask_kernel<uint16_t, 2>;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), 0, st, a);
+    return hipGetLastError() == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t division_mask_bytes(int64_t n) { return n < 0 ? 0 : (size_t)((n + 31) / 32) * 4u; }
+
+int division_relu_forward(const void* x, int64_t n, division_dtype dt, void* y, void* mask, size_t mask_capacity,
+                          void* hip_stream) {
+    return launch(0, x, n, dt, y, mask, mask_capacity, 0.0f, 0, hip_stream);
+}
+
+int division_dropout_forward(const void* x, int64_t n, division_dtype dt, float p, uint64_t seed, void* y, void* mask,
+                             size_t mask_capacity, void* hip_stream) {
+    return launch(1, x, n, dt, y, mask, mask_capacity, p, seed, hip_stream);
+}
+
+int division_mask_backward(const void* mask, size_t mask_bytes, const void* grad_out, int64_t n, division_dtype dt,
+                           void* grad_in, void* hip_stream) {
+    return launch(2, grad_out, n, dt, grad_in, const_cast<void*>(mask), mask_bytes, 0.0f, 0, hip_stream);
+}
+
+}  // extern "C"

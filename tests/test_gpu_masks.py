@@ -1,0 +1,96 @@
+"""GPU parity of the 1-bit mask operators (Relu / Dropout) against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2208_04187_amd as pkg
+
+pytestmark = pytest.mark.gpu
+
+SIZES = [1, 3, 31, 32, 33, 255, 256, 1000, 4096, 4097, 65536 + 7, (1 << 20) + 5, 3 * 64 * 56 * 56]
+
+
+def _values(n, seed, dtype):
+    g = torch.Generator().manual_seed(seed)
+    x = torch.randn(n, generator=g)
+    x[::7] = 0.0
+    x[3::11] = -0.0
+    if n > 40:
+        x[5] = float("nan"); x[6] = float("inf"); x[8] = -float("inf"); x[9] = 1e-45
+    return x.to(dtype)
+
+
+def _host(t: torch.Tensor):
+    if t.dtype == torch.bfloat16:
+        return t.contiguous().view(torch.int16).numpy().view(np.uint16), oracle.BF16
+    return t.contiguous().numpy(), oracle.F32
+
+
+def _same_bits(a: torch.Tensor, ref: np.ndarray):
+    h, _ = _host(a.cpu())
+    return np.array_equal(h.view(np.uint16 if h.dtype == np.uint16 else np.uint32), ref.view(np.uint16 if ref.dtype == np.uint16 else np.uint32))
+
+
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_relu_forward_and_backward_match_oracle(n, dtype):
+    x = _values(n, 100 + n % 97, dtype)
+    g = _values(n, 200 + n % 89, dtype)
+    xh, dt = _host(x)
+    gh, _ = _host(g)
+    y_ref, m_ref = oracle.relu_forward(xh, dt)
+    y, m = pkg.division_relu_forward(x.to("cuda:0"))
+    torch.cuda.synchronize()
+    assert np.array_equal(m.cpu().numpy().view(np.uint32), m_ref)
+    assert _same_bits(y, y_ref)
+    gin = pkg.division_mask_backward(m, g.to("cuda:0"))
+    torch.cuda.synchronize()
+    assert _same_bits(gin, oracle.mask_backward(m_ref, gh, dt))
+
+
+@pytest.mark.parametrize("p", [0.0, 0.1, 0.5, 0.9, 1.0])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_dropout_forward_matches_oracle(p, dtype):
+    for n, seed in ((1, 1), (77, 2), (4097, 0xFEDCBA9876543210), ((1 << 19) + 3, 4)):
+        x = _values(n, 300 + n % 83, dtype)
+        xh, dt = _host(x)
+        y_ref, m_ref = oracle.dropout_forward(xh, p, seed, dt)
+        y, m = pkg.division_dropout_forward(x.to("cuda:0"), p, seed)
+        torch.cuda.synchronize()
+        assert np.array_equal(m.cpu().numpy().view(np.uint32), m_ref)
+        assert _same_bits(y, y_ref)
+
+
+def test_unaligned_buffers_and_in_place():
+    n = 5003
+    base = torch.zeros(n + 3, device="cuda:0")
+    x = _values(n, 9, torch.float32)
+    base[3:].copy_(x)
+    xd = base[3:]
+    assert xd.data_ptr() % 16 != 0
+    y_ref, m_ref = oracle.relu_forward(x.numpy())
+    y, m = pkg.division_relu_forward(xd)
+    torch.cuda.synchronize()
+    assert np.array_equal(m.cpu().numpy().view(np.uint32), m_ref) and _same_bits(y, y_ref)
+    # in place: y is x itself
+    xa = x.to("cuda:0")
+    y2, m2 = pkg.division_relu_forward(xa, out=xa)
+    torch.cuda.synchronize()
+    assert y2.data_ptr() == xa.data_ptr()
+    assert np.array_equal(m2.cpu().numpy().view(np.uint32), m_ref) and _same_bits(xa, y_ref)
+    g = _values(n, 10, torch.float32).to("cuda:0")
+    ref = oracle.mask_backward(m_ref, g.cpu().numpy())
+    pkg.division_mask_backward(m2, g, out=g)
+    torch.cuda.synchronize()
+    assert _same_bits(g, ref)
+
+
+def test_mask_errors_and_empty_input():
+    x = torch.zeros(100, device="cuda:0")
+    small = torch.empty(3, dtype=torch.int32, device="cuda:0")
+    with pytest.raises(pkg.DivisionError) as e:
+        pkg.division_relu_forward(x, mask=small)
+    assert e.value.code == 2
+    y, m = pkg.division_relu_forward(torch.empty(0, device="cuda:0"))
+    assert y.numel() == 0 and m.numel() == 0

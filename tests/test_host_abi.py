@@ -88,3 +88,23 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.division_decompress_batch(2, pk, None, 64, 1, 1, 4, 4, 0, 2, 2, None) == 1
     assert L.division_decompress_batch(2, pk, xs, 8, 1, 1, 4, 4, 0, 2, 2, None) == 2
     assert L.division_decompress_batch(2, pk, vp2(addr16, addr16 + 2), 1024, 1, 1, 4, 4, 0, 2, 2, None) == 3
+
+
+def test_mask_bytes_and_host_side_errors():
+    L = pkg.lib()
+    for n in (0, 1, 31, 32, 33, 1 << 20, (1 << 31) + 5):
+        assert pkg.division_mask_bytes(n) == oracle.mask_bytes(n) == 4 * ((n + 31) // 32)
+    assert L.division_mask_bytes(-1) == 0
+    buf = ctypes.create_string_buffer(4096)
+    a16 = (ctypes.addressof(buf) + 15) & ~15
+    # all of these return before any HIP call is made
+    assert L.division_relu_forward(None, 8, 0, a16, a16 + 512, 4, None) == 1
+    assert L.division_relu_forward(a16, -1, 0, a16, a16 + 512, 4, None) == 1
+    assert L.division_relu_forward(a16, 8, 5, a16, a16 + 512, 4, None) == 1
+    assert L.division_relu_forward(a16, 64, 0, a16, a16 + 512, 4, None) == 2
+    assert L.division_relu_forward(a16 + 2, 8, 0, a16, a16 + 512, 4, None) == 3
+    assert L.division_relu_forward(a16, 8, 0, a16, a16 + 513, 4, None) == 3
+    assert L.division_relu_forward(a16, (1 << 40) + 1, 0, a16, a16 + 512, 1 << 40, None) == 4
+    assert L.division_relu_forward(a16, 0, 0, a16, a16 + 512, 0, None) == 0
+    assert L.division_dropout_forward(a16, 8, 1, 0.5, 1, None, a16 + 512, 4, None) == 1
+    assert L.division_mask_backward(a16 + 512, 0, a16, 8, 0, a16, None) == 2
