@@ -112,6 +112,56 @@ def per_shape(args, torch, pkg, dev) -> int:
     return 0
 
 
+def masks(args, torch, pkg, dev) -> int:
+    """Rates of the Relu / Dropout mask operators on maps of the workload's largest shape."""
+    from synthetic_inputs import draw_config
+
+    k, spec, x = max(draw_config(args.config, args.batch), key=lambda t: t[2].numel())
+    if spec.dtype == "bf16":
+        x = x.to(torch.bfloat16)
+    n, es = x.numel(), x.element_size()
+    nsets = max(3, args.sets)
+    g = torch.Generator().manual_seed(12345)
+    xs = [(torch.roll(x, s, 0) - 0.5 * (s + 1)).to(dev) for s in range(nsets)]       # mixed signs
+    ys = [torch.empty_like(t) for t in xs]
+    ms = [torch.empty(pkg.division_mask_bytes(n) // 4, dtype=torch.int32, device=dev) for _ in xs]
+    reps = max(20, args.steps)
+
+    def timed_us(fn):
+        for i in range(5):
+            fn(i)
+        ev = []
+        for i in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn(i)
+            e1.record()
+            ev.append((e0, e1))
+        torch.cuda.synchronize()
+        t = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in ev)
+        return t[len(t) // 2], t[0]
+
+    ops = {
+        "relu_forward": (lambda i: pkg.division_relu_forward(xs[i % nsets], out=ys[i % nsets], mask=ms[i % nsets]), 2 * n * es + n / 8),
+        "dropout_forward": (lambda i: pkg.division_dropout_forward(xs[i % nsets], 0.5, i, out=ys[i % nsets], mask=ms[i % nsets]), 2 * n * es + n / 8),
+        "mask_backward": (lambda i: pkg.division_mask_backward(ms[i % nsets], xs[i % nsets], out=ys[i % nsets]), 2 * n * es + n / 8),
+        "device_copy": (lambda i: ys[i % nsets].copy_(xs[i % nsets]), 2 * n * es),
+    }
+    res = {}
+    for name, (fn, nbytes) in ops.items():
+        med, mn = timed_us(fn)
+        res[name] = {"us_median": round(med, 2), "us_min": round(mn, 2), "algorithmic_bytes": int(nbytes),
+                     "GB_s": round(nbytes / med / 1e3, 1), "pct_hbm_peak": round(100 * nbytes / med / 1e3 / HBM_PEAK_GBS, 1)}
+    for name in ("relu_forward", "dropout_forward", "mask_backward"):
+        res[name]["vs_copy"] = round(res[name]["GB_s"] / res["device_copy"]["GB_s"], 3)
+    print(json.dumps({"metric": "1-bit mask operators, GB/s of algorithmic bytes (median of %d launches)" % reps,
+                      "unit": "GB/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16" if es == 2 else "f32",
+                      "config": {"workload": "one map %s of %s" % ("x".join(map(str, x.shape)), WORKLOAD_NAMES[args.config])},
+                      "mask_bytes": pkg.division_mask_bytes(n), "cached_fraction_of_map": round(pkg.division_mask_bytes(n) / (n * es), 5),
+                      "ops": res}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -128,6 +178,9 @@ def main() -> int:
     ap.add_argument("--per-shape", action="store_true",
                     help="time compress and decompress of every distinct tensor shape of the workload on their own, "
                          "beside a plain device copy of the same size; prints one JSON line with a 'shapes' list")
+    ap.add_argument("--masks", action="store_true",
+                    help="time the 1-bit mask operators (Relu / Dropout forward, backward) on the largest map of the "
+                         "workload, beside a plain device copy; prints one JSON line")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy 10 times (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -161,6 +214,8 @@ def main() -> int:
 
     if args.per_shape:
         return per_shape(args, torch, pkg, dev)
+    if args.masks:
+        return masks(args, torch, pkg, dev)
 
     # ---- synthetic workload on the host, then resident in HBM (several rotating sets)
     _, specs = config(args.config)
