@@ -296,6 +296,34 @@ def test_full_size_fp32_configs(idx):
     assert flips <= 1e-6 * total
 
 
+@pytest.mark.parametrize("idx", [1, 2])
+def test_full_size_configs_in_batch_launches(idx):
+    """The launch configuration the benchmark times: consecutive maps of one shape share a launch."""
+    drawn = list(draw_config(idx))
+    groups = []
+    for k, spec, x in drawn:
+        key = (tuple(x.shape), spec.B, spec.b)
+        if groups and groups[-1][0] == key and len(groups[-1][1]) < 8:
+            groups[-1][1].append((k, x))
+        else:
+            groups.append((key, [(k, x)]))
+    for (shape, B, b), members in groups:
+        xs = [x.to("cuda:0") for _, x in members]
+        seeds = [codec_seed(idx, k) for k, _ in members]
+        need = pkg.division_packed_bytes(*shape, B, b)
+        packed = [torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda:0") for _ in xs]
+        pkg.division_compress_batch(xs, B, b, seeds, packed=packed)
+        outs = pkg.division_decompress_batch(packed, shape, B, b)
+        torch.cuda.synchronize()
+        for (k, x), seed, pk, y in zip(members, seeds, packed, outs):
+            ref = oracle.compress(x.numpy(), B, b, seed, threads=16)
+            assert np.array_equal(pk.cpu().numpy(), ref), f"config {idx} tensor {k}"
+            assert np.array_equal(y.cpu().numpy(), oracle.decompress(ref, shape, B, b, threads=16)), f"config {idx} tensor {k}"
+        del xs, packed, outs
+        torch.cuda.empty_cache()
+
+
+
 def test_full_size_bf16_config3():
     for k, spec, x in draw_config(3):
         xb = x.to(torch.bfloat16)
