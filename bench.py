@@ -364,6 +364,22 @@ def main() -> int:
             p = oracle.compress(arr, sp.B, sp.b, seed, dt, threads=threads)
             oracle.decompress(p, tuple(x.shape), sp.B, sp.b, dt, threads=threads)
             tc += time.perf_counter() - a0
+        # the same oracle on ONE thread, on the first eighth of every tensor's samples
+        t1c, frac = 0.0, 0.0
+        for (k, sp, x), seed in zip(host, seeds):
+            ns = max(1, x.shape[0] // 8)
+            xsub = x[:ns].contiguous()
+            if xsub.dtype == torch.bfloat16:
+                arr, dt = xsub.view(torch.int16).numpy().view(np.uint16), oracle.BF16
+            else:
+                arr, dt = xsub.numpy(), oracle.F32
+            a0 = time.perf_counter()
+            p = oracle.compress(arr, sp.B, sp.b, seed, dt, threads=1)
+            oracle.decompress(p, tuple(xsub.shape), sp.B, sp.b, dt, threads=1)
+            t1c += time.perf_counter() - a0
+            frac += 2 * (xsub.numel() * xsub.element_size() + p.size)
+        out["cpu_baseline_single_thread"] = {"value": round(frac / t1c / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                             "sample": f"the first eighth of the samples of every tensor, {t1c:.1f} s wall"}
         out["cpu_baseline"] = {"value": round(algo_bytes_step / tc / 1e9, 3), "unit": "GB/s", "cores": threads,
                                "kind": "oracle",
                                "sample": f"one full step ({len(host)} tensors, {elements} elements) through the C oracle, "

@@ -152,7 +152,7 @@ typedef struct {
 
 static int make_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt, layout_t *L)
 {
-    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4))
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4 && b != 8))
         return 1;
     if (dt != ORACLE_F32 && dt != ORACLE_BF16)
         return 1;
@@ -307,7 +307,7 @@ int oracle_compress(const void *x, int64_t N, int64_t C, int64_t H, int64_t W, i
             volatile float d = h[i] - delta;        /* fp32 sub */
             volatile float t = d * inv;             /* fp32 mul */
             /* floor(t + u), u = r16 / 2^16, evaluated exactly in binary64:
-             * t has <= 24 significant bits and lies in [0, 16], u has 16
+             * t has <= 24 significant bits and lies in [0, 256], u has 16
              * fraction bits, so the sum needs < 53 bits. */
             double s = floor((double)t + (double)r16 / 65536.0);
             uint32_t q = s < 0.0 ? 0u : (uint32_t)s;

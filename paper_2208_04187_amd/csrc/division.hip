@@ -245,8 +245,8 @@ __device__ __forceinline__ void group_minmax(uint32_t S, float& mn, float& mx) {
 // 2j+1 first, then 2j: words are built from the last element down, so that
 // element 0 ends in the low bits).  Exact integer evaluation of
 // floor(t + r/2^16): T = trunc(t * 2^(32-BITS)), sum = T + (r << (16-BITS)),
-// code = top BITS bits of sum.  t <= L(1 + 3 ulp) and r < 2^16 keep the sum
-// below 2^32, so no clamp is needed.
+// code = top BITS bits of sum.  For BITS <= 4, t <= L(1 + 3 ulp) and r < 2^16 keep the
+// sum below 2^32, so no clamp is needed.
 template <int BITS>
 __device__ __forceinline__ uint32_t push_pair(uint32_t acc, float h0, float h1, float delta, float invs,
                                               uint32_t xw, uint32_t k2, uint32_t rscale) {
@@ -255,8 +255,14 @@ __device__ __forceinline__ uint32_t push_pair(uint32_t acc, float h0, float h1, 
     x = x ^ (x >> 15) ^ k2; x *= 0x846ca68bu;
     // final x ^= x >> 16: the high half is unchanged, the low half becomes lo ^ hi
     const uint32_t xl = x ^ (x >> 16);
-    const uint32_t T1 = (uint32_t)((h1 - delta) * invs);
-    const uint32_t T0 = (uint32_t)((h0 - delta) * invs);
+    uint32_t T1 = (uint32_t)((h1 - delta) * invs);
+    uint32_t T0 = (uint32_t)((h0 - delta) * invs);
+    if constexpr (BITS == 8) {
+        // t may exceed L by a few ulp; with 8-bit codes an ulp of 255 is as large as the random
+        // term's step (2^-16), so the sum could wrap: clamp t to L first (the code is L either way)
+        T1 = min(T1, 255u << 24);
+        T0 = min(T0, 255u << 24);
+    }
     uint32_t s1, s0;
     asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(s1) : "v"(x), "s"(rscale), "v"(T1));
     asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[0,0,0,0]" : "=v"(s0) : "v"(xl), "s"(rscale), "v"(T0));
@@ -799,7 +805,7 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
                     part = two << (pw * 2 * BITS);
                 }
                 part |= __builtin_amdgcn_update_dpp(0, (int)part, kDppXor1, 0xf, 0xf, false);
-                part |= __builtin_amdgcn_update_dpp(0, (int)part, kDppXor2, 0xf, 0xf, false);
+                if constexpr (PPW >= 4) part |= __builtin_amdgcn_update_dpp(0, (int)part, kDppXor2, 0xf, 0xf, false);
                 if constexpr (PPW == 8) part |= __builtin_amdgcn_update_dpp(0, (int)part, kDppHalfMirror, 0xf, 0xf, false);
                 if (act && pw == 0) pt.codes[(size_t)(p0 + g) * a.WPP + k] = part;
             }
@@ -1244,10 +1250,10 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
         const uint32_t k2 = mix32(k1 + pt.seed_c);
         if (tid == 0) reinterpret_cast<float2*>(pt.meta)[p] = make_float2(delta, Delta);
 
-        // ---- Quant + packing: a unit is two element pairs = 4 codes (one byte for b = 2)
+        // ---- Quant + packing: a unit is two element pairs = 4 codes (one byte for b = 2, a word for b = 8)
         {
             const uint32_t rscale = 1u << (16 - BITS);
-            constexpr uint32_t CB = BITS / 2;                         // code bytes per unit (1 or 2)
+            constexpr uint32_t CB = BITS / 2;                         // code bytes per unit (1, 2 or 4)
             uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)p * a.WPP * 4;
             const __amdgpu_buffer_rsrc_t crs =
                 __builtin_amdgcn_make_buffer_rsrc(cbase, 0, (int)(a.q4 * CB), 0x00020000);
@@ -1259,7 +1265,8 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
                 c = push_pair<BITS>(c, x[k][0], x[k][1], delta, invs, xw, k2, rscale);
                 // stores past the plane's code bytes are dropped by the buffer bound
                 if constexpr (CB == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, tid, k * NT, 0);
-                else __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c, crs, tid * 2u, k * NT * 2, 0);
+                else if constexpr (CB == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c, crs, tid * 2u, k * NT * 2, 0);
+                else __builtin_amdgcn_raw_buffer_store_b32(c, crs, tid * 4u, k * NT * 4, 0);
             }
             // pad bytes of the plane's last word are zero
             const uint32_t padb = a.WPP * 4 - a.q4 * CB;
@@ -1342,7 +1349,7 @@ __global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) {
             const float h = Elem<T>::load(xp, i) - lfc;
             const uint32_t w = pair_word(k1 + (i >> 1) * kWeyl, k2);
             const uint32_t q = (i & 1u) ? quant<1>(h, delta, inv16, w) : quant<0>(h, delta, inv16, w);
-            word |= q << (e * BITS);
+            word |= min(q, (1u << BITS) - 1u) << (e * BITS);      // t may exceed L by a few ulp
         }
         pt.codes[(size_t)p * a.WPP + k] = word;
     }
@@ -1451,7 +1458,8 @@ __global__ void __launch_bounds__(kThreads) decompress_rowvec(DecArgs a) {
         const float2 dd = s_meta[g];
         uint32_t c4;                               // the four codes, BITS apart from bit 0
         if constexpr (BITS == 2) c4 = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + fi];
-        else c4 = reinterpret_cast<const uint16_t*>(s_codes)[g * a.WPP * 2 + fi];
+        else if constexpr (BITS == 4) c4 = reinterpret_cast<const uint16_t*>(s_codes)[g * a.WPP * 2 + fi];
+        else c4 = s_codes[g * a.WPP + fi];
         const uint32_t r = fdiv(fi, a.d_w4);
         const uint32_t c = (fi - r * a.w4) * 4;
         const float lfc = Elem<T>::load(s_lfc, g * a.nb + fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B));
@@ -1496,7 +1504,8 @@ __global__ void __launch_bounds__(kThreads) decompress_table(DecArgs a) {
         const float2 dd = s_meta[g];
         uint32_t c4;
         if constexpr (BITS == 2) c4 = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + fi];
-        else c4 = reinterpret_cast<const uint16_t*>(s_codes)[g * a.WPP * 2 + fi];
+        else if constexpr (BITS == 4) c4 = reinterpret_cast<const uint16_t*>(s_codes)[g * a.WPP * 2 + fi];
+        else c4 = s_codes[g * a.WPP + fi];
         const uint32_t t = s_tab[fi];
         const T* lp = s_lfc + g * a.nb;
         float o[4];
@@ -1666,7 +1675,7 @@ struct Layout {
 size_t align16(size_t v) { return (v + 15u) & ~(size_t)15u; }
 
 int make_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt, Layout* L) {
-    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4)) return DIVISION_EINVAL;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4 && b != 8)) return DIVISION_EINVAL;
     if (dt != DIVISION_F32 && dt != DIVISION_BF16) return DIVISION_EINVAL;
     const uint64_t lim31 = 0x7fffffffull;
     if ((uint64_t)N > lim31 || (uint64_t)C > lim31 || (uint64_t)H > lim31 || (uint64_t)W > lim31) return DIVISION_ERANGE;
@@ -2118,37 +2127,37 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
         if (plan_regs(L, H, W, B, es, xa, &ra, &grid, &lds, &nw)) {
             ra.tab = tab; ra.rg = rg;
             if (dt == DIVISION_F32)
-                err = b == 2 ? launch_regs<float, 2>(B, nw, ra, dim3(grid, cnt), lds, st) : launch_regs<float, 4>(B, nw, ra, dim3(grid, cnt), lds, st);
+                err = b == 2 ? launch_regs<float, 2>(B, nw, ra, dim3(grid, cnt), lds, st) : b == 4 ? launch_regs<float, 4>(B, nw, ra, dim3(grid, cnt), lds, st) : launch_regs<float, 8>(B, nw, ra, dim3(grid, cnt), lds, st);
             else
-                err = b == 2 ? launch_regs<bf16_t, 2>(B, nw, ra, dim3(grid, cnt), lds, st) : launch_regs<bf16_t, 4>(B, nw, ra, dim3(grid, cnt), lds, st);
+                err = b == 2 ? launch_regs<bf16_t, 2>(B, nw, ra, dim3(grid, cnt), lds, st) : b == 4 ? launch_regs<bf16_t, 4>(B, nw, ra, dim3(grid, cnt), lds, st) : launch_regs<bf16_t, 8>(B, nw, ra, dim3(grid, cnt), lds, st);
         } else if (plan_lane(L, es, xa, &la, &grid, &lds)) {
             la.tab = tab; la.rg = rg;
             void (*kern)(LaneArgs);
-            if (dt == DIVISION_F32) kern = b == 2 ? compress_lane<float, 2> : compress_lane<float, 4>;
-            else kern = b == 2 ? compress_lane<bf16_t, 2> : compress_lane<bf16_t, 4>;
+            if (dt == DIVISION_F32) kern = b == 2 ? compress_lane<float, 2> : b == 4 ? compress_lane<float, 4> : compress_lane<float, 8>;
+            else kern = b == 2 ? compress_lane<bf16_t, 2> : b == 4 ? compress_lane<bf16_t, 4> : compress_lane<bf16_t, 8>;
             hipLaunchKernelGGL(kern, dim3(grid, cnt), dim3(64), lds, st, la);
             err = hipGetLastError();
         } else if (plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) {
             ia.tab = tab; ia.rg = rg;
             if (dt == DIVISION_F32)
-                err = b == 2 ? launch_items<float, 2>(B, vec, ia, dim3(grid, cnt), lds, st) : launch_items<float, 4>(B, vec, ia, dim3(grid, cnt), lds, st);
+                err = b == 2 ? launch_items<float, 2>(B, vec, ia, dim3(grid, cnt), lds, st) : b == 4 ? launch_items<float, 4>(B, vec, ia, dim3(grid, cnt), lds, st) : launch_items<float, 8>(B, vec, ia, dim3(grid, cnt), lds, st);
             else
-                err = b == 2 ? launch_items<bf16_t, 2>(B, vec, ia, dim3(grid, cnt), lds, st) : launch_items<bf16_t, 4>(B, vec, ia, dim3(grid, cnt), lds, st);
+                err = b == 2 ? launch_items<bf16_t, 2>(B, vec, ia, dim3(grid, cnt), lds, st) : b == 4 ? launch_items<bf16_t, 4>(B, vec, ia, dim3(grid, cnt), lds, st) : launch_items<bf16_t, 8>(B, vec, ia, dim3(grid, cnt), lds, st);
         } else if (plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
             wa.tab = tab; wa.rg = rg;
 #ifdef DIVISION_EXPERIMENT
             wa.skip = getenv("DIVISION_SKIP") ? (uint32_t)atoi(getenv("DIVISION_SKIP")) : 0u;
 #endif
             if (dt == DIVISION_F32)
-                err = b == 2 ? launch_wave<float, 2>(B, vec, wa, dim3(grid, cnt), lds, st) : launch_wave<float, 4>(B, vec, wa, dim3(grid, cnt), lds, st);
+                err = b == 2 ? launch_wave<float, 2>(B, vec, wa, dim3(grid, cnt), lds, st) : b == 4 ? launch_wave<float, 4>(B, vec, wa, dim3(grid, cnt), lds, st) : launch_wave<float, 8>(B, vec, wa, dim3(grid, cnt), lds, st);
             else
-                err = b == 2 ? launch_wave<bf16_t, 2>(B, vec, wa, dim3(grid, cnt), lds, st) : launch_wave<bf16_t, 4>(B, vec, wa, dim3(grid, cnt), lds, st);
+                err = b == 2 ? launch_wave<bf16_t, 2>(B, vec, wa, dim3(grid, cnt), lds, st) : b == 4 ? launch_wave<bf16_t, 4>(B, vec, wa, dim3(grid, cnt), lds, st) : launch_wave<bf16_t, 8>(B, vec, wa, dim3(grid, cnt), lds, st);
         } else if (plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) {
             a.tab = tab; a.rg = rg;
             if (dt == DIVISION_F32)
-                err = b == 2 ? launch_tile<float, 2>(B, vec, a, dim3(grid, cnt), lds, st) : launch_tile<float, 4>(B, vec, a, dim3(grid, cnt), lds, st);
+                err = b == 2 ? launch_tile<float, 2>(B, vec, a, dim3(grid, cnt), lds, st) : b == 4 ? launch_tile<float, 4>(B, vec, a, dim3(grid, cnt), lds, st) : launch_tile<float, 8>(B, vec, a, dim3(grid, cnt), lds, st);
             else
-                err = b == 2 ? launch_tile<bf16_t, 2>(B, vec, a, dim3(grid, cnt), lds, st) : launch_tile<bf16_t, 4>(B, vec, a, dim3(grid, cnt), lds, st);
+                err = b == 2 ? launch_tile<bf16_t, 2>(B, vec, a, dim3(grid, cnt), lds, st) : b == 4 ? launch_tile<bf16_t, 4>(B, vec, a, dim3(grid, cnt), lds, st) : launch_tile<bf16_t, 8>(B, vec, a, dim3(grid, cnt), lds, st);
         } else {
             AnyArgs g{};
             g.tab = tab; g.rg = rg;
@@ -2157,10 +2166,12 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
             const dim3 gr((uint32_t)L.P, cnt), bl(kThreads);
             if (dt == DIVISION_F32) {
                 if (b == 2) hipLaunchKernelGGL((compress_any<float, 2>), gr, bl, 0, st, g);
-                else hipLaunchKernelGGL((compress_any<float, 4>), gr, bl, 0, st, g);
+                else if (b == 4) hipLaunchKernelGGL((compress_any<float, 4>), gr, bl, 0, st, g);
+                else hipLaunchKernelGGL((compress_any<float, 8>), gr, bl, 0, st, g);
             } else {
                 if (b == 2) hipLaunchKernelGGL((compress_any<bf16_t, 2>), gr, bl, 0, st, g);
-                else hipLaunchKernelGGL((compress_any<bf16_t, 4>), gr, bl, 0, st, g);
+                else if (b == 4) hipLaunchKernelGGL((compress_any<bf16_t, 4>), gr, bl, 0, st, g);
+                else hipLaunchKernelGGL((compress_any<bf16_t, 8>), gr, bl, 0, st, g);
             }
             err = hipGetLastError();
         }
@@ -2202,20 +2213,20 @@ int division_decompress_batch(int count, const void* const* packed, void* const*
         a.rg = rg;
         void (*kern)(DecArgs);
         if (kind == 0) {
-            if (dt == DIVISION_F32) kern = b == 2 ? decompress_rowvec<float, 2> : decompress_rowvec<float, 4>;
-            else kern = b == 2 ? decompress_rowvec<bf16_t, 2> : decompress_rowvec<bf16_t, 4>;
+            if (dt == DIVISION_F32) kern = b == 2 ? decompress_rowvec<float, 2> : b == 4 ? decompress_rowvec<float, 4> : decompress_rowvec<float, 8>;
+            else kern = b == 2 ? decompress_rowvec<bf16_t, 2> : b == 4 ? decompress_rowvec<bf16_t, 4> : decompress_rowvec<bf16_t, 8>;
         } else if (kind == 3) {
-            if (dt == DIVISION_F32) kern = b == 2 ? decompress_table<float, 2> : decompress_table<float, 4>;
-            else kern = b == 2 ? decompress_table<bf16_t, 2> : decompress_table<bf16_t, 4>;
+            if (dt == DIVISION_F32) kern = b == 2 ? decompress_table<float, 2> : b == 4 ? decompress_table<float, 4> : decompress_table<float, 8>;
+            else kern = b == 2 ? decompress_table<bf16_t, 2> : b == 4 ? decompress_table<bf16_t, 4> : decompress_table<bf16_t, 8>;
         } else if (kind == 1) {
-            if (dt == DIVISION_F32) kern = b == 2 ? decompress_flat<float, 2> : decompress_flat<float, 4>;
-            else kern = b == 2 ? decompress_flat<bf16_t, 2> : decompress_flat<bf16_t, 4>;
+            if (dt == DIVISION_F32) kern = b == 2 ? decompress_flat<float, 2> : b == 4 ? decompress_flat<float, 4> : decompress_flat<float, 8>;
+            else kern = b == 2 ? decompress_flat<bf16_t, 2> : b == 4 ? decompress_flat<bf16_t, 4> : decompress_flat<bf16_t, 8>;
         } else if (kind == 4) {
-            if (dt == DIVISION_F32) kern = b == 2 ? decompress_lane<float, 2> : decompress_lane<float, 4>;
-            else kern = b == 2 ? decompress_lane<bf16_t, 2> : decompress_lane<bf16_t, 4>;
+            if (dt == DIVISION_F32) kern = b == 2 ? decompress_lane<float, 2> : b == 4 ? decompress_lane<float, 4> : decompress_lane<float, 8>;
+            else kern = b == 2 ? decompress_lane<bf16_t, 2> : b == 4 ? decompress_lane<bf16_t, 4> : decompress_lane<bf16_t, 8>;
         } else {
-            if (dt == DIVISION_F32) kern = b == 2 ? decompress_scalar<float, 2> : decompress_scalar<float, 4>;
-            else kern = b == 2 ? decompress_scalar<bf16_t, 2> : decompress_scalar<bf16_t, 4>;
+            if (dt == DIVISION_F32) kern = b == 2 ? decompress_scalar<float, 2> : b == 4 ? decompress_scalar<float, 4> : decompress_scalar<float, 8>;
+            else kern = b == 2 ? decompress_scalar<bf16_t, 2> : b == 4 ? decompress_scalar<bf16_t, 4> : decompress_scalar<bf16_t, 8>;
         }
         // LDS of the streaming kernels: staged codes, meta and LFC of G planes (+ the block table)
         size_t lds = 0;

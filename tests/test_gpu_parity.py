@@ -58,6 +58,14 @@ TILE_CASES = [
     ((1, 2, 44, 44), 4, 4),           # chunk kernel, one plane per chunk, 121 blocks (two rounds of block slots)
 ]
 
+# 8-bit codes (the Q = 8 column of the paper's bit-width ablation): one shape per kernel family
+B8_CASES = [
+    ((3, 5, 56, 56), 8, 8), ((2, 2, 96, 96), 8, 8), ((4, 7, 28, 28), 8, 8), ((5, 9, 14, 14), 8, 8),
+    ((37, 9, 7, 7), 8, 8), ((2, 3, 72, 72), 8, 8), ((2, 3, 55, 55), 4, 8), ((2, 3, 36, 36), 12, 8),
+    ((3, 4, 32, 32), 4, 8), ((2, 2, 9, 6), 4, 8), ((1, 2, 300, 300), 8, 8), ((2, 3, 50, 44), 8, 8),
+    ((6, 5, 10, 10), 8, 8),
+]
+
 # enough planes that a workgroup takes several chunks one after the other
 MANY_PLANE_CASES = [
     ((2048, 64, 14, 14), 8, 2),
@@ -85,7 +93,21 @@ def test_matches_oracle_many_planes(shape, B, b):
     assert st["exact"]
 
 
-@pytest.mark.parametrize("shape,B,b", TILE_CASES + ANY_CASES)
+@pytest.mark.parametrize("shape,B,seed,gen", [((2048, 512, 4, 4), 4, 123, 5), ((1024, 1024, 5, 6), 3, 77, 6)])
+def test_8bit_codes_where_the_scaled_maximum_exceeds_the_top_code(shape, B, seed, gen):
+    """With b = 8 the plane maximum scales to 255 plus a few ulp in about one plane in seven, and a
+    random term close to 1 then carries the sum to 256: the code must saturate at 255 (six resp. two
+    such elements in these inputs; the first shape runs the register kernel, the second the general one)."""
+    x = _relu_normal(shape, gen)
+    ref, dbg = oracle.compress(x.numpy(), B, 8, seed, threads=16, debug=True)
+    s = np.floor(dbg["t"].reshape(-1).astype(np.float64) + dbg["r"].reshape(-1).astype(np.float64) / 65536.0)
+    assert (s >= 256).sum() >= 2
+    packed = pkg.division_compress(x.to("cuda:0"), B, 8, seed)
+    torch.cuda.synchronize()
+    assert np.array_equal(packed.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("shape,B,b", TILE_CASES + ANY_CASES + B8_CASES)
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_matches_oracle_small(shape, B, b, dtype):
     x = _relu_normal(shape, 1000 + sum(shape) + B + b, dtype)

@@ -72,7 +72,7 @@ def test_worked_example_two_blocks_distinct_means():
 
 # ---------------------------------------------------------------- I1..I6 invariants
 
-@pytest.mark.parametrize("b", [2, 4])
+@pytest.mark.parametrize("b", [2, 4, 8])
 def test_B1_lfc_is_x_and_roundtrip_exact(b):
     x = _rng(1).standard_normal((2, 3, 5, 7)).astype(np.float32)
     p, xh = _roundtrip(x, 1, b, 3)
@@ -97,7 +97,7 @@ def test_block_constant_gives_zero_hfc(shape, B):
     assert np.array_equal(oracle.decompress(p, shape, B, 2), x)
 
 
-@pytest.mark.parametrize("b", [2, 4])
+@pytest.mark.parametrize("b", [2, 4, 8])
 @pytest.mark.parametrize("shape,B", [((2, 4, 16, 16), 8), ((1, 5, 7, 7), 8), ((2, 3, 14, 14), 8), ((1, 2, 55, 55), 4)])
 def test_reconstruction_error_bounded_by_one_step(shape, B, b):
     x = np.maximum(_rng(3).standard_normal(shape), 0).astype(np.float32)
@@ -112,7 +112,7 @@ def test_reconstruction_error_bounded_by_one_step(shape, B, b):
 
 def test_min_gets_code0_max_gets_top_code_for_every_seed():
     rng = _rng(4)
-    for b in (2, 4):
+    for b in (2, 4, 8):
         L = (1 << b) - 1
         x = rng.standard_normal((4, 6, 9, 9)).astype(np.float32) * rng.uniform(1e-3, 1e3, (4, 6, 1, 1)).astype(np.float32)
         for seed in range(40):
@@ -126,7 +126,7 @@ def test_min_gets_code0_max_gets_top_code_for_every_seed():
 def test_scale_top_is_exact_for_many_ranges():
     # the one-ulp bump of the scale guarantees fl(range*inv) >= L: max -> code L.
     rng = _rng(5)
-    for b in (2, 4):
+    for b in (2, 4, 8):
         L = (1 << b) - 1
         for _ in range(300):
             hi = np.float32(rng.uniform(0.5, 2.0) * 2.0 ** rng.integers(-20, 20))
@@ -237,7 +237,7 @@ def test_decompress_is_dequant_plus_upsampled_lfc():
 # ---------------------------------------------------------------- X2 exact-rational brute force
 
 @pytest.mark.parametrize("H,W,B,b", [(2, 2, 2, 2), (3, 5, 2, 2), (5, 7, 3, 4), (4, 4, 1, 2), (5, 7, 8, 2),
-                                     (6, 6, 4, 4), (7, 7, 8, 4), (3, 9, 4, 2)])
+                                     (6, 6, 4, 4), (7, 7, 8, 4), (3, 9, 4, 2), (5, 6, 4, 8), (7, 7, 8, 8)])
 def test_brute_force_exact_rational(H, W, B, b):
     rng = _rng(100 + H * 31 + W * 7 + B)
     N, C = 2, 2
@@ -296,7 +296,8 @@ def test_layout_closed_form_and_config_sizes():
         P, WPP = N * C, -(-(H * W * b) // 32)
         return a16(a16(a16(4 * P * WPP) + 8 * P) + es * P * (-(-H // B)) * (-(-W // B)))
     cases = [(2, 16, 32, 32, 8, 2, 4), (64, 256, 56, 56, 8, 2, 4), (64, 2048, 7, 7, 8, 2, 4), (3, 5, 55, 55, 4, 4, 4),
-             (256, 256, 56, 56, 8, 2, 2), (1, 1, 1, 1, 1, 2, 4), (7, 3, 13, 29, 5, 4, 2)]
+             (256, 256, 56, 56, 8, 2, 2), (1, 1, 1, 1, 1, 2, 4), (7, 3, 13, 29, 5, 4, 2),
+             (64, 256, 56, 56, 8, 8, 4), (5, 3, 7, 7, 8, 8, 2)]
     for N, C, H, W, B, b, es in cases:
         dt = oracle.BF16 if es == 2 else oracle.F32
         assert oracle.packed_bytes(N, C, H, W, B, b, dt) == closed(N, C, H, W, B, b, es)
@@ -305,7 +306,7 @@ def test_layout_closed_form_and_config_sizes():
     for hw, total in [(112, 3928), (56, 988), (28, 268), (14, 76), (7, 28)]:
         lay = oracle.packed_layout(16, 1, hw, hw, 8, 2)
         assert (lay["codes_bytes"] + lay["meta_bytes"] + lay["lfc_bytes"]) // 16 == total
-    for bad in [(0, 1, 4, 4, 2, 2), (1, 1, 4, 4, 0, 2), (1, 1, 4, 4, 2, 3), (1, 1, 4, 4, 2, 8)]:
+    for bad in [(0, 1, 4, 4, 2, 2), (1, 1, 4, 4, 0, 2), (1, 1, 4, 4, 2, 3), (1, 1, 4, 4, 2, 1), (1, 1, 4, 4, 2, 16)]:
         assert oracle.packed_bytes(*bad) == 0
 
 
