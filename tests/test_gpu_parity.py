@@ -66,6 +66,12 @@ B8_CASES = [
     ((6, 5, 10, 10), 8, 8),
 ]
 
+# 1-D maps (Appendix D): Minibatch x Channel x N is the H = 1 case
+ONE_D_CASES = [
+    ((4, 6, 1, 64), 8, 2), ((3, 5, 1, 197), 8, 2), ((2, 8, 1, 3136), 64, 2), ((7, 3, 1, 128), 16, 4),
+    ((5, 4, 1, 50), 64, 2), ((2, 64, 1, 1024), 8, 2), ((2, 3, 1, 2048), 4, 4), ((3, 2, 1, 12544), 8, 2),
+]
+
 # enough planes that a workgroup takes several chunks one after the other
 MANY_PLANE_CASES = [
     ((2048, 64, 14, 14), 8, 2),
@@ -107,7 +113,7 @@ def test_8bit_codes_where_the_scaled_maximum_exceeds_the_top_code(shape, B, seed
     assert np.array_equal(packed.cpu().numpy(), ref)
 
 
-@pytest.mark.parametrize("shape,B,b", TILE_CASES + ANY_CASES + B8_CASES)
+@pytest.mark.parametrize("shape,B,b", TILE_CASES + ANY_CASES + B8_CASES + ONE_D_CASES)
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_matches_oracle_small(shape, B, b, dtype):
     x = _relu_normal(shape, 1000 + sum(shape) + B + b, dtype)

@@ -213,6 +213,25 @@ def test_lfc_matches_library_avg_pool_and_upsampling(shape, B):
     assert np.array_equal(d["h"], x - up.numpy())
 
 
+@pytest.mark.parametrize("L,B", [(64, 8), (197, 8), (128, 16), (50, 64), (96, 12)])
+def test_1d_maps_are_the_H_equal_1_case(L, B):
+    # Appendix D, AveragePooling1D / UpSampling1D: a Minibatch x Channel x N map is the 2-D codec on
+    # Minibatch x Channel x 1 x N; checked against the library's 1-D pooling and nearest up-sampling
+    N, C = 3, 5
+    x = _rng(40 + L).standard_normal((N, C, 1, L)).astype(np.float32)
+    p, d = oracle.compress(x, B, 2, 3, debug=True)
+    lfc = oracle.split_packed(p, x.shape, B, 2)["lfc"].reshape(N, C, -(-L // B))
+    k = min(B, L)
+    ref = F.avg_pool1d(torch.from_numpy(x[:, :, 0, :]).double(), k, stride=k, ceil_mode=True,
+                       count_include_pad=False).float().numpy()
+    assert np.array_equal(lfc, ref)
+    if L % B == 0:
+        # the paper's floor(N/B) shape and the library's nearest interpolation
+        assert lfc.shape[-1] == L // B
+        up = F.interpolate(torch.from_numpy(lfc), size=L, mode="nearest").numpy()
+        assert np.array_equal(d["h"][:, :, 0, :], x[:, :, 0, :] - up)
+
+
 def test_map_smaller_than_block_is_one_window():
     # Sec. 4.1 footnote: N < B gives a 1x1 LFC equal to the plane mean
     x = _rng(9).standard_normal((3, 4, 7, 7)).astype(np.float32)
