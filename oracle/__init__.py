@@ -72,6 +72,10 @@ def lib() -> ctypes.CDLL:
         L.oracle_dropout_forward.argtypes = [vp, i64, ci, ctypes.c_float, u64, vp, vp]
         L.oracle_mask_backward.restype = ci
         L.oracle_mask_backward.argtypes = [vp, vp, i64, ci, vp]
+        L.oracle_maxpool_forward.restype = ci
+        L.oracle_maxpool_forward.argtypes = [vp, i64, i64, i64, i64, ci, ci, vp, vp]
+        L.oracle_maxpool_backward.restype = ci
+        L.oracle_maxpool_backward.argtypes = [vp, vp, i64, i64, i64, i64, ci, ci, vp]
         _lib = L
     return _lib
 
@@ -216,4 +220,28 @@ def mask_backward(mask: np.ndarray, grad_out: np.ndarray, dt: int = F32) -> np.n
     rc = lib().oracle_mask_backward(mask.ctypes.data, g.ctypes.data, g.size, dt, out.ctypes.data)
     if rc:
         raise ValueError("oracle_mask_backward failed")
+    return out
+
+
+def maxpool_forward(x: np.ndarray, k: int, dt: int = F32):
+    """x: (N, C, H, W).  Returns (y of shape (N, C, H//k, W//k), mask words over the input)."""
+    x = np.ascontiguousarray(x, dtype=_np_dtype(dt))
+    N, C, H, W = x.shape
+    y = np.empty((N, C, H // k, W // k), dtype=x.dtype)
+    mask = np.empty(mask_bytes(x.size) // 4, dtype=np.uint32)
+    rc = lib().oracle_maxpool_forward(x.ctypes.data, N, C, H, W, dt, k, y.ctypes.data, mask.ctypes.data)
+    if rc:
+        raise ValueError("oracle_maxpool_forward failed")
+    return y, mask
+
+
+def maxpool_backward(mask: np.ndarray, grad_out: np.ndarray, shape, k: int, dt: int = F32) -> np.ndarray:
+    N, C, H, W = shape
+    g = np.ascontiguousarray(grad_out, dtype=_np_dtype(dt))
+    assert g.shape == (N, C, H // k, W // k)
+    mask = np.ascontiguousarray(mask, dtype=np.uint32)
+    out = np.empty(shape, dtype=g.dtype)
+    rc = lib().oracle_maxpool_backward(mask.ctypes.data, g.ctypes.data, N, C, H, W, dt, k, out.ctypes.data)
+    if rc:
+        raise ValueError("oracle_maxpool_backward failed")
     return out

@@ -452,3 +452,70 @@ int oracle_mask_backward(const uint32_t *mask, const void *grad_out, int64_t n, 
     }
     return 0;
 }
+
+/* ====================================================================== *
+ * Max-Pooling layer with kernel size = stride = k (the paper's appendix on
+ * operator compression, Algorithm "Max-Pooling layer"):
+ *
+ *   forward:   H_l = Max-Pooling(H_{l-1}, k); V marks, for every k x k window,
+ *              where its maximum sits in H_{l-1}; V is packed one bit per
+ *              INPUT element and cached.
+ *   backward:  grad' = 1_{k x k} (x) grad_out  (every output gradient repeated
+ *              over its window), grad_in = V (.) grad'.
+ *
+ * Readings: output size floor(H/k) x floor(W/k); rows and columns past the last
+ * whole window belong to no window (V = 0, zero gradient).  Exactly one element
+ * per window is marked: the first maximum in row-major order inside the window
+ * (a later element wins only if it compares greater).  Where V = 0 the gradient
+ * is +0.  Mask layout: bit i%32 of word i/32 over the flat NCHW input index.
+ * ====================================================================== */
+
+int oracle_maxpool_forward(const void *x, int64_t N, int64_t C, int64_t H, int64_t W, int dt, int k,
+                           void *y, uint32_t *mask)
+{
+    if (!x || !y || !mask || N <= 0 || C <= 0 || H <= 0 || W <= 0 || k < 1 ||
+        (dt != ORACLE_F32 && dt != ORACLE_BF16))
+        return 1;
+    const int64_t OH = H / k, OW = W / k;
+    memset(mask, 0, oracle_mask_bytes(N * C * H * W));
+    for (int64_t p = 0; p < N * C; ++p)
+        for (int64_t oi = 0; oi < OH; ++oi)
+            for (int64_t oj = 0; oj < OW; ++oj) {
+                int64_t best = (p * H + oi * k) * W + oj * k;
+                float bv = load_elem(x, dt, (size_t)best);
+                for (int64_t r = 0; r < k; ++r)
+                    for (int64_t c = 0; c < k; ++c) {
+                        int64_t idx = (p * H + oi * k + r) * W + oj * k + c;
+                        float v = load_elem(x, dt, (size_t)idx);
+                        if (v > bv) { bv = v; best = idx; }
+                    }
+                mask[best / 32] |= 1u << (best % 32);
+                size_t o = (size_t)((p * OH + oi) * OW + oj);
+                if (dt == ORACLE_BF16) ((uint16_t *)y)[o] = ((const uint16_t *)x)[best];
+                else memcpy((char *)y + 4 * o, (const char *)x + 4 * best, 4);
+            }
+    return 0;
+}
+
+int oracle_maxpool_backward(const uint32_t *mask, const void *grad_out, int64_t N, int64_t C, int64_t H, int64_t W,
+                            int dt, int k, void *grad_in)
+{
+    if (!mask || !grad_out || !grad_in || N <= 0 || C <= 0 || H <= 0 || W <= 0 || k < 1 ||
+        (dt != ORACLE_F32 && dt != ORACLE_BF16))
+        return 1;
+    const int64_t OH = H / k, OW = W / k;
+    for (int64_t p = 0; p < N * C; ++p)
+        for (int64_t r = 0; r < H; ++r)
+            for (int64_t c = 0; c < W; ++c) {
+                int64_t idx = (p * H + r) * W + c;
+                int bit = (int)((mask[idx / 32] >> (idx % 32)) & 1u);
+                if (bit && r / k < OH && c / k < OW) {
+                    size_t o = (size_t)((p * OH + r / k) * OW + c / k);
+                    if (dt == ORACLE_BF16) ((uint16_t *)grad_in)[idx] = ((const uint16_t *)grad_out)[o];
+                    else memcpy((char *)grad_in + 4 * idx, (const char *)grad_out + 4 * o, 4);
+                } else {
+                    store_elem(grad_in, dt, (size_t)idx, 0.0f);
+                }
+            }
+    return 0;
+}

@@ -128,3 +128,72 @@ def test_dropout_stream_differs_from_the_codec_stream_of_the_same_seed():
     _, m = oracle.dropout_forward(x, 0.5, seed)
     codec_bits = np.array([oracle.rand16(seed, 0, i) >= 32768 for i in range(n)])
     assert abs((_bits(m, n) == codec_bits).mean() - 0.5) < 0.05
+
+
+# ---------------------------------------------------------------- Max-Pooling layer (kernel = stride = k)
+
+import torch
+import torch.nn.functional as F
+
+MP_CASES = [((2, 3, 8, 8), 2), ((1, 2, 9, 7), 2), ((2, 2, 12, 9), 3), ((1, 1, 5, 5), 1), ((3, 1, 4, 6), 4),
+            ((1, 2, 112, 112), 2), ((2, 1, 7, 7), 7), ((1, 1, 10, 13), 5)]
+
+
+@pytest.mark.parametrize("shape,k", MP_CASES)
+def test_maxpool_forward_is_the_library_pooling_with_its_argmax(shape, k):
+    rng = np.random.default_rng(sum(shape) + k)
+    x = rng.standard_normal(shape).astype(np.float32)         # no ties
+    N, C, H, W = shape
+    y, mask = oracle.maxpool_forward(x, k)
+    ty, tidx = F.max_pool2d(torch.from_numpy(x), k, stride=k, return_indices=True)
+    assert np.array_equal(y, ty.numpy())
+    bits = _bits(mask, x.size).reshape(N * C, H * W)
+    ref = np.zeros_like(bits)
+    flat = tidx.numpy().reshape(N * C, -1)                      # indices inside each plane
+    for p in range(N * C):
+        ref[p, flat[p]] = True
+    assert np.array_equal(bits, ref)
+    # footnote of the algorithm: one location per window; rows / columns past the last window: none
+    assert bits.sum() == N * C * (H // k) * (W // k)
+    b4 = bits.reshape(N, C, H, W)
+    assert not b4[:, :, (H // k) * k:, :].any() and not b4[:, :, :, (W // k) * k:].any()
+
+
+@pytest.mark.parametrize("shape,k", MP_CASES)
+def test_maxpool_backward_is_the_library_gradient(shape, k):
+    rng = np.random.default_rng(17 * sum(shape) + k)
+    x = rng.standard_normal(shape).astype(np.float32)
+    N, C, H, W = shape
+    g = rng.standard_normal((N, C, H // k, W // k)).astype(np.float32)
+    _, mask = oracle.maxpool_forward(x, k)
+    gin = oracle.maxpool_backward(mask, g, shape, k)
+    tx = torch.from_numpy(x).requires_grad_(True)
+    F.max_pool2d(tx, k, stride=k).backward(torch.from_numpy(g))
+    assert np.array_equal(gin, tx.grad.numpy())
+    # the listing's formula: V (.) (1_{k x k} (x) grad_out)
+    up = np.repeat(np.repeat(g, k, 2), k, 3)
+    full = np.zeros(shape, dtype=np.float32)
+    full[:, :, :up.shape[2], :up.shape[3]] = up
+    assert np.array_equal(gin, np.where(_bits(mask, x.size).reshape(shape), full, np.float32(0.0)))
+
+
+def test_maxpool_ties_take_the_first_location_in_row_major_order():
+    x = np.zeros((1, 1, 4, 4), dtype=np.float32)
+    x[0, 0, 1, 1] = 5.0
+    x[0, 0, 0, 3] = 2.0
+    x[0, 0, 1, 2] = 2.0                      # ties with (0,3) in the top-right window; (0,3) comes first
+    y, mask = oracle.maxpool_forward(x, 2)
+    bits = _bits(mask, 16).reshape(4, 4)
+    want = np.zeros((4, 4), dtype=bool)
+    want[1, 1] = want[0, 3] = want[2, 0] = want[2, 2] = True       # all-zero windows mark their first element
+    assert np.array_equal(bits, want)
+    assert np.array_equal(y[0, 0], [[5.0, 2.0], [0.0, 0.0]])
+
+
+def test_maxpool_bf16_passes_values_bit_for_bit():
+    rng = np.random.default_rng(23)
+    xf = rng.standard_normal((2, 3, 6, 10)).astype(np.float32)
+    xb = oracle.bf16_bits(xf)
+    y, mask = oracle.maxpool_forward(xb, 2, oracle.BF16)
+    ty = F.max_pool2d(torch.from_numpy(oracle.bf16_to_f32(xb)), 2)
+    assert np.array_equal(oracle.bf16_to_f32(y), ty.numpy())
