@@ -147,13 +147,21 @@ def masks(args, torch, pkg, dev) -> int:
         "mask_backward": (lambda i: pkg.division_mask_backward(ms[i % nsets], xs[i % nsets], out=ys[i % nsets]), 2 * n * es + n / 8),
         "device_copy": (lambda i: ys[i % nsets].copy_(xs[i % nsets]), 2 * n * es),
     }
+    if x.dim() == 4 and x.shape[2] % 2 == 0 and x.shape[3] % 2 == 0:
+        # Max-Pooling layer, k = 2: forward reads the map and writes a quarter-size map and the mask;
+        # backward reads the quarter-size gradient and the mask and writes a whole map
+        pooled = [pkg.division_maxpool_forward(t, 2) for t in xs]
+        ops["maxpool_forward_k2"] = (lambda i: pkg.division_maxpool_forward(xs[i % nsets], 2), n * es + n * es / 4 + n / 8)
+        ops["maxpool_backward_k2"] = (lambda i: pkg.division_maxpool_backward(pooled[i % nsets][1], pooled[i % nsets][0],
+                                                                             tuple(x.shape), 2), n * es + n * es / 4 + n / 8)
     res = {}
     for name, (fn, nbytes) in ops.items():
         med, mn = timed_us(fn)
         res[name] = {"us_median": round(med, 2), "us_min": round(mn, 2), "algorithmic_bytes": int(nbytes),
                      "GB_s": round(nbytes / med / 1e3, 1), "pct_hbm_peak": round(100 * nbytes / med / 1e3 / HBM_PEAK_GBS, 1)}
-    for name in ("relu_forward", "dropout_forward", "mask_backward"):
-        res[name]["vs_copy"] = round(res[name]["GB_s"] / res["device_copy"]["GB_s"], 3)
+    for name in res:
+        if name != "device_copy":
+            res[name]["vs_copy"] = round(res[name]["GB_s"] / res["device_copy"]["GB_s"], 3)
     print(json.dumps({"metric": "1-bit mask operators, GB/s of algorithmic bytes (median of %d launches)" % reps,
                       "unit": "GB/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16" if es == 2 else "f32",
                       "config": {"workload": "one map %s of %s" % ("x".join(map(str, x.shape)), WORKLOAD_NAMES[args.config])},

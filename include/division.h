@@ -179,6 +179,31 @@ int division_mask_backward(const void *mask, size_t mask_bytes, const void *grad
                            division_dtype dt, void *grad_in, void *hip_stream);
 
 /*
+ * Max-Pooling layer with kernel size = stride = k (appendix on operator
+ * compression, Algorithm "Max-Pooling layer"): the forward pass returns the
+ * pooled map and caches V, which marks where each window's maximum sits in the
+ * input, one bit per INPUT element (layout as above, flat NCHW index); the
+ * backward pass is grad_in = V (.) (1_{k x k} (x) grad_out).
+ *
+ *   x, grad_in   device, N*C*H*W elements of type dt.
+ *   y, grad_out  device, N*C*floor(H/k)*floor(W/k) elements; rows and columns
+ *                past the last whole window belong to no window (V = 0 there,
+ *                zero gradient).  No buffer may overlap another.
+ *   mask         device, 4-byte aligned, division_mask_bytes(N*C*H*W) bytes.
+ * Exactly one element per window is marked: the first maximum in row-major
+ * order inside the window.  Values pass through bit for bit; where V = 0 the
+ * gradient is +0.  k*W above 65536, N*C or H*W above 2^31-1 or N*C*H*W above
+ * 2^40 give DIVISION_ERANGE.
+ */
+int division_maxpool_forward(const void *x, int64_t N, int64_t C, int64_t H, int64_t W,
+                             division_dtype dt, int k, void *y, void *mask, size_t mask_capacity,
+                             void *hip_stream);
+
+int division_maxpool_backward(const void *mask, size_t mask_bytes, const void *grad_out,
+                              int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt, int k,
+                              void *grad_in, void *hip_stream);
+
+/*
  * Profiling aid (host-only): writes the name of the kernel template instance
  * that division_compress (direction 0, data = x) or division_decompress
  * (direction 1, data = xhat) would launch for these arguments, as it appears

@@ -8,3 +8,4 @@ from .binding import (DIVISION_BF16, DIVISION_F32, DivisionError, division_compr
 from .autograd import division_saved_tensors  # noqa: F401,E402
 from .binding import (division_dropout_forward, division_mask_backward, division_mask_bytes,  # noqa: F401,E402
                       division_relu_forward)
+from .binding import division_maxpool_backward, division_maxpool_forward  # noqa: F401,E402

@@ -59,6 +59,10 @@ def lib() -> ctypes.CDLL:
         L.division_dropout_forward.argtypes = [vp, i64, ci, ctypes.c_float, u64, vp, vp, sz, vp]
         L.division_mask_backward.restype = ci
         L.division_mask_backward.argtypes = [vp, sz, vp, i64, ci, vp, vp]
+        L.division_maxpool_forward.restype = ci
+        L.division_maxpool_forward.argtypes = [vp, i64, i64, i64, i64, ci, ci, vp, vp, sz, vp]
+        L.division_maxpool_backward.restype = ci
+        L.division_maxpool_backward.argtypes = [vp, sz, vp, i64, i64, i64, i64, ci, ci, vp, vp]
         L.division_kernel_name.restype = ci
         L.division_kernel_name.argtypes = [ci, vp, i64, i64, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
         _lib = L
@@ -237,4 +241,33 @@ def division_mask_backward(mask: torch.Tensor, grad_out: torch.Tensor, out: torc
                                       grad_out.numel(), _dt(grad_out.dtype), out.data_ptr(), _stream(stream))
     if rc:
         raise DivisionError(rc, "division_mask_backward")
+    return out
+
+
+def division_maxpool_forward(x: torch.Tensor, k: int, stream=None):
+    """x: contiguous NCHW device tensor.  Returns (y of shape N x C x H//k x W//k, location mask over x)."""
+    if x.dim() != 4:
+        raise ValueError("x must be 4-d")
+    _flat_ok(x, "x")
+    N, C, H, W = x.shape
+    y = torch.empty((N, C, H // k, W // k), dtype=x.dtype, device=x.device)
+    mask = torch.empty(division_mask_bytes(x.numel()) // 4, dtype=torch.int32, device=x.device)
+    rc = lib().division_maxpool_forward(x.data_ptr(), N, C, H, W, _dt(x.dtype), k, y.data_ptr(), mask.data_ptr(),
+                                        mask.numel() * 4, _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_maxpool_forward")
+    return y, mask
+
+
+def division_maxpool_backward(mask: torch.Tensor, grad_out: torch.Tensor, shape, k: int, stream=None):
+    """grad_in of shape `shape` (the pooled layer's input) from the location mask and grad_out."""
+    _flat_ok(grad_out, "grad_out")
+    N, C, H, W = shape
+    if tuple(grad_out.shape) != (N, C, H // k, W // k):
+        raise ValueError("grad_out has the wrong shape")
+    out = torch.empty(tuple(shape), dtype=grad_out.dtype, device=grad_out.device)
+    rc = lib().division_maxpool_backward(mask.data_ptr(), mask.numel() * mask.element_size(), grad_out.data_ptr(),
+                                         N, C, H, W, _dt(grad_out.dtype), k, out.data_ptr(), _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_maxpool_backward")
     return out

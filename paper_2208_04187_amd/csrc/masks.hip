@@ -231,6 +231,111 @@ int launch(int mode, const void* in, int64_t n, division_dtype dt, void* out, vo
     return hipGetLastError() == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
 }
 
+// ------------------------------------------------------------------ Max-Pooling layer, kernel = stride = k
+
+struct PoolArgs {
+    const void* in;        // x (forward) or grad_out (backward)
+    void* out;             // y or grad_in
+    uint32_t* mask;
+    uint32_t P, H, W, HW, OH, OW, k;
+    uint32_t band;         // output rows a workgroup handles
+    uint32_t bands;        // bands per plane
+};
+
+__global__ void __launch_bounds__(kThreads) zero_words(uint32_t* p, uint64_t n) {
+    for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kThreads) p[i] = 0u;
+}
+
+template <typename T> __device__ __forceinline__ float as_float(T v);
+template <> __device__ __forceinline__ float as_float<float>(float v) { return v; }
+template <> __device__ __forceinline__ float as_float<uint16_t>(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+
+// Forward: a workgroup takes a band of output rows of one plane.  Every thread scans whole
+// windows (first maximum in row-major order wins), writes the maxima and sets the location bits
+// in an LDS image of the band's slice of the mask; the slice then leaves as whole words, the two
+// words it may share with neighbouring slices by atomic OR (the mask is cleared beforehand).
+template <typename T>
+__global__ void __launch_bounds__(kThreads) maxpool_forward_kernel(PoolArgs a) {
+    extern __shared__ uint32_t words[];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t p = blockIdx.x / a.bands;
+    const uint32_t oi0 = (blockIdx.x - p * a.bands) * a.band;
+    const uint32_t oi1 = min(a.OH, oi0 + a.band);
+    const uint64_t start = (uint64_t)p * a.HW + (uint64_t)oi0 * a.k * a.W;      // first bit of the slice
+    const uint64_t end = (uint64_t)p * a.HW + (uint64_t)oi1 * a.k * a.W;        // one past its last bit
+    const uint64_t w0 = start >> 5;
+    const uint32_t nwords = (uint32_t)(((end - 1) >> 5) - w0) + 1u;
+    for (uint32_t w = tid; w < nwords; w += kThreads) words[w] = 0u;
+    __syncthreads();
+
+    const T* xp = static_cast<const T*>(a.in) + (size_t)p * a.HW;
+    T* yp = static_cast<T*>(a.out) + (size_t)p * a.OH * a.OW;
+    const uint32_t nout = (oi1 - oi0) * a.OW;
+    for (uint32_t o = tid; o < nout; o += kThreads) {
+        const uint32_t r = o / a.OW;
+        const uint32_t oj = o - r * a.OW;
+        const uint32_t oi = oi0 + r;
+        const uint32_t base = oi * a.k * a.W + oj * a.k;
+        uint32_t best = base;
+        T bt = xp[base];
+        float bv = as_float<T>(bt);
+        for (uint32_t wr = 0; wr < a.k; ++wr)
+            for (uint32_t wc = 0; wc < a.k; ++wc) {
+                const uint32_t idx = base + wr * a.W + wc;
+                const T t = xp[idx];
+                const float v = as_float<T>(t);
+                if (v > bv) { bv = v; bt = t; best = idx; }
+            }
+        yp[oi * a.OW + oj] = bt;
+        const uint32_t bit = (uint32_t)((uint64_t)p * a.HW + best - (w0 << 5));
+        atomicOr(&words[bit >> 5], 1u << (bit & 31u));
+    }
+    __syncthreads();
+    for (uint32_t w = tid; w < nwords; w += kThreads) {
+        const uint32_t v = words[w];
+        if (w == 0 || w == nwords - 1) { if (v) atomicOr(&a.mask[w0 + w], v); }
+        else a.mask[w0 + w] = v;
+    }
+}
+
+// Backward: grad_in = V (.) (1_{k x k} (x) grad_out), one input element per thread and step.
+template <typename T>
+__global__ void __launch_bounds__(kThreads) maxpool_backward_kernel(PoolArgs a) {
+    const uint32_t p = blockIdx.y;
+    const T* gp = static_cast<const T*>(a.in) + (size_t)p * a.OH * a.OW;
+    T* op = static_cast<T*>(a.out) + (size_t)p * a.HW;
+    const uint64_t bit0 = (uint64_t)p * a.HW;
+    for (uint32_t i = blockIdx.x * kThreads + threadIdx.x; i < a.HW; i += gridDim.x * kThreads) {
+        const uint64_t bit = bit0 + i;
+        const bool set = (a.mask[bit >> 5] >> (uint32_t)(bit & 31u)) & 1u;
+        const uint32_t r = i / a.W;
+        const uint32_t c = i - r * a.W;
+        const uint32_t oi = r / a.k, oj = c / a.k;
+        T v = 0;
+        if (set && oi < a.OH && oj < a.OW) v = gp[oi * a.OW + oj];
+        op[i] = v;
+    }
+}
+
+int pool_args(bool forward, const void* in, void* out, const void* mask, int64_t N, int64_t C, int64_t H, int64_t W,
+              division_dtype dt, int k, size_t mask_bytes, PoolArgs* a) {
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || k < 1 || (dt != DIVISION_F32 && dt != DIVISION_BF16)) return DIVISION_EINVAL;
+    // the pooled-size buffer (y / grad_out) may be null when there is no whole window
+    const bool no_window = H / k == 0 || W / k == 0;
+    if (!mask || (!in && !(no_window && !forward)) || (!out && !(no_window && forward))) return DIVISION_EINVAL;
+    const uint64_t P = (uint64_t)N * (uint64_t)C, HW = (uint64_t)H * (uint64_t)W;
+    if (N > 0x7fffffff || C > 0x7fffffff || H > 0x7fffffff || W > 0x7fffffff || P > 0x7fffffffull || HW > 0x7fffffffull ||
+        P * HW > (1ull << 40) || k > 0x7fff)
+        return DIVISION_ERANGE;
+    if (mask_bytes < division_mask_bytes((int64_t)(P * HW))) return DIVISION_ESIZE;
+    const size_t es = dt == DIVISION_BF16 ? 2 : 4;
+    if (((uintptr_t)in % es) != 0 || ((uintptr_t)out % es) != 0 || ((uintptr_t)mask % 4) != 0) return DIVISION_EALIGN;
+    a->in = in; a->out = out; a->mask = static_cast<uint32_t*>(const_cast<void*>(mask));
+    a->P = (uint32_t)P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)HW;
+    a->OH = (uint32_t)(H / k); a->OW = (uint32_t)(W / k); a->k = (uint32_t)k;
+    return DIVISION_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -250,6 +355,59 @@ int division_dropout_forward(const void* x, int64_t n, division_dtype dt, float 
 int division_mask_backward(const void* mask, size_t mask_bytes, const void* grad_out, int64_t n, division_dtype dt,
                            void* grad_in, void* hip_stream) {
     return launch(2, grad_out, n, dt, grad_in, const_cast<void*>(mask), mask_bytes, 0.0f, 0, hip_stream);
+}
+
+int division_maxpool_forward(const void* x, int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt, int k,
+                             void* y, void* mask, size_t mask_capacity, void* hip_stream) {
+    PoolArgs a{};
+    const int rc = pool_args(true, x, y, mask, N, C, H, W, dt, k, mask_capacity, &a);
+    if (rc != DIVISION_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const uint64_t nwords = ((uint64_t)a.P * a.HW + 31) / 32;
+    const uint32_t zgrid = (uint32_t)((nwords + kThreads * 8ull - 1) / (kThreads * 8ull));
+    hipLaunchKernelGGL(zero_words, dim3(zgrid < 1 ? 1 : zgrid), dim3(kThreads), 0, st, a.mask, nwords);
+    if (hipGetLastError() != hipSuccess) return DIVISION_EHIP;
+    if (a.OH == 0 || a.OW == 0) return DIVISION_OK;          // no whole window: empty output, all-zero mask
+    // a band's slice of the mask lives in LDS: at most 64 Ki bits (+ the two edge words)
+    const uint64_t row_bits = (uint64_t)a.k * a.W;
+    if (row_bits > 65536) return DIVISION_ERANGE;
+    uint32_t band = (uint32_t)(65536 / row_bits);
+    if (band > a.OH) band = a.OH;
+    // small planes: fewer rows per band than fit, so that the launch still has enough workgroups
+    while (band > 1 && (uint64_t)a.P * ((a.OH + band - 1) / band) < 2048) band = (band + 1) / 2;
+    a.band = band;
+    a.bands = (a.OH + band - 1) / band;
+    const uint64_t grid = (uint64_t)a.P * a.bands;
+    if (grid > 0x7fffffffull) return DIVISION_ERANGE;
+    const size_t lds = 4 * ((size_t)band * row_bits / 32 + 2);
+    void (*kern)(PoolArgs) = dt == DIVISION_F32 ? maxpool_forward_kernel<float> : maxpool_forward_kernel<uint16_t>;
+    hipLaunchKernelGGL(kern, dim3((uint32_t)grid), dim3(kThreads), lds, st, a);
+    return hipGetLastError() == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
+}
+
+int division_maxpool_backward(const void* mask, size_t mask_bytes, const void* grad_out, int64_t N, int64_t C,
+                              int64_t H, int64_t W, division_dtype dt, int k, void* grad_in, void* hip_stream) {
+    PoolArgs a{};
+    const int rc = pool_args(false, grad_out, grad_in, mask, N, C, H, W, dt, k, mask_bytes, &a);
+    if (rc != DIVISION_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    void (*kern)(PoolArgs) = dt == DIVISION_F32 ? maxpool_backward_kernel<float> : maxpool_backward_kernel<uint16_t>;
+    uint32_t gx = (a.HW + kThreads * 4u - 1) / (kThreads * 4u);
+    if (gx > 4096) gx = 4096;
+    // grid.y takes a slice of planes per launch; a multiple of 32 planes, so that every slice's
+    // first mask bit starts a word
+    constexpr uint32_t kSlice = 65504;
+    const size_t es = dt == DIVISION_BF16 ? 2 : 4;
+    for (uint32_t p0 = 0; p0 < a.P; p0 += kSlice) {
+        PoolArgs b = a;
+        const uint32_t np = a.P - p0 < kSlice ? a.P - p0 : kSlice;
+        b.in = static_cast<const char*>(a.in) + (size_t)p0 * a.OH * a.OW * es;
+        b.out = static_cast<char*>(a.out) + (size_t)p0 * a.HW * es;
+        b.mask = a.mask + ((uint64_t)p0 * a.HW) / 32;
+        hipLaunchKernelGGL(kern, dim3(gx, np), dim3(kThreads), 0, st, b);
+        if (hipGetLastError() != hipSuccess) return DIVISION_EHIP;
+    }
+    return DIVISION_OK;
 }
 
 }  // extern "C"

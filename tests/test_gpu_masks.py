@@ -94,3 +94,32 @@ def test_mask_errors_and_empty_input():
     assert e.value.code == 2
     y, m = pkg.division_relu_forward(torch.empty(0, device="cuda:0"))
     assert y.numel() == 0 and m.numel() == 0
+
+
+# ---------------------------------------------------------------- Max-Pooling layer
+
+MP_CASES = [((2, 3, 8, 8), 2), ((1, 2, 9, 7), 2), ((2, 2, 12, 9), 3), ((1, 1, 5, 5), 1), ((3, 1, 4, 6), 4),
+            ((2, 5, 112, 112), 2), ((2, 1, 7, 7), 7), ((1, 1, 10, 13), 5), ((70, 33, 14, 14), 2),
+            ((1, 1, 3, 3), 4), ((1, 2, 600, 300), 2), ((2, 3, 56, 56), 3)]
+
+
+@pytest.mark.parametrize("shape,k", MP_CASES)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_maxpool_matches_oracle(shape, k, dtype):
+    g = torch.Generator().manual_seed(sum(shape) + k)
+    x = torch.randn(shape, generator=g)
+    x[..., ::3] = x[..., ::3].round()                 # plenty of ties, also across windows
+    x = x.to(dtype)
+    N, C, H, W = shape
+    go = torch.randn((N, C, H // k, W // k), generator=g).to(dtype)
+    xh, dt = _host(x)
+    gh, _ = _host(go)
+    y_ref, m_ref = oracle.maxpool_forward(xh, k, dt)
+    y, m = pkg.division_maxpool_forward(x.to("cuda:0"), k)
+    torch.cuda.synchronize()
+    assert np.array_equal(m.cpu().numpy().view(np.uint32), m_ref)
+    if y_ref.size:
+        assert _same_bits(y, y_ref)
+    gin = pkg.division_maxpool_backward(m, go.to("cuda:0"), shape, k)
+    torch.cuda.synchronize()
+    assert _same_bits(gin, oracle.maxpool_backward(m_ref, gh, shape, k, dt))
