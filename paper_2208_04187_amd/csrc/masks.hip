@@ -254,7 +254,7 @@ template <> __device__ __forceinline__ float as_float<uint16_t>(uint16_t v) { re
 // windows (first maximum in row-major order wins), writes the maxima and sets the location bits
 // in an LDS image of the band's slice of the mask; the slice then leaves as whole words, the two
 // words it may share with neighbouring slices by atomic OR (the mask is cleared beforehand).
-template <typename T>
+template <typename T, bool K2>
 __global__ void __launch_bounds__(kThreads) maxpool_forward_kernel(PoolArgs a) {
     extern __shared__ uint32_t words[];
     const uint32_t tid = threadIdx.x;
@@ -277,15 +277,28 @@ __global__ void __launch_bounds__(kThreads) maxpool_forward_kernel(PoolArgs a) {
         const uint32_t oi = oi0 + r;
         const uint32_t base = oi * a.k * a.W + oj * a.k;
         uint32_t best = base;
-        T bt = xp[base];
-        float bv = as_float<T>(bt);
-        for (uint32_t wr = 0; wr < a.k; ++wr)
-            for (uint32_t wc = 0; wc < a.k; ++wc) {
-                const uint32_t idx = base + wr * a.W + wc;
-                const T t = xp[idx];
-                const float v = as_float<T>(t);
-                if (v > bv) { bv = v; bt = t; best = idx; }
-            }
+        T bt;
+        if (K2) {
+            // 2 x 2 window, rows of two adjacent elements each in one load (W even, x aligned to two elements)
+            struct alignas(2 * sizeof(T)) Pair { T a, b; };
+            const Pair r0 = *reinterpret_cast<const Pair*>(xp + base);
+            const Pair r1 = *reinterpret_cast<const Pair*>(xp + base + a.W);
+            bt = r0.a;
+            float bv = as_float<T>(bt);
+            if (as_float<T>(r0.b) > bv) { bv = as_float<T>(r0.b); bt = r0.b; best = base + 1; }
+            if (as_float<T>(r1.a) > bv) { bv = as_float<T>(r1.a); bt = r1.a; best = base + a.W; }
+            if (as_float<T>(r1.b) > bv) { bv = as_float<T>(r1.b); bt = r1.b; best = base + a.W + 1; }
+        } else {
+            bt = xp[base];
+            float bv = as_float<T>(bt);
+            for (uint32_t wr = 0; wr < a.k; ++wr)
+                for (uint32_t wc = 0; wc < a.k; ++wc) {
+                    const uint32_t idx = base + wr * a.W + wc;
+                    const T t = xp[idx];
+                    const float v = as_float<T>(t);
+                    if (v > bv) { bv = v; bt = t; best = idx; }
+                }
+        }
         yp[oi * a.OW + oj] = bt;
         const uint32_t bit = (uint32_t)((uint64_t)p * a.HW + best - (w0 << 5));
         atomicOr(&words[bit >> 5], 1u << (bit & 31u));
@@ -298,22 +311,39 @@ __global__ void __launch_bounds__(kThreads) maxpool_forward_kernel(PoolArgs a) {
     }
 }
 
-// Backward: grad_in = V (.) (1_{k x k} (x) grad_out), one input element per thread and step.
-template <typename T>
+// Backward: grad_in = V (.) (1_{k x k} (x) grad_out).  VEC = 4: a thread takes four consecutive
+// elements of one row per step (W % 4 == 0, grad_in 16-byte resp. 8-byte aligned): one 16-byte
+// store, one mask word read.  VEC = 1: element by element.
+template <typename T, int VEC>
 __global__ void __launch_bounds__(kThreads) maxpool_backward_kernel(PoolArgs a) {
     const uint32_t p = blockIdx.y;
     const T* gp = static_cast<const T*>(a.in) + (size_t)p * a.OH * a.OW;
     T* op = static_cast<T*>(a.out) + (size_t)p * a.HW;
     const uint64_t bit0 = (uint64_t)p * a.HW;
-    for (uint32_t i = blockIdx.x * kThreads + threadIdx.x; i < a.HW; i += gridDim.x * kThreads) {
+    const uint32_t nv = a.HW / VEC;
+    for (uint32_t vi = blockIdx.x * kThreads + threadIdx.x; vi < nv; vi += gridDim.x * kThreads) {
+        const uint32_t i = vi * VEC;
         const uint64_t bit = bit0 + i;
-        const bool set = (a.mask[bit >> 5] >> (uint32_t)(bit & 31u)) & 1u;
+        // HW % 4 == 0 when VEC == 4, so the four bits never straddle a word
+        const uint32_t bits = (a.mask[bit >> 5] >> (uint32_t)(bit & 31u)) & ((1u << VEC) - 1u);
         const uint32_t r = i / a.W;
         const uint32_t c = i - r * a.W;
-        const uint32_t oi = r / a.k, oj = c / a.k;
-        T v = 0;
-        if (set && oi < a.OH && oj < a.OW) v = gp[oi * a.OW + oj];
-        op[i] = v;
+        const uint32_t oi = r / a.k;
+        const T* grow = gp + oi * a.OW;
+        T v[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const uint32_t oj = (c + e) / a.k;
+            v[e] = 0;
+            if (((bits >> e) & 1u) && oi < a.OH && oj < a.OW) v[e] = grow[oj];
+        }
+        if constexpr (VEC == 4) {
+            struct alignas(4 * sizeof(T)) Quad { T q[4]; };
+            Quad o; o.q[0] = v[0]; o.q[1] = v[1]; o.q[2] = v[2]; o.q[3] = v[3];
+            *reinterpret_cast<Quad*>(op + i) = o;
+        } else {
+            op[i] = v[0];
+        }
     }
 }
 
@@ -380,7 +410,11 @@ int division_maxpool_forward(const void* x, int64_t N, int64_t C, int64_t H, int
     const uint64_t grid = (uint64_t)a.P * a.bands;
     if (grid > 0x7fffffffull) return DIVISION_ERANGE;
     const size_t lds = 4 * ((size_t)band * row_bits / 32 + 2);
-    void (*kern)(PoolArgs) = dt == DIVISION_F32 ? maxpool_forward_kernel<float> : maxpool_forward_kernel<uint16_t>;
+    const size_t es = dt == DIVISION_BF16 ? 2 : 4;
+    const bool k2 = k == 2 && a.W % 2 == 0 && ((uintptr_t)x % (2 * es)) == 0;       // a.HW is even then
+    void (*kern)(PoolArgs);
+    if (dt == DIVISION_F32) kern = k2 ? maxpool_forward_kernel<float, true> : maxpool_forward_kernel<float, false>;
+    else kern = k2 ? maxpool_forward_kernel<uint16_t, true> : maxpool_forward_kernel<uint16_t, false>;
     hipLaunchKernelGGL(kern, dim3((uint32_t)grid), dim3(kThreads), lds, st, a);
     return hipGetLastError() == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
 }
@@ -391,8 +425,14 @@ int division_maxpool_backward(const void* mask, size_t mask_bytes, const void* g
     const int rc = pool_args(false, grad_out, grad_in, mask, N, C, H, W, dt, k, mask_bytes, &a);
     if (rc != DIVISION_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    void (*kern)(PoolArgs) = dt == DIVISION_F32 ? maxpool_backward_kernel<float> : maxpool_backward_kernel<uint16_t>;
-    uint32_t gx = (a.HW + kThreads * 4u - 1) / (kThreads * 4u);
+    const size_t esz = dt == DIVISION_BF16 ? 2 : 4;
+    const bool vec4 = a.W % 4 == 0 && ((uintptr_t)grad_in % (4 * esz)) == 0;
+    void (*kern)(PoolArgs);
+    if (dt == DIVISION_F32) kern = vec4 ? maxpool_backward_kernel<float, 4> : maxpool_backward_kernel<float, 1>;
+    else kern = vec4 ? maxpool_backward_kernel<uint16_t, 4> : maxpool_backward_kernel<uint16_t, 1>;
+    const uint32_t per = vec4 ? 4u : 1u;
+    uint32_t gx = (a.HW / per + kThreads * 2u - 1) / (kThreads * 2u);
+    if (gx < 1) gx = 1;
     if (gx > 4096) gx = 4096;
     // grid.y takes a slice of planes per launch; a multiple of 32 planes, so that every slice's
     // first mask bit starts a word
