@@ -416,3 +416,49 @@ def test_saved_tensor_hook_caches_the_map_and_rebuilds_it_in_backward():
     assert np.array_equal(w.grad.cpu().numpy(), ref)
     # dL/dh needs only w, which is a parameter and is never cached
     assert torch.equal(h.grad, w.detach())
+
+
+# ---------------------------------------------------------------- HIP graph capture
+
+def test_compress_and_decompress_replay_from_a_hip_graph():
+    """The library allocates nothing and records no memset, so a step can be captured once and
+    replayed; every replay (with the program's own eager work in between) must reproduce the eager result."""
+    shapes = [((6, 8, 56, 56), 8, 2), ((5, 9, 14, 14), 8, 2), ((37, 9, 7, 7), 8, 2), ((4, 7, 28, 28), 8, 4)]
+    xs = [torch.empty(s, device="cuda:0") for s, _, _ in shapes]
+    packed = [torch.empty(pkg.division_packed_bytes(*s, B, b), dtype=torch.uint8, device="cuda:0") for s, B, b in shapes]
+    outs = [torch.empty(s, device="cuda:0") for s, _, _ in shapes]
+
+    def step(stream=None):
+        for x, pk, y, (s, B, b) in zip(xs, packed, outs, shapes):
+            pkg.division_compress(x, B, b, 1234, packed=pk, stream=stream)
+            pkg.division_decompress(pk, s, B, b, out=y, stream=stream)
+
+    def fill(k):
+        for i, (x, (s, _, _)) in enumerate(zip(xs, shapes)):
+            x.copy_(_relu_normal(s, 9000 + 10 * k + i))
+
+    fill(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(side)                      # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(side)
+    for k in range(1, 4):
+        fill(k)                         # eager work between replays
+        for pk in packed:
+            pk.fill_(0xEE)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [(pk.clone(), y.clone()) for pk, y in zip(packed, outs)]
+        for pk in packed:
+            pk.fill_(0x11)
+        step()                          # the same step, eagerly
+        torch.cuda.synchronize()
+        for (gp, gy), pk, y, x, (s, B, b) in zip(got, packed, outs, xs, shapes):
+            assert torch.equal(gp, pk) and torch.equal(gy, y)
+            assert np.array_equal(gp.cpu().numpy(), oracle.compress(x.cpu().numpy(), B, b, 1234))
