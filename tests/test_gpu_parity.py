@@ -462,3 +462,45 @@ def test_compress_and_decompress_replay_from_a_hip_graph():
         for (gp, gy), pk, y, x, (s, B, b) in zip(got, packed, outs, xs, shapes):
             assert torch.equal(gp, pk) and torch.equal(gy, y)
             assert np.array_equal(gp.cpu().numpy(), oracle.compress(x.cpu().numpy(), B, b, 1234))
+
+
+# ---------------------------------------------------------------- seeded sweep over shapes and parameters
+
+def _sweep_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    sizes = [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 13, 14, 16, 17, 20, 24, 28, 31, 32, 33, 40, 48, 55, 56, 57, 64, 72]
+    cases = []
+    for _ in range(n):
+        H, W = int(rng.choice(sizes)), int(rng.choice(sizes))
+        if rng.random() < 0.5:
+            W = H                                              # square maps are the common case
+        B = int(rng.choice([1, 2, 3, 4, 4, 4, 5, 6, 7, 8, 8, 8, 8, 9, 12, 16, 64]))
+        b = int(rng.choice([2, 2, 4, 8]))
+        N, C = int(rng.integers(1, 6)), int(rng.integers(1, 12))
+        if H * W <= 64 and rng.random() < 0.5:
+            N, C = int(rng.integers(20, 90)), int(rng.integers(3, 9))      # several rounds of small planes
+        cases.append(((N, C, H, W), B, b, bool(rng.random() < 0.3), int(rng.integers(0, 2 ** 63))))
+    return cases
+
+
+@pytest.mark.parametrize("chunk", range(6))
+def test_seeded_sweep_of_shapes_block_sizes_and_code_widths(chunk):
+    """240 pseudo-random (shape, B, b, dtype, seed) combinations, 40 per test: every kernel family
+    and most of their ragged paths; single and batched calls must both be bit-exact."""
+    for shape, B, b, bf16, seed in _sweep_cases(240, 20240511)[40 * chunk:40 * (chunk + 1)]:
+        dtype = torch.bfloat16 if bf16 else torch.float32
+        x = _relu_normal(shape, seed % 100003, dtype)
+        xh, dt = to_host_array(x)
+        ref = oracle.compress(xh, B, b, seed, dt)
+        xd = x.to("cuda:0")
+        need = pkg.division_packed_bytes(*shape, B, b, dtype)
+        pk = torch.full((need,), 0xA5, dtype=torch.uint8, device="cuda:0")
+        pkg.division_compress(xd, B, b, seed, packed=pk)
+        pks = pkg.division_compress_batch([xd, xd], B, b, [seed + 1, seed])
+        y = pkg.division_decompress(pk, shape, B, b, dtype)
+        torch.cuda.synchronize()
+        tag = f"shape={shape} B={B} b={b} dtype={dtype} seed={seed}"
+        assert np.array_equal(pk.cpu().numpy(), ref), tag
+        assert torch.equal(pks[1], pk), tag
+        yh, _ = to_host_array(y.cpu())
+        assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt)), tag
