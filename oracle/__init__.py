@@ -17,6 +17,7 @@ import numpy as np
 
 F32 = 0
 BF16 = 1
+F32_C16 = 2      # x fp32; H^L, delta, Delta cached as bfloat16 (the paper's format)
 
 _HERE = Path(__file__).resolve().parent
 _SRC = _HERE / "division_oracle.c"
@@ -81,6 +82,7 @@ def lib() -> ctypes.CDLL:
 
 
 def _np_dtype(dt: int):
+    """numpy type of x and of the reconstruction"""
     return np.uint16 if dt == BF16 else np.float32
 
 
@@ -136,14 +138,17 @@ def decompress(packed: np.ndarray, shape, B: int, b: int, dt: int = F32, threads
 
 
 def split_packed(packed: np.ndarray, shape, B: int, b: int, dt: int = F32) -> dict:
-    """Views of the three regions: codes u32[P][WPP], meta f32[P][2], lfc T[P][LH][LW]."""
+    """Views of the three regions: codes u32[P][WPP], meta [P][2] (float32, or bf16 bit patterns as
+    uint16 in the F32_C16 mode), lfc [P][LH][LW] (float32 for F32, else bf16 bit patterns)."""
     N, C, H, W = shape
     lay = packed_layout(N, C, H, W, B, b, dt)
     P = N * C
     LH, LW = -(-H // B), -(-W // B)
     codes = packed[lay["codes_off"]:lay["codes_off"] + lay["codes_bytes"]].view(np.uint32).reshape(P, -1)
-    meta = packed[lay["meta_off"]:lay["meta_off"] + lay["meta_bytes"]].view(np.float32).reshape(P, 2)
-    lfc = packed[lay["lfc_off"]:lay["lfc_off"] + lay["lfc_bytes"]].view(_np_dtype(dt)).reshape(P, LH, LW)
+    meta = packed[lay["meta_off"]:lay["meta_off"] + lay["meta_bytes"]]
+    meta = (meta.view(np.uint16) if dt == F32_C16 else meta.view(np.float32)).reshape(P, 2)
+    lfc = packed[lay["lfc_off"]:lay["lfc_off"] + lay["lfc_bytes"]]
+    lfc = (lfc.view(np.float32) if dt == F32 else lfc.view(np.uint16)).reshape(P, LH, LW)
     return {"codes": codes, "meta": meta, "lfc": lfc}
 
 

@@ -28,7 +28,9 @@
  *   - pooled size is ceil(H/B) x ceil(W/B); edge windows average only their
  *     valid elements.  Identical to the paper whenever B divides the map size
  *     and whenever the map is smaller than B (one window covering the map).
- *   - one (delta, Delta) pair per (sample, channel) plane, stored as fp32.
+ *   - one (delta, Delta) pair per (sample, channel) plane, stored as fp32; in the ORACLE_F32_C16
+ *     mode (the paper's cached format) as bfloat16, delta rounded down and Delta rounded up so
+ *     that the decoder's values bracket every residual (see plane_scale_c16).
  *   - stochastic rounding rounds UP with probability frac(x) (the unbiased
  *     rule the paper's second footnote on Eq. (quantization) requires).
  *   - a plane whose residual range is below 2^-90 is degenerate: Delta = 0,
@@ -58,7 +60,12 @@
 #include <math.h>
 #include <stdlib.h>
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+/* element type of x and of the reconstruction / how the tuple is cached:
+ *   ORACLE_F32       x fp32;  H^L fp32, (delta, Delta) fp32
+ *   ORACLE_BF16      x bf16;  H^L bf16, (delta, Delta) fp32
+ *   ORACLE_F32_C16   x fp32;  H^L, delta and Delta cached as bfloat16, the format of the paper
+ *                    (Sec. 4.1: "cached in the format of bfloat16"; N^2 Q/8 + 4 bytes per channel) */
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F32_C16 = 2 };
 
 /* ---------- storage types ------------------------------------------------ */
 
@@ -89,7 +96,36 @@ static float load_elem(const void *x, int dt, size_t idx)
     return ((const float *)x)[idx];
 }
 
-static size_t elem_size(int dt) { return dt == ORACLE_BF16 ? 2u : 4u; }
+static size_t lfc_size(int dt) { return dt == ORACLE_F32 ? 4u : 2u; }             /* of the cached H^L */
+static size_t meta_size(int dt) { return dt == ORACLE_F32_C16 ? 4u : 8u; }        /* of (delta, Delta) per plane */
+
+/* largest bfloat16 <= f and smallest bfloat16 >= f (finite f) */
+static float bf16_floor(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint32_t t = u & 0xffff0000u;                       /* toward zero */
+    if ((u & 0x80000000u) && (u & 0xffffu)) t += 0x10000u;   /* negative: one step away from zero */
+    float r;
+    memcpy(&r, &t, 4);
+    return r;
+}
+static float bf16_ceil(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint32_t t = u & 0xffff0000u;
+    if (!(u & 0x80000000u) && (u & 0xffffu)) t += 0x10000u;  /* positive: one step away from zero */
+    float r;
+    memcpy(&r, &t, 4);
+    return r;
+}
+static uint16_t bf16_bits_exact(float f)                /* f is a bfloat16 value already */
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    return (uint16_t)(u >> 16);
+}
 
 static size_t align16(size_t v) { return (v + 15u) & ~(size_t)15u; }
 
@@ -154,7 +190,7 @@ static int make_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b,
 {
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4 && b != 8))
         return 1;
-    if (dt != ORACLE_F32 && dt != ORACLE_BF16)
+    if (dt != ORACLE_F32 && dt != ORACLE_BF16 && dt != ORACLE_F32_C16)
         return 1;
     L->P = (size_t)N * (size_t)C;
     L->HW = (size_t)H * (size_t)W;
@@ -165,9 +201,9 @@ static int make_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b,
     L->codes_off = 0;
     L->codes_bytes = 4u * L->P * L->WPP;
     L->meta_off = align16(L->codes_bytes);
-    L->meta_bytes = 8u * L->P;
+    L->meta_bytes = meta_size(dt) * L->P;
     L->lfc_off = align16(L->meta_off + L->meta_bytes);
-    L->lfc_bytes = elem_size(dt) * L->P * L->LH * L->LW;
+    L->lfc_bytes = lfc_size(dt) * L->P * L->LH * L->LW;
     L->total = align16(L->lfc_off + L->lfc_bytes);
     return 0;
 }
@@ -214,7 +250,7 @@ static void plane_lfc(const void *x, int dt, size_t base, size_t H, size_t W, si
                     ++cnt;
                 }
             float m = (float)(S / (double)cnt);
-            if (dt == ORACLE_BF16)
+            if (dt != ORACLE_F32)
                 m = bf16_to_float(float_to_bf16(m));
             lfc_f[bi * LW + bj] = m;
         }
@@ -238,6 +274,34 @@ static void plane_scale(const float *h, size_t HW, int b, float *delta, float *D
         volatile float top = range * s;             /* fp32 mul */
         if (top < Lf)
             s = nextafterf(s, INFINITY);
+        *Delta = D;
+        *inv = s;
+    } else {
+        *Delta = 0.0f;
+        *inv = 0.0f;
+    }
+}
+
+/* The same with delta and Delta cached as bfloat16 (ORACLE_F32_C16).  Reading: the quantiser
+ * must use the very values the decoder will see, and every residual must stay inside their code
+ * range, so delta is the plane minimum rounded DOWN to bfloat16 and Delta is
+ * fl(fl(max - delta) / L) rounded UP to bfloat16; the scale is inv = fl(1 / Delta).  The top code
+ * need not be reached.  A plane with fl(max - delta) below 2^-90 is degenerate (Delta = 0). */
+static void plane_scale_c16(const float *h, size_t HW, int b, float *delta, float *Delta, float *inv)
+{
+    float lo = h[0], hi = h[0];
+    for (size_t i = 1; i < HW; ++i) {
+        if (h[i] < lo) lo = h[i];
+        if (h[i] > hi) hi = h[i];
+    }
+    const float Lf = (float)((1 << b) - 1);
+    const float d = bf16_floor(lo);
+    volatile float range = hi - d;                  /* fp32 sub */
+    *delta = d;
+    if (range >= 0x1p-90f && range <= 3.4028234663852886e38f) {
+        volatile float q = range / Lf;              /* fp32 div */
+        const float D = bf16_ceil(q);
+        volatile float s = 1.0f / D;                /* fp32 div */
         *Delta = D;
         *inv = s;
     } else {
@@ -282,7 +346,7 @@ int oracle_compress(const void *x, int64_t N, int64_t C, int64_t H, int64_t W, i
 
         /* store H^L in the storage type */
         for (size_t k = 0; k < L.LH * L.LW; ++k) {
-            if (dt == ORACLE_BF16)
+            if (dt != ORACLE_F32)
                 ((uint16_t *)(pk + L.lfc_off))[p * L.LH * L.LW + k] = float_to_bf16(lfc_f[k]);
             else
                 ((float *)(pk + L.lfc_off))[p * L.LH * L.LW + k] = lfc_f[k];
@@ -297,9 +361,15 @@ int oracle_compress(const void *x, int64_t N, int64_t C, int64_t H, int64_t W, i
             }
 
         float delta, Delta, inv;
-        plane_scale(h, L.HW, b, &delta, &Delta, &inv);
-        ((float *)(pk + L.meta_off))[2 * p + 0] = delta;
-        ((float *)(pk + L.meta_off))[2 * p + 1] = Delta;
+        if (dt == ORACLE_F32_C16) {
+            plane_scale_c16(h, L.HW, b, &delta, &Delta, &inv);
+            ((uint16_t *)(pk + L.meta_off))[2 * p + 0] = bf16_bits_exact(delta);
+            ((uint16_t *)(pk + L.meta_off))[2 * p + 1] = bf16_bits_exact(Delta);
+        } else {
+            plane_scale(h, L.HW, b, &delta, &Delta, &inv);
+            ((float *)(pk + L.meta_off))[2 * p + 0] = delta;
+            ((float *)(pk + L.meta_off))[2 * p + 1] = Delta;
+        }
 
         uint32_t *codes = (uint32_t *)(pk + L.codes_off) + p * L.WPP;
         for (size_t i = 0; i < L.HW; ++i) {
@@ -342,14 +412,20 @@ int oracle_decompress(const void *packed, int64_t N, int64_t C, int64_t H, int64
     for (int64_t pp = 0; pp < (int64_t)L.P; ++pp) {
         size_t p = (size_t)pp;
         const uint32_t *codes = (const uint32_t *)(pk + L.codes_off) + p * L.WPP;
-        float delta = ((const float *)(pk + L.meta_off))[2 * p + 0];
-        float Delta = ((const float *)(pk + L.meta_off))[2 * p + 1];
+        float delta, Delta;
+        if (dt == ORACLE_F32_C16) {
+            delta = bf16_to_float(((const uint16_t *)(pk + L.meta_off))[2 * p + 0]);
+            Delta = bf16_to_float(((const uint16_t *)(pk + L.meta_off))[2 * p + 1]);
+        } else {
+            delta = ((const float *)(pk + L.meta_off))[2 * p + 0];
+            Delta = ((const float *)(pk + L.meta_off))[2 * p + 1];
+        }
         for (size_t r = 0; r < (size_t)H; ++r)
             for (size_t c = 0; c < (size_t)W; ++c) {
                 size_t i = r * (size_t)W + c;
                 uint32_t q = (codes[i / cpw] >> ((i % cpw) * (unsigned)b)) & Lq;
                 size_t k = p * L.LH * L.LW + (r / (size_t)B) * L.LW + (c / (size_t)B);
-                float lfc = (dt == ORACLE_BF16)
+                float lfc = (dt != ORACLE_F32)
                                 ? bf16_to_float(((const uint16_t *)(pk + L.lfc_off))[k])
                                 : ((const float *)(pk + L.lfc_off))[k];
                 volatile float hh = (float)q * Delta;   /* Sec. 4.2: Delta * V   */

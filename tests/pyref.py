@@ -74,8 +74,37 @@ def rand16(seed: int, plane: int, i: int) -> int:
     return (w >> 16) if (i & 1) else (w & 0xFFFF)
 
 
-def codec_plane(x, H, W, B, b, seed, plane):
+def bf16_floor(fr: Fraction) -> Fraction:
+    """largest bfloat16 value <= fr (8 significant bits, binary32 exponent range; normal range only)"""
+    if fr == 0:
+        return Fraction(0)
+    e = math.floor(math.log2(abs(fr)))
+    while Fraction(2) ** e > abs(fr):
+        e -= 1
+    while Fraction(2) ** (e + 1) <= abs(fr):
+        e += 1
+    ulp = Fraction(2) ** (e - 7)
+    return math.floor(fr / ulp) * ulp
+
+
+def bf16_ceil(fr: Fraction) -> Fraction:
+    return -bf16_floor(-fr)
+
+
+def bf16_nearest(fr: Fraction) -> Fraction:
+    lo, hi = bf16_floor(fr), bf16_ceil(fr)
+    if lo == hi:
+        return lo
+    if fr - lo != hi - fr:
+        return lo if fr - lo < hi - fr else hi
+    # tie: even mantissa
+    ulp = hi - lo
+    return lo if (lo / ulp) % 2 == 0 else hi
+
+
+def codec_plane(x, H, W, B, b, seed, plane, c16=False):
     """x: list of H*W Fractions (exact binary32 values), row-major.
+    c16: H^L, delta and Delta cached as bfloat16 (delta rounded down, Delta rounded up).
 
     Returns dict(lfc=[..], delta, Delta, codes=[..], xhat=[..]) with Fractions / ints.
     The block mean of an element is found by searching, per element, all
@@ -92,11 +121,18 @@ def codec_plane(x, H, W, B, b, seed, plane):
             members = [x[rr * W + cc] for rr in range(H) for cc in range(W)
                        if rr // B == key[0] and cc // B == key[1]]
             mean_of[key] = f32(sum(members, Fraction(0)) / len(members))
+            if c16:
+                mean_of[key] = bf16_nearest(mean_of[key])
     lfc = [mean_of[(i, j)] for i in range(LH) for j in range(LW)]
     h = [f32(x[r * W + c] - mean_of[(r // B, c // B)]) for r in range(H) for c in range(W)]
     delta, hmax = min(h), max(h)
+    if c16:
+        delta = bf16_floor(delta)
     rng = f32(hmax - delta)
-    if rng >= Fraction(2) ** -90:
+    if rng >= Fraction(2) ** -90 and c16:
+        Delta = bf16_ceil(f32(rng / L))
+        inv = f32(1 / Delta)
+    elif rng >= Fraction(2) ** -90:
         Delta = f32(rng / L)
         inv = f32(Fraction(L) / rng)
         if f32(rng * inv) < L:
