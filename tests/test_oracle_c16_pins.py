@@ -131,4 +131,4 @@ def test_degenerate_and_constant_planes():
     # bfloat16 value, so the plane is NOT degenerate; it comes back within one (tiny) step
     Delta = float(oracle.bf16_to_f32(s["meta"][0, 1:2])[0])
     assert 0 < Delta <= 0.3 * 2.0 ** -8
-    assert np.all(np.abs(xh[0, 0] - x[0, 0]) <= Delta * (1 + 1e-5))
+    assert np.all(np.abs(xh[0, 0] - x[0, 0]) <= Delta + 2.0 ** -24)      # one step plus the fp32 rounding of the sum
