@@ -180,6 +180,8 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=None, help="override the batch size (not a valid headline run)")
     ap.add_argument("--mode", choices=["batch", "layer"], default="batch",
                     help="batch: consecutive same-shape maps share a launch (<= 8 per call); layer: one call per map")
+    ap.add_argument("--c16", action="store_true",
+                    help="cache H^L, delta and Delta as bfloat16 (the paper's format; fp32 workloads only)")
     ap.add_argument("--compare-modes", action="store_true",
                     help="also time the other launch mode (before the reported one) and add its figures to the line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -236,7 +238,7 @@ def main() -> int:
     xs, packs, outs = [], [], []
     for s in range(nsets):
         xs.append([(x.to(dev) if s == 0 else torch.roll(x.to(dev), s, 0).contiguous()) for _, _, x in host])
-        packs.append([torch.empty(pkg.division_packed_bytes(*x.shape, sp.B, sp.b, x.dtype), dtype=torch.uint8, device=dev)
+        packs.append([torch.empty(pkg.division_packed_bytes(*x.shape, sp.B, sp.b, x.dtype, args.c16), dtype=torch.uint8, device=dev)
                       for _, sp, x in host])
         outs.append([torch.empty(x.shape, dtype=x.dtype, device=dev) for _, _, x in host])
     shapes = [tuple(x.shape) for _, _, x in host]
@@ -279,15 +281,15 @@ def main() -> int:
             if len(g) == 1:
                 i = g[0]
                 if d == 0:
-                    pkg.division_compress(xs[s][i], sp.B, sp.b, seeds[i], packed=packs[s][i])
+                    pkg.division_compress(xs[s][i], sp.B, sp.b, seeds[i], packed=packs[s][i], c16=args.c16)
                 else:
-                    pkg.division_decompress(packs[s][i], shapes[i], sp.B, sp.b, dtypes[i], out=outs[s][i])
+                    pkg.division_decompress(packs[s][i], shapes[i], sp.B, sp.b, dtypes[i], out=outs[s][i], c16=args.c16)
             elif d == 0:
                 pkg.division_compress_batch([xs[s][i] for i in g], sp.B, sp.b, [seeds[i] for i in g],
-                                            packed=[packs[s][i] for i in g])
+                                            packed=[packs[s][i] for i in g], c16=args.c16)
             else:
                 pkg.division_decompress_batch([packs[s][i] for i in g], shapes[g[0]], sp.B, sp.b, dtypes[g[0]],
-                                              out=[outs[s][i] for i in g])
+                                              out=[outs[s][i] for i in g], c16=args.c16)
             if rec:
                 e1.record()
                 events.append(((d, g), e0, e1))
@@ -342,6 +344,7 @@ def main() -> int:
                    "input_bytes": input_bytes, "packed_bytes": packed_bytes,
                    "B": host[0][1].B, "b": host[0][1].b, "buffer_sets": nsets,
                    "launch_mode": args.mode, "launches_per_step": n_launches,
+                   "cache_format": "bf16 H^L, delta, Delta (Sec. 4.1)" if args.c16 else "H^L in the map's type, fp32 delta, Delta",
                    "batch_override": args.batch},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "activation_GB_s": round(2 * input_bytes / (ms_per_step * 1e-3) / 1e9, 1),
@@ -351,13 +354,13 @@ def main() -> int:
         "kernel_ms_last_warmup_step": {k: round(v, 4) for k, v in sorted(per_kernel.items())},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(dominant) if args.config == 2 and args.batch is None else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(dominant) if args.config == 2 and args.batch is None and not args.c16 else None,
                      "algorithmic_bytes_per_launch": round(avg_bytes), "avg_launch_ms": round(avg_ms, 5),
                      "launches_timed": len(dom_ms)},
     }
 
     # ---- CPU baseline: the oracle as it stands, on the host cores, same workload
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.c16:
         import numpy as np
 
         import oracle

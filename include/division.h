@@ -20,7 +20,9 @@
  *          element i = r*W + c of a plane sits in word i / CPW at bit
  *          (i % CPW) * b; pad bits are zero.
  *   meta   at align16(end of codes)       float  [P][2] = (delta_p, Delta_p)
+ *          (DIVISION_F32_C16: bfloat16 [P][2])
  *   lfc    at align16(end of meta)        T      [P][LH][LW], T = element type
+ *          (DIVISION_F32_C16: bfloat16)
  *   total  = align16(end of lfc)          == division_packed_bytes(...)
  */
 #ifndef DIVISION_H
@@ -33,8 +35,18 @@
 extern "C" {
 #endif
 
-/* Element type of x, of the reconstructed map and of the stored LFC. */
-typedef enum { DIVISION_F32 = 0, DIVISION_BF16 = 1 } division_dtype;
+/*
+ * Element type of x and of the reconstructed map, and how the tuple is cached:
+ *   DIVISION_F32      x fp32;  H^L fp32, (delta, Delta) fp32
+ *   DIVISION_BF16     x bf16;  H^L bf16, (delta, Delta) fp32
+ *   DIVISION_F32_C16  x fp32;  H^L, delta and Delta cached as bfloat16: the format of Sec. 4.1
+ *                     (N^2 Q/8 + 4 bytes per channel for V^H, delta, Delta; H^L 0.8 % of the map
+ *                     at B = 8).  delta is the plane minimum rounded DOWN to bfloat16 and Delta
+ *                     is fl(fl(max - delta)/L) rounded UP, so that the cached values bracket every
+ *                     residual and the quantiser uses exactly what the decoder reads.
+ * (The mask operators below take DIVISION_F32 or DIVISION_BF16 only.)
+ */
+typedef enum { DIVISION_F32 = 0, DIVISION_BF16 = 1, DIVISION_F32_C16 = 2 } division_dtype;
 
 /* Return codes of every int-returning entry point. */
 enum {

@@ -13,6 +13,7 @@ import torch
 
 DIVISION_F32 = 0
 DIVISION_BF16 = 1
+DIVISION_F32_C16 = 2      # fp32 maps; H^L, delta, Delta cached as bfloat16 (the paper's format)
 
 ERRORS = {1: "DIVISION_EINVAL", 2: "DIVISION_ESIZE", 3: "DIVISION_EALIGN",
           4: "DIVISION_ERANGE", 5: "DIVISION_EHIP"}
@@ -69,12 +70,13 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
-def _dt(t: torch.dtype) -> int:
+def _dt(t: torch.dtype, c16: bool = False) -> int:
+    """c16: cache H^L, delta and Delta as bfloat16 (fp32 maps only; the paper's format)."""
     if t == torch.float32:
-        return DIVISION_F32
-    if t == torch.bfloat16:
+        return DIVISION_F32_C16 if c16 else DIVISION_F32
+    if t == torch.bfloat16 and not c16:
         return DIVISION_BF16
-    raise TypeError(f"unsupported dtype {t}")
+    raise TypeError(f"unsupported dtype {t}" + (" with c16" if c16 else ""))
 
 
 def _stream(stream) -> int:
@@ -83,13 +85,13 @@ def _stream(stream) -> int:
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
-def division_packed_bytes(N: int, C: int, H: int, W: int, B: int, b: int, dtype=torch.float32) -> int:
-    return int(lib().division_packed_bytes(N, C, H, W, B, b, _dt(dtype)))
+def division_packed_bytes(N: int, C: int, H: int, W: int, B: int, b: int, dtype=torch.float32, c16: bool = False) -> int:
+    return int(lib().division_packed_bytes(N, C, H, W, B, b, _dt(dtype, c16)))
 
 
-def division_packed_layout(N: int, C: int, H: int, W: int, B: int, b: int, dtype=torch.float32) -> dict:
+def division_packed_layout(N: int, C: int, H: int, W: int, B: int, b: int, dtype=torch.float32, c16: bool = False) -> dict:
     vals = [ctypes.c_size_t() for _ in range(6)]
-    rc = lib().division_packed_layout(N, C, H, W, B, b, _dt(dtype), *[ctypes.byref(v) for v in vals])
+    rc = lib().division_packed_layout(N, C, H, W, B, b, _dt(dtype, c16), *[ctypes.byref(v) for v in vals])
     if rc:
         raise DivisionError(rc, "division_packed_layout")
     names = ["codes_off", "codes_bytes", "meta_off", "meta_bytes", "lfc_off", "lfc_bytes"]
@@ -97,17 +99,17 @@ def division_packed_layout(N: int, C: int, H: int, W: int, B: int, b: int, dtype
 
 
 def division_compress(x: torch.Tensor, B: int, b: int, seed: int, packed: torch.Tensor | None = None,
-                      stream=None) -> torch.Tensor:
+                      stream=None, c16: bool = False) -> torch.Tensor:
     """x: contiguous NCHW device tensor (float32 or bfloat16).  Returns the packed uint8 buffer."""
     if x.dim() != 4 or not x.is_cuda or not x.is_contiguous():
         raise ValueError("x must be a contiguous 4-d device tensor")
     N, C, H, W = x.shape
-    need = division_packed_bytes(N, C, H, W, B, b, x.dtype)
+    need = division_packed_bytes(N, C, H, W, B, b, x.dtype, c16)
     if need == 0:
         raise DivisionError(1, "division_packed_bytes")
     if packed is None:
         packed = torch.empty(need, dtype=torch.uint8, device=x.device)
-    rc = lib().division_compress(x.data_ptr(), N, C, H, W, _dt(x.dtype), B, b, seed & (2 ** 64 - 1),
+    rc = lib().division_compress(x.data_ptr(), N, C, H, W, _dt(x.dtype, c16), B, b, seed & (2 ** 64 - 1),
                                  packed.data_ptr(), packed.numel() * packed.element_size(), _stream(stream))
     if rc:
         raise DivisionError(rc, "division_compress")
@@ -115,12 +117,12 @@ def division_compress(x: torch.Tensor, B: int, b: int, seed: int, packed: torch.
 
 
 def division_decompress(packed: torch.Tensor, shape, B: int, b: int, dtype=torch.float32,
-                        out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+                        out: torch.Tensor | None = None, stream=None, c16: bool = False) -> torch.Tensor:
     N, C, H, W = shape
     if out is None:
         out = torch.empty(shape, dtype=dtype, device=packed.device)
     rc = lib().division_decompress(packed.data_ptr(), packed.numel() * packed.element_size(),
-                                   N, C, H, W, _dt(dtype), B, b, out.data_ptr(), _stream(stream))
+                                   N, C, H, W, _dt(dtype, c16), B, b, out.data_ptr(), _stream(stream))
     if rc:
         raise DivisionError(rc, "division_decompress")
     return out
@@ -130,7 +132,7 @@ def _ptr_array(tensors):
     return (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
 
 
-def division_compress_batch(xs, B: int, b: int, seeds, packed=None, stream=None):
+def division_compress_batch(xs, B: int, b: int, seeds, packed=None, stream=None, c16: bool = False):
     """xs: contiguous NCHW device tensors of ONE shape and dtype; seeds: one per tensor.
     Returns the list of packed uint8 buffers (those given in `packed`, else new ones)."""
     xs = list(xs)
@@ -144,7 +146,7 @@ def division_compress_batch(xs, B: int, b: int, seeds, packed=None, stream=None)
         if x.dim() != 4 or not x.is_cuda or not x.is_contiguous() or x.shape != x0.shape or x.dtype != x0.dtype:
             raise ValueError("xs must be contiguous 4-d device tensors of one shape and dtype")
     N, C, H, W = x0.shape
-    need = division_packed_bytes(N, C, H, W, B, b, x0.dtype)
+    need = division_packed_bytes(N, C, H, W, B, b, x0.dtype, c16)
     if need == 0:
         raise DivisionError(1, "division_packed_bytes")
     if packed is None:
@@ -155,13 +157,14 @@ def division_compress_batch(xs, B: int, b: int, seeds, packed=None, stream=None)
     cap = min(p.numel() * p.element_size() for p in packed)
     sd = (ctypes.c_uint64 * len(xs))(*[s & (2 ** 64 - 1) for s in seeds])
     rc = lib().division_compress_batch(len(xs), _ptr_array(xs), _ptr_array(packed), sd, N, C, H, W,
-                                       _dt(x0.dtype), B, b, cap, _stream(stream))
+                                       _dt(x0.dtype, c16), B, b, cap, _stream(stream))
     if rc:
         raise DivisionError(rc, "division_compress_batch")
     return packed
 
 
-def division_decompress_batch(packed, shape, B: int, b: int, dtype=torch.float32, out=None, stream=None):
+def division_decompress_batch(packed, shape, B: int, b: int, dtype=torch.float32, out=None, stream=None,
+                              c16: bool = False):
     """packed: buffers written by division_compress(_batch) for maps of `shape`.  Returns the list of maps."""
     packed = list(packed)
     if not packed:
@@ -174,7 +177,7 @@ def division_decompress_batch(packed, shape, B: int, b: int, dtype=torch.float32
         raise ValueError("one output per packed buffer")
     nbytes = min(p.numel() * p.element_size() for p in packed)
     rc = lib().division_decompress_batch(len(packed), _ptr_array(packed), _ptr_array(out), nbytes,
-                                         N, C, H, W, _dt(dtype), B, b, _stream(stream))
+                                         N, C, H, W, _dt(dtype, c16), B, b, _stream(stream))
     if rc:
         raise DivisionError(rc, "division_decompress_batch")
     return out

@@ -23,6 +23,7 @@
 #include <stddef.h>
 #include <stdio.h>
 #include <stdlib.h>
+#include <type_traits>
 #include "../../include/division.h"
 
 namespace {
@@ -38,6 +39,10 @@ constexpr int kLoadAux = 0;
 // ------------------------------------------------------------------ helpers
 
 struct bf16_t { uint16_t v; };
+// an fp32 map whose H^L, delta and Delta are cached as bfloat16 (the paper's format): same
+// element as float, different cache layout; a type of its own so that the choice costs nothing
+// at run time
+struct f32c16_t { float v; };
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -56,6 +61,13 @@ template <> struct Elem<float> {
     static __device__ __forceinline__ void store(float* p, size_t i, float v) { p[i] = v; }
     static __device__ __forceinline__ float round(float v) { return v; }
 };
+template <> struct Elem<f32c16_t> {
+    static __device__ __forceinline__ float load(const f32c16_t* p, size_t i) { return p[i].v; }
+    static __device__ __forceinline__ void store(f32c16_t* p, size_t i, float v) { p[i].v = v; }
+    static __device__ __forceinline__ float round(float v) { return v; }
+};
+template <typename T> constexpr uint32_t kC16 = 0;
+template <> constexpr uint32_t kC16<f32c16_t> = 1;
 template <> struct Elem<bf16_t> {
     static __device__ __forceinline__ float load(const bf16_t* p, size_t i) { return bf16_bits_to_float(p[i].v); }
     static __device__ __forceinline__ void store(bf16_t* p, size_t i, float v) { p[i].v = (uint16_t)float_to_bf16_bits(v); }
@@ -98,6 +110,73 @@ __device__ __forceinline__ void plane_scale(float mn, float mx, float Lf, float&
         Delta = 0.0f;
         inv = 0.0f;
     }
+}
+
+// ---- the paper's cached format (c16): fp32 maps whose H^L, delta and Delta are cached as bfloat16
+
+// largest bfloat16 <= f and smallest bfloat16 >= f (finite f)
+__device__ __forceinline__ float bf16_floor_f(float f) {
+    const uint32_t u = __float_as_uint(f);
+    uint32_t t = u & 0xffff0000u;                                    // toward zero
+    if ((u & 0x80000000u) && (u & 0xffffu)) t += 0x10000u;           // negative: one step away from zero
+    return __uint_as_float(t);
+}
+__device__ __forceinline__ float bf16_ceil_f(float f) {
+    const uint32_t u = __float_as_uint(f);
+    uint32_t t = u & 0xffff0000u;
+    if (!(u & 0x80000000u) && (u & 0xffffu)) t += 0x10000u;
+    return __uint_as_float(t);
+}
+
+// Scale of one plane from its residual extremes.  Plain: delta = min, Delta, inv as plane_scale.
+// c16: the quantiser has to use the very values the decoder will read and every residual has to
+// stay inside their code range, so delta = min rounded DOWN to bfloat16, Delta =
+// fl(fl(max - delta) / L) rounded UP to bfloat16, inv = fl(1 / Delta).
+__device__ __forceinline__ void plane_scale_any(float mn, float mx, float Lf, uint32_t c16,
+                                                float& delta, float& Delta, float& inv) {
+    if (!c16) {
+        delta = mn;
+        plane_scale(mn, mx, Lf, Delta, inv);
+        return;
+    }
+    delta = bf16_floor_f(mn);
+    const float range = mx - delta;
+    if (range >= 0x1p-90f && range <= 3.4028234663852886e38f) {
+        Delta = bf16_ceil_f(range / Lf);
+        inv = 1.0f / Delta;
+    } else {
+        Delta = 0.0f;
+        inv = 0.0f;
+    }
+}
+
+// (delta, Delta) of plane p: two floats, or two bfloat16 in one word (c16)
+__device__ __forceinline__ void meta_store(float* meta, uint32_t p, float delta, float Delta, uint32_t c16) {
+    if (c16) reinterpret_cast<uint32_t*>(meta)[p] = (__float_as_uint(delta) >> 16) | (__float_as_uint(Delta) & 0xffff0000u);
+    else reinterpret_cast<float2*>(meta)[p] = make_float2(delta, Delta);
+}
+__device__ __forceinline__ float2 meta_load(const float* meta, uint32_t p, uint32_t c16) {
+    if (c16) {
+        const uint32_t w = reinterpret_cast<const uint32_t*>(meta)[p];
+        return make_float2(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
+    }
+    return reinterpret_cast<const float2*>(meta)[p];
+}
+
+// H^L: stored in the element type of x, or as bfloat16 (c16; x is fp32 then)
+template <typename T>
+__device__ __forceinline__ float lfc_round(float v, uint32_t c16) {
+    return (sizeof(T) == 2 || c16) ? bf16_bits_to_float(float_to_bf16_bits(v)) : v;
+}
+template <typename T>
+__device__ __forceinline__ void lfc_store(void* base, size_t idx, float v, uint32_t c16) {
+    if (sizeof(T) == 2 || c16) static_cast<uint16_t*>(base)[idx] = (uint16_t)float_to_bf16_bits(v);
+    else static_cast<float*>(base)[idx] = v;
+}
+template <typename T>
+__device__ __forceinline__ float lfc_load(const void* base, size_t idx, uint32_t c16) {
+    if (sizeof(T) == 2 || c16) return bf16_bits_to_float(static_cast<const uint16_t*>(base)[idx]);
+    return static_cast<const float*>(base)[idx];
 }
 
 // quantise one element against its pair word: floor(t + r/2^16) with
@@ -374,9 +453,9 @@ __global__ void __launch_bounds__(NT) compress_tile(TileArgs a) {
         float m;
         if ((cnt & (cnt - 1)) == 0) m = (float)(S * (1.0 / (double)cnt));   // power of two: exact scaling
         else m = (float)(S / (double)cnt);
-        const float lfc = Elem<T>::round(m);
+        const float lfc = lfc_round<T>(m, kC16<T>);
         if (valid && (s % IPB) == 0)
-            Elem<T>::store(static_cast<T*>(pt.lfc), (size_t)(p0 + g) * a.nb + bi * a.LW + bj, lfc);
+            lfc_store<T>(pt.lfc, (size_t)(p0 + g) * a.nb + bi * a.LW + bj, lfc, kC16<T>);
 
         // Sec. 4.1: H^H = H - UpSampling(H^L); written back over x
         float hmin = __builtin_inff(), hmax = -__builtin_inff();
@@ -419,13 +498,13 @@ __global__ void __launch_bounds__(NT) compress_tile(TileArgs a) {
             }
             group_minmax(S, mn, mx);
             if (live && sub == 0) {
-                float Delta, inv;
-                plane_scale(mn, mx, Lf, Delta, inv);
+                float delta, Delta, inv;
+                plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
                 const uint32_t p = p0 + g;
-                reinterpret_cast<float2*>(pt.meta)[p] = make_float2(mn, Delta);
+                meta_store(pt.meta, p, delta, Delta, kC16<T>);
                 const uint32_t k1 = mix32(p ^ pt.seed_a);
                 const uint32_t k2 = mix32(k1 + pt.seed_c);
-                params[g] = make_float4(mn, inv * (float)(1u << (32 - BITS)), __uint_as_float(k1), __uint_as_float(k2));
+                params[g] = make_float4(delta, inv * (float)(1u << (32 - BITS)), __uint_as_float(k1), __uint_as_float(k2));
             }
         }
     }
@@ -541,7 +620,7 @@ __device__ __forceinline__ ItemGeom item_geom(const WaveArgs& a, uint32_t rem) {
 }
 
 template <typename T, int B, int VEC, bool FULLROWS>
-__device__ __forceinline__ void pool_item(float* xs, const WaveArgs& a, T* lfc_plane, uint32_t g, const ItemGeom& gm,
+__device__ __forceinline__ void pool_item(float* xs, const WaveArgs& a, void* lfc_base, size_t lfc_plane, uint32_t g, const ItemGeom& gm,
                                           bool live, float& hmin, float& hmax) {
     constexpr int IPB = B / VEC;
     const bool valid = live && gm.in_plane;
@@ -574,8 +653,8 @@ __device__ __forceinline__ void pool_item(float* xs, const WaveArgs& a, T* lfc_p
     S = group_sum<IPB>(S);
 
     // exact sum / count, one rounding to fp32, then to the storage type
-    const float lfc = Elem<T>::round(mean_of(S, gm.cnt));
-    if (live && gm.writes_lfc) Elem<T>::store(lfc_plane, gm.lfc_idx, lfc);
+    const float lfc = lfc_round<T>(mean_of(S, gm.cnt), kC16<T>);
+    if (live && gm.writes_lfc) lfc_store<T>(lfc_base, lfc_plane + gm.lfc_idx, lfc, kC16<T>);
 
     // H^H = H - UpSampling(H^L), written back over x
     float mn = __builtin_inff(), mx = -__builtin_inff();
@@ -698,19 +777,19 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
             for (uint32_t g0 = 0; g0 < Gc; g0 += ppr) {
                 const uint32_t g = g0 + gsub;
                 const bool live = g < Gc;
-                T* lfc_plane = static_cast<T*>(pt.lfc) + (size_t)(p0 + g) * a.nb;
+                const size_t lfc_plane = (size_t)(p0 + g) * a.nb;      // the plane's first LFC element
                 float mn = __builtin_inff(), mx = -__builtin_inff();
 #ifdef DIVISION_EXPERIMENT
                 if (a.skip & 1u) { mn = 0.f; mx = 1.f; } else
 #endif
                 if (small) {
-                    if (fullrows) pool_item<T, B, VEC, true>(xs, a, lfc_plane, g, geom0, live, mn, mx);
-                    else pool_item<T, B, VEC, false>(xs, a, lfc_plane, g, geom0, live, mn, mx);
+                    if (fullrows) pool_item<T, B, VEC, true>(xs, a, pt.lfc, lfc_plane, g, geom0, live, mn, mx);
+                    else pool_item<T, B, VEC, false>(xs, a, pt.lfc, lfc_plane, g, geom0, live, mn, mx);
                 } else {
                     for (uint32_t t = 0; t < rpp; ++t) {
                         const ItemGeom gm = item_geom<B, VEC>(a, t * 64 + sub);
-                        if (fullrows) pool_item<T, B, VEC, true>(xs, a, lfc_plane, g, gm, live, mn, mx);
-                        else pool_item<T, B, VEC, false>(xs, a, lfc_plane, g, gm, live, mn, mx);
+                        if (fullrows) pool_item<T, B, VEC, true>(xs, a, pt.lfc, lfc_plane, g, gm, live, mn, mx);
+                        else pool_item<T, B, VEC, false>(xs, a, pt.lfc, lfc_plane, g, gm, live, mn, mx);
                     }
                 }
                 group_minmax(S, mn, mx);
@@ -723,13 +802,13 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
         // ---- phase 2: one lane per plane: scale of Eq. (quantization) and the plane's keys
         for (uint32_t g = lane; g < Gc; g += 64) {
             const float4 mm = params[g];
-            float Delta, inv;
-            plane_scale(mm.x, mm.y, Lf, Delta, inv);
+            float delta, Delta, inv;
+            plane_scale_any(mm.x, mm.y, Lf, kC16<T>, delta, Delta, inv);
             const uint32_t p = p0 + g;
             const uint32_t k1 = mix32(p ^ pt.seed_a);
             const uint32_t k2 = mix32(k1 + pt.seed_c);
-            reinterpret_cast<float2*>(pt.meta)[p] = make_float2(mm.x, Delta);
-            params[g] = make_float4(mm.x, inv * (float)(1u << (32 - BITS)), __uint_as_float(k1), __uint_as_float(k2));
+            meta_store(pt.meta, p, delta, Delta, kC16<T>);
+            params[g] = make_float4(delta, inv * (float)(1u << (32 - BITS)), __uint_as_float(k1), __uint_as_float(k2));
         }
         wave_sync();
 
@@ -921,8 +1000,8 @@ __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
         }
         Sm = valid ? Sm : 0.0;
         Sm = group_sum<IPB>(Sm);
-        const float lfc = Elem<T>::round(mean_of(Sm, cnt));
-        if (valid && writes_lfc) Elem<T>::store(static_cast<T*>(pt.lfc), (size_t)(p0 + g) * a.nb + lfc_idx, lfc);
+        const float lfc = lfc_round<T>(mean_of(Sm, cnt), kC16<T>);
+        if (valid && writes_lfc) lfc_store<T>(pt.lfc, (size_t)(p0 + g) * a.nb + lfc_idx, lfc, kC16<T>);
 
         // ---- residual H^H = H - UpSampling(H^L) in place, plane min / max
         float mn = __builtin_inff(), mx = -__builtin_inff();
@@ -939,14 +1018,13 @@ __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
         group_minmax(a.S, mn, mx);
 
         // ---- scale of Eq. (quantization), keys, meta: every lane of the plane computes the same values
-        float Delta, inv;
-        plane_scale(mn, mx, Lf, Delta, inv);
-        const float delta = mn;
+        float delta, Delta, inv;
+        plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
         const float invs = inv * (float)(1u << (32 - BITS));
         const uint32_t p = p0 + g;
         const uint32_t k1 = mix32(p ^ pt.seed_a);
         const uint32_t k2 = mix32(k1 + pt.seed_c);
-        if (live && sub == 0) reinterpret_cast<float2*>(pt.meta)[p] = make_float2(delta, Delta);
+        if (live && sub == 0) meta_store(pt.meta, p, delta, Delta, kC16<T>);
         wave_sync();                                           // the zeroed words precede the ORs below
 
         // ---- Quant + packing: the VEC codes of a row are OR-ed into their word (a row part never straddles words)
@@ -1059,18 +1137,17 @@ __global__ void __launch_bounds__(64) compress_lane(LaneArgs a) {
             mn = fminf(mn, v);
             mx = fmaxf(mx, v);
         }
-        const float lfc = Elem<T>::round(mean_of(S, a.HW));
+        const float lfc = lfc_round<T>(mean_of(S, a.HW), kC16<T>);
         const float hmn = mn - lfc, hmx = mx - lfc;
-        float Delta, inv;
-        plane_scale(hmn, hmx, Lf, Delta, inv);
-        const float delta = hmn;
+        float delta, Delta, inv;
+        plane_scale_any(hmn, hmx, Lf, kC16<T>, delta, Delta, inv);
         const float invs = inv * (float)(1u << (32 - BITS));
         const uint32_t p = p0 + lane;
         const uint32_t k1 = mix32(p ^ pt.seed_a);
         const uint32_t k2 = mix32(k1 + pt.seed_c);
         if (live) {
-            Elem<T>::store(static_cast<T*>(pt.lfc), p, lfc);
-            reinterpret_cast<float2*>(pt.meta)[p] = make_float2(delta, Delta);
+            lfc_store<T>(pt.lfc, p, lfc, kC16<T>);
+            meta_store(pt.meta, p, delta, Delta, kC16<T>);
         }
 
         // ---- residual, Quant of Eq. (quantization), packing: whole words, then the ragged last one
@@ -1213,9 +1290,9 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
                     }
                 cnt = rows * units * 4;
             }
-            const float lfc = Elem<T>::round(mean_of(S, cnt));
+            const float lfc = lfc_round<T>(mean_of(S, cnt), kC16<T>);
             lfcs[t] = lfc;
-            Elem<T>::store(static_cast<T*>(pt.lfc), (size_t)p * a.nb + t, lfc);
+            lfc_store<T>(pt.lfc, (size_t)p * a.nb + t, lfc, kC16<T>);
         }
         if constexpr (NW == 1) wave_sync(); else lds_barrier();
 
@@ -1242,13 +1319,12 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
         }
 
         // ---- scale of Eq. (quantization), keys, meta
-        float Delta, inv;
-        plane_scale(mn, mx, Lf, Delta, inv);
-        const float delta = mn;
+        float delta, Delta, inv;
+        plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
         const float invs = inv * (float)(1u << (32 - BITS));
         const uint32_t k1 = mix32(p ^ pt.seed_a);
         const uint32_t k2 = mix32(k1 + pt.seed_c);
-        if (tid == 0) reinterpret_cast<float2*>(pt.meta)[p] = make_float2(delta, Delta);
+        if (tid == 0) meta_store(pt.meta, p, delta, Delta, kC16<T>);
 
         // ---- Quant + packing: a unit is two element pairs = 4 codes (one byte for b = 2, a word for b = 8)
         {
@@ -1295,7 +1371,7 @@ __global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) {
     const uint32_t p = blockIdx.x;
     const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
     const T* xp = static_cast<const T*>(pt.x) + (size_t)p * a.HW;
-    T* lfcp = static_cast<T*>(pt.lfc) + (size_t)p * a.nb;
+    const size_t lfc0 = (size_t)p * a.nb;      // this plane's first LFC element
 
     // pass A: block means; block min/max of the residual follow from the
     // block min/max of x because x -> fl(x - m) is monotone
@@ -1311,8 +1387,8 @@ __global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) {
                 const float v = Elem<T>::load(xp, (size_t)r * a.W + c);
                 S += (double)v; xmin = fminf(xmin, v); xmax = fmaxf(xmax, v); ++cnt;
             }
-        const float lfc = Elem<T>::round((float)(S / (double)cnt));
-        Elem<T>::store(lfcp, blk, lfc);
+        const float lfc = lfc_round<T>((float)(S / (double)cnt), kC16<T>);
+        lfc_store<T>(pt.lfc, lfc0 + blk, lfc, kC16<T>);
         mn = fminf(mn, xmin - lfc);
         mx = fmaxf(mx, xmax - lfc);
     }
@@ -1326,12 +1402,12 @@ __global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) {
         __syncthreads();
     }
     if (tid == 0) {
-        float Delta, inv;
-        plane_scale(red_min[0], red_max[0], Lf, Delta, inv);
-        reinterpret_cast<float2*>(pt.meta)[p] = make_float2(red_min[0], Delta);
+        float delta, Delta, inv;
+        plane_scale_any(red_min[0], red_max[0], Lf, kC16<T>, delta, Delta, inv);
+        meta_store(pt.meta, p, delta, Delta, kC16<T>);
         const uint32_t k1 = mix32(p ^ pt.seed_a);
         const uint32_t k2 = mix32(k1 + pt.seed_c);
-        sh_params = make_float4(red_min[0], inv * 65536.0f, __uint_as_float(k1), __uint_as_float(k2));
+        sh_params = make_float4(delta, inv * 65536.0f, __uint_as_float(k1), __uint_as_float(k2));
     }
     __syncthreads();
     const float delta = sh_params.x, inv16 = sh_params.y;
@@ -1345,7 +1421,7 @@ __global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) {
             if (i >= a.HW) break;
             const uint32_t r = i / a.W, c = i - r * a.W;
             // written by this workgroup in pass A; visible after the barrier above
-            const float lfc = Elem<T>::load(lfcp, (r / a.B) * a.LW + c / a.B);
+            const float lfc = lfc_load<T>(pt.lfc, lfc0 + (r / a.B) * a.LW + c / a.B, kC16<T>);
             const float h = Elem<T>::load(xp, i) - lfc;
             const uint32_t w = pair_word(k1 + (i >> 1) * kWeyl, k2);
             const uint32_t q = (i & 1u) ? quant<1>(h, delta, inv16, w) : quant<0>(h, delta, inv16, w);
@@ -1422,10 +1498,16 @@ __device__ __forceinline__ void stage_packed(const DecArgs& a, const DecPtrs& pt
     } else {
         for (uint32_t i = tid; i < nw; i += kThreads) s_codes[i] = src[i];
     }
-    for (uint32_t i = tid; i < Gc; i += kThreads) s_meta[i] = reinterpret_cast<const float2*>(pt.meta)[p0 + i];
+    for (uint32_t i = tid; i < Gc; i += kThreads) s_meta[i] = meta_load(pt.meta, p0 + i, kC16<T>);
     const uint32_t nl = Gc * a.nb;
-    const T* lsrc = static_cast<const T*>(pt.lfc) + (size_t)p0 * a.nb;
-    for (uint32_t i = tid; i < nl; i += kThreads) s_lfc[i] = lsrc[i];
+    if (sizeof(T) == 4 && kC16<T>) {
+        // bfloat16 H^L of an fp32 map: widened here, so that the streaming loops read floats as ever
+        const uint16_t* lsrc = static_cast<const uint16_t*>(pt.lfc) + (size_t)p0 * a.nb;
+        for (uint32_t i = tid; i < nl; i += kThreads) reinterpret_cast<float*>(s_lfc)[i] = bf16_bits_to_float(lsrc[i]);
+    } else {
+        const T* lsrc = static_cast<const T*>(pt.lfc) + (size_t)p0 * a.nb;
+        for (uint32_t i = tid; i < nl; i += kThreads) s_lfc[i] = lsrc[i];
+    }
     lds_barrier();
 }
 
@@ -1604,14 +1686,14 @@ __global__ void __launch_bounds__(kThreads) decompress_scalar(DecArgs a) {
     constexpr uint32_t CPW = 32 / BITS;
     constexpr uint32_t Lq = (1u << BITS) - 1u;
     const uint32_t p = blockIdx.x;
-    const float2 dd = reinterpret_cast<const float2*>(pt.meta)[p];
-    const T* lfcp = static_cast<const T*>(pt.lfc) + (size_t)p * a.nb;
+    const float2 dd = meta_load(pt.meta, p, kC16<T>);
+    const size_t lfc0 = (size_t)p * a.nb;
     const uint32_t* cp = pt.codes + (size_t)p * a.WPP;
     T* out = static_cast<T*>(pt.xhat) + (size_t)p * a.HW;
     for (uint32_t i = threadIdx.x; i < a.HW; i += kThreads) {
         const uint32_t r = i / a.W, c = i - r * a.W;
         const uint32_t q = (cp[i / CPW] >> ((i % CPW) * BITS)) & Lq;
-        const float lfc = Elem<T>::load(lfcp, (r / a.B) * a.LW + c / a.B);
+        const float lfc = lfc_load<T>(pt.lfc, lfc0 + (r / a.B) * a.LW + c / a.B, kC16<T>);
         Elem<T>::store(out, i, dequant(q, dd.y, dd.x, lfc));
     }
 }
@@ -1639,8 +1721,8 @@ __global__ void __launch_bounds__(64) decompress_lane(DecArgs a) {
         const uint32_t p0 = round * 64u;
         const uint32_t Gc = min(64u, a.P - p0);
         const uint32_t p = lane < Gc ? p0 + lane : p0;        // lanes past the last plane redo plane p0 (never stored)
-        const float2 dd = reinterpret_cast<const float2*>(pt.meta)[p];
-        const float lfc = Elem<T>::load(static_cast<const T*>(pt.lfc), p);
+        const float2 dd = meta_load(pt.meta, p, kC16<T>);
+        const float lfc = lfc_load<T>(pt.lfc, p, kC16<T>);
         const uint32_t* cp = pt.codes + (size_t)p * a.WPP;
         const uint32_t wfull = a.HW / CPW;
         for (uint32_t w = 0; w < wfull; ++w) {
@@ -1676,7 +1758,7 @@ size_t align16(size_t v) { return (v + 15u) & ~(size_t)15u; }
 
 int make_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt, Layout* L) {
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4 && b != 8)) return DIVISION_EINVAL;
-    if (dt != DIVISION_F32 && dt != DIVISION_BF16) return DIVISION_EINVAL;
+    if (dt != DIVISION_F32 && dt != DIVISION_BF16 && dt != DIVISION_F32_C16) return DIVISION_EINVAL;
     const uint64_t lim31 = 0x7fffffffull;
     if ((uint64_t)N > lim31 || (uint64_t)C > lim31 || (uint64_t)H > lim31 || (uint64_t)W > lim31) return DIVISION_ERANGE;
     L->P = (uint64_t)N * (uint64_t)C;
@@ -1687,13 +1769,14 @@ int make_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt
     L->nb = L->LH * L->LW;
     const uint64_t cpw = 32 / b;
     L->WPP = (L->HW + cpw - 1) / cpw;
-    const size_t es = dt == DIVISION_BF16 ? 2 : 4;
+    const size_t lfc_es = dt == DIVISION_F32 ? 4 : 2;          // H^L: element type of x, bfloat16 in the cached-as-bf16 mode
+    const size_t meta_es = dt == DIVISION_F32_C16 ? 4 : 8;      // (delta, Delta) per plane
     L->codes_off = 0;
     L->codes_bytes = (size_t)(4 * L->P * L->WPP);
     L->meta_off = align16(L->codes_bytes);
-    L->meta_bytes = (size_t)(8 * L->P);
+    L->meta_bytes = (size_t)(meta_es * L->P);
     L->lfc_off = align16(L->meta_off + L->meta_bytes);
-    L->lfc_bytes = (size_t)(es * L->P * L->nb);
+    L->lfc_bytes = (size_t)(lfc_es * L->P * L->nb);
     L->total = align16(L->lfc_off + L->lfc_bytes);
     return DIVISION_OK;
 }
@@ -2061,6 +2144,16 @@ int plan_decompress(const Layout& L, int64_t H, int64_t W, int B, size_t es, con
     return 2;
 }
 
+// calls f(T{}, std::integral_constant<int, BITS>{}) for the element / cache type and code width of a call
+template <typename F>
+hipError_t with_type_bits(division_dtype dt, int b, F&& f) {
+    auto bits = [&](auto tag) -> hipError_t {
+        return b == 2 ? f(tag, std::integral_constant<int, 2>{}) : b == 4 ? f(tag, std::integral_constant<int, 4>{})
+                                                                          : f(tag, std::integral_constant<int, 8>{});
+    };
+    return dt == DIVISION_F32 ? bits(float{}) : dt == DIVISION_BF16 ? bits(bf16_t{}) : bits(f32c16_t{});
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ C ABI
@@ -2120,61 +2213,40 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
         RegsArgs ra{};
         ItemsArgs ia{};
         LaneArgs la{};
+        AnyArgs g{};
         size_t lds = 0;
         uint32_t grid = 0;
         int vec = 1, nt = 64, nw = 1;
-        hipError_t err;
-        if (plan_regs(L, H, W, B, es, xa, &ra, &grid, &lds, &nw)) {
-            ra.tab = tab; ra.rg = rg;
-            if (dt == DIVISION_F32)
-                err = b == 2 ? launch_regs<float, 2>(B, nw, ra, dim3(grid, cnt), lds, st) : b == 4 ? launch_regs<float, 4>(B, nw, ra, dim3(grid, cnt), lds, st) : launch_regs<float, 8>(B, nw, ra, dim3(grid, cnt), lds, st);
-            else
-                err = b == 2 ? launch_regs<bf16_t, 2>(B, nw, ra, dim3(grid, cnt), lds, st) : b == 4 ? launch_regs<bf16_t, 4>(B, nw, ra, dim3(grid, cnt), lds, st) : launch_regs<bf16_t, 8>(B, nw, ra, dim3(grid, cnt), lds, st);
-        } else if (plan_lane(L, es, xa, &la, &grid, &lds)) {
-            la.tab = tab; la.rg = rg;
-            void (*kern)(LaneArgs);
-            if (dt == DIVISION_F32) kern = b == 2 ? compress_lane<float, 2> : b == 4 ? compress_lane<float, 4> : compress_lane<float, 8>;
-            else kern = b == 2 ? compress_lane<bf16_t, 2> : b == 4 ? compress_lane<bf16_t, 4> : compress_lane<bf16_t, 8>;
-            hipLaunchKernelGGL(kern, dim3(grid, cnt), dim3(64), lds, st, la);
-            err = hipGetLastError();
-        } else if (plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) {
-            ia.tab = tab; ia.rg = rg;
-            if (dt == DIVISION_F32)
-                err = b == 2 ? launch_items<float, 2>(B, vec, ia, dim3(grid, cnt), lds, st) : b == 4 ? launch_items<float, 4>(B, vec, ia, dim3(grid, cnt), lds, st) : launch_items<float, 8>(B, vec, ia, dim3(grid, cnt), lds, st);
-            else
-                err = b == 2 ? launch_items<bf16_t, 2>(B, vec, ia, dim3(grid, cnt), lds, st) : b == 4 ? launch_items<bf16_t, 4>(B, vec, ia, dim3(grid, cnt), lds, st) : launch_items<bf16_t, 8>(B, vec, ia, dim3(grid, cnt), lds, st);
-        } else if (plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
-            wa.tab = tab; wa.rg = rg;
+        enum { REGS, LANE, ITEMS, WAVE, TILE, ANY } kind;
+        if (plan_regs(L, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
+        else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
+        else if (plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
+        else if (plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
+            kind = WAVE; wa.tab = tab; wa.rg = rg;
 #ifdef DIVISION_EXPERIMENT
             wa.skip = getenv("DIVISION_SKIP") ? (uint32_t)atoi(getenv("DIVISION_SKIP")) : 0u;
 #endif
-            if (dt == DIVISION_F32)
-                err = b == 2 ? launch_wave<float, 2>(B, vec, wa, dim3(grid, cnt), lds, st) : b == 4 ? launch_wave<float, 4>(B, vec, wa, dim3(grid, cnt), lds, st) : launch_wave<float, 8>(B, vec, wa, dim3(grid, cnt), lds, st);
-            else
-                err = b == 2 ? launch_wave<bf16_t, 2>(B, vec, wa, dim3(grid, cnt), lds, st) : b == 4 ? launch_wave<bf16_t, 4>(B, vec, wa, dim3(grid, cnt), lds, st) : launch_wave<bf16_t, 8>(B, vec, wa, dim3(grid, cnt), lds, st);
-        } else if (plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) {
-            a.tab = tab; a.rg = rg;
-            if (dt == DIVISION_F32)
-                err = b == 2 ? launch_tile<float, 2>(B, vec, a, dim3(grid, cnt), lds, st) : b == 4 ? launch_tile<float, 4>(B, vec, a, dim3(grid, cnt), lds, st) : launch_tile<float, 8>(B, vec, a, dim3(grid, cnt), lds, st);
-            else
-                err = b == 2 ? launch_tile<bf16_t, 2>(B, vec, a, dim3(grid, cnt), lds, st) : b == 4 ? launch_tile<bf16_t, 4>(B, vec, a, dim3(grid, cnt), lds, st) : launch_tile<bf16_t, 8>(B, vec, a, dim3(grid, cnt), lds, st);
-        } else {
-            AnyArgs g{};
+        } else if (plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) { kind = TILE; a.tab = tab; a.rg = rg; }
+        else {
+            kind = ANY;
             g.tab = tab; g.rg = rg;
             g.P = (uint32_t)L.P; g.H = (uint32_t)H; g.W = (uint32_t)W; g.HW = (uint32_t)L.HW;
             g.LH = (uint32_t)L.LH; g.LW = (uint32_t)L.LW; g.nb = (uint32_t)L.nb; g.WPP = (uint32_t)L.WPP; g.B = (uint32_t)B;
-            const dim3 gr((uint32_t)L.P, cnt), bl(kThreads);
-            if (dt == DIVISION_F32) {
-                if (b == 2) hipLaunchKernelGGL((compress_any<float, 2>), gr, bl, 0, st, g);
-                else if (b == 4) hipLaunchKernelGGL((compress_any<float, 4>), gr, bl, 0, st, g);
-                else hipLaunchKernelGGL((compress_any<float, 8>), gr, bl, 0, st, g);
-            } else {
-                if (b == 2) hipLaunchKernelGGL((compress_any<bf16_t, 2>), gr, bl, 0, st, g);
-                else if (b == 4) hipLaunchKernelGGL((compress_any<bf16_t, 4>), gr, bl, 0, st, g);
-                else hipLaunchKernelGGL((compress_any<bf16_t, 8>), gr, bl, 0, st, g);
-            }
-            err = hipGetLastError();
+            grid = (uint32_t)L.P;
         }
+        const dim3 gd(grid, cnt);
+        const hipError_t err = with_type_bits(dt, b, [&](auto tag, auto bits) -> hipError_t {
+            using T = decltype(tag);
+            constexpr int BITS = decltype(bits)::value;
+            switch (kind) {
+                case REGS: return launch_regs<T, BITS>(B, nw, ra, gd, lds, st);
+                case ITEMS: return launch_items<T, BITS>(B, vec, ia, gd, lds, st);
+                case WAVE: return launch_wave<T, BITS>(B, vec, wa, gd, lds, st);
+                case TILE: return launch_tile<T, BITS>(B, vec, a, gd, lds, st);
+                case LANE: hipLaunchKernelGGL((compress_lane<T, BITS>), gd, dim3(64), lds, st, la); return hipGetLastError();
+                default: hipLaunchKernelGGL((compress_any<T, BITS>), gd, dim3(kThreads), 0, st, g); return hipGetLastError();
+            }
+        });
         if (err != hipSuccess) return DIVISION_EHIP;
     }
     return DIVISION_OK;
@@ -2211,23 +2283,14 @@ int division_decompress_batch(int count, const void* const* packed, void* const*
         const int kind = plan_decompress(L, H, W, B, es, reinterpret_cast<const void*>(all_out ? all_out : 16), &a, &grid);
         for (int i = 0; i < cnt; ++i) { a.tab.pk[i] = packed[i0 + i]; a.tab.xhat[i] = xhat[i0 + i]; }
         a.rg = rg;
-        void (*kern)(DecArgs);
-        if (kind == 0) {
-            if (dt == DIVISION_F32) kern = b == 2 ? decompress_rowvec<float, 2> : b == 4 ? decompress_rowvec<float, 4> : decompress_rowvec<float, 8>;
-            else kern = b == 2 ? decompress_rowvec<bf16_t, 2> : b == 4 ? decompress_rowvec<bf16_t, 4> : decompress_rowvec<bf16_t, 8>;
-        } else if (kind == 3) {
-            if (dt == DIVISION_F32) kern = b == 2 ? decompress_table<float, 2> : b == 4 ? decompress_table<float, 4> : decompress_table<float, 8>;
-            else kern = b == 2 ? decompress_table<bf16_t, 2> : b == 4 ? decompress_table<bf16_t, 4> : decompress_table<bf16_t, 8>;
-        } else if (kind == 1) {
-            if (dt == DIVISION_F32) kern = b == 2 ? decompress_flat<float, 2> : b == 4 ? decompress_flat<float, 4> : decompress_flat<float, 8>;
-            else kern = b == 2 ? decompress_flat<bf16_t, 2> : b == 4 ? decompress_flat<bf16_t, 4> : decompress_flat<bf16_t, 8>;
-        } else if (kind == 4) {
-            if (dt == DIVISION_F32) kern = b == 2 ? decompress_lane<float, 2> : b == 4 ? decompress_lane<float, 4> : decompress_lane<float, 8>;
-            else kern = b == 2 ? decompress_lane<bf16_t, 2> : b == 4 ? decompress_lane<bf16_t, 4> : decompress_lane<bf16_t, 8>;
-        } else {
-            if (dt == DIVISION_F32) kern = b == 2 ? decompress_scalar<float, 2> : b == 4 ? decompress_scalar<float, 4> : decompress_scalar<float, 8>;
-            else kern = b == 2 ? decompress_scalar<bf16_t, 2> : b == 4 ? decompress_scalar<bf16_t, 4> : decompress_scalar<bf16_t, 8>;
-        }
+        void (*kern)(DecArgs) = nullptr;
+        with_type_bits(dt, b, [&](auto tag, auto bits) -> hipError_t {
+            using T = decltype(tag);
+            constexpr int BITS = decltype(bits)::value;
+            kern = kind == 0 ? decompress_rowvec<T, BITS> : kind == 3 ? decompress_table<T, BITS>
+                 : kind == 1 ? decompress_flat<T, BITS> : kind == 4 ? decompress_lane<T, BITS> : decompress_scalar<T, BITS>;
+            return hipSuccess;
+        });
         // LDS of the streaming kernels: staged codes, meta and LFC of G planes (+ the block table)
         size_t lds = 0;
         if (kind == 4) lds = 4ull * (64ull * L.HW + 4);
@@ -2251,7 +2314,7 @@ int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, 
     const int rc = make_layout(N, C, H, W, B, b, (int)dt, &L);
     if (rc != DIVISION_OK) return rc;
     const size_t es = dt == DIVISION_BF16 ? 2 : 4;
-    const char* tn = dt == DIVISION_BF16 ? "bf16_t" : "float";
+    const char* tn = dt == DIVISION_BF16 ? "bf16_t" : dt == DIVISION_F32_C16 ? "f32c16_t" : "float";
     int n;
     if (direction == 0) {
         TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;

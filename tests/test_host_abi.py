@@ -108,3 +108,13 @@ def test_mask_bytes_and_host_side_errors():
     assert L.division_relu_forward(a16, 0, 0, a16, a16 + 512, 0, None) == 0
     assert L.division_dropout_forward(a16, 8, 1, 0.5, 1, None, a16 + 512, 4, None) == 1
     assert L.division_mask_backward(a16 + 512, 0, a16, 8, 0, a16, None) == 2
+
+
+def test_layout_of_the_bfloat16_cached_mode_matches_oracle():
+    import torch
+    for s in SHAPES:
+        assert pkg.division_packed_bytes(*s, dtype=torch.float32, c16=True) == oracle.packed_bytes(*s, oracle.F32_C16)
+        assert pkg.division_packed_layout(*s, dtype=torch.float32, c16=True) == oracle.packed_layout(*s, oracle.F32_C16)
+    with pytest.raises(TypeError):
+        pkg.division_packed_bytes(1, 1, 4, 4, 2, 2, dtype=torch.bfloat16, c16=True)
+    assert pkg.lib().division_packed_bytes(1, 1, 4, 4, 2, 2, 3) == 0           # unknown dtype code
