@@ -268,7 +268,7 @@ def main() -> int:
 
     def kname(d, g):
         i = g[0]
-        return pkg.division_kernel_name(d, shapes[i], host[i][1].B, host[i][1].b, dtypes[i])
+        return pkg.division_kernel_name(d, shapes[i], host[i][1].B, host[i][1].b, dtypes[i], c16=args.c16)
 
     def run_step(launches, s: int, timed_group=None, events=None):
         for d, g in launches:

@@ -183,11 +183,12 @@ def division_decompress_batch(packed, shape, B: int, b: int, dtype=torch.float32
     return out
 
 
-def division_kernel_name(direction: int, shape, B: int, b: int, dtype=torch.float32, data_ptr: int = 0) -> str:
+def division_kernel_name(direction: int, shape, B: int, b: int, dtype=torch.float32, data_ptr: int = 0,
+                         c16: bool = False) -> str:
     """Name of the kernel instance a call would launch (direction 0 = compress, 1 = decompress)."""
     buf = ctypes.create_string_buffer(128)
     N, C, H, W = shape
-    rc = lib().division_kernel_name(direction, data_ptr or None, N, C, H, W, _dt(dtype), B, b, buf, 128)
+    rc = lib().division_kernel_name(direction, data_ptr or None, N, C, H, W, _dt(dtype, c16), B, b, buf, 128)
     if rc:
         raise DivisionError(rc, "division_kernel_name")
     return buf.value.decode()
