@@ -8,16 +8,20 @@
 // Compile with -ffp-contract=off: the codec's fp32 steps are single IEEE
 // operations (sub, mul, add), never fused, so that codes are reproducible.
 //
-// Work decomposition (one GPU, planes are independent):
-//   * A workgroup owns a chunk of G consecutive (sample, channel) planes.
-//   * compress_tile: the chunk is read from HBM exactly once with 16-byte
-//     coalesced loads into LDS; block means, residuals, the plane min/max and
-//     the quantisation all work out of LDS; the packed words, (delta, Delta)
-//     and the LFC are written once.  No intermediate tensor touches HBM.
-//   * decompress_*: pure streaming, one packed read and one 16-byte store per
-//     four reconstructed elements.
-//   * compress_any / decompress_scalar: slow fall-backs for block sizes and
-//     plane sizes the tiled kernels do not cover.
+// Work decomposition (one GPU; (sample, channel) planes are independent and every element of
+// x is read from HBM exactly once, no intermediate tensor touches HBM):
+//   compress_regs    planes of 2K-3K / 8K-13K elements (56x56, 112x112): one plane per workgroup
+//                    of one / four wavefronts, the plane stays in registers from load to codes
+//   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes): a lane per
+//                    pooling item, loaded straight from global memory, DPP reductions
+//   compress_lane    one-block planes with an odd element count (7x7): a lane per plane
+//   compress_wave    other planes up to 17 KB: one wavefront per chunk of planes staged in LDS
+//   compress_tile    other planes up to 156 KB: four wavefronts per chunk staged in LDS
+//   compress_any     everything else (block sizes other than 4 and 8, giant planes): slow
+//   decompress_rowvec / _table / _flat / _lane / _scalar: streaming, the packed slice of a
+//                    workgroup staged in LDS, one 16-byte non-temporal store per four elements
+// Every kernel takes a table of up to 8 maps of one shape (blockIdx.y picks the map).
+// Element / cache types: float, bf16_t, f32c16_t (fp32 map, tuple cached as bfloat16).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
@@ -559,9 +563,6 @@ struct WaveArgs {
     uint32_t ippp_log2;  // log2(ippp) when ippp <= 64
     uint32_t vec_load;   // chunk starts are 16-byte aligned
     FastDiv d_ipr, d_wpp;
-#ifdef DIVISION_EXPERIMENT
-    uint32_t skip;       // timing experiments only: bit 0 skips pooling, bit 1 skips quantisation
-#endif
 };
 
 // (float)(S / cnt) for a small positive integer cnt, the way the reference
@@ -727,11 +728,8 @@ __device__ __forceinline__ void chunk_to_lds(const ChunkRegs& r, float* xs, uint
 // different phases in flight, so that the HBM loads of some overlap the
 // arithmetic of others (measured faster than persistent wavefronts that
 // prefetch their next chunk, which ran in lock step).
-#ifndef DIVISION_WAVE_ATTR
-#define DIVISION_WAVE_ATTR
-#endif
 template <typename T, int BITS, int B, int VEC>
-__global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs a) {
+__global__ void __launch_bounds__(64) compress_wave(WaveArgs a) {
     extern __shared__ float4 smem4[];
     float4* params = smem4;                                   // [G] (delta, inv scaled, k1, k2)
     float* xs = reinterpret_cast<float*>(smem4 + a.G);        // [G*HW] x, later the residual h
@@ -770,18 +768,11 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
             const uint32_t sub = lane & (S - 1);
             const bool fullrows = (a.H % B) == 0;
             const ItemGeom geom0 = item_geom<B, VEC>(a, sub);      // the lane's item when a plane fits one round
-#if !defined(DIVISION_STRIP1)
-#ifdef DIVISION_EXPERIMENT
-            if (!(a.skip & 8u))
-#endif
             for (uint32_t g0 = 0; g0 < Gc; g0 += ppr) {
                 const uint32_t g = g0 + gsub;
                 const bool live = g < Gc;
                 const size_t lfc_plane = (size_t)(p0 + g) * a.nb;      // the plane's first LFC element
                 float mn = __builtin_inff(), mx = -__builtin_inff();
-#ifdef DIVISION_EXPERIMENT
-                if (a.skip & 1u) { mn = 0.f; mx = 1.f; } else
-#endif
                 if (small) {
                     if (fullrows) pool_item<T, B, VEC, true>(xs, a, pt.lfc, lfc_plane, g, geom0, live, mn, mx);
                     else pool_item<T, B, VEC, false>(xs, a, pt.lfc, lfc_plane, g, geom0, live, mn, mx);
@@ -795,7 +786,6 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
                 group_minmax(S, mn, mx);
                 if (live && sub == 0) params[g] = make_float4(mn, mx, 0.0f, 0.0f);
             }
-#endif
         }
         wave_sync();
 
@@ -821,18 +811,6 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
             const uint32_t tailw = nwords & 63u;
             const bool pair_tail = tailw != 0 && tailw * PPW <= 64;
             const uint32_t nfull = pair_tail ? nwords - tailw : nwords;
-#ifdef DIVISION_EXPERIMENT
-            if (a.skip & 2u) {
-                for (uint32_t wi = lane; wi < nwords; wi += 64) {
-                    const uint32_t g = fdiv(wi, a.d_wpp);
-                    const uint32_t k = wi - g * a.WPP;
-                    if (!(a.skip & 32u) || k == 0)
-                        pt.codes[(size_t)(p0 + g) * a.WPP + k] = (a.skip & 4u) ? 0u : __float_as_uint(xs[g * a.HW + k * CPW]);
-                }
-                return;
-            }
-#endif
-#if !defined(DIVISION_STRIP3)
             for (uint32_t wi = lane; wi < nfull; wi += 64) {
                 const uint32_t g = fdiv(wi, a.d_wpp);
                 const uint32_t k = wi - g * a.WPP;
@@ -888,7 +866,6 @@ __global__ void __launch_bounds__(64) DIVISION_WAVE_ATTR compress_wave(WaveArgs 
                 if constexpr (PPW == 8) part |= __builtin_amdgcn_update_dpp(0, (int)part, kDppHalfMirror, 0xf, 0xf, false);
                 if (act && pw == 0) pt.codes[(size_t)(p0 + g) * a.WPP + k] = part;
             }
-#endif
         }
     }
 }
@@ -1189,7 +1166,6 @@ struct RegsArgs {
     uint32_t q4;         // units (4 consecutive elements) per plane = H*W/4
     uint32_t w4;         // units per row = W/4
     uint32_t ppw;        // planes a workgroup handles one after the other
-    uint32_t stag_n, stag_shift, stag_iters;   // start-up stagger (see compress_regs)
     FastDiv d_w4, d_LW;
 };
 
@@ -1227,13 +1203,6 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
     }
     if (tid == 0) lfcs[a.nb] = __builtin_nanf("");
     const bool full_blocks = (a.H % B) == 0 && (a.W % B) == 0;
-
-    // Start-up stagger: the workgroups resident first all load at once, are
-    // served evenly and so finish loading together, then all compute while the
-    // memory idles.  Half of that first wave of workgroups starts late, which
-    // puts the two halves in opposite phases.
-    if (blockIdx.y == 0 && blockIdx.x < a.stag_n && ((blockIdx.x >> a.stag_shift) & 1u))
-        for (uint32_t i = 0; i < a.stag_iters; ++i) __builtin_amdgcn_s_sleep(127);
 
     const uint32_t pbeg = blockIdx.x * a.ppw;
     const uint32_t pend = min(a.P, pbeg + a.ppw);
@@ -1796,24 +1765,11 @@ Regions make_regions(const Layout& L) {
     return rg;
 }
 
-// tuning of the compress kernels: nt = 64 enables the one-wavefront kernel; `lds`
-// is the preferred LDS footprint of one wavefront's chunk (small chunks = many
-// wavefronts per CU), a single plane of up to kWavePlaneMax bytes is taken
-// whatever `lds` says.  DIVISION_TUNE="nt=256,lds=16384" overrides the defaults
-// for experiments.
+// Preferred LDS footprint of one wavefront's chunk in compress_wave (small chunks = many wavefronts
+// per CU; 8.7 KB measured best over the ResNet-50 set); a single plane of up to kWavePlaneMax bytes is
+// taken whatever the preference says.
+constexpr uint32_t kWaveChunkLds = 8704u;
 constexpr uint32_t kWavePlaneMax = 17u << 10;
-struct Tune { int nt; uint32_t lds; };
-Tune tile_tune() {
-    static Tune t = [] {
-        Tune v{64, 8704u};
-        if (const char* e = getenv("DIVISION_TUNE")) {
-            int nt = 0; unsigned lds = 0;
-            if (sscanf(e, "nt=%d,lds=%u", &nt, &lds) == 2 && (nt == 64 || nt == 256) && lds >= 1024) { v.nt = nt; v.lds = lds; }
-        }
-        return v;
-    }();
-    return t;
-}
 
 int num_cus() {
     static int n = [] {
@@ -1868,8 +1824,7 @@ hipError_t launch_wave(int B, int vec, const WaveArgs& a, dim3 grid, size_t lds,
 // Fills the plane-in-registers compress plan; false when the shape is not covered.
 bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* x,
                RegsArgs* a, uint32_t* grid, size_t* lds, int* nw_out) {
-    static const bool disabled = getenv("DIVISION_NO_REGS") != nullptr;      // experiments only
-    if (disabled || (B != 4 && B != 8) || W % 4 != 0) return false;
+    if ((B != 4 && B != 8) || W % 4 != 0) return false;
     if (((uintptr_t)x % (4 * es)) != 0) return false;
     const uint64_t q4 = L.HW / 4;
     int nw;
@@ -1881,15 +1836,9 @@ bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
     a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
     a->LH = (uint32_t)L.LH; a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP;
     a->q4 = (uint32_t)q4; a->w4 = (uint32_t)w4;
-    static const int ppw_env = getenv("DIVISION_PPW") ? atoi(getenv("DIVISION_PPW")) : 0;      // experiments only
-    a->ppw = ppw_env > 0 ? (uint32_t)ppw_env : 1u;
+    a->ppw = 1;      // one plane per workgroup measured best (more workgroups, better balance)
     a->d_w4 = make_fastdiv((uint32_t)w4);
     a->d_LW = make_fastdiv((uint32_t)L.LW);
-    a->stag_n = 0; a->stag_shift = 0; a->stag_iters = 0;
-    if (const char* e = getenv("DIVISION_STAGGER")) {      // experiments only: "n,shift,iters"
-        unsigned n = 0, sh = 0, it = 0;
-        if (sscanf(e, "%u,%u,%u", &n, &sh, &it) == 3 && sh < 32 && it <= 64) { a->stag_n = n; a->stag_shift = sh; a->stag_iters = it; }
-    }
     *lds = 8ull * kRegUnits * nt + 4ull * ((L.nb + 1 + 3) & ~3ull) + 8ull * nw + 16;
     *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
     *nw_out = nw;
@@ -1911,13 +1860,11 @@ bool lane_shape(const Layout& L) { return L.nb == 1 && (L.HW & 1) == 1 && L.HW <
 
 // Fills the lane-per-plane compress plan; false when the shape is not covered.
 bool plan_lane(const Layout& L, size_t es, const void* x, LaneArgs* a, uint32_t* grid, size_t* lds) {
-    static const bool disabled = getenv("DIVISION_NO_LANE") != nullptr;      // experiments only
-    if (disabled || !lane_shape(L)) return false;
+    if (!lane_shape(L)) return false;
     a->P = (uint32_t)L.P; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP;
     a->nrounds = (uint32_t)((L.P + 63) / 64);
     a->vec_load = ((uintptr_t)x % 16) == 0;
-    static const int rpw_env = getenv("DIVISION_RPW") ? atoi(getenv("DIVISION_RPW")) : 0;      // experiments only
-    uint32_t rpw = rpw_env > 0 ? (uint32_t)rpw_env : 2u;
+    uint32_t rpw = 2;
     while (rpw > 1 && a->nrounds / rpw < 32u * (uint32_t)num_cus()) --rpw;
     a->rpw = rpw;
     *lds = 4ull * (64ull * L.HW + 4) + 16 * (es == 2 ? 1 : 0);
@@ -1928,8 +1875,7 @@ bool plan_lane(const Layout& L, size_t es, const void* x, LaneArgs* a, uint32_t*
 // Fills the items-from-global compress plan (small planes); false when the shape is not covered.
 bool plan_items(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* x,
                 ItemsArgs* a, uint32_t* grid, size_t* lds, int* vec_out) {
-    static const bool disabled = getenv("DIVISION_NO_ITEMS") != nullptr;      // experiments only
-    if (disabled || (B != 4 && B != 8) || W % 2 != 0) return false;
+    if ((B != 4 && B != 8) || W % 2 != 0) return false;
     const int vec = W % 4 == 0 ? 4 : 2;
     if (((uintptr_t)x % (vec * es)) != 0) return false;
     const uint64_t ipb = (uint64_t)B / vec;
@@ -1947,8 +1893,7 @@ bool plan_items(const Layout& L, int64_t H, int64_t W, int B, size_t es, const v
     a->ppr = (uint32_t)ppr;
     a->nrounds = (uint32_t)((L.P + ppr - 1) / ppr);
     a->d_ipr = make_fastdiv((uint32_t)ipr);
-    static const int rpw_env = getenv("DIVISION_RPW") ? atoi(getenv("DIVISION_RPW")) : 0;      // experiments only
-    uint32_t rpw = rpw_env > 0 ? (uint32_t)rpw_env : 2u;
+    uint32_t rpw = 2;
     while (rpw > 1 && a->nrounds / rpw < 32u * (uint32_t)num_cus()) --rpw;
     a->rpw = rpw;
     *lds = 4ull * ppr * L.WPP + 16;
@@ -1968,10 +1913,9 @@ hipError_t launch_items(int B, int vec, const ItemsArgs& a, dim3 grid, size_t ld
 
 bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, const void* x,
                WaveArgs* a, uint32_t* grid, size_t* lds, int* vec_out) {
-    const Tune tune = tile_tune();
-    if ((B != 4 && B != 8) || tune.nt != 64) return false;
+    if (B != 4 && B != 8) return false;
     const uint64_t per_plane = 4ull * L.HW + 16ull;
-    if (per_plane > kWavePlaneMax || tune.lds > 48u * 1024u) return false;
+    if (per_plane > kWavePlaneMax) return false;
     const int vec = (W % 4 == 0) ? 4 : (W % 2 == 0) ? 2 : 1;
     const uint32_t ipb = (uint32_t)B / (uint32_t)vec;
     const uint64_t slots = ((uint64_t)W + vec - 1) / vec;
@@ -1980,7 +1924,7 @@ bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
     uint64_t ippp = 1, lg = 0;
     if (ipp <= 64) { while (ippp < ipp) { ippp *= 2; ++lg; } }
     else ippp = (ipp + 63) / 64 * 64;
-    uint64_t Gmax = tune.lds / per_plane;
+    uint64_t Gmax = kWaveChunkLds / per_plane;
     if (Gmax < 1) Gmax = 1;
     if (Gmax > L.P) Gmax = L.P;
     const uint64_t unit = 16 / gcd_u64(16, L.HW * es);
@@ -2090,8 +2034,7 @@ int plan_decompress(const Layout& L, int64_t H, int64_t W, int B, size_t es, con
     const bool out_vec_aligned = ((uintptr_t)xhat % (4 * es)) == 0;
     const uint64_t target = 16ull * 4 * kThreads;      // elements per workgroup
     // one-block planes with an odd element count: a lane per plane, 64 planes per round
-    static const bool no_lane = getenv("DIVISION_NO_LANE") != nullptr;      // experiments only
-    if (!no_lane && lane_shape(L)) {
+    if (lane_shape(L)) {
         const uint32_t nrounds = (uint32_t)((L.P + 63) / 64);
         uint32_t rpw = 2;
         while (rpw > 1 && nrounds / rpw < 32u * (uint32_t)num_cus()) --rpw;
@@ -2223,9 +2166,6 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
         else if (plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
         else if (plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
             kind = WAVE; wa.tab = tab; wa.rg = rg;
-#ifdef DIVISION_EXPERIMENT
-            wa.skip = getenv("DIVISION_SKIP") ? (uint32_t)atoi(getenv("DIVISION_SKIP")) : 0u;
-#endif
         } else if (plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) { kind = TILE; a.tab = tab; a.rg = rg; }
         else {
             kind = ANY;
