@@ -17,17 +17,19 @@ from .binding import division_compress, division_decompress
 
 
 class _Cached:
-    __slots__ = ("packed", "shape", "dtype", "B", "b")
+    __slots__ = ("packed", "shape", "dtype", "B", "b", "c16")
 
-    def __init__(self, packed, shape, dtype, B, b):
-        self.packed, self.shape, self.dtype, self.B, self.b = packed, shape, dtype, B, b
+    def __init__(self, packed, shape, dtype, B, b, c16):
+        self.packed, self.shape, self.dtype, self.B, self.b, self.c16 = packed, shape, dtype, B, b, c16
 
 
 class division_saved_tensors(torch.autograd.graph.saved_tensors_hooks):
     """Context manager.  `seed` selects the stochastic-rounding streams: the k-th map cached inside
-    the context uses seed + k, so a training step is reproducible and no two maps share a stream."""
+    the context uses seed + k, so a training step is reproducible and no two maps share a stream.
+    `c16` caches fp32 maps in the paper's format (bfloat16 H^L, delta, Delta); bfloat16 maps are
+    cached in their own format either way."""
 
-    def __init__(self, B: int = 8, b: int = 2, seed: int = 0, min_elements: int = 1024):
+    def __init__(self, B: int = 8, b: int = 2, seed: int = 0, min_elements: int = 1024, c16: bool = False):
         self.cached_maps = 0        # maps cached so far
         self.cached_bytes = 0       # bytes of their packed buffers
         self.original_bytes = 0     # bytes the maps themselves would have held
@@ -38,15 +40,16 @@ class division_saved_tensors(torch.autograd.graph.saved_tensors_hooks):
                         and not isinstance(t, torch.nn.Parameter) and not (t.is_leaf and t.requires_grad))
             if not eligible:
                 return t
-            packed = division_compress(t.detach(), B, b, seed + self.cached_maps)
+            use16 = c16 and t.dtype == torch.float32
+            packed = division_compress(t.detach(), B, b, seed + self.cached_maps, c16=use16)
             self.cached_maps += 1
             self.cached_bytes += packed.numel()
             self.original_bytes += t.numel() * t.element_size()
-            return _Cached(packed, tuple(t.shape), t.dtype, B, b)
+            return _Cached(packed, tuple(t.shape), t.dtype, B, b, use16)
 
         def unpack(obj):
             if isinstance(obj, _Cached):
-                return division_decompress(obj.packed, obj.shape, obj.B, obj.b, obj.dtype)
+                return division_decompress(obj.packed, obj.shape, obj.B, obj.b, obj.dtype, c16=obj.c16)
             return obj
 
         super().__init__(pack, unpack)

@@ -399,20 +399,22 @@ def test_block_mean_on_rounding_midpoints():
 
 # ---------------------------------------------------------------- Algorithm 1 through autograd
 
-def test_saved_tensor_hook_caches_the_map_and_rebuilds_it_in_backward():
+@pytest.mark.parametrize("c16", [False, True])
+def test_saved_tensor_hook_caches_the_map_and_rebuilds_it_in_backward(c16):
     shape, B, b, seed = (4, 6, 28, 28), 8, 2, 91
+    odt = oracle.F32_C16 if c16 else oracle.F32
     x = _relu_normal(shape, 7300).to("cuda:0")
     w = torch.nn.Parameter(torch.linspace(0.5, 1.5, x.numel(), device="cuda:0").view(shape))
     h = x.clone().requires_grad_(True)
-    hooks = pkg.division_saved_tensors(B, b, seed)
+    hooks = pkg.division_saved_tensors(B, b, seed, c16=c16)
     with hooks:
         y = (h * 1.0) * w            # autograd saves the intermediate map (h * 1.0) for w's gradient
         loss = y.sum()
     loss.backward()
     assert hooks.cached_maps == 1
-    assert hooks.cached_bytes == pkg.division_packed_bytes(*shape, B, b)
+    assert hooks.cached_bytes == pkg.division_packed_bytes(*shape, B, b, c16=c16)
     # dL/dw is the reconstructed map itself, bit for bit what the oracle rebuilds from the oracle's tuple
-    ref = oracle.decompress(oracle.compress(x.cpu().numpy(), B, b, seed), shape, B, b)
+    ref = oracle.decompress(oracle.compress(x.cpu().numpy(), B, b, seed, odt), shape, B, b, odt)
     assert np.array_equal(w.grad.cpu().numpy(), ref)
     # dL/dh needs only w, which is a parameter and is never cached
     assert torch.equal(h.grad, w.detach())
