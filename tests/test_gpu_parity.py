@@ -556,3 +556,24 @@ def test_bfloat16_cached_mode_full_size_resnet50_set():
         total_pk += pk.numel()
         del pk, y
     assert total_in / total_pk > 12.0          # 12.2x against 11.5x with fp32 H^L and (delta, Delta)
+
+
+# ---------------------------------------------------------------- byte offsets beyond 4 GiB
+
+@pytest.mark.parametrize("shape,B,b", [((1400, 256, 56, 56), 8, 2), ((1100, 1024, 32, 32), 4, 4)])
+def test_full_size_maps_larger_than_4GiB(shape, B, b):
+    """1.1 G elements (4.5 GB of fp32): plane offsets in bytes and in elements pass 2^32 resp. 2^30;
+    the last planes are the ones a 32-bit index would send elsewhere."""
+    g = torch.Generator(device="cuda:0").manual_seed(77)
+    xd = torch.relu(torch.randn(shape, generator=g, device="cuda:0"))
+    x = xd.cpu().numpy()
+    seed = 0xB16B00B5
+    pk = pkg.division_compress(xd, B, b, seed)
+    torch.cuda.synchronize()
+    ref = oracle.compress(x, B, b, seed, threads=16)
+    assert np.array_equal(pk.cpu().numpy(), ref)
+    del ref
+    y = pkg.division_decompress(pk, shape, B, b)
+    torch.cuda.synchronize()
+    yr = oracle.decompress(pk.cpu().numpy(), shape, B, b, threads=16)
+    assert np.array_equal(y.cpu().numpy(), yr)
