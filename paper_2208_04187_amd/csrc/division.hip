@@ -894,8 +894,9 @@ struct ItemsArgs {
 // plane's min / max are DPP reductions and every lane ends up with its plane's
 // scale.  The item is quantised out of the registers; its VEC codes per row are
 // OR-ed into the round's packed words in LDS (cleared first, so pad bits stay
-// zero), which then leave as whole coalesced words.
-template <typename T, int BITS, int B, int VEC>
+// zero), which then leave as whole coalesced words.  R = rows an item holds: B, or 1 for
+// maps of a single row (1-D maps), whose items would otherwise carry B - 1 masked rows.
+template <typename T, int BITS, int B, int VEC, int R>
 __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
     constexpr int IPB = B / VEC;          // items per block (power of two)
     constexpr int CPW = 32 / BITS;        // codes per word
@@ -918,7 +919,7 @@ __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
     const uint32_t cnt = max(min((uint32_t)B, a.H - min(a.H, r0)) * min((uint32_t)B, a.W - min(a.W, bj * B)), 1u);
     const uint32_t lfc_idx = bi * a.LW + bj;
     const bool writes_lfc = in_plane && (sl % IPB) == 0;
-    const bool fullrows = (a.H % B) == 0;
+    const bool fullrows = R == 1 || (a.H % B) == 0;
     const uint32_t rscale = 1u << (16 - BITS);
     const uint32_t xoff = (off / 2u) * kWeyl;                 // pair counter of the item's first row
     const uint32_t rowW = (a.W / 2u) * kWeyl;                 // pair counter distance between rows
@@ -933,7 +934,7 @@ __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
 
         // ---- load the item: rows past the map re-read row 0 (no effect on min / max, left out of the sum);
         // lanes without an item read item 0 of the round and have their effects masked
-        float v[B][VEC];
+        float v[R][VEC];
         {
             const T* src = static_cast<const T*>(pt.x) + (size_t)p0 * a.HW;
             const __amdgpu_buffer_rsrc_t rsrc =
@@ -941,7 +942,7 @@ __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
             const uint32_t base = (valid ? g * a.HW + off : 0u) * (uint32_t)sizeof(T);
             const uint32_t rowb = a.W * (uint32_t)sizeof(T);
 #pragma unroll
-            for (int rr = 0; rr < B; ++rr) {
+            for (int rr = 0; rr < R; ++rr) {
                 const uint32_t vo = fullrows ? base : base + ((uint32_t)rr < nrows ? rr * rowb : 0u);
                 const uint32_t so = fullrows ? rr * rowb : 0u;
                 if constexpr (sizeof(T) == 4 && VEC == 4) {
@@ -969,7 +970,7 @@ __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
         // ---- Sec. 4.1 AveragePooling: block sum in binary64 over the block's adjacent lanes
         double Sm = 0.0;
 #pragma unroll
-        for (int rr = 0; rr < B; ++rr) {
+        for (int rr = 0; rr < R; ++rr) {
             double rs = (double)v[rr][0];
 #pragma unroll
             for (int c = 1; c < VEC; ++c) rs += (double)v[rr][c];
@@ -983,7 +984,7 @@ __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
         // ---- residual H^H = H - UpSampling(H^L) in place, plane min / max
         float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
-        for (int rr = 0; rr < B; ++rr)
+        for (int rr = 0; rr < R; ++rr)
 #pragma unroll
             for (int c = 0; c < VEC; ++c) {
                 v[rr][c] = v[rr][c] - lfc;
@@ -1009,7 +1010,7 @@ __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
             const uint32_t xw0 = k1 + xoff;
             uint32_t* const pw = cw + g * a.WPP;
 #pragma unroll
-            for (int rr = 0; rr < B; ++rr) {
+            for (int rr = 0; rr < R; ++rr) {
                 const uint32_t xw = xw0 + (uint32_t)rr * rowW;
                 uint32_t c;
                 if constexpr (VEC == 4) {
@@ -1905,8 +1906,13 @@ bool plan_items(const Layout& L, int64_t H, int64_t W, int B, size_t es, const v
 template <typename T, int BITS>
 hipError_t launch_items(int B, int vec, const ItemsArgs& a, dim3 grid, size_t lds, hipStream_t st) {
     void (*kern)(ItemsArgs);
-    if (B == 8) kern = vec == 4 ? compress_items<T, BITS, 8, 4> : compress_items<T, BITS, 8, 2>;
-    else kern = vec == 4 ? compress_items<T, BITS, 4, 4> : compress_items<T, BITS, 4, 2>;
+    if (a.H == 1) {
+        if (B == 8) kern = vec == 4 ? compress_items<T, BITS, 8, 4, 1> : compress_items<T, BITS, 8, 2, 1>;
+        else kern = vec == 4 ? compress_items<T, BITS, 4, 4, 1> : compress_items<T, BITS, 4, 2, 1>;
+    } else {
+        if (B == 8) kern = vec == 4 ? compress_items<T, BITS, 8, 4, 8> : compress_items<T, BITS, 8, 2, 8>;
+        else kern = vec == 4 ? compress_items<T, BITS, 4, 4, 4> : compress_items<T, BITS, 4, 2, 4>;
+    }
     hipLaunchKernelGGL(kern, grid, dim3(64), lds, st, a);
     return hipGetLastError();
 }
@@ -2263,7 +2269,7 @@ int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, 
         else if (plan_lane(L, es, data, &la, &grid, &lds))
             n = snprintf(out, cap, "compress_lane<%s, %d>", tn, b);
         else if (plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
-            n = snprintf(out, cap, "compress_items<%s, %d, %d, %d>", tn, b, B, vec);
+            n = snprintf(out, cap, "compress_items<%s, %d, %d, %d, %d>", tn, b, B, vec, H == 1 ? 1 : B);
         else if (plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_wave<%s, %d, %d, %d>", tn, b, B, vec);
         else if (plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
