@@ -17,7 +17,8 @@
 //   compress_lane    one-block planes with an odd element count (7x7): a lane per plane
 //   compress_wave    other planes up to 17 KB: one wavefront per chunk of planes staged in LDS
 //   compress_tile    other planes up to 156 KB: four wavefronts per chunk staged in LDS
-//   compress_any     everything else (block sizes other than 4 and 8, giant planes): slow
+//   compress_rows    any block size (12, 16, 18, 64 of the paper's sweep), chunk staged in LDS
+//   compress_any     everything else (giant planes): slow
 //   decompress_rowvec / _table / _flat / _lane / _scalar: streaming, the packed slice of a
 //                    workgroup staged in LDS, one 16-byte non-temporal store per four elements
 // Every kernel takes a table of up to 8 maps of one shape (blockIdx.y picks the map).
@@ -1322,6 +1323,183 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
     }
 }
 
+// ------------------------------------------------------------------ compress, any block size, chunk in LDS
+
+struct RowsArgs {
+    CompTab tab;
+    Regions rg;
+    uint32_t P, H, W, HW, LH, LW, nb, WPP, B;
+    uint32_t G;          // planes per workgroup
+    uint32_t xs_floats;  // LDS floats reserved for the chunk (multiple of 4, + slack for ragged last words)
+    uint32_t vec_load;   // chunk starts are 16-byte aligned
+    FastDiv d_W, d_B, d_LW, d_HLW, d_nb, d_wpp;
+};
+
+// Any block size B (the paper's sweep uses 12, 16, 18 and 64 besides 8).  A workgroup of four
+// wavefronts stages a chunk of G planes in LDS with coalesced loads, then
+//   1. a lane per (row, block column): binary64 sum, min and max of that row segment;
+//   2. a lane per block: adds its rows' partial sums in row order -> LFC, and the extremes of the
+//      block's residual (x -> fl(x - m) is monotone, so they are fl(min x - m), fl(max x - m));
+//   3. a lane per plane: min / max over its blocks, scale, keys, meta;
+//   4. a lane per packed word: residual against the block's LFC, quantise, pack.
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) compress_rows(RowsArgs a) {
+    extern __shared__ float4 smem4[];
+    float4* params = smem4;                                                   // [G] (delta, inv scaled, k1, k2)
+    float* xs = reinterpret_cast<float*>(smem4 + a.G);                        // [xs_floats] the chunk as fp32
+    float4* rowp = reinterpret_cast<float4*>(xs + a.xs_floats);               // [G*H*LW] (sum lo, sum hi, min, max)
+    float* lfcs = reinterpret_cast<float*>(rowp + a.G * a.H * a.LW);          // [G*nb]
+    float2* bext = reinterpret_cast<float2*>(lfcs + ((a.G * a.nb + 1u) & ~1u)); // [G*nb] residual extremes per block
+
+    constexpr int CPW = 32 / BITS;
+    constexpr int PPW = CPW / 2;
+    constexpr float Lf = float((1 << BITS) - 1);
+    const uint32_t tid = threadIdx.x;
+    const uint32_t p0 = blockIdx.x * a.G;
+    const uint32_t Gc = min(a.G, a.P - p0);
+    const uint32_t n = Gc * a.HW;
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
+
+    // ---- chunk -> LDS (fp32): coalesced 16-byte loads, up to 8 in flight per lane
+    {
+        const T* src = static_cast<const T*>(pt.x) + (size_t)p0 * a.HW;
+        constexpr uint32_t EPV = 16 / sizeof(T);
+        constexpr int U = 8;
+        const uint32_t nv = a.vec_load ? n / EPV : 0;
+        const u32x4* src4 = reinterpret_cast<const u32x4*>(src);
+        for (uint32_t v0 = 0; v0 < nv; v0 += U * kThreads) {
+            u32x4 q[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t v = v0 + u * kThreads + tid;
+                if (v < nv) q[u] = __builtin_nontemporal_load(src4 + v);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t v = v0 + u * kThreads + tid;
+                if (v < nv) {
+                    if constexpr (sizeof(T) == 4) {
+                        reinterpret_cast<u32x4*>(xs)[v] = q[u];
+                    } else {
+                        float4 lo, hi;
+                        lo.x = __uint_as_float(q[u].x << 16); lo.y = __uint_as_float(q[u].x & 0xffff0000u);
+                        lo.z = __uint_as_float(q[u].y << 16); lo.w = __uint_as_float(q[u].y & 0xffff0000u);
+                        hi.x = __uint_as_float(q[u].z << 16); hi.y = __uint_as_float(q[u].z & 0xffff0000u);
+                        hi.z = __uint_as_float(q[u].w << 16); hi.w = __uint_as_float(q[u].w & 0xffff0000u);
+                        reinterpret_cast<float4*>(xs)[2 * v] = lo;
+                        reinterpret_cast<float4*>(xs)[2 * v + 1] = hi;
+                    }
+                }
+            }
+        }
+        for (uint32_t e = nv * EPV + tid; e < n; e += kThreads) xs[e] = Elem<T>::load(src, e);
+    }
+    lds_barrier();
+
+    // ---- 1. row segments (Sec. 4.1 AveragePooling, first half)
+    const uint32_t HLW = a.H * a.LW;
+    for (uint32_t s = tid; s < Gc * HLW; s += kThreads) {
+        const uint32_t g = fdiv(s, a.d_HLW);
+        const uint32_t rem = s - g * HLW;
+        const uint32_t r = fdiv(rem, a.d_LW);
+        const uint32_t bj = rem - r * a.LW;
+        const uint32_t c0 = bj * a.B;
+        const uint32_t cols = min(a.B, a.W - c0);
+        const float* row = xs + g * a.HW + r * a.W + c0;
+        double S = 0.0;
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+        for (uint32_t c = 0; c < cols; ++c) {
+            const float v = row[c];
+            S += (double)v;
+            mn = fminf(mn, v);
+            mx = fmaxf(mx, v);
+        }
+        const uint64_t sb = (uint64_t)__double_as_longlong(S);
+        rowp[s] = make_float4(__uint_as_float((uint32_t)sb), __uint_as_float((uint32_t)(sb >> 32)), mn, mx);
+    }
+    lds_barrier();
+
+    // ---- 2. blocks: LFC and the extremes of the block's residual.  All lanes of a wavefront run
+    // the loop body (mean_of votes across the wavefront); slots past the chunk redo block 0.
+    const uint32_t nblk = Gc * a.nb;
+    for (uint32_t t0 = 0; t0 < nblk; t0 += kThreads) {
+        const uint32_t t = t0 + tid;
+        const bool live = t < nblk;
+        const uint32_t tt = live ? t : 0u;
+        const uint32_t g = fdiv(tt, a.d_nb);
+        const uint32_t blk = tt - g * a.nb;
+        const uint32_t bi = fdiv(blk, a.d_LW);
+        const uint32_t bj = blk - bi * a.LW;
+        const uint32_t r0 = bi * a.B;
+        const uint32_t rows = min(a.B, a.H - r0);
+        const uint32_t cols = min(a.B, a.W - bj * a.B);
+        const float4* rp = rowp + g * HLW + r0 * a.LW + bj;
+        double S = 0.0;
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+        for (uint32_t rr = 0; rr < rows; ++rr) {
+            const float4 q = rp[rr * a.LW];
+            S += __longlong_as_double((long long)(((uint64_t)__float_as_uint(q.y) << 32) | __float_as_uint(q.x)));
+            mn = fminf(mn, q.z);
+            mx = fmaxf(mx, q.w);
+        }
+        const float lfc = lfc_round<T>(mean_of(S, rows * cols), kC16<T>);
+        if (live) {
+            lfcs[t] = lfc;
+            lfc_store<T>(pt.lfc, (size_t)p0 * a.nb + t, lfc, kC16<T>);
+            bext[t] = make_float2(mn - lfc, mx - lfc);
+        }
+    }
+    lds_barrier();
+
+    // ---- 3. planes: scale of Eq. (quantization), keys, meta
+    for (uint32_t g = tid; g < Gc; g += kThreads) {
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+        for (uint32_t j = 0; j < a.nb; ++j) {
+            const float2 e = bext[g * a.nb + j];
+            mn = fminf(mn, e.x);
+            mx = fmaxf(mx, e.y);
+        }
+        float delta, Delta, inv;
+        plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
+        const uint32_t p = p0 + g;
+        const uint32_t k1 = mix32(p ^ pt.seed_a);
+        const uint32_t k2 = mix32(k1 + pt.seed_c);
+        meta_store(pt.meta, p, delta, Delta, kC16<T>);
+        params[g] = make_float4(delta, inv * (float)(1u << (32 - BITS)), __uint_as_float(k1), __uint_as_float(k2));
+    }
+    lds_barrier();
+
+    // ---- 4. residual, Quant of Eq. (quantization), packing: one word per lane and step
+    const uint32_t rscale = 1u << (16 - BITS);
+    const uint32_t nwords = Gc * a.WPP;
+    for (uint32_t wi = tid; wi < nwords; wi += kThreads) {
+        const uint32_t g = fdiv(wi, a.d_wpp);
+        const uint32_t k = wi - g * a.WPP;
+        const float4 pr = params[g];
+        const uint32_t k1 = __float_as_uint(pr.z), k2 = __float_as_uint(pr.w);
+        const uint32_t e0 = k * CPW;
+        const uint32_t left = a.HW - e0;                       // elements of the plane from e0 on (>= 1)
+        const float* xp = xs + g * a.HW;
+        const float* lp = lfcs + g * a.nb;
+        float h[CPW];
+#pragma unroll
+        for (int e = 0; e < CPW; ++e) {
+            // a ragged last word repeats the plane's last element; those codes are cleared below
+            const uint32_t i = e0 + min((uint32_t)e, left - 1u);
+            const uint32_t r = fdiv(i, a.d_W);
+            const uint32_t c = i - r * a.W;
+            h[e] = xp[i] - lp[fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B)];
+        }
+        const uint32_t xw0 = k1 + (k * PPW) * kWeyl;
+        uint32_t word = 0;
+#pragma unroll
+        for (int j = PPW - 1; j >= 0; --j)
+            word = push_pair<BITS>(word, h[2 * j], h[2 * j + 1], pr.x, pr.y, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+        if (left < (uint32_t)CPW) word &= (1u << (left * BITS)) - 1u;          // pad bits are zero
+        pt.codes[(size_t)(p0 + g) * a.WPP + k] = word;
+    }
+}
+
 // ------------------------------------------------------------------ compress, any shape (slow)
 
 struct AnyArgs {
@@ -1784,7 +1962,8 @@ int num_cus() {
 }
 
 // dynamic LDS above the default limit needs a one-time opt-in per kernel
-hipError_t allow_large_lds(void (*kern)(TileArgs), size_t lds) {
+template <typename Args>
+hipError_t allow_large_lds(void (*kern)(Args), size_t lds) {
     if (lds <= 48u * 1024u) return hipSuccess;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax);
@@ -1966,6 +2145,45 @@ bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
     *grid = (uint32_t)((L.P + G - 1) / G);
     *vec_out = vec;
     return true;
+}
+
+// Fills the any-block-size compress plan; false when a plane does not fit LDS or the 32-bit index tricks.
+bool plan_rows(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, const void* x,
+               RowsArgs* a, uint32_t* grid, size_t* lds) {
+    (void)b;
+    if ((uint64_t)B > L.HW + 64) return false;      // keeps fdiv(r, B) exact; such a B is "one block" anyway: see below
+    const uint64_t per_plane = 4ull * L.HW + 16ull * (uint64_t)H * L.LW + 12ull * L.nb + 16ull;
+    if (per_plane + 256 > kLdsMax) return false;
+    if (!fastdiv_ok(L.HW, (uint64_t)W) || !fastdiv_ok((uint64_t)(H > W ? H : W), (uint64_t)B)) return false;
+    uint64_t G = kLdsTarget / per_plane;
+    if (G < 1) G = 1;
+    if (G > L.P) G = L.P;
+    // chunk starts on 16-byte boundaries when G is a multiple of `unit`
+    const uint64_t unit = 16 / gcd_u64(16, L.HW * es);
+    uint32_t vec_load = ((uintptr_t)x % 16) == 0;
+    if (vec_load && G % unit != 0) {
+        if (G > unit) G -= G % unit;
+        else if (unit * per_plane + 256 <= kLdsMax && unit <= L.P) G = unit;
+        else if (G < L.P) vec_load = 0;
+    }
+    const uint64_t HLW = (uint64_t)H * L.LW;
+    if (!fastdiv_ok(G * HLW + kThreads, HLW) || !fastdiv_ok(HLW, L.LW) || !fastdiv_ok(G * L.nb + kThreads, L.nb) ||
+        !fastdiv_ok(L.nb, L.LW) || !fastdiv_ok(G * L.WPP + kThreads, L.WPP))
+        return false;
+    a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
+    a->LH = (uint32_t)L.LH; a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP; a->B = (uint32_t)B;
+    a->G = (uint32_t)G;
+    a->xs_floats = (uint32_t)((G * L.HW + 3) / 4 * 4);
+    a->vec_load = vec_load;
+    a->d_W = make_fastdiv((uint32_t)W);
+    a->d_B = make_fastdiv((uint32_t)B);
+    a->d_LW = make_fastdiv((uint32_t)L.LW);
+    a->d_HLW = make_fastdiv((uint32_t)HLW);
+    a->d_nb = make_fastdiv((uint32_t)L.nb);
+    a->d_wpp = make_fastdiv((uint32_t)L.WPP);
+    *lds = 16ull * G + 4ull * a->xs_floats + 16ull * G * HLW + 4ull * ((G * L.nb + 1) & ~1ull) + 8ull * G * L.nb + 16;
+    *grid = (uint32_t)((L.P + G - 1) / G);
+    return *lds <= kLdsMax;
 }
 
 // Fills the tiled-compress launch plan; false when the shape is not covered.
@@ -2162,17 +2380,19 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
         RegsArgs ra{};
         ItemsArgs ia{};
         LaneArgs la{};
+        RowsArgs wa2{};
         AnyArgs g{};
         size_t lds = 0;
         uint32_t grid = 0;
         int vec = 1, nt = 64, nw = 1;
-        enum { REGS, LANE, ITEMS, WAVE, TILE, ANY } kind;
+        enum { REGS, LANE, ITEMS, WAVE, TILE, ROWS, ANY } kind;
         if (plan_regs(L, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
         else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
         else if (plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
         else if (plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
             kind = WAVE; wa.tab = tab; wa.rg = rg;
         } else if (plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) { kind = TILE; a.tab = tab; a.rg = rg; }
+        else if (plan_rows(L, H, W, B, b, es, xa, &wa2, &grid, &lds)) { kind = ROWS; wa2.tab = tab; wa2.rg = rg; }
         else {
             kind = ANY;
             g.tab = tab; g.rg = rg;
@@ -2190,6 +2410,12 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
                 case WAVE: return launch_wave<T, BITS>(B, vec, wa, gd, lds, st);
                 case TILE: return launch_tile<T, BITS>(B, vec, a, gd, lds, st);
                 case LANE: hipLaunchKernelGGL((compress_lane<T, BITS>), gd, dim3(64), lds, st, la); return hipGetLastError();
+                case ROWS: {
+                    const hipError_t e = allow_large_lds(compress_rows<T, BITS>, lds);
+                    if (e != hipSuccess) return e;
+                    hipLaunchKernelGGL((compress_rows<T, BITS>), gd, dim3(kThreads), lds, st, wa2);
+                    return hipGetLastError();
+                }
                 default: hipLaunchKernelGGL((compress_any<T, BITS>), gd, dim3(kThreads), 0, st, g); return hipGetLastError();
             }
         });
@@ -2263,7 +2489,7 @@ int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, 
     const char* tn = dt == DIVISION_BF16 ? "bf16_t" : dt == DIVISION_F32_C16 ? "f32c16_t" : "float";
     int n;
     if (direction == 0) {
-        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
+        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (plan_regs(L, H, W, B, es, data, &ra, &grid, &lds, &nw))
             n = snprintf(out, cap, "compress_regs<%s, %d, %d, %d>", tn, b, B, nw);
         else if (plan_lane(L, es, data, &la, &grid, &lds))
@@ -2274,6 +2500,8 @@ int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, 
             n = snprintf(out, cap, "compress_wave<%s, %d, %d, %d>", tn, b, B, vec);
         else if (plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
             n = snprintf(out, cap, "compress_tile<%s, %d, %d, %d, %d>", tn, b, B, vec, nt);
+        else if (plan_rows(L, H, W, B, b, es, data, &wa2, &grid, &lds))
+            n = snprintf(out, cap, "compress_rows<%s, %d>", tn, b);
         else
             n = snprintf(out, cap, "compress_any<%s, %d>", tn, b);
     } else {
