@@ -508,6 +508,57 @@ def test_seeded_sweep_of_shapes_block_sizes_and_code_widths(chunk):
         assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt)), tag
 
 
+# ---------------------------------------------------------------- the block sizes of the paper's sweep (Sec. 5, B ablation)
+
+ROWS_CASES = [
+    # shape, B, b                       what it exercises in the general-block-size kernel
+    ((8, 24, 56, 56), 12, 2),           # 4 full blocks + one of 8 per side, several planes per chunk, many chunks
+    ((8, 24, 56, 56), 16, 2),           # 3 full blocks + one of 8
+    ((8, 24, 56, 56), 18, 4),           # 3 full blocks + one of 2
+    ((8, 24, 56, 56), 64, 2),           # block larger than the map: one block per plane
+    ((7, 19, 28, 28), 12, 2),           # odd plane count: ragged last chunk
+    ((7, 19, 28, 28), 18, 8),
+    ((5, 33, 14, 14), 12, 4),           # blocks of 12 and 2
+    ((3, 5, 112, 112), 16, 2),          # one plane per chunk, 49 blocks
+    ((3, 5, 112, 112), 64, 2),          # blocks of 64 and 48
+    ((2, 3, 150, 150), 18, 2),          # 90 KB plane, 81 blocks, ragged blocks of 6
+    ((6, 11, 7, 100), 16, 2),           # block taller than the map, seven columns of blocks
+    ((6, 11, 100, 7), 16, 4),           # block wider than the map
+    ((4, 9, 27, 35), 5, 2),             # odd everything: H*W odd, blocks of 5 and 2 / 5 exactly
+    ((4, 9, 27, 35), 7, 4),
+    ((3, 7, 30, 30), 6, 2),
+    ((16, 48, 1, 196), 16, 2),          # 1-D maps
+    ((5, 7, 1, 1000), 12, 4),
+    ((2, 3, 33, 31), 2, 2),             # tiny blocks: 272 blocks per plane
+    ((2, 3, 40, 40), 1, 4),             # B = 1
+]
+
+
+@pytest.mark.parametrize("shape,B,b", ROWS_CASES)
+@pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
+def test_general_block_size_kernel_matches_oracle(shape, B, b, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    c16 = mode == "c16"
+    assert pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16).startswith("compress_rows<")
+    g = torch.Generator().manual_seed(7000 + sum(shape) + 13 * B + b)
+    x = (torch.randn(shape, generator=g) * 2.0 + 0.25).to(dtype)       # signed values
+    x[0, 0] = 1.5                                                     # one constant plane (degenerate scale)
+    dt = oracle.F32_C16 if c16 else (oracle.BF16 if mode == "bf16" else oracle.F32)
+    xh, _ = to_host_array(x)
+    seed = 0x0B10C5 + B
+    ref = oracle.compress(xh, B, b, seed, dt, threads=16)
+    xd = x.to("cuda:0")
+    pk = pkg.division_compress(xd, B, b, seed, c16=c16)
+    y = pkg.division_decompress(pk, shape, B, b, dtype, c16=c16)
+    pb = pkg.division_compress_batch([xd, xd, xd], B, b, [seed + 1, seed, seed + 2], c16=c16)
+    torch.cuda.synchronize()
+    assert np.array_equal(pk.cpu().numpy(), ref)
+    assert torch.equal(pb[1], pk)
+    assert np.array_equal(pb[2].cpu().numpy(), oracle.compress(xh, B, b, seed + 2, dt, threads=16))
+    yh, _ = to_host_array(y.cpu())
+    assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt))
+
+
 # ---------------------------------------------------------------- the paper's cached format (bfloat16 H^L, delta, Delta)
 
 C16_CASES = [
