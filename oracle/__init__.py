@@ -47,6 +47,14 @@ def lib() -> ctypes.CDLL:
         L.oracle_packed_bytes.argtypes = [i64, i64, i64, i64, ci, ci, ci]
         L.oracle_packed_layout.restype = ci
         L.oracle_packed_layout.argtypes = [i64, i64, i64, i64, ci, ci, ci] + [ctypes.POINTER(sz)] * 6
+        L.oracle_packed_bytes_3d.restype = sz
+        L.oracle_packed_bytes_3d.argtypes = [i64, i64, i64, i64, i64, ci, ci, ci]
+        L.oracle_packed_layout_3d.restype = ci
+        L.oracle_packed_layout_3d.argtypes = [i64, i64, i64, i64, i64, ci, ci, ci] + [ctypes.POINTER(sz)] * 6
+        L.oracle_compress_3d.restype = ci
+        L.oracle_compress_3d.argtypes = [vp, i64, i64, i64, i64, i64, ci, ci, ci, u64, vp, vp, vp, vp, ci]
+        L.oracle_decompress_3d.restype = ci
+        L.oracle_decompress_3d.argtypes = [vp, i64, i64, i64, i64, i64, ci, ci, ci, vp, ci]
         L.oracle_compress.restype = ci
         L.oracle_compress.argtypes = [vp, i64, i64, i64, i64, ci, ci, ci, u64, vp, vp, vp, vp, ci]
         L.oracle_decompress.restype = ci
@@ -90,6 +98,20 @@ def packed_bytes(N, C, H, W, B, b, dt=F32) -> int:
     return int(lib().oracle_packed_bytes(N, C, H, W, B, b, dt))
 
 
+def packed_bytes_3d(N, C, D, H, W, B, b, dt=F32) -> int:
+    """3-D maps of Appendix D: planes of D x H x W elements, blocks of B x B x B."""
+    return int(lib().oracle_packed_bytes_3d(N, C, D, H, W, B, b, dt))
+
+
+def packed_layout_3d(N, C, D, H, W, B, b, dt=F32) -> dict:
+    vals = [ctypes.c_size_t() for _ in range(6)]
+    rc = lib().oracle_packed_layout_3d(N, C, D, H, W, B, b, dt, *[ctypes.byref(v) for v in vals])
+    if rc:
+        raise ValueError("invalid codec arguments")
+    k = ["codes_off", "codes_bytes", "meta_off", "meta_bytes", "lfc_off", "lfc_bytes"]
+    return {n: int(v.value) for n, v in zip(k, vals)}
+
+
 def packed_layout(N, C, H, W, B, b, dt=F32) -> dict:
     vals = [ctypes.c_size_t() for _ in range(6)]
     rc = lib().oracle_packed_layout(N, C, H, W, B, b, dt, *[ctypes.byref(v) for v in vals])
@@ -101,12 +123,15 @@ def packed_layout(N, C, H, W, B, b, dt=F32) -> dict:
 
 def compress(x: np.ndarray, B: int, b: int, seed: int, dt: int = F32, threads: int = 1,
              debug: bool = False):
-    """x: (N,C,H,W) float32 array, or uint16 array holding bf16 bit patterns.
+    """x: (N,C,H,W) float32 array, or uint16 array holding bf16 bit patterns; a 5-D array
+    (N,C,D,H,W) is a batch of 3-D maps (Appendix D).
 
     Returns the packed buffer (uint8 array); with ``debug`` also a dict with
     the per-element pre-round value t, the 16 random bits r and the residual h.
     """
-    assert x.ndim == 4 and x.dtype == _np_dtype(dt) and x.flags.c_contiguous
+    assert x.ndim in (4, 5) and x.dtype == _np_dtype(dt) and x.flags.c_contiguous
+    if x.ndim == 5:
+        return _compress_3d(x, B, b, seed, dt, threads, debug)
     N, C, H, W = x.shape
     nb = packed_bytes(N, C, H, W, B, b, dt)
     if nb == 0:
@@ -126,7 +151,36 @@ def compress(x: np.ndarray, B: int, b: int, seed: int, dt: int = F32, threads: i
     return (out, {"t": t, "r": r, "h": h}) if debug else out
 
 
+def _compress_3d(x, B, b, seed, dt, threads, debug):
+    N, C, D, H, W = x.shape
+    nb = packed_bytes_3d(N, C, D, H, W, B, b, dt)
+    if nb == 0:
+        raise ValueError("invalid codec arguments")
+    out = np.empty(nb, dtype=np.uint8)
+    t = r = h = None
+    if debug:
+        t = np.empty(x.shape, np.float32)
+        r = np.empty(x.shape, np.uint16)
+        h = np.empty(x.shape, np.float32)
+    rc = lib().oracle_compress_3d(
+        x.ctypes.data, N, C, D, H, W, dt, B, b, seed & (2 ** 64 - 1), out.ctypes.data,
+        t.ctypes.data if debug else None, r.ctypes.data if debug else None,
+        h.ctypes.data if debug else None, threads)
+    if rc:
+        raise ValueError("oracle_compress_3d rejected its arguments")
+    return (out, {"t": t, "r": r, "h": h}) if debug else out
+
+
 def decompress(packed: np.ndarray, shape, B: int, b: int, dt: int = F32, threads: int = 1) -> np.ndarray:
+    if len(shape) == 5:
+        N, C, D, H, W = shape
+        assert packed.dtype == np.uint8 and packed.flags.c_contiguous
+        assert packed.size >= packed_bytes_3d(N, C, D, H, W, B, b, dt)
+        out = np.empty(shape, dtype=_np_dtype(dt))
+        rc = lib().oracle_decompress_3d(packed.ctypes.data, N, C, D, H, W, dt, B, b, out.ctypes.data, threads)
+        if rc:
+            raise ValueError("oracle_decompress_3d rejected its arguments")
+        return out
     N, C, H, W = shape
     assert packed.dtype == np.uint8 and packed.flags.c_contiguous
     assert packed.size >= packed_bytes(N, C, H, W, B, b, dt)
@@ -140,6 +194,16 @@ def decompress(packed: np.ndarray, shape, B: int, b: int, dt: int = F32, threads
 def split_packed(packed: np.ndarray, shape, B: int, b: int, dt: int = F32) -> dict:
     """Views of the three regions: codes u32[P][WPP], meta [P][2] (float32, or bf16 bit patterns as
     uint16 in the F32_C16 mode), lfc [P][LH][LW] (float32 for F32, else bf16 bit patterns)."""
+    if len(shape) == 5:
+        N, C, D, H, W = shape
+        lay = packed_layout_3d(N, C, D, H, W, B, b, dt)
+        P = N * C
+        codes = packed[lay["codes_off"]:lay["codes_off"] + lay["codes_bytes"]].view(np.uint32).reshape(P, -1)
+        meta = packed[lay["meta_off"]:lay["meta_off"] + lay["meta_bytes"]]
+        meta = (meta.view(np.uint16) if dt == F32_C16 else meta.view(np.float32)).reshape(P, 2)
+        lfc = packed[lay["lfc_off"]:lay["lfc_off"] + lay["lfc_bytes"]]
+        lfc = (lfc.view(np.float32) if dt == F32 else lfc.view(np.uint16)).reshape(P, -(-D // B), -(-H // B), -(-W // B))
+        return {"codes": codes, "meta": meta, "lfc": lfc}
     N, C, H, W = shape
     lay = packed_layout(N, C, H, W, B, b, dt)
     P = N * C

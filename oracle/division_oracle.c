@@ -13,7 +13,8 @@
  * "AveragePooling / UpSampling / Quant / Cache" and "Dequant / UpSampling+add";
  * Appendix D for the pooled shapes):
  *
- *   for every (sample, channel) plane of an NCHW tensor
+ *   for every (sample, channel) plane of an NCHW tensor (or NCDHW: the 3-D maps of Appendix D,
+ *   blocks of B x B x B; the 1-D maps are the H = 1 case)
  *     H^L   = average pooling of the plane, window = stride = B      (Sec. 4.1)
  *     H^H   = H - UpSampling(H^L)          (nearest, block replicate) (Sec. 4.1)
  *     delta = min H^H, h_max = max H^H, Delta = (h_max-delta)/(2^Q-1) (Eq. quantization)
@@ -47,7 +48,9 @@
  * round-to-nearest-even, never fused.  Compile with -ffp-contract=off and
  * without -ffast-math.  Block means are accumulated in binary64.
  *
- * Parity pins: tests/test_oracle_pins.py checks this file against worked
+ * Parity pins: tests/test_oracle_3d_pins.py pins the 3-D maps (library 3-D pooling and
+ * up-sampling, an exact-rational brute force over coordinates, reduction to the 2-D
+ * codec, axis permutations).  tests/test_oracle_pins.py checks this file against worked
  * examples, closed forms, library pooling/upsampling, a brute-force
  * exact-rational re-derivation and statistical properties.  The random
  * generator has no counterpart in the paper: its pins are this build's own
@@ -182,18 +185,20 @@ uint32_t oracle_rand16(uint64_t seed, uint32_t plane, uint32_t i)
 /* ---------- packed layout ------------------------------------------------ */
 
 typedef struct {
-    size_t P, HW, LH, LW, WPP;
+    size_t P, HW, LD, LH, LW, WPP;      /* HW = elements per plane (D*H*W); LD x LH x LW pooled */
     size_t codes_off, codes_bytes, meta_off, meta_bytes, lfc_off, lfc_bytes, total;
 } layout_t;
 
-static int make_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt, layout_t *L)
+/* A plane is D x H x W (Appendix D, 3-D maps); D = 1 is the 2-D map of Sec. 4.1, D = H = 1 the 1-D one. */
+static int make_layout(int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int B, int b, int dt, layout_t *L)
 {
-    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4 && b != 8))
+    if (N <= 0 || C <= 0 || D <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4 && b != 8))
         return 1;
     if (dt != ORACLE_F32 && dt != ORACLE_BF16 && dt != ORACLE_F32_C16)
         return 1;
     L->P = (size_t)N * (size_t)C;
-    L->HW = (size_t)H * (size_t)W;
+    L->HW = (size_t)D * (size_t)H * (size_t)W;
+    L->LD = ((size_t)D + (size_t)B - 1) / (size_t)B;
     L->LH = ((size_t)H + (size_t)B - 1) / (size_t)B;
     L->LW = ((size_t)W + (size_t)B - 1) / (size_t)B;
     size_t cpw = 32u / (unsigned)b;
@@ -203,25 +208,30 @@ static int make_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b,
     L->meta_off = align16(L->codes_bytes);
     L->meta_bytes = meta_size(dt) * L->P;
     L->lfc_off = align16(L->meta_off + L->meta_bytes);
-    L->lfc_bytes = lfc_size(dt) * L->P * L->LH * L->LW;
+    L->lfc_bytes = lfc_size(dt) * L->P * L->LD * L->LH * L->LW;
     L->total = align16(L->lfc_off + L->lfc_bytes);
     return 0;
 }
 
-size_t oracle_packed_bytes(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt)
+size_t oracle_packed_bytes_3d(int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int B, int b, int dt)
 {
     layout_t L;
-    if (make_layout(N, C, H, W, B, b, dt, &L))
+    if (make_layout(N, C, D, H, W, B, b, dt, &L))
         return 0;
     return L.total;
 }
 
-int oracle_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt,
-                         size_t *codes_off, size_t *codes_bytes, size_t *meta_off,
-                         size_t *meta_bytes, size_t *lfc_off, size_t *lfc_bytes)
+size_t oracle_packed_bytes(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt)
+{
+    return oracle_packed_bytes_3d(N, C, 1, H, W, B, b, dt);
+}
+
+int oracle_packed_layout_3d(int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int B, int b, int dt,
+                            size_t *codes_off, size_t *codes_bytes, size_t *meta_off,
+                            size_t *meta_bytes, size_t *lfc_off, size_t *lfc_bytes)
 {
     layout_t L;
-    if (make_layout(N, C, H, W, B, b, dt, &L))
+    if (make_layout(N, C, D, H, W, B, b, dt, &L))
         return 1;
     *codes_off = L.codes_off; *codes_bytes = L.codes_bytes;
     *meta_off = L.meta_off;   *meta_bytes = L.meta_bytes;
@@ -229,30 +239,42 @@ int oracle_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int 
     return 0;
 }
 
+int oracle_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt,
+                         size_t *codes_off, size_t *codes_bytes, size_t *meta_off,
+                         size_t *meta_bytes, size_t *lfc_off, size_t *lfc_bytes)
+{
+    return oracle_packed_layout_3d(N, C, 1, H, W, B, b, dt, codes_off, codes_bytes, meta_off, meta_bytes,
+                                   lfc_off, lfc_bytes);
+}
+
 /* ---------- one plane, step by step -------------------------------------- */
 
-/* Sec. 4.1: H^L = AveragePooling(H), window = stride = B, clipped at the
- * border.  The mean is the exact sum (binary64 accumulation, row-major)
- * divided by the element count, rounded once to fp32, then rounded to the
- * storage type.  lfc_f receives the stored value widened back to fp32. */
-static void plane_lfc(const void *x, int dt, size_t base, size_t H, size_t W, size_t B,
-                      size_t LH, size_t LW, float *lfc_f)
+/* Sec. 4.1 and Appendix D Eq. (average_poolnd): H^L = AveragePooling(H), window = stride = B in
+ * every dimension of the map (B x B x B for a 3-D map, B x B for D = 1), clipped at the
+ * border.  The mean is the exact sum (binary64 accumulation, depth-major then
+ * row-major) divided by the element count, rounded once to fp32, then rounded to
+ * the storage type.  lfc_f receives the stored value widened back to fp32. */
+static void plane_lfc(const void *x, int dt, size_t base, size_t D, size_t H, size_t W, size_t B,
+                      size_t LD, size_t LH, size_t LW, float *lfc_f)
 {
+    for (size_t bd = 0; bd < LD; ++bd)
     for (size_t bi = 0; bi < LH; ++bi) {
         for (size_t bj = 0; bj < LW; ++bj) {
+            size_t d1 = (bd + 1) * B < D ? (bd + 1) * B : D;
             size_t r1 = (bi + 1) * B < H ? (bi + 1) * B : H;
             size_t c1 = (bj + 1) * B < W ? (bj + 1) * B : W;
             double S = 0.0;
             size_t cnt = 0;
-            for (size_t r = bi * B; r < r1; ++r)
-                for (size_t c = bj * B; c < c1; ++c) {
-                    S += (double)load_elem(x, dt, base + r * W + c);
-                    ++cnt;
-                }
+            for (size_t d = bd * B; d < d1; ++d)
+                for (size_t r = bi * B; r < r1; ++r)
+                    for (size_t c = bj * B; c < c1; ++c) {
+                        S += (double)load_elem(x, dt, base + (d * H + r) * W + c);
+                        ++cnt;
+                    }
             float m = (float)(S / (double)cnt);
             if (dt != ORACLE_F32)
                 m = bf16_to_float(float_to_bf16(m));
-            lfc_f[bi * LW + bj] = m;
+            lfc_f[(bd * LH + bi) * LW + bj] = m;
         }
     }
 }
@@ -320,12 +342,12 @@ static void plane_scale_c16(const float *h, size_t HW, int b, float *delta, floa
  * Planes are independent; `threads` > 1 distributes them over OpenMP threads
  * (no arithmetic is reordered by that).  Returns 0, or 1 on invalid arguments.
  */
-int oracle_compress(const void *x, int64_t N, int64_t C, int64_t H, int64_t W, int dt,
-                    int B, int b, uint64_t seed, void *packed,
-                    float *t_out, uint16_t *r_out, float *h_out, int threads)
+int oracle_compress_3d(const void *x, int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int dt,
+                       int B, int b, uint64_t seed, void *packed,
+                       float *t_out, uint16_t *r_out, float *h_out, int threads)
 {
     layout_t L;
-    if (!x || !packed || make_layout(N, C, H, W, B, b, dt, &L))
+    if (!x || !packed || make_layout(N, C, D, H, W, B, b, dt, &L))
         return 1;
     if (L.P > 0x7fffffffu || L.HW > 0x7fffffffu)
         return 1;
@@ -339,26 +361,29 @@ int oracle_compress(const void *x, int64_t N, int64_t C, int64_t H, int64_t W, i
     for (int64_t pp = 0; pp < (int64_t)L.P; ++pp) {
         size_t p = (size_t)pp;
         size_t base = p * L.HW;
-        float *lfc_f = (float *)malloc(sizeof(float) * L.LH * L.LW);
+        const size_t nb = L.LD * L.LH * L.LW;
+        float *lfc_f = (float *)malloc(sizeof(float) * nb);
         float *h = (float *)malloc(sizeof(float) * L.HW);
 
-        plane_lfc(x, dt, base, (size_t)H, (size_t)W, (size_t)B, L.LH, L.LW, lfc_f);
+        plane_lfc(x, dt, base, (size_t)D, (size_t)H, (size_t)W, (size_t)B, L.LD, L.LH, L.LW, lfc_f);
 
         /* store H^L in the storage type */
-        for (size_t k = 0; k < L.LH * L.LW; ++k) {
+        for (size_t k = 0; k < nb; ++k) {
             if (dt != ORACLE_F32)
-                ((uint16_t *)(pk + L.lfc_off))[p * L.LH * L.LW + k] = float_to_bf16(lfc_f[k]);
+                ((uint16_t *)(pk + L.lfc_off))[p * nb + k] = float_to_bf16(lfc_f[k]);
             else
-                ((float *)(pk + L.lfc_off))[p * L.LH * L.LW + k] = lfc_f[k];
+                ((float *)(pk + L.lfc_off))[p * nb + k] = lfc_f[k];
         }
 
-        /* Sec. 4.1: H^H = H - UpSampling(H^L), nearest = block replicate */
-        for (size_t r = 0; r < (size_t)H; ++r)
-            for (size_t c = 0; c < (size_t)W; ++c) {
-                volatile float d = load_elem(x, dt, base + r * W + c)
-                                   - lfc_f[(r / B) * L.LW + (c / B)];
-                h[r * W + c] = d;
-            }
+        /* Sec. 4.1, Eq. (up_samplend): H^H = H - UpSampling(H^L), nearest = block replicate */
+        for (size_t z = 0; z < (size_t)D; ++z)
+            for (size_t r = 0; r < (size_t)H; ++r)
+                for (size_t c = 0; c < (size_t)W; ++c) {
+                    size_t i = (z * (size_t)H + r) * (size_t)W + c;
+                    volatile float d = load_elem(x, dt, base + i)
+                                       - lfc_f[((z / B) * L.LH + (r / B)) * L.LW + (c / B)];
+                    h[i] = d;
+                }
 
         float delta, Delta, inv;
         if (dt == ORACLE_F32_C16) {
@@ -393,15 +418,22 @@ int oracle_compress(const void *x, int64_t N, int64_t C, int64_t H, int64_t W, i
     return 0;
 }
 
+int oracle_compress(const void *x, int64_t N, int64_t C, int64_t H, int64_t W, int dt,
+                    int B, int b, uint64_t seed, void *packed,
+                    float *t_out, uint16_t *r_out, float *h_out, int threads)
+{
+    return oracle_compress_3d(x, N, C, 1, H, W, dt, B, b, seed, packed, t_out, r_out, h_out, threads);
+}
+
 /*
  * Decompress (Sec. 4.2 and the reconstruction equation):
  *   hh = fl(q * Delta); hh = fl(hh + delta); v = fl(lfc + hh); xhat = (T)v.
  */
-int oracle_decompress(const void *packed, int64_t N, int64_t C, int64_t H, int64_t W, int dt,
-                      int B, int b, void *xhat, int threads)
+int oracle_decompress_3d(const void *packed, int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int dt,
+                         int B, int b, void *xhat, int threads)
 {
     layout_t L;
-    if (!xhat || !packed || make_layout(N, C, H, W, B, b, dt, &L))
+    if (!xhat || !packed || make_layout(N, C, D, H, W, B, b, dt, &L))
         return 1;
     const uint8_t *pk = (const uint8_t *)packed;
     const uint32_t Lq = (1u << b) - 1u;
@@ -420,11 +452,13 @@ int oracle_decompress(const void *packed, int64_t N, int64_t C, int64_t H, int64
             delta = ((const float *)(pk + L.meta_off))[2 * p + 0];
             Delta = ((const float *)(pk + L.meta_off))[2 * p + 1];
         }
+        for (size_t z = 0; z < (size_t)D; ++z)
         for (size_t r = 0; r < (size_t)H; ++r)
             for (size_t c = 0; c < (size_t)W; ++c) {
-                size_t i = r * (size_t)W + c;
+                size_t i = (z * (size_t)H + r) * (size_t)W + c;
                 uint32_t q = (codes[i / cpw] >> ((i % cpw) * (unsigned)b)) & Lq;
-                size_t k = p * L.LH * L.LW + (r / (size_t)B) * L.LW + (c / (size_t)B);
+                size_t k = p * L.LD * L.LH * L.LW
+                           + ((z / (size_t)B) * L.LH + (r / (size_t)B)) * L.LW + (c / (size_t)B);
                 float lfc = (dt != ORACLE_F32)
                                 ? bf16_to_float(((const uint16_t *)(pk + L.lfc_off))[k])
                                 : ((const float *)(pk + L.lfc_off))[k];
@@ -438,6 +472,12 @@ int oracle_decompress(const void *packed, int64_t N, int64_t C, int64_t H, int64
             }
     }
     return 0;
+}
+
+int oracle_decompress(const void *packed, int64_t N, int64_t C, int64_t H, int64_t W, int dt,
+                      int B, int b, void *xhat, int threads)
+{
+    return oracle_decompress_3d(packed, N, C, 1, H, W, dt, B, b, xhat, threads);
 }
 
 /* bf16 helpers exported so tests can build bf16 inputs without torch */

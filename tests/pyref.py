@@ -147,3 +147,42 @@ def codec_plane(x, H, W, B, b, seed, plane, c16=False):
         hh = f32(f32(q * Delta) + delta)
         xhat.append(f32(mean_of[(i // W // B, i % W // B)] + hh))
     return {"lfc": lfc, "delta": delta, "Delta": Delta, "codes": codes, "xhat": xhat, "h": h}
+
+
+def codec_volume(x, dims, B, b, seed, plane):
+    """Exact-rational codec of one plane with any number of map dimensions (Appendix D: 1-D, 2-D
+    and 3-D maps share one definition).  x: list of prod(dims) Fractions in row-major order.
+    The block of an element is the tuple of its coordinates floor-divided by B; the members of a
+    block are found by a search over all elements (no block loop)."""
+    L = (1 << b) - 1
+    n = len(x)
+    coords = []
+    for i in range(n):
+        c, rem = [], i
+        for d in reversed(dims):
+            c.append(rem % d)
+            rem //= d
+        coords.append(tuple(reversed(c)))
+    key = [tuple(v // B for v in c) for c in coords]
+    mean_of = {}
+    for k in sorted(set(key)):
+        members = [x[i] for i in range(n) if key[i] == k]
+        mean_of[k] = f32(sum(members, Fraction(0)) / len(members))
+    lfc = [mean_of[k] for k in sorted(mean_of)]           # row-major order of the pooled map
+    h = [f32(x[i] - mean_of[key[i]]) for i in range(n)]
+    delta, hmax = min(h), max(h)
+    rng = f32(hmax - delta)
+    if rng >= Fraction(2) ** -90:
+        Delta = f32(rng / L)
+        inv = f32(Fraction(L) / rng)
+        if f32(rng * inv) < L:
+            inv = f32_next_up(inv)
+    else:
+        Delta = inv = Fraction(0)
+    codes, xhat = [], []
+    for i, hv in enumerate(h):
+        t = f32(f32(hv - delta) * inv)
+        q = min(L, math.floor(t + Fraction(rand16(seed, plane, i), 65536)))
+        codes.append(q)
+        xhat.append(f32(mean_of[key[i]] + f32(f32(q * Delta) + delta)))
+    return {"lfc": lfc, "delta": delta, "Delta": Delta, "codes": codes, "xhat": xhat, "h": h}
