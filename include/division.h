@@ -228,6 +228,38 @@ int division_kernel_name(int direction, const void *data,
                          int64_t N, int64_t C, int64_t H, int64_t W,
                          division_dtype dt, int B, int b, char *out, size_t cap);
 
+/*
+ * 3-D activation maps (Appendix D: AveragePooling3D / UpSampling3D, the Quant of
+ * Eq. (quantization) unchanged).  x is an N x C x D x H x W tensor, contiguous in
+ * that order; a plane is the D*H*W elements of one (sample, channel) pair, the
+ * blocks are B x B x B (clipped at the far faces, ceil(D/B) x ceil(H/B) x
+ * ceil(W/B) of them, stored in that order), element i of a plane is its
+ * row-major index ((d*H + h)*W + w) for the code position and the random
+ * numbers.  The packed buffer has the layout of the 2-D one with HW = D*H*W
+ * and the block count above.  D = 1 gives exactly the 2-D calls; so does a
+ * volume with H = 1 or W = 1 (D x W resp. D x H maps).  Pointers, alignment,
+ * ownership, stream and error codes as for division_compress /
+ * division_decompress; D*H and D*H*W above 2^31-1 give DIVISION_ERANGE.
+ */
+size_t division_packed_bytes_3d(int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int B, int b,
+                                division_dtype dt);
+
+int division_packed_layout_3d(int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int B, int b,
+                              division_dtype dt, size_t *codes_off, size_t *codes_bytes, size_t *meta_off,
+                              size_t *meta_bytes, size_t *lfc_off, size_t *lfc_bytes);
+
+int division_compress_3d(const void *x, int64_t N, int64_t C, int64_t D, int64_t H, int64_t W,
+                         division_dtype dt, int B, int b, uint64_t seed, void *packed,
+                         size_t packed_capacity, void *hip_stream);
+
+int division_decompress_3d(const void *packed, size_t packed_bytes, int64_t N, int64_t C, int64_t D,
+                           int64_t H, int64_t W, division_dtype dt, int B, int b, void *xhat,
+                           void *hip_stream);
+
+/* division_kernel_name for the 3-D calls. */
+int division_kernel_name_3d(int direction, const void *data, int64_t N, int64_t C, int64_t D, int64_t H,
+                            int64_t W, division_dtype dt, int B, int b, char *out, size_t cap);
+
 /* Version of this ABI (host-only). */
 int division_abi_version(void);
 

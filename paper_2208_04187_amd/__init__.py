@@ -9,3 +9,5 @@ from .autograd import division_saved_tensors  # noqa: F401,E402
 from .binding import (division_dropout_forward, division_mask_backward, division_mask_bytes,  # noqa: F401,E402
                       division_relu_forward)
 from .binding import division_maxpool_backward, division_maxpool_forward  # noqa: F401,E402
+from .binding import (division_compress_3d, division_decompress_3d, division_kernel_name_3d,  # noqa: F401,E402
+                      division_packed_bytes_3d, division_packed_layout_3d)

@@ -66,6 +66,16 @@ def lib() -> ctypes.CDLL:
         L.division_maxpool_backward.argtypes = [vp, sz, vp, i64, i64, i64, i64, ci, ci, vp, vp]
         L.division_kernel_name.restype = ci
         L.division_kernel_name.argtypes = [ci, vp, i64, i64, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
+        L.division_packed_bytes_3d.restype = sz
+        L.division_packed_bytes_3d.argtypes = [i64, i64, i64, i64, i64, ci, ci, ci]
+        L.division_packed_layout_3d.restype = ci
+        L.division_packed_layout_3d.argtypes = [i64, i64, i64, i64, i64, ci, ci, ci] + [ctypes.POINTER(sz)] * 6
+        L.division_compress_3d.restype = ci
+        L.division_compress_3d.argtypes = [vp, i64, i64, i64, i64, i64, ci, ci, ci, u64, vp, sz, vp]
+        L.division_decompress_3d.restype = ci
+        L.division_decompress_3d.argtypes = [vp, sz, i64, i64, i64, i64, i64, ci, ci, ci, vp, vp]
+        L.division_kernel_name_3d.restype = ci
+        L.division_kernel_name_3d.argtypes = [ci, vp, i64, i64, i64, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
         _lib = L
     return _lib
 
@@ -126,6 +136,61 @@ def division_decompress(packed: torch.Tensor, shape, B: int, b: int, dtype=torch
     if rc:
         raise DivisionError(rc, "division_decompress")
     return out
+
+
+def division_packed_bytes_3d(N: int, C: int, D: int, H: int, W: int, B: int, b: int, dtype=torch.float32,
+                             c16: bool = False) -> int:
+    return int(lib().division_packed_bytes_3d(N, C, D, H, W, B, b, _dt(dtype, c16)))
+
+
+def division_packed_layout_3d(N: int, C: int, D: int, H: int, W: int, B: int, b: int, dtype=torch.float32,
+                              c16: bool = False) -> dict:
+    vals = [ctypes.c_size_t() for _ in range(6)]
+    rc = lib().division_packed_layout_3d(N, C, D, H, W, B, b, _dt(dtype, c16), *[ctypes.byref(v) for v in vals])
+    if rc:
+        raise DivisionError(rc, "division_packed_layout_3d")
+    names = ["codes_off", "codes_bytes", "meta_off", "meta_bytes", "lfc_off", "lfc_bytes"]
+    return {n: int(v.value) for n, v in zip(names, vals)}
+
+
+def division_compress_3d(x: torch.Tensor, B: int, b: int, seed: int, packed: torch.Tensor | None = None,
+                         stream=None, c16: bool = False) -> torch.Tensor:
+    """x: contiguous N x C x D x H x W device tensor (float32 or bfloat16).  Returns the packed uint8 buffer."""
+    if x.dim() != 5 or not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous 5-d device tensor")
+    N, C, D, H, W = x.shape
+    need = division_packed_bytes_3d(N, C, D, H, W, B, b, x.dtype, c16)
+    if need == 0:
+        raise DivisionError(1, "division_packed_bytes_3d")
+    if packed is None:
+        packed = torch.empty(need, dtype=torch.uint8, device=x.device)
+    rc = lib().division_compress_3d(x.data_ptr(), N, C, D, H, W, _dt(x.dtype, c16), B, b, seed & (2 ** 64 - 1),
+                                    packed.data_ptr(), packed.numel() * packed.element_size(), _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_compress_3d")
+    return packed
+
+
+def division_decompress_3d(packed: torch.Tensor, shape, B: int, b: int, dtype=torch.float32,
+                           out: torch.Tensor | None = None, stream=None, c16: bool = False) -> torch.Tensor:
+    N, C, D, H, W = shape
+    if out is None:
+        out = torch.empty(shape, dtype=dtype, device=packed.device)
+    rc = lib().division_decompress_3d(packed.data_ptr(), packed.numel() * packed.element_size(),
+                                      N, C, D, H, W, _dt(dtype, c16), B, b, out.data_ptr(), _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_decompress_3d")
+    return out
+
+
+def division_kernel_name_3d(direction: int, shape, B: int, b: int, dtype=torch.float32, data_ptr: int = 0,
+                            c16: bool = False) -> str:
+    buf = ctypes.create_string_buffer(128)
+    N, C, D, H, W = shape
+    rc = lib().division_kernel_name_3d(direction, data_ptr or None, N, C, D, H, W, _dt(dtype, c16), B, b, buf, 128)
+    if rc:
+        raise DivisionError(rc, "division_kernel_name_3d")
+    return buf.value.decode()
 
 
 def _ptr_array(tensors):

@@ -1328,11 +1328,12 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
 struct RowsArgs {
     CompTab tab;
     Regions rg;
-    uint32_t P, H, W, HW, LH, LW, nb, WPP, B;
+    uint32_t P, H, W, HW, LH, LW, nb, WPP, B;      // H, LH: rows / block rows over all depth slices of a 3-D map
+    uint32_t D, Hs, LHs; // depth, rows and block rows of one depth slice (D = 1, Hs = H, LHs = LH for a 2-D map)
     uint32_t G;          // planes per workgroup
     uint32_t xs_floats;  // LDS floats reserved for the chunk (multiple of 4, + slack for ragged last words)
     uint32_t vec_load;   // chunk starts are 16-byte aligned
-    FastDiv d_W, d_B, d_LW, d_HLW, d_nb, d_wpp;
+    FastDiv d_W, d_B, d_LW, d_HLW, d_nb, d_wpp, d_Hs, d_LHs;
 };
 
 // Any block size B (the paper's sweep uses 12, 16, 18 and 64 besides 8).  A workgroup of four
@@ -1342,8 +1343,10 @@ struct RowsArgs {
 //      block's residual (x -> fl(x - m) is monotone, so they are fl(min x - m), fl(max x - m));
 //   3. a lane per plane: min / max over its blocks, scale, keys, meta;
 //   4. a lane per packed word: residual against the block's LFC, quantise, pack.
-template <typename T, int BITS>
-__global__ void __launch_bounds__(kThreads) compress_rows(RowsArgs a) {
+// ND = 3: the plane is a 3-D map (Appendix D) of D slices of Hs rows, blocks of B x B x B; its D*Hs
+// rows are staged and summed as rows like those of a 2-D map, a block adds the rows of its B slices.
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void compress_rows_body(const RowsArgs& a) {
     extern __shared__ float4 smem4[];
     float4* params = smem4;                                                   // [G] (delta, inv scaled, k1, k2)
     float* xs = reinterpret_cast<float*>(smem4 + a.G);                        // [xs_floats] the chunk as fp32
@@ -1428,21 +1431,27 @@ __global__ void __launch_bounds__(kThreads) compress_rows(RowsArgs a) {
         const uint32_t tt = live ? t : 0u;
         const uint32_t g = fdiv(tt, a.d_nb);
         const uint32_t blk = tt - g * a.nb;
-        const uint32_t bi = fdiv(blk, a.d_LW);
-        const uint32_t bj = blk - bi * a.LW;
+        const uint32_t bq = fdiv(blk, a.d_LW);                  // block row, counted over all depth slices
+        const uint32_t bj = blk - bq * a.LW;
+        uint32_t bd = 0, bi = bq;
+        if constexpr (ND == 3) { bd = fdiv(bq, a.d_LHs); bi = bq - bd * a.LHs; }
         const uint32_t r0 = bi * a.B;
-        const uint32_t rows = min(a.B, a.H - r0);
+        const uint32_t rows = min(a.B, a.Hs - r0);
         const uint32_t cols = min(a.B, a.W - bj * a.B);
-        const float4* rp = rowp + g * HLW + r0 * a.LW + bj;
+        const uint32_t z0 = bd * a.B;
+        const uint32_t deps = ND == 3 ? min(a.B, a.D - z0) : 1u;
         double S = 0.0;
         float mn = __builtin_inff(), mx = -__builtin_inff();
-        for (uint32_t rr = 0; rr < rows; ++rr) {
-            const float4 q = rp[rr * a.LW];
-            S += __longlong_as_double((long long)(((uint64_t)__float_as_uint(q.y) << 32) | __float_as_uint(q.x)));
-            mn = fminf(mn, q.z);
-            mx = fmaxf(mx, q.w);
+        for (uint32_t z = 0; z < deps; ++z) {
+            const float4* rp = rowp + g * HLW + ((z0 + z) * a.Hs + r0) * a.LW + bj;
+            for (uint32_t rr = 0; rr < rows; ++rr) {
+                const float4 q = rp[rr * a.LW];
+                S += __longlong_as_double((long long)(((uint64_t)__float_as_uint(q.y) << 32) | __float_as_uint(q.x)));
+                mn = fminf(mn, q.z);
+                mx = fmaxf(mx, q.w);
+            }
         }
-        const float lfc = lfc_round<T>(mean_of(S, rows * cols), kC16<T>);
+        const float lfc = lfc_round<T>(mean_of(S, deps * rows * cols), kC16<T>);
         if (live) {
             lfcs[t] = lfc;
             lfc_store<T>(pt.lfc, (size_t)p0 * a.nb + t, lfc, kC16<T>);
@@ -1488,7 +1497,14 @@ __global__ void __launch_bounds__(kThreads) compress_rows(RowsArgs a) {
             const uint32_t i = e0 + min((uint32_t)e, left - 1u);
             const uint32_t r = fdiv(i, a.d_W);
             const uint32_t c = i - r * a.W;
-            h[e] = xp[i] - lp[fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B)];
+            uint32_t brow;
+            if constexpr (ND == 3) {
+                const uint32_t z = fdiv(r, a.d_Hs);
+                brow = fdiv(z, a.d_B) * a.LHs + fdiv(r - z * a.Hs, a.d_B);
+            } else {
+                brow = fdiv(r, a.d_B);
+            }
+            h[e] = xp[i] - lp[brow * a.LW + fdiv(c, a.d_B)];
         }
         const uint32_t xw0 = k1 + (k * PPW) * kWeyl;
         uint32_t word = 0;
@@ -1500,17 +1516,24 @@ __global__ void __launch_bounds__(kThreads) compress_rows(RowsArgs a) {
     }
 }
 
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) compress_rows(RowsArgs a) { compress_rows_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) compress_rows_3d(RowsArgs a) { compress_rows_body<T, BITS, 3>(a); }
+
 // ------------------------------------------------------------------ compress, any shape (slow)
 
 struct AnyArgs {
     CompTab tab;
     Regions rg;
-    uint32_t P, H, W, HW, LH, LW, nb, WPP, B;
+    uint32_t P, H, W, HW, LH, LW, nb, WPP, B;      // H, LH: rows / block rows of one depth slice
+    uint32_t D;                                     // depth slices (1 for a 2-D map)
 };
 
 // One workgroup per plane; x is re-read from global memory in each pass.
-template <typename T, int BITS>
-__global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) {
+// ND = 3: planes of D x H x W elements with blocks of B x B x B (Appendix D).
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void compress_any_body(const AnyArgs& a) {
     __shared__ float red_min[kThreads], red_max[kThreads];
     __shared__ float4 sh_params;
     constexpr int CPW = 32 / BITS;
@@ -1525,16 +1548,20 @@ __global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) {
     // block min/max of x because x -> fl(x - m) is monotone
     float mn = __builtin_inff(), mx = -__builtin_inff();
     for (uint32_t blk = tid; blk < a.nb; blk += kThreads) {
-        const uint32_t bi = blk / a.LW, bj = blk - bi * a.LW;
+        const uint32_t bq = blk / a.LW, bj = blk - bq * a.LW;
+        uint32_t bd = 0, bi = bq;
+        if constexpr (ND == 3) { bd = bq / a.LH; bi = bq - bd * a.LH; }
         const uint32_t r1 = min(a.H, (bi + 1) * a.B), c1 = min(a.W, (bj + 1) * a.B);
+        const uint32_t z1 = ND == 3 ? min(a.D, (bd + 1) * a.B) : 1u;
         double S = 0.0;
         float xmin = __builtin_inff(), xmax = -__builtin_inff();
         uint32_t cnt = 0;
-        for (uint32_t r = bi * a.B; r < r1; ++r)
-            for (uint32_t c = bj * a.B; c < c1; ++c) {
-                const float v = Elem<T>::load(xp, (size_t)r * a.W + c);
-                S += (double)v; xmin = fminf(xmin, v); xmax = fmaxf(xmax, v); ++cnt;
-            }
+        for (uint32_t z = bd * a.B; z < z1; ++z)
+            for (uint32_t r = bi * a.B; r < r1; ++r)
+                for (uint32_t c = bj * a.B; c < c1; ++c) {
+                    const float v = Elem<T>::load(xp, ((size_t)z * a.H + r) * a.W + c);
+                    S += (double)v; xmin = fminf(xmin, v); xmax = fmaxf(xmax, v); ++cnt;
+                }
         const float lfc = lfc_round<T>((float)(S / (double)cnt), kC16<T>);
         lfc_store<T>(pt.lfc, lfc0 + blk, lfc, kC16<T>);
         mn = fminf(mn, xmin - lfc);
@@ -1568,8 +1595,15 @@ __global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) {
             const uint32_t i = k * CPW + e;
             if (i >= a.HW) break;
             const uint32_t r = i / a.W, c = i - r * a.W;
+            uint32_t brow;
+            if constexpr (ND == 3) {
+                const uint32_t z = r / a.H;
+                brow = (z / a.B) * a.LH + (r - z * a.H) / a.B;
+            } else {
+                brow = r / a.B;
+            }
             // written by this workgroup in pass A; visible after the barrier above
-            const float lfc = lfc_load<T>(pt.lfc, lfc0 + (r / a.B) * a.LW + c / a.B, kC16<T>);
+            const float lfc = lfc_load<T>(pt.lfc, lfc0 + brow * a.LW + c / a.B, kC16<T>);
             const float h = Elem<T>::load(xp, i) - lfc;
             const uint32_t w = pair_word(k1 + (i >> 1) * kWeyl, k2);
             const uint32_t q = (i & 1u) ? quant<1>(h, delta, inv16, w) : quant<0>(h, delta, inv16, w);
@@ -1578,6 +1612,11 @@ __global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) {
         pt.codes[(size_t)p * a.WPP + k] = word;
     }
 }
+
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) compress_any(AnyArgs a) { compress_any_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) compress_any_3d(AnyArgs a) { compress_any_body<T, BITS, 3>(a); }
 
 // ------------------------------------------------------------------ decompress
 
@@ -1588,8 +1627,21 @@ struct DecArgs {
     uint32_t G;          // planes per workgroup
     uint32_t q4;         // HW / 4
     uint32_t w4;         // W / 4
-    FastDiv d_q4, d_w4, d_B, d_W, d_HW;
+    uint32_t Hs, LHs;    // 3-D maps: rows and block rows of one depth slice (H counts the rows of all slices)
+    FastDiv d_q4, d_w4, d_B, d_W, d_HW, d_Hs;
 };
+
+// Index of the first block of the block row that holds row r; for a 3-D map (Appendix D,
+// UpSampling3D) r counts the rows of all depth slices.
+template <int ND>
+__device__ __forceinline__ uint32_t lfc_row(const DecArgs& a, uint32_t r) {
+    if constexpr (ND == 3) {
+        const uint32_t z = fdiv(r, a.d_Hs);
+        return (fdiv(z, a.d_B) * a.LHs + fdiv(r - z * a.Hs, a.d_B)) * a.LW;
+    } else {
+        return fdiv(r, a.d_B) * a.LW;
+    }
+}
 
 // Sec. 4.2: hh = Delta*q + delta ; reconstruction: xhat = lfc + hh (three fp32 ops)
 __device__ __forceinline__ float dequant(uint32_t q, float Delta, float delta, float lfc) {
@@ -1670,8 +1722,8 @@ __device__ __forceinline__ void dec_lds(const DecArgs& a, uint32_t*& s_codes, fl
 
 // W % 4 == 0 and B % 4 == 0: the four elements of a vector lie in one row and
 // share one LFC value.  A workgroup streams G whole planes.
-template <typename T, int BITS>
-__global__ void __launch_bounds__(kThreads) decompress_rowvec(DecArgs a) {
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void decompress_rowvec_body(const DecArgs& a) {
     const DecPtrs pt = dec_ptrs(a.tab, a.rg);
     uint32_t* s_codes; float2* s_meta; T* s_lfc;
     dec_lds<T>(a, s_codes, s_meta, s_lfc);
@@ -1692,13 +1744,18 @@ __global__ void __launch_bounds__(kThreads) decompress_rowvec(DecArgs a) {
         else c4 = s_codes[g * a.WPP + fi];
         const uint32_t r = fdiv(fi, a.d_w4);
         const uint32_t c = (fi - r * a.w4) * 4;
-        const float lfc = Elem<T>::load(s_lfc, g * a.nb + fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B));
+        const float lfc = Elem<T>::load(s_lfc, g * a.nb + lfc_row<ND>(a, r) + fdiv(c, a.d_B));
         float o[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = dequant((c4 >> (e * BITS)) & Lq, dd.y, dd.x, lfc);
         store4(out, (size_t)vi * 4, o[0], o[1], o[2], o[3]);
     }
 }
+
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_rowvec(DecArgs a) { decompress_rowvec_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_rowvec_3d(DecArgs a) { decompress_rowvec_body<T, BITS, 3>(a); }
 
 // H*W a multiple of 4 and at most 255 blocks per plane: the LFC index of every
 // element of a plane is looked up in a table (one byte per element, four per
@@ -1750,8 +1807,8 @@ __global__ void __launch_bounds__(kThreads) decompress_table(DecArgs a) {
 // four consecutive elements per lane step; every element finds its own plane,
 // row, column and block.  G*HW is a multiple of 4 whenever G < P remains, so
 // vector stores stay aligned; the ragged end of the last chunk is scalar.
-template <typename T, int BITS>
-__global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) {
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void decompress_flat_body(const DecArgs& a) {
     const DecPtrs pt = dec_ptrs(a.tab, a.rg);
     uint32_t* s_codes; float2* s_meta; T* s_lfc;
     dec_lds<T>(a, s_codes, s_meta, s_lfc);
@@ -1793,12 +1850,12 @@ __global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) {
             const T* lp = s_lfc + g * a.nb;
             uint32_t r = fdiv(i, a.d_W);
             uint32_t c = i - r * a.W;
-            uint32_t rowoff = fdiv(r, a.d_B) * a.LW;
+            uint32_t rowoff = lfc_row<ND>(a, r);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float lfc = Elem<T>::load(lp, rowoff + fdiv(c, a.d_B));
                 o[e] = dequant((w >> (e * BITS)) & Lq, dd.y, dd.x, lfc);
-                if (++c == a.W) { c = 0; ++r; rowoff = fdiv(r, a.d_B) * a.LW; }
+                if (++c == a.W) { c = 0; ++r; rowoff = lfc_row<ND>(a, r); }
             }
             store4(out, e0, o[0], o[1], o[2], o[3]);
             continue;
@@ -1811,7 +1868,7 @@ __global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) {
             if (e0 + e < n) {
                 const float2 dd = s_meta[g];
                 const uint32_t q = (s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS)) & Lq;
-                const float lfc = Elem<T>::load(s_lfc, g * a.nb + fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B));
+                const float lfc = Elem<T>::load(s_lfc, g * a.nb + lfc_row<ND>(a, r) + fdiv(c, a.d_B));
                 o[e] = dequant(q, dd.y, dd.x, lfc);
                 ++i;
                 if (++c == a.W) { c = 0; ++r; }
@@ -1827,9 +1884,14 @@ __global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) {
     }
 }
 
-// planes too large for the 32-bit index tricks above: one element per thread step
 template <typename T, int BITS>
-__global__ void __launch_bounds__(kThreads) decompress_scalar(DecArgs a) {
+__global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) { decompress_flat_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_flat_3d(DecArgs a) { decompress_flat_body<T, BITS, 3>(a); }
+
+// planes too large for the 32-bit index tricks above: one element per thread step
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void decompress_scalar_body(const DecArgs& a) {
     const DecPtrs pt = dec_ptrs(a.tab, a.rg);
     constexpr uint32_t CPW = 32 / BITS;
     constexpr uint32_t Lq = (1u << BITS) - 1u;
@@ -1841,10 +1903,22 @@ __global__ void __launch_bounds__(kThreads) decompress_scalar(DecArgs a) {
     for (uint32_t i = threadIdx.x; i < a.HW; i += kThreads) {
         const uint32_t r = i / a.W, c = i - r * a.W;
         const uint32_t q = (cp[i / CPW] >> ((i % CPW) * BITS)) & Lq;
-        const float lfc = lfc_load<T>(pt.lfc, lfc0 + (r / a.B) * a.LW + c / a.B, kC16<T>);
+        uint32_t brow;
+        if constexpr (ND == 3) {
+            const uint32_t z = r / a.Hs;
+            brow = (z / a.B) * a.LHs + (r - z * a.Hs) / a.B;
+        } else {
+            brow = r / a.B;
+        }
+        const float lfc = lfc_load<T>(pt.lfc, lfc0 + brow * a.LW + c / a.B, kC16<T>);
         Elem<T>::store(out, i, dequant(q, dd.y, dd.x, lfc));
     }
 }
+
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_scalar(DecArgs a) { decompress_scalar_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_scalar_3d(DecArgs a) { decompress_scalar_body<T, BITS, 3>(a); }
 
 // ------------------------------------------------------------------ host side
 
@@ -1898,23 +1972,27 @@ __global__ void __launch_bounds__(64) decompress_lane(DecArgs a) {
 }
 
 struct Layout {
-    uint64_t P, HW, LH, LW, nb, WPP;
+    uint64_t P, HW, LD, LH, LW, nb, WPP;      // HW = elements per plane (D*H*W), nb = LD*LH*LW blocks
     size_t codes_off, codes_bytes, meta_off, meta_bytes, lfc_off, lfc_bytes, total;
 };
 
 size_t align16(size_t v) { return (v + 15u) & ~(size_t)15u; }
 
-int make_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, int dt, Layout* L) {
-    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4 && b != 8)) return DIVISION_EINVAL;
+// A plane is D x H x W elements (Appendix D: 3-D maps); D = 1 for the 2-D maps of Sec. 4.1.
+int make_layout(int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int B, int b, int dt, Layout* L) {
+    if (N <= 0 || C <= 0 || D <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4 && b != 8)) return DIVISION_EINVAL;
     if (dt != DIVISION_F32 && dt != DIVISION_BF16 && dt != DIVISION_F32_C16) return DIVISION_EINVAL;
     const uint64_t lim31 = 0x7fffffffull;
-    if ((uint64_t)N > lim31 || (uint64_t)C > lim31 || (uint64_t)H > lim31 || (uint64_t)W > lim31) return DIVISION_ERANGE;
+    if ((uint64_t)N > lim31 || (uint64_t)C > lim31 || (uint64_t)D > lim31 || (uint64_t)H > lim31 || (uint64_t)W > lim31)
+        return DIVISION_ERANGE;
     L->P = (uint64_t)N * (uint64_t)C;
-    L->HW = (uint64_t)H * (uint64_t)W;
+    if ((uint64_t)D * (uint64_t)H > lim31) return DIVISION_ERANGE;
+    L->HW = (uint64_t)D * (uint64_t)H * (uint64_t)W;
     if (L->P > lim31 || L->HW > lim31 || L->P * L->HW > (1ull << 40)) return DIVISION_ERANGE;
+    L->LD = ((uint64_t)D + B - 1) / B;
     L->LH = ((uint64_t)H + B - 1) / B;
     L->LW = ((uint64_t)W + B - 1) / B;
-    L->nb = L->LH * L->LW;
+    L->nb = L->LD * L->LH * L->LW;
     const uint64_t cpw = 32 / b;
     L->WPP = (L->HW + cpw - 1) / cpw;
     const size_t lfc_es = dt == DIVISION_F32 ? 4 : 2;          // H^L: element type of x, bfloat16 in the cached-as-bf16 mode
@@ -2148,13 +2226,16 @@ bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
 }
 
 // Fills the any-block-size compress plan; false when a plane does not fit LDS or the 32-bit index tricks.
-bool plan_rows(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, const void* x,
+// Hs = rows of one depth slice, D = depth slices (1 for a 2-D map).
+bool plan_rows(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, int b, size_t es, const void* x,
                RowsArgs* a, uint32_t* grid, size_t* lds) {
     (void)b;
+    const int64_t H = D * Hs;                       // rows of all slices
     if ((uint64_t)B > L.HW + 64) return false;      // keeps fdiv(r, B) exact; such a B is "one block" anyway: see below
     const uint64_t per_plane = 4ull * L.HW + 16ull * (uint64_t)H * L.LW + 12ull * L.nb + 16ull;
     if (per_plane + 256 > kLdsMax) return false;
     if (!fastdiv_ok(L.HW, (uint64_t)W) || !fastdiv_ok((uint64_t)(H > W ? H : W), (uint64_t)B)) return false;
+    if (!fastdiv_ok((uint64_t)H, (uint64_t)Hs) || !fastdiv_ok(L.LD * L.LH, L.LH)) return false;
     uint64_t G = kLdsTarget / per_plane;
     if (G < 1) G = 1;
     if (G > L.P) G = L.P;
@@ -2171,12 +2252,15 @@ bool plan_rows(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
         !fastdiv_ok(L.nb, L.LW) || !fastdiv_ok(G * L.WPP + kThreads, L.WPP))
         return false;
     a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
-    a->LH = (uint32_t)L.LH; a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP; a->B = (uint32_t)B;
+    a->LH = (uint32_t)(L.LD * L.LH); a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP; a->B = (uint32_t)B;
+    a->D = (uint32_t)D; a->Hs = (uint32_t)Hs; a->LHs = (uint32_t)L.LH;
     a->G = (uint32_t)G;
     a->xs_floats = (uint32_t)((G * L.HW + 3) / 4 * 4);
     a->vec_load = vec_load;
     a->d_W = make_fastdiv((uint32_t)W);
     a->d_B = make_fastdiv((uint32_t)B);
+    a->d_Hs = make_fastdiv((uint32_t)Hs);
+    a->d_LHs = make_fastdiv((uint32_t)L.LH);
     a->d_LW = make_fastdiv((uint32_t)L.LW);
     a->d_HLW = make_fastdiv((uint32_t)HLW);
     a->d_nb = make_fastdiv((uint32_t)L.nb);
@@ -2247,14 +2331,19 @@ size_t dec_lds_bytes(const Layout& L, size_t es, uint64_t G) {
 }
 constexpr size_t kDecLdsMax = 60u << 10;
 
-int plan_decompress(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* xhat,
+// Hs = rows of one depth slice, D = depth slices (1 for a 2-D map; the table kernel takes 2-D maps only).
+int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, size_t es, const void* xhat,
                     DecArgs* a, uint32_t* grid) {
+    const int64_t H = D * Hs;
     a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
-    a->LH = (uint32_t)L.LH; a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP; a->B = (uint32_t)B;
+    a->LH = (uint32_t)(L.LD * L.LH); a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP; a->B = (uint32_t)B;
+    a->Hs = (uint32_t)Hs; a->LHs = (uint32_t)L.LH;
     a->d_B = make_fastdiv((uint32_t)B);
     a->d_W = make_fastdiv((uint32_t)W);
     a->d_HW = make_fastdiv((uint32_t)L.HW);
-    const bool small_idx = fastdiv_ok((uint64_t)H, (uint64_t)B) && fastdiv_ok((uint64_t)W, (uint64_t)B);
+    a->d_Hs = make_fastdiv((uint32_t)Hs);
+    const bool small_idx = fastdiv_ok((uint64_t)H, (uint64_t)B) && fastdiv_ok((uint64_t)W, (uint64_t)B) &&
+                           fastdiv_ok((uint64_t)H, (uint64_t)Hs);
     const bool out_vec_aligned = ((uintptr_t)xhat % (4 * es)) == 0;
     const uint64_t target = 16ull * 4 * kThreads;      // elements per workgroup
     // one-block planes with an odd element count: a lane per plane, 64 planes per round
@@ -2282,7 +2371,7 @@ int plan_decompress(const Layout& L, int64_t H, int64_t W, int B, size_t es, con
         }
     }
     // planes of whole vectors with few blocks: LFC indices from a table in LDS
-    if (L.HW % 4 == 0 && L.nb > 1 && L.nb <= 255 && small_idx && out_vec_aligned && fastdiv_ok(L.HW, (uint64_t)W)) {
+    if (D == 1 && L.HW % 4 == 0 && L.nb > 1 && L.nb <= 255 && small_idx && out_vec_aligned && fastdiv_ok(L.HW, (uint64_t)W)) {
         a->q4 = (uint32_t)(L.HW / 4);
         uint64_t G = (target / 4 + a->q4 - 1) / a->q4;
         if (G > L.P) G = L.P;
@@ -2321,38 +2410,32 @@ hipError_t with_type_bits(division_dtype dt, int b, F&& f) {
     return dt == DIVISION_F32 ? bits(float{}) : dt == DIVISION_BF16 ? bits(bf16_t{}) : bits(f32c16_t{});
 }
 
-}  // namespace
-
-// ------------------------------------------------------------------ C ABI
-
-extern "C" {
-
-int division_abi_version(void) { return 1; }
-
-size_t division_packed_bytes(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, division_dtype dt) {
-    Layout L;
-    if (make_layout(N, C, H, W, B, b, (int)dt, &L) != DIVISION_OK) return 0;
-    return L.total;
+// A 3-D map with a dimension of extent 1 is a 2-D map with the same flat element order, the same
+// blocks and the same packed buffer: D x 1 x W -> D x W, D x H x 1 -> D x H.  (1 x H x W needs nothing.)
+void squeeze_dims(int64_t& D, int64_t& H, int64_t& W) {
+    if (D > 1 && H == 1) { H = D; D = 1; }
+    else if (D > 1 && W == 1) { W = H; H = D; D = 1; }
 }
 
-int division_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, division_dtype dt,
-                           size_t* codes_off, size_t* codes_bytes, size_t* meta_off, size_t* meta_bytes,
-                           size_t* lfc_off, size_t* lfc_bytes) {
+int packed_layout_impl(int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int B, int b, division_dtype dt,
+                       size_t* codes_off, size_t* codes_bytes, size_t* meta_off, size_t* meta_bytes,
+                       size_t* lfc_off, size_t* lfc_bytes) {
     if (!codes_off || !codes_bytes || !meta_off || !meta_bytes || !lfc_off || !lfc_bytes) return DIVISION_EINVAL;
     Layout L;
-    if (make_layout(N, C, H, W, B, b, (int)dt, &L) != DIVISION_OK) return DIVISION_EINVAL;
+    if (make_layout(N, C, D, H, W, B, b, (int)dt, &L) != DIVISION_OK) return DIVISION_EINVAL;
     *codes_off = L.codes_off; *codes_bytes = L.codes_bytes;
     *meta_off = L.meta_off;   *meta_bytes = L.meta_bytes;
     *lfc_off = L.lfc_off;     *lfc_bytes = L.lfc_bytes;
     return DIVISION_OK;
 }
 
-int division_compress_batch(int count, const void* const* x, void* const* packed, const uint64_t* seeds,
-                            int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
-                            int B, int b, size_t packed_capacity, void* hip_stream) {
+int compress_impl(int count, const void* const* x, void* const* packed, const uint64_t* seeds,
+                  int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, division_dtype dt,
+                  int B, int b, size_t packed_capacity, void* hip_stream) {
     if (count < 0 || (count > 0 && (!x || !packed || !seeds))) return DIVISION_EINVAL;
+    squeeze_dims(D, H, W);
     Layout L;
-    const int rc = make_layout(N, C, H, W, B, b, (int)dt, &L);
+    const int rc = make_layout(N, C, D, H, W, B, b, (int)dt, &L);
     if (rc != DIVISION_OK) return rc;
     if (packed_capacity < L.total) return DIVISION_ESIZE;
     const size_t es = dt == DIVISION_BF16 ? 2 : 4;
@@ -2386,17 +2469,18 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
         uint32_t grid = 0;
         int vec = 1, nt = 64, nw = 1;
         enum { REGS, LANE, ITEMS, WAVE, TILE, ROWS, ANY } kind;
-        if (plan_regs(L, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
+        const bool flat = D == 1;               // the register, item, wavefront and tile kernels take 2-D maps
+        if (flat && plan_regs(L, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
         else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
-        else if (plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
-        else if (plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
+        else if (flat && plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
+        else if (flat && plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
             kind = WAVE; wa.tab = tab; wa.rg = rg;
-        } else if (plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) { kind = TILE; a.tab = tab; a.rg = rg; }
-        else if (plan_rows(L, H, W, B, b, es, xa, &wa2, &grid, &lds)) { kind = ROWS; wa2.tab = tab; wa2.rg = rg; }
+        } else if (flat && plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) { kind = TILE; a.tab = tab; a.rg = rg; }
+        else if (plan_rows(L, D, H, W, B, b, es, xa, &wa2, &grid, &lds)) { kind = ROWS; wa2.tab = tab; wa2.rg = rg; }
         else {
             kind = ANY;
             g.tab = tab; g.rg = rg;
-            g.P = (uint32_t)L.P; g.H = (uint32_t)H; g.W = (uint32_t)W; g.HW = (uint32_t)L.HW;
+            g.P = (uint32_t)L.P; g.H = (uint32_t)H; g.W = (uint32_t)W; g.HW = (uint32_t)L.HW; g.D = (uint32_t)D;
             g.LH = (uint32_t)L.LH; g.LW = (uint32_t)L.LW; g.nb = (uint32_t)L.nb; g.WPP = (uint32_t)L.WPP; g.B = (uint32_t)B;
             grid = (uint32_t)L.P;
         }
@@ -2411,12 +2495,17 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
                 case TILE: return launch_tile<T, BITS>(B, vec, a, gd, lds, st);
                 case LANE: hipLaunchKernelGGL((compress_lane<T, BITS>), gd, dim3(64), lds, st, la); return hipGetLastError();
                 case ROWS: {
-                    const hipError_t e = allow_large_lds(compress_rows<T, BITS>, lds);
+                    void (*kern)(RowsArgs) = flat ? compress_rows<T, BITS> : compress_rows_3d<T, BITS>;
+                    const hipError_t e = allow_large_lds(kern, lds);
                     if (e != hipSuccess) return e;
-                    hipLaunchKernelGGL((compress_rows<T, BITS>), gd, dim3(kThreads), lds, st, wa2);
+                    hipLaunchKernelGGL(kern, gd, dim3(kThreads), lds, st, wa2);
                     return hipGetLastError();
                 }
-                default: hipLaunchKernelGGL((compress_any<T, BITS>), gd, dim3(kThreads), 0, st, g); return hipGetLastError();
+                default: {
+                    void (*kern)(AnyArgs) = flat ? compress_any<T, BITS> : compress_any_3d<T, BITS>;
+                    hipLaunchKernelGGL(kern, gd, dim3(kThreads), 0, st, g);
+                    return hipGetLastError();
+                }
             }
         });
         if (err != hipSuccess) return DIVISION_EHIP;
@@ -2424,18 +2513,13 @@ int division_compress_batch(int count, const void* const* x, void* const* packed
     return DIVISION_OK;
 }
 
-int division_compress(const void* x, int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
-                      int B, int b, uint64_t seed, void* packed, size_t packed_capacity, void* hip_stream) {
-    if (!x || !packed) return DIVISION_EINVAL;
-    return division_compress_batch(1, &x, &packed, &seed, N, C, H, W, dt, B, b, packed_capacity, hip_stream);
-}
-
-int division_decompress_batch(int count, const void* const* packed, void* const* xhat, size_t packed_bytes,
-                              int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
-                              int B, int b, void* hip_stream) {
+int decompress_impl(int count, const void* const* packed, void* const* xhat, size_t packed_bytes,
+                    int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, division_dtype dt,
+                    int B, int b, void* hip_stream) {
     if (count < 0 || (count > 0 && (!packed || !xhat))) return DIVISION_EINVAL;
+    squeeze_dims(D, H, W);
     Layout L;
-    const int rc = make_layout(N, C, H, W, B, b, (int)dt, &L);
+    const int rc = make_layout(N, C, D, H, W, B, b, (int)dt, &L);
     if (rc != DIVISION_OK) return rc;
     if (packed_bytes < L.total) return DIVISION_ESIZE;
     const size_t es = dt == DIVISION_BF16 ? 2 : 4;
@@ -2452,15 +2536,19 @@ int division_decompress_batch(int count, const void* const* packed, void* const*
         const int cnt = count - i0 < kMaxBatch ? count - i0 : kMaxBatch;
         DecArgs a{};
         uint32_t grid = 0;
-        const int kind = plan_decompress(L, H, W, B, es, reinterpret_cast<const void*>(all_out ? all_out : 16), &a, &grid);
+        const int kind = plan_decompress(L, D, H, W, B, es, reinterpret_cast<const void*>(all_out ? all_out : 16), &a, &grid);
         for (int i = 0; i < cnt; ++i) { a.tab.pk[i] = packed[i0 + i]; a.tab.xhat[i] = xhat[i0 + i]; }
         a.rg = rg;
         void (*kern)(DecArgs) = nullptr;
         with_type_bits(dt, b, [&](auto tag, auto bits) -> hipError_t {
             using T = decltype(tag);
             constexpr int BITS = decltype(bits)::value;
-            kern = kind == 0 ? decompress_rowvec<T, BITS> : kind == 3 ? decompress_table<T, BITS>
-                 : kind == 1 ? decompress_flat<T, BITS> : kind == 4 ? decompress_lane<T, BITS> : decompress_scalar<T, BITS>;
+            if (D == 1)
+                kern = kind == 0 ? decompress_rowvec<T, BITS> : kind == 3 ? decompress_table<T, BITS>
+                     : kind == 1 ? decompress_flat<T, BITS> : kind == 4 ? decompress_lane<T, BITS> : decompress_scalar<T, BITS>;
+            else
+                kern = kind == 0 ? decompress_rowvec_3d<T, BITS> : kind == 1 ? decompress_flat_3d<T, BITS>
+                     : kind == 4 ? decompress_lane<T, BITS> : decompress_scalar_3d<T, BITS>;
             return hipSuccess;
         });
         // LDS of the streaming kernels: staged codes, meta and LFC of G planes (+ the block table)
@@ -2473,43 +2561,119 @@ int division_decompress_batch(int count, const void* const* packed, void* const*
     return DIVISION_OK;
 }
 
-int division_decompress(const void* packed, size_t packed_bytes, int64_t N, int64_t C, int64_t H, int64_t W,
-                        division_dtype dt, int B, int b, void* xhat, void* hip_stream) {
-    if (!xhat || !packed) return DIVISION_EINVAL;
-    return division_decompress_batch(1, &packed, &xhat, packed_bytes, N, C, H, W, dt, B, b, hip_stream);
-}
-
-int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, int64_t H, int64_t W,
-                         division_dtype dt, int B, int b, char* out, size_t cap) {
+int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int64_t D, int64_t H, int64_t W,
+                     division_dtype dt, int B, int b, char* out, size_t cap) {
     if (!out || cap == 0) return DIVISION_EINVAL;
+    squeeze_dims(D, H, W);
     Layout L;
-    const int rc = make_layout(N, C, H, W, B, b, (int)dt, &L);
+    const int rc = make_layout(N, C, D, H, W, B, b, (int)dt, &L);
     if (rc != DIVISION_OK) return rc;
+    const bool flat = D == 1;
+    const char* sfx = flat ? "" : "_3d";
     const size_t es = dt == DIVISION_BF16 ? 2 : 4;
     const char* tn = dt == DIVISION_BF16 ? "bf16_t" : dt == DIVISION_F32_C16 ? "f32c16_t" : "float";
     int n;
     if (direction == 0) {
         TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
-        if (plan_regs(L, H, W, B, es, data, &ra, &grid, &lds, &nw))
+        if (flat && plan_regs(L, H, W, B, es, data, &ra, &grid, &lds, &nw))
             n = snprintf(out, cap, "compress_regs<%s, %d, %d, %d>", tn, b, B, nw);
         else if (plan_lane(L, es, data, &la, &grid, &lds))
             n = snprintf(out, cap, "compress_lane<%s, %d>", tn, b);
-        else if (plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
+        else if (flat && plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_items<%s, %d, %d, %d, %d>", tn, b, B, vec, H == 1 ? 1 : B);
-        else if (plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))
+        else if (flat && plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_wave<%s, %d, %d, %d>", tn, b, B, vec);
-        else if (plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
+        else if (flat && plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
             n = snprintf(out, cap, "compress_tile<%s, %d, %d, %d, %d>", tn, b, B, vec, nt);
-        else if (plan_rows(L, H, W, B, b, es, data, &wa2, &grid, &lds))
-            n = snprintf(out, cap, "compress_rows<%s, %d>", tn, b);
+        else if (plan_rows(L, D, H, W, B, b, es, data, &wa2, &grid, &lds))
+            n = snprintf(out, cap, "compress_rows%s<%s, %d>", sfx, tn, b);
         else
-            n = snprintf(out, cap, "compress_any<%s, %d>", tn, b);
+            n = snprintf(out, cap, "compress_any%s<%s, %d>", sfx, tn, b);
     } else {
         DecArgs a{}; uint32_t grid = 0;
-        const int kind = plan_decompress(L, H, W, B, es, data, &a, &grid);
-        n = snprintf(out, cap, "%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 3 ? "decompress_table" : kind == 1 ? "decompress_flat" : kind == 4 ? "decompress_lane" : "decompress_scalar", tn, b);
+        const int kind = plan_decompress(L, D, H, W, B, es, data, &a, &grid);
+        n = snprintf(out, cap, "%s%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 3 ? "decompress_table" : kind == 1 ? "decompress_flat" : kind == 4 ? "decompress_lane" : "decompress_scalar",
+                     kind == 4 ? "" : sfx, tn, b);
     }
     return (n < 0 || (size_t)n >= cap) ? DIVISION_ESIZE : DIVISION_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI
+
+extern "C" {
+
+int division_abi_version(void) { return 1; }
+
+size_t division_packed_bytes(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, division_dtype dt) {
+    Layout L;
+    if (make_layout(N, C, 1, H, W, B, b, (int)dt, &L) != DIVISION_OK) return 0;
+    return L.total;
+}
+
+size_t division_packed_bytes_3d(int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int B, int b, division_dtype dt) {
+    Layout L;
+    if (make_layout(N, C, D, H, W, B, b, (int)dt, &L) != DIVISION_OK) return 0;
+    return L.total;
+}
+
+int division_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W, int B, int b, division_dtype dt,
+                           size_t* codes_off, size_t* codes_bytes, size_t* meta_off, size_t* meta_bytes,
+                           size_t* lfc_off, size_t* lfc_bytes) {
+    return packed_layout_impl(N, C, 1, H, W, B, b, dt, codes_off, codes_bytes, meta_off, meta_bytes, lfc_off, lfc_bytes);
+}
+
+int division_packed_layout_3d(int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int B, int b, division_dtype dt,
+                              size_t* codes_off, size_t* codes_bytes, size_t* meta_off, size_t* meta_bytes,
+                              size_t* lfc_off, size_t* lfc_bytes) {
+    return packed_layout_impl(N, C, D, H, W, B, b, dt, codes_off, codes_bytes, meta_off, meta_bytes, lfc_off, lfc_bytes);
+}
+
+int division_compress_batch(int count, const void* const* x, void* const* packed, const uint64_t* seeds,
+                            int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
+                            int B, int b, size_t packed_capacity, void* hip_stream) {
+    return compress_impl(count, x, packed, seeds, N, C, 1, H, W, dt, B, b, packed_capacity, hip_stream);
+}
+
+int division_compress(const void* x, int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
+                      int B, int b, uint64_t seed, void* packed, size_t packed_capacity, void* hip_stream) {
+    if (!x || !packed) return DIVISION_EINVAL;
+    return compress_impl(1, &x, &packed, &seed, N, C, 1, H, W, dt, B, b, packed_capacity, hip_stream);
+}
+
+int division_compress_3d(const void* x, int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, division_dtype dt,
+                         int B, int b, uint64_t seed, void* packed, size_t packed_capacity, void* hip_stream) {
+    if (!x || !packed) return DIVISION_EINVAL;
+    return compress_impl(1, &x, &packed, &seed, N, C, D, H, W, dt, B, b, packed_capacity, hip_stream);
+}
+
+int division_decompress_batch(int count, const void* const* packed, void* const* xhat, size_t packed_bytes,
+                              int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
+                              int B, int b, void* hip_stream) {
+    return decompress_impl(count, packed, xhat, packed_bytes, N, C, 1, H, W, dt, B, b, hip_stream);
+}
+
+int division_decompress(const void* packed, size_t packed_bytes, int64_t N, int64_t C, int64_t H, int64_t W,
+                        division_dtype dt, int B, int b, void* xhat, void* hip_stream) {
+    if (!xhat || !packed) return DIVISION_EINVAL;
+    return decompress_impl(1, &packed, &xhat, packed_bytes, N, C, 1, H, W, dt, B, b, hip_stream);
+}
+
+int division_decompress_3d(const void* packed, size_t packed_bytes, int64_t N, int64_t C, int64_t D, int64_t H, int64_t W,
+                           division_dtype dt, int B, int b, void* xhat, void* hip_stream) {
+    if (!xhat || !packed) return DIVISION_EINVAL;
+    return decompress_impl(1, &packed, &xhat, packed_bytes, N, C, D, H, W, dt, B, b, hip_stream);
+}
+
+int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, int64_t H, int64_t W,
+                         division_dtype dt, int B, int b, char* out, size_t cap) {
+    return kernel_name_impl(direction, data, N, C, 1, H, W, dt, B, b, out, cap);
+}
+
+int division_kernel_name_3d(int direction, const void* data, int64_t N, int64_t C, int64_t D, int64_t H, int64_t W,
+                            division_dtype dt, int B, int b, char* out, size_t cap) {
+    return kernel_name_impl(direction, data, N, C, D, H, W, dt, B, b, out, cap);
 }
 
 }  // extern "C"

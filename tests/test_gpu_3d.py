@@ -1,0 +1,98 @@
+"""GPU parity of the 3-D activation maps (Appendix D) against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2208_04187_amd as pkg
+from tests.parity import to_host_array
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # shape (N, C, D, H, W), B, b                 what it exercises
+    ((2, 3, 8, 8, 8), 4, 2),                      # cubes of 4: LDS kernel, vector rows
+    ((3, 5, 16, 16, 16), 8, 2),                   # 4096-element planes, several per chunk
+    ((2, 3, 5, 9, 13), 4, 2),                     # every extent ragged, odd plane size
+    ((2, 2, 6, 10, 7), 3, 4),
+    ((5, 7, 4, 12, 20), 8, 4),                    # depth shorter than the block
+    ((2, 3, 12, 4, 20), 8, 8),                    # rows shorter than the block
+    ((3, 2, 10, 14, 14), 4, 8),
+    ((2, 3, 9, 9, 9), 2, 2),                      # 125 blocks per plane
+    ((2, 2, 7, 6, 5), 1, 4),                      # B = 1
+    ((2, 3, 16, 28, 28), 8, 2),                   # 12544-element planes
+    ((1, 2, 16, 56, 56), 8, 2),                   # plane beyond LDS: workgroup per plane
+    ((1, 3, 20, 30, 34), 12, 4),                  # same, ragged, B = 12
+    ((1, 2, 40, 40, 40), 8, 8),                   # codes of a plane beyond the staged decompress: scalar kernel
+    ((1, 2, 33, 35, 37), 16, 2),
+    ((4, 9, 3, 3, 3), 8, 2),                      # one block, odd element count: lane kernels
+    ((3, 4, 2, 4, 6), 8, 4),                      # one block, even element count
+    ((2, 3, 7, 1, 30), 8, 2),                     # H = 1: a D x W map
+    ((2, 3, 7, 30, 1), 8, 2),                     # W = 1: a D x H map
+    ((2, 3, 1, 28, 28), 8, 2),                    # D = 1: the 2-D call
+    ((70, 9, 4, 4, 4), 4, 2),                     # 630 small planes, ragged last chunk
+]
+
+
+@pytest.mark.parametrize("shape,B,b", CASES)
+@pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
+def test_volumes_match_oracle(shape, B, b, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    c16 = mode == "c16"
+    dt = oracle.F32_C16 if c16 else (oracle.BF16 if mode == "bf16" else oracle.F32)
+    g = torch.Generator().manual_seed(9000 + sum(shape) + 17 * B + b)
+    x = torch.relu(torch.randn(shape, generator=g) * 1.5 + 0.2).to(dtype)
+    x[0, 0] = -2.25                                                   # constant plane: degenerate scale
+    xh, _ = to_host_array(x)
+    seed = 0x3D3D3D3D00 + B
+    ref = oracle.compress(xh, B, b, seed, dt, threads=16)
+    need = pkg.division_packed_bytes_3d(*shape, B, b, dtype, c16)
+    assert need == ref.size
+    pk = torch.full((need,), 0xA5, dtype=torch.uint8, device="cuda:0")
+    pkg.division_compress_3d(x.to("cuda:0"), B, b, seed, packed=pk, c16=c16)
+    y = pkg.division_decompress_3d(pk, shape, B, b, dtype, c16=c16)
+    torch.cuda.synchronize()
+    assert np.array_equal(pk.cpu().numpy(), ref)
+    yh, _ = to_host_array(y.cpu())
+    assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt, threads=16))
+
+
+def test_volume_kernels_cover_what_the_cases_claim():
+    kn = pkg.division_kernel_name_3d
+    assert kn(0, (3, 5, 16, 16, 16), 8, 2) == "compress_rows_3d<float, 2>"
+    assert kn(1, (3, 5, 16, 16, 16), 8, 2) == "decompress_rowvec_3d<float, 2>"
+    assert kn(0, (1, 2, 16, 56, 56), 8, 2).startswith("compress_any_3d<") or kn(0, (1, 2, 16, 56, 56), 8, 2).startswith("compress_slab")
+    assert kn(1, (2, 3, 5, 9, 13), 4, 2) == "decompress_flat_3d<float, 2>"
+    assert kn(1, (1, 2, 40, 40, 40), 8, 8) == "decompress_scalar_3d<float, 8>"
+    assert kn(0, (4, 9, 3, 3, 3), 8, 2) == "compress_lane<float, 2>"
+    assert kn(0, (2, 3, 7, 1, 30), 8, 2) == pkg.division_kernel_name(0, (2, 3, 7, 30), 8, 2)
+    assert kn(0, (2, 3, 1, 28, 28), 8, 2) == pkg.division_kernel_name(0, (2, 3, 28, 28), 8, 2)
+
+
+def test_volume_with_unit_depth_equals_the_2d_call_and_runs_on_a_side_stream():
+    x = torch.relu(torch.randn((3, 4, 1, 28, 28), generator=torch.Generator().manual_seed(1))).to("cuda:0")
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        a = pkg.division_compress_3d(x, 8, 2, 77, stream=st)
+    st.synchronize()
+    b2 = pkg.division_compress(x[:, :, 0].contiguous(), 8, 2, 77)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b2)
+
+
+def test_volume_error_codes():
+    x = torch.zeros((2, 2, 4, 4, 4), device="cuda:0")
+    need = pkg.division_packed_bytes_3d(2, 2, 4, 4, 4, 4, 2)
+    small = torch.empty(need - 16, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(pkg.DivisionError) as e:
+        pkg.division_compress_3d(x, 4, 2, 0, packed=small)
+    assert e.value.code == 2                                            # DIVISION_ESIZE
+    assert pkg.division_packed_bytes_3d(2, 2, 0, 4, 4, 4, 2) == 0
+    assert pkg.division_packed_bytes_3d(2, 2, 4, 4, 4, 4, 3) == 0
+    with pytest.raises(ValueError):
+        pkg.division_compress_3d(x[0], 4, 2, 0)
+    pk = pkg.division_compress_3d(x, 4, 2, 0)
+    with pytest.raises(pkg.DivisionError):
+        pkg.division_decompress_3d(pk[:-16], (2, 2, 4, 4, 4), 4, 2)
+    torch.cuda.synchronize()
