@@ -170,6 +170,67 @@ def masks(args, torch, pkg, dev) -> int:
     return 0
 
 
+VARIANTS = [
+    # what, shape, B, b     (fp32 maps; the 2-D shapes are those of the ResNet-50 set at batch 64)
+    ("block size 12", (64, 256, 56, 56), 12, 2), ("block size 16", (64, 256, 56, 56), 16, 2),
+    ("block size 18", (64, 256, 56, 56), 18, 2), ("block size 64", (64, 256, 56, 56), 64, 2),
+    ("block size 12", (64, 512, 28, 28), 12, 2), ("block size 18", (64, 512, 28, 28), 18, 2),
+    ("block size 12", (64, 1024, 14, 14), 12, 2),
+    ("8-bit codes", (64, 256, 56, 56), 8, 8), ("4-bit codes", (64, 256, 56, 56), 8, 4),
+    ("1-D map", (64, 384, 1, 3136), 8, 4), ("1-D map", (256, 768, 1, 196), 16, 2), ("1-D map", (64, 196, 1, 3072), 64, 2),
+    ("3-D map", (8, 64, 16, 56, 56), 8, 2), ("3-D map", (8, 128, 8, 28, 28), 8, 2), ("3-D map", (8, 256, 4, 14, 14), 8, 2),
+    ("3-D map", (8, 512, 2, 7, 7), 8, 2), ("3-D map", (64, 64, 16, 16, 16), 8, 2), ("3-D map", (64, 64, 16, 16, 16), 4, 2),
+]
+
+
+def variants(args, torch, pkg, dev) -> int:
+    """Single-call compress and decompress rates of the parameter and shape variants outside the headline
+    workload: the block sizes and code widths of the paper's sweep, 1-D and 3-D maps (Appendix D)."""
+    nsets = max(3, args.sets)
+    reps = max(20, args.steps)
+
+    def timed_us(fn):
+        for i in range(3):
+            fn(i)
+        ev = []
+        for i in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn(i)
+            e1.record()
+            ev.append((e0, e1))
+        torch.cuda.synchronize()
+        t = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in ev)
+        return t[len(t) // 2]
+
+    rows = []
+    for what, shape, B, b in VARIANTS:
+        g = torch.Generator(device=dev).manual_seed(sum(shape) + B)
+        xs = [torch.relu(torch.randn(shape, generator=g, device=dev)) for _ in range(nsets)]
+        three_d = len(shape) == 5
+        nbytes = pkg.division_packed_bytes_3d(*shape, B, b) if three_d else pkg.division_packed_bytes(*shape, B, b)
+        pk = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(nsets)]
+        out = [torch.empty(shape, device=dev) for _ in range(nsets)]
+        comp = pkg.division_compress_3d if three_d else pkg.division_compress
+        dec = pkg.division_decompress_3d if three_d else pkg.division_decompress
+        kn = pkg.division_kernel_name_3d if three_d else pkg.division_kernel_name
+        tc = timed_us(lambda i: comp(xs[i % nsets], B, b, i, packed=pk[i % nsets]))
+        td = timed_us(lambda i: dec(pk[i % nsets], shape, B, b, out=out[i % nsets]))
+        tcopy = timed_us(lambda i: out[i % nsets].copy_(xs[i % nsets]))
+        in_b = xs[0].numel() * 4
+        alg = in_b + nbytes
+        rows.append({"what": what, "shape": list(shape), "B": B, "b": b, "compression_ratio": round(in_b / nbytes, 2),
+                     "compress_kernel": kn(0, shape, B, b), "decompress_kernel": kn(1, shape, B, b),
+                     "compress_us": round(tc, 1), "decompress_us": round(td, 1),
+                     "compress_GB_s": round(alg / tc / 1e3, 1), "decompress_GB_s": round(alg / td / 1e3, 1),
+                     "device_copy_GB_s": round(2 * in_b / tcopy / 1e3, 1)})
+        del xs, pk, out
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "compress / decompress GB/s (algorithmic bytes) of parameter and shape variants, single calls, median of %d" % reps,
+                      "unit": "GB/s", "n_gpus": 1, "data": "synthetic", "dtype": "f32", "config": {"workload": "variants"}, "variants": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -191,6 +252,8 @@ def main() -> int:
     ap.add_argument("--masks", action="store_true",
                     help="time the 1-bit mask operators (Relu / Dropout forward, backward) on the largest map of the "
                          "workload, beside a plain device copy; prints one JSON line")
+    ap.add_argument("--variants", action="store_true",
+                    help="rates of the block sizes / code widths of the paper's sweep and of 1-D and 3-D maps")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy 10 times (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -226,6 +289,8 @@ def main() -> int:
         return per_shape(args, torch, pkg, dev)
     if args.masks:
         return masks(args, torch, pkg, dev)
+    if args.variants:
+        return variants(args, torch, pkg, dev)
 
     # ---- synthetic workload on the host, then resident in HBM (several rotating sets)
     _, specs = config(args.config)

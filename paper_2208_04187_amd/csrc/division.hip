@@ -1478,9 +1478,14 @@ __device__ __forceinline__ void compress_rows_body(const RowsArgs& a) {
     }
     lds_barrier();
 
-    // ---- 4. residual, Quant of Eq. (quantization), packing: one word per lane and step
+    // ---- 4. residual, Quant of Eq. (quantization), packing: one word per lane and step.
+    // Adjacent lanes own adjacent words, CPW floats apart in LDS: were all lanes to read their
+    // k-th pair at once they would meet in 64 / CPW banks.  Lane l therefore starts at pair
+    // `rot` = (l / (64 / CPW)) mod PPW and goes round its word; the pairs are pushed in that
+    // cyclic order and the word is rotated into place at the end.
     const uint32_t rscale = 1u << (16 - BITS);
     const uint32_t nwords = Gc * a.WPP;
+    const uint32_t rot = (tid / (64u / CPW)) & (uint32_t)(PPW - 1);
     for (uint32_t wi = tid; wi < nwords; wi += kThreads) {
         const uint32_t g = fdiv(wi, a.d_wpp);
         const uint32_t k = wi - g * a.WPP;
@@ -1490,27 +1495,31 @@ __device__ __forceinline__ void compress_rows_body(const RowsArgs& a) {
         const uint32_t left = a.HW - e0;                       // elements of the plane from e0 on (>= 1)
         const float* xp = xs + g * a.HW;
         const float* lp = lfcs + g * a.nb;
-        float h[CPW];
-#pragma unroll
-        for (int e = 0; e < CPW; ++e) {
-            // a ragged last word repeats the plane's last element; those codes are cleared below
-            const uint32_t i = e0 + min((uint32_t)e, left - 1u);
-            const uint32_t r = fdiv(i, a.d_W);
-            const uint32_t c = i - r * a.W;
-            uint32_t brow;
-            if constexpr (ND == 3) {
-                const uint32_t z = fdiv(r, a.d_Hs);
-                brow = fdiv(z, a.d_B) * a.LHs + fdiv(r - z * a.Hs, a.d_B);
-            } else {
-                brow = fdiv(r, a.d_B);
-            }
-            h[e] = xp[i] - lp[brow * a.LW + fdiv(c, a.d_B)];
-        }
         const uint32_t xw0 = k1 + (k * PPW) * kWeyl;
         uint32_t word = 0;
 #pragma unroll
-        for (int j = PPW - 1; j >= 0; --j)
-            word = push_pair<BITS>(word, h[2 * j], h[2 * j + 1], pr.x, pr.y, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+        for (int t = PPW - 1; t >= 0; --t) {
+            const uint32_t j = (rot + (uint32_t)t) & (uint32_t)(PPW - 1);
+            float h[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                // a ragged last word repeats the plane's last element; those codes are cleared below
+                const uint32_t i = e0 + min(2u * j + (uint32_t)e, left - 1u);
+                const uint32_t r = fdiv(i, a.d_W);
+                const uint32_t c = i - r * a.W;
+                uint32_t brow;
+                if constexpr (ND == 3) {
+                    const uint32_t z = fdiv(r, a.d_Hs);
+                    brow = fdiv(z, a.d_B) * a.LHs + fdiv(r - z * a.Hs, a.d_B);
+                } else {
+                    brow = fdiv(r, a.d_B);
+                }
+                h[e] = xp[i] - lp[brow * a.LW + fdiv(c, a.d_B)];
+            }
+            word = push_pair<BITS>(word, h[0], h[1], pr.x, pr.y, xw0 + j * kWeyl, k2, rscale);
+        }
+        // pushed from pair rot+PPW-1 down to pair rot (mod PPW): pair rot sits in the low bits
+        word = __builtin_amdgcn_alignbit(word, word, (32u - rot * 2u * BITS) & 31u);
         if (left < (uint32_t)CPW) word &= (1u << (left * BITS)) - 1u;          // pad bits are zero
         pt.codes[(size_t)(p0 + g) * a.WPP + k] = word;
     }
