@@ -1333,8 +1333,25 @@ struct RowsArgs {
     uint32_t G;          // planes per workgroup
     uint32_t xs_floats;  // LDS floats reserved for the chunk (multiple of 4, + slack for ragged last words)
     uint32_t vec_load;   // chunk starts are 16-byte aligned
-    FastDiv d_W, d_B, d_LW, d_HLW, d_nb, d_wpp, d_Hs, d_LHs;
+    uint32_t keep;       // the chunk is at most kRowsKeep 16-byte vectors per lane, each inside one row: lanes keep what they load
+    uint32_t qv;         // 16-byte vectors per plane (when keep)
+    FastDiv d_W, d_B, d_LW, d_HLW, d_nb, d_wpp, d_Hs, d_LHs, d_qv;
 };
+
+constexpr int kRowsKeep = 13;     // 16-byte vectors a lane of compress_rows holds in registers
+
+// the elements of one 16-byte vector of x as fp32
+template <typename T>
+__device__ __forceinline__ void unpack_vec(const u32x4& q, float (&x)[16 / sizeof(T)]) {
+    if constexpr (sizeof(T) == 4) {
+        x[0] = __uint_as_float(q.x); x[1] = __uint_as_float(q.y); x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
+    } else {
+        x[0] = __uint_as_float(q.x << 16); x[1] = __uint_as_float(q.x & 0xffff0000u);
+        x[2] = __uint_as_float(q.y << 16); x[3] = __uint_as_float(q.y & 0xffff0000u);
+        x[4] = __uint_as_float(q.z << 16); x[5] = __uint_as_float(q.z & 0xffff0000u);
+        x[6] = __uint_as_float(q.w << 16); x[7] = __uint_as_float(q.w & 0xffff0000u);
+    }
+}
 
 // Any block size B (the paper's sweep uses 12, 16, 18 and 64 besides 8).  A workgroup of four
 // wavefronts stages a chunk of G planes in LDS with coalesced loads, then
@@ -1343,6 +1360,9 @@ struct RowsArgs {
 //      block's residual (x -> fl(x - m) is monotone, so they are fl(min x - m), fl(max x - m));
 //   3. a lane per plane: min / max over its blocks, scale, keys, meta;
 //   4. a lane per packed word: residual against the block's LFC, quantise, pack.
+// When rows are whole 16-byte vectors and the chunk is at most kRowsKeep of them per lane (the usual
+// case) the lanes keep the vectors they loaded in registers and step 4 runs on those: a vector's
+// codes leave as one to eight bytes, and x is read from LDS by the pooling steps only.
 // ND = 3: the plane is a 3-D map (Appendix D) of D slices of Hs rows, blocks of B x B x B; its D*Hs
 // rows are staged and summed as rows like those of a 2-D map, a block adds the rows of its B slices.
 template <typename T, int BITS, int ND>
@@ -1363,39 +1383,53 @@ __device__ __forceinline__ void compress_rows_body(const RowsArgs& a) {
     const uint32_t n = Gc * a.HW;
     const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
 
-    // ---- chunk -> LDS (fp32): coalesced 16-byte loads, up to 8 in flight per lane
+    // ---- chunk -> LDS (fp32): coalesced 16-byte loads, all of a lane's in flight at once (up to
+    // kRowsKeep, kept for step 4) or eight at a time
+    constexpr uint32_t EPV = 16 / sizeof(T);
+    const uint32_t nv = a.vec_load ? n / EPV : 0;
+    const bool keep = a.keep != 0;                      // uniform
+    u32x4 kept[kRowsKeep];
     {
         const T* src = static_cast<const T*>(pt.x) + (size_t)p0 * a.HW;
-        constexpr uint32_t EPV = 16 / sizeof(T);
-        constexpr int U = 8;
-        const uint32_t nv = a.vec_load ? n / EPV : 0;
         const u32x4* src4 = reinterpret_cast<const u32x4*>(src);
-        for (uint32_t v0 = 0; v0 < nv; v0 += U * kThreads) {
-            u32x4 q[U];
+        auto to_lds = [&](const u32x4& q, uint32_t v) {
+            if constexpr (sizeof(T) == 4) {
+                reinterpret_cast<u32x4*>(xs)[v] = q;
+            } else {
+                float f[8];
+                unpack_vec<T>(q, f);
+                reinterpret_cast<float4*>(xs)[2 * v] = make_float4(f[0], f[1], f[2], f[3]);
+                reinterpret_cast<float4*>(xs)[2 * v + 1] = make_float4(f[4], f[5], f[6], f[7]);
+            }
+        };
+        if (keep) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t v = v0 + u * kThreads + tid;
-                if (v < nv) q[u] = __builtin_nontemporal_load(src4 + v);
+            for (int k = 0; k < kRowsKeep; ++k) {
+                const uint32_t v = k * kThreads + tid;
+                if (v < nv) kept[k] = __builtin_nontemporal_load(src4 + v);
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t v = v0 + u * kThreads + tid;
-                if (v < nv) {
-                    if constexpr (sizeof(T) == 4) {
-                        reinterpret_cast<u32x4*>(xs)[v] = q[u];
-                    } else {
-                        float4 lo, hi;
-                        lo.x = __uint_as_float(q[u].x << 16); lo.y = __uint_as_float(q[u].x & 0xffff0000u);
-                        lo.z = __uint_as_float(q[u].y << 16); lo.w = __uint_as_float(q[u].y & 0xffff0000u);
-                        hi.x = __uint_as_float(q[u].z << 16); hi.y = __uint_as_float(q[u].z & 0xffff0000u);
-                        hi.z = __uint_as_float(q[u].w << 16); hi.w = __uint_as_float(q[u].w & 0xffff0000u);
-                        reinterpret_cast<float4*>(xs)[2 * v] = lo;
-                        reinterpret_cast<float4*>(xs)[2 * v + 1] = hi;
-                    }
+            for (int k = 0; k < kRowsKeep; ++k) {
+                const uint32_t v = k * kThreads + tid;
+                if (v < nv) to_lds(kept[k], v);
+            }
+        } else {
+            constexpr int U = 8;
+            for (uint32_t v0 = 0; v0 < nv; v0 += U * kThreads) {
+                u32x4 q[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t v = v0 + u * kThreads + tid;
+                    if (v < nv) q[u] = __builtin_nontemporal_load(src4 + v);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t v = v0 + u * kThreads + tid;
+                    if (v < nv) to_lds(q[u], v);
                 }
             }
+            for (uint32_t e = nv * EPV + tid; e < n; e += kThreads) xs[e] = Elem<T>::load(src, e);
         }
-        for (uint32_t e = nv * EPV + tid; e < n; e += kThreads) xs[e] = Elem<T>::load(src, e);
     }
     lds_barrier();
 
@@ -1484,6 +1518,66 @@ __device__ __forceinline__ void compress_rows_body(const RowsArgs& a) {
     // `rot` = (l / (64 / CPW)) mod PPW and goes round its word; the pairs are pushed in that
     // cyclic order and the word is rotated into place at the end.
     const uint32_t rscale = 1u << (16 - BITS);
+    if (keep) {
+        // the lane's own vectors: EPV consecutive elements of one plane each, EPV * BITS / 8 code bytes
+        constexpr uint32_t CBV = EPV * BITS / 8;
+        uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)p0 * a.WPP * 4;
+#pragma unroll
+        for (int k = 0; k < kRowsKeep; ++k) {
+            const uint32_t v = k * kThreads + tid;
+            if (v < nv) {
+                const uint32_t g = fdiv(v, a.d_qv);
+                const uint32_t f = v - g * a.qv;                 // vector index inside the plane
+                const float4 pr = params[g];
+                const uint32_t k1 = __float_as_uint(pr.z), k2 = __float_as_uint(pr.w);
+                const float* lp = lfcs + g * a.nb;
+                float h[EPV];
+                unpack_vec<T>(kept[k], h);
+                const uint32_t i0 = f * EPV;
+                auto block_row = [&](uint32_t r) -> uint32_t {
+                    if constexpr (ND == 3) {
+                        const uint32_t z = fdiv(r, a.d_Hs);
+                        return fdiv(z, a.d_B) * a.LHs + fdiv(r - z * a.Hs, a.d_B);
+                    } else {
+                        return fdiv(r, a.d_B);
+                    }
+                };
+                // W is a multiple of EPV on this path: the vector lies in one row
+                const uint32_t r = fdiv(i0, a.d_W);
+                const uint32_t c0 = i0 - r * a.W;
+                const float* lrow = lp + block_row(r) * a.LW;
+#pragma unroll
+                for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lrow[fdiv(c0 + e, a.d_B)];
+                const uint32_t xw0 = k1 + (f * (EPV / 2)) * kWeyl;
+                uint8_t* dst = cbase + (size_t)g * a.WPP * 4 + f * CBV;
+                if constexpr (CBV <= 4) {
+                    uint32_t c = 0;
+#pragma unroll
+                    for (int j = EPV / 2 - 1; j >= 0; --j)
+                        c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], pr.x, pr.y, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+                    if constexpr (CBV == 1) *dst = (uint8_t)c;
+                    else if constexpr (CBV == 2) *reinterpret_cast<uint16_t*>(dst) = (uint16_t)c;
+                    else *reinterpret_cast<uint32_t*>(dst) = c;
+                } else {
+                    // eight 8-bit codes: two words
+                    uint32_t lo = 0, hi = 0;
+                    hi = push_pair<BITS>(hi, h[6], h[7], pr.x, pr.y, xw0 + 3u * kWeyl, k2, rscale);
+                    hi = push_pair<BITS>(hi, h[4], h[5], pr.x, pr.y, xw0 + 2u * kWeyl, k2, rscale);
+                    lo = push_pair<BITS>(lo, h[2], h[3], pr.x, pr.y, xw0 + kWeyl, k2, rscale);
+                    lo = push_pair<BITS>(lo, h[0], h[1], pr.x, pr.y, xw0, k2, rscale);
+                    reinterpret_cast<uint32_t*>(dst)[0] = lo;
+                    reinterpret_cast<uint32_t*>(dst)[1] = hi;
+                }
+            }
+        }
+        // pad bytes of every plane's last word are zero
+        const uint32_t padb = a.WPP * 4 - a.qv * CBV;
+        for (uint32_t t = tid; t < Gc * padb; t += kThreads) {
+            const uint32_t g = t / padb;
+            cbase[(size_t)g * a.WPP * 4 + a.qv * CBV + (t - g * padb)] = 0;
+        }
+        return;
+    }
     const uint32_t nwords = Gc * a.WPP;
     const uint32_t rot = (tid / (64u / CPW)) & (uint32_t)(PPW - 1);
     for (uint32_t wi = tid; wi < nwords; wi += kThreads) {
@@ -2266,6 +2360,10 @@ bool plan_rows(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, int b, 
     a->G = (uint32_t)G;
     a->xs_floats = (uint32_t)((G * L.HW + 3) / 4 * 4);
     a->vec_load = vec_load;
+    const uint64_t epv = 16 / es;
+    a->keep = vec_load && (uint64_t)W % epv == 0 && G * (L.HW / epv) <= (uint64_t)kRowsKeep * kThreads;
+    a->qv = (uint32_t)(L.HW / epv);
+    a->d_qv = make_fastdiv(a->qv ? a->qv : 1u);
     a->d_W = make_fastdiv((uint32_t)W);
     a->d_B = make_fastdiv((uint32_t)B);
     a->d_Hs = make_fastdiv((uint32_t)Hs);
