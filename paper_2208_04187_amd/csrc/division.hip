@@ -35,6 +35,7 @@ namespace {
 
 constexpr int kThreads = 256;              // 4 wavefronts of 64
 constexpr uint32_t kLdsTarget = 40u << 10; // preferred LDS bytes per workgroup (4 groups per CU)
+constexpr uint32_t kRowsLdsTarget = 40u << 10; // same for compress_rows
 constexpr uint32_t kLdsMax = 156u << 10;   // hard limit per workgroup (160 KB per CU)
 constexpr uint32_t kWeyl = 0x9E3779B9u;
 // cache policy of the loads of x: default.  x is read exactly once, but marking
@@ -1334,6 +1335,7 @@ struct RowsArgs {
     uint32_t xs_floats;  // LDS floats reserved for the chunk (multiple of 4, + slack for ragged last words)
     uint32_t vec_load;   // chunk starts are 16-byte aligned
     uint32_t keep;       // the chunk is at most kRowsKeep 16-byte vectors per lane, each inside one row: lanes keep what they load
+    uint32_t vecblk;     // keep, and the block size is a multiple of the vector too: a vector lies in one block
     uint32_t qv;         // 16-byte vectors per plane (when keep)
     FastDiv d_W, d_B, d_LW, d_HLW, d_nb, d_wpp, d_Hs, d_LHs, d_qv;
 };
@@ -1408,10 +1410,33 @@ __device__ __forceinline__ void compress_rows_body(const RowsArgs& a) {
                 const uint32_t v = k * kThreads + tid;
                 if (v < nv) kept[k] = __builtin_nontemporal_load(src4 + v);
             }
+            if (a.vecblk) {
+                // a vector lies inside one block: LDS takes its sum, min and max instead of its elements
 #pragma unroll
-            for (int k = 0; k < kRowsKeep; ++k) {
-                const uint32_t v = k * kThreads + tid;
-                if (v < nv) to_lds(kept[k], v);
+                for (int k = 0; k < kRowsKeep; ++k) {
+                    const uint32_t v = k * kThreads + tid;
+                    if (v < nv) {
+                        float f[EPV];
+                        unpack_vec<T>(kept[k], f);
+                        double S = ((double)f[0] + (double)f[1]) + ((double)f[2] + (double)f[3]);
+                        float mn = fminf(fminf(f[0], f[1]), fminf(f[2], f[3]));
+                        float mx = fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3]));
+                        if constexpr (EPV == 8) {
+                            S += ((double)f[4] + (double)f[5]) + ((double)f[6] + (double)f[7]);
+                            mn = fminf(mn, fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
+                            mx = fmaxf(mx, fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
+                        }
+                        const uint64_t sb = (uint64_t)__double_as_longlong(S);
+                        reinterpret_cast<float4*>(xs)[v] =
+                            make_float4(__uint_as_float((uint32_t)sb), __uint_as_float((uint32_t)(sb >> 32)), mn, mx);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < kRowsKeep; ++k) {
+                    const uint32_t v = k * kThreads + tid;
+                    if (v < nv) to_lds(kept[k], v);
+                }
             }
         } else {
             constexpr int U = 8;
@@ -1442,14 +1467,25 @@ __device__ __forceinline__ void compress_rows_body(const RowsArgs& a) {
         const uint32_t bj = rem - r * a.LW;
         const uint32_t c0 = bj * a.B;
         const uint32_t cols = min(a.B, a.W - c0);
-        const float* row = xs + g * a.HW + r * a.W + c0;
         double S = 0.0;
         float mn = __builtin_inff(), mx = -__builtin_inff();
-        for (uint32_t c = 0; c < cols; ++c) {
-            const float v = row[c];
-            S += (double)v;
-            mn = fminf(mn, v);
-            mx = fmaxf(mx, v);
+        if (a.vecblk) {
+            // the segment is whole vectors: add their sums
+            const float4* rec = reinterpret_cast<const float4*>(xs) + (g * a.HW + r * a.W + c0) / EPV;
+            for (uint32_t u = 0; u < cols / EPV; ++u) {
+                const float4 q = rec[u];
+                S += __longlong_as_double((long long)(((uint64_t)__float_as_uint(q.y) << 32) | __float_as_uint(q.x)));
+                mn = fminf(mn, q.z);
+                mx = fmaxf(mx, q.w);
+            }
+        } else {
+            const float* row = xs + g * a.HW + r * a.W + c0;
+            for (uint32_t c = 0; c < cols; ++c) {
+                const float v = row[c];
+                S += (double)v;
+                mn = fminf(mn, v);
+                mx = fmaxf(mx, v);
+            }
         }
         const uint64_t sb = (uint64_t)__double_as_longlong(S);
         rowp[s] = make_float4(__uint_as_float((uint32_t)sb), __uint_as_float((uint32_t)(sb >> 32)), mn, mx);
@@ -1478,6 +1514,7 @@ __device__ __forceinline__ void compress_rows_body(const RowsArgs& a) {
         float mn = __builtin_inff(), mx = -__builtin_inff();
         for (uint32_t z = 0; z < deps; ++z) {
             const float4* rp = rowp + g * HLW + ((z0 + z) * a.Hs + r0) * a.LW + bj;
+#pragma unroll 4
             for (uint32_t rr = 0; rr < rows; ++rr) {
                 const float4 q = rp[rr * a.LW];
                 S += __longlong_as_double((long long)(((uint64_t)__float_as_uint(q.y) << 32) | __float_as_uint(q.x)));
@@ -1494,14 +1531,19 @@ __device__ __forceinline__ void compress_rows_body(const RowsArgs& a) {
     }
     lds_barrier();
 
-    // ---- 3. planes: scale of Eq. (quantization), keys, meta
-    for (uint32_t g = tid; g < Gc; g += kThreads) {
+    // ---- 3. planes: scale of Eq. (quantization), keys, meta.  Sixteen lanes share a plane's blocks.
+    for (uint32_t g0 = 0; g0 < Gc; g0 += kThreads / 16) {
+        const uint32_t g = g0 + (tid >> 4);
         float mn = __builtin_inff(), mx = -__builtin_inff();
-        for (uint32_t j = 0; j < a.nb; ++j) {
-            const float2 e = bext[g * a.nb + j];
-            mn = fminf(mn, e.x);
-            mx = fmaxf(mx, e.y);
+        if (g < Gc) {
+            for (uint32_t j = tid & 15u; j < a.nb; j += 16) {
+                const float2 e = bext[g * a.nb + j];
+                mn = fminf(mn, e.x);
+                mx = fmaxf(mx, e.y);
+            }
         }
+        group_minmax(16, mn, mx);
+        if (g >= Gc || (tid & 15u) != 0) continue;
         float delta, Delta, inv;
         plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
         const uint32_t p = p0 + g;
@@ -2339,7 +2381,7 @@ bool plan_rows(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, int b, 
     if (per_plane + 256 > kLdsMax) return false;
     if (!fastdiv_ok(L.HW, (uint64_t)W) || !fastdiv_ok((uint64_t)(H > W ? H : W), (uint64_t)B)) return false;
     if (!fastdiv_ok((uint64_t)H, (uint64_t)Hs) || !fastdiv_ok(L.LD * L.LH, L.LH)) return false;
-    uint64_t G = kLdsTarget / per_plane;
+    uint64_t G = kRowsLdsTarget / per_plane;
     if (G < 1) G = 1;
     if (G > L.P) G = L.P;
     // chunk starts on 16-byte boundaries when G is a multiple of `unit`
@@ -2362,6 +2404,7 @@ bool plan_rows(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, int b, 
     a->vec_load = vec_load;
     const uint64_t epv = 16 / es;
     a->keep = vec_load && (uint64_t)W % epv == 0 && G * (L.HW / epv) <= (uint64_t)kRowsKeep * kThreads;
+    a->vecblk = a->keep && (uint64_t)B % epv == 0;
     a->qv = (uint32_t)(L.HW / epv);
     a->d_qv = make_fastdiv(a->qv ? a->qv : 1u);
     a->d_W = make_fastdiv((uint32_t)W);
