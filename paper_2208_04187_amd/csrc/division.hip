@@ -1355,6 +1355,54 @@ __device__ __forceinline__ void unpack_vec(const u32x4& q, float (&x)[16 / sizeo
     }
 }
 
+// One 16-byte vector of x (EPV consecutive elements of one row: W is a multiple of EPV) -> its
+// EPV * BITS / 8 code bytes.  f = vector index inside the plane, lp = the plane's LFC values (LDS),
+// pr = (delta, scaled inv, k1, k2) of the plane, plane_codes = the plane's packed words.
+// Args carries W, LW, Hs, LHs and the dividers d_W, d_B, d_Hs.
+template <typename T, int BITS, int ND, typename Args>
+__device__ __forceinline__ void quant_vector(const Args& a, const u32x4& q, uint32_t f, const float4 pr, const float* lp,
+                                             uint8_t* plane_codes) {
+    constexpr uint32_t EPV = 16 / sizeof(T);
+    constexpr uint32_t CBV = EPV * BITS / 8;
+    const uint32_t rscale = 1u << (16 - BITS);
+    const uint32_t k1 = __float_as_uint(pr.z), k2 = __float_as_uint(pr.w);
+    float h[EPV];
+    unpack_vec<T>(q, h);
+    const uint32_t i0 = f * EPV;
+    const uint32_t r = fdiv(i0, a.d_W);                  // row, counted over all depth slices of a 3-D map
+    const uint32_t c0 = i0 - r * a.W;
+    uint32_t brow;
+    if constexpr (ND == 3) {
+        const uint32_t z = fdiv(r, a.d_Hs);
+        brow = fdiv(z, a.d_B) * a.LHs + fdiv(r - z * a.Hs, a.d_B);
+    } else {
+        brow = fdiv(r, a.d_B);
+    }
+    const float* lrow = lp + brow * a.LW;
+#pragma unroll
+    for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lrow[fdiv(c0 + e, a.d_B)];
+    const uint32_t xw0 = k1 + (f * (EPV / 2)) * kWeyl;
+    uint8_t* dst = plane_codes + f * CBV;
+    if constexpr (CBV <= 4) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int j = EPV / 2 - 1; j >= 0; --j)
+            c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], pr.x, pr.y, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+        if constexpr (CBV == 1) *dst = (uint8_t)c;
+        else if constexpr (CBV == 2) *reinterpret_cast<uint16_t*>(dst) = (uint16_t)c;
+        else *reinterpret_cast<uint32_t*>(dst) = c;
+    } else {
+        // eight 8-bit codes: two words
+        uint32_t lo = 0, hi = 0;
+        hi = push_pair<BITS>(hi, h[6], h[7], pr.x, pr.y, xw0 + 3u * kWeyl, k2, rscale);
+        hi = push_pair<BITS>(hi, h[4], h[5], pr.x, pr.y, xw0 + 2u * kWeyl, k2, rscale);
+        lo = push_pair<BITS>(lo, h[2], h[3], pr.x, pr.y, xw0 + kWeyl, k2, rscale);
+        lo = push_pair<BITS>(lo, h[0], h[1], pr.x, pr.y, xw0, k2, rscale);
+        reinterpret_cast<uint32_t*>(dst)[0] = lo;
+        reinterpret_cast<uint32_t*>(dst)[1] = hi;
+    }
+}
+
 // Any block size B (the paper's sweep uses 12, 16, 18 and 64 besides 8).  A workgroup of four
 // wavefronts stages a chunk of G planes in LDS with coalesced loads, then
 //   1. a lane per (row, block column): binary64 sum, min and max of that row segment;
@@ -1570,46 +1618,7 @@ __device__ __forceinline__ void compress_rows_body(const RowsArgs& a) {
             if (v < nv) {
                 const uint32_t g = fdiv(v, a.d_qv);
                 const uint32_t f = v - g * a.qv;                 // vector index inside the plane
-                const float4 pr = params[g];
-                const uint32_t k1 = __float_as_uint(pr.z), k2 = __float_as_uint(pr.w);
-                const float* lp = lfcs + g * a.nb;
-                float h[EPV];
-                unpack_vec<T>(kept[k], h);
-                const uint32_t i0 = f * EPV;
-                auto block_row = [&](uint32_t r) -> uint32_t {
-                    if constexpr (ND == 3) {
-                        const uint32_t z = fdiv(r, a.d_Hs);
-                        return fdiv(z, a.d_B) * a.LHs + fdiv(r - z * a.Hs, a.d_B);
-                    } else {
-                        return fdiv(r, a.d_B);
-                    }
-                };
-                // W is a multiple of EPV on this path: the vector lies in one row
-                const uint32_t r = fdiv(i0, a.d_W);
-                const uint32_t c0 = i0 - r * a.W;
-                const float* lrow = lp + block_row(r) * a.LW;
-#pragma unroll
-                for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lrow[fdiv(c0 + e, a.d_B)];
-                const uint32_t xw0 = k1 + (f * (EPV / 2)) * kWeyl;
-                uint8_t* dst = cbase + (size_t)g * a.WPP * 4 + f * CBV;
-                if constexpr (CBV <= 4) {
-                    uint32_t c = 0;
-#pragma unroll
-                    for (int j = EPV / 2 - 1; j >= 0; --j)
-                        c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], pr.x, pr.y, xw0 + (uint32_t)j * kWeyl, k2, rscale);
-                    if constexpr (CBV == 1) *dst = (uint8_t)c;
-                    else if constexpr (CBV == 2) *reinterpret_cast<uint16_t*>(dst) = (uint16_t)c;
-                    else *reinterpret_cast<uint32_t*>(dst) = c;
-                } else {
-                    // eight 8-bit codes: two words
-                    uint32_t lo = 0, hi = 0;
-                    hi = push_pair<BITS>(hi, h[6], h[7], pr.x, pr.y, xw0 + 3u * kWeyl, k2, rscale);
-                    hi = push_pair<BITS>(hi, h[4], h[5], pr.x, pr.y, xw0 + 2u * kWeyl, k2, rscale);
-                    lo = push_pair<BITS>(lo, h[2], h[3], pr.x, pr.y, xw0 + kWeyl, k2, rscale);
-                    lo = push_pair<BITS>(lo, h[0], h[1], pr.x, pr.y, xw0, k2, rscale);
-                    reinterpret_cast<uint32_t*>(dst)[0] = lo;
-                    reinterpret_cast<uint32_t*>(dst)[1] = hi;
-                }
+                quant_vector<T, BITS, ND>(a, kept[k], f, params[g], lfcs + g * a.nb, cbase + (size_t)g * a.WPP * 4);
             }
         }
         // pad bytes of every plane's last word are zero
@@ -1665,6 +1674,149 @@ template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) compress_rows(RowsArgs a) { compress_rows_body<T, BITS, 2>(a); }
 template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) compress_rows_3d(RowsArgs a) { compress_rows_body<T, BITS, 3>(a); }
+
+// ------------------------------------------------------------------ compress, planes beyond LDS
+
+struct PlaneArgs {
+    CompTab tab;
+    Regions rg;
+    uint32_t P, W, HW, LW, nb, WPP, B;
+    uint32_t D, Hs, LHs;     // depth slices, rows and block rows of one slice (D = 1 for a 2-D map)
+    uint32_t nitem;          // D * LHs * LW: blocks of one depth slice each
+    uint32_t qv;             // 16-byte vectors per plane
+    FastDiv d_W, d_B, d_Hs, d_LW, d_LHs, d_slice;      // d_slice divides by LHs * LW
+};
+
+// Planes too large for LDS (the 3-D maps of video models, 2-D maps from 200 x 200 up): one
+// workgroup per plane, x is read twice, both times with 16-byte loads (rows and blocks are whole
+// vectors here).
+//   A. a lane per (depth slice, block): sum, min and max of the block's elements in that slice;
+//      neighbouring lanes read neighbouring row segments;
+//   B. a lane per block: adds its slices -> LFC (LDS and packed buffer), residual extremes;
+//   C. range of the plane, scale of Eq. (quantization), keys, meta;
+//   D. a lane per vector: residual against the LFC, Quant, code bytes out (the second read of x
+//      comes out of the caches as far as they hold the plane).
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void compress_plane_body(const PlaneArgs& a) {
+    extern __shared__ float4 smem4[];
+    float4* part = smem4;                                          // [nitem] (sum lo, sum hi, min, max)
+    float* lfcs = reinterpret_cast<float*>(part + a.nitem);       // [nb]
+    float* red = lfcs + ((a.nb + 3u) & ~3u);                       // [2 * kThreads / 64] + 4 params
+    constexpr uint32_t EPV = 16 / sizeof(T);
+    constexpr uint32_t CBV = EPV * BITS / 8;
+    constexpr float Lf = float((1 << BITS) - 1);
+    const uint32_t tid = threadIdx.x;
+    const uint32_t p = blockIdx.x;
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
+    const u32x4* xv = reinterpret_cast<const u32x4*>(static_cast<const T*>(pt.x) + (size_t)p * a.HW);
+    const uint32_t wv = a.W / EPV;                                 // vectors per row
+    const uint32_t slice = a.LHs * a.LW;
+
+    // ---- A. blocks of one slice (Sec. 4.1 / Appendix D AveragePooling, first half)
+    for (uint32_t it = tid; it < a.nitem; it += kThreads) {
+        const uint32_t z = fdiv(it, a.d_slice);
+        const uint32_t rem = it - z * slice;
+        const uint32_t bi = fdiv(rem, a.d_LW);
+        const uint32_t bj = rem - bi * a.LW;
+        const uint32_t r0 = bi * a.B, c0 = bj * a.B;
+        const uint32_t rows = min(a.B, a.Hs - r0);
+        const uint32_t nvec = min(a.B, a.W - c0) / EPV;
+        const u32x4* src = xv + (size_t)(z * a.Hs + r0) * wv + c0 / EPV;
+        double S = 0.0;
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+        for (uint32_t rr = 0; rr < rows; ++rr) {
+            for (uint32_t u = 0; u < nvec; ++u) {
+                float f[EPV];
+                unpack_vec<T>(src[(size_t)rr * wv + u], f);
+                S += ((double)f[0] + (double)f[1]) + ((double)f[2] + (double)f[3]);
+                mn = fminf(mn, fminf(fminf(f[0], f[1]), fminf(f[2], f[3])));
+                mx = fmaxf(mx, fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])));
+                if constexpr (EPV == 8) {
+                    S += ((double)f[4] + (double)f[5]) + ((double)f[6] + (double)f[7]);
+                    mn = fminf(mn, fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
+                    mx = fmaxf(mx, fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
+                }
+            }
+        }
+        const uint64_t sb = (uint64_t)__double_as_longlong(S);
+        part[it] = make_float4(__uint_as_float((uint32_t)sb), __uint_as_float((uint32_t)(sb >> 32)), mn, mx);
+    }
+    lds_barrier();
+
+    // ---- B. blocks: LFC and residual extremes.  All lanes of a wavefront run the loop body
+    // (mean_of votes across the wavefront); slots past the plane redo block 0.
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+    for (uint32_t t0 = 0; t0 < a.nb; t0 += kThreads) {
+        const uint32_t t = t0 + tid;
+        const bool live = t < a.nb;
+        const uint32_t blk = live ? t : 0u;
+        const uint32_t bd = fdiv(blk, a.d_slice);
+        const uint32_t rem = blk - bd * slice;
+        const uint32_t bi = fdiv(rem, a.d_LW);
+        const uint32_t bj = rem - bi * a.LW;
+        const uint32_t rows = min(a.B, a.Hs - bi * a.B);
+        const uint32_t cols = min(a.B, a.W - bj * a.B);
+        const uint32_t z0 = bd * a.B;
+        const uint32_t deps = min(a.B, a.D - z0);
+        double S = 0.0;
+        float bmn = __builtin_inff(), bmx = -__builtin_inff();
+#pragma unroll 4
+        for (uint32_t z = 0; z < deps; ++z) {
+            const float4 q = part[(z0 + z) * slice + rem];
+            S += __longlong_as_double((long long)(((uint64_t)__float_as_uint(q.y) << 32) | __float_as_uint(q.x)));
+            bmn = fminf(bmn, q.z);
+            bmx = fmaxf(bmx, q.w);
+        }
+        const float lfc = lfc_round<T>(mean_of(S, deps * rows * cols), kC16<T>);
+        if (live) {
+            lfcs[t] = lfc;
+            lfc_store<T>(pt.lfc, (size_t)p * a.nb + t, lfc, kC16<T>);
+            mn = fminf(mn, bmn - lfc);               // x -> fl(x - m) is monotone
+            mx = fmaxf(mx, bmx - lfc);
+        }
+    }
+
+    // ---- C. range of the plane, scale, keys, meta
+    group_minmax(64, mn, mx);
+    if ((tid & 63u) == 0) { red[2 * (tid >> 6)] = mn; red[2 * (tid >> 6) + 1] = mx; }
+    lds_barrier();
+    if (tid == 0) {
+        for (uint32_t w = 0; w < kThreads / 64; ++w) { mn = fminf(mn, red[2 * w]); mx = fmaxf(mx, red[2 * w + 1]); }
+        float delta, Delta, inv;
+        plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
+        meta_store(pt.meta, p, delta, Delta, kC16<T>);
+        const uint32_t k1 = mix32(p ^ pt.seed_a);
+        const uint32_t k2 = mix32(k1 + pt.seed_c);
+        float4* prm = reinterpret_cast<float4*>(red + 2 * (kThreads / 64));
+        *prm = make_float4(delta, inv * (float)(1u << (32 - BITS)), __uint_as_float(k1), __uint_as_float(k2));
+    }
+    lds_barrier();
+    const float4 pr = *reinterpret_cast<const float4*>(red + 2 * (kThreads / 64));
+
+    // ---- D. residual, Quant, packing: a vector per lane and step, four steps in flight
+    uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)p * a.WPP * 4;
+    constexpr int U = 4;
+    for (uint32_t v0 = 0; v0 < a.qv; v0 += U * kThreads) {
+        u32x4 q[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t v = v0 + u * kThreads + tid;
+            if (v < a.qv) q[u] = xv[v];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t v = v0 + u * kThreads + tid;
+            if (v < a.qv) quant_vector<T, BITS, ND>(a, q[u], v, pr, lfcs, cbase);
+        }
+    }
+    const uint32_t padb = a.WPP * 4 - a.qv * CBV;                  // pad bytes of the last word are zero
+    if (tid < padb) cbase[a.qv * CBV + tid] = 0;
+}
+
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) compress_plane(PlaneArgs a) { compress_plane_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) compress_plane_3d(PlaneArgs a) { compress_plane_body<T, BITS, 3>(a); }
 
 // ------------------------------------------------------------------ compress, any shape (slow)
 
@@ -2420,6 +2572,36 @@ bool plan_rows(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, int b, 
     return *lds <= kLdsMax;
 }
 
+// Fills the workgroup-per-plane plan for planes beyond LDS; false when rows or blocks are not whole
+// 16-byte vectors or the per-slice partial sums do not fit LDS.
+bool plan_plane(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, size_t es, const void* x,
+                PlaneArgs* a, uint32_t* grid, size_t* lds) {
+    const uint64_t epv = 16 / es;
+    if (((uintptr_t)x % 16) != 0 || (uint64_t)W % epv != 0 || (uint64_t)B % epv != 0) return false;
+    const uint64_t H = (uint64_t)D * (uint64_t)Hs;
+    const uint64_t slice = L.LH * L.LW;
+    const uint64_t nitem = (uint64_t)D * slice;
+    const uint64_t need = 16ull * nitem + 4ull * ((L.nb + 3) & ~3ull) + 8ull * (kThreads / 64) + 16 + 16;
+    if (need > kLdsMax) return false;
+    if (!fastdiv_ok(L.HW, (uint64_t)W) || !fastdiv_ok(H > (uint64_t)W ? H : (uint64_t)W, (uint64_t)B) ||
+        !fastdiv_ok(H, (uint64_t)Hs) || !fastdiv_ok(nitem + kThreads, slice) || !fastdiv_ok(slice, L.LW))
+        return false;
+    a->P = (uint32_t)L.P; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW; a->LW = (uint32_t)L.LW;
+    a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP; a->B = (uint32_t)B;
+    a->D = (uint32_t)D; a->Hs = (uint32_t)Hs; a->LHs = (uint32_t)L.LH;
+    a->nitem = (uint32_t)nitem;
+    a->qv = (uint32_t)(L.HW / epv);
+    a->d_W = make_fastdiv((uint32_t)W);
+    a->d_B = make_fastdiv((uint32_t)B);
+    a->d_Hs = make_fastdiv((uint32_t)Hs);
+    a->d_LW = make_fastdiv((uint32_t)L.LW);
+    a->d_LHs = make_fastdiv((uint32_t)L.LH);
+    a->d_slice = make_fastdiv((uint32_t)slice);
+    *lds = need;
+    *grid = (uint32_t)L.P;
+    return true;
+}
+
 // Fills the tiled-compress launch plan; false when the shape is not covered.
 bool plan_tile(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, const void* x,
                TileArgs* a, uint32_t* grid, size_t* lds, int* vec_out, int* nt_out) {
@@ -2614,11 +2796,12 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         ItemsArgs ia{};
         LaneArgs la{};
         RowsArgs wa2{};
+        PlaneArgs pa{};
         AnyArgs g{};
         size_t lds = 0;
         uint32_t grid = 0;
         int vec = 1, nt = 64, nw = 1;
-        enum { REGS, LANE, ITEMS, WAVE, TILE, ROWS, ANY } kind;
+        enum { REGS, LANE, ITEMS, WAVE, TILE, ROWS, PLANE, ANY } kind;
         const bool flat = D == 1;               // the register, item, wavefront and tile kernels take 2-D maps
         if (flat && plan_regs(L, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
         else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
@@ -2627,6 +2810,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
             kind = WAVE; wa.tab = tab; wa.rg = rg;
         } else if (flat && plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) { kind = TILE; a.tab = tab; a.rg = rg; }
         else if (plan_rows(L, D, H, W, B, b, es, xa, &wa2, &grid, &lds)) { kind = ROWS; wa2.tab = tab; wa2.rg = rg; }
+        else if (plan_plane(L, D, H, W, B, es, xa, &pa, &grid, &lds)) { kind = PLANE; pa.tab = tab; pa.rg = rg; }
         else {
             kind = ANY;
             g.tab = tab; g.rg = rg;
@@ -2649,6 +2833,13 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
                     const hipError_t e = allow_large_lds(kern, lds);
                     if (e != hipSuccess) return e;
                     hipLaunchKernelGGL(kern, gd, dim3(kThreads), lds, st, wa2);
+                    return hipGetLastError();
+                }
+                case PLANE: {
+                    void (*kern)(PlaneArgs) = flat ? compress_plane<T, BITS> : compress_plane_3d<T, BITS>;
+                    const hipError_t e = allow_large_lds(kern, lds);
+                    if (e != hipSuccess) return e;
+                    hipLaunchKernelGGL(kern, gd, dim3(kThreads), lds, st, pa);
                     return hipGetLastError();
                 }
                 default: {
@@ -2724,7 +2915,7 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     const char* tn = dt == DIVISION_BF16 ? "bf16_t" : dt == DIVISION_F32_C16 ? "f32c16_t" : "float";
     int n;
     if (direction == 0) {
-        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
+        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (flat && plan_regs(L, H, W, B, es, data, &ra, &grid, &lds, &nw))
             n = snprintf(out, cap, "compress_regs<%s, %d, %d, %d>", tn, b, B, nw);
         else if (plan_lane(L, es, data, &la, &grid, &lds))
@@ -2737,6 +2928,8 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
             n = snprintf(out, cap, "compress_tile<%s, %d, %d, %d, %d>", tn, b, B, vec, nt);
         else if (plan_rows(L, D, H, W, B, b, es, data, &wa2, &grid, &lds))
             n = snprintf(out, cap, "compress_rows%s<%s, %d>", sfx, tn, b);
+        else if (plan_plane(L, D, H, W, B, es, data, &pa, &grid, &lds))
+            n = snprintf(out, cap, "compress_plane%s<%s, %d>", sfx, tn, b);
         else
             n = snprintf(out, cap, "compress_any%s<%s, %d>", sfx, tn, b);
     } else {

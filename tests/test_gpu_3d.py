@@ -24,7 +24,9 @@ CASES = [
     ((1, 2, 16, 56, 56), 8, 2),                   # plane beyond LDS: workgroup per plane
     ((1, 3, 20, 30, 34), 12, 4),                  # same, ragged, B = 12
     ((1, 2, 40, 40, 40), 8, 8),                   # codes of a plane beyond the staged decompress: scalar kernel
-    ((1, 2, 33, 35, 37), 16, 2),
+    ((1, 2, 33, 35, 37), 16, 2),                  # odd extents beyond LDS: the scalar workgroup-per-plane kernel
+    ((2, 3, 18, 44, 48), 8, 4),                   # ragged blocks in depth and rows, workgroup-per-plane kernel
+    ((1, 2, 24, 40, 64), 16, 2),
     ((4, 9, 3, 3, 3), 8, 2),                      # one block, odd element count: lane kernels
     ((3, 4, 2, 4, 6), 8, 4),                      # one block, even element count
     ((2, 3, 7, 1, 30), 8, 2),                     # H = 1: a D x W map
@@ -61,7 +63,9 @@ def test_volume_kernels_cover_what_the_cases_claim():
     kn = pkg.division_kernel_name_3d
     assert kn(0, (3, 5, 16, 16, 16), 8, 2) == "compress_rows_3d<float, 2>"
     assert kn(1, (3, 5, 16, 16, 16), 8, 2) == "decompress_rowvec_3d<float, 2>"
-    assert kn(0, (1, 2, 16, 56, 56), 8, 2).startswith("compress_any_3d<") or kn(0, (1, 2, 16, 56, 56), 8, 2).startswith("compress_slab")
+    assert kn(0, (1, 2, 16, 56, 56), 8, 2) == "compress_plane_3d<float, 2>"
+    assert kn(0, (1, 2, 16, 56, 56), 8, 2, torch.bfloat16) == "compress_plane_3d<bf16_t, 2>"
+    assert kn(0, (1, 2, 33, 35, 37), 16, 2) == "compress_any_3d<float, 2>"
     assert kn(1, (2, 3, 5, 9, 13), 4, 2) == "decompress_flat_3d<float, 2>"
     assert kn(1, (1, 2, 40, 40, 40), 8, 8) == "decompress_scalar_3d<float, 8>"
     assert kn(0, (4, 9, 3, 3, 3), 8, 2) == "compress_lane<float, 2>"

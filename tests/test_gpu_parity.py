@@ -85,7 +85,9 @@ ANY_CASES = [
     ((2, 3, 36, 36), 12, 2),          # block sizes of the paper's sweep
     ((2, 2, 36, 36), 18, 2),
     ((2, 3, 56, 56), 64, 2),          # block larger than the map
-    ((1, 2, 300, 300), 8, 2),         # plane too large for LDS
+    ((1, 2, 300, 300), 8, 2),         # plane too large for LDS: vector workgroup-per-plane kernel
+    ((1, 2, 301, 299), 8, 2),         # same, odd extents: scalar workgroup-per-plane kernel
+    ((2, 3, 224, 224), 12, 4),        # image-sized plane, ragged blocks of 8
     ((2, 2, 33, 17), 16, 4),
     ((5, 13, 7, 5), 16, 4),           # one-block planes under a block size the tiled kernels do not cover
     ((70, 3, 7, 7), 64, 2),           # 210 planes: three full rounds of 64 and a ragged one
