@@ -100,3 +100,17 @@ def test_volume_error_codes():
     with pytest.raises(pkg.DivisionError):
         pkg.division_decompress_3d(pk[:-16], (2, 2, 4, 4, 4), 4, 2)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("shape,B,b", [((8, 64, 16, 56, 56), 8, 2), ((32, 128, 8, 28, 28), 8, 2), ((4, 16, 16, 112, 112), 8, 4)])
+def test_full_size_volumes_match_oracle(shape, B, b):
+    """Shapes of a 3-D ResNet-18 on 16 x 112 x 112 clips (workgroup-per-plane and chunked kernels), whole tensor."""
+    g = torch.Generator().manual_seed(sum(shape))
+    x = torch.relu(torch.randn(shape, generator=g))
+    seed = 0xF00D + B
+    ref = oracle.compress(x.numpy(), B, b, seed, threads=16)
+    pk = pkg.division_compress_3d(x.to("cuda:0"), B, b, seed)
+    y = pkg.division_decompress_3d(pk, shape, B, b)
+    torch.cuda.synchronize()
+    assert np.array_equal(pk.cpu().numpy(), ref)
+    assert np.array_equal(y.cpu().numpy(), oracle.decompress(ref, shape, B, b, threads=16))
