@@ -422,6 +422,24 @@ def test_saved_tensor_hook_caches_the_map_and_rebuilds_it_in_backward(c16):
     assert torch.equal(h.grad, w.detach())
 
 
+@pytest.mark.parametrize("shape", [(3, 8, 200), (2, 4, 6, 20, 12)])
+def test_saved_tensor_hook_takes_1d_and_3d_maps(shape):
+    B, b, seed = 8, 4, 17
+    g = torch.Generator().manual_seed(len(shape))
+    x = torch.randn(shape, generator=g).to("cuda:0")
+    w = torch.nn.Parameter(torch.full(shape, 2.0, device="cuda:0"))
+    h = x.clone().requires_grad_(True)
+    hooks = pkg.division_saved_tensors(B, b, seed)
+    with hooks:
+        loss = ((h * 1.0) * w).sum()
+    loss.backward()
+    assert hooks.cached_maps == 1
+    oshape = shape if len(shape) == 5 else (shape[0], shape[1], 1, shape[2])
+    xh = x.cpu().numpy().reshape(oshape)
+    ref = oracle.decompress(oracle.compress(xh, B, b, seed), oshape, B, b).reshape(shape)
+    assert np.array_equal(w.grad.cpu().numpy(), ref)
+
+
 # ---------------------------------------------------------------- HIP graph capture
 
 def test_compress_and_decompress_replay_from_a_hip_graph():
