@@ -1925,6 +1925,7 @@ struct DecArgs {
     uint32_t q4;         // HW / 4
     uint32_t w4;         // W / 4
     uint32_t Hs, LHs;    // 3-D maps: rows and block rows of one depth slice (H counts the rows of all slices)
+    uint32_t pair8;      // 2-byte elements, W a multiple of 8, output 16-byte aligned: a lane step writes 8 elements
     FastDiv d_q4, d_w4, d_B, d_W, d_HW, d_Hs;
 };
 
@@ -2031,6 +2032,46 @@ __device__ __forceinline__ void decompress_rowvec_body(const DecArgs& a) {
     const uint32_t nvec = Gc * a.q4;
     constexpr uint32_t Lq = (1u << BITS) - 1u;
     T* out = static_cast<T*>(pt.xhat) + (size_t)p0 * a.HW;
+    if constexpr (sizeof(T) == 2) {
+        if (a.pair8) {
+            // two neighbouring vectors of one row per lane step: one 16-byte store
+            for (uint32_t vi = 2 * tid; vi < nvec; vi += 2 * kThreads) {
+                const uint32_t g = fdiv(vi, a.d_q4);
+                const uint32_t fi = vi - g * a.q4;                     // even
+                const float2 dd = s_meta[g];
+                uint32_t lo, hi;                                       // codes of elements 0-3 and 4-7
+                if constexpr (BITS == 2) {
+                    lo = reinterpret_cast<const uint16_t*>(s_codes)[(g * a.WPP * 4 + fi) >> 1];
+                    hi = lo >> 8;
+                } else if constexpr (BITS == 4) {
+                    lo = s_codes[(g * a.WPP * 2 + fi) >> 1];
+                    hi = lo >> 16;
+                } else {
+                    lo = s_codes[g * a.WPP + fi];
+                    hi = s_codes[g * a.WPP + fi + 1];
+                }
+                const uint32_t r = fdiv(fi, a.d_w4);
+                const uint32_t c = (fi - r * a.w4) * 4;
+                const T* lrow = s_lfc + g * a.nb + lfc_row<ND>(a, r);
+                const float l0 = Elem<T>::load(lrow, fdiv(c, a.d_B)), l1 = Elem<T>::load(lrow, fdiv(c + 4, a.d_B));
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    w[e] = float_to_bf16_bits(dequant((lo >> (2 * e * BITS)) & Lq, dd.y, dd.x, l0)) |
+                           (float_to_bf16_bits(dequant((lo >> ((2 * e + 1) * BITS)) & Lq, dd.y, dd.x, l0)) << 16);
+                    w[2 + e] = float_to_bf16_bits(dequant((hi >> (2 * e * BITS)) & Lq, dd.y, dd.x, l1)) |
+                               (float_to_bf16_bits(dequant((hi >> ((2 * e + 1) * BITS)) & Lq, dd.y, dd.x, l1)) << 16);
+                }
+                u32x4 o; o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
+#ifndef DIVISION_TEMPORAL_STORE
+                __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(out + (size_t)vi * 4));
+#else
+                *reinterpret_cast<u32x4*>(out + (size_t)vi * 4) = o;
+#endif
+            }
+            return;
+        }
+    }
     for (uint32_t vi = tid; vi < nvec; vi += kThreads) {
         const uint32_t g = fdiv(vi, a.d_q4);
         const uint32_t fi = vi - g * a.q4;        // vector index inside the plane
@@ -2698,6 +2739,7 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
             a->G = (uint32_t)G;
             a->d_q4 = make_fastdiv(a->q4);
             a->d_w4 = make_fastdiv(a->w4);
+            a->pair8 = es == 2 && W % 8 == 0 && ((uintptr_t)xhat % 16) == 0;
             *grid = (uint32_t)((L.P + G - 1) / G);
             return 0;
         }
