@@ -2791,6 +2791,14 @@ void squeeze_dims(int64_t& D, int64_t& H, int64_t& W) {
     else if (D > 1 && W == 1) { W = H; H = D; D = 1; }
 }
 
+// A plane that is a single block has the same cached tuple under every block size that covers it:
+// small 2-D planes are handed to the kernels specialised for B = 4 and B = 8.
+int covering_block(const Layout& L, int64_t D, int64_t H, int64_t W, int B) {
+    if (L.nb != 1 || D != 1) return B;
+    const int64_t m = H > W ? H : W;
+    return m <= 4 ? 4 : m <= 8 ? 8 : B;
+}
+
 int packed_layout_impl(int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int B, int b, division_dtype dt,
                        size_t* codes_off, size_t* codes_bytes, size_t* meta_off, size_t* meta_bytes,
                        size_t* lfc_off, size_t* lfc_bytes) {
@@ -2811,6 +2819,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
     Layout L;
     const int rc = make_layout(N, C, D, H, W, B, b, (int)dt, &L);
     if (rc != DIVISION_OK) return rc;
+    B = covering_block(L, D, H, W, B);
     if (packed_capacity < L.total) return DIVISION_ESIZE;
     const size_t es = dt == DIVISION_BF16 ? 2 : 4;
     uintptr_t all_x = 0;            // alignment of the batch = alignment of the OR of its pointers
@@ -2904,6 +2913,7 @@ int decompress_impl(int count, const void* const* packed, void* const* xhat, siz
     Layout L;
     const int rc = make_layout(N, C, D, H, W, B, b, (int)dt, &L);
     if (rc != DIVISION_OK) return rc;
+    B = covering_block(L, D, H, W, B);
     if (packed_bytes < L.total) return DIVISION_ESIZE;
     const size_t es = dt == DIVISION_BF16 ? 2 : 4;
     uintptr_t all_out = 0;
@@ -2951,6 +2961,7 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     Layout L;
     const int rc = make_layout(N, C, D, H, W, B, b, (int)dt, &L);
     if (rc != DIVISION_OK) return rc;
+    B = covering_block(L, D, H, W, B);
     const bool flat = D == 1;
     const char* sfx = flat ? "" : "_3d";
     const size_t es = dt == DIVISION_BF16 ? 2 : 4;
