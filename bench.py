@@ -174,6 +174,7 @@ VARIANTS = [
     # what, shape, B, b     (fp32 maps; the 2-D shapes are those of the ResNet-50 set at batch 64)
     ("block size 12", (64, 256, 56, 56), 12, 2), ("block size 16", (64, 256, 56, 56), 16, 2),
     ("block size 18", (64, 256, 56, 56), 18, 2), ("block size 64", (64, 256, 56, 56), 64, 2),
+    ("block size 64", (64, 512, 28, 28), 64, 2), ("block size 64", (64, 1024, 14, 14), 64, 2),
     ("block size 12", (64, 512, 28, 28), 12, 2), ("block size 18", (64, 512, 28, 28), 18, 2),
     ("block size 12", (64, 1024, 14, 14), 12, 2),
     ("8-bit codes", (64, 256, 56, 56), 8, 8), ("4-bit codes", (64, 256, 56, 56), 8, 4),

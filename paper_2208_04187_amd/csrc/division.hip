@@ -1324,6 +1324,150 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
     }
 }
 
+// the elements of one 16-byte vector of x as fp32
+template <typename T>
+__device__ __forceinline__ void unpack_vec(const u32x4& q, float (&x)[16 / sizeof(T)]) {
+    if constexpr (sizeof(T) == 4) {
+        x[0] = __uint_as_float(q.x); x[1] = __uint_as_float(q.y); x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
+    } else {
+        x[0] = __uint_as_float(q.x << 16); x[1] = __uint_as_float(q.x & 0xffff0000u);
+        x[2] = __uint_as_float(q.y << 16); x[3] = __uint_as_float(q.y & 0xffff0000u);
+        x[4] = __uint_as_float(q.z << 16); x[5] = __uint_as_float(q.z & 0xffff0000u);
+        x[6] = __uint_as_float(q.w << 16); x[7] = __uint_as_float(q.w & 0xffff0000u);
+    }
+}
+
+// ------------------------------------------------------------------ compress, planes that are one block
+
+struct OneArgs {
+    CompTab tab;
+    Regions rg;
+    uint32_t P, HW, WPP;
+    uint32_t qv;         // 16-byte vectors per plane
+    uint32_t S, S_log2;  // lanes per plane (power of two, at most 64)
+    uint32_t ppw;        // planes per wavefront = 64 / S
+};
+
+constexpr int kOneUnits = 13;     // vectors per lane: planes of up to 13 * 64 vectors
+
+// sum over aligned groups of S lanes (S a power of two <= 64, uniform in the wave) in a fixed
+// order, result in every lane of the group; all lanes must be active
+__device__ __forceinline__ double group_sum_any(uint32_t S, double v) {
+    if (S >= 2)  v += dpp_f64<kDppXor1>(v);
+    if (S >= 4)  v += dpp_f64<kDppXor2>(v);
+    if (S >= 8)  v += dpp_f64<kDppHalfMirror>(v);
+    if (S >= 16) v += dpp_f64<kDppMirror>(v);
+    if (S >= 32) {
+        const uint64_t u = (uint64_t)__double_as_longlong(v);
+        const int lo = (int)(uint32_t)u, hi = (int)(uint32_t)(u >> 32);
+        auto row = [&](int lane) -> double {
+            const uint32_t l = (uint32_t)__builtin_amdgcn_readlane(lo, lane), h = (uint32_t)__builtin_amdgcn_readlane(hi, lane);
+            return __longlong_as_double((long long)(((uint64_t)h << 32) | l));
+        };
+        const double r0 = row(0), r1 = row(16), r2 = row(32), r3 = row(48);
+        if (S == 64) v = (r0 + r1) + (r2 + r3);
+        else v = (threadIdx.x & 32u) ? r2 + r3 : r0 + r1;
+    }
+    return v;
+}
+
+// The block covers the whole plane (B at least every extent of the map: the later layers of a
+// network, or a block size like 64 on maps of 56 x 56 and below): H^L is the plane's mean, rows
+// and columns play no part, and the plane is a flat run of 16-byte vectors.  One wavefront per
+// 64 / S planes; the S lanes of a plane keep its vectors in registers (vector u in lane u mod S),
+// sums and extremes are reductions over those lanes, the codes leave as one to eight bytes per
+// vector.  LDS is not used.
+template <typename T, int BITS>
+__global__ void __launch_bounds__(64) compress_one(OneArgs a) {
+    constexpr int K = kOneUnits;
+    constexpr uint32_t EPV = 16 / sizeof(T);
+    constexpr uint32_t CBV = EPV * BITS / 8;
+    constexpr float Lf = float((1 << BITS) - 1);
+    const uint32_t tid = threadIdx.x;
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
+    const uint32_t sub = tid & (a.S - 1u);
+    const uint32_t p = blockIdx.x * a.ppw + (tid >> a.S_log2);
+    const bool live = p < a.P;
+    const uint32_t pc = live ? p : a.P - 1u;          // lanes past the last plane redo it; their stores are masked
+    const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const T*>(pt.x) + (size_t)pc * a.HW);
+
+    u32x4 q[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t u = sub + (uint32_t)k * a.S;
+        if (u < a.qv) q[k] = __builtin_nontemporal_load(src + u);
+    }
+    // ---- Sec. 4.1 AveragePooling with one window: the mean of the plane
+    double S = 0.0;
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t u = sub + (uint32_t)k * a.S;
+        if (u < a.qv) {
+            float f[EPV];
+            unpack_vec<T>(q[k], f);
+            double s4 = ((double)f[0] + (double)f[1]) + ((double)f[2] + (double)f[3]);
+            mn = fminf(mn, fminf(fminf(f[0], f[1]), fminf(f[2], f[3])));
+            mx = fmaxf(mx, fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])));
+            if constexpr (EPV == 8) {
+                s4 += ((double)f[4] + (double)f[5]) + ((double)f[6] + (double)f[7]);
+                mn = fminf(mn, fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
+                mx = fmaxf(mx, fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
+            }
+            S += s4;
+        }
+    }
+    S = group_sum_any(a.S, S);
+    const float lfc = lfc_round<T>(mean_of(S, a.HW), kC16<T>);
+    // ---- extremes of the residual (x -> fl(x - m) is monotone), scale of Eq. (quantization), keys
+    mn = mn - lfc;
+    mx = mx - lfc;
+    group_minmax(a.S, mn, mx);
+    float delta, Delta, inv;
+    plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
+    const float invs = inv * (float)(1u << (32 - BITS));
+    const uint32_t k1 = mix32(pc ^ pt.seed_a);
+    const uint32_t k2 = mix32(k1 + pt.seed_c);
+    uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)pc * a.WPP * 4;
+    if (live && sub == 0) {
+        meta_store(pt.meta, p, delta, Delta, kC16<T>);
+        lfc_store<T>(pt.lfc, (size_t)p, lfc, kC16<T>);
+        const uint32_t padb = a.WPP * 4 - a.qv * CBV;                 // pad bytes of the last word are zero
+        for (uint32_t t = 0; t < padb; ++t) cbase[a.qv * CBV + t] = 0;
+    }
+    // ---- residual, Quant, packing
+    const uint32_t rscale = 1u << (16 - BITS);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t u = sub + (uint32_t)k * a.S;
+        if (live && u < a.qv) {
+            float h[EPV];
+            unpack_vec<T>(q[k], h);
+#pragma unroll
+            for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lfc;
+            const uint32_t xw0 = k1 + (u * (EPV / 2)) * kWeyl;
+            uint8_t* dst = cbase + u * CBV;
+            if constexpr (CBV <= 4) {
+                uint32_t c = 0;
+#pragma unroll
+                for (int j = EPV / 2 - 1; j >= 0; --j)
+                    c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+                if constexpr (CBV == 1) *dst = (uint8_t)c;
+                else if constexpr (CBV == 2) *reinterpret_cast<uint16_t*>(dst) = (uint16_t)c;
+                else *reinterpret_cast<uint32_t*>(dst) = c;
+            } else {
+                uint32_t lo = 0, hi = 0;
+                hi = push_pair<BITS>(hi, h[6], h[7], delta, invs, xw0 + 3u * kWeyl, k2, rscale);
+                hi = push_pair<BITS>(hi, h[4], h[5], delta, invs, xw0 + 2u * kWeyl, k2, rscale);
+                lo = push_pair<BITS>(lo, h[2], h[3], delta, invs, xw0 + kWeyl, k2, rscale);
+                lo = push_pair<BITS>(lo, h[0], h[1], delta, invs, xw0, k2, rscale);
+                reinterpret_cast<uint32_t*>(dst)[0] = lo;
+                reinterpret_cast<uint32_t*>(dst)[1] = hi;
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ compress, any block size, chunk in LDS
 
 struct RowsArgs {
@@ -1341,19 +1485,6 @@ struct RowsArgs {
 };
 
 constexpr int kRowsKeep = 13;     // 16-byte vectors a lane of compress_rows holds in registers
-
-// the elements of one 16-byte vector of x as fp32
-template <typename T>
-__device__ __forceinline__ void unpack_vec(const u32x4& q, float (&x)[16 / sizeof(T)]) {
-    if constexpr (sizeof(T) == 4) {
-        x[0] = __uint_as_float(q.x); x[1] = __uint_as_float(q.y); x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
-    } else {
-        x[0] = __uint_as_float(q.x << 16); x[1] = __uint_as_float(q.x & 0xffff0000u);
-        x[2] = __uint_as_float(q.y << 16); x[3] = __uint_as_float(q.y & 0xffff0000u);
-        x[4] = __uint_as_float(q.z << 16); x[5] = __uint_as_float(q.z & 0xffff0000u);
-        x[6] = __uint_as_float(q.w << 16); x[7] = __uint_as_float(q.w & 0xffff0000u);
-    }
-}
 
 // One 16-byte vector of x (EPV consecutive elements of one row: W is a multiple of EPV) -> its
 // EPV * BITS / 8 code bytes.  f = vector index inside the plane, lp = the plane's LFC values (LDS),
@@ -2564,6 +2695,29 @@ bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
 }
 
 // Fills the any-block-size compress plan; false when a plane does not fit LDS or the 32-bit index tricks.
+// Fills the one-block plan: the block covers the plane, which is whole 16-byte vectors, at most
+// kOneUnits per lane of a wavefront.
+bool plan_one(const Layout& L, size_t es, const void* x, OneArgs* a, uint32_t* grid) {
+    const uint64_t epv = 16 / es;
+    if (L.nb != 1 || ((uintptr_t)x % 16) != 0 || L.HW % epv != 0) return false;
+    const uint64_t qv = L.HW / epv;
+    if (qv > (uint64_t)kOneUnits * 64) return false;
+    // lanes per plane: the power of two that wastes the fewest lane slots (ties: the larger one)
+    uint32_t best_S = 0, best_log = 0;
+    uint64_t best_slots = ~0ull;
+    for (uint32_t lg = 0; lg <= 6; ++lg) {
+        const uint64_t S = 1ull << lg, K = (qv + S - 1) / S;
+        if (K > (uint64_t)kOneUnits) continue;
+        if (S * K <= best_slots) { best_slots = S * K; best_S = (uint32_t)S; best_log = lg; }
+    }
+    a->P = (uint32_t)L.P; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP;
+    a->qv = (uint32_t)qv;
+    a->S = best_S; a->S_log2 = best_log;
+    a->ppw = 64u / best_S;
+    *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
+    return true;
+}
+
 // Hs = rows of one depth slice, D = depth slices (1 for a 2-D map).
 bool plan_rows(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, int b, size_t es, const void* x,
                RowsArgs* a, uint32_t* grid, size_t* lds) {
@@ -2848,11 +3002,12 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         LaneArgs la{};
         RowsArgs wa2{};
         PlaneArgs pa{};
+        OneArgs oa{};
         AnyArgs g{};
         size_t lds = 0;
         uint32_t grid = 0;
         int vec = 1, nt = 64, nw = 1;
-        enum { REGS, LANE, ITEMS, WAVE, TILE, ROWS, PLANE, ANY } kind;
+        enum { REGS, LANE, ITEMS, WAVE, TILE, ONE, ROWS, PLANE, ANY } kind;
         const bool flat = D == 1;               // the register, item, wavefront and tile kernels take 2-D maps
         if (flat && plan_regs(L, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
         else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
@@ -2860,6 +3015,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         else if (flat && plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
             kind = WAVE; wa.tab = tab; wa.rg = rg;
         } else if (flat && plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) { kind = TILE; a.tab = tab; a.rg = rg; }
+        else if (plan_one(L, es, xa, &oa, &grid)) { kind = ONE; oa.tab = tab; oa.rg = rg; lds = 0; }
         else if (plan_rows(L, D, H, W, B, b, es, xa, &wa2, &grid, &lds)) { kind = ROWS; wa2.tab = tab; wa2.rg = rg; }
         else if (plan_plane(L, D, H, W, B, es, xa, &pa, &grid, &lds)) { kind = PLANE; pa.tab = tab; pa.rg = rg; }
         else {
@@ -2879,6 +3035,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
                 case WAVE: return launch_wave<T, BITS>(B, vec, wa, gd, lds, st);
                 case TILE: return launch_tile<T, BITS>(B, vec, a, gd, lds, st);
                 case LANE: hipLaunchKernelGGL((compress_lane<T, BITS>), gd, dim3(64), lds, st, la); return hipGetLastError();
+                case ONE: hipLaunchKernelGGL((compress_one<T, BITS>), gd, dim3(64), 0, st, oa); return hipGetLastError();
                 case ROWS: {
                     void (*kern)(RowsArgs) = flat ? compress_rows<T, BITS> : compress_rows_3d<T, BITS>;
                     const hipError_t e = allow_large_lds(kern, lds);
@@ -2968,7 +3125,7 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     const char* tn = dt == DIVISION_BF16 ? "bf16_t" : dt == DIVISION_F32_C16 ? "f32c16_t" : "float";
     int n;
     if (direction == 0) {
-        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
+        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; OneArgs oa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (flat && plan_regs(L, H, W, B, es, data, &ra, &grid, &lds, &nw))
             n = snprintf(out, cap, "compress_regs<%s, %d, %d, %d>", tn, b, B, nw);
         else if (plan_lane(L, es, data, &la, &grid, &lds))
@@ -2979,6 +3136,8 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
             n = snprintf(out, cap, "compress_wave<%s, %d, %d, %d>", tn, b, B, vec);
         else if (flat && plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
             n = snprintf(out, cap, "compress_tile<%s, %d, %d, %d, %d>", tn, b, B, vec, nt);
+        else if (plan_one(L, es, data, &oa, &grid))
+            n = snprintf(out, cap, "compress_one<%s, %d>", tn, b);
         else if (plan_rows(L, D, H, W, B, b, es, data, &wa2, &grid, &lds))
             n = snprintf(out, cap, "compress_rows%s<%s, %d>", sfx, tn, b);
         else if (plan_plane(L, D, H, W, B, es, data, &pa, &grid, &lds))

@@ -535,7 +535,7 @@ ROWS_CASES = [
     ((8, 24, 56, 56), 12, 2),           # 4 full blocks + one of 8 per side, several planes per chunk, many chunks
     ((8, 24, 56, 56), 16, 2),           # 3 full blocks + one of 8
     ((8, 24, 56, 56), 18, 4),           # 3 full blocks + one of 2
-    ((8, 24, 56, 56), 64, 2),           # block larger than the map: one block per plane
+    ((8, 24, 54, 57), 64, 2),           # block larger than the map on a plane that is not whole vectors
     ((7, 19, 28, 28), 12, 2),           # odd plane count: ragged last chunk
     ((7, 19, 28, 28), 18, 8),
     ((5, 33, 14, 14), 12, 4),           # blocks of 12 and 2
@@ -554,12 +554,44 @@ ROWS_CASES = [
 ]
 
 
+# planes that are one block (B at least every extent): the flat one-block kernel
+ONE_BLOCK_CASES = [
+    ((8, 24, 56, 56), 64, 2),           # 784 vectors: all 64 lanes, 13 vectors each (the Swin-T setting B = 64)
+    ((7, 19, 28, 28), 64, 4),           # 196 vectors: 16 lanes per plane, 4 planes per wavefront, ragged last wavefront
+    ((5, 33, 14, 14), 64, 2),           # 49 vectors: 4 lanes per plane
+    ((3, 5, 6, 10), 16, 8),             # 15 vectors
+    ((130, 3, 12, 12), 16, 2),          # 390 planes of 36 vectors
+    ((8, 8, 1, 3072), 4096, 2),         # 1-D map under one block
+    ((9, 7, 1, 52), 64, 4),             # 13 vectors: a lane per plane, 63 planes: one wavefront, one lane idle
+    ((2, 3, 56, 56), 128, 8),
+    ((3, 3, 10, 16), 18, 2),            # ragged last code word (160 elements at 16 per word: exact) and B = 18
+    ((3, 3, 10, 14), 18, 2),            # 140 elements: the last word of a plane is partly pad
+]
+
+
+@pytest.mark.parametrize("shape,B,b", ONE_BLOCK_CASES)
+@pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
+def test_one_block_kernel_matches_oracle(shape, B, b, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    c16 = mode == "c16"
+    hw = shape[2] * shape[3]
+    if mode != "bf16" or hw % 8 == 0:
+        assert pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16).startswith("compress_one<")
+    _check_variant(shape, B, b, mode)
+
+
 @pytest.mark.parametrize("shape,B,b", ROWS_CASES)
 @pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
 def test_general_block_size_kernel_matches_oracle(shape, B, b, mode):
     dtype = torch.bfloat16 if mode == "bf16" else torch.float32
     c16 = mode == "c16"
     assert pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16).startswith("compress_rows<")
+    _check_variant(shape, B, b, mode)
+
+
+def _check_variant(shape, B, b, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    c16 = mode == "c16"
     g = torch.Generator().manual_seed(7000 + sum(shape) + 13 * B + b)
     x = (torch.randn(shape, generator=g) * 2.0 + 0.25).to(dtype)       # signed values
     x[0, 0] = 1.5                                                     # one constant plane (degenerate scale)
