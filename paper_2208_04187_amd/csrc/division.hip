@@ -1169,7 +1169,8 @@ struct RegsArgs {
     uint32_t q4;         // units (4 consecutive elements) per plane = H*W/4
     uint32_t w4;         // units per row = W/4
     uint32_t ppw;        // planes a workgroup handles one after the other
-    FastDiv d_w4, d_LW;
+    uint32_t B;          // block size, read by the instance for any B (template argument 0) only
+    FastDiv d_w4, d_LW, d_B, d_upb;      // d_upb divides by B / 4
 };
 
 constexpr int kRegUnits = 13;     // units per lane: planes of up to 13 * (threads per workgroup) units
@@ -1181,6 +1182,10 @@ constexpr int kRegUnits = 13;     // units per lane: planes of up to 13 * (threa
 // per block (~7 KB per wavefront), so occupancy is set by registers, not LDS.
 // A unit lies inside one block (W % 4 == 0, B % 4 == 0), which block is the
 // same for every plane and is worked out once per workgroup.
+// B = 0 is the instance for any block size that is a multiple of 4 (12, 16, 64 of the paper's
+// sweep): the block size comes from the arguments, the loops over a block's unit sums run to
+// their bounds instead of being unrolled, and rounds of units past the plane are skipped, so
+// that planes far below 13 units per lane are worth taking too.
 template <typename T, int BITS, int B, int NW>
 __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
     constexpr int NT = 64 * NW;
@@ -1202,10 +1207,14 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
         const uint32_t f = tid + NT * k;
         const uint32_t row = fdiv(f, a.d_w4);
         const uint32_t c4 = f - row * a.w4;
-        blk[k] = f < a.q4 ? (row / B) * a.LW + c4 / UPB : a.nb;
+        if constexpr (B != 0) blk[k] = f < a.q4 ? (row / B) * a.LW + c4 / UPB : a.nb;
+        else blk[k] = f < a.q4 ? fdiv(row, a.d_B) * a.LW + fdiv(c4, a.d_upb) : a.nb;
     }
     if (tid == 0) lfcs[a.nb] = __builtin_nanf("");
-    const bool full_blocks = (a.H % B) == 0 && (a.W % B) == 0;
+    bool full_blocks = false;
+    if constexpr (B != 0) full_blocks = (a.H % B) == 0 && (a.W % B) == 0;
+    // rounds of units a plane has (uniform); the instances for B = 4 and 8 always run all K
+    auto round_live = [&](int k) -> bool { return B != 0 || (uint32_t)(NT * k) < a.q4; };
 
     const uint32_t pbeg = blockIdx.x * a.ppw;
     const uint32_t pend = min(a.P, pbeg + a.ppw);
@@ -1218,6 +1227,10 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
                 __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(a.HW * sizeof(T)), 0x00020000);
 #pragma unroll
             for (int k = 0; k < K; ++k) {
+                if (!round_live(k)) {
+                    x[k][0] = x[k][1] = x[k][2] = x[k][3] = 0.0f;
+                    continue;
+                }
                 if constexpr (sizeof(T) == 4) {
                     const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, tid * 16u, k * NT * 16, kLoadAux);
                     x[k][0] = __uint_as_float(q.x); x[k][1] = __uint_as_float(q.y);
@@ -1233,17 +1246,36 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
         // ---- Sec. 4.1 AveragePooling, step 1: one binary64 sum per unit
 #pragma unroll
         for (int k = 0; k < K; ++k)
-            usum[tid + NT * k] = ((double)x[k][0] + (double)x[k][1]) + ((double)x[k][2] + (double)x[k][3]);
+            if (round_live(k)) usum[tid + NT * k] = ((double)x[k][0] + (double)x[k][1]) + ((double)x[k][2] + (double)x[k][3]);
         if constexpr (NW == 1) wave_sync(); else lds_barrier();
 
         // ---- step 2: a lane per block adds the block's unit sums in a fixed order
         for (uint32_t t = tid; t < a.nb; t += NT) {
             const uint32_t bi = fdiv(t, a.d_LW);
             const uint32_t bj = t - bi * a.LW;
-            const uint32_t u0 = bi * B * a.w4 + bj * UPB;
             double S = 0.0;
             uint32_t cnt;
-            if (full_blocks) {
+            if constexpr (B == 0) {
+                const uint32_t upb = a.B / 4;
+                const uint32_t rows = min(a.B, a.H - bi * a.B);
+                const uint32_t units = min(upb, a.w4 - bj * upb);
+                const double* us = usum + bi * a.B * a.w4 + bj * upb;
+                // B <= 16: at most four units per block row; a fixed four reads per row (units past
+                // the block re-read its first and add nothing) let several rows' reads go out together
+#pragma unroll 4
+                for (uint32_t rr = 0; rr < rows; ++rr) {
+#pragma unroll
+                    for (uint32_t u = 0; u < 4; ++u) {
+                        const bool ok = u < units;
+                        const double v = us[ok ? rr * a.w4 + u : 0u];
+                        S += ok ? v : 0.0;
+                    }
+                }
+                cnt = rows * units * 4;
+            }
+            const uint32_t u0 = bi * B * a.w4 + bj * UPB;
+            if constexpr (B == 0) {
+            } else if (full_blocks) {
 #pragma unroll
                 for (int rr = 0; rr < B; ++rr)
 #pragma unroll
@@ -1274,6 +1306,7 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
         float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
         for (int k = 0; k < K; ++k) {
+            if (!round_live(k)) continue;
             const float lfc = lfcs[blk[k]];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -1308,6 +1341,7 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
             const uint32_t xw0 = k1 + (2u * tid) * kWeyl;
 #pragma unroll
             for (int k = 0; k < K; ++k) {
+                if (!round_live(k)) continue;
                 const uint32_t xw = xw0 + (uint32_t)(2 * NT * k) * kWeyl;
                 uint32_t c = push_pair<BITS>(0u, x[k][2], x[k][3], delta, invs, xw + kWeyl, k2, rscale);
                 c = push_pair<BITS>(c, x[k][0], x[k][1], delta, invs, xw, k2, rscale);
@@ -2551,21 +2585,32 @@ hipError_t launch_wave(int B, int vec, const WaveArgs& a, dim3 grid, size_t lds,
 // Fills the plane-in-registers compress plan; false when the shape is not covered.
 bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* x,
                RegsArgs* a, uint32_t* grid, size_t* lds, int* nw_out) {
-    if ((B != 4 && B != 8) || W % 4 != 0) return false;
+    if (B % 4 != 0 || W % 4 != 0) return false;
     if (((uintptr_t)x % (4 * es)) != 0) return false;
     const uint64_t q4 = L.HW / 4;
+    const bool any_b = B != 4 && B != 8;          // the instance that reads B from its arguments
     int nw;
-    if (q4 >= 512 && q4 <= (uint64_t)kRegUnits * 64) nw = 1;
+    if (any_b) {
+        // a lane adds B * B / 4 unit sums one after the other: blocks of up to 16 x 16, several per plane
+        if (B > 16 || L.nb == 1) return false;
+        if (q4 >= 512 && q4 <= (uint64_t)kRegUnits * 64) nw = 1;
+        else if (q4 > (uint64_t)kRegUnits * 64 && q4 <= (uint64_t)kRegUnits * 256) nw = 4;
+        else return false;
+    } else if (q4 >= 512 && q4 <= (uint64_t)kRegUnits * 64) nw = 1;
     else if (q4 >= 2048 && q4 <= (uint64_t)kRegUnits * 256) nw = 4;
     else return false;
     const uint64_t nt = 64ull * nw, w4 = (uint64_t)W / 4;
     if (!fastdiv_ok(kRegUnits * nt, w4) || !fastdiv_ok(L.nb + nt, L.LW) || L.HW * es >= (1ull << 31)) return false;
+    if (!fastdiv_ok((uint64_t)H, (uint64_t)B) || !fastdiv_ok(w4, (uint64_t)B / 4)) return false;
     a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
     a->LH = (uint32_t)L.LH; a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP;
     a->q4 = (uint32_t)q4; a->w4 = (uint32_t)w4;
     a->ppw = 1;      // one plane per workgroup measured best (more workgroups, better balance)
+    a->B = (uint32_t)B;
     a->d_w4 = make_fastdiv((uint32_t)w4);
     a->d_LW = make_fastdiv((uint32_t)L.LW);
+    a->d_B = make_fastdiv((uint32_t)B);
+    a->d_upb = make_fastdiv((uint32_t)B / 4);
     *lds = 8ull * kRegUnits * nt + 4ull * ((L.nb + 1 + 3) & ~3ull) + 8ull * nw + 16;
     *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
     *nw_out = nw;
@@ -2575,8 +2620,8 @@ bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
 template <typename T, int BITS>
 hipError_t launch_regs(int B, int nw, const RegsArgs& a, dim3 grid, size_t lds, hipStream_t st) {
     void (*kern)(RegsArgs);
-    if (nw == 1) kern = B == 8 ? compress_regs<T, BITS, 8, 1> : compress_regs<T, BITS, 4, 1>;
-    else kern = B == 8 ? compress_regs<T, BITS, 8, 4> : compress_regs<T, BITS, 4, 4>;
+    if (nw == 1) kern = B == 8 ? compress_regs<T, BITS, 8, 1> : B == 4 ? compress_regs<T, BITS, 4, 1> : compress_regs<T, BITS, 0, 1>;
+    else kern = B == 8 ? compress_regs<T, BITS, 8, 4> : B == 4 ? compress_regs<T, BITS, 4, 4> : compress_regs<T, BITS, 0, 4>;
     hipLaunchKernelGGL(kern, grid, dim3(64 * nw), lds, st, a);
     return hipGetLastError();
 }
@@ -3127,7 +3172,7 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     if (direction == 0) {
         TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; OneArgs oa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (flat && plan_regs(L, H, W, B, es, data, &ra, &grid, &lds, &nw))
-            n = snprintf(out, cap, "compress_regs<%s, %d, %d, %d>", tn, b, B, nw);
+            n = snprintf(out, cap, "compress_regs<%s, %d, %d, %d>", tn, b, (B == 4 || B == 8) ? B : 0, nw);
         else if (plan_lane(L, es, data, &la, &grid, &lds))
             n = snprintf(out, cap, "compress_lane<%s, %d>", tn, b);
         else if (flat && plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))

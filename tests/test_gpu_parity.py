@@ -585,7 +585,30 @@ def test_one_block_kernel_matches_oracle(shape, B, b, mode):
 def test_general_block_size_kernel_matches_oracle(shape, B, b, mode):
     dtype = torch.bfloat16 if mode == "bf16" else torch.float32
     c16 = mode == "c16"
-    assert pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16).startswith("compress_rows<")
+    name = pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16)
+    # block sizes 12 and 16 on planes of whole 4-element units take the register kernel's any-B instance
+    assert name.startswith("compress_rows<") or (name.startswith("compress_regs<") and ", 0, " in name)
+    _check_variant(shape, B, b, mode)
+
+
+# the register kernel's instance for any block size that is a multiple of 4 (up to 16)
+REGS_ANY_CASES = [
+    ((4, 6, 40, 52), 12, 2),            # 520 units, blocks of 12 and 4 both ways
+    ((3, 4, 64, 64), 16, 4),            # 1024 units: four wavefronts, full blocks
+    ((2, 5, 48, 44), 12, 8),            # 528 units: rounds of units past the plane are skipped
+    ((5, 3, 48, 48), 12, 2),            # full blocks of 12
+    ((9, 2, 56, 56), 16, 2),            # blocks 16, 16, 16, 8
+    ((2, 2, 112, 112), 12, 4),          # 3136 units, 100 blocks
+    ((3, 2, 24, 100), 16, 2),
+]
+
+
+@pytest.mark.parametrize("shape,B,b", REGS_ANY_CASES)
+@pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
+def test_register_kernel_any_block_size_matches_oracle(shape, B, b, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    name = pkg.division_kernel_name(0, shape, B, b, dtype, c16=mode == "c16")
+    assert name.startswith("compress_regs<") and ", 0, " in name
     _check_variant(shape, B, b, mode)
 
 
