@@ -114,3 +114,42 @@ def test_full_size_volumes_match_oracle(shape, B, b):
     torch.cuda.synchronize()
     assert np.array_equal(pk.cpu().numpy(), ref)
     assert np.array_equal(y.cpu().numpy(), oracle.decompress(ref, shape, B, b, threads=16))
+
+
+def _volume_sweep(n, seed0):
+    rng = np.random.default_rng(seed0)
+    cases = []
+    for _ in range(n):
+        D = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16, 17]))
+        H = int(rng.integers(1, 41))
+        W = int(rng.choice([H, int(rng.integers(1, 61)), 4 * int(rng.integers(1, 16)), 8 * int(rng.integers(1, 9))]))
+        B = int(rng.choice([1, 2, 3, 4, 4, 5, 8, 8, 8, 12, 16, 18, 64]))
+        b = int(rng.choice([2, 2, 4, 8]))
+        N, C = int(rng.integers(1, 5)), int(rng.integers(1, 9))
+        if D * H * W <= 256 and rng.random() < 0.5:
+            N, C = int(rng.integers(10, 60)), int(rng.integers(3, 9))
+        mode = str(rng.choice(["f32", "f32", "bf16", "c16"]))
+        cases.append(((N, C, D, H, W), B, b, mode, int(rng.integers(0, 2 ** 63))))
+    return cases
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_seeded_sweep_of_volumes(chunk):
+    """160 pseudo-random (shape, B, b, format, seed) combinations of 3-D maps, 40 per test."""
+    for shape, B, b, mode, seed in _volume_sweep(160, 20260117)[40 * chunk:40 * (chunk + 1)]:
+        dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+        c16 = mode == "c16"
+        dt = oracle.F32_C16 if c16 else (oracle.BF16 if mode == "bf16" else oracle.F32)
+        g = torch.Generator().manual_seed(seed % 100003)
+        x = torch.relu(torch.randn(shape, generator=g) + 0.3).to(dtype)
+        xh, _ = to_host_array(x)
+        ref = oracle.compress(xh, B, b, seed, dt)
+        need = pkg.division_packed_bytes_3d(*shape, B, b, dtype, c16)
+        pk = torch.full((need,), 0x5A, dtype=torch.uint8, device="cuda:0")
+        pkg.division_compress_3d(x.to("cuda:0"), B, b, seed, packed=pk, c16=c16)
+        y = pkg.division_decompress_3d(pk, shape, B, b, dtype, c16=c16)
+        torch.cuda.synchronize()
+        tag = f"shape={shape} B={B} b={b} mode={mode} seed={seed} kernel={pkg.division_kernel_name_3d(0, shape, B, b, dtype, c16=c16)}"
+        assert np.array_equal(pk.cpu().numpy(), ref), tag
+        yh, _ = to_host_array(y.cpu())
+        assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt)), tag

@@ -528,6 +528,45 @@ def test_seeded_sweep_of_shapes_block_sizes_and_code_widths(chunk):
         assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt)), tag
 
 
+def _sweep_cases_whole_vectors(n, seed0):
+    """Maps whose rows are whole 4- or 8-element vectors, under every block size: the register and
+    one-block kernels and the vector paths of the general ones."""
+    rng = np.random.default_rng(seed0)
+    cases = []
+    for _ in range(n):
+        W = 4 * int(rng.integers(1, 33))
+        H = int(rng.choice([1, W, int(rng.integers(1, 130))]))
+        B = int(rng.choice([4, 8, 12, 12, 16, 16, 18, 20, 24, 32, 64, 64, 128]))
+        b = int(rng.choice([2, 2, 4, 8]))
+        N, C = int(rng.integers(1, 5)), int(rng.integers(1, 10))
+        if H * W <= 1024 and rng.random() < 0.5:
+            N, C = int(rng.integers(8, 40)), int(rng.integers(3, 12))
+        mode = str(rng.choice(["f32", "f32", "bf16", "c16"]))
+        cases.append(((N, C, H, W), B, b, mode, int(rng.integers(0, 2 ** 63))))
+    return cases
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_seeded_sweep_of_vector_row_maps_under_every_block_size(chunk):
+    for shape, B, b, mode, seed in _sweep_cases_whole_vectors(160, 20260118)[40 * chunk:40 * (chunk + 1)]:
+        dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+        c16 = mode == "c16"
+        dt = oracle.F32_C16 if c16 else (oracle.BF16 if mode == "bf16" else oracle.F32)
+        g = torch.Generator().manual_seed(seed % 100003)
+        x = (torch.randn(shape, generator=g) * 1.7 - 0.2).to(dtype)
+        xh, _ = to_host_array(x)
+        ref = oracle.compress(xh, B, b, seed, dt)
+        need = pkg.division_packed_bytes(*shape, B, b, dtype, c16)
+        pk = torch.full((need,), 0xC3, dtype=torch.uint8, device="cuda:0")
+        pkg.division_compress(x.to("cuda:0"), B, b, seed, packed=pk, c16=c16)
+        y = pkg.division_decompress(pk, shape, B, b, dtype, c16=c16)
+        torch.cuda.synchronize()
+        tag = f"shape={shape} B={B} b={b} mode={mode} seed={seed} kernel={pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16)}"
+        assert np.array_equal(pk.cpu().numpy(), ref), tag
+        yh, _ = to_host_array(y.cpu())
+        assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt)), tag
+
+
 # ---------------------------------------------------------------- the block sizes of the paper's sweep (Sec. 5, B ablation)
 
 ROWS_CASES = [
