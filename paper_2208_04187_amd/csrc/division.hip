@@ -1260,15 +1260,16 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
                 const uint32_t rows = min(a.B, a.H - bi * a.B);
                 const uint32_t units = min(upb, a.w4 - bj * upb);
                 const double* us = usum + bi * a.B * a.w4 + bj * upb;
-                // B <= 16: at most four units per block row; a fixed four reads per row (units past
-                // the block re-read its first and add nothing) let several rows' reads go out together
-#pragma unroll 4
+                // four reads at a time (units past the block re-read its first and add nothing), so
+                // that several reads go out together
                 for (uint32_t rr = 0; rr < rows; ++rr) {
+                    for (uint32_t ub = 0; ub < units; ub += 4) {
 #pragma unroll
-                    for (uint32_t u = 0; u < 4; ++u) {
-                        const bool ok = u < units;
-                        const double v = us[ok ? rr * a.w4 + u : 0u];
-                        S += ok ? v : 0.0;
+                        for (uint32_t u = 0; u < 4; ++u) {
+                            const bool ok = ub + u < units;
+                            const double v = us[ok ? rr * a.w4 + ub + u : 0u];
+                            S += ok ? v : 0.0;
+                        }
                     }
                 }
                 cnt = rows * units * 4;
@@ -2591,8 +2592,10 @@ bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
     const bool any_b = B != 4 && B != 8;          // the instance that reads B from its arguments
     int nw;
     if (any_b) {
-        // a lane adds B * B / 4 unit sums one after the other: blocks of up to 16 x 16, several per plane
-        if (B > 16 || L.nb == 1) return false;
+        // a lane adds the unit sums of its block one after the other: at most 64 of them (blocks of
+        // up to 16 x 16, longer ones on maps of few rows), several blocks per plane
+        const uint64_t brows = (uint64_t)B < (uint64_t)H ? (uint64_t)B : (uint64_t)H;
+        if (brows * ((uint64_t)B / 4) > 64 || L.nb == 1) return false;
         if (q4 >= 512 && q4 <= (uint64_t)kRegUnits * 64) nw = 1;
         else if (q4 > (uint64_t)kRegUnits * 64 && q4 <= (uint64_t)kRegUnits * 256) nw = 4;
         else return false;

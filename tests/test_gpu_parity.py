@@ -639,6 +639,10 @@ REGS_ANY_CASES = [
     ((9, 2, 56, 56), 16, 2),            # blocks 16, 16, 16, 8
     ((2, 2, 112, 112), 12, 4),          # 3136 units, 100 blocks
     ((3, 2, 24, 100), 16, 2),
+    ((3, 5, 1, 3072), 64, 2),           # 1-D map, blocks of 64 elements (16 units)
+    ((2, 4, 2, 2048), 64, 4),           # two rows: 32 units per block
+    ((3, 3, 1, 2400), 32, 8),           # 75 blocks of 32
+    ((2, 3, 1, 2100), 64, 2),           # ragged last block of 52
 ]
 
 
