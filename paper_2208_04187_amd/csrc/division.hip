@@ -1381,6 +1381,8 @@ struct OneArgs {
     uint32_t qv;         // 16-byte vectors per plane
     uint32_t S, S_log2;  // lanes per plane (power of two, at most 64)
     uint32_t ppw;        // planes per wavefront = 64 / S
+    uint32_t upb, upb_log2;  // compress_line: vectors per block (power of two, at most S); nb = blocks per plane
+    uint32_t nb;
 };
 
 constexpr int kOneUnits = 13;     // vectors per lane: planes of up to 13 * 64 vectors
@@ -1480,6 +1482,106 @@ __global__ void __launch_bounds__(64) compress_one(OneArgs a) {
             unpack_vec<T>(q[k], h);
 #pragma unroll
             for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lfc;
+            const uint32_t xw0 = k1 + (u * (EPV / 2)) * kWeyl;
+            uint8_t* dst = cbase + u * CBV;
+            if constexpr (CBV <= 4) {
+                uint32_t c = 0;
+#pragma unroll
+                for (int j = EPV / 2 - 1; j >= 0; --j)
+                    c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+                if constexpr (CBV == 1) *dst = (uint8_t)c;
+                else if constexpr (CBV == 2) *reinterpret_cast<uint16_t*>(dst) = (uint16_t)c;
+                else *reinterpret_cast<uint32_t*>(dst) = c;
+            } else {
+                uint32_t lo = 0, hi = 0;
+                hi = push_pair<BITS>(hi, h[6], h[7], delta, invs, xw0 + 3u * kWeyl, k2, rscale);
+                hi = push_pair<BITS>(hi, h[4], h[5], delta, invs, xw0 + 2u * kWeyl, k2, rscale);
+                lo = push_pair<BITS>(lo, h[2], h[3], delta, invs, xw0 + kWeyl, k2, rscale);
+                lo = push_pair<BITS>(lo, h[0], h[1], delta, invs, xw0, k2, rscale);
+                reinterpret_cast<uint32_t*>(dst)[0] = lo;
+                reinterpret_cast<uint32_t*>(dst)[1] = hi;
+            }
+        }
+    }
+}
+
+// 1-D maps (Appendix D, AveragePooling1D: Minibatch x Channel x N, the maps of linear and
+// transformer layers) whose block is a power-of-two number of 16-byte vectors (B = 4, 8, 16, 32, 64
+// for fp32): laid out like compress_one, the `upb` vectors of a block sit in neighbouring lanes of
+// one round, so a block's sum is a DPP reduction over those lanes and its LFC stays in a register.
+// No LDS.
+template <typename T, int BITS>
+__global__ void __launch_bounds__(64) compress_line(OneArgs a) {
+    constexpr int K = kOneUnits;
+    constexpr uint32_t EPV = 16 / sizeof(T);
+    constexpr uint32_t CBV = EPV * BITS / 8;
+    constexpr float Lf = float((1 << BITS) - 1);
+    const uint32_t tid = threadIdx.x;
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
+    const uint32_t sub = tid & (a.S - 1u);
+    const uint32_t p = blockIdx.x * a.ppw + (tid >> a.S_log2);
+    const bool live = p < a.P;
+    const uint32_t pc = live ? p : a.P - 1u;          // lanes past the last plane redo it; their stores are masked
+    const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const T*>(pt.x) + (size_t)pc * a.HW);
+
+    u32x4 q[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t u = sub + (uint32_t)k * a.S;
+        if (u < a.qv) q[k] = __builtin_nontemporal_load(src + u);
+    }
+    // ---- AveragePooling1D: block sums over the lanes of a block, residual extremes of the plane
+    float lfcv[K];
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        if ((uint32_t)k * a.S >= a.qv) { lfcv[k] = 0.0f; continue; }          // uniform: no vector of this round exists
+        const uint32_t u = sub + (uint32_t)k * a.S;
+        const bool valid = u < a.qv;
+        float f[EPV];
+        double s4 = 0.0;
+        if (valid) {
+            unpack_vec<T>(q[k], f);
+            s4 = ((double)f[0] + (double)f[1]) + ((double)f[2] + (double)f[3]);
+            if constexpr (EPV == 8) s4 += ((double)f[4] + (double)f[5]) + ((double)f[6] + (double)f[7]);
+        }
+        const double Sb = group_sum_any(a.upb, s4);
+        const uint32_t ustart = u & ~(a.upb - 1u);
+        const uint32_t nvec = valid ? min(a.upb, a.qv - ustart) : 1u;           // the last block may be short
+        const float lfc = lfc_round<T>(mean_of(Sb, nvec * EPV), kC16<T>);
+        lfcv[k] = lfc;
+        if (valid) {
+#pragma unroll
+            for (uint32_t e = 0; e < EPV; ++e) {
+                const float h = f[e] - lfc;
+                mn = fminf(mn, h);
+                mx = fmaxf(mx, h);
+            }
+            if (live && u == ustart) lfc_store<T>(pt.lfc, (size_t)p * a.nb + (u >> a.upb_log2), lfc, kC16<T>);
+        }
+    }
+    group_minmax(a.S, mn, mx);
+    float delta, Delta, inv;
+    plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
+    const float invs = inv * (float)(1u << (32 - BITS));
+    const uint32_t k1 = mix32(pc ^ pt.seed_a);
+    const uint32_t k2 = mix32(k1 + pt.seed_c);
+    uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)pc * a.WPP * 4;
+    if (live && sub == 0) {
+        meta_store(pt.meta, p, delta, Delta, kC16<T>);
+        const uint32_t padb = a.WPP * 4 - a.qv * CBV;                 // pad bytes of the last word are zero
+        for (uint32_t t = 0; t < padb; ++t) cbase[a.qv * CBV + t] = 0;
+    }
+    // ---- residual, Quant, packing
+    const uint32_t rscale = 1u << (16 - BITS);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t u = sub + (uint32_t)k * a.S;
+        if (live && u < a.qv) {
+            float h[EPV];
+            unpack_vec<T>(q[k], h);
+#pragma unroll
+            for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lfcv[k];
             const uint32_t xw0 = k1 + (u * (EPV / 2)) * kWeyl;
             uint8_t* dst = cbase + u * CBV;
             if constexpr (CBV <= 4) {
@@ -2750,13 +2852,12 @@ bool plan_one(const Layout& L, size_t es, const void* x, OneArgs* a, uint32_t* g
     if (L.nb != 1 || ((uintptr_t)x % 16) != 0 || L.HW % epv != 0) return false;
     const uint64_t qv = L.HW / epv;
     if (qv > (uint64_t)kOneUnits * 64) return false;
-    // lanes per plane: the power of two that wastes the fewest lane slots (ties: the larger one)
+    // lanes per plane: the smallest power of two from 8 up (a plane's lanes then read 128 contiguous
+    // bytes per round) that keeps the plane within kOneUnits rounds
     uint32_t best_S = 0, best_log = 0;
-    uint64_t best_slots = ~0ull;
-    for (uint32_t lg = 0; lg <= 6; ++lg) {
-        const uint64_t S = 1ull << lg, K = (qv + S - 1) / S;
-        if (K > (uint64_t)kOneUnits) continue;
-        if (S * K <= best_slots) { best_slots = S * K; best_S = (uint32_t)S; best_log = lg; }
+    for (uint32_t lg = 3; lg <= 6; ++lg) {
+        const uint64_t S = 1ull << lg;
+        if ((qv + S - 1) / S <= (uint64_t)kOneUnits) { best_S = (uint32_t)S; best_log = lg; break; }
     }
     a->P = (uint32_t)L.P; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP;
     a->qv = (uint32_t)qv;
@@ -2765,6 +2866,39 @@ bool plan_one(const Layout& L, size_t es, const void* x, OneArgs* a, uint32_t* g
     *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
     return true;
 }
+
+// Fills the plan of compress_line: a 1-D map (one row) of whole 16-byte vectors, several blocks per
+// plane, a block a power-of-two number of vectors, at most kOneUnits vectors per lane.
+bool plan_line(const Layout& L, int64_t D, int64_t H, int B, size_t es, const void* x, OneArgs* a, uint32_t* grid) {
+    const uint64_t epv = 16 / es;
+    if (D != 1 || H != 1 || L.nb < 2 || ((uintptr_t)x % 16) != 0 || L.HW % epv != 0 || (uint64_t)B % epv != 0) return false;
+    const uint64_t qv = L.HW / epv, upb = (uint64_t)B / epv;
+    if ((upb & (upb - 1)) != 0 || upb > 64 || qv > (uint64_t)kOneUnits * 64) return false;
+    uint32_t upb_log = 0;
+    while ((1ull << upb_log) < upb) ++upb_log;
+    // lanes per plane: the smallest power of two that is a block, at least 8 (a plane's lanes then read
+    // 128 contiguous bytes per round) and keeps the plane within kOneUnits rounds: few lanes per plane
+    // mean many planes per wavefront to share its fixed costs (measured: 8 or 16 lanes beat both the
+    // choice with the fewest idle lane slots and wider ones)
+    uint32_t best_S = 0, best_log = 0;
+    for (uint32_t lg = upb_log > 3 ? upb_log : 3; lg <= 6; ++lg) {
+        const uint64_t S = 1ull << lg;
+        if ((qv + S - 1) / S <= (uint64_t)kOneUnits) { best_S = (uint32_t)S; best_log = lg; break; }
+    }
+    if (best_S == 0) return false;
+    a->P = (uint32_t)L.P; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP;
+    a->qv = (uint32_t)qv;
+    a->S = best_S; a->S_log2 = best_log;
+    a->ppw = 64u / best_S;
+    a->upb = (uint32_t)upb; a->upb_log2 = upb_log;
+    a->nb = (uint32_t)L.nb;
+    *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
+    return true;
+}
+
+// 1-D maps the register kernel would take as well: compress_line is the faster one for 2-byte
+// elements (it loads 16 bytes per lane, the register kernel 8); for fp32 the register kernel is (by 5-10 %)
+bool line_first(const Layout& L, size_t es) { return es == 2 || L.HW / 4 < 512; }
 
 // Hs = rows of one depth slice, D = depth slices (1 for a 2-D map).
 bool plan_rows(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, int b, size_t es, const void* x,
@@ -3055,10 +3189,12 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         size_t lds = 0;
         uint32_t grid = 0;
         int vec = 1, nt = 64, nw = 1;
-        enum { REGS, LANE, ITEMS, WAVE, TILE, ONE, ROWS, PLANE, ANY } kind;
+        enum { REGS, LANE, LINE, ITEMS, WAVE, TILE, ONE, ROWS, PLANE, ANY } kind;
         const bool flat = D == 1;               // the register, item, wavefront and tile kernels take 2-D maps
-        if (flat && plan_regs(L, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
+        if (line_first(L, es) && plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
+        else if (flat && plan_regs(L, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
         else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
+        else if (plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
         else if (flat && plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
         else if (flat && plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
             kind = WAVE; wa.tab = tab; wa.rg = rg;
@@ -3084,6 +3220,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
                 case TILE: return launch_tile<T, BITS>(B, vec, a, gd, lds, st);
                 case LANE: hipLaunchKernelGGL((compress_lane<T, BITS>), gd, dim3(64), lds, st, la); return hipGetLastError();
                 case ONE: hipLaunchKernelGGL((compress_one<T, BITS>), gd, dim3(64), 0, st, oa); return hipGetLastError();
+                case LINE: hipLaunchKernelGGL((compress_line<T, BITS>), gd, dim3(64), 0, st, oa); return hipGetLastError();
                 case ROWS: {
                     void (*kern)(RowsArgs) = flat ? compress_rows<T, BITS> : compress_rows_3d<T, BITS>;
                     const hipError_t e = allow_large_lds(kern, lds);
@@ -3174,10 +3311,14 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     int n;
     if (direction == 0) {
         TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; OneArgs oa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
-        if (flat && plan_regs(L, H, W, B, es, data, &ra, &grid, &lds, &nw))
+        if (line_first(L, es) && plan_line(L, D, H, B, es, data, &oa, &grid))
+            n = snprintf(out, cap, "compress_line<%s, %d>", tn, b);
+        else if (flat && plan_regs(L, H, W, B, es, data, &ra, &grid, &lds, &nw))
             n = snprintf(out, cap, "compress_regs<%s, %d, %d, %d>", tn, b, (B == 4 || B == 8) ? B : 0, nw);
         else if (plan_lane(L, es, data, &la, &grid, &lds))
             n = snprintf(out, cap, "compress_lane<%s, %d>", tn, b);
+        else if (plan_line(L, D, H, B, es, data, &oa, &grid))
+            n = snprintf(out, cap, "compress_line<%s, %d>", tn, b);
         else if (flat && plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_items<%s, %d, %d, %d, %d>", tn, b, B, vec, H == 1 ? 1 : B);
         else if (flat && plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))

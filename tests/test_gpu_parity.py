@@ -619,6 +619,29 @@ def test_one_block_kernel_matches_oracle(shape, B, b, mode):
     _check_variant(shape, B, b, mode)
 
 
+# 1-D maps (Appendix D; the maps of linear and transformer layers): the register kernel for one row
+LINE_CASES = [
+    ((32, 16, 1, 768), 8, 4),           # hidden size 768, the B = 8 / Q = 4 setting of the paper's language-model run
+    ((6, 50, 1, 96), 64, 2),            # two blocks of 64 and 32 elements
+    ((6, 50, 1, 96), 8, 2),
+    ((100, 1, 1, 128), 16, 2),          # 128 features, the B = 16 setting of the paper's MLP run
+    ((9, 7, 1, 196), 16, 8),            # 49 vectors, short last block
+    ((3, 4, 1, 1664), 32, 2),           # 416 vectors: 32 lanes x 13
+    ((5, 3, 1, 200), 8, 2),             # 50 vectors
+    ((70, 3, 1, 24), 4, 4),             # tiny planes: 6 vectors, 8 lanes per plane, ragged last wavefront
+    ((4, 4, 1, 1024), 64, 4),
+]
+
+
+@pytest.mark.parametrize("shape,B,b", LINE_CASES)
+@pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
+def test_one_row_kernel_matches_oracle(shape, B, b, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    if mode != "bf16" or (shape[3] % 8 == 0 and B % 8 == 0):
+        assert pkg.division_kernel_name(0, shape, B, b, dtype, c16=mode == "c16").startswith("compress_line<")
+    _check_variant(shape, B, b, mode)
+
+
 @pytest.mark.parametrize("shape,B,b", ROWS_CASES)
 @pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
 def test_general_block_size_kernel_matches_oracle(shape, B, b, mode):
