@@ -8,19 +8,28 @@
 // Compile with -ffp-contract=off: the codec's fp32 steps are single IEEE
 // operations (sub, mul, add), never fused, so that codes are reproducible.
 //
-// Work decomposition (one GPU; (sample, channel) planes are independent and every element of
-// x is read from HBM exactly once, no intermediate tensor touches HBM):
-//   compress_regs    planes of 2K-3K / 8K-13K elements (56x56, 112x112): one plane per workgroup
-//                    of one / four wavefronts, the plane stays in registers from load to codes
-//   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes): a lane per
-//                    pooling item, loaded straight from global memory, DPP reductions
+// Work decomposition (one GPU; (sample, channel) planes are independent; except in compress_plane
+// and compress_any every element of x is read from HBM exactly once, and no intermediate tensor
+// touches HBM).  The host picks the first kernel of this list that covers the shape:
+//   compress_line    1-D maps (one row) whose block is a power-of-two number of 16-byte vectors: planes
+//                    in registers, block sums by DPP (before compress_regs for 2-byte elements and
+//                    planes below 2048 elements, after it otherwise)
+//   compress_regs    planes of 2K-3K / 8K-13K elements (56x56, 112x112), B = 4, 8 (template) or 12, 16
+//                    (from the arguments): one plane per workgroup of one / four wavefronts, the
+//                    plane stays in registers from load to codes
 //   compress_lane    one-block planes with an odd element count (7x7): a lane per plane
-//   compress_wave    other planes up to 17 KB: one wavefront per chunk of planes staged in LDS
-//   compress_tile    other planes up to 156 KB: four wavefronts per chunk staged in LDS
-//   compress_rows    any block size (12, 16, 18, 64 of the paper's sweep), chunk staged in LDS
-//   compress_any     everything else (giant planes): slow
+//   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8: a lane
+//                    per pooling item, loaded straight from global memory, DPP reductions
+//   compress_wave    other planes up to 17 KB, B = 4, 8: one wavefront per chunk of planes staged in LDS
+//   compress_tile    other planes up to 156 KB, B = 4, 8: four wavefronts per chunk staged in LDS
+//   compress_one     planes that are a single block (B = 64 on 56x56 and below): flat vectors in registers
+//   compress_rows    any block size, 3-D maps: chunk staged in LDS, vectors kept in registers for Quant
+//   compress_plane   planes beyond LDS with vector rows and blocks (video volumes, image-sized maps):
+//                    a workgroup per plane, two vector passes over x
+//   compress_any     everything else (giant planes with odd extents): scalar, slow
 //   decompress_rowvec / _table / _flat / _lane / _scalar: streaming, the packed slice of a
-//                    workgroup staged in LDS, one 16-byte non-temporal store per four elements
+//                    workgroup staged in LDS, one 16-byte non-temporal store per lane step
+// The kernels with a _3d twin take N x C x D x H x W maps with B x B x B blocks (Appendix D).
 // Every kernel takes a table of up to 8 maps of one shape (blockIdx.y picks the map).
 // Element / cache types: float, bf16_t, f32c16_t (fp32 map, tuple cached as bfloat16).
 #include <hip/hip_runtime.h>
