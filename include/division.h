@@ -256,6 +256,39 @@ int division_decompress_3d(const void *packed, size_t packed_bytes, int64_t N, i
                            int64_t H, int64_t W, division_dtype dt, int B, int b, void *xhat,
                            void *hip_stream);
 
+/*
+ * A whole step in one call: the maps a forward (backward) pass caches (rebuilds), of any mix of
+ * shapes, element types, block sizes and code widths (Algorithm 1 loops over the layers; this
+ * call takes the loop's maps as an array of descriptors).  Map i gives exactly the bytes the
+ * single-map call with its fields gives.  Maps that agree in (N, C, D, H, W, dt, B, b) are
+ * served together, up to 8 per kernel launch, in the order of their first appearance.
+ *
+ *   maps   HOST array of `count` descriptors, read during the call only.
+ *          x       device, the map (compress only; ignored by decompress)
+ *          packed  device, the cached tuple: written by compress (capacity
+ *                  packed_bytes), read by decompress (size packed_bytes)
+ *          xhat    device, the rebuilt map (decompress only; ignored by compress)
+ *          D       depth of a 3-D map, 1 for 2-D and 1-D maps
+ *          seed    stochastic-rounding stream of the map (compress only)
+ *
+ * All descriptors are checked before anything is launched; the first invalid one decides the
+ * error code.  count == 0 is a no-op; count < 0 or maps == NULL with count > 0 is DIVISION_EINVAL.
+ */
+typedef struct division_map {
+    const void *x;
+    void *packed;
+    void *xhat;
+    size_t packed_bytes;
+    int64_t N, C, D, H, W;
+    division_dtype dt;
+    int B, b;
+    uint64_t seed;
+} division_map;
+
+int division_compress_maps(int count, const division_map *maps, void *hip_stream);
+
+int division_decompress_maps(int count, const division_map *maps, void *hip_stream);
+
 /* division_kernel_name for the 3-D calls. */
 int division_kernel_name_3d(int direction, const void *data, int64_t N, int64_t C, int64_t D, int64_t H,
                             int64_t W, division_dtype dt, int B, int b, char *out, size_t cap);

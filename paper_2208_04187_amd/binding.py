@@ -66,6 +66,10 @@ def lib() -> ctypes.CDLL:
         L.division_maxpool_backward.argtypes = [vp, sz, vp, i64, i64, i64, i64, ci, ci, vp, vp]
         L.division_kernel_name.restype = ci
         L.division_kernel_name.argtypes = [ci, vp, i64, i64, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
+        L.division_compress_maps.restype = ci
+        L.division_compress_maps.argtypes = [ci, vp, vp]
+        L.division_decompress_maps.restype = ci
+        L.division_decompress_maps.argtypes = [ci, vp, vp]
         L.division_packed_bytes_3d.restype = sz
         L.division_packed_bytes_3d.argtypes = [i64, i64, i64, i64, i64, ci, ci, ci]
         L.division_packed_layout_3d.restype = ci
@@ -191,6 +195,75 @@ def division_kernel_name_3d(direction: int, shape, B: int, b: int, dtype=torch.f
     if rc:
         raise DivisionError(rc, "division_kernel_name_3d")
     return buf.value.decode()
+
+
+class _MapDesc(ctypes.Structure):
+    """division_map of include/division.h"""
+    _fields_ = [("x", ctypes.c_void_p), ("packed", ctypes.c_void_p), ("xhat", ctypes.c_void_p),
+                ("packed_bytes", ctypes.c_size_t),
+                ("N", ctypes.c_int64), ("C", ctypes.c_int64), ("D", ctypes.c_int64), ("H", ctypes.c_int64), ("W", ctypes.c_int64),
+                ("dt", ctypes.c_int), ("B", ctypes.c_int), ("b", ctypes.c_int), ("seed", ctypes.c_uint64)]
+
+
+def _dims5(shape):
+    """(N, C, D, H, W) of a 4-d (D = 1) or 5-d shape"""
+    if len(shape) == 4:
+        return shape[0], shape[1], 1, shape[2], shape[3]
+    if len(shape) == 5:
+        return tuple(shape)
+    raise ValueError("maps are 4-d (N, C, H, W) or 5-d (N, C, D, H, W)")
+
+
+def _per_map(v, n):
+    return list(v) if isinstance(v, (list, tuple)) else [v] * n
+
+
+def division_compress_maps(xs, B, b, seeds, packed=None, stream=None, c16: bool = False):
+    """One call for maps of any mix of shapes (the maps one forward pass caches).  xs: contiguous 4-d or
+    5-d device tensors; B, b: one value or one per map; seeds: one per map.  Returns the packed buffers."""
+    n = len(xs)
+    Bs, bs = _per_map(B, n), _per_map(b, n)
+    if len(seeds) != n or len(Bs) != n or len(bs) != n:
+        raise ValueError("one seed (and block size, code width) per map")
+    descs = (_MapDesc * max(n, 1))()
+    made = []
+    for i, x in enumerate(xs):
+        if not x.is_cuda or not x.is_contiguous():
+            raise ValueError("every map must be a contiguous device tensor")
+        N, C, D, H, W = _dims5(x.shape)
+        use16 = c16 and x.dtype == torch.float32
+        need = int(lib().division_packed_bytes_3d(N, C, D, H, W, Bs[i], bs[i], _dt(x.dtype, use16)))
+        if need == 0:
+            raise DivisionError(1, "division_packed_bytes_3d")
+        pk = packed[i] if packed is not None else torch.empty(need, dtype=torch.uint8, device=x.device)
+        made.append(pk)
+        descs[i] = _MapDesc(x.data_ptr(), pk.data_ptr(), None, pk.numel() * pk.element_size(), N, C, D, H, W,
+                            _dt(x.dtype, use16), Bs[i], bs[i], seeds[i] & (2 ** 64 - 1))
+    rc = lib().division_compress_maps(n, descs, _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_compress_maps")
+    return made
+
+
+def division_decompress_maps(packed, shapes, B, b, dtypes=torch.float32, out=None, stream=None, c16: bool = False):
+    """The reverse of division_compress_maps: rebuilds every map of a backward pass in one call."""
+    n = len(packed)
+    Bs, bs, dts = _per_map(B, n), _per_map(b, n), _per_map(dtypes, n)
+    if len(shapes) != n or len(Bs) != n or len(bs) != n or len(dts) != n:
+        raise ValueError("one shape (and block size, code width, dtype) per map")
+    descs = (_MapDesc * max(n, 1))()
+    made = []
+    for i, pk in enumerate(packed):
+        N, C, D, H, W = _dims5(shapes[i])
+        use16 = c16 and dts[i] == torch.float32
+        y = out[i] if out is not None else torch.empty(tuple(shapes[i]), dtype=dts[i], device=pk.device)
+        made.append(y)
+        descs[i] = _MapDesc(None, pk.data_ptr(), y.data_ptr(), pk.numel() * pk.element_size(), N, C, D, H, W,
+                            _dt(dts[i], use16), Bs[i], bs[i], 0)
+    rc = lib().division_decompress_maps(n, descs, _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_decompress_maps")
+    return made
 
 
 def _ptr_array(tensors):

@@ -38,6 +38,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 #include <type_traits>
+#include <vector>
 #include "../../include/division.h"
 
 namespace {
@@ -3417,6 +3418,57 @@ int division_decompress_3d(const void* packed, size_t packed_bytes, int64_t N, i
                            division_dtype dt, int B, int b, void* xhat, void* hip_stream) {
     if (!xhat || !packed) return DIVISION_EINVAL;
     return decompress_impl(1, &packed, &xhat, packed_bytes, N, C, D, H, W, dt, B, b, hip_stream);
+}
+
+// Both directions of the descriptor-array calls: validates every map, then serves the maps that
+// share a shape and parameters together, in order of first appearance.
+static int run_maps(int count, const division_map* maps, void* hip_stream, bool compress) {
+    if (count < 0 || (count > 0 && !maps)) return DIVISION_EINVAL;
+    for (int i = 0; i < count; ++i) {
+        const division_map& m = maps[i];
+        Layout L;
+        const int rc = make_layout(m.N, m.C, m.D, m.H, m.W, m.B, m.b, (int)m.dt, &L);
+        if (rc != DIVISION_OK) return rc;
+        if (!m.packed || (compress ? !m.x : !m.xhat)) return DIVISION_EINVAL;
+        if (m.packed_bytes < L.total) return DIVISION_ESIZE;
+        const size_t es = m.dt == DIVISION_BF16 ? 2 : 4;
+        const void* data = compress ? m.x : m.xhat;
+        if (((uintptr_t)data % es) != 0 || ((uintptr_t)m.packed % 16) != 0) return DIVISION_EALIGN;
+    }
+    auto same = [](const division_map& p, const division_map& q) {
+        return p.N == q.N && p.C == q.C && p.D == q.D && p.H == q.H && p.W == q.W && p.dt == q.dt && p.B == q.B && p.b == q.b;
+    };
+    std::vector<char> done((size_t)count, 0);
+    std::vector<const void*> in;
+    std::vector<void*> out;
+    std::vector<uint64_t> seeds;
+    for (int i = 0; i < count; ++i) {
+        if (done[(size_t)i]) continue;
+        in.clear(); out.clear(); seeds.clear();
+        size_t cap = ~(size_t)0;
+        for (int j = i; j < count; ++j) {
+            if (done[(size_t)j] || !same(maps[i], maps[j])) continue;
+            done[(size_t)j] = 1;
+            in.push_back(compress ? maps[j].x : maps[j].packed);
+            out.push_back(compress ? maps[j].packed : maps[j].xhat);
+            seeds.push_back(maps[j].seed);
+            if (maps[j].packed_bytes < cap) cap = maps[j].packed_bytes;
+        }
+        const division_map& m = maps[i];
+        const int rc = compress
+            ? compress_impl((int)in.size(), in.data(), out.data(), seeds.data(), m.N, m.C, m.D, m.H, m.W, m.dt, m.B, m.b, cap, hip_stream)
+            : decompress_impl((int)in.size(), in.data(), out.data(), cap, m.N, m.C, m.D, m.H, m.W, m.dt, m.B, m.b, hip_stream);
+        if (rc != DIVISION_OK) return rc;
+    }
+    return DIVISION_OK;
+}
+
+int division_compress_maps(int count, const division_map* maps, void* hip_stream) {
+    return run_maps(count, maps, hip_stream, true);
+}
+
+int division_decompress_maps(int count, const division_map* maps, void* hip_stream) {
+    return run_maps(count, maps, hip_stream, false);
 }
 
 int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, int64_t H, int64_t W,

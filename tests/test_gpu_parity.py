@@ -399,6 +399,31 @@ def test_block_mean_on_rounding_midpoints():
     assert st["exact"]
 
 
+def test_descriptor_array_calls_serve_a_mixed_step():
+    """Maps of different shapes, dimensionalities, types and parameters in one call each way; every map
+    must come out exactly as its single-map call gives it (and as the oracle does)."""
+    g = torch.Generator().manual_seed(4242)
+    specs = [((2, 8, 56, 56), 8, 2, torch.float32), ((2, 16, 28, 28), 8, 2, torch.float32), ((2, 8, 56, 56), 8, 2, torch.float32),
+             ((3, 5, 14, 14), 8, 4, torch.bfloat16), ((2, 3, 4, 12, 12), 4, 2, torch.float32), ((2, 16, 28, 28), 8, 2, torch.float32),
+             ((4, 6, 1, 768), 8, 4, torch.float32), ((2, 8, 56, 56), 12, 2, torch.float32), ((2, 9, 7, 7), 8, 2, torch.float32),
+             ((2, 16, 28, 28), 8, 2, torch.float32)] + [((2, 8, 56, 56), 8, 2, torch.float32)] * 9     # 11 maps of one shape: two launches
+    xs = [torch.relu(torch.randn(sh, generator=g)).to(dt).to("cuda:0") for sh, _, _, dt in specs]
+    Bs, bs = [s[1] for s in specs], [s[2] for s in specs]
+    seeds = [1000 + 7 * i for i in range(len(specs))]
+    pks = pkg.division_compress_maps(xs, Bs, bs, seeds)
+    ys = pkg.division_decompress_maps(pks, [s[0] for s in specs], Bs, bs, [s[3] for s in specs])
+    torch.cuda.synchronize()
+    for i, (sh, B, b, dt) in enumerate(specs):
+        xh, odt = to_host_array(xs[i].cpu())
+        ref = oracle.compress(xh, B, b, seeds[i], odt)
+        assert np.array_equal(pks[i].cpu().numpy(), ref), (i, sh)
+        yh, _ = to_host_array(ys[i].cpu())
+        assert np.array_equal(yh, oracle.decompress(ref, sh, B, b, odt)), (i, sh)
+    assert pkg.division_compress_maps([], 8, 2, []) == []
+    with pytest.raises(pkg.DivisionError):
+        pkg.division_compress_maps(xs[:2], [8, 8], [2, 3], [1, 2])
+
+
 # ---------------------------------------------------------------- Algorithm 1 through autograd
 
 @pytest.mark.parametrize("c16", [False, True])

@@ -90,6 +90,33 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.division_decompress_batch(2, pk, vp2(addr16, addr16 + 2), 1024, 1, 1, 4, 4, 0, 2, 2, None) == 3
 
 
+def test_descriptor_array_calls_check_every_map_before_any_launch():
+    from paper_2208_04187_amd.binding import _MapDesc
+    L = pkg.lib()
+    buf = ctypes.create_string_buffer(8192)
+    a = (ctypes.addressof(buf) + 15) & ~15
+    good = dict(x=a, packed=a + 1024, xhat=a + 2048, packed_bytes=1024, N=1, C=1, D=1, H=4, W=4, dt=0, B=2, b=2, seed=3)
+
+    def call(fn, *over):
+        descs = (_MapDesc * len(over))(*[_MapDesc(**{**good, **o}) for o in over])
+        return fn(len(over), descs, None)
+
+    assert L.division_compress_maps(0, None, None) == 0
+    assert L.division_compress_maps(2, None, None) == 1
+    assert L.division_compress_maps(-1, None, None) == 1
+    # the second map is invalid: nothing is launched (no HIP call is made on this GPU-less host)
+    assert call(L.division_compress_maps, {}, {"x": None}) == 1
+    assert call(L.division_compress_maps, {}, {"b": 3}) == 1
+    assert call(L.division_compress_maps, {}, {"D": 0}) == 1
+    assert call(L.division_compress_maps, {}, {"packed_bytes": 16}) == 2
+    assert call(L.division_compress_maps, {}, {"packed": a + 1025}) == 3
+    assert call(L.division_compress_maps, {}, {"N": 2 ** 20, "C": 2 ** 20}) == 4
+    assert call(L.division_decompress_maps, {}, {"xhat": None}) == 1
+    assert call(L.division_decompress_maps, {}, {"x": None, "xhat": a + 2050}) == 3
+    assert call(L.division_decompress_maps, {}, {"packed_bytes": 8}) == 2
+    assert ctypes.sizeof(_MapDesc) == 96          # the C struct: 3 pointers, size_t, 5 x int64, 3 x int (+ pad), uint64
+
+
 def test_mask_bytes_and_host_side_errors():
     L = pkg.lib()
     for n in (0, 1, 31, 32, 33, 1 << 20, (1 << 31) + 5):
