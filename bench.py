@@ -154,6 +154,21 @@ def masks(args, torch, pkg, dev) -> int:
         ops["maxpool_forward_k2"] = (lambda i: pkg.division_maxpool_forward(xs[i % nsets], 2), n * es + n * es / 4 + n / 8)
         ops["maxpool_backward_k2"] = (lambda i: pkg.division_maxpool_backward(pooled[i % nsets][1], pooled[i % nsets][0],
                                                                              tuple(x.shape), 2), n * es + n * es / 4 + n / 8)
+    if x.dim() == 4 and es == 4:
+        # Relu followed by the compression of its output (the conv-BN-Relu block of Theorem 3): two kernels
+        # against the fused one; algorithmic bytes = x in, y out, mask, packed (+ y in again when unfused)
+        sp_B, sp_b = 8, 2
+        pkb = pkg.division_packed_bytes(*x.shape, sp_B, sp_b)
+        pks = [torch.empty(pkb, dtype=torch.uint8, device=dev) for _ in xs]
+
+        def two(i):
+            pkg.division_relu_forward(xs[i % nsets], out=ys[i % nsets], mask=ms[i % nsets])
+            pkg.division_compress(ys[i % nsets], sp_B, sp_b, i, packed=pks[i % nsets])
+
+        ops["relu_then_compress_two_kernels"] = (two, 3 * n * es + n / 8 + pkb)
+        ops["relu_compress_fused" if pkg.division_relu_compress_fused(tuple(x.shape), sp_B, sp_b) else "relu_compress_unfused_shape"] = (
+            lambda i: pkg.division_relu_compress(xs[i % nsets], sp_B, sp_b, i, out=ys[i % nsets], mask=ms[i % nsets],
+                                                 packed=pks[i % nsets]), 2 * n * es + n / 8 + pkb)
     res = {}
     for name, (fn, nbytes) in ops.items():
         med, mn = timed_us(fn)

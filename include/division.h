@@ -257,6 +257,24 @@ int division_decompress_3d(const void *packed, size_t packed_bytes, int64_t N, i
                            void *hip_stream);
 
 /*
+ * The Relu operator fused with the compression of its output (a conv-BN-Relu block caches the
+ * Relu's 1-bit mask for the Relu's own backward pass and the Relu's output, compressed, for the
+ * next layer's: Appendix, Relu listing, and Sec. 4.1).  Equivalent to division_relu_forward(x -> y,
+ * mask) followed by division_compress(y -> packed), with the same outputs bit for bit; for the
+ * large maps (those division_relu_compress_fused reports: planes of 2048-3328 or 8192-13312
+ * elements in whole 32-element mask words, B = 4 or 8, 16-byte aligned x and y) one kernel does
+ * both and y does not travel through HBM a second time.  Other shapes run the two kernels one
+ * after the other.  y may be x itself (in place); arguments as for the two calls it replaces.
+ */
+int division_relu_compress(const void *x, int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
+                           int B, int b, uint64_t seed, void *y, void *mask, size_t mask_capacity,
+                           void *packed, size_t packed_capacity, void *hip_stream);
+
+/* 1 when division_relu_compress runs as one kernel for this shape (aligned pointers assumed), else 0
+ * (host-only). */
+int division_relu_compress_fused(int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt, int B, int b);
+
+/*
  * A whole step in one call: the maps a forward (backward) pass caches (rebuilds), of any mix of
  * shapes, element types, block sizes and code widths (Algorithm 1 loops over the layers; this
  * call takes the loop's maps as an array of descriptors).  Map i gives exactly the bytes the

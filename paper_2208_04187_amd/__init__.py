@@ -12,3 +12,4 @@ from .binding import division_maxpool_backward, division_maxpool_forward  # noqa
 from .binding import (division_compress_3d, division_decompress_3d, division_kernel_name_3d,  # noqa: F401,E402
                       division_packed_bytes_3d, division_packed_layout_3d)
 from .binding import division_compress_maps, division_decompress_maps  # noqa: F401,E402
+from .binding import division_relu_compress, division_relu_compress_fused  # noqa: F401,E402

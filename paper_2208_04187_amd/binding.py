@@ -66,6 +66,10 @@ def lib() -> ctypes.CDLL:
         L.division_maxpool_backward.argtypes = [vp, sz, vp, i64, i64, i64, i64, ci, ci, vp, vp]
         L.division_kernel_name.restype = ci
         L.division_kernel_name.argtypes = [ci, vp, i64, i64, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
+        L.division_relu_compress.restype = ci
+        L.division_relu_compress.argtypes = [vp, i64, i64, i64, i64, ci, ci, ci, u64, vp, vp, sz, vp, sz, vp]
+        L.division_relu_compress_fused.restype = ci
+        L.division_relu_compress_fused.argtypes = [i64, i64, i64, i64, ci, ci, ci]
         L.division_compress_maps.restype = ci
         L.division_compress_maps.argtypes = [ci, vp, vp]
         L.division_decompress_maps.restype = ci
@@ -356,6 +360,37 @@ def division_relu_forward(x: torch.Tensor, out: torch.Tensor | None = None, mask
     if rc:
         raise DivisionError(rc, "division_relu_forward")
     return out, mask
+
+
+def division_relu_compress(x: torch.Tensor, B: int, b: int, seed: int, out: torch.Tensor | None = None,
+                           mask: torch.Tensor | None = None, packed: torch.Tensor | None = None, stream=None,
+                           c16: bool = False):
+    """Relu and the compression of its output in one call (one kernel for the large maps).
+    Returns (y, mask, packed)."""
+    if x.dim() != 4 or not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous 4-d device tensor")
+    N, C, H, W = x.shape
+    n = x.numel()
+    if out is None:
+        out = torch.empty_like(x)
+    if mask is None:
+        mask = torch.empty(division_mask_bytes(n) // 4, dtype=torch.int32, device=x.device)
+    if packed is None:
+        need = division_packed_bytes(N, C, H, W, B, b, x.dtype, c16)
+        if need == 0:
+            raise DivisionError(1, "division_packed_bytes")
+        packed = torch.empty(need, dtype=torch.uint8, device=x.device)
+    rc = lib().division_relu_compress(x.data_ptr(), N, C, H, W, _dt(x.dtype, c16), B, b, seed & (2 ** 64 - 1),
+                                      out.data_ptr(), mask.data_ptr(), mask.numel() * mask.element_size(),
+                                      packed.data_ptr(), packed.numel() * packed.element_size(), _stream(stream))
+    if rc:
+        raise DivisionError(rc, "division_relu_compress")
+    return out, mask, packed
+
+
+def division_relu_compress_fused(shape, B: int, b: int, dtype=torch.float32, c16: bool = False) -> bool:
+    N, C, H, W = shape
+    return bool(lib().division_relu_compress_fused(N, C, H, W, _dt(dtype, c16), B, b))
 
 
 def division_dropout_forward(x: torch.Tensor, p: float, seed: int, out: torch.Tensor | None = None,

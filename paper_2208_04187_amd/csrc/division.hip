@@ -1181,6 +1181,8 @@ struct RegsArgs {
     uint32_t ppw;        // planes a workgroup handles one after the other
     uint32_t B;          // block size, read by the instance for any B (template argument 0) only
     FastDiv d_w4, d_LW, d_B, d_upb;      // d_upb divides by B / 4
+    void* y;             // relu_compress_regs: the activation's output map and its 1-bit mask (one map per launch)
+    uint32_t* mask;
 };
 
 constexpr int kRegUnits = 13;     // units per lane: planes of up to 13 * (threads per workgroup) units
@@ -1196,8 +1198,12 @@ constexpr int kRegUnits = 13;     // units per lane: planes of up to 13 * (threa
 // sweep): the block size comes from the arguments, the loops over a block's unit sums run to
 // their bounds instead of being unrolled, and rounds of units past the plane are skipped, so
 // that planes far below 13 units per lane are worth taking too.
-template <typename T, int BITS, int B, int NW>
-__global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
+// RELU: x is the input of a Relu operator (Appendix, Relu listing) whose output y is the map to
+// cache: y = x where x > 0 else +0 is written out, its 1-bit mask too (H*W a multiple of 32: a
+// plane's mask is whole words, a word is the eight units of eight neighbouring lanes), and y is
+// what gets compressed, without a second trip through HBM.
+template <typename T, int BITS, int B, int NW, bool RELU>
+__device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
     constexpr int NT = 64 * NW;
     constexpr int K = kRegUnits;
     constexpr int UPB = B / 4;            // units per block row
@@ -1251,6 +1257,42 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
                     x[k][0] = __uint_as_float(q.x << 16); x[k][1] = __uint_as_float(q.x & 0xffff0000u);
                     x[k][2] = __uint_as_float(q.y << 16); x[k][3] = __uint_as_float(q.y & 0xffff0000u);
                 }
+            }
+        }
+        if constexpr (RELU) {
+            T* ydst = static_cast<T*>(a.y) + (size_t)p * a.HW;
+            const __amdgpu_buffer_rsrc_t yrs =
+                __builtin_amdgcn_make_buffer_rsrc(ydst, 0, (int)(a.HW * sizeof(T)), 0x00020000);
+            const __amdgpu_buffer_rsrc_t mrs =
+                __builtin_amdgcn_make_buffer_rsrc(a.mask + (size_t)p * (a.HW / 32), 0, (int)(a.HW / 8), 0x00020000);
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                if (!round_live(k)) continue;
+                uint32_t nib = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool pos = x[k][e] > 0.0f;
+                    nib |= (pos ? 1u : 0u) << e;
+                    x[k][e] = pos ? x[k][e] : 0.0f;
+                }
+                // stores past the plane are dropped by the buffer bound
+                if constexpr (sizeof(T) == 4) {
+                    u32x4 o;
+                    o.x = __float_as_uint(x[k][0]); o.y = __float_as_uint(x[k][1]);
+                    o.z = __float_as_uint(x[k][2]); o.w = __float_as_uint(x[k][3]);
+                    __builtin_amdgcn_raw_buffer_store_b128(o, yrs, tid * 16u, k * NT * 16, 0);
+                } else {
+                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                    u32x2 o;
+                    o.x = (__float_as_uint(x[k][0]) >> 16) | (__float_as_uint(x[k][1]) & 0xffff0000u);
+                    o.y = (__float_as_uint(x[k][2]) >> 16) | (__float_as_uint(x[k][3]) & 0xffff0000u);
+                    __builtin_amdgcn_raw_buffer_store_b64(o, yrs, tid * 8u, k * NT * 8, 0);
+                }
+                uint32_t w = nib << (4u * (tid & 7u));
+                w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppXor1, 0xf, 0xf, false);
+                w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppXor2, 0xf, 0xf, false);
+                w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppHalfMirror, 0xf, 0xf, false);
+                if ((tid & 7u) == 0) __builtin_amdgcn_raw_buffer_store_b32(w, mrs, (tid >> 3) * 4u, k * (NT / 8) * 4, 0);
             }
         }
         // ---- Sec. 4.1 AveragePooling, step 1: one binary64 sum per unit
@@ -1368,6 +1410,11 @@ __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
         if constexpr (NW == 1) wave_sync(); else lds_barrier();      // usum, lfcs and red are reused
     }
 }
+
+template <typename T, int BITS, int B, int NW>
+__global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) { compress_regs_body<T, BITS, B, NW, false>(a); }
+template <typename T, int BITS, int B, int NW>
+__global__ void __launch_bounds__(64 * NW) relu_compress_regs(RegsArgs a) { compress_regs_body<T, BITS, B, NW, true>(a); }
 
 // the elements of one 16-byte vector of x as fp32
 template <typename T>
@@ -3418,6 +3465,62 @@ int division_decompress_3d(const void* packed, size_t packed_bytes, int64_t N, i
                            division_dtype dt, int B, int b, void* xhat, void* hip_stream) {
     if (!xhat || !packed) return DIVISION_EINVAL;
     return decompress_impl(1, &packed, &xhat, packed_bytes, N, C, D, H, W, dt, B, b, hip_stream);
+}
+
+int division_relu_compress(const void* x, int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
+                           int B, int b, uint64_t seed, void* y, void* mask, size_t mask_capacity,
+                           void* packed, size_t packed_capacity, void* hip_stream) {
+    if (!x || !y || !mask || !packed) return DIVISION_EINVAL;
+    Layout L;
+    const int rc = make_layout(N, C, 1, H, W, B, b, (int)dt, &L);
+    if (rc != DIVISION_OK) return rc;
+    const size_t es = dt == DIVISION_BF16 ? 2 : 4;
+    const int64_t n = (int64_t)(L.P * L.HW);
+    if (mask_capacity < division_mask_bytes(n) || packed_capacity < L.total) return DIVISION_ESIZE;
+    if (((uintptr_t)x % es) != 0 || ((uintptr_t)y % es) != 0 || ((uintptr_t)mask % 4) != 0 || ((uintptr_t)packed % 16) != 0)
+        return DIVISION_EALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    // fused: the planes the register kernel takes, when a plane's mask is whole words
+    RegsArgs ra{};
+    uint32_t grid = 0;
+    size_t lds = 0;
+    int nw = 1;
+    const void* both = reinterpret_cast<const void*>((uintptr_t)x | (uintptr_t)y);
+    if (L.HW % 32 == 0 && (B == 4 || B == 8) && plan_regs(L, H, W, B, es, both, &ra, &grid, &lds, &nw)) {
+        ra.tab.x[0] = x;
+        ra.tab.pk[0] = packed;
+        ra.tab.seed_a[0] = mix32((uint32_t)(seed & 0xffffffffu) ^ 0x243F6A88u);
+        ra.tab.seed_c[0] = mix32((uint32_t)(seed >> 32) ^ 0x85A308D3u);
+        ra.rg = make_regions(L);
+        ra.y = y;
+        ra.mask = static_cast<uint32_t*>(mask);
+        const hipError_t err = with_type_bits(dt, b, [&](auto tag, auto bits) -> hipError_t {
+            using T = decltype(tag);
+            constexpr int BITS = decltype(bits)::value;
+            void (*kern)(RegsArgs);
+            if (nw == 1) kern = B == 8 ? relu_compress_regs<T, BITS, 8, 1> : relu_compress_regs<T, BITS, 4, 1>;
+            else kern = B == 8 ? relu_compress_regs<T, BITS, 8, 4> : relu_compress_regs<T, BITS, 4, 4>;
+            hipLaunchKernelGGL(kern, dim3(grid, 1), dim3(64 * nw), lds, st, ra);
+            return hipGetLastError();
+        });
+        return err == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
+    }
+    // other shapes: the operator, then the codec on its output
+    const int r1 = division_relu_forward(x, n, dt == DIVISION_F32_C16 ? DIVISION_F32 : dt, y, mask, mask_capacity, hip_stream);
+    if (r1 != DIVISION_OK) return r1;
+    const void* yin = y;
+    return compress_impl(1, &yin, &packed, &seed, N, C, 1, H, W, dt, B, b, packed_capacity, hip_stream);
+}
+
+int division_relu_compress_fused(int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt, int B, int b) {
+    Layout L;
+    if (make_layout(N, C, 1, H, W, B, b, (int)dt, &L) != DIVISION_OK) return 0;
+    RegsArgs ra{};
+    uint32_t grid = 0;
+    size_t lds = 0;
+    int nw = 1;
+    return L.HW % 32 == 0 && (B == 4 || B == 8) &&
+           plan_regs(L, H, W, B, dt == DIVISION_BF16 ? 2 : 4, reinterpret_cast<const void*>((uintptr_t)16), &ra, &grid, &lds, &nw);
 }
 
 // Both directions of the descriptor-array calls: validates every map, then serves the maps that

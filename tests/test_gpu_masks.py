@@ -123,3 +123,46 @@ def test_maxpool_matches_oracle(shape, k, dtype):
     gin = pkg.division_maxpool_backward(m, go.to("cuda:0"), shape, k)
     torch.cuda.synchronize()
     assert _same_bits(gin, oracle.maxpool_backward(m_ref, gh, shape, k, dt))
+
+
+# ---------------------------------------------------------------- Relu fused with the compression of its output
+
+@pytest.mark.parametrize("shape,B,b,fused", [
+    ((3, 5, 56, 56), 8, 2, True),        # one wavefront per plane
+    ((2, 3, 112, 112), 8, 4, True),      # four wavefronts per plane
+    ((2, 4, 48, 48), 4, 8, True),        # B = 4, 2304 elements
+    ((3, 4, 64, 32), 8, 2, True),        # 2048 elements
+    ((2, 3, 50, 44), 8, 2, False),       # 2200 elements: not whole mask words per plane -> two kernels
+    ((4, 7, 28, 28), 8, 2, False),       # small planes -> two kernels
+    ((2, 3, 56, 56), 12, 2, False),      # block size outside the fused instances
+    ((5, 9, 7, 7), 8, 4, False),
+])
+@pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
+def test_relu_fused_with_compression_matches_relu_then_compress(shape, B, b, fused, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    c16 = mode == "c16"
+    dt = oracle.F32_C16 if c16 else (oracle.BF16 if mode == "bf16" else oracle.F32)
+    rdt = oracle.BF16 if mode == "bf16" else oracle.F32
+    assert pkg.division_relu_compress_fused(shape, B, b, dtype, c16) == fused
+    g = torch.Generator().manual_seed(sum(shape) + B)
+    x = (torch.randn(shape, generator=g) * 1.5).to(dtype)
+    x[0, 0, 0, :4] = torch.tensor([0.0, -0.0, float("nan"), -1e-30]).to(dtype)
+    xh = x.view(torch.int16).numpy().view(np.uint16) if mode == "bf16" else x.numpy()
+    y_ref, m_ref = oracle.relu_forward(xh, rdt)
+    seed = 0xFE11 + B
+    p_ref = oracle.compress(y_ref.reshape(shape), B, b, seed, dt)
+    xd = x.to("cuda:0")
+    y, m, pk = pkg.division_relu_compress(xd, B, b, seed, c16=c16)
+    torch.cuda.synchronize()
+    yh = y.cpu().view(torch.int16).numpy().view(np.uint16) if mode == "bf16" else y.cpu().numpy()
+    assert np.array_equal(yh.view(np.uint16 if mode == "bf16" else np.uint32), y_ref.reshape(shape).view(np.uint16 if mode == "bf16" else np.uint32))
+    assert np.array_equal(m.cpu().numpy().view(np.uint32), m_ref)
+    assert np.array_equal(pk.cpu().numpy(), p_ref)
+    # in place, and the same bytes as the two separate calls
+    x2 = xd.clone()
+    y2, m2, pk2 = pkg.division_relu_compress(x2, B, b, seed, out=x2, c16=c16)
+    y3, m3 = pkg.division_relu_forward(xd)
+    pk3 = pkg.division_compress(y3, B, b, seed, c16=c16)
+    torch.cuda.synchronize()
+    assert torch.equal(pk2, pk) and torch.equal(m2, m) and torch.equal(pk3, pk) and torch.equal(m3, m)
+    assert torch.equal(x2.view(torch.int16 if mode == "bf16" else torch.int32), y.view(torch.int16 if mode == "bf16" else torch.int32))
