@@ -674,7 +674,8 @@ def test_general_block_size_kernel_matches_oracle(shape, B, b, mode):
     c16 = mode == "c16"
     name = pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16)
     # block sizes 12 and 16 on planes of whole 4-element units take the register kernel's any-B instance
-    assert name.startswith("compress_rows<") or (name.startswith("compress_regs<") and ", 0, " in name)
+    # (1-D maps with power-of-two blocks the one-row kernel)
+    assert name.startswith(("compress_rows<", "compress_line<")) or (name.startswith("compress_regs<") and ", 0, " in name)
     _check_variant(shape, B, b, mode)
 
 
@@ -699,7 +700,8 @@ REGS_ANY_CASES = [
 def test_register_kernel_any_block_size_matches_oracle(shape, B, b, mode):
     dtype = torch.bfloat16 if mode == "bf16" else torch.float32
     name = pkg.division_kernel_name(0, shape, B, b, dtype, c16=mode == "c16")
-    assert name.startswith("compress_regs<") and ", 0, " in name
+    one_row_bf16 = shape[2] == 1 and mode == "bf16"            # 2-byte 1-D maps go to the one-row kernel first
+    assert (name.startswith("compress_regs<") and ", 0, " in name) or (one_row_bf16 and name.startswith("compress_line<"))
     _check_variant(shape, B, b, mode)
 
 
