@@ -3097,6 +3097,26 @@ size_t dec_lds_bytes(const Layout& L, size_t es, uint64_t G) {
 }
 constexpr size_t kDecLdsMax = 60u << 10;
 
+// Planes per workgroup of the streaming decompress kernels: about 32 KB of output, in whole 128-byte
+// lines where that is possible within twice the target, so that no line is shared by two
+// workgroups.  Measured inside a whole compress + decompress step over the ResNet-50 set: 24-48 KB
+// is the flat optimum (64 KB: 0.5-1 % slower, 12 KB: 4 % slower, 6 KB: 12 %).  A decompress kernel
+// timed on its own, launch after launch, prefers 12 KB by 15 %, but not between other kernels.
+// `mult`: G must be a multiple of it (flat kernel: whole 4-element vectors).
+constexpr uint64_t kDecChunkBytes = 32768;
+uint64_t dec_planes(const Layout& L, size_t es, uint64_t mult) {
+    const uint64_t target = kDecChunkBytes / es;
+    uint64_t G = (target + L.HW / 2) / L.HW;
+    if (G < 1) G = 1;
+    uint64_t unit = 128 / gcd_u64(128, L.HW * es);
+    unit = unit / gcd_u64(unit, mult) * mult;
+    if (unit * L.HW > 2 * target) unit = mult;
+    G = (G + unit / 2) / unit * unit;
+    if (G < unit) G = unit;
+    if (G > L.P) G = L.P;
+    return G;
+}
+
 // Hs = rows of one depth slice, D = depth slices (1 for a 2-D map; the table kernel takes 2-D maps only).
 int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, size_t es, const void* xhat,
                     DecArgs* a, uint32_t* grid) {
@@ -3111,7 +3131,6 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
     const bool small_idx = fastdiv_ok((uint64_t)H, (uint64_t)B) && fastdiv_ok((uint64_t)W, (uint64_t)B) &&
                            fastdiv_ok((uint64_t)H, (uint64_t)Hs);
     const bool out_vec_aligned = ((uintptr_t)xhat % (4 * es)) == 0;
-    const uint64_t target = 16ull * 4 * kThreads;      // elements per workgroup
     // one-block planes with an odd element count: a lane per plane, 64 planes per round
     if (lane_shape(L)) {
         const uint32_t nrounds = (uint32_t)((L.P + 63) / 64);
@@ -3125,8 +3144,7 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
     if (W % 4 == 0 && B % 4 == 0 && small_idx && out_vec_aligned) {
         a->q4 = (uint32_t)(L.HW / 4);
         a->w4 = (uint32_t)(W / 4);
-        uint64_t G = (target / 4 + a->q4 - 1) / a->q4;
-        if (G > L.P) G = L.P;
+        uint64_t G = dec_planes(L, es, 1);
         while (G > 1 && !fastdiv_ok(G * a->q4 + kThreads, a->q4)) --G;
         if (fastdiv_ok(G * a->q4 + kThreads, a->q4) && fastdiv_ok(a->q4, a->w4) && dec_lds_bytes(L, es, G) <= kDecLdsMax) {
             a->G = (uint32_t)G;
@@ -3140,8 +3158,7 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
     // planes of whole vectors with few blocks: LFC indices from a table in LDS
     if (D == 1 && L.HW % 4 == 0 && L.nb > 1 && L.nb <= 255 && small_idx && out_vec_aligned && fastdiv_ok(L.HW, (uint64_t)W)) {
         a->q4 = (uint32_t)(L.HW / 4);
-        uint64_t G = (target / 4 + a->q4 - 1) / a->q4;
-        if (G > L.P) G = L.P;
+        uint64_t G = dec_planes(L, es, 1);
         while (G > 1 && !fastdiv_ok(G * a->q4 + kThreads, a->q4)) --G;
         if (fastdiv_ok(G * a->q4 + kThreads, a->q4) && dec_lds_bytes(L, es, G) + 4ull * a->q4 + 16 <= kDecLdsMax) {
             a->G = (uint32_t)G;
@@ -3153,9 +3170,7 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
     // general path: flat run of G planes, G*HW a multiple of 4
     if (small_idx && out_vec_aligned && fastdiv_ok(L.HW, (uint64_t)W)) {
         const uint64_t unit = 4 / gcd_u64(4, L.HW);
-        uint64_t G = (target + L.HW - 1) / L.HW;
-        G = (G + unit - 1) / unit * unit;
-        if (G > L.P) G = L.P;
+        const uint64_t G = dec_planes(L, es, unit);
         if (fastdiv_ok(G * L.HW + 4ull * kThreads, L.HW) && dec_lds_bytes(L, es, G) <= kDecLdsMax) {
             a->G = (uint32_t)G;
             *grid = (uint32_t)((L.P + G - 1) / G);
