@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # benchmark (each counter scaled by what it reads for a plain 1 GiB copy: x2.000
 # and x1.000), averaged over the kernel's launches in one step of the default
 # workload; profiles/bench_resnet50_set_hbm_traffic.md has the figures.
-MEASURED_TRAFFIC_BYTES = {"decompress_rowvec<float, 2>": 448.3e6}
+MEASURED_TRAFFIC_BYTES = {"decompress_rowvec<float, 2>": 447.8e6}
 
 WORKLOAD_NAMES = {
     0: "single 2x16x32x32 fp32 tensor, B=8 b=2 (configs[0])",
