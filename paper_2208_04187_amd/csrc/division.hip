@@ -27,8 +27,9 @@
 //   compress_plane   planes beyond LDS with vector rows and blocks (video volumes, image-sized maps):
 //                    a workgroup per plane, two vector passes over x
 //   compress_any     everything else (giant planes with odd extents): scalar, slow
-//   decompress_rowvec / _table / _flat / _lane / _scalar: streaming, the packed slice of a
-//                    workgroup staged in LDS, one 16-byte non-temporal store per lane step
+//   decompress_rowvec / _table / _words / _flat / _lane / _scalar: streaming, the packed slice of a
+//                    workgroup staged in LDS, one 16-byte non-temporal store per lane step (_words:
+//                    odd widths, the chunk rebuilt in LDS word by word first)
 // The kernels with a _3d twin take N x C x D x H x W maps with B x B x B blocks (Appendix D).
 // Every kernel takes a table of up to 8 maps of one shape (blockIdx.y picks the map).
 // Element / cache types: float, bf16_t, f32c16_t (fp32 map, tuple cached as bfloat16).
@@ -2251,7 +2252,8 @@ struct DecArgs {
     uint32_t w4;         // W / 4
     uint32_t Hs, LHs;    // 3-D maps: rows and block rows of one depth slice (H counts the rows of all slices)
     uint32_t pair8;      // 2-byte elements, W a multiple of 8, output 16-byte aligned: a lane step writes 8 elements
-    FastDiv d_q4, d_w4, d_B, d_W, d_HW, d_Hs;
+    uint32_t out_off;    // decompress_words: byte offset of the staged output in LDS
+    FastDiv d_q4, d_w4, d_B, d_W, d_HW, d_Hs, d_wpp;
 };
 
 // Index of the first block of the block row that holds row r; for a 3-D map (Appendix D,
@@ -2551,6 +2553,80 @@ template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) { decompress_flat_body<T, BITS, 2>(a); }
 template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) decompress_flat_3d(DecArgs a) { decompress_flat_body<T, BITS, 3>(a); }
+
+// Maps whose rows are not whole vectors (odd widths, odd plane sizes) with several blocks per
+// plane: the chunk of G planes is rebuilt in LDS first, a lane per packed word (the word's
+// elements lie in one plane; the lane walks them with a running row and column, starting at a
+// lane-dependent element so that the lanes of a wavefront write to different banks), then leaves
+// with aligned 16-byte stores like the other streaming kernels (G*HW is a multiple of 4 except in
+// the last chunk, whose ragged end is scalar).
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void decompress_words_body(const DecArgs& a) {
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
+    uint32_t* s_codes; float2* s_meta; T* s_lfc;
+    dec_lds<T>(a, s_codes, s_meta, s_lfc);
+    extern __shared__ float4 smem4[];
+    float* s_out = reinterpret_cast<float*>(reinterpret_cast<char*>(smem4) + a.out_off);
+    constexpr uint32_t CPW = 32 / BITS;
+    constexpr uint32_t Lq = (1u << BITS) - 1u;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t p0 = blockIdx.x * a.G;
+    const uint32_t Gc = min(a.G, a.P - p0);
+    stage_packed<T>(a, pt, p0, Gc, s_codes, s_meta, s_lfc, tid);      // ends with a barrier
+
+    // ---- Sec. 4.2 and the reconstruction equation, a packed word per lane and step
+    const uint32_t nwords = Gc * a.WPP;
+    const uint32_t rot = (tid / (64u / CPW)) & (CPW - 1u);           // lanes CPW floats apart share a bank
+    for (uint32_t wi = tid; wi < nwords; wi += kThreads) {
+        const uint32_t g = fdiv(wi, a.d_wpp);
+        const uint32_t k = wi - g * a.WPP;
+        const uint32_t word = s_codes[wi];
+        const float2 dd = s_meta[g];
+        const T* lp = s_lfc + g * a.nb;
+        float* op = s_out + g * a.HW;
+        const uint32_t i0 = k * CPW;
+        const uint32_t cnt = min(CPW, a.HW - i0);                   // elements of the plane in this word
+        // start at element `rot` of the word, go to its end, then from its first element up to rot
+        uint32_t e = rot;
+        uint32_t r = fdiv(i0 + e, a.d_W);
+        uint32_t c = i0 + e - r * a.W;
+        uint32_t rowoff = lfc_row<ND>(a, r);
+#pragma unroll
+        for (uint32_t step = 0; step < CPW; ++step) {
+            if (e < cnt) {
+                const float lfc = Elem<T>::load(lp, rowoff + fdiv(c, a.d_B));
+                op[i0 + e] = dequant((word >> (e * BITS)) & Lq, dd.y, dd.x, lfc);
+            }
+            ++e;
+            if (e == CPW) {                                          // wrap to the word's first element
+                e = 0;
+                r = fdiv(i0, a.d_W);
+                c = i0 - r * a.W;
+                rowoff = lfc_row<ND>(a, r);
+            } else if (++c == a.W) {
+                c = 0;
+                ++r;
+                rowoff = lfc_row<ND>(a, r);
+            }
+        }
+    }
+    lds_barrier();
+
+    // ---- out: 16-byte stores of the rebuilt chunk
+    const uint32_t n = Gc * a.HW;
+    T* out = static_cast<T*>(pt.xhat) + (size_t)p0 * a.HW;
+    const uint32_t nvec = n >> 2;
+    for (uint32_t v = tid; v < nvec; v += kThreads) {
+        const float4 o = reinterpret_cast<const float4*>(s_out)[v];
+        store4(out, (size_t)v * 4, o.x, o.y, o.z, o.w);
+    }
+    for (uint32_t t = (nvec << 2) + tid; t < n; t += kThreads) Elem<T>::store(out, t, s_out[t]);
+}
+
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_words(DecArgs a) { decompress_words_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_words_3d(DecArgs a) { decompress_words_body<T, BITS, 3>(a); }
 
 // planes too large for the 32-bit index tricks above: one element per thread step
 template <typename T, int BITS, int ND>
@@ -3090,7 +3166,8 @@ bool plan_tile(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
     return *lds <= kLdsMax;
 }
 
-// Fills the decompress launch plan; returns 0 (row vectors), 3 (block table), 1 (flat) or 2 (scalar).
+// Fills the decompress launch plan; returns 0 (row vectors), 3 (block table), 5 (word by word through
+// LDS), 1 (flat), 4 (lane per plane) or 2 (scalar).
 // LDS bytes of the streaming decompress kernels for G planes per workgroup
 size_t dec_lds_bytes(const Layout& L, size_t es, uint64_t G) {
     return 4ull * ((G * L.WPP + 3) & ~(uint64_t)3) + 8ull * G + es * G * L.nb + 16;
@@ -3165,6 +3242,19 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
             a->d_q4 = make_fastdiv(a->q4);
             *grid = (uint32_t)((L.P + G - 1) / G);
             return 3;
+        }
+    }
+    // several blocks per plane, rows not whole vectors: rebuilt in LDS word by word
+    if (L.nb > 1 && small_idx && out_vec_aligned && fastdiv_ok(L.HW, (uint64_t)W)) {
+        const uint64_t unit = 4 / gcd_u64(4, L.HW);
+        uint64_t G = dec_planes(L, 4, unit);          // the chunk is staged as fp32 whatever the element type
+        const uint64_t staged = (dec_lds_bytes(L, es, G) + 15) & ~15ull;
+        if (fastdiv_ok(G * L.WPP + kThreads, L.WPP) && staged + 4ull * ((G * L.HW + 3) & ~3ull) <= kDecLdsMax) {
+            a->G = (uint32_t)G;
+            a->out_off = (uint32_t)staged;
+            a->d_wpp = make_fastdiv((uint32_t)L.WPP);
+            *grid = (uint32_t)((L.P + G - 1) / G);
+            return 5;
         }
     }
     // general path: flat run of G planes, G*HW a multiple of 4
@@ -3352,16 +3442,20 @@ int decompress_impl(int count, const void* const* packed, void* const* xhat, siz
             constexpr int BITS = decltype(bits)::value;
             if (D == 1)
                 kern = kind == 0 ? decompress_rowvec<T, BITS> : kind == 3 ? decompress_table<T, BITS>
-                     : kind == 1 ? decompress_flat<T, BITS> : kind == 4 ? decompress_lane<T, BITS> : decompress_scalar<T, BITS>;
+                     : kind == 5 ? decompress_words<T, BITS> : kind == 1 ? decompress_flat<T, BITS>
+                     : kind == 4 ? decompress_lane<T, BITS> : decompress_scalar<T, BITS>;
             else
-                kern = kind == 0 ? decompress_rowvec_3d<T, BITS> : kind == 1 ? decompress_flat_3d<T, BITS>
+                kern = kind == 0 ? decompress_rowvec_3d<T, BITS> : kind == 5 ? decompress_words_3d<T, BITS>
+                     : kind == 1 ? decompress_flat_3d<T, BITS>
                      : kind == 4 ? decompress_lane<T, BITS> : decompress_scalar_3d<T, BITS>;
             return hipSuccess;
         });
         // LDS of the streaming kernels: staged codes, meta and LFC of G planes (+ the block table)
         size_t lds = 0;
         if (kind == 4) lds = 4ull * (64ull * L.HW + 4);
+        else if (kind == 5) lds = a.out_off + 4ull * ((a.G * L.HW + 3) & ~3ull);
         else if (kind != 2) lds = dec_lds_bytes(L, es, a.G) + (kind == 3 ? 4ull * a.q4 + 16 : 0);
+        if (allow_large_lds(kern, lds) != hipSuccess) return DIVISION_EHIP;
         hipLaunchKernelGGL(kern, dim3(grid, cnt), dim3(kind == 4 ? 64 : kThreads), lds, st, a);
         if (hipGetLastError() != hipSuccess) return DIVISION_EHIP;
     }
@@ -3408,7 +3502,7 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     } else {
         DecArgs a{}; uint32_t grid = 0;
         const int kind = plan_decompress(L, D, H, W, B, es, data, &a, &grid);
-        n = snprintf(out, cap, "%s%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 3 ? "decompress_table" : kind == 1 ? "decompress_flat" : kind == 4 ? "decompress_lane" : "decompress_scalar",
+        n = snprintf(out, cap, "%s%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 3 ? "decompress_table" : kind == 5 ? "decompress_words" : kind == 1 ? "decompress_flat" : kind == 4 ? "decompress_lane" : "decompress_scalar",
                      kind == 4 ? "" : sfx, tn, b);
     }
     return (n < 0 || (size_t)n >= cap) ? DIVISION_ESIZE : DIVISION_OK;

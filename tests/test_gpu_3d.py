@@ -66,7 +66,7 @@ def test_volume_kernels_cover_what_the_cases_claim():
     assert kn(0, (1, 2, 16, 56, 56), 8, 2) == "compress_plane_3d<float, 2>"
     assert kn(0, (1, 2, 16, 56, 56), 8, 2, torch.bfloat16) == "compress_plane_3d<bf16_t, 2>"
     assert kn(0, (1, 2, 33, 35, 37), 16, 2) == "compress_any_3d<float, 2>"
-    assert kn(1, (2, 3, 5, 9, 13), 4, 2) == "decompress_flat_3d<float, 2>"
+    assert kn(1, (2, 3, 5, 9, 13), 4, 2) == "decompress_words_3d<float, 2>"
     assert kn(1, (1, 2, 40, 40, 40), 8, 8) == "decompress_scalar_3d<float, 8>"
     assert kn(0, (4, 9, 3, 3, 3), 8, 2) == "compress_lane<float, 2>"
     assert kn(0, (2, 3, 7, 1, 30), 8, 2) == pkg.division_kernel_name(0, (2, 3, 7, 30), 8, 2)
