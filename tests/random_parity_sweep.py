@@ -1,0 +1,62 @@
+"""Wide random parity sweep of the HIP library against the CPU oracle: random 1-D, 2-D and 3-D shapes,
+block sizes, code widths and cache formats through every kernel family, bit for bit.  Not collected by
+pytest (it runs for as long as it is told to); on an MI355X:
+
+    python -u tests/random_parity_sweep.py [rng seed] [seconds]
+
+prints the number of cases, the mismatches (exit status 1 if any) and how often each kernel ran.
+"""
+import sys, os, time, collections
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+import numpy as np, torch
+import oracle, paper_2208_04187_amd as pkg
+rng = np.random.default_rng(int(sys.argv[1]) if len(sys.argv) > 1 else 1)
+budget = float(sys.argv[2]) if len(sys.argv) > 2 else 240.0
+t0 = time.time(); n = 0; kern = collections.Counter(); bad = 0
+def host(x):
+    return x.contiguous().view(torch.int16).numpy().view(np.uint16) if x.dtype == torch.bfloat16 else x.numpy()
+while time.time() - t0 < budget:
+    three = rng.random() < 0.3
+    kind = rng.integers(0, 6)
+    if kind == 0: H = W = int(rng.choice([4, 7, 8, 13, 14, 16, 17, 27, 28, 32, 35, 55, 56, 64, 73, 112]))
+    elif kind == 1: H, W = int(rng.integers(1, 80)), int(rng.integers(1, 80))
+    elif kind == 2: H, W = 1, int(rng.choice([24, 64, 96, 128, 196, 200, 384, 768, 1000, 1024, 3072, 4096]))
+    elif kind == 3: H, W = int(rng.integers(1, 40)), 4 * int(rng.integers(1, 40))
+    elif kind == 4: H, W = int(rng.integers(100, 320)), int(rng.integers(100, 320))
+    else: H, W = 8 * int(rng.integers(1, 20)), 8 * int(rng.integers(1, 20))
+    D = int(rng.choice([2, 3, 4, 8, 16])) if three else 1
+    if three and D * H * W > 300000: H, W = H // 4 + 1, W // 4 + 1
+    B = int(rng.choice([1, 2, 3, 4, 4, 4, 5, 6, 8, 8, 8, 8, 12, 16, 18, 32, 64, 128]))
+    b = int(rng.choice([2, 2, 4, 8]))
+    maxpl = max(1, 600000 // (D * H * W))
+    P = int(rng.integers(1, min(maxpl, 400) + 1))
+    C = int(rng.integers(1, P + 1)); N = max(1, P // C)
+    mode = str(rng.choice(["f32", "f32", "bf16", "c16"]))
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    c16 = mode == "c16"
+    dt = oracle.F32_C16 if c16 else (oracle.BF16 if mode == "bf16" else oracle.F32)
+    shape = (N, C, D, H, W) if three else (N, C, H, W)
+    g = torch.Generator().manual_seed(int(rng.integers(0, 2**31)))
+    x = torch.randn(shape, generator=g) * float(rng.choice([0.01, 1.0, 300.0]))
+    if rng.random() < 0.6: x = torch.relu(x)
+    x = x.to(dtype)
+    seed = int(rng.integers(0, 2**63))
+    ref = oracle.compress(host(x), B, b, seed, dt, threads=16)
+    xd = x.to("cuda:0")
+    if three:
+        name = pkg.division_kernel_name_3d(0, shape, B, b, dtype, c16=c16) + " | " + pkg.division_kernel_name_3d(1, shape, B, b, dtype, c16=c16)
+        pk = pkg.division_compress_3d(xd, B, b, seed, c16=c16); y = pkg.division_decompress_3d(pk, shape, B, b, dtype, c16=c16)
+    else:
+        name = pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16) + " | " + pkg.division_kernel_name(1, shape, B, b, dtype, c16=c16)
+        pk = pkg.division_compress(xd, B, b, seed, c16=c16); y = pkg.division_decompress(pk, shape, B, b, dtype, c16=c16)
+    torch.cuda.synchronize()
+    ok = np.array_equal(pk.cpu().numpy(), ref) and np.array_equal(host(y.cpu()), oracle.decompress(ref, shape, B, b, dt, threads=16))
+    for k in name.split(" | "): kern[k.split("<")[0]] += 1
+    n += 1
+    if not ok:
+        bad += 1
+        print("MISMATCH", shape, B, b, mode, seed, name, flush=True)
+    if n % 200 == 0: print(n, "cases", round(time.time() - t0), "s", flush=True)
+print("cases", n, "mismatches", bad)
+print(dict(kern))
+sys.exit(1 if bad else 0)
