@@ -2836,6 +2836,7 @@ bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
         else return false;
     } else if (q4 >= 512 && q4 <= (uint64_t)kRegUnits * 64) nw = 1;
     else if (q4 >= 2048 && q4 <= (uint64_t)kRegUnits * 256) nw = 4;
+    else if (q4 > (uint64_t)kRegUnits * 256 && q4 <= (uint64_t)kRegUnits * 1024) nw = 16;   // image-sized planes: 1024 threads, one workgroup per CU
     else return false;
     const uint64_t nt = 64ull * nw, w4 = (uint64_t)W / 4;
     if (!fastdiv_ok(kRegUnits * nt, w4) || !fastdiv_ok(L.nb + nt, L.LW) || L.HW * es >= (1ull << 31)) return false;
@@ -2852,14 +2853,17 @@ bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
     *lds = 8ull * kRegUnits * nt + 4ull * ((L.nb + 1 + 3) & ~3ull) + 8ull * nw + 16;
     *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
     *nw_out = nw;
-    return *lds <= 60u * 1024u;
+    return *lds <= (nw == 16 ? (size_t)kLdsMax : (size_t)(60u * 1024u));
 }
 
 template <typename T, int BITS>
 hipError_t launch_regs(int B, int nw, const RegsArgs& a, dim3 grid, size_t lds, hipStream_t st) {
     void (*kern)(RegsArgs);
     if (nw == 1) kern = B == 8 ? compress_regs<T, BITS, 8, 1> : B == 4 ? compress_regs<T, BITS, 4, 1> : compress_regs<T, BITS, 0, 1>;
-    else kern = B == 8 ? compress_regs<T, BITS, 8, 4> : B == 4 ? compress_regs<T, BITS, 4, 4> : compress_regs<T, BITS, 0, 4>;
+    else if (nw == 4) kern = B == 8 ? compress_regs<T, BITS, 8, 4> : B == 4 ? compress_regs<T, BITS, 4, 4> : compress_regs<T, BITS, 0, 4>;
+    else kern = B == 8 ? compress_regs<T, BITS, 8, 16> : compress_regs<T, BITS, 4, 16>;
+    const hipError_t e = allow_large_lds(kern, lds);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, dim3(64 * nw), lds, st, a);
     return hipGetLastError();
 }
@@ -3595,7 +3599,7 @@ int division_relu_compress(const void* x, int64_t N, int64_t C, int64_t H, int64
     size_t lds = 0;
     int nw = 1;
     const void* both = reinterpret_cast<const void*>((uintptr_t)x | (uintptr_t)y);
-    if (L.HW % 32 == 0 && (B == 4 || B == 8) && plan_regs(L, H, W, B, es, both, &ra, &grid, &lds, &nw)) {
+    if (L.HW % 32 == 0 && (B == 4 || B == 8) && plan_regs(L, H, W, B, es, both, &ra, &grid, &lds, &nw) && nw <= 4) {
         ra.tab.x[0] = x;
         ra.tab.pk[0] = packed;
         ra.tab.seed_a[0] = mix32((uint32_t)(seed & 0xffffffffu) ^ 0x243F6A88u);
@@ -3629,7 +3633,7 @@ int division_relu_compress_fused(int64_t N, int64_t C, int64_t H, int64_t W, div
     size_t lds = 0;
     int nw = 1;
     return L.HW % 32 == 0 && (B == 4 || B == 8) &&
-           plan_regs(L, H, W, B, dt == DIVISION_BF16 ? 2 : 4, reinterpret_cast<const void*>((uintptr_t)16), &ra, &grid, &lds, &nw);
+           plan_regs(L, H, W, B, dt == DIVISION_BF16 ? 2 : 4, reinterpret_cast<const void*>((uintptr_t)16), &ra, &grid, &lds, &nw) && nw <= 4;
 }
 
 // Both directions of the descriptor-array calls: validates every map, then serves the maps that

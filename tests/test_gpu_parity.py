@@ -679,6 +679,25 @@ def test_general_block_size_kernel_matches_oracle(shape, B, b, mode):
     _check_variant(shape, B, b, mode)
 
 
+# image-sized planes (13 K - 53 K elements) in the registers of a 1024-thread workgroup
+BIG_REGS_CASES = [
+    ((2, 3, 224, 224), 8, 2),           # 12544 units: 13 per lane but the last round
+    ((2, 2, 200, 200), 8, 4),           # 25 x 25 blocks
+    ((1, 3, 160, 168), 4, 8),           # B = 4: 1680 blocks
+    ((2, 2, 128, 128), 8, 2),           # 4096 units: four rounds
+    ((1, 2, 228, 232), 8, 2),           # 13224 units: nearly full; ragged blocks both ways
+]
+
+
+@pytest.mark.parametrize("shape,B,b", BIG_REGS_CASES)
+@pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
+def test_register_kernel_with_1024_threads_matches_oracle(shape, B, b, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    name = pkg.division_kernel_name(0, shape, B, b, dtype, c16=mode == "c16")
+    assert name.startswith("compress_regs<") and name.endswith(", 16>")
+    _check_variant(shape, B, b, mode)
+
+
 # the register kernel's instance for any block size that is a multiple of 4 (up to 16)
 REGS_ANY_CASES = [
     ((4, 6, 40, 52), 12, 2),            # 520 units, blocks of 12 and 4 both ways
