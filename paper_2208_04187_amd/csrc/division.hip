@@ -14,9 +14,10 @@
 //   compress_line    1-D maps (one row) whose block is a power-of-two number of 16-byte vectors: planes
 //                    in registers, block sums by DPP (before compress_regs for 2-byte elements and
 //                    planes below 2048 elements, after it otherwise)
-//   compress_regs    planes of 2K-3K / 8K-13K elements (56x56, 112x112), B = 4, 8 (template) or 12, 16
-//                    (from the arguments): one plane per workgroup of one / four wavefronts, the
-//                    plane stays in registers from load to codes
+//   compress_regs    planes of 2K-3K / 8K-13K / up to 53K elements (56x56, 112x112, 224x224; 3-D maps of
+//                    those sizes), B = 4, 8 (template) or 12, 16 (from the arguments): one plane per
+//                    workgroup of one / four / sixteen wavefronts, the plane stays in registers from
+//                    load to codes
 //   compress_lane    one-block planes with an odd element count (7x7): a lane per plane
 //   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8: a lane
 //                    per pooling item, loaded straight from global memory, DPP reductions
@@ -1184,6 +1185,8 @@ struct RegsArgs {
     FastDiv d_w4, d_LW, d_B, d_upb;      // d_upb divides by B / 4
     void* y;             // relu_compress_regs: the activation's output map and its 1-bit mask (one map per launch)
     uint32_t* mask;
+    uint32_t D;          // compress_regs_3d: depth slices; H, LH then count the rows / block rows of ONE slice
+    FastDiv d_H, d_slice;    // divide by H and by LH * LW
 };
 
 constexpr int kRegUnits = 13;     // units per lane: planes of up to 13 * (threads per workgroup) units
@@ -1203,7 +1206,9 @@ constexpr int kRegUnits = 13;     // units per lane: planes of up to 13 * (threa
 // cache: y = x where x > 0 else +0 is written out, its 1-bit mask too (H*W a multiple of 32: a
 // plane's mask is whole words, a word is the eight units of eight neighbouring lanes), and y is
 // what gets compressed, without a second trip through HBM.
-template <typename T, int BITS, int B, int NW, bool RELU>
+// ND = 3: planes of D x H x W elements with blocks of B x B x B (Appendix D); a unit's block and the
+// units of a block are found with the depth as a third coordinate, everything else is the same.
+template <typename T, int BITS, int B, int NW, bool RELU, int ND = 2>
 __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
     constexpr int NT = 64 * NW;
     constexpr int K = kRegUnits;
@@ -1213,6 +1218,7 @@ __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
     double* usum = reinterpret_cast<double*>(smem4);                  // [K*NT] per-unit sums
     float* lfcs = reinterpret_cast<float*>(usum + K * NT);            // [nb + 1], last = NaN sentinel
     float* red = lfcs + ((a.nb + 1 + 3) & ~3u);                        // [2*NW] cross-wave min / max
+    double* zsum = reinterpret_cast<double*>(red + 2 * NW + 2);       // [nb*B] (3-D maps) one sum per block and depth slice
 
     const uint32_t tid = threadIdx.x;
     const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
@@ -1222,16 +1228,20 @@ __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const uint32_t f = tid + NT * k;
-        const uint32_t row = fdiv(f, a.d_w4);
+        const uint32_t row = fdiv(f, a.d_w4);          // row, counted over all depth slices
         const uint32_t c4 = f - row * a.w4;
-        if constexpr (B != 0) blk[k] = f < a.q4 ? (row / B) * a.LW + c4 / UPB : a.nb;
+        if constexpr (ND == 3) {
+            const uint32_t z = fdiv(row, a.d_H);
+            blk[k] = f < a.q4 ? ((z / B) * a.LH + (row - z * a.H) / B) * a.LW + c4 / UPB : a.nb;
+        } else if constexpr (B != 0) blk[k] = f < a.q4 ? (row / B) * a.LW + c4 / UPB : a.nb;
         else blk[k] = f < a.q4 ? fdiv(row, a.d_B) * a.LW + fdiv(c4, a.d_upb) : a.nb;
     }
     if (tid == 0) lfcs[a.nb] = __builtin_nanf("");
     bool full_blocks = false;
-    if constexpr (B != 0) full_blocks = (a.H % B) == 0 && (a.W % B) == 0;
-    // rounds of units a plane has (uniform); the instances for B = 4 and 8 always run all K
-    auto round_live = [&](int k) -> bool { return B != 0 || (uint32_t)(NT * k) < a.q4; };
+    if constexpr (B != 0) full_blocks = (a.H % B) == 0 && (a.W % B) == 0 && (ND == 2 || (a.D % B) == 0);
+    // rounds of units a plane has (uniform); the one- and four-wavefront instances for B = 4 and 8
+    // always run all K (their planes fill at least eight of them)
+    auto round_live = [&](int k) -> bool { return (B != 0 && NW != 16 && ND == 2) || (uint32_t)(NT * k) < a.q4; };
 
     const uint32_t pbeg = blockIdx.x * a.ppw;
     const uint32_t pend = min(a.P, pbeg + a.ppw);
@@ -1302,6 +1312,33 @@ __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
             if (round_live(k)) usum[tid + NT * k] = ((double)x[k][0] + (double)x[k][1]) + ((double)x[k][2] + (double)x[k][3]);
         if constexpr (NW == 1) wave_sync(); else lds_barrier();
 
+        if constexpr (ND == 3) {
+            // ---- step 2a (3-D maps): a lane per (block, depth slice) adds that slice's B x UPB unit sums
+            for (uint32_t t2 = tid; t2 < a.nb * B; t2 += NT) {
+                const uint32_t t = t2 / B, z = t2 - t * B;
+                const uint32_t bd = fdiv(t, a.d_slice);
+                const uint32_t rem = t - bd * (a.LH * a.LW);
+                const uint32_t bi3 = fdiv(rem, a.d_LW);
+                const uint32_t bj3 = rem - bi3 * a.LW;
+                const uint32_t deps = min((uint32_t)B, a.D - bd * B);
+                const uint32_t rows = min((uint32_t)B, a.H - bi3 * B);
+                const uint32_t units = min((uint32_t)UPB, a.w4 - bj3 * UPB);
+                double Sz = 0.0;
+                if (z < deps) {
+                    const double* us = usum + ((bd * B + z) * a.H + bi3 * B) * a.w4 + bj3 * UPB;
+#pragma unroll
+                    for (int rr = 0; rr < B; ++rr)
+#pragma unroll
+                        for (int u = 0; u < UPB; ++u) {
+                            const bool ok = (uint32_t)rr < rows && (uint32_t)u < units;
+                            const double v = us[ok ? rr * a.w4 + u : 0u];
+                            Sz += ok ? v : 0.0;
+                        }
+                }
+                zsum[t2] = Sz;
+            }
+            if constexpr (NW == 1) wave_sync(); else lds_barrier();
+        }
         // ---- step 2: a lane per block adds the block's unit sums in a fixed order
         for (uint32_t t = tid; t < a.nb; t += NT) {
             const uint32_t bi = fdiv(t, a.d_LW);
@@ -1328,7 +1365,19 @@ __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
                 cnt = rows * units * 4;
             }
             const uint32_t u0 = bi * B * a.w4 + bj * UPB;
-            if constexpr (B == 0) {
+            if constexpr (ND == 3) {
+                // t = (bd * LH + bi3) * LW + bj: the block's units are B slices x B rows x UPB units
+                const uint32_t bd = fdiv(t, a.d_slice);
+                const uint32_t rem = t - bd * (a.LH * a.LW);
+                const uint32_t bi3 = fdiv(rem, a.d_LW);
+                const uint32_t bj3 = rem - bi3 * a.LW;
+                const uint32_t deps = min((uint32_t)B, a.D - bd * B);
+                const uint32_t rows = min((uint32_t)B, a.H - bi3 * B);
+                const uint32_t units = min((uint32_t)UPB, a.w4 - bj3 * UPB);
+#pragma unroll
+                for (int z = 0; z < B; ++z) S += zsum[t * B + z];          // slices past the map hold 0
+                cnt = deps * rows * units * 4;
+            } else if constexpr (B == 0) {
             } else if (full_blocks) {
 #pragma unroll
                 for (int rr = 0; rr < B; ++rr)
@@ -1416,6 +1465,8 @@ template <typename T, int BITS, int B, int NW>
 __global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) { compress_regs_body<T, BITS, B, NW, false>(a); }
 template <typename T, int BITS, int B, int NW>
 __global__ void __launch_bounds__(64 * NW) relu_compress_regs(RegsArgs a) { compress_regs_body<T, BITS, B, NW, true>(a); }
+template <typename T, int BITS, int B, int NW>
+__global__ void __launch_bounds__(64 * NW) compress_regs_3d(RegsArgs a) { compress_regs_body<T, BITS, B, NW, false, 3>(a); }
 
 // the elements of one 16-byte vector of x as fp32
 template <typename T>
@@ -2819,9 +2870,10 @@ hipError_t launch_wave(int B, int vec, const WaveArgs& a, dim3 grid, size_t lds,
 }
 
 // Fills the plane-in-registers compress plan; false when the shape is not covered.
-bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* x,
+bool plan_regs(const Layout& L, int64_t D, int64_t H, int64_t W, int B, size_t es, const void* x,
                RegsArgs* a, uint32_t* grid, size_t* lds, int* nw_out) {
     if (B % 4 != 0 || W % 4 != 0) return false;
+    if (D > 1 && B != 8) return false;            // 3-D maps: the B = 8 instances only
     if (((uintptr_t)x % (4 * es)) != 0) return false;
     const uint64_t q4 = L.HW / 4;
     const bool any_b = B != 4 && B != 8;          // the instance that reads B from its arguments
@@ -2835,12 +2887,16 @@ bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
         else if (q4 > (uint64_t)kRegUnits * 64 && q4 <= (uint64_t)kRegUnits * 256) nw = 4;
         else return false;
     } else if (q4 >= 512 && q4 <= (uint64_t)kRegUnits * 64) nw = 1;
-    else if (q4 >= 2048 && q4 <= (uint64_t)kRegUnits * 256) nw = 4;
+    else if (q4 >= (D > 1 ? (uint64_t)kRegUnits * 64 + 1 : 2048) && q4 <= (uint64_t)kRegUnits * 256) nw = 4;
     else if (q4 > (uint64_t)kRegUnits * 256 && q4 <= (uint64_t)kRegUnits * 1024) nw = 16;   // image-sized planes: 1024 threads, one workgroup per CU
     else return false;
     const uint64_t nt = 64ull * nw, w4 = (uint64_t)W / 4;
     if (!fastdiv_ok(kRegUnits * nt, w4) || !fastdiv_ok(L.nb + nt, L.LW) || L.HW * es >= (1ull << 31)) return false;
     if (!fastdiv_ok((uint64_t)H, (uint64_t)B) || !fastdiv_ok(w4, (uint64_t)B / 4)) return false;
+    if (!fastdiv_ok((uint64_t)D * (uint64_t)H, (uint64_t)H) || !fastdiv_ok(L.nb + nt, L.LH * L.LW)) return false;
+    a->D = (uint32_t)D;
+    a->d_H = make_fastdiv((uint32_t)H);
+    a->d_slice = make_fastdiv((uint32_t)(L.LH * L.LW));
     a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
     a->LH = (uint32_t)L.LH; a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP;
     a->q4 = (uint32_t)q4; a->w4 = (uint32_t)w4;
@@ -2850,7 +2906,7 @@ bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
     a->d_LW = make_fastdiv((uint32_t)L.LW);
     a->d_B = make_fastdiv((uint32_t)B);
     a->d_upb = make_fastdiv((uint32_t)B / 4);
-    *lds = 8ull * kRegUnits * nt + 4ull * ((L.nb + 1 + 3) & ~3ull) + 8ull * nw + 16;
+    *lds = 8ull * kRegUnits * nt + 4ull * ((L.nb + 1 + 3) & ~3ull) + 8ull * nw + 16 + (D > 1 ? 8ull * L.nb * B + 16 : 0);
     *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
     *nw_out = nw;
     return *lds <= (nw == 16 ? (size_t)kLdsMax : (size_t)(60u * 1024u));
@@ -2859,7 +2915,8 @@ bool plan_regs(const Layout& L, int64_t H, int64_t W, int B, size_t es, const vo
 template <typename T, int BITS>
 hipError_t launch_regs(int B, int nw, const RegsArgs& a, dim3 grid, size_t lds, hipStream_t st) {
     void (*kern)(RegsArgs);
-    if (nw == 1) kern = B == 8 ? compress_regs<T, BITS, 8, 1> : B == 4 ? compress_regs<T, BITS, 4, 1> : compress_regs<T, BITS, 0, 1>;
+    if (a.D > 1) kern = nw == 1 ? compress_regs_3d<T, BITS, 8, 1> : nw == 4 ? compress_regs_3d<T, BITS, 8, 4> : compress_regs_3d<T, BITS, 8, 16>;
+    else if (nw == 1) kern = B == 8 ? compress_regs<T, BITS, 8, 1> : B == 4 ? compress_regs<T, BITS, 4, 1> : compress_regs<T, BITS, 0, 1>;
     else if (nw == 4) kern = B == 8 ? compress_regs<T, BITS, 8, 4> : B == 4 ? compress_regs<T, BITS, 4, 4> : compress_regs<T, BITS, 0, 4>;
     else kern = B == 8 ? compress_regs<T, BITS, 8, 16> : compress_regs<T, BITS, 4, 16>;
     const hipError_t e = allow_large_lds(kern, lds);
@@ -3358,7 +3415,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         enum { REGS, LANE, LINE, ITEMS, WAVE, TILE, ONE, ROWS, PLANE, ANY } kind;
         const bool flat = D == 1;               // the register, item, wavefront and tile kernels take 2-D maps
         if (line_first(L, es) && plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
-        else if (flat && plan_regs(L, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
+        else if (plan_regs(L, D, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
         else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
         else if (plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
         else if (flat && plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
@@ -3483,8 +3540,8 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
         TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; OneArgs oa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (line_first(L, es) && plan_line(L, D, H, B, es, data, &oa, &grid))
             n = snprintf(out, cap, "compress_line<%s, %d>", tn, b);
-        else if (flat && plan_regs(L, H, W, B, es, data, &ra, &grid, &lds, &nw))
-            n = snprintf(out, cap, "compress_regs<%s, %d, %d, %d>", tn, b, (B == 4 || B == 8) ? B : 0, nw);
+        else if (plan_regs(L, D, H, W, B, es, data, &ra, &grid, &lds, &nw))
+            n = snprintf(out, cap, "compress_regs%s<%s, %d, %d, %d>", sfx, tn, b, (B == 4 || B == 8) ? B : 0, nw);
         else if (plan_lane(L, es, data, &la, &grid, &lds))
             n = snprintf(out, cap, "compress_lane<%s, %d>", tn, b);
         else if (plan_line(L, D, H, B, es, data, &oa, &grid))
@@ -3599,7 +3656,7 @@ int division_relu_compress(const void* x, int64_t N, int64_t C, int64_t H, int64
     size_t lds = 0;
     int nw = 1;
     const void* both = reinterpret_cast<const void*>((uintptr_t)x | (uintptr_t)y);
-    if (L.HW % 32 == 0 && (B == 4 || B == 8) && plan_regs(L, H, W, B, es, both, &ra, &grid, &lds, &nw) && nw <= 4) {
+    if (L.HW % 32 == 0 && (B == 4 || B == 8) && plan_regs(L, 1, H, W, B, es, both, &ra, &grid, &lds, &nw) && nw <= 4) {
         ra.tab.x[0] = x;
         ra.tab.pk[0] = packed;
         ra.tab.seed_a[0] = mix32((uint32_t)(seed & 0xffffffffu) ^ 0x243F6A88u);
@@ -3633,7 +3690,7 @@ int division_relu_compress_fused(int64_t N, int64_t C, int64_t H, int64_t W, div
     size_t lds = 0;
     int nw = 1;
     return L.HW % 32 == 0 && (B == 4 || B == 8) &&
-           plan_regs(L, H, W, B, dt == DIVISION_BF16 ? 2 : 4, reinterpret_cast<const void*>((uintptr_t)16), &ra, &grid, &lds, &nw) && nw <= 4;
+           plan_regs(L, 1, H, W, B, dt == DIVISION_BF16 ? 2 : 4, reinterpret_cast<const void*>((uintptr_t)16), &ra, &grid, &lds, &nw) && nw <= 4;
 }
 
 // Both directions of the descriptor-array calls: validates every map, then serves the maps that

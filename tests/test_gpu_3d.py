@@ -20,7 +20,10 @@ CASES = [
     ((3, 2, 10, 14, 14), 4, 8),
     ((2, 3, 9, 9, 9), 2, 2),                      # 125 blocks per plane
     ((2, 2, 7, 6, 5), 1, 4),                      # B = 1
-    ((2, 3, 16, 28, 28), 8, 2),                   # 12544-element planes
+    ((2, 3, 16, 28, 28), 8, 2),                   # 12544-element planes: register kernel, four wavefronts
+    ((2, 3, 4, 28, 28), 8, 4),                    # 3136 elements: register kernel, one wavefront, depth shorter than the block
+    ((2, 2, 20, 44, 48), 8, 2),                   # 42240 elements: 1024 threads, ragged blocks in depth and rows
+    ((1, 2, 9, 36, 40), 8, 8),                    # ragged everywhere, 8-bit codes
     ((1, 2, 16, 56, 56), 8, 2),                   # plane beyond LDS: workgroup per plane
     ((1, 3, 20, 30, 34), 12, 4),                  # same, ragged, B = 12
     ((1, 2, 40, 40, 40), 8, 8),                   # codes of a plane beyond the staged decompress: scalar kernel
@@ -61,11 +64,14 @@ def test_volumes_match_oracle(shape, B, b, mode):
 
 def test_volume_kernels_cover_what_the_cases_claim():
     kn = pkg.division_kernel_name_3d
-    assert kn(0, (3, 5, 16, 16, 16), 8, 2) == "compress_rows_3d<float, 2>"
-    assert kn(1, (3, 5, 16, 16, 16), 8, 2) == "decompress_rowvec_3d<float, 2>"
-    assert kn(0, (1, 2, 16, 56, 56), 8, 2) == "compress_plane_3d<float, 2>"
-    assert kn(0, (1, 2, 16, 56, 56), 8, 2, torch.bfloat16) == "compress_plane_3d<bf16_t, 2>"
+    assert kn(0, (3, 5, 16, 16, 16), 8, 2) == "compress_regs_3d<float, 2, 8, 4>"
+    assert kn(0, (2, 3, 4, 28, 28), 8, 2) == "compress_regs_3d<float, 2, 8, 1>"
+    assert kn(0, (1, 2, 16, 56, 56), 8, 2) == "compress_regs_3d<float, 2, 8, 16>"
+    assert kn(0, (1, 2, 16, 56, 56), 8, 2, torch.bfloat16) == "compress_regs_3d<bf16_t, 2, 8, 16>"
+    assert kn(0, (2, 3, 5, 9, 13), 4, 2) == "compress_rows_3d<float, 2>"
+    assert kn(0, (1, 2, 24, 40, 64), 16, 2) == "compress_plane_3d<float, 2>"
     assert kn(0, (1, 2, 33, 35, 37), 16, 2) == "compress_any_3d<float, 2>"
+    assert kn(1, (3, 5, 16, 16, 16), 8, 2) == "decompress_rowvec_3d<float, 2>"
     assert kn(1, (2, 3, 5, 9, 13), 4, 2) == "decompress_words_3d<float, 2>"
     assert kn(1, (1, 2, 40, 40, 40), 8, 8) == "decompress_scalar_3d<float, 8>"
     assert kn(0, (4, 9, 3, 3, 3), 8, 2) == "compress_lane<float, 2>"
