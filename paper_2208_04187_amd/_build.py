@@ -1,19 +1,36 @@
-"""Builds libdivision.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
+"""Builds libdivision.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
+
+division.hip instantiates its kernels once per element / cache type; it is compiled as three
+translation units (-DDIVISION_PART=0, 1, 2: float, bfloat16, bfloat16-cached float) beside masks.hip,
+all four in parallel, and the objects are linked into the one library.
+"""
 from __future__ import annotations
 
 import os
+import shutil
 import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 from pathlib import Path
 
 PKG = Path(__file__).resolve().parent
-SRCS = [PKG / "csrc" / "division.hip", PKG / "csrc" / "masks.hip"]
+DIVISION = PKG / "csrc" / "division.hip"
+MASKS = PKG / "csrc" / "masks.hip"
+SRCS = [DIVISION, MASKS]
 LIB = PKG / "libdivision.so"
+# (object name, source, extra flags)
+UNITS = [
+    ("division_f32.o", DIVISION, ["-DDIVISION_PART=0"]),
+    ("division_bf16.o", DIVISION, ["-DDIVISION_PART=1"]),
+    ("division_c16.o", DIVISION, ["-DDIVISION_PART=2"]),
+    ("masks.o", MASKS, []),
+]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17",
     "-ffp-contract=off",                       # fp32 steps of the codec are never fused
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-fPIC", "-shared",
+    "-fPIC",
     "-Rpass-analysis=kernel-resource-usage",   # parsed below: no kernel may spill to scratch
 ]
 
@@ -21,17 +38,32 @@ HIPCC_FLAGS = [
 def build(verbose: bool = False) -> Path:
     """Compile unconditionally; returns the path of the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB.with_name(LIB.name + ".tmp%d" % os.getpid())
-    cmd = [hipcc, *HIPCC_FLAGS, "-o", str(tmp), *map(str, SRCS)]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stderr)
-    spills = [ln for ln in res.stderr.splitlines()
-              if "ScratchSize [bytes/lane]:" in ln and not ln.split("ScratchSize [bytes/lane]:")[1].strip().startswith("0")]
-    if spills:
-        tmp.unlink(missing_ok=True)
-        raise RuntimeError("a kernel spills registers to scratch memory (performance guard):\n" + "\n".join(spills[:5]))
-    if verbose and res.stderr:
-        print("\n".join(ln for ln in res.stderr.splitlines() if "remark:" not in ln))
-    os.replace(tmp, LIB)
+    objdir = Path(tempfile.mkdtemp(prefix="division_build_"))
+    try:
+        def compile_unit(unit):
+            name, src, extra = unit
+            cmd = [hipcc, *HIPCC_FLAGS, *extra, "-c", "-o", str(objdir / name), str(src)]
+            return name, subprocess.run(cmd, capture_output=True, text=True)
+
+        with ThreadPoolExecutor(max_workers=len(UNITS)) as pool:
+            results = list(pool.map(compile_unit, UNITS))
+        for name, res in results:
+            if res.returncode != 0:
+                raise RuntimeError("hipcc failed on %s:\n%s" % (name, res.stderr))
+        log = "".join(res.stderr for _, res in results)
+        spills = [ln for ln in log.splitlines()
+                  if "ScratchSize [bytes/lane]:" in ln and not ln.split("ScratchSize [bytes/lane]:")[1].strip().startswith("0")]
+        if spills:
+            raise RuntimeError("a kernel spills registers to scratch memory (performance guard):\n" + "\n".join(spills[:5]))
+        if verbose and log:
+            print("\n".join(ln for ln in log.splitlines() if "remark:" not in ln))
+        tmp = LIB.with_name(LIB.name + ".tmp%d" % os.getpid())
+        link = [hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", str(tmp), *(str(objdir / u[0]) for u in UNITS)]
+        res = subprocess.run(link, capture_output=True, text=True)
+        if res.returncode != 0:
+            tmp.unlink(missing_ok=True)
+            raise RuntimeError("link failed:\n" + res.stderr)
+        os.replace(tmp, LIB)
+    finally:
+        shutil.rmtree(objdir, ignore_errors=True)
     return LIB

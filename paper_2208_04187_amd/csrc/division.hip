@@ -43,6 +43,34 @@
 #include <vector>
 #include "../../include/division.h"
 
+// The kernels are instantiated per element / cache type (float, bf16_t, f32c16_t).  To build the
+// library in parallel this file can be compiled three times with -DDIVISION_PART=0, 1, 2: each part
+// instantiates the kernels of one type behind three bridge functions, part 0 also holds the C ABI.
+// Without the macro one translation unit holds everything.
+#if !defined(DIVISION_PART)
+#define DIVISION_HOST 1
+#define DIVISION_HAS_F32 1
+#define DIVISION_HAS_BF16 1
+#define DIVISION_HAS_C16 1
+#else
+#define DIVISION_HOST (DIVISION_PART == 0)
+#define DIVISION_HAS_F32 (DIVISION_PART == 0)
+#define DIVISION_HAS_BF16 (DIVISION_PART == 1)
+#define DIVISION_HAS_C16 (DIVISION_PART == 2)
+#endif
+// launch descriptors travel through the bridges as untyped pointers (their types live in the
+// unnamed namespace of each part; the parts are built from this one source, so the layouts agree)
+#define DIVISION_BRIDGE __attribute__((visibility("hidden")))
+DIVISION_BRIDGE hipError_t division_bridge_compress_f32(const void* launch, int b);
+DIVISION_BRIDGE hipError_t division_bridge_compress_bf16(const void* launch, int b);
+DIVISION_BRIDGE hipError_t division_bridge_compress_c16(const void* launch, int b);
+DIVISION_BRIDGE hipError_t division_bridge_decompress_f32(const void* launch, int b);
+DIVISION_BRIDGE hipError_t division_bridge_decompress_bf16(const void* launch, int b);
+DIVISION_BRIDGE hipError_t division_bridge_decompress_c16(const void* launch, int b);
+DIVISION_BRIDGE hipError_t division_bridge_relu_f32(const void* launch, int b);
+DIVISION_BRIDGE hipError_t division_bridge_relu_bf16(const void* launch, int b);
+DIVISION_BRIDGE hipError_t division_bridge_relu_c16(const void* launch, int b);
+
 namespace {
 
 constexpr int kThreads = 256;              // 4 wavefronts of 64
@@ -3334,13 +3362,115 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
 }
 
 // calls f(T{}, std::integral_constant<int, BITS>{}) for the element / cache type and code width of a call
+// calls f(std::integral_constant<int, BITS>{}) for the code width of a call
 template <typename F>
-hipError_t with_type_bits(division_dtype dt, int b, F&& f) {
-    auto bits = [&](auto tag) -> hipError_t {
-        return b == 2 ? f(tag, std::integral_constant<int, 2>{}) : b == 4 ? f(tag, std::integral_constant<int, 4>{})
-                                                                          : f(tag, std::integral_constant<int, 8>{});
-    };
-    return dt == DIVISION_F32 ? bits(float{}) : dt == DIVISION_BF16 ? bits(bf16_t{}) : bits(f32c16_t{});
+hipError_t with_bits(int b, F&& f) {
+    return b == 2 ? f(std::integral_constant<int, 2>{}) : b == 4 ? f(std::integral_constant<int, 4>{})
+                                                                  : f(std::integral_constant<int, 8>{});
+}
+
+enum CompKind { REGS, LANE, LINE, ITEMS, WAVE, TILE, ONE, ROWS, PLANE, ANY };
+
+// everything a compress launch needs once the plan is made (the arguments of the kernel that was picked)
+struct CompLaunch {
+    int kind, B, vec, nt, nw, flat;
+    uint32_t gx, gy;
+    size_t lds;
+    hipStream_t st;
+    TileArgs a; WaveArgs wa; RegsArgs ra; ItemsArgs ia; LaneArgs la; RowsArgs wa2; PlaneArgs pa; OneArgs oa; AnyArgs g;
+};
+struct DecLaunch {
+    int kind, flat;
+    uint32_t gx, gy;
+    size_t lds;
+    hipStream_t st;
+    DecArgs a;
+};
+
+template <typename T>
+hipError_t do_compress(const CompLaunch& c, int b) {
+    const dim3 gd(c.gx, c.gy);
+    hipStream_t st = c.st;
+    const size_t lds = c.lds;
+    const bool flat = c.flat != 0;
+    return with_bits(b, [&](auto bits) -> hipError_t {
+        constexpr int BITS = decltype(bits)::value;
+        switch (c.kind) {
+            case REGS: return launch_regs<T, BITS>(c.B, c.nw, c.ra, gd, lds, st);
+            case ITEMS: return launch_items<T, BITS>(c.B, c.vec, c.ia, gd, lds, st);
+            case WAVE: return launch_wave<T, BITS>(c.B, c.vec, c.wa, gd, lds, st);
+            case TILE: return launch_tile<T, BITS>(c.B, c.vec, c.a, gd, lds, st);
+            case LANE: hipLaunchKernelGGL((compress_lane<T, BITS>), gd, dim3(64), lds, st, c.la); return hipGetLastError();
+            case ONE: hipLaunchKernelGGL((compress_one<T, BITS>), gd, dim3(64), 0, st, c.oa); return hipGetLastError();
+            case LINE: hipLaunchKernelGGL((compress_line<T, BITS>), gd, dim3(64), 0, st, c.oa); return hipGetLastError();
+            case ROWS: {
+                void (*kern)(RowsArgs) = flat ? compress_rows<T, BITS> : compress_rows_3d<T, BITS>;
+                const hipError_t e = allow_large_lds(kern, lds);
+                if (e != hipSuccess) return e;
+                hipLaunchKernelGGL(kern, gd, dim3(kThreads), lds, st, c.wa2);
+                return hipGetLastError();
+            }
+            case PLANE: {
+                void (*kern)(PlaneArgs) = flat ? compress_plane<T, BITS> : compress_plane_3d<T, BITS>;
+                const hipError_t e = allow_large_lds(kern, lds);
+                if (e != hipSuccess) return e;
+                hipLaunchKernelGGL(kern, gd, dim3(kThreads), lds, st, c.pa);
+                return hipGetLastError();
+            }
+            default: {
+                void (*kern)(AnyArgs) = flat ? compress_any<T, BITS> : compress_any_3d<T, BITS>;
+                hipLaunchKernelGGL(kern, gd, dim3(kThreads), 0, st, c.g);
+                return hipGetLastError();
+            }
+        }
+    });
+}
+
+template <typename T>
+hipError_t do_decompress(const DecLaunch& c, int b) {
+    return with_bits(b, [&](auto bits) -> hipError_t {
+        constexpr int BITS = decltype(bits)::value;
+        const int kind = c.kind;
+        void (*kern)(DecArgs);
+        if (c.flat)
+            kern = kind == 0 ? decompress_rowvec<T, BITS> : kind == 3 ? decompress_table<T, BITS>
+                 : kind == 5 ? decompress_words<T, BITS> : kind == 1 ? decompress_flat<T, BITS>
+                 : kind == 4 ? decompress_lane<T, BITS> : decompress_scalar<T, BITS>;
+        else
+            kern = kind == 0 ? decompress_rowvec_3d<T, BITS> : kind == 5 ? decompress_words_3d<T, BITS>
+                 : kind == 1 ? decompress_flat_3d<T, BITS>
+                 : kind == 4 ? decompress_lane<T, BITS> : decompress_scalar_3d<T, BITS>;
+        const hipError_t e = allow_large_lds(kern, c.lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, dim3(c.gx, c.gy), dim3(kind == 4 ? 64 : kThreads), c.lds, c.st, c.a);
+        return hipGetLastError();
+    });
+}
+
+// the Relu + compress kernel of the register kernel's planes (one map per launch; c.ra carries y and mask)
+template <typename T>
+hipError_t do_relu(const CompLaunch& c, int b) {
+    return with_bits(b, [&](auto bits) -> hipError_t {
+        constexpr int BITS = decltype(bits)::value;
+        void (*kern)(RegsArgs);
+        if (c.nw == 1) kern = c.B == 8 ? relu_compress_regs<T, BITS, 8, 1> : relu_compress_regs<T, BITS, 4, 1>;
+        else kern = c.B == 8 ? relu_compress_regs<T, BITS, 8, 4> : relu_compress_regs<T, BITS, 4, 4>;
+        hipLaunchKernelGGL(kern, dim3(c.gx, 1), dim3(64 * c.nw), c.lds, c.st, c.ra);
+        return hipGetLastError();
+    });
+}
+
+hipError_t bridge_compress(division_dtype dt, const CompLaunch& c, int b) {
+    return dt == DIVISION_F32 ? division_bridge_compress_f32(&c, b)
+         : dt == DIVISION_BF16 ? division_bridge_compress_bf16(&c, b) : division_bridge_compress_c16(&c, b);
+}
+hipError_t bridge_decompress(division_dtype dt, const DecLaunch& c, int b) {
+    return dt == DIVISION_F32 ? division_bridge_decompress_f32(&c, b)
+         : dt == DIVISION_BF16 ? division_bridge_decompress_bf16(&c, b) : division_bridge_decompress_c16(&c, b);
+}
+hipError_t bridge_relu(division_dtype dt, const CompLaunch& c, int b) {
+    return dt == DIVISION_F32 ? division_bridge_relu_f32(&c, b)
+         : dt == DIVISION_BF16 ? division_bridge_relu_bf16(&c, b) : division_bridge_relu_c16(&c, b);
 }
 
 // A 3-D map with a dimension of extent 1 is a 2-D map with the same flat element order, the same
@@ -3412,7 +3542,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         size_t lds = 0;
         uint32_t grid = 0;
         int vec = 1, nt = 64, nw = 1;
-        enum { REGS, LANE, LINE, ITEMS, WAVE, TILE, ONE, ROWS, PLANE, ANY } kind;
+        CompKind kind;
         const bool flat = D == 1;               // the register, item, wavefront and tile kernels take 2-D maps
         if (line_first(L, es) && plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
         else if (plan_regs(L, D, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
@@ -3432,39 +3562,11 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
             g.LH = (uint32_t)L.LH; g.LW = (uint32_t)L.LW; g.nb = (uint32_t)L.nb; g.WPP = (uint32_t)L.WPP; g.B = (uint32_t)B;
             grid = (uint32_t)L.P;
         }
-        const dim3 gd(grid, cnt);
-        const hipError_t err = with_type_bits(dt, b, [&](auto tag, auto bits) -> hipError_t {
-            using T = decltype(tag);
-            constexpr int BITS = decltype(bits)::value;
-            switch (kind) {
-                case REGS: return launch_regs<T, BITS>(B, nw, ra, gd, lds, st);
-                case ITEMS: return launch_items<T, BITS>(B, vec, ia, gd, lds, st);
-                case WAVE: return launch_wave<T, BITS>(B, vec, wa, gd, lds, st);
-                case TILE: return launch_tile<T, BITS>(B, vec, a, gd, lds, st);
-                case LANE: hipLaunchKernelGGL((compress_lane<T, BITS>), gd, dim3(64), lds, st, la); return hipGetLastError();
-                case ONE: hipLaunchKernelGGL((compress_one<T, BITS>), gd, dim3(64), 0, st, oa); return hipGetLastError();
-                case LINE: hipLaunchKernelGGL((compress_line<T, BITS>), gd, dim3(64), 0, st, oa); return hipGetLastError();
-                case ROWS: {
-                    void (*kern)(RowsArgs) = flat ? compress_rows<T, BITS> : compress_rows_3d<T, BITS>;
-                    const hipError_t e = allow_large_lds(kern, lds);
-                    if (e != hipSuccess) return e;
-                    hipLaunchKernelGGL(kern, gd, dim3(kThreads), lds, st, wa2);
-                    return hipGetLastError();
-                }
-                case PLANE: {
-                    void (*kern)(PlaneArgs) = flat ? compress_plane<T, BITS> : compress_plane_3d<T, BITS>;
-                    const hipError_t e = allow_large_lds(kern, lds);
-                    if (e != hipSuccess) return e;
-                    hipLaunchKernelGGL(kern, gd, dim3(kThreads), lds, st, pa);
-                    return hipGetLastError();
-                }
-                default: {
-                    void (*kern)(AnyArgs) = flat ? compress_any<T, BITS> : compress_any_3d<T, BITS>;
-                    hipLaunchKernelGGL(kern, gd, dim3(kThreads), 0, st, g);
-                    return hipGetLastError();
-                }
-            }
-        });
+        CompLaunch c{};
+        c.kind = kind; c.B = B; c.vec = vec; c.nt = nt; c.nw = nw; c.flat = flat;
+        c.gx = grid; c.gy = (uint32_t)cnt; c.lds = lds; c.st = st;
+        c.a = a; c.wa = wa; c.ra = ra; c.ia = ia; c.la = la; c.wa2 = wa2; c.pa = pa; c.oa = oa; c.g = g;
+        const hipError_t err = bridge_compress(dt, c, b);
         if (err != hipSuccess) return DIVISION_EHIP;
     }
     return DIVISION_OK;
@@ -3497,28 +3599,14 @@ int decompress_impl(int count, const void* const* packed, void* const* xhat, siz
         const int kind = plan_decompress(L, D, H, W, B, es, reinterpret_cast<const void*>(all_out ? all_out : 16), &a, &grid);
         for (int i = 0; i < cnt; ++i) { a.tab.pk[i] = packed[i0 + i]; a.tab.xhat[i] = xhat[i0 + i]; }
         a.rg = rg;
-        void (*kern)(DecArgs) = nullptr;
-        with_type_bits(dt, b, [&](auto tag, auto bits) -> hipError_t {
-            using T = decltype(tag);
-            constexpr int BITS = decltype(bits)::value;
-            if (D == 1)
-                kern = kind == 0 ? decompress_rowvec<T, BITS> : kind == 3 ? decompress_table<T, BITS>
-                     : kind == 5 ? decompress_words<T, BITS> : kind == 1 ? decompress_flat<T, BITS>
-                     : kind == 4 ? decompress_lane<T, BITS> : decompress_scalar<T, BITS>;
-            else
-                kern = kind == 0 ? decompress_rowvec_3d<T, BITS> : kind == 5 ? decompress_words_3d<T, BITS>
-                     : kind == 1 ? decompress_flat_3d<T, BITS>
-                     : kind == 4 ? decompress_lane<T, BITS> : decompress_scalar_3d<T, BITS>;
-            return hipSuccess;
-        });
         // LDS of the streaming kernels: staged codes, meta and LFC of G planes (+ the block table)
         size_t lds = 0;
         if (kind == 4) lds = 4ull * (64ull * L.HW + 4);
         else if (kind == 5) lds = a.out_off + 4ull * ((a.G * L.HW + 3) & ~3ull);
         else if (kind != 2) lds = dec_lds_bytes(L, es, a.G) + (kind == 3 ? 4ull * a.q4 + 16 : 0);
-        if (allow_large_lds(kern, lds) != hipSuccess) return DIVISION_EHIP;
-        hipLaunchKernelGGL(kern, dim3(grid, cnt), dim3(kind == 4 ? 64 : kThreads), lds, st, a);
-        if (hipGetLastError() != hipSuccess) return DIVISION_EHIP;
+        DecLaunch c{};
+        c.kind = kind; c.flat = D == 1; c.gx = grid; c.gy = (uint32_t)cnt; c.lds = lds; c.st = st; c.a = a;
+        if (bridge_decompress(dt, c, b) != hipSuccess) return DIVISION_EHIP;
     }
     return DIVISION_OK;
 }
@@ -3571,8 +3659,27 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
 
 }  // namespace
 
+// ------------------------------------------------------------------ bridges: the kernels of one type each
+
+#if DIVISION_HAS_F32
+hipError_t division_bridge_compress_f32(const void* c, int b) { return do_compress<float>(*static_cast<const CompLaunch*>(c), b); }
+hipError_t division_bridge_decompress_f32(const void* c, int b) { return do_decompress<float>(*static_cast<const DecLaunch*>(c), b); }
+hipError_t division_bridge_relu_f32(const void* c, int b) { return do_relu<float>(*static_cast<const CompLaunch*>(c), b); }
+#endif
+#if DIVISION_HAS_BF16
+hipError_t division_bridge_compress_bf16(const void* c, int b) { return do_compress<bf16_t>(*static_cast<const CompLaunch*>(c), b); }
+hipError_t division_bridge_decompress_bf16(const void* c, int b) { return do_decompress<bf16_t>(*static_cast<const DecLaunch*>(c), b); }
+hipError_t division_bridge_relu_bf16(const void* c, int b) { return do_relu<bf16_t>(*static_cast<const CompLaunch*>(c), b); }
+#endif
+#if DIVISION_HAS_C16
+hipError_t division_bridge_compress_c16(const void* c, int b) { return do_compress<f32c16_t>(*static_cast<const CompLaunch*>(c), b); }
+hipError_t division_bridge_decompress_c16(const void* c, int b) { return do_decompress<f32c16_t>(*static_cast<const DecLaunch*>(c), b); }
+hipError_t division_bridge_relu_c16(const void* c, int b) { return do_relu<f32c16_t>(*static_cast<const CompLaunch*>(c), b); }
+#endif
+
 // ------------------------------------------------------------------ C ABI
 
+#if DIVISION_HOST
 extern "C" {
 
 int division_abi_version(void) { return 1; }
@@ -3664,15 +3771,9 @@ int division_relu_compress(const void* x, int64_t N, int64_t C, int64_t H, int64
         ra.rg = make_regions(L);
         ra.y = y;
         ra.mask = static_cast<uint32_t*>(mask);
-        const hipError_t err = with_type_bits(dt, b, [&](auto tag, auto bits) -> hipError_t {
-            using T = decltype(tag);
-            constexpr int BITS = decltype(bits)::value;
-            void (*kern)(RegsArgs);
-            if (nw == 1) kern = B == 8 ? relu_compress_regs<T, BITS, 8, 1> : relu_compress_regs<T, BITS, 4, 1>;
-            else kern = B == 8 ? relu_compress_regs<T, BITS, 8, 4> : relu_compress_regs<T, BITS, 4, 4>;
-            hipLaunchKernelGGL(kern, dim3(grid, 1), dim3(64 * nw), lds, st, ra);
-            return hipGetLastError();
-        });
+        CompLaunch c{};
+        c.B = B; c.nw = nw; c.gx = grid; c.gy = 1; c.lds = lds; c.st = st; c.ra = ra;
+        const hipError_t err = bridge_relu(dt, c, b);
         return err == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
     }
     // other shapes: the operator, then the codec on its output
@@ -3755,3 +3856,4 @@ int division_kernel_name_3d(int direction, const void* data, int64_t N, int64_t 
 }
 
 }  // extern "C"
+#endif  // DIVISION_HOST
