@@ -21,6 +21,10 @@
 //   compress_lane    one-block planes with an odd element count (7x7): a lane per plane
 //   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8: a lane
 //                    per pooling item, loaded straight from global memory, DPP reductions
+//   compress_units   2-D planes of 512 to about 27K elements whose rows or blocks are not whole 16-byte vectors
+//                    (odd widths: 27x27, 55x55, 147x147; B = 18): four consecutive elements per lane step
+//                    whatever the width, the block of each element looked up in a table made once per
+//                    workgroup, the plane parked in LDS for the block sums, next plane's loads in flight
 //   compress_wave    other planes up to 17 KB, B = 4, 8: one wavefront per chunk of planes staged in LDS
 //   compress_tile    other planes up to 156 KB, B = 4, 8: four wavefronts per chunk staged in LDS
 //   compress_one     planes that are a single block (B = 64 on 56x56 and below): flat vectors in registers
@@ -1496,6 +1500,225 @@ __global__ void __launch_bounds__(64 * NW) relu_compress_regs(RegsArgs a) { comp
 template <typename T, int BITS, int B, int NW>
 __global__ void __launch_bounds__(64 * NW) compress_regs_3d(RegsArgs a) { compress_regs_body<T, BITS, B, NW, false, 3>(a); }
 
+// ------------------------------------------------------------------ compress, plane in registers, any width
+
+struct UnitsArgs {
+    CompTab tab;
+    Regions rg;
+    uint32_t P, H, W, HW, LW, nb, WPP, B;
+    uint32_t q4;         // units (4 consecutive elements) per plane, the last one may be partly past it
+    uint32_t q4p;        // q4 rounded up to whole rounds of the workgroup's lanes
+    uint32_t nitem;      // nb * B row segments
+    FastDiv d_W, d_B, d_LW;
+};
+
+// Planes whose rows or blocks are not whole 16-byte vectors (odd widths: 55 x 55, 27 x 27,
+// 147 x 147; block sizes such as 18): the register kernel's structure with the block found per
+// element instead of per unit.  A unit is four consecutive elements of the plane whatever the
+// width (planes start on 4-byte boundaries, which is all a 16-byte buffer load needs), lane `tid`
+// keeps units tid, tid+NT, ... in registers from the load to the codes, and which block each
+// element belongs to is the same for every plane: worked out once per workgroup and kept as the
+// LDS byte offset of the block's LFC, two offsets per register.  Block sums: the plane is also
+// parked in LDS; a lane per (block, row of the block) adds its row segment in binary64 (lanes of
+// one block read rows W floats apart: no bank conflicts for odd W), a lane per block adds its
+// rows.  Elements of the last unit past the plane take the NaN sentinel like whole units past it.
+constexpr int kUnitsK = 8;        // units, and row segments, per lane
+
+template <typename T, int BITS, int NW>
+__global__ void __launch_bounds__(64 * NW) compress_units(UnitsArgs a) {
+    constexpr int NT = 64 * NW;
+    constexpr int K = kUnitsK;
+    constexpr float Lf = float((1 << BITS) - 1);
+    typedef uint32_t raw_t __attribute__((ext_vector_type(sizeof(T))));     // a unit as loaded: 16 or 8 bytes
+    extern __shared__ float4 smem4[];
+    float4* xs4 = smem4;                                                  // [q4p] the plane, later its residual
+    float* xs = reinterpret_cast<float*>(smem4);
+    double* rsum = reinterpret_cast<double*>(xs + 4 * a.q4p);             // [nitem] row-segment sums
+    float* lfcs = reinterpret_cast<float*>(rsum + a.nitem);               // [nb + 1], last = NaN sentinel
+    float* red = lfcs + ((a.nb + 1 + 3) & ~3u);                           // [2*NW] cross-wave min / max
+
+    const uint32_t tid = threadIdx.x;
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
+    // rounds of units a plane has (uniform); units of the last round past the plane are worked on like
+    // the others: they load zeros, take the NaN sentinel, and their code stores are dropped
+    auto round_live = [&](int k) -> bool { return (uint32_t)(NT * k) < a.q4; };
+
+    // LDS byte offset of the LFC of each element's block (4 * nb = the sentinel for elements past the plane)
+    uint32_t lo[K][2];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        uint32_t off[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t e = 4u * (tid + NT * k) + j;
+            const uint32_t r = fdiv(e, a.d_W);
+            const uint32_t c = e - r * a.W;
+            off[j] = 4u * (e < a.HW ? fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B) : a.nb);
+        }
+        lo[k][0] = off[0] | (off[1] << 16);
+        lo[k][1] = off[2] | (off[3] << 16);
+    }
+    // the row segments of the lane (item i = block * B + row of the block): where the segment starts in
+    // the plane, and in the top bits how many elements it has (0: a row past the map, or no item)
+    uint32_t it[K];
+#pragma unroll
+    for (int m = 0; m < K; ++m) {
+        const uint32_t i = tid + NT * m;
+        const uint32_t t = fdiv(i, a.d_B), rr = i - t * a.B;
+        const uint32_t bi = fdiv(t, a.d_LW), bj = t - bi * a.LW;
+        const uint32_t r = bi * a.B + rr;
+        const uint32_t bw = min(a.B, a.W - bj * a.B);
+        it[m] = (i < a.nitem && r < a.H) ? (r * a.W + bj * a.B) | (bw << 20) : 0u;
+    }
+    if (tid == 0) lfcs[a.nb] = __builtin_nanf("");
+    const uint32_t tail = a.HW & 3u;          // elements of the last unit inside the plane (0: all four)
+
+    // 2-byte elements, odd planes of an odd element count: the plane starts in the middle of a dword.
+    // Its loads then start one element early (every load stays dword-aligned and inside dwords that hold
+    // elements of the map) and land in LDS one element lower.  The same for all planes of the workgroup:
+    // the grid is even then, or every workgroup has one plane.
+    const uint32_t shift = sizeof(T) == 2 ? (blockIdx.x * a.HW) & 1u : 0u;
+
+    // the loads of a plane: coalesced, all in flight at once; dwords past the plane read as zero
+    raw_t q[K];
+    auto issue_loads = [&](uint32_t p) {
+        const T* src = static_cast<const T*>(pt.x) + ((size_t)p * a.HW - shift);
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)((((a.HW + shift) * sizeof(T)) + 3u) & ~3u), 0x00020000);
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            if (!round_live(k)) continue;
+            if constexpr (sizeof(T) == 4) q[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, tid * 16u, k * NT * 16, kLoadAux);
+            else q[k] = __builtin_amdgcn_raw_buffer_load_b64(rsrc, tid * 8u, k * NT * 8, kLoadAux);
+        }
+    };
+
+    // a workgroup takes planes blockIdx.x, blockIdx.x + gridDim.x, ...: the tables above are made once
+    if (blockIdx.x < a.P) issue_loads(blockIdx.x);
+    for (uint32_t p = blockIdx.x; p < a.P; p += gridDim.x) {
+        // ---- park the plane in LDS as fp32, then start the next plane's loads: they fly while this one is worked on
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            if (!round_live(k)) continue;
+            float4 v;
+            if constexpr (sizeof(T) == 4) {
+                v = make_float4(__uint_as_float(q[k].x), __uint_as_float(q[k].y), __uint_as_float(q[k].z), __uint_as_float(q[k].w));
+            } else {
+                v = make_float4(__uint_as_float(q[k].x << 16), __uint_as_float(q[k].x & 0xffff0000u),
+                                __uint_as_float(q[k].y << 16), __uint_as_float(q[k].y & 0xffff0000u));
+            }
+            if (sizeof(T) == 2 && shift) {
+                float* d = xs + 4u * (tid + NT * k);
+                if (tid + NT * k != 0) d[-1] = v.x;
+                d[0] = v.y; d[1] = v.z; d[2] = v.w;
+            } else {
+                xs4[tid + NT * k] = v;
+            }
+        }
+        if (p + gridDim.x < a.P) issue_loads(p + gridDim.x);
+        if constexpr (NW == 1) wave_sync(); else lds_barrier();
+
+        // ---- Sec. 4.1 AveragePooling, step 1: a lane per (block, row) adds the row's elements inside the block
+#pragma unroll
+        for (int m = 0; m < K; ++m) {
+            if ((uint32_t)(NT * m) >= a.nitem) continue;
+            const uint32_t bw = it[m] >> 20;
+            const float* src = xs + (it[m] & 0xfffffu);
+            double S = 0.0;
+            uint32_t c = 0;
+            for (; c + 8 <= bw; c += 8) {
+                float v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = src[c + j];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) S += (double)v[j];
+            }
+            if (c + 4 <= bw) {
+                const float v0 = src[c], v1 = src[c + 1], v2 = src[c + 2], v3 = src[c + 3];
+                S += (double)v0; S += (double)v1; S += (double)v2; S += (double)v3;
+                c += 4;
+            }
+            for (; c < bw; ++c) S += (double)src[c];
+            if (tid + NT * m < a.nitem) rsum[tid + NT * m] = S;
+        }
+        if constexpr (NW == 1) wave_sync(); else lds_barrier();
+
+        // ---- step 2: a lane per block adds its rows from the top down
+        for (uint32_t t = tid; t < a.nb; t += NT) {
+            const uint32_t bi = fdiv(t, a.d_LW), bj = t - bi * a.LW;
+            const uint32_t rows = min(a.B, a.H - bi * a.B);
+            const uint32_t bw = min(a.B, a.W - bj * a.B);
+            double S = 0.0;
+            for (uint32_t rr = 0; rr < rows; ++rr) S += rsum[t * a.B + rr];
+            const float lfc = lfc_round<T>(mean_of(S, rows * bw), kC16<T>);
+            lfcs[t] = lfc;
+            lfc_store<T>(pt.lfc, (size_t)p * a.nb + t, lfc, kC16<T>);
+        }
+        if constexpr (NW == 1) wave_sync(); else lds_barrier();
+
+        // ---- residual H^H = H - UpSampling(H^L), written back over the plane; plane min / max (NaN
+        // residuals of elements past the plane are skipped by min / max)
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            if (!round_live(k)) continue;
+            const char* lb = reinterpret_cast<const char*>(lfcs);
+            float4 v = xs4[tid + NT * k];
+            v.x -= *reinterpret_cast<const float*>(lb + (lo[k][0] & 0xffffu));
+            v.y -= *reinterpret_cast<const float*>(lb + (lo[k][0] >> 16));
+            v.z -= *reinterpret_cast<const float*>(lb + (lo[k][1] & 0xffffu));
+            v.w -= *reinterpret_cast<const float*>(lb + (lo[k][1] >> 16));
+            xs4[tid + NT * k] = v;
+            mn = fminf(fminf(mn, v.x), fminf(v.y, fminf(v.z, v.w)));
+            mx = fmaxf(fmaxf(mx, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
+        }
+        group_minmax(64, mn, mx);
+        if constexpr (NW > 1) {
+            if ((tid & 63u) == 0) { red[2 * (tid >> 6)] = mn; red[2 * (tid >> 6) + 1] = mx; }
+            lds_barrier();
+#pragma unroll
+            for (int w = 0; w < NW; ++w) { mn = fminf(mn, red[2 * w]); mx = fmaxf(mx, red[2 * w + 1]); }
+        }
+
+        // ---- scale of Eq. (quantization), keys, meta
+        float delta, Delta, inv;
+        plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
+        const float invs = inv * (float)(1u << (32 - BITS));
+        const uint32_t k1 = mix32(p ^ pt.seed_a);
+        const uint32_t k2 = mix32(k1 + pt.seed_c);
+        if (tid == 0) meta_store(pt.meta, p, delta, Delta, kC16<T>);
+
+        // ---- Quant + packing: a unit is two element pairs = 4 codes; a lane reads back the residuals it wrote
+        {
+            const uint32_t rscale = 1u << (16 - BITS);
+            constexpr uint32_t CB = BITS / 2;                         // code bytes per unit (1, 2 or 4)
+            uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)p * a.WPP * 4;
+            const __amdgpu_buffer_rsrc_t crs =
+                __builtin_amdgcn_make_buffer_rsrc(cbase, 0, (int)(a.q4 * CB), 0x00020000);
+            const uint32_t xw0 = k1 + (2u * tid) * kWeyl;
+            const uint32_t tailmask = tail ? (1u << (tail * BITS)) - 1u : 0xffffffffu;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                if (!round_live(k)) continue;
+                const float4 v = xs4[tid + NT * k];
+                const uint32_t xw = xw0 + (uint32_t)(2 * NT * k) * kWeyl;
+                uint32_t c = push_pair<BITS>(0u, v.z, v.w, delta, invs, xw + kWeyl, k2, rscale);
+                c = push_pair<BITS>(c, v.x, v.y, delta, invs, xw, k2, rscale);
+                // the last unit's elements past the plane leave zero bits; stores of units past the plane are
+                // dropped by the buffer bound
+                if (tid + NT * k + 1 == a.q4) c &= tailmask;
+                if constexpr (CB == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, tid, k * NT, 0);
+                else if constexpr (CB == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c, crs, tid * 2u, k * NT * 2, 0);
+                else __builtin_amdgcn_raw_buffer_store_b32(c, crs, tid * 4u, k * NT * 4, 0);
+            }
+            // pad bytes of the plane's last word are zero
+            const uint32_t padb = a.WPP * 4 - a.q4 * CB;
+            if (tid < padb) cbase[a.q4 * CB + tid] = 0;
+        }
+        if constexpr (NW == 1) wave_sync(); else lds_barrier();      // xs, rsum, lfcs and red are reused
+    }
+}
+
 // the elements of one 16-byte vector of x as fp32
 template <typename T>
 __device__ __forceinline__ void unpack_vec(const u32x4& q, float (&x)[16 / sizeof(T)]) {
@@ -2953,6 +3176,58 @@ hipError_t launch_regs(int B, int nw, const RegsArgs& a, dim3 grid, size_t lds, 
     return hipGetLastError();
 }
 
+// Fills the plan of the register kernel for any width; false when the shape is not covered: 2-D maps
+// of at most 8 x 1024 units that fit LDS beside their row sums (up to about 163 x 163 elements).
+constexpr uint64_t kUnitsMin = 128;       // units per plane from which the kernel is worth its per-plane set-up
+bool plan_units(const Layout& L, int64_t D, int64_t H, int64_t W, int B, size_t es, const void* x,
+                UnitsArgs* a, uint32_t* grid, size_t* lds, int* nw_out) {
+    if (D != 1 || H == 1 || ((uintptr_t)x % 4) != 0) return false;
+    // small planes of even width under B = 4 and 8 are the wavefront kernel's (pairs of elements per
+    // lane): measured faster there
+    if ((B == 4 || B == 8) && W % 2 == 0 && 4ull * L.HW + 16ull <= kWavePlaneMax) return false;
+    const uint64_t q4 = (L.HW + 3) / 4;
+    if (q4 < kUnitsMin || L.nb > 16383) return false;        // LFC offsets are kept as 16-bit byte offsets
+    const uint64_t nitem = L.nb * (uint64_t)B;
+    int nw = 1;
+    while (nw < 16 && (q4 > (uint64_t)kUnitsK * 64 * nw || nitem > (uint64_t)kUnitsK * 64 * nw)) nw *= 2;
+    if (q4 > (uint64_t)kUnitsK * 64 * nw) return false;
+    const uint64_t nt = 64ull * nw;
+    const uint64_t q4p = (q4 + nt - 1) / nt * nt;
+    if (nitem > (uint64_t)kUnitsK * nt || B > 4095) return false;        // row segments: at most 8 per lane too
+    if (!fastdiv_ok(4ull * kUnitsK * nt + 4, (uint64_t)W) || !fastdiv_ok(4ull * kUnitsK * nt + 4, (uint64_t)B) ||
+        !fastdiv_ok(nitem + nt, (uint64_t)B) || !fastdiv_ok(L.nb + nt, L.LW))
+        return false;
+    a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
+    a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP; a->B = (uint32_t)B;
+    a->q4 = (uint32_t)q4; a->q4p = (uint32_t)q4p; a->nitem = (uint32_t)nitem;
+    a->d_W = make_fastdiv((uint32_t)W);
+    a->d_B = make_fastdiv((uint32_t)B);
+    a->d_LW = make_fastdiv((uint32_t)L.LW);
+    *lds = 16ull * q4p + 8ull * nitem + 4ull * ((L.nb + 1 + 3) & ~3ull) + 8ull * nw + 16;
+    if (*lds > (size_t)kLdsMax) return false;
+    // as many workgroups as the machine holds at once (LDS, and 16 wavefronts per CU), each taking every
+    // grid-th plane
+    uint64_t per_cu = (160ull << 10) / *lds;
+    if (per_cu > 16ull / nw) per_cu = 16ull / nw;
+    if (per_cu < 1) per_cu = 1;
+    uint64_t g = 256ull * per_cu;
+    g += g & 1;            // even: with 2-byte elements the planes of a workgroup then start alike within a dword
+    *grid = (uint32_t)(g < L.P ? g : L.P);
+    *nw_out = nw;
+    return *lds <= (size_t)kLdsMax;
+}
+
+template <typename T, int BITS>
+hipError_t launch_units(int nw, const UnitsArgs& a, dim3 grid, size_t lds, hipStream_t st) {
+    void (*kern)(UnitsArgs) = nw == 1 ? compress_units<T, BITS, 1> : nw == 2 ? compress_units<T, BITS, 2>
+                            : nw == 4 ? compress_units<T, BITS, 4> : nw == 8 ? compress_units<T, BITS, 8>
+                                                                             : compress_units<T, BITS, 16>;
+    const hipError_t e = allow_large_lds(kern, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, grid, dim3(64 * nw), lds, st, a);
+    return hipGetLastError();
+}
+
 // Fills the one-wavefront compress plan; false when the shape is not covered.
 // one-block planes with an odd element count: the shapes the lane-per-plane kernels take
 bool lane_shape(const Layout& L) { return L.nb == 1 && (L.HW & 1) == 1 && L.HW <= 64; }
@@ -3087,6 +3362,13 @@ bool plan_one(const Layout& L, size_t es, const void* x, OneArgs* a, uint32_t* g
     a->ppw = 64u / best_S;
     *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
     return true;
+}
+
+// single-block planes of whole vectors: compress_one's, ahead of the kernels for general shapes
+bool one_shape(const Layout& L, size_t es, const void* x) {
+    OneArgs tmp{};
+    uint32_t g = 0;
+    return plan_one(L, es, x, &tmp, &g);
 }
 
 // Fills the plan of compress_line: a 1-D map (one row) of whole 16-byte vectors, several blocks per
@@ -3369,7 +3651,7 @@ hipError_t with_bits(int b, F&& f) {
                                                                   : f(std::integral_constant<int, 8>{});
 }
 
-enum CompKind { REGS, LANE, LINE, ITEMS, WAVE, TILE, ONE, ROWS, PLANE, ANY };
+enum CompKind { REGS, LANE, LINE, ITEMS, UNITS, WAVE, TILE, ONE, ROWS, PLANE, ANY };
 
 // everything a compress launch needs once the plan is made (the arguments of the kernel that was picked)
 struct CompLaunch {
@@ -3377,7 +3659,7 @@ struct CompLaunch {
     uint32_t gx, gy;
     size_t lds;
     hipStream_t st;
-    TileArgs a; WaveArgs wa; RegsArgs ra; ItemsArgs ia; LaneArgs la; RowsArgs wa2; PlaneArgs pa; OneArgs oa; AnyArgs g;
+    TileArgs a; WaveArgs wa; RegsArgs ra; ItemsArgs ia; LaneArgs la; RowsArgs wa2; PlaneArgs pa; OneArgs oa; AnyArgs g; UnitsArgs ua;
 };
 struct DecLaunch {
     int kind, flat;
@@ -3398,6 +3680,7 @@ hipError_t do_compress(const CompLaunch& c, int b) {
         switch (c.kind) {
             case REGS: return launch_regs<T, BITS>(c.B, c.nw, c.ra, gd, lds, st);
             case ITEMS: return launch_items<T, BITS>(c.B, c.vec, c.ia, gd, lds, st);
+            case UNITS: return launch_units<T, BITS>(c.nw, c.ua, gd, lds, st);
             case WAVE: return launch_wave<T, BITS>(c.B, c.vec, c.wa, gd, lds, st);
             case TILE: return launch_tile<T, BITS>(c.B, c.vec, c.a, gd, lds, st);
             case LANE: hipLaunchKernelGGL((compress_lane<T, BITS>), gd, dim3(64), lds, st, c.la); return hipGetLastError();
@@ -3539,6 +3822,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         PlaneArgs pa{};
         OneArgs oa{};
         AnyArgs g{};
+        UnitsArgs ua{};
         size_t lds = 0;
         uint32_t grid = 0;
         int vec = 1, nt = 64, nw = 1;
@@ -3549,6 +3833,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
         else if (plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
         else if (flat && plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
+        else if (!one_shape(L, es, xa) && plan_units(L, D, H, W, B, es, xa, &ua, &grid, &lds, &nw)) { kind = UNITS; ua.tab = tab; ua.rg = rg; }
         else if (flat && plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
             kind = WAVE; wa.tab = tab; wa.rg = rg;
         } else if (flat && plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) { kind = TILE; a.tab = tab; a.rg = rg; }
@@ -3565,7 +3850,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         CompLaunch c{};
         c.kind = kind; c.B = B; c.vec = vec; c.nt = nt; c.nw = nw; c.flat = flat;
         c.gx = grid; c.gy = (uint32_t)cnt; c.lds = lds; c.st = st;
-        c.a = a; c.wa = wa; c.ra = ra; c.ia = ia; c.la = la; c.wa2 = wa2; c.pa = pa; c.oa = oa; c.g = g;
+        c.a = a; c.wa = wa; c.ra = ra; c.ia = ia; c.la = la; c.wa2 = wa2; c.pa = pa; c.oa = oa; c.g = g; c.ua = ua;
         const hipError_t err = bridge_compress(dt, c, b);
         if (err != hipSuccess) return DIVISION_EHIP;
     }
@@ -3625,7 +3910,7 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     const char* tn = dt == DIVISION_BF16 ? "bf16_t" : dt == DIVISION_F32_C16 ? "f32c16_t" : "float";
     int n;
     if (direction == 0) {
-        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; OneArgs oa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
+        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; OneArgs oa{}; UnitsArgs ua{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (line_first(L, es) && plan_line(L, D, H, B, es, data, &oa, &grid))
             n = snprintf(out, cap, "compress_line<%s, %d>", tn, b);
         else if (plan_regs(L, D, H, W, B, es, data, &ra, &grid, &lds, &nw))
@@ -3636,6 +3921,8 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
             n = snprintf(out, cap, "compress_line<%s, %d>", tn, b);
         else if (flat && plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_items<%s, %d, %d, %d, %d>", tn, b, B, vec, H == 1 ? 1 : B);
+        else if (!one_shape(L, es, data) && plan_units(L, D, H, W, B, es, data, &ua, &grid, &lds, &nw))
+            n = snprintf(out, cap, "compress_units<%s, %d, %d>", tn, b, nw);
         else if (flat && plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_wave<%s, %d, %d, %d>", tn, b, B, vec);
         else if (flat && plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))

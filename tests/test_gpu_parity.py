@@ -615,6 +615,9 @@ ROWS_CASES = [
     ((5, 7, 1, 1000), 12, 4),
     ((2, 3, 33, 31), 2, 2),             # tiny blocks: 272 blocks per plane
     ((2, 3, 40, 40), 1, 4),             # B = 1
+    ((6, 10, 20, 20), 12, 2),           # planes below 512 elements stay with this kernel: whole-vector rows,
+    ((5, 8, 21, 21), 6, 4),             # odd rows,
+    ((9, 4, 11, 45), 18, 8),            # wide and flat
 ]
 
 
@@ -674,8 +677,11 @@ def test_general_block_size_kernel_matches_oracle(shape, B, b, mode):
     c16 = mode == "c16"
     name = pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16)
     # block sizes 12 and 16 on planes of whole 4-element units take the register kernel's any-B instance
-    # (1-D maps with power-of-two blocks the one-row kernel)
-    assert name.startswith(("compress_rows<", "compress_line<")) or (name.startswith("compress_regs<") and ", 0, " in name)
+    # (1-D maps with power-of-two blocks the one-row kernel), other planes of 512 elements and more
+    # the register kernel for any width
+    units = shape[2] > 1 and shape[2] * shape[3] >= 512
+    assert (name.startswith(("compress_rows<", "compress_line<")) or (name.startswith("compress_regs<") and ", 0, " in name)
+            or (units and name.startswith("compress_units<")))
     _check_variant(shape, B, b, mode)
 
 
@@ -722,6 +728,48 @@ def test_register_kernel_any_block_size_matches_oracle(shape, B, b, mode):
     one_row_bf16 = shape[2] == 1 and mode == "bf16"            # 2-byte 1-D maps go to the one-row kernel first
     assert (name.startswith("compress_regs<") and ", 0, " in name) or (one_row_bf16 and name.startswith("compress_line<"))
     _check_variant(shape, B, b, mode)
+
+
+# planes whose rows or blocks are not whole 16-byte vectors: the register kernel with a block per element
+UNITS_CASES = [
+    ((2, 3, 55, 55), 8, 2),             # 757 units (the last one holds one element), two wavefronts
+    ((3, 2, 55, 55), 4, 4),             # 784 row segments of 4 (3 at the right edge)
+    ((3, 5, 27, 27), 8, 2),             # 183 units: one wavefront, three rounds
+    ((2, 3, 27, 27), 4, 8),
+    ((2, 2, 147, 147), 8, 2),           # 5403 units: sixteen wavefronts
+    ((1, 3, 149, 149), 4, 4),           # 5476 row segments
+    ((2, 2, 73, 73), 8, 4),             # 1333 units: four wavefronts
+    ((2, 3, 35, 35), 3, 2),             # B = 3: 432 row segments, blocks of 3 and 2
+    ((2, 3, 56, 56), 18, 2),            # rows of whole vectors, blocks of 18, 18, 18, 2
+    ((3, 2, 57, 57), 12, 8),
+    ((2, 2, 30, 34), 18, 2),            # even width that is not a multiple of 4
+    ((2, 2, 163, 163), 8, 2),           # 6643 units, 143 KB of LDS: about the largest plane the kernel takes
+    ((2, 2, 33, 61), 5, 4),
+    ((4, 3, 23, 23), 64, 2),            # one block per plane with an odd element count
+]
+
+
+@pytest.mark.parametrize("shape,B,b", UNITS_CASES)
+@pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
+def test_register_kernel_any_width_matches_oracle(shape, B, b, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    assert pkg.division_kernel_name(0, shape, B, b, dtype, c16=mode == "c16").startswith("compress_units<")
+    _check_variant(shape, B, b, mode)
+
+
+# more planes than workgroups: a workgroup takes every grid-th plane, the next one's loads in flight
+@pytest.mark.parametrize("shape,B,b", [((21, 100, 55, 55), 8, 2), ((3, 100, 147, 147), 8, 2), ((42, 100, 27, 27), 4, 4),
+                                        ((3, 1001, 35, 35), 8, 2)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_register_kernel_any_width_many_planes(shape, B, b, dtype):
+    assert pkg.division_kernel_name(0, shape, B, b, dtype).startswith("compress_units<")
+    x = _relu_normal(shape, 4242 + shape[1], dtype)
+    xh, _ = to_host_array(x)
+    dt = oracle.BF16 if dtype == torch.bfloat16 else oracle.F32
+    ref = oracle.compress(xh, B, b, 99, dt, threads=16)
+    pk = pkg.division_compress(x.to("cuda:0"), B, b, 99)
+    torch.cuda.synchronize()
+    assert np.array_equal(pk.cpu().numpy(), ref)
 
 
 def _check_variant(shape, B, b, mode):
