@@ -34,7 +34,10 @@
 //   compress_any     everything else (giant planes with odd extents): scalar, slow
 //   decompress_rowvec / _table / _words / _flat / _lane / _scalar: streaming, the packed slice of a
 //                    workgroup staged in LDS, one 16-byte non-temporal store per lane step (_words:
-//                    odd widths, the chunk rebuilt in LDS word by word first)
+//                    small planes of odd width, the chunk rebuilt in LDS word by word first)
+//   decompress_units the counterpart of compress_units (odd widths from 512 elements per plane up): four
+//                    consecutive elements per lane step, block table made once per workgroup, the next
+//                    plane's codes and LFC in flight
 // The kernels with a _3d twin take N x C x D x H x W maps with B x B x B blocks (Appendix D).
 // Every kernel takes a table of up to 8 maps of one shape (blockIdx.y picks the map).
 // Element / cache types: float, bf16_t, f32c16_t (fp32 map, tuple cached as bfloat16).
@@ -2930,6 +2933,104 @@ __global__ void __launch_bounds__(kThreads) decompress_words(DecArgs a) { decomp
 template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) decompress_words_3d(DecArgs a) { decompress_words_body<T, BITS, 3>(a); }
 
+// 2-D planes whose rows or blocks are not whole vectors (odd widths), the counterpart of compress_units:
+// a lane step rebuilds four consecutive elements of the plane whatever the width and writes them with
+// one store (planes start on 4-byte boundaries).  Which block each element belongs to is the same for
+// every plane: a table of LDS offsets made once per workgroup, which then takes planes blockIdx.x,
+// blockIdx.x + gridDim.x, ...  A plane's LFC goes through LDS (two buffers, one barrier per plane);
+// the next plane's codes, LFC and meta are loaded while the current one is rebuilt.
+constexpr int kUnitsLfc = 4;      // LFC values a lane stages per plane: planes of up to 4 * threads blocks
+template <typename T, int BITS, int NW>
+__global__ void __launch_bounds__(64 * NW) decompress_units(DecArgs a) {
+    constexpr int NT = 64 * NW;
+    constexpr int K = kUnitsK;
+    constexpr int KL = kUnitsLfc;
+    constexpr uint32_t CB = BITS / 2;                  // code bytes per unit
+    constexpr uint32_t Lq = (1u << BITS) - 1u;
+    extern __shared__ float4 smem4[];
+    float* lbuf = reinterpret_cast<float*>(smem4);     // [2][nbp]
+    const uint32_t nbp = (a.nb + 3u) & ~3u;
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
+    const uint32_t tid = threadIdx.x;
+    auto round_live = [&](int k) -> bool { return (uint32_t)(NT * k) < a.q4; };
+
+    // LDS byte offset of the LFC of each element's block (elements past the plane: block 0, never stored)
+    uint32_t lo[K][2];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        uint32_t off[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t e = 4u * (tid + NT * k) + j;
+            const uint32_t r = fdiv(e, a.d_W);
+            const uint32_t c = e - r * a.W;
+            off[j] = e < a.HW ? 4u * (fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B)) : 0u;
+        }
+        lo[k][0] = off[0] | (off[1] << 16);
+        lo[k][1] = off[2] | (off[3] << 16);
+    }
+    const uint32_t tail = a.HW & 3u;                   // elements of the last unit inside the plane (0: all four)
+
+    uint32_t codes[K];
+    float lf[KL];
+    float2 dd;
+    auto issue_loads = [&](uint32_t p) {
+        const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint32_t*>(pt.codes) + (size_t)p * a.WPP, 0, (int)(a.q4 * CB), 0x00020000);
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            if (!round_live(k)) continue;
+            if constexpr (CB == 1) codes[k] = __builtin_amdgcn_raw_buffer_load_b8(crs, tid, k * NT, 0);
+            else if constexpr (CB == 2) codes[k] = __builtin_amdgcn_raw_buffer_load_b16(crs, tid * 2u, k * NT * 2, 0);
+            else codes[k] = __builtin_amdgcn_raw_buffer_load_b32(crs, tid * 4u, k * NT * 4, 0);
+        }
+#pragma unroll
+        for (int m = 0; m < KL; ++m) {
+            const uint32_t t = tid + NT * m;
+            if ((uint32_t)(NT * m) < a.nb) lf[m] = t < a.nb ? lfc_load<T>(pt.lfc, (size_t)p * a.nb + t, kC16<T>) : 0.0f;
+        }
+        dd = meta_load(pt.meta, p, kC16<T>);
+    };
+
+    if (blockIdx.x < a.P) issue_loads(blockIdx.x);
+    uint32_t flip = 0;
+    for (uint32_t p = blockIdx.x; p < a.P; p += gridDim.x, flip ^= 1u) {
+        float* lfcs = lbuf + flip * nbp;
+#pragma unroll
+        for (int m = 0; m < KL; ++m) {
+            const uint32_t t = tid + NT * m;
+            if ((uint32_t)(NT * m) < a.nb && t < a.nb) lfcs[t] = lf[m];
+        }
+        uint32_t c4[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) c4[k] = round_live(k) ? codes[k] : 0u;
+        const float2 sc = dd;
+        if (p + gridDim.x < a.P) issue_loads(p + gridDim.x);
+        if constexpr (NW == 1) wave_sync(); else lds_barrier();
+
+        T* out = static_cast<T*>(pt.xhat) + (size_t)p * a.HW;
+        const char* lb = reinterpret_cast<const char*>(lfcs);
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            if (!round_live(k)) continue;
+            const uint32_t f = tid + NT * k;
+            float o[4];
+            o[0] = dequant(c4[k] & Lq, sc.y, sc.x, *reinterpret_cast<const float*>(lb + (lo[k][0] & 0xffffu)));
+            o[1] = dequant((c4[k] >> BITS) & Lq, sc.y, sc.x, *reinterpret_cast<const float*>(lb + (lo[k][0] >> 16)));
+            o[2] = dequant((c4[k] >> (2 * BITS)) & Lq, sc.y, sc.x, *reinterpret_cast<const float*>(lb + (lo[k][1] & 0xffffu)));
+            o[3] = dequant((c4[k] >> (3 * BITS)) & Lq, sc.y, sc.x, *reinterpret_cast<const float*>(lb + (lo[k][1] >> 16)));
+            if (4u * f + 4u <= a.HW) {
+                store4(out, (size_t)f * 4, o[0], o[1], o[2], o[3]);
+            } else if (4u * f < a.HW) {
+                // the plane's last unit when H*W is not a multiple of 4: element by element
+#pragma unroll
+                for (uint32_t e = 0; e < 3; ++e)
+                    if (e < tail) Elem<T>::store(out, (size_t)f * 4 + e, o[e]);
+            }
+        }
+    }
+}
+
 // planes too large for the 32-bit index tricks above: one element per thread step
 template <typename T, int BITS, int ND>
 __device__ __forceinline__ void decompress_scalar_body(const DecArgs& a) {
@@ -3615,6 +3716,23 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
             return 3;
         }
     }
+    // 2-D planes of 512 elements and more whose rows or blocks are not whole vectors: four consecutive
+    // elements per lane step, planes starting on 4-byte boundaries
+    if (D == 1 && Hs > 1 && small_idx && ((uintptr_t)xhat % 4) == 0 && (L.HW * es) % 4 == 0 && L.nb <= 16383) {
+        const uint64_t q4 = (L.HW + 3) / 4;
+        int nw = 1;
+        while (nw < 16 && (q4 > (uint64_t)kUnitsK * 64 * nw || L.nb > (uint64_t)kUnitsLfc * 64 * nw)) nw *= 2;
+        const uint64_t nt = 64ull * nw;
+        if (q4 >= kUnitsMin && q4 <= (uint64_t)kUnitsK * nt && L.nb <= (uint64_t)kUnitsLfc * nt &&
+            fastdiv_ok(4ull * kUnitsK * nt + 4, (uint64_t)W) && fastdiv_ok(4ull * kUnitsK * nt + 4, (uint64_t)B)) {
+            a->q4 = (uint32_t)q4;
+            a->G = (uint32_t)nw;                  // wavefronts per workgroup
+            uint64_t g = (uint64_t)num_cus() * (16ull / nw);
+            g += g & 1;
+            *grid = (uint32_t)(g < L.P ? g : L.P);
+            return 6;
+        }
+    }
     // several blocks per plane, rows not whole vectors: rebuilt in LDS word by word
     if (L.nb > 1 && small_idx && out_vec_aligned && fastdiv_ok(L.HW, (uint64_t)W)) {
         const uint64_t unit = 4 / gcd_u64(4, L.HW);
@@ -3662,7 +3780,7 @@ struct CompLaunch {
     TileArgs a; WaveArgs wa; RegsArgs ra; ItemsArgs ia; LaneArgs la; RowsArgs wa2; PlaneArgs pa; OneArgs oa; AnyArgs g; UnitsArgs ua;
 };
 struct DecLaunch {
-    int kind, flat;
+    int kind, flat, nw;
     uint32_t gx, gy;
     size_t lds;
     hipStream_t st;
@@ -3715,6 +3833,13 @@ hipError_t do_decompress(const DecLaunch& c, int b) {
         constexpr int BITS = decltype(bits)::value;
         const int kind = c.kind;
         void (*kern)(DecArgs);
+        if (kind == 6) {
+            kern = c.nw == 1 ? decompress_units<T, BITS, 1> : c.nw == 2 ? decompress_units<T, BITS, 2>
+                 : c.nw == 4 ? decompress_units<T, BITS, 4> : c.nw == 8 ? decompress_units<T, BITS, 8>
+                                                                        : decompress_units<T, BITS, 16>;
+            hipLaunchKernelGGL(kern, dim3(c.gx, c.gy), dim3(64 * c.nw), c.lds, c.st, c.a);
+            return hipGetLastError();
+        }
         if (c.flat)
             kern = kind == 0 ? decompress_rowvec<T, BITS> : kind == 3 ? decompress_table<T, BITS>
                  : kind == 5 ? decompress_words<T, BITS> : kind == 1 ? decompress_flat<T, BITS>
@@ -3887,10 +4012,11 @@ int decompress_impl(int count, const void* const* packed, void* const* xhat, siz
         // LDS of the streaming kernels: staged codes, meta and LFC of G planes (+ the block table)
         size_t lds = 0;
         if (kind == 4) lds = 4ull * (64ull * L.HW + 4);
+        else if (kind == 6) lds = 8ull * ((L.nb + 3) & ~3ull);
         else if (kind == 5) lds = a.out_off + 4ull * ((a.G * L.HW + 3) & ~3ull);
         else if (kind != 2) lds = dec_lds_bytes(L, es, a.G) + (kind == 3 ? 4ull * a.q4 + 16 : 0);
         DecLaunch c{};
-        c.kind = kind; c.flat = D == 1; c.gx = grid; c.gy = (uint32_t)cnt; c.lds = lds; c.st = st; c.a = a;
+        c.kind = kind; c.flat = D == 1; c.nw = kind == 6 ? (int)a.G : 0; c.gx = grid; c.gy = (uint32_t)cnt; c.lds = lds; c.st = st; c.a = a;
         if (bridge_decompress(dt, c, b) != hipSuccess) return DIVISION_EHIP;
     }
     return DIVISION_OK;
@@ -3938,8 +4064,11 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     } else {
         DecArgs a{}; uint32_t grid = 0;
         const int kind = plan_decompress(L, D, H, W, B, es, data, &a, &grid);
-        n = snprintf(out, cap, "%s%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 3 ? "decompress_table" : kind == 5 ? "decompress_words" : kind == 1 ? "decompress_flat" : kind == 4 ? "decompress_lane" : "decompress_scalar",
-                     kind == 4 ? "" : sfx, tn, b);
+        if (kind == 6)
+            n = snprintf(out, cap, "decompress_units<%s, %d, %d>", tn, b, (int)a.G);
+        else
+            n = snprintf(out, cap, "%s%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 3 ? "decompress_table" : kind == 5 ? "decompress_words" : kind == 1 ? "decompress_flat" : kind == 4 ? "decompress_lane" : "decompress_scalar",
+                         kind == 4 ? "" : sfx, tn, b);
     }
     return (n < 0 || (size_t)n >= cap) ? DIVISION_ESIZE : DIVISION_OK;
 }

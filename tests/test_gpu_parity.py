@@ -746,6 +746,8 @@ UNITS_CASES = [
     ((2, 2, 163, 163), 8, 2),           # 6643 units, 143 KB of LDS: about the largest plane the kernel takes
     ((2, 2, 33, 61), 5, 4),
     ((4, 3, 23, 23), 64, 2),            # one block per plane with an odd element count
+    ((3, 3, 26, 45), 8, 2),             # odd width, even element count: 2-byte planes start on 4-byte boundaries
+    ((2, 3, 38, 75), 4, 4),             # H*W % 4 == 2: the last unit holds two elements
 ]
 
 
@@ -754,6 +756,8 @@ UNITS_CASES = [
 def test_register_kernel_any_width_matches_oracle(shape, B, b, mode):
     dtype = torch.bfloat16 if mode == "bf16" else torch.float32
     assert pkg.division_kernel_name(0, shape, B, b, dtype, c16=mode == "c16").startswith("compress_units<")
+    if shape[3] % 2 == 1 and (mode != "bf16" or shape[2] % 2 == 0):      # planes that start on 4-byte boundaries
+        assert pkg.division_kernel_name(1, shape, B, b, dtype, c16=mode == "c16").startswith("decompress_units<")
     _check_variant(shape, B, b, mode)
 
 
@@ -768,8 +772,11 @@ def test_register_kernel_any_width_many_planes(shape, B, b, dtype):
     dt = oracle.BF16 if dtype == torch.bfloat16 else oracle.F32
     ref = oracle.compress(xh, B, b, 99, dt, threads=16)
     pk = pkg.division_compress(x.to("cuda:0"), B, b, 99)
+    y = pkg.division_decompress(pk, shape, B, b, dtype)
     torch.cuda.synchronize()
     assert np.array_equal(pk.cpu().numpy(), ref)
+    yh, _ = to_host_array(y.cpu())
+    assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt))
 
 
 def _check_variant(shape, B, b, mode):
