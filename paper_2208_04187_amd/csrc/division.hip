@@ -2954,14 +2954,20 @@ __global__ void __launch_bounds__(64 * NW) decompress_units(DecArgs a) {
     const uint32_t tid = threadIdx.x;
     auto round_live = [&](int k) -> bool { return (uint32_t)(NT * k) < a.q4; };
 
-    // LDS byte offset of the LFC of each element's block (elements past the plane: block 0, never stored)
+    // 2-byte elements, odd planes of an odd element count: the plane starts in the middle of a dword.
+    // Its units then start one element early, so that every store is dword-aligned; the element before
+    // the plane and those past it are left alone.  The same for all planes of the workgroup: the grid is
+    // even then, or every workgroup has one plane.
+    const uint32_t shift = sizeof(T) == 2 ? (blockIdx.x * a.HW) & 1u : 0u;
+
+    // LDS byte offset of the LFC of each element's block (elements outside the plane: block 0, never stored)
     uint32_t lo[K][2];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         uint32_t off[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint32_t e = 4u * (tid + NT * k) + j;
+            const uint32_t e = 4u * (tid + NT * k) + j - shift;       // wraps for the element before the plane
             const uint32_t r = fdiv(e, a.d_W);
             const uint32_t c = e - r * a.W;
             off[j] = e < a.HW ? 4u * (fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B)) : 0u;
@@ -2969,17 +2975,31 @@ __global__ void __launch_bounds__(64 * NW) decompress_units(DecArgs a) {
         lo[k][0] = off[0] | (off[1] << 16);
         lo[k][1] = off[2] | (off[3] << 16);
     }
-    const uint32_t tail = a.HW & 3u;                   // elements of the last unit inside the plane (0: all four)
-
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     uint32_t codes[K];
+    u32x2 wide[sizeof(T) == 2 ? K : 1];                // shifted units: the two code words a unit's codes lie in
     float lf[KL];
     float2 dd;
     auto issue_loads = [&](uint32_t p) {
         const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint32_t*>(pt.codes) + (size_t)p * a.WPP, 0, (int)(a.q4 * CB), 0x00020000);
+        if constexpr (sizeof(T) == 2) {
+            if (shift) {
+                // codes of elements 4f-1 .. 4f+2: 4 * BITS bits from bit (4f-1) * BITS of the plane's code words
+                const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<uint32_t*>(pt.codes) + (size_t)p * a.WPP, 0, (int)(a.WPP * 4u), 0x00020000);
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    if (!round_live(k)) continue;
+                    const uint32_t f = tid + NT * k;
+                    const uint32_t bit = f ? (4u * f - 1u) * BITS : 0u;
+                    wide[k] = __builtin_amdgcn_raw_buffer_load_b64(wrs, (bit >> 5) * 4u, 0, 0);
+                }
+            }
+        }
 #pragma unroll
         for (int k = 0; k < K; ++k) {
-            if (!round_live(k)) continue;
+            if (!round_live(k) || shift) continue;
             if constexpr (CB == 1) codes[k] = __builtin_amdgcn_raw_buffer_load_b8(crs, tid, k * NT, 0);
             else if constexpr (CB == 2) codes[k] = __builtin_amdgcn_raw_buffer_load_b16(crs, tid * 2u, k * NT * 2, 0);
             else codes[k] = __builtin_amdgcn_raw_buffer_load_b32(crs, tid * 4u, k * NT * 4, 0);
@@ -3003,12 +3023,25 @@ __global__ void __launch_bounds__(64 * NW) decompress_units(DecArgs a) {
         }
         uint32_t c4[K];
 #pragma unroll
-        for (int k = 0; k < K; ++k) c4[k] = round_live(k) ? codes[k] : 0u;
+        for (int k = 0; k < K; ++k) {
+            c4[k] = 0u;
+            if (!round_live(k)) continue;
+            if constexpr (sizeof(T) == 2) {
+                if (shift) {
+                    const uint32_t f = tid + NT * k;
+                    const uint32_t bit = f ? (4u * f - 1u) * BITS : 0u;
+                    const uint32_t c = __builtin_amdgcn_alignbit(wide[k].y, wide[k].x, bit & 31u);
+                    c4[k] = f ? c : c << BITS;             // unit 0: the slot before the plane, then elements 0, 1, 2
+                    continue;
+                }
+            }
+            c4[k] = codes[k];
+        }
         const float2 sc = dd;
         if (p + gridDim.x < a.P) issue_loads(p + gridDim.x);
         if constexpr (NW == 1) wave_sync(); else lds_barrier();
 
-        T* out = static_cast<T*>(pt.xhat) + (size_t)p * a.HW;
+        T* out = static_cast<T*>(pt.xhat) + (size_t)p * a.HW;       // element e of the plane at out[e]
         const char* lb = reinterpret_cast<const char*>(lfcs);
 #pragma unroll
         for (int k = 0; k < K; ++k) {
@@ -3019,13 +3052,17 @@ __global__ void __launch_bounds__(64 * NW) decompress_units(DecArgs a) {
             o[1] = dequant((c4[k] >> BITS) & Lq, sc.y, sc.x, *reinterpret_cast<const float*>(lb + (lo[k][0] >> 16)));
             o[2] = dequant((c4[k] >> (2 * BITS)) & Lq, sc.y, sc.x, *reinterpret_cast<const float*>(lb + (lo[k][1] & 0xffffu)));
             o[3] = dequant((c4[k] >> (3 * BITS)) & Lq, sc.y, sc.x, *reinterpret_cast<const float*>(lb + (lo[k][1] >> 16)));
-            if (4u * f + 4u <= a.HW) {
-                store4(out, (size_t)f * 4, o[0], o[1], o[2], o[3]);
-            } else if (4u * f < a.HW) {
-                // the plane's last unit when H*W is not a multiple of 4: element by element
+            const uint32_t e0 = 4u * f - shift;                  // the unit's first element (wraps for unit 0 of a shifted plane)
+            if (e0 + 4u <= a.HW && (shift == 0u || f != 0u)) {
+                store4(out - shift, (size_t)f * 4, o[0], o[1], o[2], o[3]);
+            } else {
+                // a unit that reaches outside the plane (the last one when H*W is not a multiple of 4,
+                // the first one of a shifted plane): element by element
 #pragma unroll
-                for (uint32_t e = 0; e < 3; ++e)
-                    if (e < tail) Elem<T>::store(out, (size_t)f * 4 + e, o[e]);
+                for (uint32_t j = 0; j < 4; ++j) {
+                    const uint32_t e = e0 + j;
+                    if (e < a.HW) Elem<T>::store(out, e, o[j]);
+                }
             }
         }
     }
@@ -3718,7 +3755,7 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
     }
     // 2-D planes of 512 elements and more whose rows or blocks are not whole vectors: four consecutive
     // elements per lane step, planes starting on 4-byte boundaries
-    if (D == 1 && Hs > 1 && small_idx && ((uintptr_t)xhat % 4) == 0 && (L.HW * es) % 4 == 0 && L.nb <= 16383) {
+    if (D == 1 && Hs > 1 && small_idx && ((uintptr_t)xhat % 4) == 0 && L.nb <= 16383) {
         const uint64_t q4 = (L.HW + 3) / 4;
         int nw = 1;
         while (nw < 16 && (q4 > (uint64_t)kUnitsK * 64 * nw || L.nb > (uint64_t)kUnitsLfc * 64 * nw)) nw *= 2;
