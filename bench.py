@@ -250,12 +250,18 @@ VARIANTS = [
     ("3-D map", (32, 64, 16, 56, 56), 8, 2), ("3-D map", (32, 128, 8, 28, 28), 8, 2), ("3-D map", (32, 256, 4, 14, 14), 8, 2),
     ("3-D map", (32, 512, 2, 7, 7), 8, 2), ("3-D map", (64, 64, 16, 16, 16), 8, 2), ("3-D map", (64, 64, 16, 16, 16), 4, 2),
     ("large plane", (64, 3, 224, 224), 8, 2), ("large plane", (64, 16, 224, 224), 8, 2),
+    # odd widths: AlexNet's 55 x 55, 27 x 27 and 13 x 13 at batch 256, Inception-v3's 147, 73, 35 and 17 at batch 64 / 128
+    ("odd width", (256, 96, 55, 55), 8, 2), ("odd width", (256, 96, 55, 55), 4, 4), ("odd width", (256, 256, 27, 27), 8, 2),
+    ("odd width", (256, 384, 13, 13), 8, 2), ("odd width", (64, 64, 147, 147), 8, 2), ("odd width", (64, 96, 73, 73), 8, 2),
+    ("odd width", (128, 288, 35, 35), 8, 2), ("odd width", (128, 768, 17, 17), 8, 2),
+    ("odd width, block size 18", (256, 96, 55, 55), 18, 2),
 ]
 
 
 def variants(args, torch, pkg, dev) -> int:
     """Single-call compress and decompress rates of the parameter and shape variants outside the headline
-    workload: the block sizes and code widths of the paper's sweep, 1-D and 3-D maps (Appendix D)."""
+    workload: the block sizes and code widths of the paper's sweep, 1-D and 3-D maps (Appendix D), image-sized
+    planes and planes of odd width."""
     nsets = max(3, args.sets)
     reps = max(20, args.steps or 20)
 
