@@ -3366,7 +3366,6 @@ hipError_t launch_units(int nw, const UnitsArgs& a, dim3 grid, size_t lds, hipSt
     return hipGetLastError();
 }
 
-// Fills the one-wavefront compress plan; false when the shape is not covered.
 // one-block planes with an odd element count: the shapes the lane-per-plane kernels take
 bool lane_shape(const Layout& L) { return L.nb == 1 && (L.HW & 1) == 1 && L.HW <= 64; }
 
@@ -3428,6 +3427,7 @@ hipError_t launch_items(int B, int vec, const ItemsArgs& a, dim3 grid, size_t ld
     return hipGetLastError();
 }
 
+// Fills the one-wavefront compress plan; false when the shape is not covered.
 bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, const void* x,
                WaveArgs* a, uint32_t* grid, size_t* lds, int* vec_out) {
     if (B != 4 && B != 8) return false;
@@ -3479,7 +3479,6 @@ bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
     return true;
 }
 
-// Fills the any-block-size compress plan; false when a plane does not fit LDS or the 32-bit index tricks.
 // Fills the one-block plan: the block covers the plane, which is whole 16-byte vectors, at most
 // kOneUnits per lane of a wavefront.
 bool plan_one(const Layout& L, size_t es, const void* x, OneArgs* a, uint32_t* grid) {
@@ -3542,6 +3541,7 @@ bool plan_line(const Layout& L, int64_t D, int64_t H, int B, size_t es, const vo
 // elements (it loads 16 bytes per lane, the register kernel 8); for fp32 the register kernel is (by 5-10 %)
 bool line_first(const Layout& L, size_t es) { return es == 2 || L.HW / 4 < 512; }
 
+// Fills the any-block-size compress plan; false when a plane does not fit LDS or the 32-bit index tricks.
 // Hs = rows of one depth slice, D = depth slices (1 for a 2-D map).
 bool plan_rows(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, int b, size_t es, const void* x,
                RowsArgs* a, uint32_t* grid, size_t* lds) {
@@ -3675,8 +3675,6 @@ bool plan_tile(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
     return *lds <= kLdsMax;
 }
 
-// Fills the decompress launch plan; returns 0 (row vectors), 3 (block table), 5 (word by word through
-// LDS), 1 (flat), 4 (lane per plane) or 2 (scalar).
 // LDS bytes of the streaming decompress kernels for G planes per workgroup
 size_t dec_lds_bytes(const Layout& L, size_t es, uint64_t G) {
     return 4ull * ((G * L.WPP + 3) & ~(uint64_t)3) + 8ull * G + es * G * L.nb + 16;
@@ -3703,6 +3701,8 @@ uint64_t dec_planes(const Layout& L, size_t es, uint64_t mult) {
     return G;
 }
 
+// Fills the decompress launch plan; returns 0 (row vectors), 3 (block table), 6 (four consecutive elements
+// per lane step, any width), 5 (word by word through LDS), 1 (flat), 4 (lane per plane) or 2 (scalar).
 // Hs = rows of one depth slice, D = depth slices (1 for a 2-D map; the table kernel takes 2-D maps only).
 int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, size_t es, const void* xhat,
                     DecArgs* a, uint32_t* grid) {
