@@ -21,7 +21,7 @@
 //   compress_lane    one-block planes with an odd element count (7x7): a lane per plane
 //   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8: a lane
 //                    per pooling item, loaded straight from global memory, DPP reductions
-//   compress_units   2-D planes of 512 to about 27K elements whose rows or blocks are not whole 16-byte vectors
+//   compress_units   2-D planes of 256 to about 27K elements whose rows or blocks are not whole 16-byte vectors
 //                    (odd widths: 27x27, 55x55, 147x147; B = 18): four consecutive elements per lane step
 //                    whatever the width, the block of each element looked up in a table made once per
 //                    workgroup, the plane parked in LDS for the block sums, next plane's loads in flight
@@ -1510,41 +1510,62 @@ struct UnitsArgs {
     Regions rg;
     uint32_t P, H, W, HW, LW, nb, WPP, B;
     uint32_t q4;         // units (4 consecutive elements) per plane, the last one may be partly past it
-    uint32_t q4p;        // q4 rounded up to whole rounds of the workgroup's lanes
+    uint32_t q4p;        // q4 rounded up to whole rounds of the plane's lanes
     uint32_t nitem;      // nb * B row segments
+    uint32_t S, S_log2;  // instance NW = 0: lanes per plane (8, 16 or 32), 64 / S planes per wavefront
+    uint32_t reg_bytes;  // LDS bytes of one plane's region (a multiple of 16)
+    uint32_t nrounds;    // rounds of planes the grid walks over: P, or P / (64 / S) rounded up (NW = 0)
     FastDiv d_W, d_B, d_LW;
 };
 
 // Planes whose rows or blocks are not whole 16-byte vectors (odd widths: 55 x 55, 27 x 27,
 // 147 x 147; block sizes such as 18): the register kernel's structure with the block found per
 // element instead of per unit.  A unit is four consecutive elements of the plane whatever the
-// width (planes start on 4-byte boundaries, which is all a 16-byte buffer load needs), lane `tid`
-// keeps units tid, tid+NT, ... in registers from the load to the codes, and which block each
-// element belongs to is the same for every plane: worked out once per workgroup and kept as the
-// LDS byte offset of the block's LFC, two offsets per register.  Block sums: the plane is also
-// parked in LDS; a lane per (block, row of the block) adds its row segment in binary64 (lanes of
-// one block read rows W floats apart: no bank conflicts for odd W), a lane per block adds its
-// rows.  Elements of the last unit past the plane take the NaN sentinel like whole units past it.
+// width (planes start on 4-byte boundaries, which is all a 16-byte buffer load needs); lane l of
+// the S lanes of a plane takes units l, l+S, ...  Which block each element belongs to is the same
+// for every plane: worked out once per workgroup and kept as the LDS byte offset of the block's
+// LFC, two offsets per register.  The plane is parked in LDS (the next plane's loads go out right
+// after and fly during the rest); a lane per (block, row of the block) adds its row segment in
+// binary64 (lanes of one block read rows W floats apart: no bank conflicts for odd W), a lane per
+// block adds its rows; the residual goes back to LDS and is quantised from there.  Elements of
+// the last unit past the plane take the NaN sentinel like whole units past it.
+// NW = 1 .. 16: the NW wavefronts of the workgroup share one plane (S = 64 * NW).  NW = 0: small
+// planes (below 512 elements), S = 8, 16 or 32 lanes per plane and 64 / S planes per wavefront,
+// each with its own LDS region; reductions stay inside the S lanes.
 constexpr int kUnitsK = 8;        // units, and row segments, per lane
 
 template <typename T, int BITS, int NW>
-__global__ void __launch_bounds__(64 * NW) compress_units(UnitsArgs a) {
-    constexpr int NT = 64 * NW;
+__global__ void __launch_bounds__(NW ? 64 * NW : 64) compress_units(UnitsArgs a) {
+    constexpr bool SUB = NW == 0;
+    constexpr int NT = SUB ? 64 : 64 * NW;
     constexpr int K = kUnitsK;
     constexpr float Lf = float((1 << BITS) - 1);
+    constexpr uint32_t UB = 4 * sizeof(T);                                 // bytes of a unit in x
     typedef uint32_t raw_t __attribute__((ext_vector_type(sizeof(T))));     // a unit as loaded: 16 or 8 bytes
+    const uint32_t tid = threadIdx.x;
+    const uint32_t S = SUB ? a.S : (uint32_t)NT;                          // lanes per plane
+    const uint32_t l = SUB ? tid & (S - 1u) : tid;                        // lane among them
+    const uint32_t g = SUB ? tid >> a.S_log2 : 0u;                        // which plane of the round
+    const uint32_t G = SUB ? 64u >> a.S_log2 : 1u;                        // planes per round
     extern __shared__ float4 smem4[];
-    float4* xs4 = smem4;                                                  // [q4p] the plane, later its residual
-    float* xs = reinterpret_cast<float*>(smem4);
+    char* region = reinterpret_cast<char*>(smem4) + g * a.reg_bytes;
+    float4* xs4 = reinterpret_cast<float4*>(region);                      // [q4p] the plane, later its residual
+    float* xs = reinterpret_cast<float*>(region);
     double* rsum = reinterpret_cast<double*>(xs + 4 * a.q4p);             // [nitem] row-segment sums
     float* lfcs = reinterpret_cast<float*>(rsum + a.nitem);               // [nb + 1], last = NaN sentinel
     float* red = lfcs + ((a.nb + 1 + 3) & ~3u);                           // [2*NW] cross-wave min / max
-
-    const uint32_t tid = threadIdx.x;
     const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
+    auto sync = [&]() { if constexpr (NW <= 1) wave_sync(); else lds_barrier(); };
     // rounds of units a plane has (uniform); units of the last round past the plane are worked on like
-    // the others: they load zeros, take the NaN sentinel, and their code stores are dropped
-    auto round_live = [&](int k) -> bool { return (uint32_t)(NT * k) < a.q4; };
+    // the others: they load zeros or a neighbour's elements and take the NaN sentinel
+    auto round_live = [&](int k) -> bool { return S * (uint32_t)k < a.q4; };
+
+    // 2-byte elements, odd planes of an odd element count: the plane starts in the middle of a dword.
+    // Its loads then start one element early (every load stays dword-aligned and inside dwords that hold
+    // elements of the map) and land in LDS one element lower.  The same for all planes a lane works on:
+    // the grid is even or every workgroup has one plane (NW >= 1); a round is an even number of planes (NW = 0).
+    const uint32_t shift = sizeof(T) == 2 ? ((blockIdx.x * G + g) * a.HW) & 1u : 0u;
+    const uint32_t shift0 = SUB ? 0u : shift;                             // of the round's first plane
 
     // LDS byte offset of the LFC of each element's block (4 * nb = the sentinel for elements past the plane)
     uint32_t lo[K][2];
@@ -1553,7 +1574,7 @@ __global__ void __launch_bounds__(64 * NW) compress_units(UnitsArgs a) {
         uint32_t off[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint32_t e = 4u * (tid + NT * k) + j;
+            const uint32_t e = 4u * (l + S * k) + j;
             const uint32_t r = fdiv(e, a.d_W);
             const uint32_t c = e - r * a.W;
             off[j] = 4u * (e < a.HW ? fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B) : a.nb);
@@ -1566,40 +1587,40 @@ __global__ void __launch_bounds__(64 * NW) compress_units(UnitsArgs a) {
     uint32_t it[K];
 #pragma unroll
     for (int m = 0; m < K; ++m) {
-        const uint32_t i = tid + NT * m;
+        const uint32_t i = l + S * m;
         const uint32_t t = fdiv(i, a.d_B), rr = i - t * a.B;
         const uint32_t bi = fdiv(t, a.d_LW), bj = t - bi * a.LW;
         const uint32_t r = bi * a.B + rr;
         const uint32_t bw = min(a.B, a.W - bj * a.B);
         it[m] = (i < a.nitem && r < a.H) ? (r * a.W + bj * a.B) | (bw << 20) : 0u;
     }
-    if (tid == 0) lfcs[a.nb] = __builtin_nanf("");
+    if (l == 0) lfcs[a.nb] = __builtin_nanf("");
     const uint32_t tail = a.HW & 3u;          // elements of the last unit inside the plane (0: all four)
 
-    // 2-byte elements, odd planes of an odd element count: the plane starts in the middle of a dword.
-    // Its loads then start one element early (every load stays dword-aligned and inside dwords that hold
-    // elements of the map) and land in LDS one element lower.  The same for all planes of the workgroup:
-    // the grid is even then, or every workgroup has one plane.
-    const uint32_t shift = sizeof(T) == 2 ? (blockIdx.x * a.HW) & 1u : 0u;
-
-    // the loads of a plane: coalesced, all in flight at once; dwords past the plane read as zero
+    // the loads of a round of planes: coalesced, all in flight at once; dwords past the round's last
+    // plane read as zero
     raw_t q[K];
-    auto issue_loads = [&](uint32_t p) {
-        const T* src = static_cast<const T*>(pt.x) + ((size_t)p * a.HW - shift);
-        const __amdgpu_buffer_rsrc_t rsrc =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)((((a.HW + shift) * sizeof(T)) + 3u) & ~3u), 0x00020000);
+    auto issue_loads = [&](uint32_t rd) {
+        const uint32_t pf = rd * G;                                      // the round's first plane
+        const uint32_t np = min(G, a.P - pf);
+        const T* src = static_cast<const T*>(pt.x) + ((size_t)pf * a.HW - shift0);
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<T*>(src), 0, (int)((((np * a.HW + shift0) * sizeof(T)) + 3u) & ~3u), 0x00020000);
+        const uint32_t voff = (g * a.HW - (shift - shift0)) * (uint32_t)sizeof(T) + l * UB;
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             if (!round_live(k)) continue;
-            if constexpr (sizeof(T) == 4) q[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, tid * 16u, k * NT * 16, kLoadAux);
-            else q[k] = __builtin_amdgcn_raw_buffer_load_b64(rsrc, tid * 8u, k * NT * 8, kLoadAux);
+            if constexpr (sizeof(T) == 4) q[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, (int)(S * k * UB), kLoadAux);
+            else q[k] = __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff, (int)(S * k * UB), kLoadAux);
         }
     };
 
-    // a workgroup takes planes blockIdx.x, blockIdx.x + gridDim.x, ...: the tables above are made once
-    if (blockIdx.x < a.P) issue_loads(blockIdx.x);
-    for (uint32_t p = blockIdx.x; p < a.P; p += gridDim.x) {
-        // ---- park the plane in LDS as fp32, then start the next plane's loads: they fly while this one is worked on
+    // a workgroup takes rounds blockIdx.x, blockIdx.x + gridDim.x, ...: the tables above are made once
+    if (blockIdx.x < a.nrounds) issue_loads(blockIdx.x);
+    for (uint32_t rd = blockIdx.x; rd < a.nrounds; rd += gridDim.x) {
+        const uint32_t p = rd * G + g;
+        const bool pv = p < a.P;                                          // (NW = 0) the last round may have fewer planes
+        // ---- park the plane in LDS as fp32, then start the next round's loads: they fly while this one is worked on
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             if (!round_live(k)) continue;
@@ -1611,53 +1632,53 @@ __global__ void __launch_bounds__(64 * NW) compress_units(UnitsArgs a) {
                                 __uint_as_float(q[k].y << 16), __uint_as_float(q[k].y & 0xffff0000u));
             }
             if (sizeof(T) == 2 && shift) {
-                float* d = xs + 4u * (tid + NT * k);
-                if (tid + NT * k != 0) d[-1] = v.x;
+                float* d = xs + 4u * (l + S * k);
+                if (l + S * k != 0) d[-1] = v.x;
                 d[0] = v.y; d[1] = v.z; d[2] = v.w;
             } else {
-                xs4[tid + NT * k] = v;
+                xs4[l + S * k] = v;
             }
         }
-        if (p + gridDim.x < a.P) issue_loads(p + gridDim.x);
-        if constexpr (NW == 1) wave_sync(); else lds_barrier();
+        if (rd + gridDim.x < a.nrounds) issue_loads(rd + gridDim.x);
+        sync();
 
         // ---- Sec. 4.1 AveragePooling, step 1: a lane per (block, row) adds the row's elements inside the block
 #pragma unroll
         for (int m = 0; m < K; ++m) {
-            if ((uint32_t)(NT * m) >= a.nitem) continue;
+            if (S * (uint32_t)m >= a.nitem) continue;
             const uint32_t bw = it[m] >> 20;
             const float* src = xs + (it[m] & 0xfffffu);
-            double S = 0.0;
+            double Sr = 0.0;
             uint32_t c = 0;
             for (; c + 8 <= bw; c += 8) {
                 float v[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) v[j] = src[c + j];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) S += (double)v[j];
+                for (int j = 0; j < 8; ++j) Sr += (double)v[j];
             }
             if (c + 4 <= bw) {
                 const float v0 = src[c], v1 = src[c + 1], v2 = src[c + 2], v3 = src[c + 3];
-                S += (double)v0; S += (double)v1; S += (double)v2; S += (double)v3;
+                Sr += (double)v0; Sr += (double)v1; Sr += (double)v2; Sr += (double)v3;
                 c += 4;
             }
-            for (; c < bw; ++c) S += (double)src[c];
-            if (tid + NT * m < a.nitem) rsum[tid + NT * m] = S;
+            for (; c < bw; ++c) Sr += (double)src[c];
+            if (l + S * m < a.nitem) rsum[l + S * m] = Sr;
         }
-        if constexpr (NW == 1) wave_sync(); else lds_barrier();
+        sync();
 
         // ---- step 2: a lane per block adds its rows from the top down
-        for (uint32_t t = tid; t < a.nb; t += NT) {
+        for (uint32_t t = l; t < a.nb; t += S) {
             const uint32_t bi = fdiv(t, a.d_LW), bj = t - bi * a.LW;
             const uint32_t rows = min(a.B, a.H - bi * a.B);
             const uint32_t bw = min(a.B, a.W - bj * a.B);
-            double S = 0.0;
-            for (uint32_t rr = 0; rr < rows; ++rr) S += rsum[t * a.B + rr];
-            const float lfc = lfc_round<T>(mean_of(S, rows * bw), kC16<T>);
+            double Sb = 0.0;
+            for (uint32_t rr = 0; rr < rows; ++rr) Sb += rsum[t * a.B + rr];
+            const float lfc = lfc_round<T>(mean_of(Sb, rows * bw), kC16<T>);
             lfcs[t] = lfc;
-            lfc_store<T>(pt.lfc, (size_t)p * a.nb + t, lfc, kC16<T>);
+            if (pv) lfc_store<T>(pt.lfc, (size_t)p * a.nb + t, lfc, kC16<T>);
         }
-        if constexpr (NW == 1) wave_sync(); else lds_barrier();
+        sync();
 
         // ---- residual H^H = H - UpSampling(H^L), written back over the plane; plane min / max (NaN
         // residuals of elements past the plane are skipped by min / max)
@@ -1666,21 +1687,25 @@ __global__ void __launch_bounds__(64 * NW) compress_units(UnitsArgs a) {
         for (int k = 0; k < K; ++k) {
             if (!round_live(k)) continue;
             const char* lb = reinterpret_cast<const char*>(lfcs);
-            float4 v = xs4[tid + NT * k];
+            float4 v = xs4[l + S * k];
             v.x -= *reinterpret_cast<const float*>(lb + (lo[k][0] & 0xffffu));
             v.y -= *reinterpret_cast<const float*>(lb + (lo[k][0] >> 16));
             v.z -= *reinterpret_cast<const float*>(lb + (lo[k][1] & 0xffffu));
             v.w -= *reinterpret_cast<const float*>(lb + (lo[k][1] >> 16));
-            xs4[tid + NT * k] = v;
+            xs4[l + S * k] = v;
             mn = fminf(fminf(mn, v.x), fminf(v.y, fminf(v.z, v.w)));
             mx = fmaxf(fmaxf(mx, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
         }
-        group_minmax(64, mn, mx);
-        if constexpr (NW > 1) {
-            if ((tid & 63u) == 0) { red[2 * (tid >> 6)] = mn; red[2 * (tid >> 6) + 1] = mx; }
-            lds_barrier();
+        if constexpr (SUB) {
+            group_minmax(S, mn, mx);
+        } else {
+            group_minmax(64, mn, mx);
+            if constexpr (NW > 1) {
+                if ((tid & 63u) == 0) { red[2 * (tid >> 6)] = mn; red[2 * (tid >> 6) + 1] = mx; }
+                lds_barrier();
 #pragma unroll
-            for (int w = 0; w < NW; ++w) { mn = fminf(mn, red[2 * w]); mx = fmaxf(mx, red[2 * w + 1]); }
+                for (int w = 0; w < NW; ++w) { mn = fminf(mn, red[2 * w]); mx = fmaxf(mx, red[2 * w + 1]); }
+            }
         }
 
         // ---- scale of Eq. (quantization), keys, meta
@@ -1689,36 +1714,40 @@ __global__ void __launch_bounds__(64 * NW) compress_units(UnitsArgs a) {
         const float invs = inv * (float)(1u << (32 - BITS));
         const uint32_t k1 = mix32(p ^ pt.seed_a);
         const uint32_t k2 = mix32(k1 + pt.seed_c);
-        if (tid == 0) meta_store(pt.meta, p, delta, Delta, kC16<T>);
+        if (l == 0 && pv) meta_store(pt.meta, p, delta, Delta, kC16<T>);
 
         // ---- Quant + packing: a unit is two element pairs = 4 codes; a lane reads back the residuals it wrote
         {
             const uint32_t rscale = 1u << (16 - BITS);
             constexpr uint32_t CB = BITS / 2;                         // code bytes per unit (1, 2 or 4)
-            uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)p * a.WPP * 4;
-            const __amdgpu_buffer_rsrc_t crs =
-                __builtin_amdgcn_make_buffer_rsrc(cbase, 0, (int)(a.q4 * CB), 0x00020000);
-            const uint32_t xw0 = k1 + (2u * tid) * kWeyl;
+            // NW >= 1: the buffer ends with the plane's last unit, so that stores of units past the plane
+            // are dropped; NW = 0: it ends with the round's last plane, units past a plane are skipped
+            const uint32_t pf = rd * G;
+            uint8_t* cround = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)pf * a.WPP * 4;
+            const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(
+                cround, 0, (int)(SUB ? min(G, a.P - pf) * a.WPP * 4u : a.q4 * CB), 0x00020000);
+            const uint32_t cvoff = g * a.WPP * 4u + l * CB;
+            const uint32_t xw0 = k1 + (2u * l) * kWeyl;
             const uint32_t tailmask = tail ? (1u << (tail * BITS)) - 1u : 0xffffffffu;
 #pragma unroll
             for (int k = 0; k < K; ++k) {
                 if (!round_live(k)) continue;
-                const float4 v = xs4[tid + NT * k];
-                const uint32_t xw = xw0 + (uint32_t)(2 * NT * k) * kWeyl;
+                const float4 v = xs4[l + S * k];
+                const uint32_t xw = xw0 + (2u * S * (uint32_t)k) * kWeyl;
                 uint32_t c = push_pair<BITS>(0u, v.z, v.w, delta, invs, xw + kWeyl, k2, rscale);
                 c = push_pair<BITS>(c, v.x, v.y, delta, invs, xw, k2, rscale);
-                // the last unit's elements past the plane leave zero bits; stores of units past the plane are
-                // dropped by the buffer bound
-                if (tid + NT * k + 1 == a.q4) c &= tailmask;
-                if constexpr (CB == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, tid, k * NT, 0);
-                else if constexpr (CB == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c, crs, tid * 2u, k * NT * 2, 0);
-                else __builtin_amdgcn_raw_buffer_store_b32(c, crs, tid * 4u, k * NT * 4, 0);
+                // the last unit's elements past the plane leave zero bits
+                if (l + S * k + 1 == a.q4) c &= tailmask;
+                if (SUB && l + S * k >= a.q4) continue;
+                if constexpr (CB == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, cvoff, (int)(S * k), 0);
+                else if constexpr (CB == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c, crs, cvoff, (int)(S * k * 2), 0);
+                else __builtin_amdgcn_raw_buffer_store_b32(c, crs, cvoff, (int)(S * k * 4), 0);
             }
             // pad bytes of the plane's last word are zero
             const uint32_t padb = a.WPP * 4 - a.q4 * CB;
-            if (tid < padb) cbase[a.q4 * CB + tid] = 0;
+            if (l < padb && pv) cround[(size_t)g * a.WPP * 4 + a.q4 * CB + l] = 0;
         }
-        if constexpr (NW == 1) wave_sync(); else lds_barrier();      // xs, rsum, lfcs and red are reused
+        sync();      // xs, rsum, lfcs and red are reused
     }
 }
 
@@ -3316,7 +3345,9 @@ hipError_t launch_regs(int B, int nw, const RegsArgs& a, dim3 grid, size_t lds, 
 
 // Fills the plan of the register kernel for any width; false when the shape is not covered: 2-D maps
 // of at most 8 x 1024 units that fit LDS beside their row sums (up to about 163 x 163 elements).
-constexpr uint64_t kUnitsMin = 128;       // units per plane from which the kernel is worth its per-plane set-up
+constexpr uint64_t kUnitsMin = 128;       // units per plane from which a plane gets a whole wavefront or more
+constexpr uint64_t kUnitsSubMin = 64;     // units per plane from which the instance with 16 or 32 lanes per plane is used
+                                          // (17 x 17: 1.7 -> 2.3 TB/s; 13 x 13 and 15 x 15 are no faster than in compress_wave)
 bool plan_units(const Layout& L, int64_t D, int64_t H, int64_t W, int B, size_t es, const void* x,
                 UnitsArgs* a, uint32_t* grid, size_t* lds, int* nw_out) {
     if (D != 1 || H == 1 || ((uintptr_t)x % 4) != 0) return false;
@@ -3324,45 +3355,62 @@ bool plan_units(const Layout& L, int64_t D, int64_t H, int64_t W, int B, size_t 
     // lane): measured faster there
     if ((B == 4 || B == 8) && W % 2 == 0 && 4ull * L.HW + 16ull <= kWavePlaneMax) return false;
     const uint64_t q4 = (L.HW + 3) / 4;
-    if (q4 < kUnitsMin || L.nb > 16383) return false;        // LFC offsets are kept as 16-bit byte offsets
+    if (L.nb > 16383 || B > 4095) return false;              // LFC offsets are kept as 16-bit byte offsets
     const uint64_t nitem = L.nb * (uint64_t)B;
     int nw = 1;
-    while (nw < 16 && (q4 > (uint64_t)kUnitsK * 64 * nw || nitem > (uint64_t)kUnitsK * 64 * nw)) nw *= 2;
-    if (q4 > (uint64_t)kUnitsK * 64 * nw) return false;
-    const uint64_t nt = 64ull * nw;
-    const uint64_t q4p = (q4 + nt - 1) / nt * nt;
-    if (nitem > (uint64_t)kUnitsK * nt || B > 4095) return false;        // row segments: at most 8 per lane too
-    if (!fastdiv_ok(4ull * kUnitsK * nt + 4, (uint64_t)W) || !fastdiv_ok(4ull * kUnitsK * nt + 4, (uint64_t)B) ||
-        !fastdiv_ok(nitem + nt, (uint64_t)B) || !fastdiv_ok(L.nb + nt, L.LW))
+    uint64_t S = 64;                                          // lanes per plane
+    if (q4 < kUnitsMin) {
+        // small planes: 8, 16 or 32 lanes each, several planes per wavefront
+        if (q4 < kUnitsSubMin) return false;
+        S = 8;
+        while (S < 64 && (q4 > (uint64_t)kUnitsK * S || nitem > (uint64_t)kUnitsK * S)) S *= 2;
+        nw = S < 64 ? 0 : 1;
+    }
+    if (nw) {
+        while (nw < 16 && (q4 > (uint64_t)kUnitsK * 64 * nw || nitem > (uint64_t)kUnitsK * 64 * nw)) nw *= 2;
+        S = 64ull * nw;
+    }
+    if (q4 > (uint64_t)kUnitsK * S || nitem > (uint64_t)kUnitsK * S) return false;       // 8 units and 8 row segments per lane
+    const uint64_t q4p = (q4 + S - 1) / S * S;
+    if (!fastdiv_ok(4ull * kUnitsK * S + 4, (uint64_t)W) || !fastdiv_ok(4ull * kUnitsK * S + 4, (uint64_t)B) ||
+        !fastdiv_ok(nitem + S, (uint64_t)B) || !fastdiv_ok(L.nb + S, L.LW))
         return false;
     a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
     a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP; a->B = (uint32_t)B;
     a->q4 = (uint32_t)q4; a->q4p = (uint32_t)q4p; a->nitem = (uint32_t)nitem;
+    a->S = (uint32_t)S;
+    a->S_log2 = 0;
+    while ((1ull << a->S_log2) < S) ++a->S_log2;
     a->d_W = make_fastdiv((uint32_t)W);
     a->d_B = make_fastdiv((uint32_t)B);
     a->d_LW = make_fastdiv((uint32_t)L.LW);
-    *lds = 16ull * q4p + 8ull * nitem + 4ull * ((L.nb + 1 + 3) & ~3ull) + 8ull * nw + 16;
+    const uint64_t G = nw ? 1 : 64 / S;                       // planes per round
+    const uint64_t reg = (16ull * q4p + 8ull * nitem + 4ull * ((L.nb + 1 + 3) & ~3ull) + 8ull * (nw ? nw : 1) + 16 + 15) & ~15ull;
+    a->reg_bytes = (uint32_t)reg;
+    a->nrounds = (uint32_t)((L.P + G - 1) / G);
+    *lds = reg * G;
     if (*lds > (size_t)kLdsMax) return false;
     // as many workgroups as the machine holds at once (LDS, and 16 wavefronts per CU), each taking every
-    // grid-th plane
+    // grid-th round of planes
+    const uint64_t wpg = nw ? (uint64_t)nw : 1;               // wavefronts per workgroup
     uint64_t per_cu = (160ull << 10) / *lds;
-    if (per_cu > 16ull / nw) per_cu = 16ull / nw;
+    if (per_cu > 16ull / wpg) per_cu = 16ull / wpg;
     if (per_cu < 1) per_cu = 1;
-    uint64_t g = 256ull * per_cu;
+    uint64_t g = (uint64_t)num_cus() * per_cu;
     g += g & 1;            // even: with 2-byte elements the planes of a workgroup then start alike within a dword
-    *grid = (uint32_t)(g < L.P ? g : L.P);
+    *grid = (uint32_t)(g < a->nrounds ? g : a->nrounds);
     *nw_out = nw;
-    return *lds <= (size_t)kLdsMax;
+    return true;
 }
 
 template <typename T, int BITS>
 hipError_t launch_units(int nw, const UnitsArgs& a, dim3 grid, size_t lds, hipStream_t st) {
-    void (*kern)(UnitsArgs) = nw == 1 ? compress_units<T, BITS, 1> : nw == 2 ? compress_units<T, BITS, 2>
-                            : nw == 4 ? compress_units<T, BITS, 4> : nw == 8 ? compress_units<T, BITS, 8>
-                                                                             : compress_units<T, BITS, 16>;
+    void (*kern)(UnitsArgs) = nw == 0 ? compress_units<T, BITS, 0> : nw == 1 ? compress_units<T, BITS, 1>
+                            : nw == 2 ? compress_units<T, BITS, 2> : nw == 4 ? compress_units<T, BITS, 4>
+                            : nw == 8 ? compress_units<T, BITS, 8> : compress_units<T, BITS, 16>;
     const hipError_t e = allow_large_lds(kern, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, grid, dim3(64 * nw), lds, st, a);
+    hipLaunchKernelGGL(kern, grid, dim3(nw ? 64 * nw : 64), lds, st, a);
     return hipGetLastError();
 }
 

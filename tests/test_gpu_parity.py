@@ -615,9 +615,9 @@ ROWS_CASES = [
     ((5, 7, 1, 1000), 12, 4),
     ((2, 3, 33, 31), 2, 2),             # tiny blocks: 272 blocks per plane
     ((2, 3, 40, 40), 1, 4),             # B = 1
-    ((6, 10, 20, 20), 12, 2),           # planes below 512 elements stay with this kernel: whole-vector rows,
-    ((5, 8, 21, 21), 6, 4),             # odd rows,
-    ((9, 4, 11, 45), 18, 8),            # wide and flat
+    ((6, 10, 12, 20), 12, 2),           # planes below 256 elements stay with this kernel: whole-vector rows,
+    ((5, 8, 15, 15), 6, 4),             # odd rows,
+    ((9, 4, 7, 33), 18, 8),             # wide and flat
 ]
 
 
@@ -677,9 +677,9 @@ def test_general_block_size_kernel_matches_oracle(shape, B, b, mode):
     c16 = mode == "c16"
     name = pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16)
     # block sizes 12 and 16 on planes of whole 4-element units take the register kernel's any-B instance
-    # (1-D maps with power-of-two blocks the one-row kernel), other planes of 512 elements and more
+    # (1-D maps with power-of-two blocks the one-row kernel), other planes of 256 elements and more
     # the register kernel for any width
-    units = shape[2] > 1 and shape[2] * shape[3] >= 512
+    units = shape[2] > 1 and shape[2] * shape[3] >= 256
     assert (name.startswith(("compress_rows<", "compress_line<")) or (name.startswith("compress_regs<") and ", 0, " in name)
             or (units and name.startswith("compress_units<")))
     _check_variant(shape, B, b, mode)
@@ -748,6 +748,11 @@ UNITS_CASES = [
     ((4, 3, 23, 23), 64, 2),            # one block per plane with an odd element count
     ((3, 3, 26, 45), 8, 2),             # odd width, even element count: 2-byte planes start on 4-byte boundaries
     ((2, 3, 38, 75), 4, 4),             # H*W % 4 == 2: the last unit holds two elements
+    ((6, 5, 17, 17), 8, 2),             # planes below 512 elements: 16 lanes per plane, four planes per wavefront;
+    ((5, 7, 19, 19), 4, 4),             # 30 planes: the last round has two
+    ((3, 3, 21, 21), 2, 8),             # 242 row segments: 32 lanes per plane
+    ((4, 6, 17, 17), 18, 2),            # one block per plane
+    ((7, 3, 17, 23), 6, 2),
 ]
 
 
@@ -756,14 +761,14 @@ UNITS_CASES = [
 def test_register_kernel_any_width_matches_oracle(shape, B, b, mode):
     dtype = torch.bfloat16 if mode == "bf16" else torch.float32
     assert pkg.division_kernel_name(0, shape, B, b, dtype, c16=mode == "c16").startswith("compress_units<")
-    if shape[3] % 2 == 1:
+    if shape[3] % 2 == 1 and shape[2] * shape[3] >= 512:      # (smaller planes are rebuilt chunk-wise in LDS)
         assert pkg.division_kernel_name(1, shape, B, b, dtype, c16=mode == "c16").startswith("decompress_units<")
     _check_variant(shape, B, b, mode)
 
 
 # more planes than workgroups: a workgroup takes every grid-th plane, the next one's loads in flight
 @pytest.mark.parametrize("shape,B,b", [((21, 100, 55, 55), 8, 2), ((3, 100, 147, 147), 8, 2), ((42, 100, 27, 27), 4, 4),
-                                        ((3, 1001, 35, 35), 8, 2)])
+                                        ((3, 1001, 35, 35), 8, 2), ((5, 4001, 17, 17), 8, 2)])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_register_kernel_any_width_many_planes(shape, B, b, dtype):
     assert pkg.division_kernel_name(0, shape, B, b, dtype).startswith("compress_units<")
