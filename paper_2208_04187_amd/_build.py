@@ -1,7 +1,7 @@
 """Builds libdivision.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
 
-division.hip instantiates its kernels once per element / cache type; it is compiled as three
-translation units (-DDIVISION_PART=0, 1, 2: float, bfloat16, bfloat16-cached float) beside masks.hip,
+division.hip (with the kernel families and the host side in the .h fragments it includes) instantiates
+its kernels once per element / cache type; it is compiled as three translation units (-DDIVISION_PART=0, 1, 2: float, bfloat16, bfloat16-cached float) beside masks.hip,
 all four in parallel, and the objects are linked into the one library.
 """
 from __future__ import annotations

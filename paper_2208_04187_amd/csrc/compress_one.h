@@ -1,0 +1,234 @@
+// Part of division.hip (included inside its unnamed namespace, in this order): compress_one and compress_line.
+
+// ------------------------------------------------------------------ compress, planes that are one block
+
+struct OneArgs {
+    CompTab tab;
+    Regions rg;
+    uint32_t P, HW, WPP;
+    uint32_t qv;         // 16-byte vectors per plane
+    uint32_t S, S_log2;  // lanes per plane (power of two, at most 64)
+    uint32_t ppw;        // planes per wavefront = 64 / S
+    uint32_t upb, upb_log2;  // compress_line: vectors per block (power of two, at most S); nb = blocks per plane
+    uint32_t nb;
+};
+
+constexpr int kOneUnits = 13;     // vectors per lane: planes of up to 13 * 64 vectors
+
+// sum over aligned groups of S lanes (S a power of two <= 64, uniform in the wave) in a fixed
+// order, result in every lane of the group; all lanes must be active
+__device__ __forceinline__ double group_sum_any(uint32_t S, double v) {
+    if (S >= 2)  v += dpp_f64<kDppXor1>(v);
+    if (S >= 4)  v += dpp_f64<kDppXor2>(v);
+    if (S >= 8)  v += dpp_f64<kDppHalfMirror>(v);
+    if (S >= 16) v += dpp_f64<kDppMirror>(v);
+    if (S >= 32) {
+        const uint64_t u = (uint64_t)__double_as_longlong(v);
+        const int lo = (int)(uint32_t)u, hi = (int)(uint32_t)(u >> 32);
+        auto row = [&](int lane) -> double {
+            const uint32_t l = (uint32_t)__builtin_amdgcn_readlane(lo, lane), h = (uint32_t)__builtin_amdgcn_readlane(hi, lane);
+            return __longlong_as_double((long long)(((uint64_t)h << 32) | l));
+        };
+        const double r0 = row(0), r1 = row(16), r2 = row(32), r3 = row(48);
+        if (S == 64) v = (r0 + r1) + (r2 + r3);
+        else v = (threadIdx.x & 32u) ? r2 + r3 : r0 + r1;
+    }
+    return v;
+}
+
+// The block covers the whole plane (B at least every extent of the map: the later layers of a
+// network, or a block size like 64 on maps of 56 x 56 and below): H^L is the plane's mean, rows
+// and columns play no part, and the plane is a flat run of 16-byte vectors.  One wavefront per
+// 64 / S planes; the S lanes of a plane keep its vectors in registers (vector u in lane u mod S),
+// sums and extremes are reductions over those lanes, the codes leave as one to eight bytes per
+// vector.  LDS is not used.
+template <typename T, int BITS>
+__global__ void __launch_bounds__(64) compress_one(OneArgs a) {
+    constexpr int K = kOneUnits;
+    constexpr uint32_t EPV = 16 / sizeof(T);
+    constexpr uint32_t CBV = EPV * BITS / 8;
+    constexpr float Lf = float((1 << BITS) - 1);
+    const uint32_t tid = threadIdx.x;
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
+    const uint32_t sub = tid & (a.S - 1u);
+    const uint32_t p = blockIdx.x * a.ppw + (tid >> a.S_log2);
+    const bool live = p < a.P;
+    const uint32_t pc = live ? p : a.P - 1u;          // lanes past the last plane redo it; their stores are masked
+    const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const T*>(pt.x) + (size_t)pc * a.HW);
+
+    u32x4 q[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t u = sub + (uint32_t)k * a.S;
+        if (u < a.qv) q[k] = __builtin_nontemporal_load(src + u);
+    }
+    // ---- Sec. 4.1 AveragePooling with one window: the mean of the plane
+    double S = 0.0;
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t u = sub + (uint32_t)k * a.S;
+        if (u < a.qv) {
+            float f[EPV];
+            unpack_vec<T>(q[k], f);
+            double s4 = ((double)f[0] + (double)f[1]) + ((double)f[2] + (double)f[3]);
+            mn = fminf(mn, fminf(fminf(f[0], f[1]), fminf(f[2], f[3])));
+            mx = fmaxf(mx, fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])));
+            if constexpr (EPV == 8) {
+                s4 += ((double)f[4] + (double)f[5]) + ((double)f[6] + (double)f[7]);
+                mn = fminf(mn, fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
+                mx = fmaxf(mx, fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
+            }
+            S += s4;
+        }
+    }
+    S = group_sum_any(a.S, S);
+    const float lfc = lfc_round<T>(mean_of(S, a.HW), kC16<T>);
+    // ---- extremes of the residual (x -> fl(x - m) is monotone), scale of Eq. (quantization), keys
+    mn = mn - lfc;
+    mx = mx - lfc;
+    group_minmax(a.S, mn, mx);
+    float delta, Delta, inv;
+    plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
+    const float invs = inv * (float)(1u << (32 - BITS));
+    const uint32_t k1 = mix32(pc ^ pt.seed_a);
+    const uint32_t k2 = mix32(k1 + pt.seed_c);
+    uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)pc * a.WPP * 4;
+    if (live && sub == 0) {
+        meta_store(pt.meta, p, delta, Delta, kC16<T>);
+        lfc_store<T>(pt.lfc, (size_t)p, lfc, kC16<T>);
+        const uint32_t padb = a.WPP * 4 - a.qv * CBV;                 // pad bytes of the last word are zero
+        for (uint32_t t = 0; t < padb; ++t) cbase[a.qv * CBV + t] = 0;
+    }
+    // ---- residual, Quant, packing
+    const uint32_t rscale = 1u << (16 - BITS);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t u = sub + (uint32_t)k * a.S;
+        if (live && u < a.qv) {
+            float h[EPV];
+            unpack_vec<T>(q[k], h);
+#pragma unroll
+            for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lfc;
+            const uint32_t xw0 = k1 + (u * (EPV / 2)) * kWeyl;
+            uint8_t* dst = cbase + u * CBV;
+            if constexpr (CBV <= 4) {
+                uint32_t c = 0;
+#pragma unroll
+                for (int j = EPV / 2 - 1; j >= 0; --j)
+                    c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+                if constexpr (CBV == 1) *dst = (uint8_t)c;
+                else if constexpr (CBV == 2) *reinterpret_cast<uint16_t*>(dst) = (uint16_t)c;
+                else *reinterpret_cast<uint32_t*>(dst) = c;
+            } else {
+                uint32_t lo = 0, hi = 0;
+                hi = push_pair<BITS>(hi, h[6], h[7], delta, invs, xw0 + 3u * kWeyl, k2, rscale);
+                hi = push_pair<BITS>(hi, h[4], h[5], delta, invs, xw0 + 2u * kWeyl, k2, rscale);
+                lo = push_pair<BITS>(lo, h[2], h[3], delta, invs, xw0 + kWeyl, k2, rscale);
+                lo = push_pair<BITS>(lo, h[0], h[1], delta, invs, xw0, k2, rscale);
+                reinterpret_cast<uint32_t*>(dst)[0] = lo;
+                reinterpret_cast<uint32_t*>(dst)[1] = hi;
+            }
+        }
+    }
+}
+
+// 1-D maps (Appendix D, AveragePooling1D: Minibatch x Channel x N, the maps of linear and
+// transformer layers) whose block is a power-of-two number of 16-byte vectors (B = 4, 8, 16, 32, 64
+// for fp32): laid out like compress_one, the `upb` vectors of a block sit in neighbouring lanes of
+// one round, so a block's sum is a DPP reduction over those lanes and its LFC stays in a register.
+// No LDS.
+template <typename T, int BITS>
+__global__ void __launch_bounds__(64) compress_line(OneArgs a) {
+    constexpr int K = kOneUnits;
+    constexpr uint32_t EPV = 16 / sizeof(T);
+    constexpr uint32_t CBV = EPV * BITS / 8;
+    constexpr float Lf = float((1 << BITS) - 1);
+    const uint32_t tid = threadIdx.x;
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
+    const uint32_t sub = tid & (a.S - 1u);
+    const uint32_t p = blockIdx.x * a.ppw + (tid >> a.S_log2);
+    const bool live = p < a.P;
+    const uint32_t pc = live ? p : a.P - 1u;          // lanes past the last plane redo it; their stores are masked
+    const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const T*>(pt.x) + (size_t)pc * a.HW);
+
+    u32x4 q[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t u = sub + (uint32_t)k * a.S;
+        if (u < a.qv) q[k] = __builtin_nontemporal_load(src + u);
+    }
+    // ---- AveragePooling1D: block sums over the lanes of a block, residual extremes of the plane
+    float lfcv[K];
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        if ((uint32_t)k * a.S >= a.qv) { lfcv[k] = 0.0f; continue; }          // uniform: no vector of this round exists
+        const uint32_t u = sub + (uint32_t)k * a.S;
+        const bool valid = u < a.qv;
+        float f[EPV];
+        double s4 = 0.0;
+        if (valid) {
+            unpack_vec<T>(q[k], f);
+            s4 = ((double)f[0] + (double)f[1]) + ((double)f[2] + (double)f[3]);
+            if constexpr (EPV == 8) s4 += ((double)f[4] + (double)f[5]) + ((double)f[6] + (double)f[7]);
+        }
+        const double Sb = group_sum_any(a.upb, s4);
+        const uint32_t ustart = u & ~(a.upb - 1u);
+        const uint32_t nvec = valid ? min(a.upb, a.qv - ustart) : 1u;           // the last block may be short
+        const float lfc = lfc_round<T>(mean_of(Sb, nvec * EPV), kC16<T>);
+        lfcv[k] = lfc;
+        if (valid) {
+#pragma unroll
+            for (uint32_t e = 0; e < EPV; ++e) {
+                const float h = f[e] - lfc;
+                mn = fminf(mn, h);
+                mx = fmaxf(mx, h);
+            }
+            if (live && u == ustart) lfc_store<T>(pt.lfc, (size_t)p * a.nb + (u >> a.upb_log2), lfc, kC16<T>);
+        }
+    }
+    group_minmax(a.S, mn, mx);
+    float delta, Delta, inv;
+    plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
+    const float invs = inv * (float)(1u << (32 - BITS));
+    const uint32_t k1 = mix32(pc ^ pt.seed_a);
+    const uint32_t k2 = mix32(k1 + pt.seed_c);
+    uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)pc * a.WPP * 4;
+    if (live && sub == 0) {
+        meta_store(pt.meta, p, delta, Delta, kC16<T>);
+        const uint32_t padb = a.WPP * 4 - a.qv * CBV;                 // pad bytes of the last word are zero
+        for (uint32_t t = 0; t < padb; ++t) cbase[a.qv * CBV + t] = 0;
+    }
+    // ---- residual, Quant, packing
+    const uint32_t rscale = 1u << (16 - BITS);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t u = sub + (uint32_t)k * a.S;
+        if (live && u < a.qv) {
+            float h[EPV];
+            unpack_vec<T>(q[k], h);
+#pragma unroll
+            for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lfcv[k];
+            const uint32_t xw0 = k1 + (u * (EPV / 2)) * kWeyl;
+            uint8_t* dst = cbase + u * CBV;
+            if constexpr (CBV <= 4) {
+                uint32_t c = 0;
+#pragma unroll
+                for (int j = EPV / 2 - 1; j >= 0; --j)
+                    c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+                if constexpr (CBV == 1) *dst = (uint8_t)c;
+                else if constexpr (CBV == 2) *reinterpret_cast<uint16_t*>(dst) = (uint16_t)c;
+                else *reinterpret_cast<uint32_t*>(dst) = c;
+            } else {
+                uint32_t lo = 0, hi = 0;
+                hi = push_pair<BITS>(hi, h[6], h[7], delta, invs, xw0 + 3u * kWeyl, k2, rscale);
+                hi = push_pair<BITS>(hi, h[4], h[5], delta, invs, xw0 + 2u * kWeyl, k2, rscale);
+                lo = push_pair<BITS>(lo, h[2], h[3], delta, invs, xw0 + kWeyl, k2, rscale);
+                lo = push_pair<BITS>(lo, h[0], h[1], delta, invs, xw0, k2, rscale);
+                reinterpret_cast<uint32_t*>(dst)[0] = lo;
+                reinterpret_cast<uint32_t*>(dst)[1] = hi;
+            }
+        }
+    }
+}

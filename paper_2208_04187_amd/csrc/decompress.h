@@ -1,0 +1,603 @@
+// Part of division.hip (included inside its unnamed namespace, in this order): the decompress kernels.
+
+// ------------------------------------------------------------------ decompress
+
+struct DecArgs {
+    DecTab tab;
+    Regions rg;
+    uint32_t P, H, W, HW, LH, LW, nb, WPP, B;
+    uint32_t G;          // planes per workgroup
+    uint32_t q4;         // HW / 4
+    uint32_t w4;         // W / 4
+    uint32_t Hs, LHs;    // 3-D maps: rows and block rows of one depth slice (H counts the rows of all slices)
+    uint32_t pair8;      // 2-byte elements, W a multiple of 8, output 16-byte aligned: a lane step writes 8 elements
+    uint32_t out_off;    // decompress_words: byte offset of the staged output in LDS
+    FastDiv d_q4, d_w4, d_B, d_W, d_HW, d_Hs, d_wpp;
+};
+
+// Index of the first block of the block row that holds row r; for a 3-D map (Appendix D,
+// UpSampling3D) r counts the rows of all depth slices.
+template <int ND>
+__device__ __forceinline__ uint32_t lfc_row(const DecArgs& a, uint32_t r) {
+    if constexpr (ND == 3) {
+        const uint32_t z = fdiv(r, a.d_Hs);
+        return (fdiv(z, a.d_B) * a.LHs + fdiv(r - z * a.Hs, a.d_B)) * a.LW;
+    } else {
+        return fdiv(r, a.d_B) * a.LW;
+    }
+}
+
+// Sec. 4.2: hh = Delta*q + delta ; reconstruction: xhat = lfc + hh (three fp32 ops)
+__device__ __forceinline__ float dequant(uint32_t q, float Delta, float delta, float lfc) {
+    float hh = (float)q * Delta;
+    hh = hh + delta;
+    return lfc + hh;
+}
+
+// Four reconstructed elements leave with one store.  The map is written once
+// and not read again by this library, so the stores are non-temporal: they do
+// not displace what the neighbouring kernels keep in the caches (3.5 % on the
+// whole compress + decompress step).  Build with -DDIVISION_TEMPORAL_STORE when
+// the consumer of the map runs right behind and should find it in the
+// last-level cache.
+template <typename T>
+__device__ __forceinline__ void store4(T* dst, size_t i, float a, float b, float c, float d) {
+#ifndef DIVISION_TEMPORAL_STORE
+    if constexpr (sizeof(T) == 4) {
+        f32x4 v; v.x = a; v.y = b; v.z = c; v.w = d;
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst + i));
+    } else {
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        u32x2 o;
+        o.x = float_to_bf16_bits(a) | (float_to_bf16_bits(b) << 16);
+        o.y = float_to_bf16_bits(c) | (float_to_bf16_bits(d) << 16);
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(dst + i));
+    }
+#else
+    if constexpr (sizeof(T) == 4) {
+        *reinterpret_cast<float4*>(dst + i) = make_float4(a, b, c, d);
+    } else {
+        uint2 o;
+        o.x = float_to_bf16_bits(a) | (float_to_bf16_bits(b) << 16);
+        o.y = float_to_bf16_bits(c) | (float_to_bf16_bits(d) << 16);
+        *reinterpret_cast<uint2*>(dst + i) = o;
+    }
+#endif
+}
+
+// Copies this workgroup's slices of the three packed regions (codes, meta, LFC
+// of planes p0 .. p0+Gc-1: about 8 % of the output volume) into LDS with
+// coalesced loads, so that the streaming loop below depends on LDS latency
+// only and its 16-byte stores go out back to back.
+template <typename T>
+__device__ __forceinline__ void stage_packed(const DecArgs& a, const DecPtrs& pt, uint32_t p0, uint32_t Gc, uint32_t* s_codes,
+                                             float2* s_meta, T* s_lfc, uint32_t tid) {
+    const uint32_t nw = Gc * a.WPP;
+    const uint32_t* src = pt.codes + (size_t)p0 * a.WPP;
+    if ((((size_t)p0 * a.WPP) & 3u) == 0) {
+        const uint32_t nq = nw >> 2;
+        for (uint32_t i = tid; i < nq; i += kThreads)
+            reinterpret_cast<u32x4*>(s_codes)[i] = reinterpret_cast<const u32x4*>(src)[i];
+        for (uint32_t i = (nq << 2) + tid; i < nw; i += kThreads) s_codes[i] = src[i];
+    } else {
+        for (uint32_t i = tid; i < nw; i += kThreads) s_codes[i] = src[i];
+    }
+    for (uint32_t i = tid; i < Gc; i += kThreads) s_meta[i] = meta_load(pt.meta, p0 + i, kC16<T>);
+    const uint32_t nl = Gc * a.nb;
+    if (sizeof(T) == 4 && kC16<T>) {
+        // bfloat16 H^L of an fp32 map: widened here, so that the streaming loops read floats as ever
+        const uint16_t* lsrc = static_cast<const uint16_t*>(pt.lfc) + (size_t)p0 * a.nb;
+        for (uint32_t i = tid; i < nl; i += kThreads) reinterpret_cast<float*>(s_lfc)[i] = bf16_bits_to_float(lsrc[i]);
+    } else {
+        const T* lsrc = static_cast<const T*>(pt.lfc) + (size_t)p0 * a.nb;
+        for (uint32_t i = tid; i < nl; i += kThreads) s_lfc[i] = lsrc[i];
+    }
+    lds_barrier();
+}
+
+// LDS carve-up shared by the two streaming kernels (the host sizes it the same way)
+template <typename T>
+__device__ __forceinline__ void dec_lds(const DecArgs& a, uint32_t*& s_codes, float2*& s_meta, T*& s_lfc) {
+    extern __shared__ float4 smem4[];
+    s_codes = reinterpret_cast<uint32_t*>(smem4);
+    s_meta = reinterpret_cast<float2*>(s_codes + ((a.G * a.WPP + 3u) & ~3u));
+    s_lfc = reinterpret_cast<T*>(s_meta + a.G);
+}
+
+// W % 4 == 0 and B % 4 == 0: the four elements of a vector lie in one row and
+// share one LFC value.  A workgroup streams G whole planes.
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void decompress_rowvec_body(const DecArgs& a) {
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
+    uint32_t* s_codes; float2* s_meta; T* s_lfc;
+    dec_lds<T>(a, s_codes, s_meta, s_lfc);
+    const uint32_t tid = threadIdx.x;
+    const uint32_t p0 = blockIdx.x * a.G;
+    const uint32_t Gc = min(a.G, a.P - p0);
+    stage_packed<T>(a, pt, p0, Gc, s_codes, s_meta, s_lfc, tid);
+    const uint32_t nvec = Gc * a.q4;
+    constexpr uint32_t Lq = (1u << BITS) - 1u;
+    T* out = static_cast<T*>(pt.xhat) + (size_t)p0 * a.HW;
+    if constexpr (sizeof(T) == 2) {
+        if (a.pair8) {
+            // two neighbouring vectors of one row per lane step: one 16-byte store
+            for (uint32_t vi = 2 * tid; vi < nvec; vi += 2 * kThreads) {
+                const uint32_t g = fdiv(vi, a.d_q4);
+                const uint32_t fi = vi - g * a.q4;                     // even
+                const float2 dd = s_meta[g];
+                uint32_t lo, hi;                                       // codes of elements 0-3 and 4-7
+                if constexpr (BITS == 2) {
+                    lo = reinterpret_cast<const uint16_t*>(s_codes)[(g * a.WPP * 4 + fi) >> 1];
+                    hi = lo >> 8;
+                } else if constexpr (BITS == 4) {
+                    lo = s_codes[(g * a.WPP * 2 + fi) >> 1];
+                    hi = lo >> 16;
+                } else {
+                    lo = s_codes[g * a.WPP + fi];
+                    hi = s_codes[g * a.WPP + fi + 1];
+                }
+                const uint32_t r = fdiv(fi, a.d_w4);
+                const uint32_t c = (fi - r * a.w4) * 4;
+                const T* lrow = s_lfc + g * a.nb + lfc_row<ND>(a, r);
+                const float l0 = Elem<T>::load(lrow, fdiv(c, a.d_B)), l1 = Elem<T>::load(lrow, fdiv(c + 4, a.d_B));
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    w[e] = float_to_bf16_bits(dequant((lo >> (2 * e * BITS)) & Lq, dd.y, dd.x, l0)) |
+                           (float_to_bf16_bits(dequant((lo >> ((2 * e + 1) * BITS)) & Lq, dd.y, dd.x, l0)) << 16);
+                    w[2 + e] = float_to_bf16_bits(dequant((hi >> (2 * e * BITS)) & Lq, dd.y, dd.x, l1)) |
+                               (float_to_bf16_bits(dequant((hi >> ((2 * e + 1) * BITS)) & Lq, dd.y, dd.x, l1)) << 16);
+                }
+                u32x4 o; o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
+#ifndef DIVISION_TEMPORAL_STORE
+                __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(out + (size_t)vi * 4));
+#else
+                *reinterpret_cast<u32x4*>(out + (size_t)vi * 4) = o;
+#endif
+            }
+            return;
+        }
+    }
+    for (uint32_t vi = tid; vi < nvec; vi += kThreads) {
+        const uint32_t g = fdiv(vi, a.d_q4);
+        const uint32_t fi = vi - g * a.q4;        // vector index inside the plane
+        const float2 dd = s_meta[g];
+        uint32_t c4;                               // the four codes, BITS apart from bit 0
+        if constexpr (BITS == 2) c4 = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + fi];
+        else if constexpr (BITS == 4) c4 = reinterpret_cast<const uint16_t*>(s_codes)[g * a.WPP * 2 + fi];
+        else c4 = s_codes[g * a.WPP + fi];
+        const uint32_t r = fdiv(fi, a.d_w4);
+        const uint32_t c = (fi - r * a.w4) * 4;
+        const float lfc = Elem<T>::load(s_lfc, g * a.nb + lfc_row<ND>(a, r) + fdiv(c, a.d_B));
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = dequant((c4 >> (e * BITS)) & Lq, dd.y, dd.x, lfc);
+        store4(out, (size_t)vi * 4, o[0], o[1], o[2], o[3]);
+    }
+}
+
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_rowvec(DecArgs a) { decompress_rowvec_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_rowvec_3d(DecArgs a) { decompress_rowvec_body<T, BITS, 3>(a); }
+
+// H*W a multiple of 4 and at most 255 blocks per plane: the LFC index of every
+// element of a plane is looked up in a table (one byte per element, four per
+// vector) that the workgroup builds once in LDS, so the streaming loop has no
+// row / column arithmetic.  A workgroup streams G whole planes.
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_table(DecArgs a) {
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
+    uint32_t* s_codes; float2* s_meta; T* s_lfc;
+    dec_lds<T>(a, s_codes, s_meta, s_lfc);
+    uint32_t* s_tab = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(s_lfc) + ((a.G * a.nb * sizeof(T) + 15u) & ~15u));
+    constexpr uint32_t Lq = (1u << BITS) - 1u;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t p0 = blockIdx.x * a.G;
+    const uint32_t Gc = min(a.G, a.P - p0);
+    for (uint32_t fi = tid; fi < a.q4; fi += kThreads) {
+        uint32_t r = fdiv(fi * 4, a.d_W);
+        uint32_t c = fi * 4 - r * a.W;
+        uint32_t t = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            t |= (fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B)) << (8 * e);
+            if (++c == a.W) { c = 0; ++r; }
+        }
+        s_tab[fi] = t;
+    }
+    stage_packed<T>(a, pt, p0, Gc, s_codes, s_meta, s_lfc, tid);      // ends with a barrier
+    const uint32_t nvec = Gc * a.q4;
+    T* out = static_cast<T*>(pt.xhat) + (size_t)p0 * a.HW;
+    for (uint32_t vi = tid; vi < nvec; vi += kThreads) {
+        const uint32_t g = fdiv(vi, a.d_q4);
+        const uint32_t fi = vi - g * a.q4;
+        const float2 dd = s_meta[g];
+        uint32_t c4;
+        if constexpr (BITS == 2) c4 = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + fi];
+        else if constexpr (BITS == 4) c4 = reinterpret_cast<const uint16_t*>(s_codes)[g * a.WPP * 2 + fi];
+        else c4 = s_codes[g * a.WPP + fi];
+        const uint32_t t = s_tab[fi];
+        const T* lp = s_lfc + g * a.nb;
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            o[e] = dequant((c4 >> (e * BITS)) & Lq, dd.y, dd.x, Elem<T>::load(lp, (t >> (8 * e)) & 0xffu));
+        store4(out, (size_t)vi * 4, o[0], o[1], o[2], o[3]);
+    }
+}
+
+// Any W, H, B: a workgroup streams G whole planes as one flat run of elements,
+// four consecutive elements per lane step; every element finds its own plane,
+// row, column and block.  G*HW is a multiple of 4 whenever G < P remains, so
+// vector stores stay aligned; the ragged end of the last chunk is scalar.
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void decompress_flat_body(const DecArgs& a) {
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
+    uint32_t* s_codes; float2* s_meta; T* s_lfc;
+    dec_lds<T>(a, s_codes, s_meta, s_lfc);
+    constexpr uint32_t CPW = 32 / BITS;
+    constexpr uint32_t Lq = (1u << BITS) - 1u;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t p0 = blockIdx.x * a.G;
+    const uint32_t Gc = min(a.G, a.P - p0);
+    stage_packed<T>(a, pt, p0, Gc, s_codes, s_meta, s_lfc, tid);
+    const uint32_t n = Gc * a.HW;
+    T* out = static_cast<T*>(pt.xhat) + (size_t)p0 * a.HW;
+    const bool one_block = a.nb == 1;             // map smaller than the block: LFC is one value per plane
+    for (uint32_t e0 = tid * 4; e0 < n; e0 += kThreads * 4) {
+        uint32_t g = fdiv(e0, a.d_HW);
+        uint32_t i = e0 - g * a.HW;
+        float o[4];
+        if (one_block && e0 + 4 <= n && a.HW >= 4) {
+            // at most one plane boundary inside the vector: elements before it use
+            // plane g, the others plane g+1 (which exists because e0+4 <= n)
+            const uint32_t n0 = min(4u, a.HW - i);
+            const uint32_t g1 = n0 < 4 ? g + 1 : g;
+            const float2 da = s_meta[g], db = s_meta[g1];
+            const float la = Elem<T>::load(s_lfc, g), lb = Elem<T>::load(s_lfc, g1);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool first = (uint32_t)e < n0;
+                const uint32_t idx = first ? i + e : (uint32_t)e - n0;
+                const uint32_t w = s_codes[(first ? g : g1) * a.WPP + idx / CPW];
+                const uint32_t q = (w >> ((idx % CPW) * BITS)) & Lq;
+                o[e] = dequant(q, first ? da.y : db.y, first ? da.x : db.x, first ? la : lb);
+            }
+            store4(out, e0, o[0], o[1], o[2], o[3]);
+            continue;
+        }
+        if (!one_block && i + 4 <= a.HW && (i % CPW) + 4 <= CPW) {
+            // the four elements share plane, scale and code word
+            const float2 dd = s_meta[g];
+            const uint32_t w = s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS);
+            const T* lp = s_lfc + g * a.nb;
+            uint32_t r = fdiv(i, a.d_W);
+            uint32_t c = i - r * a.W;
+            uint32_t rowoff = lfc_row<ND>(a, r);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lfc = Elem<T>::load(lp, rowoff + fdiv(c, a.d_B));
+                o[e] = dequant((w >> (e * BITS)) & Lq, dd.y, dd.x, lfc);
+                if (++c == a.W) { c = 0; ++r; rowoff = lfc_row<ND>(a, r); }
+            }
+            store4(out, e0, o[0], o[1], o[2], o[3]);
+            continue;
+        }
+        uint32_t r = fdiv(i, a.d_W);
+        uint32_t c = i - r * a.W;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            o[e] = 0.0f;
+            if (e0 + e < n) {
+                const float2 dd = s_meta[g];
+                const uint32_t q = (s_codes[g * a.WPP + i / CPW] >> ((i % CPW) * BITS)) & Lq;
+                const float lfc = Elem<T>::load(s_lfc, g * a.nb + lfc_row<ND>(a, r) + fdiv(c, a.d_B));
+                o[e] = dequant(q, dd.y, dd.x, lfc);
+                ++i;
+                if (++c == a.W) { c = 0; ++r; }
+                if (i == a.HW) { i = 0; r = 0; c = 0; ++g; }
+            }
+        }
+        if (e0 + 4 <= n) {
+            store4(out, e0, o[0], o[1], o[2], o[3]);
+        } else {
+            for (int e = 0; e < 4; ++e)
+                if (e0 + e < n) Elem<T>::store(out, e0 + e, o[e]);
+        }
+    }
+}
+
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_flat(DecArgs a) { decompress_flat_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_flat_3d(DecArgs a) { decompress_flat_body<T, BITS, 3>(a); }
+
+// Maps whose rows are not whole vectors (odd widths, odd plane sizes) with several blocks per
+// plane: the chunk of G planes is rebuilt in LDS first, a lane per packed word (the word's
+// elements lie in one plane; the lane walks them with a running row and column, starting at a
+// lane-dependent element so that the lanes of a wavefront write to different banks), then leaves
+// with aligned 16-byte stores like the other streaming kernels (G*HW is a multiple of 4 except in
+// the last chunk, whose ragged end is scalar).
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void decompress_words_body(const DecArgs& a) {
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
+    uint32_t* s_codes; float2* s_meta; T* s_lfc;
+    dec_lds<T>(a, s_codes, s_meta, s_lfc);
+    extern __shared__ float4 smem4[];
+    float* s_out = reinterpret_cast<float*>(reinterpret_cast<char*>(smem4) + a.out_off);
+    constexpr uint32_t CPW = 32 / BITS;
+    constexpr uint32_t Lq = (1u << BITS) - 1u;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t p0 = blockIdx.x * a.G;
+    const uint32_t Gc = min(a.G, a.P - p0);
+    stage_packed<T>(a, pt, p0, Gc, s_codes, s_meta, s_lfc, tid);      // ends with a barrier
+
+    // ---- Sec. 4.2 and the reconstruction equation, a packed word per lane and step
+    const uint32_t nwords = Gc * a.WPP;
+    const uint32_t rot = (tid / (64u / CPW)) & (CPW - 1u);           // lanes CPW floats apart share a bank
+    for (uint32_t wi = tid; wi < nwords; wi += kThreads) {
+        const uint32_t g = fdiv(wi, a.d_wpp);
+        const uint32_t k = wi - g * a.WPP;
+        const uint32_t word = s_codes[wi];
+        const float2 dd = s_meta[g];
+        const T* lp = s_lfc + g * a.nb;
+        float* op = s_out + g * a.HW;
+        const uint32_t i0 = k * CPW;
+        const uint32_t cnt = min(CPW, a.HW - i0);                   // elements of the plane in this word
+        // start at element `rot` of the word, go to its end, then from its first element up to rot
+        uint32_t e = rot;
+        uint32_t r = fdiv(i0 + e, a.d_W);
+        uint32_t c = i0 + e - r * a.W;
+        uint32_t rowoff = lfc_row<ND>(a, r);
+#pragma unroll
+        for (uint32_t step = 0; step < CPW; ++step) {
+            if (e < cnt) {
+                const float lfc = Elem<T>::load(lp, rowoff + fdiv(c, a.d_B));
+                op[i0 + e] = dequant((word >> (e * BITS)) & Lq, dd.y, dd.x, lfc);
+            }
+            ++e;
+            if (e == CPW) {                                          // wrap to the word's first element
+                e = 0;
+                r = fdiv(i0, a.d_W);
+                c = i0 - r * a.W;
+                rowoff = lfc_row<ND>(a, r);
+            } else if (++c == a.W) {
+                c = 0;
+                ++r;
+                rowoff = lfc_row<ND>(a, r);
+            }
+        }
+    }
+    lds_barrier();
+
+    // ---- out: 16-byte stores of the rebuilt chunk
+    const uint32_t n = Gc * a.HW;
+    T* out = static_cast<T*>(pt.xhat) + (size_t)p0 * a.HW;
+    const uint32_t nvec = n >> 2;
+    for (uint32_t v = tid; v < nvec; v += kThreads) {
+        const float4 o = reinterpret_cast<const float4*>(s_out)[v];
+        store4(out, (size_t)v * 4, o.x, o.y, o.z, o.w);
+    }
+    for (uint32_t t = (nvec << 2) + tid; t < n; t += kThreads) Elem<T>::store(out, t, s_out[t]);
+}
+
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_words(DecArgs a) { decompress_words_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_words_3d(DecArgs a) { decompress_words_body<T, BITS, 3>(a); }
+
+// 2-D planes whose rows or blocks are not whole vectors (odd widths), the counterpart of compress_units:
+// a lane step rebuilds four consecutive elements of the plane whatever the width and writes them with
+// one store (planes start on 4-byte boundaries).  Which block each element belongs to is the same for
+// every plane: a table of LDS offsets made once per workgroup, which then takes planes blockIdx.x,
+// blockIdx.x + gridDim.x, ...  A plane's LFC goes through LDS (two buffers, one barrier per plane);
+// the next plane's codes, LFC and meta are loaded while the current one is rebuilt.
+constexpr int kUnitsLfc = 4;      // LFC values a lane stages per plane: planes of up to 4 * threads blocks
+template <typename T, int BITS, int NW>
+__global__ void __launch_bounds__(64 * NW) decompress_units(DecArgs a) {
+    constexpr int NT = 64 * NW;
+    constexpr int K = kUnitsK;
+    constexpr int KL = kUnitsLfc;
+    constexpr uint32_t CB = BITS / 2;                  // code bytes per unit
+    constexpr uint32_t Lq = (1u << BITS) - 1u;
+    extern __shared__ float4 smem4[];
+    float* lbuf = reinterpret_cast<float*>(smem4);     // [2][nbp]
+    const uint32_t nbp = (a.nb + 3u) & ~3u;
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
+    const uint32_t tid = threadIdx.x;
+    auto round_live = [&](int k) -> bool { return (uint32_t)(NT * k) < a.q4; };
+
+    // 2-byte elements, odd planes of an odd element count: the plane starts in the middle of a dword.
+    // Its units then start one element early, so that every store is dword-aligned; the element before
+    // the plane and those past it are left alone.  The same for all planes of the workgroup: the grid is
+    // even then, or every workgroup has one plane.
+    const uint32_t shift = sizeof(T) == 2 ? (blockIdx.x * a.HW) & 1u : 0u;
+
+    // LDS byte offset of the LFC of each element's block (elements outside the plane: block 0, never stored)
+    uint32_t lo[K][2];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        uint32_t off[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t e = 4u * (tid + NT * k) + j - shift;       // wraps for the element before the plane
+            const uint32_t r = fdiv(e, a.d_W);
+            const uint32_t c = e - r * a.W;
+            off[j] = e < a.HW ? 4u * (fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B)) : 0u;
+        }
+        lo[k][0] = off[0] | (off[1] << 16);
+        lo[k][1] = off[2] | (off[3] << 16);
+    }
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    uint32_t codes[K];
+    u32x2 wide[sizeof(T) == 2 ? K : 1];                // shifted units: the two code words a unit's codes lie in
+    float lf[KL];
+    float2 dd;
+    auto issue_loads = [&](uint32_t p) {
+        const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint32_t*>(pt.codes) + (size_t)p * a.WPP, 0, (int)(a.q4 * CB), 0x00020000);
+        if constexpr (sizeof(T) == 2) {
+            if (shift) {
+                // codes of elements 4f-1 .. 4f+2: 4 * BITS bits from bit (4f-1) * BITS of the plane's code words
+                const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<uint32_t*>(pt.codes) + (size_t)p * a.WPP, 0, (int)(a.WPP * 4u), 0x00020000);
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    if (!round_live(k)) continue;
+                    const uint32_t f = tid + NT * k;
+                    const uint32_t bit = f ? (4u * f - 1u) * BITS : 0u;
+                    wide[k] = __builtin_amdgcn_raw_buffer_load_b64(wrs, (bit >> 5) * 4u, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            if (!round_live(k) || shift) continue;
+            if constexpr (CB == 1) codes[k] = __builtin_amdgcn_raw_buffer_load_b8(crs, tid, k * NT, 0);
+            else if constexpr (CB == 2) codes[k] = __builtin_amdgcn_raw_buffer_load_b16(crs, tid * 2u, k * NT * 2, 0);
+            else codes[k] = __builtin_amdgcn_raw_buffer_load_b32(crs, tid * 4u, k * NT * 4, 0);
+        }
+#pragma unroll
+        for (int m = 0; m < KL; ++m) {
+            const uint32_t t = tid + NT * m;
+            if ((uint32_t)(NT * m) < a.nb) lf[m] = t < a.nb ? lfc_load<T>(pt.lfc, (size_t)p * a.nb + t, kC16<T>) : 0.0f;
+        }
+        dd = meta_load(pt.meta, p, kC16<T>);
+    };
+
+    if (blockIdx.x < a.P) issue_loads(blockIdx.x);
+    uint32_t flip = 0;
+    for (uint32_t p = blockIdx.x; p < a.P; p += gridDim.x, flip ^= 1u) {
+        float* lfcs = lbuf + flip * nbp;
+#pragma unroll
+        for (int m = 0; m < KL; ++m) {
+            const uint32_t t = tid + NT * m;
+            if ((uint32_t)(NT * m) < a.nb && t < a.nb) lfcs[t] = lf[m];
+        }
+        uint32_t c4[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            c4[k] = 0u;
+            if (!round_live(k)) continue;
+            if constexpr (sizeof(T) == 2) {
+                if (shift) {
+                    const uint32_t f = tid + NT * k;
+                    const uint32_t bit = f ? (4u * f - 1u) * BITS : 0u;
+                    const uint32_t c = __builtin_amdgcn_alignbit(wide[k].y, wide[k].x, bit & 31u);
+                    c4[k] = f ? c : c << BITS;             // unit 0: the slot before the plane, then elements 0, 1, 2
+                    continue;
+                }
+            }
+            c4[k] = codes[k];
+        }
+        const float2 sc = dd;
+        if (p + gridDim.x < a.P) issue_loads(p + gridDim.x);
+        if constexpr (NW == 1) wave_sync(); else lds_barrier();
+
+        T* out = static_cast<T*>(pt.xhat) + (size_t)p * a.HW;       // element e of the plane at out[e]
+        const char* lb = reinterpret_cast<const char*>(lfcs);
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            if (!round_live(k)) continue;
+            const uint32_t f = tid + NT * k;
+            float o[4];
+            o[0] = dequant(c4[k] & Lq, sc.y, sc.x, *reinterpret_cast<const float*>(lb + (lo[k][0] & 0xffffu)));
+            o[1] = dequant((c4[k] >> BITS) & Lq, sc.y, sc.x, *reinterpret_cast<const float*>(lb + (lo[k][0] >> 16)));
+            o[2] = dequant((c4[k] >> (2 * BITS)) & Lq, sc.y, sc.x, *reinterpret_cast<const float*>(lb + (lo[k][1] & 0xffffu)));
+            o[3] = dequant((c4[k] >> (3 * BITS)) & Lq, sc.y, sc.x, *reinterpret_cast<const float*>(lb + (lo[k][1] >> 16)));
+            const uint32_t e0 = 4u * f - shift;                  // the unit's first element (wraps for unit 0 of a shifted plane)
+            if (e0 + 4u <= a.HW && (shift == 0u || f != 0u)) {
+                store4(out - shift, (size_t)f * 4, o[0], o[1], o[2], o[3]);
+            } else {
+                // a unit that reaches outside the plane (the last one when H*W is not a multiple of 4,
+                // the first one of a shifted plane): element by element
+#pragma unroll
+                for (uint32_t j = 0; j < 4; ++j) {
+                    const uint32_t e = e0 + j;
+                    if (e < a.HW) Elem<T>::store(out, e, o[j]);
+                }
+            }
+        }
+    }
+}
+
+// planes too large for the 32-bit index tricks above: one element per thread step
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void decompress_scalar_body(const DecArgs& a) {
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
+    constexpr uint32_t CPW = 32 / BITS;
+    constexpr uint32_t Lq = (1u << BITS) - 1u;
+    const uint32_t p = blockIdx.x;
+    const float2 dd = meta_load(pt.meta, p, kC16<T>);
+    const size_t lfc0 = (size_t)p * a.nb;
+    const uint32_t* cp = pt.codes + (size_t)p * a.WPP;
+    T* out = static_cast<T*>(pt.xhat) + (size_t)p * a.HW;
+    for (uint32_t i = threadIdx.x; i < a.HW; i += kThreads) {
+        const uint32_t r = i / a.W, c = i - r * a.W;
+        const uint32_t q = (cp[i / CPW] >> ((i % CPW) * BITS)) & Lq;
+        uint32_t brow;
+        if constexpr (ND == 3) {
+            const uint32_t z = r / a.Hs;
+            brow = (z / a.B) * a.LHs + (r - z * a.Hs) / a.B;
+        } else {
+            brow = r / a.B;
+        }
+        const float lfc = lfc_load<T>(pt.lfc, lfc0 + brow * a.LW + c / a.B, kC16<T>);
+        Elem<T>::store(out, i, dequant(q, dd.y, dd.x, lfc));
+    }
+}
+
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_scalar(DecArgs a) { decompress_scalar_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(kThreads) decompress_scalar_3d(DecArgs a) { decompress_scalar_body<T, BITS, 3>(a); }
+
+// One-block planes with an odd number of elements (the shapes compress_lane
+// takes): one wavefront per round of 64 planes, lane g reconstructs plane g from
+// its WPP code words into LDS (stride HW words, odd: no bank conflicts), then the
+// round leaves with coalesced 16-byte stores.  a.G = rounds per workgroup.
+template <typename T, int BITS>
+__global__ void __launch_bounds__(64) decompress_lane(DecArgs a) {
+    constexpr int CPW = 32 / BITS;
+    constexpr uint32_t Lmask = (1u << BITS) - 1u;
+    extern __shared__ float4 smem4[];
+    float* xs = reinterpret_cast<float*>(smem4);              // [64 * HW (+3)]
+    const uint32_t lane = threadIdx.x;
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
+    const uint32_t nrounds = (a.P + 63u) / 64u;
+    float* mine = xs + lane * a.HW;
+    const bool out_vec = (reinterpret_cast<uintptr_t>(pt.xhat) % (4 * sizeof(T))) == 0;
+
+    const uint32_t rend = min(nrounds, (blockIdx.x + 1) * a.G);
+    for (uint32_t round = blockIdx.x * a.G; round < rend; ++round) {
+        const uint32_t p0 = round * 64u;
+        const uint32_t Gc = min(64u, a.P - p0);
+        const uint32_t p = lane < Gc ? p0 + lane : p0;        // lanes past the last plane redo plane p0 (never stored)
+        const float2 dd = meta_load(pt.meta, p, kC16<T>);
+        const float lfc = lfc_load<T>(pt.lfc, p, kC16<T>);
+        const uint32_t* cp = pt.codes + (size_t)p * a.WPP;
+        const uint32_t wfull = a.HW / CPW;
+        for (uint32_t w = 0; w < wfull; ++w) {
+            const uint32_t word = cp[w];
+#pragma unroll
+            for (int j = 0; j < CPW; ++j) mine[w * CPW + j] = dequant((word >> (j * BITS)) & Lmask, dd.y, dd.x, lfc);
+        }
+        const uint32_t left = a.HW - wfull * CPW;
+        if (left) {
+            const uint32_t word = cp[wfull];
+            for (uint32_t j = 0; j < left; ++j) mine[wfull * CPW + j] = dequant((word >> (j * BITS)) & Lmask, dd.y, dd.x, lfc);
+        }
+        wave_sync();
+
+        const uint32_t n = Gc * a.HW;
+        T* out = static_cast<T*>(pt.xhat) + (size_t)p0 * a.HW;
+        const uint32_t nv = out_vec ? n / 4u : 0u;
+        for (uint32_t vi = lane; vi < nv; vi += 64) {
+            const float4 f = reinterpret_cast<const float4*>(xs)[vi];
+            store4(out, (size_t)vi * 4, f.x, f.y, f.z, f.w);
+        }
+        for (uint32_t e = nv * 4u + lane; e < n; e += 64) Elem<T>::store(out, e, xs[e]);
+        wave_sync();      // LDS is reused by the next round
+    }
+}
