@@ -5,14 +5,15 @@
 struct UnitsArgs {
     CompTab tab;
     Regions rg;
-    uint32_t P, H, W, HW, LW, nb, WPP, B;
+    uint32_t P, H, W, HW, LW, nb, WPP, B;      // H = rows of one depth slice
+    uint32_t D, LH, Bz;  // depth slices (1: a 2-D map), block rows per slice, depth of a block (B, or 1 for 2-D maps)
     uint32_t q4;         // units (4 consecutive elements) per plane, the last one may be partly past it
     uint32_t q4p;        // q4 rounded up to whole rounds of the plane's lanes
-    uint32_t nitem;      // nb * B row segments
+    uint32_t nitem;      // nb * Bz * B row segments
     uint32_t S, S_log2;  // instance NW = 0: lanes per plane (8, 16 or 32), 64 / S planes per wavefront
     uint32_t reg_bytes;  // LDS bytes of one plane's region (a multiple of 16)
     uint32_t nrounds;    // rounds of planes the grid walks over: P, or P / (64 / S) rounded up (NW = 0)
-    FastDiv d_W, d_B, d_LW;
+    FastDiv d_W, d_B, d_LW, d_H, d_BBz, d_slice;      // d_BBz divides by Bz * B, d_slice by LH * LW
 };
 
 // Planes whose rows or blocks are not whole 16-byte vectors (odd widths: 55 x 55, 27 x 27,
@@ -26,6 +27,8 @@ struct UnitsArgs {
 // binary64 (lanes of one block read rows W floats apart: no bank conflicts for odd W), a lane per
 // block adds its rows; the residual goes back to LDS and is quantised from there.  Elements of
 // the last unit past the plane take the NaN sentinel like whole units past it.
+// 3-D maps (Appendix D): planes of D x H x W elements with blocks of B x B x B; an element's block
+// and the row segments of a block are found with the depth as a third coordinate, the rest is the same.
 // NW = 1 .. 16: the NW wavefronts of the workgroup share one plane (S = 64 * NW).  NW = 0: small
 // planes (below 512 elements), S = 8, 16 or 32 lanes per plane and 64 / S planes per wavefront,
 // each with its own LDS region; reductions stay inside the S lanes.
@@ -72,24 +75,29 @@ __global__ void __launch_bounds__(NW ? 64 * NW : 64) compress_units(UnitsArgs a)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t e = 4u * (l + S * k) + j;
-            const uint32_t r = fdiv(e, a.d_W);
-            const uint32_t c = e - r * a.W;
-            off[j] = 4u * (e < a.HW ? fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B) : a.nb);
+            const uint32_t ra = fdiv(e, a.d_W);                       // row, counted over all depth slices
+            const uint32_t c = e - ra * a.W;
+            const uint32_t z = fdiv(ra, a.d_H);
+            const uint32_t r = ra - z * a.H;
+            off[j] = 4u * (e < a.HW ? (fdiv(z, a.d_B) * a.LH + fdiv(r, a.d_B)) * a.LW + fdiv(c, a.d_B) : a.nb);
         }
         lo[k][0] = off[0] | (off[1] << 16);
         lo[k][1] = off[2] | (off[3] << 16);
     }
-    // the row segments of the lane (item i = block * B + row of the block): where the segment starts in
-    // the plane, and in the top bits how many elements it has (0: a row past the map, or no item)
+    // the row segments of the lane (item i = (block * Bz + slice of the block) * B + row of the block):
+    // where the segment starts in the plane, and in the top bits how many elements it has (0: a row or
+    // slice past the map, or no item)
     uint32_t it[K];
 #pragma unroll
     for (int m = 0; m < K; ++m) {
         const uint32_t i = l + S * m;
-        const uint32_t t = fdiv(i, a.d_B), rr = i - t * a.B;
-        const uint32_t bi = fdiv(t, a.d_LW), bj = t - bi * a.LW;
-        const uint32_t r = bi * a.B + rr;
+        const uint32_t t = fdiv(i, a.d_BBz), rem = i - t * (a.Bz * a.B);
+        const uint32_t zz = fdiv(rem, a.d_B), rr = rem - zz * a.B;
+        const uint32_t bd = fdiv(t, a.d_slice), t2 = t - bd * (a.LH * a.LW);
+        const uint32_t bi = fdiv(t2, a.d_LW), bj = t2 - bi * a.LW;
+        const uint32_t z = bd * a.B + zz, r = bi * a.B + rr;
         const uint32_t bw = min(a.B, a.W - bj * a.B);
-        it[m] = (i < a.nitem && r < a.H) ? (r * a.W + bj * a.B) | (bw << 20) : 0u;
+        it[m] = (i < a.nitem && z < a.D && r < a.H) ? ((z * a.H + r) * a.W + bj * a.B) | (bw << 20) : 0u;
     }
     if (l == 0) lfcs[a.nb] = __builtin_nanf("");
     const uint32_t tail = a.HW & 3u;          // elements of the last unit inside the plane (0: all four)
@@ -164,14 +172,17 @@ __global__ void __launch_bounds__(NW ? 64 * NW : 64) compress_units(UnitsArgs a)
         }
         sync();
 
-        // ---- step 2: a lane per block adds its rows from the top down
+        // ---- step 2: a lane per block adds its rows, slice by slice from the top down
         for (uint32_t t = l; t < a.nb; t += S) {
-            const uint32_t bi = fdiv(t, a.d_LW), bj = t - bi * a.LW;
+            const uint32_t bd = fdiv(t, a.d_slice), t2 = t - bd * (a.LH * a.LW);
+            const uint32_t bi = fdiv(t2, a.d_LW), bj = t2 - bi * a.LW;
+            const uint32_t deps = min(a.Bz, a.D - bd * a.B);
             const uint32_t rows = min(a.B, a.H - bi * a.B);
             const uint32_t bw = min(a.B, a.W - bj * a.B);
             double Sb = 0.0;
-            for (uint32_t rr = 0; rr < rows; ++rr) Sb += rsum[t * a.B + rr];
-            const float lfc = lfc_round<T>(mean_of(Sb, rows * bw), kC16<T>);
+            for (uint32_t zz = 0; zz < deps; ++zz)
+                for (uint32_t rr = 0; rr < rows; ++rr) Sb += rsum[(t * a.Bz + zz) * a.B + rr];
+            const float lfc = lfc_round<T>(mean_of(Sb, deps * rows * bw), kC16<T>);
             lfcs[t] = lfc;
             if (pv) lfc_store<T>(pt.lfc, (size_t)p * a.nb + t, lfc, kC16<T>);
         }

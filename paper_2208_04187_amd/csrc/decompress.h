@@ -387,7 +387,7 @@ __global__ void __launch_bounds__(kThreads) decompress_words(DecArgs a) { decomp
 template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) decompress_words_3d(DecArgs a) { decompress_words_body<T, BITS, 3>(a); }
 
-// 2-D planes whose rows or blocks are not whole vectors (odd widths), the counterpart of compress_units:
+// Planes (2-D or 3-D maps) whose rows or blocks are not whole vectors (odd widths), the counterpart of compress_units:
 // a lane step rebuilds four consecutive elements of the plane whatever the width and writes them with
 // one store (planes start on 4-byte boundaries).  Which block each element belongs to is the same for
 // every plane: a table of LDS offsets made once per workgroup, which then takes planes blockIdx.x,
@@ -422,9 +422,11 @@ __global__ void __launch_bounds__(64 * NW) decompress_units(DecArgs a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t e = 4u * (tid + NT * k) + j - shift;       // wraps for the element before the plane
-            const uint32_t r = fdiv(e, a.d_W);
-            const uint32_t c = e - r * a.W;
-            off[j] = e < a.HW ? 4u * (fdiv(r, a.d_B) * a.LW + fdiv(c, a.d_B)) : 0u;
+            const uint32_t ra = fdiv(e, a.d_W);                       // row, counted over all depth slices
+            const uint32_t c = e - ra * a.W;
+            const uint32_t z = fdiv(ra, a.d_Hs);
+            const uint32_t r = ra - z * a.Hs;
+            off[j] = e < a.HW ? 4u * ((fdiv(z, a.d_B) * a.LHs + fdiv(r, a.d_B)) * a.LW + fdiv(c, a.d_B)) : 0u;
         }
         lo[k][0] = off[0] | (off[1] << 16);
         lo[k][1] = off[2] | (off[3] << 16);

@@ -21,14 +21,14 @@
 //   compress_lane    one-block planes with an odd element count (7x7): a lane per plane
 //   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8: a lane
 //                    per pooling item, loaded straight from global memory, DPP reductions
-//   compress_units   2-D planes of 256 to about 27K elements whose rows or blocks are not whole 16-byte vectors
+//   compress_units   planes (2-D or 3-D maps) of 256 to about 27K elements whose rows or blocks are not whole 16-byte vectors
 //                    (odd widths: 27x27, 55x55, 147x147; B = 18): four consecutive elements per lane step
 //                    whatever the width, the block of each element looked up in a table made once per
 //                    workgroup, the plane parked in LDS for the block sums, next plane's loads in flight
 //   compress_wave    other planes up to 17 KB, B = 4, 8: one wavefront per chunk of planes staged in LDS
 //   compress_tile    other planes up to 156 KB, B = 4, 8: four wavefronts per chunk staged in LDS
 //   compress_one     planes that are a single block (B = 64 on 56x56 and below): flat vectors in registers
-//   compress_rows    any block size, 3-D maps: chunk staged in LDS, vectors kept in registers for Quant
+//   compress_rows    any block size, small 3-D maps: chunk staged in LDS, vectors kept in registers for Quant
 //   compress_plane   planes beyond LDS with vector rows and blocks (video volumes, image-sized maps):
 //                    a workgroup per plane, two vector passes over x
 //   compress_any     everything else (giant planes with odd extents): scalar, slow

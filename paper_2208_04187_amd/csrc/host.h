@@ -173,13 +173,14 @@ constexpr uint64_t kUnitsSubMin = 64;     // units per plane from which the inst
                                           // (17 x 17: 1.7 -> 2.3 TB/s; 13 x 13 and 15 x 15 are no faster than in compress_wave)
 bool plan_units(const Layout& L, int64_t D, int64_t H, int64_t W, int B, size_t es, const void* x,
                 UnitsArgs* a, uint32_t* grid, size_t* lds, int* nw_out) {
-    if (D != 1 || H == 1 || ((uintptr_t)x % 4) != 0) return false;
+    if (H == 1 || ((uintptr_t)x % 4) != 0) return false;
     // small planes of even width under B = 4 and 8 are the wavefront kernel's (pairs of elements per
     // lane): measured faster there
-    if ((B == 4 || B == 8) && W % 2 == 0 && 4ull * L.HW + 16ull <= kWavePlaneMax) return false;
+    if (D == 1 && (B == 4 || B == 8) && W % 2 == 0 && 4ull * L.HW + 16ull <= kWavePlaneMax) return false;
     const uint64_t q4 = (L.HW + 3) / 4;
     if (L.nb > 16383 || B > 4095) return false;              // LFC offsets are kept as 16-bit byte offsets
-    const uint64_t nitem = L.nb * (uint64_t)B;
+    const uint64_t Bz = D > 1 ? (uint64_t)B : 1;              // depth of a block
+    const uint64_t nitem = L.nb * Bz * (uint64_t)B;
     int nw = 1;
     uint64_t S = 64;                                          // lanes per plane
     if (q4 < kUnitsMin) {
@@ -196,10 +197,15 @@ bool plan_units(const Layout& L, int64_t D, int64_t H, int64_t W, int B, size_t 
     if (q4 > (uint64_t)kUnitsK * S || nitem > (uint64_t)kUnitsK * S) return false;       // 8 units and 8 row segments per lane
     const uint64_t q4p = (q4 + S - 1) / S * S;
     if (!fastdiv_ok(4ull * kUnitsK * S + 4, (uint64_t)W) || !fastdiv_ok(4ull * kUnitsK * S + 4, (uint64_t)B) ||
-        !fastdiv_ok(nitem + S, (uint64_t)B) || !fastdiv_ok(L.nb + S, L.LW))
+        !fastdiv_ok(nitem + S, (uint64_t)B * Bz) || !fastdiv_ok(L.nb + S, L.LH * L.LW) ||
+        !fastdiv_ok(4ull * kUnitsK * S + 4, (uint64_t)H))
         return false;
     a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->W = (uint32_t)W; a->HW = (uint32_t)L.HW;
     a->LW = (uint32_t)L.LW; a->nb = (uint32_t)L.nb; a->WPP = (uint32_t)L.WPP; a->B = (uint32_t)B;
+    a->D = (uint32_t)D; a->LH = (uint32_t)L.LH; a->Bz = (uint32_t)Bz;
+    a->d_H = make_fastdiv((uint32_t)H);
+    a->d_BBz = make_fastdiv((uint32_t)(Bz * (uint64_t)B));
+    a->d_slice = make_fastdiv((uint32_t)(L.LH * L.LW));
     a->q4 = (uint32_t)q4; a->q4p = (uint32_t)q4p; a->nitem = (uint32_t)nitem;
     a->S = (uint32_t)S;
     a->S_log2 = 0;
@@ -624,15 +630,16 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
             return 3;
         }
     }
-    // 2-D planes of 512 elements and more whose rows or blocks are not whole vectors: four consecutive
+    // planes (2-D or 3-D) of 512 elements and more whose rows or blocks are not whole vectors: four consecutive
     // elements per lane step, planes starting on 4-byte boundaries
-    if (D == 1 && Hs > 1 && small_idx && ((uintptr_t)xhat % 4) == 0 && L.nb <= 16383) {
+    if (Hs > 1 && small_idx && ((uintptr_t)xhat % 4) == 0 && L.nb <= 16383) {
         const uint64_t q4 = (L.HW + 3) / 4;
         int nw = 1;
         while (nw < 16 && (q4 > (uint64_t)kUnitsK * 64 * nw || L.nb > (uint64_t)kUnitsLfc * 64 * nw)) nw *= 2;
         const uint64_t nt = 64ull * nw;
         if (q4 >= kUnitsMin && q4 <= (uint64_t)kUnitsK * nt && L.nb <= (uint64_t)kUnitsLfc * nt &&
-            fastdiv_ok(4ull * kUnitsK * nt + 4, (uint64_t)W) && fastdiv_ok(4ull * kUnitsK * nt + 4, (uint64_t)B)) {
+            fastdiv_ok(4ull * kUnitsK * nt + 4, (uint64_t)W) && fastdiv_ok(4ull * kUnitsK * nt + 4, (uint64_t)B) &&
+            fastdiv_ok(4ull * kUnitsK * nt + 4, (uint64_t)Hs)) {
             a->q4 = (uint32_t)q4;
             a->G = (uint32_t)nw;                  // wavefronts per workgroup
             uint64_t g = (uint64_t)num_cus() * (16ull / nw);

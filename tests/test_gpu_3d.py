@@ -36,6 +36,12 @@ CASES = [
     ((2, 3, 7, 30, 1), 8, 2),                     # W = 1: a D x H map
     ((2, 3, 1, 28, 28), 8, 2),                    # D = 1: the 2-D call
     ((70, 9, 4, 4, 4), 4, 2),                     # 630 small planes, ragged last chunk
+    ((2, 3, 4, 14, 14), 8, 2),                    # 784 elements, rows of 14: four consecutive elements per lane step
+    ((2, 2, 3, 35, 35), 4, 4),                    # odd rows, 3675 elements (odd: 2-byte planes start mid-dword)
+    ((2, 2, 8, 27, 27), 8, 2),                    # 5832 elements, four wavefronts per plane
+    ((2, 3, 6, 10, 11), 5, 8),                    # blocks of 5: 2 x 2 x 3 of them, ragged in every direction
+    ((5, 3, 4, 9, 9), 8, 2),                      # 324 elements: 16 lanes per plane
+    ((3, 2, 5, 7, 7), 4, 2),                      # 245 elements: the chunk kernels
 ]
 
 
@@ -68,11 +74,16 @@ def test_volume_kernels_cover_what_the_cases_claim():
     assert kn(0, (2, 3, 4, 28, 28), 8, 2) == "compress_regs_3d<float, 2, 8, 1>"
     assert kn(0, (1, 2, 16, 56, 56), 8, 2) == "compress_regs_3d<float, 2, 8, 16>"
     assert kn(0, (1, 2, 16, 56, 56), 8, 2, torch.bfloat16) == "compress_regs_3d<bf16_t, 2, 8, 16>"
-    assert kn(0, (2, 3, 5, 9, 13), 4, 2) == "compress_rows_3d<float, 2>"
+    assert kn(0, (2, 3, 5, 9, 13), 4, 2) == "compress_units<float, 2, 1>"
+    assert kn(0, (2, 2, 8, 27, 27), 8, 2) == "compress_units<float, 2, 4>"
+    assert kn(0, (5, 3, 4, 9, 9), 8, 2) == "compress_units<float, 2, 0>"
+    assert kn(0, (3, 2, 5, 7, 7), 4, 2) == "compress_rows_3d<float, 2>"
     assert kn(0, (1, 2, 24, 40, 64), 16, 2) == "compress_plane_3d<float, 2>"
     assert kn(0, (1, 2, 33, 35, 37), 16, 2) == "compress_any_3d<float, 2>"
     assert kn(1, (3, 5, 16, 16, 16), 8, 2) == "decompress_rowvec_3d<float, 2>"
-    assert kn(1, (2, 3, 5, 9, 13), 4, 2) == "decompress_words_3d<float, 2>"
+    assert kn(1, (2, 3, 5, 9, 13), 4, 2) == "decompress_units<float, 2, 1>"
+    assert kn(1, (2, 2, 3, 35, 35), 4, 4, torch.bfloat16) == "decompress_units<bf16_t, 4, 2>"
+    assert kn(1, (3, 2, 5, 7, 7), 4, 2) == "decompress_words_3d<float, 2>"
     assert kn(1, (1, 2, 40, 40, 40), 8, 8) == "decompress_scalar_3d<float, 8>"
     assert kn(0, (4, 9, 3, 3, 3), 8, 2) == "compress_lane<float, 2>"
     assert kn(0, (2, 3, 7, 1, 30), 8, 2) == pkg.division_kernel_name(0, (2, 3, 7, 30), 8, 2)
