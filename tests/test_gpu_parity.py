@@ -858,7 +858,7 @@ def test_bfloat16_cached_mode_full_size_resnet50_set():
 
 # ---------------------------------------------------------------- byte offsets beyond 4 GiB
 
-@pytest.mark.parametrize("shape,B,b", [((1400, 256, 56, 56), 8, 2), ((1100, 1024, 32, 32), 4, 4)])
+@pytest.mark.parametrize("shape,B,b", [((1400, 256, 56, 56), 8, 2), ((1100, 1024, 32, 32), 4, 4), ((3700, 96, 55, 55), 4, 2)])
 def test_full_size_maps_larger_than_4GiB(shape, B, b):
     """1.1 G elements (4.5 GB of fp32): plane offsets in bytes and in elements pass 2^32 resp. 2^30;
     the last planes are the ones a 32-bit index would send elsewhere."""
