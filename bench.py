@@ -222,6 +222,30 @@ def masks(args, torch, pkg, dev) -> int:
         ops["relu_compress_fused" if pkg.division_relu_compress_fused(tuple(x.shape), sp_B, sp_b) else "relu_compress_unfused_shape"] = (
             lambda i: pkg.division_relu_compress(xs[i % nsets], sp_B, sp_b, i, out=ys[i % nsets], mask=ms[i % nsets],
                                                  packed=pks[i % nsets]), 2 * n * es + n / 8 + pkb)
+        # the same pair on the other shapes of the workload (one map each)
+        seen = {tuple(x.shape)}
+        for _, sp2, x2 in draw_config(args.config, args.batch):
+            if tuple(x2.shape) in seen or x2.dim() != 4 or sp2.dtype == "bf16":
+                continue
+            seen.add(tuple(x2.shape))
+            n2 = x2.numel()
+            xs2 = [(torch.roll(x2, s, 0) - 0.5 * (s + 1)).to(dev) for s in range(nsets)]
+            ys2 = [torch.empty_like(t) for t in xs2]
+            ms2 = [torch.empty(pkg.division_mask_bytes(n2) // 4, dtype=torch.int32, device=dev) for _ in xs2]
+            pkb2 = pkg.division_packed_bytes(*x2.shape, sp_B, sp_b)
+            pks2 = [torch.empty(pkb2, dtype=torch.uint8, device=dev) for _ in xs2]
+            tag = "x".join(map(str, x2.shape))
+            fused2 = pkg.division_relu_compress_fused(tuple(x2.shape), sp_B, sp_b)
+
+            def two2(i, xs2=xs2, ys2=ys2, ms2=ms2, pks2=pks2):
+                pkg.division_relu_forward(xs2[i % nsets], out=ys2[i % nsets], mask=ms2[i % nsets])
+                pkg.division_compress(ys2[i % nsets], sp_B, sp_b, i, packed=pks2[i % nsets])
+
+            def one2(i, xs2=xs2, ys2=ys2, ms2=ms2, pks2=pks2):
+                pkg.division_relu_compress(xs2[i % nsets], sp_B, sp_b, i, out=ys2[i % nsets], mask=ms2[i % nsets], packed=pks2[i % nsets])
+
+            ops["relu_then_compress_two_kernels " + tag] = (two2, 3 * n2 * 4 + n2 / 8 + pkb2)
+            ops[("relu_compress_fused " if fused2 else "relu_compress_unfused_shape ") + tag] = (one2, 2 * n2 * 4 + n2 / 8 + pkb2)
     res = {}
     for name, (fn, nbytes) in ops.items():
         med, mn = timed_us(fn)

@@ -14,6 +14,8 @@ struct ItemsArgs {
     uint32_t rpw;        // rounds a workgroup handles one after the other
     uint32_t nrounds;    // ceil(P / ppr)
     FastDiv d_ipr;
+    void* y;             // relu_compress_items: the activation's output map and its 1-bit mask (one map per launch);
+    uint32_t* mask;      // rpw * ppr * HW is a multiple of 32 then: a workgroup's mask bits are whole words
 };
 
 // Small planes (at most 64 pooling items, e.g. 28x28 and 14x14 with B = 8): one
@@ -26,13 +28,18 @@ struct ItemsArgs {
 // OR-ed into the round's packed words in LDS (cleared first, so pad bits stay
 // zero), which then leave as whole coalesced words.  R = rows an item holds: B, or 1 for
 // maps of a single row (1-D maps), whose items would otherwise carry B - 1 masked rows.
-template <typename T, int BITS, int B, int VEC, int R>
-__global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
+// RELU: x is the input of a Relu operator (Appendix, Relu listing) whose output y is the map to
+// cache: y = x where x > 0 else +0 is written out row by row as it was loaded, and y is what gets
+// compressed.  The 1-bit mask (bit i of the whole map = x_i > 0) of the planes a workgroup handles
+// is OR-ed together in LDS and leaves as whole words when the workgroup is done.
+template <typename T, int BITS, int B, int VEC, int R, bool RELU>
+__device__ __forceinline__ void compress_items_body(const ItemsArgs& a) {
     constexpr int IPB = B / VEC;          // items per block (power of two)
     constexpr int CPW = 32 / BITS;        // codes per word
     constexpr float Lf = float((1 << BITS) - 1);
     extern __shared__ float4 smem4[];
     uint32_t* cw = reinterpret_cast<uint32_t*>(smem4);        // [ppr * WPP] packed words of the round
+    uint32_t* mw = cw + ((a.ppr * a.WPP + 3u) & ~3u);         // RELU: [rpw * ppr * HW / 32] mask words of the workgroup
 
     const uint32_t lane = threadIdx.x;
     const CompPtrs pt = comp_ptrs(a.tab, a.rg, lane);
@@ -56,6 +63,11 @@ __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
     const uint32_t rwords = a.ppr * a.WPP;
 
     const uint32_t rend = min(a.nrounds, (blockIdx.x + 1) * a.rpw);
+    const uint32_t mbits = a.rpw * a.ppr * a.HW;               // RELU: mask bits of a workgroup (a multiple of 32)
+    if constexpr (RELU) {
+        for (uint32_t w = lane; w < mbits / 32u; w += 64) mw[w] = 0u;
+        wave_sync();
+    }
     for (uint32_t round = blockIdx.x * a.rpw; round < rend; ++round) {
         const uint32_t p0 = round * a.ppr;
         const uint32_t Gc = min(a.ppr, a.P - p0);
@@ -96,6 +108,49 @@ __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
         }
         // the round's packed words start at zero
         for (uint32_t w = lane; w < rwords; w += 64) cw[w] = 0u;
+        if constexpr (RELU) {
+            // y = Relu(x) back to memory the way x came in, the mask bits of the rows into LDS
+            T* ydst = static_cast<T*>(a.y) + (size_t)p0 * a.HW;
+            const __amdgpu_buffer_rsrc_t yrs =
+                __builtin_amdgcn_make_buffer_rsrc(ydst, 0, (int)(Gc * a.HW * sizeof(T)), 0x00020000);
+            const uint32_t base = (g * a.HW + off) * (uint32_t)sizeof(T);
+            const uint32_t rowb = a.W * (uint32_t)sizeof(T);
+            const uint32_t bit0 = (round - blockIdx.x * a.rpw) * a.ppr * a.HW + g * a.HW + off;    // of the item's first row
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr) {
+                uint32_t bits = 0;
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) {
+                    const bool pos = v[rr][c] > 0.0f;
+                    bits |= (pos ? 1u : 0u) << c;
+                    v[rr][c] = pos ? v[rr][c] : 0.0f;
+                }
+                if (!valid || !(fullrows || (uint32_t)rr < nrows)) continue;
+                const uint32_t vo = base + (uint32_t)rr * rowb;
+                if constexpr (sizeof(T) == 4 && VEC == 4) {
+                    u32x4 o;
+                    o.x = __float_as_uint(v[rr][0]); o.y = __float_as_uint(v[rr][1]);
+                    o.z = __float_as_uint(v[rr][2]); o.w = __float_as_uint(v[rr][3]);
+                    __builtin_amdgcn_raw_buffer_store_b128(o, yrs, vo, 0, 0);
+                } else if constexpr (sizeof(T) == 4 && VEC == 2) {
+                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                    u32x2 o;
+                    o.x = __float_as_uint(v[rr][0]); o.y = __float_as_uint(v[rr][1]);
+                    __builtin_amdgcn_raw_buffer_store_b64(o, yrs, vo, 0, 0);
+                } else if constexpr (VEC == 4) {
+                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                    u32x2 o;
+                    o.x = (__float_as_uint(v[rr][0]) >> 16) | (__float_as_uint(v[rr][1]) & 0xffff0000u);
+                    o.y = (__float_as_uint(v[rr][2]) >> 16) | (__float_as_uint(v[rr][3]) & 0xffff0000u);
+                    __builtin_amdgcn_raw_buffer_store_b64(o, yrs, vo, 0, 0);
+                } else {
+                    __builtin_amdgcn_raw_buffer_store_b32((__float_as_uint(v[rr][0]) >> 16) | (__float_as_uint(v[rr][1]) & 0xffff0000u),
+                                                          yrs, vo, 0, 0);
+                }
+                const uint32_t e = bit0 + (uint32_t)rr * a.W;          // VEC bits inside one word (e is a multiple of VEC)
+                if (bits) __hip_atomic_fetch_or(mw + e / 32u, bits << (e % 32u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
 
         // ---- Sec. 4.1 AveragePooling: block sum in binary64 over the block's adjacent lanes
         double Sm = 0.0;
@@ -162,4 +217,17 @@ __global__ void __launch_bounds__(64) compress_items(ItemsArgs a) {
         }
         wave_sync();                                           // the words are cleared again by the next round
     }
+    if constexpr (RELU) {
+        // the workgroup's mask words: bits [blockIdx.x * mbits, ...) of the map, as far as the map goes
+        const uint64_t first = (uint64_t)blockIdx.x * mbits;
+        const uint64_t total = (uint64_t)a.P * a.HW;
+        const uint32_t nbits = (uint32_t)min((uint64_t)mbits, total - first);
+        uint32_t* dst = a.mask + first / 32u;
+        for (uint32_t w = lane; w < (nbits + 31u) / 32u; w += 64) dst[w] = mw[w];
+    }
 }
+
+template <typename T, int BITS, int B, int VEC, int R>
+__global__ void __launch_bounds__(64) compress_items(ItemsArgs a) { compress_items_body<T, BITS, B, VEC, R, false>(a); }
+template <typename T, int BITS, int B, int VEC>
+__global__ void __launch_bounds__(64) relu_compress_items(ItemsArgs a) { compress_items_body<T, BITS, B, VEC, B, true>(a); }

@@ -19,7 +19,8 @@
 //                    workgroup of one / four / sixteen wavefronts, the plane stays in registers from
 //                    load to codes
 //   compress_lane    one-block planes with an odd element count (7x7): a lane per plane
-//   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8: a lane
+//   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8 (and their Relu +
+//                    compress instance, relu_compress_items): a lane
 //                    per pooling item, loaded straight from global memory, DPP reductions
 //   compress_units   planes (2-D or 3-D maps) of 256 to about 27K elements whose rows or blocks are not whole 16-byte vectors
 //                    (odd widths: 27x27, 55x55, 147x147; B = 18): four consecutive elements per lane step
@@ -218,7 +219,24 @@ int division_relu_compress(const void* x, int64_t N, int64_t C, int64_t H, int64
         ra.y = y;
         ra.mask = static_cast<uint32_t*>(mask);
         CompLaunch c{};
-        c.B = B; c.nw = nw; c.gx = grid; c.gy = 1; c.lds = lds; c.st = st; c.ra = ra;
+        c.kind = REGS; c.B = B; c.nw = nw; c.gx = grid; c.gy = 1; c.lds = lds; c.st = st; c.ra = ra;
+        const hipError_t err = bridge_relu(dt, c, b);
+        return err == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
+    }
+    // fused too: the small planes of the items kernel (28 x 28, 14 x 14, the CIFAR shapes)
+    ItemsArgs ia{};
+    int vec = 1;
+    const int Bc = covering_block(L, 1, H, W, B);
+    if ((Bc == 4 || Bc == 8) && plan_relu_items(L, H, W, Bc, es, both, &ia, &grid, &lds, &vec)) {
+        ia.tab.x[0] = x;
+        ia.tab.pk[0] = packed;
+        ia.tab.seed_a[0] = mix32((uint32_t)(seed & 0xffffffffu) ^ 0x243F6A88u);
+        ia.tab.seed_c[0] = mix32((uint32_t)(seed >> 32) ^ 0x85A308D3u);
+        ia.rg = make_regions(L);
+        ia.y = y;
+        ia.mask = static_cast<uint32_t*>(mask);
+        CompLaunch c{};
+        c.kind = ITEMS; c.B = Bc; c.vec = vec; c.gx = grid; c.gy = 1; c.lds = lds; c.st = st; c.ia = ia;
         const hipError_t err = bridge_relu(dt, c, b);
         return err == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
     }
@@ -236,8 +254,13 @@ int division_relu_compress_fused(int64_t N, int64_t C, int64_t H, int64_t W, div
     uint32_t grid = 0;
     size_t lds = 0;
     int nw = 1;
-    return L.HW % 32 == 0 && (B == 4 || B == 8) &&
-           plan_regs(L, 1, H, W, B, dt == DIVISION_BF16 ? 2 : 4, reinterpret_cast<const void*>((uintptr_t)16), &ra, &grid, &lds, &nw) && nw <= 4;
+    const size_t es = dt == DIVISION_BF16 ? 2 : 4;
+    const void* aligned = reinterpret_cast<const void*>((uintptr_t)16);
+    if (L.HW % 32 == 0 && (B == 4 || B == 8) && plan_regs(L, 1, H, W, B, es, aligned, &ra, &grid, &lds, &nw) && nw <= 4) return 1;
+    ItemsArgs ia{};
+    int vec = 1;
+    const int Bc = covering_block(L, 1, H, W, B);
+    return (Bc == 4 || Bc == 8) && plan_relu_items(L, H, W, Bc, es, aligned, &ia, &grid, &lds, &vec);
 }
 
 // Both directions of the descriptor-array calls: validates every map, then serves the maps that

@@ -304,6 +304,30 @@ hipError_t launch_items(int B, int vec, const ItemsArgs& a, dim3 grid, size_t ld
     return hipGetLastError();
 }
 
+// The Relu + compress instance of the items kernel (2-D maps, items of B rows).
+template <typename T, int BITS>
+hipError_t launch_relu_items(int B, int vec, const ItemsArgs& a, dim3 grid, size_t lds, hipStream_t st) {
+    void (*kern)(ItemsArgs);
+    if (B == 8) kern = vec == 4 ? relu_compress_items<T, BITS, 8, 4> : relu_compress_items<T, BITS, 8, 2>;
+    else kern = vec == 4 ? relu_compress_items<T, BITS, 4, 4> : relu_compress_items<T, BITS, 4, 2>;
+    hipLaunchKernelGGL(kern, grid, dim3(64), lds, st, a);
+    return hipGetLastError();
+}
+
+// Plan of the fused Relu + compress call on the shapes of the items kernel: the rounds a workgroup
+// handles are rounded up until its mask bits are whole words.  False when the shape is not covered.
+bool plan_relu_items(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* xy,
+                     ItemsArgs* a, uint32_t* grid, size_t* lds, int* vec_out) {
+    if (H == 1 || !plan_items(L, H, W, B, es, xy, a, grid, lds, vec_out)) return false;
+    uint32_t m = 1;
+    while (((uint64_t)m * a->ppr * L.HW) % 32 != 0) ++m;              // at most 16: H*W is even here
+    a->rpw = (a->rpw + m - 1) / m * m;
+    const uint64_t mbits = (uint64_t)a->rpw * a->ppr * L.HW;
+    *lds = 4ull * (((uint64_t)a->ppr * L.WPP + 3) & ~3ull) + mbits / 8 + 16;
+    *grid = (a->nrounds + a->rpw - 1) / a->rpw;
+    return *lds <= 60u * 1024u;
+}
+
 // Fills the one-wavefront compress plan; false when the shape is not covered.
 bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, const void* x,
                WaveArgs* a, uint32_t* grid, size_t* lds, int* vec_out) {
@@ -770,11 +794,13 @@ hipError_t do_decompress(const DecLaunch& c, int b) {
     });
 }
 
-// the Relu + compress kernel of the register kernel's planes (one map per launch; c.ra carries y and mask)
+// the Relu + compress kernels: the register kernel's planes (c.ra carries y and mask) or, c.kind == ITEMS,
+// the items kernel's (c.ia); one map per launch
 template <typename T>
 hipError_t do_relu(const CompLaunch& c, int b) {
     return with_bits(b, [&](auto bits) -> hipError_t {
         constexpr int BITS = decltype(bits)::value;
+        if (c.kind == ITEMS) return launch_relu_items<T, BITS>(c.B, c.vec, c.ia, dim3(c.gx, 1), c.lds, c.st);
         void (*kern)(RegsArgs);
         if (c.nw == 1) kern = c.B == 8 ? relu_compress_regs<T, BITS, 8, 1> : relu_compress_regs<T, BITS, 4, 1>;
         else kern = c.B == 8 ? relu_compress_regs<T, BITS, 8, 4> : relu_compress_regs<T, BITS, 4, 4>;

@@ -133,9 +133,19 @@ def test_maxpool_matches_oracle(shape, k, dtype):
     ((2, 4, 48, 48), 4, 8, True),        # B = 4, 2304 elements
     ((3, 4, 64, 32), 8, 2, True),        # 2048 elements
     ((2, 3, 50, 44), 8, 2, False),       # 2200 elements: not whole mask words per plane -> two kernels
-    ((4, 7, 28, 28), 8, 2, False),       # small planes -> two kernels
     ((2, 3, 56, 56), 12, 2, False),      # block size outside the fused instances
-    ((5, 9, 7, 7), 8, 4, False),
+    ((5, 9, 7, 7), 8, 4, False),         # lane-per-plane kernel -> two kernels
+    ((2, 3, 30, 30), 4, 2, False),       # more than 64 pooling items per plane -> two kernels
+    ((4, 7, 28, 28), 8, 2, True),        # small planes: the items kernel, 784 mask bits per plane, two rounds per workgroup
+    ((5, 9, 14, 14), 8, 2, True),        # four planes per round (784 bits), 45 planes: the last round holds one
+    ((130, 3, 14, 14), 8, 4, True),      # 98 rounds
+    ((6, 5, 32, 32), 4, 2, True),        # CIFAR shapes: whole mask words per plane
+    ((3, 7, 16, 16), 4, 8, True),
+    ((5, 3, 8, 8), 4, 2, True),
+    ((4, 5, 4, 4), 4, 2, True),          # one block per plane, 16 bits each
+    ((7, 3, 10, 30), 8, 2, True),        # 300 bits per plane: four rounds of two planes per workgroup
+    ((3, 3, 6, 10), 4, 2, True),         # 60 bits per plane
+    ((2, 3, 30, 30), 8, 2, True),        # ragged blocks both ways
 ])
 @pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
 def test_relu_fused_with_compression_matches_relu_then_compress(shape, B, b, fused, mode):
