@@ -19,11 +19,11 @@
 //                    workgroup of one / four / sixteen wavefronts, the plane stays in registers from
 //                    load to codes
 //   compress_lane    one-block planes with an odd element count (7x7): a lane per plane
-//   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8 (and their Relu +
-//                    compress instance, relu_compress_items): a lane
-//                    per pooling item, loaded straight from global memory, DPP reductions
-//   compress_units   planes (2-D or 3-D maps) of 256 to about 27K elements whose rows or blocks are not whole 16-byte vectors
-//                    (odd widths: 27x27, 55x55, 147x147; B = 18): four consecutive elements per lane step
+//   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8: a lane per
+//                    pooling item, loaded straight from global memory, DPP reductions (relu_compress_items:
+//                    the same with a Relu applied to the rows as they arrive)
+//   compress_units   planes (2-D or 3-D maps) of 256 to about 27K elements whose rows or blocks are not whole
+//                    16-byte vectors (odd widths: 27x27, 55x55, 147x147; B = 18): four consecutive elements per lane step
 //                    whatever the width, the block of each element looked up in a table made once per
 //                    workgroup, the plane parked in LDS for the block sums, next plane's loads in flight
 //   compress_wave    other planes up to 17 KB, B = 4, 8: one wavefront per chunk of planes staged in LDS
