@@ -753,6 +753,10 @@ UNITS_CASES = [
     ((3, 3, 21, 21), 2, 8),             # 242 row segments: 32 lanes per plane
     ((4, 6, 17, 17), 18, 2),            # one block per plane
     ((7, 3, 17, 23), 6, 2),
+    ((1, 1, 55, 55), 8, 2),             # a single plane
+    ((2, 2, 2, 1001), 8, 4),            # two long rows: 126 blocks in one block row
+    ((1, 3, 127, 129), 8, 2),           # 16383 elements: eight wavefronts
+    ((3, 1, 3, 4099), 8, 2),            # 513 blocks of 3 rows: 4104 row segments
 ]
 
 
