@@ -408,11 +408,13 @@ __global__ void __launch_bounds__(64 * NW) decompress_units(DecArgs a) {
     const uint32_t tid = threadIdx.x;
     auto round_live = [&](int k) -> bool { return (uint32_t)(NT * k) < a.q4; };
 
-    // 2-byte elements, odd planes of an odd element count: the plane starts in the middle of a dword.
-    // Its units then start one element early, so that every store is dword-aligned; the element before
-    // the plane and those past it are left alone.  The same for all planes of the workgroup: the grid is
-    // even then, or every workgroup has one plane.
-    const uint32_t shift = sizeof(T) == 2 ? (blockIdx.x * a.HW) & 1u : 0u;
+    // Planes whose element count is not a multiple of 4 start 1, 2 or 3 elements past a unit boundary of
+    // the map.  Their units then start that many elements early: every store is a whole, aligned unit of
+    // the map (16 bytes for 4-byte elements: a write-only probe runs at 5.9 TB/s there and at 4.6 TB/s
+    // with 16-byte stores at 4-byte-aligned addresses; 2-byte elements need it, a store in the middle of
+    // a dword is not possible), the elements before the plane and those past it are left alone.  The
+    // same for all planes of the workgroup: the grid is a multiple of 4, or every workgroup has one plane.
+    const uint32_t shift = (blockIdx.x * a.HW) & 3u;
 
     // LDS byte offset of the LFC of each element's block (elements outside the plane: block 0, never stored)
     uint32_t lo[K][2];
@@ -432,33 +434,30 @@ __global__ void __launch_bounds__(64 * NW) decompress_units(DecArgs a) {
         lo[k][1] = off[2] | (off[3] << 16);
     }
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-    uint32_t codes[K];
-    u32x2 wide[sizeof(T) == 2 ? K : 1];                // shifted units: the two code words a unit's codes lie in
+    u32x2 wide[K];      // .x: the unit's codes as loaded; shifted units: the two code words the unit's codes lie in
     float lf[KL];
     float2 dd;
     auto issue_loads = [&](uint32_t p) {
         const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint32_t*>(pt.codes) + (size_t)p * a.WPP, 0, (int)(a.q4 * CB), 0x00020000);
-        if constexpr (sizeof(T) == 2) {
-            if (shift) {
-                // codes of elements 4f-1 .. 4f+2: 4 * BITS bits from bit (4f-1) * BITS of the plane's code words
-                const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
-                    const_cast<uint32_t*>(pt.codes) + (size_t)p * a.WPP, 0, (int)(a.WPP * 4u), 0x00020000);
+            const_cast<uint32_t*>(pt.codes) + (size_t)p * a.WPP, 0, (int)(a.WPP * 4u), 0x00020000);
+        if (shift) {
+            // codes of elements 4f-shift .. 4f-shift+3: 4 * BITS bits from bit (4f-shift) * BITS of the plane's code words
+            const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<uint32_t*>(pt.codes) + (size_t)p * a.WPP, 0, (int)(a.WPP * 4u), 0x00020000);
 #pragma unroll
-                for (int k = 0; k < K; ++k) {
-                    if (!round_live(k)) continue;
-                    const uint32_t f = tid + NT * k;
-                    const uint32_t bit = f ? (4u * f - 1u) * BITS : 0u;
-                    wide[k] = __builtin_amdgcn_raw_buffer_load_b64(wrs, (bit >> 5) * 4u, 0, 0);
-                }
+            for (int k = 0; k < K; ++k) {
+                if (!round_live(k)) continue;
+                const uint32_t f = tid + NT * k;
+                const uint32_t bit = f ? (4u * f - shift) * BITS : 0u;
+                wide[k] = __builtin_amdgcn_raw_buffer_load_b64(wrs, (bit >> 5) * 4u, 0, 0);
             }
         }
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             if (!round_live(k) || shift) continue;
-            if constexpr (CB == 1) codes[k] = __builtin_amdgcn_raw_buffer_load_b8(crs, tid, k * NT, 0);
-            else if constexpr (CB == 2) codes[k] = __builtin_amdgcn_raw_buffer_load_b16(crs, tid * 2u, k * NT * 2, 0);
-            else codes[k] = __builtin_amdgcn_raw_buffer_load_b32(crs, tid * 4u, k * NT * 4, 0);
+            if constexpr (CB == 1) wide[k].x = __builtin_amdgcn_raw_buffer_load_b8(crs, tid, k * NT, 0);
+            else if constexpr (CB == 2) wide[k].x = __builtin_amdgcn_raw_buffer_load_b16(crs, tid * 2u, k * NT * 2, 0);
+            else wide[k].x = __builtin_amdgcn_raw_buffer_load_b32(crs, tid * 4u, k * NT * 4, 0);
         }
 #pragma unroll
         for (int m = 0; m < KL; ++m) {
@@ -482,16 +481,14 @@ __global__ void __launch_bounds__(64 * NW) decompress_units(DecArgs a) {
         for (int k = 0; k < K; ++k) {
             c4[k] = 0u;
             if (!round_live(k)) continue;
-            if constexpr (sizeof(T) == 2) {
-                if (shift) {
-                    const uint32_t f = tid + NT * k;
-                    const uint32_t bit = f ? (4u * f - 1u) * BITS : 0u;
-                    const uint32_t c = __builtin_amdgcn_alignbit(wide[k].y, wide[k].x, bit & 31u);
-                    c4[k] = f ? c : c << BITS;             // unit 0: the slot before the plane, then elements 0, 1, 2
-                    continue;
-                }
+            if (shift) {
+                const uint32_t f = tid + NT * k;
+                const uint32_t bit = f ? (4u * f - shift) * BITS : 0u;
+                const uint32_t c = __builtin_amdgcn_alignbit(wide[k].y, wide[k].x, bit & 31u);
+                c4[k] = f ? c : c << (shift * BITS);       // unit 0: the slots before the plane, then its first elements
+                continue;
             }
-            c4[k] = codes[k];
+            c4[k] = wide[k].x;
         }
         const float2 sc = dd;
         if (p + gridDim.x < a.P) issue_loads(p + gridDim.x);

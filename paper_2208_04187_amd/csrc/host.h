@@ -657,7 +657,8 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
     // planes (2-D or 3-D) of 512 elements and more whose rows or blocks are not whole vectors: four consecutive
     // elements per lane step, planes starting on 4-byte boundaries
     if (Hs > 1 && small_idx && ((uintptr_t)xhat % 4) == 0 && L.nb <= 16383) {
-        const uint64_t q4 = (L.HW + 3) / 4;
+        // units per plane, counting the one more that a plane starting 3 elements past a unit boundary takes
+        const uint64_t q4 = (L.HW + (L.HW % 4 ? 6 : 0)) / 4;
         int nw = 1;
         while (nw < 16 && (q4 > (uint64_t)kUnitsK * 64 * nw || L.nb > (uint64_t)kUnitsLfc * 64 * nw)) nw *= 2;
         const uint64_t nt = 64ull * nw;
@@ -667,7 +668,7 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
             a->q4 = (uint32_t)q4;
             a->G = (uint32_t)nw;                  // wavefronts per workgroup
             uint64_t g = (uint64_t)num_cus() * (16ull / nw);
-            g += g & 1;
+            g = (g + 3) & ~3ull;        // the planes of a workgroup start alike within a unit of the map
             *grid = (uint32_t)(g < L.P ? g : L.P);
             return 6;
         }
