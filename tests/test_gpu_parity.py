@@ -757,6 +757,8 @@ UNITS_CASES = [
     ((2, 2, 2, 1001), 8, 4),            # two long rows: 126 blocks in one block row
     ((1, 3, 127, 129), 8, 2),           # 16383 elements: eight wavefronts
     ((3, 1, 3, 4099), 8, 2),            # 513 blocks of 3 rows: 4104 row segments
+    ((2, 2, 3000, 3), 8, 2),            # rows shorter than a unit: a unit spans two rows
+    ((1, 2, 1000, 5), 4, 4),
 ]
 
 
