@@ -36,6 +36,8 @@
  *     rule the paper's second footnote on Eq. (quantization) requires).
  *   - a plane whose residual range is below 2^-90 is degenerate: Delta = 0,
  *     all codes 0.
+ *   - where a plane's smallest residual is zero and both +0 and -0 occur, delta is -0 (and the
+ *     maximum of such a pair is +0): the order of IEEE 754-2019 minimum / maximum.
  *   - the scale factor is inv = fl((2^Q-1)/range), bumped by one ulp when
  *     fl(range*inv) would fall short of 2^Q-1, so that the plane's maximum
  *     always receives the top code.
@@ -279,14 +281,30 @@ static void plane_lfc(const void *x, int dt, size_t base, size_t D, size_t H, si
     }
 }
 
-/* Eq. (quantization): per-plane scale.  Returns delta, Delta and the scale inv. */
-static void plane_scale(const float *h, size_t HW, int b, float *delta, float *Delta, float *inv)
+/* Eq. (quantization): min and max of a plane's residuals.  The paper does not say which zero is the
+ * minimum of a plane that holds both +0 and -0; the reading taken is the total order of IEEE 754-2019
+ * minimum / maximum (-0 below +0), so that the result does not depend on the order of the elements. */
+static int orders_below(float a, float b)
+{
+    return a < b || (a == b && signbit(a) && !signbit(b));
+}
+
+static void plane_extremes(const float *h, size_t HW, float *lo_out, float *hi_out)
 {
     float lo = h[0], hi = h[0];
     for (size_t i = 1; i < HW; ++i) {
-        if (h[i] < lo) lo = h[i];
-        if (h[i] > hi) hi = h[i];
+        if (orders_below(h[i], lo)) lo = h[i];
+        if (orders_below(hi, h[i])) hi = h[i];
     }
+    *lo_out = lo;
+    *hi_out = hi;
+}
+
+/* Eq. (quantization): per-plane scale.  Returns delta, Delta and the scale inv. */
+static void plane_scale(const float *h, size_t HW, int b, float *delta, float *Delta, float *inv)
+{
+    float lo, hi;
+    plane_extremes(h, HW, &lo, &hi);
     const float Lf = (float)((1 << b) - 1);
     volatile float range = hi - lo;                 /* fp32 sub */
     *delta = lo;
@@ -311,11 +329,8 @@ static void plane_scale(const float *h, size_t HW, int b, float *delta, float *D
  * need not be reached.  A plane with fl(max - delta) below 2^-90 is degenerate (Delta = 0). */
 static void plane_scale_c16(const float *h, size_t HW, int b, float *delta, float *Delta, float *inv)
 {
-    float lo = h[0], hi = h[0];
-    for (size_t i = 1; i < HW; ++i) {
-        if (h[i] < lo) lo = h[i];
-        if (h[i] > hi) hi = h[i];
-    }
+    float lo, hi;
+    plane_extremes(h, HW, &lo, &hi);
     const float Lf = (float)((1 << b) - 1);
     const float d = bf16_floor(lo);
     volatile float range = hi - d;                  /* fp32 sub */

@@ -172,6 +172,7 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
             unpack_vec<T>(q[k], f);
             s4 = ((double)f[0] + (double)f[1]) + ((double)f[2] + (double)f[3]);
             if constexpr (EPV == 8) s4 += ((double)f[4] + (double)f[5]) + ((double)f[6] + (double)f[7]);
+            s4 += 0.0;                                    // a block of negative zeros sums to +0, as a sum from 0 does
         }
         const double Sb = group_sum_any(a.upb, s4);
         const uint32_t ustart = u & ~(a.upb - 1u);

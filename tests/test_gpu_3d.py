@@ -170,3 +170,25 @@ def test_seeded_sweep_of_volumes(chunk):
         assert np.array_equal(pk.cpu().numpy(), ref), tag
         yh, _ = to_host_array(y.cpu())
         assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt)), tag
+
+
+# values at the edges of binary32 (zero, constant, subnormal, overflowing and signed-zero planes) under the volume kernels
+@pytest.mark.parametrize("shape,B", [((1, 12, 16, 16, 16), 8), ((1, 12, 4, 28, 28), 8), ((1, 12, 16, 56, 56), 8),
+                                      ((2, 6, 5, 9, 13), 4), ((2, 6, 8, 27, 27), 8), ((3, 4, 4, 9, 9), 8), ((3, 4, 5, 7, 7), 4),
+                                      ((1, 12, 24, 40, 64), 16), ((1, 12, 33, 35, 37), 16), ((4, 3, 3, 3, 3), 8)])
+@pytest.mark.parametrize("mode,b", [("f32", 2), ("bf16", 4), ("c16", 8)])
+def test_volumes_with_values_at_the_edges_of_binary32(shape, B, mode, b):
+    from tests.test_gpu_parity import _special_planes
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    c16 = mode == "c16"
+    dt = oracle.F32_C16 if c16 else (oracle.BF16 if mode == "bf16" else oracle.F32)
+    N, C, D, H, W = shape
+    x = _special_planes((N, C, D * H, W), 57 + B).view(shape).to(dtype)
+    xh, _ = to_host_array(x)
+    ref = oracle.compress(xh, B, b, 4048, dt, threads=16)
+    pk = pkg.division_compress_3d(x.to("cuda:0"), B, b, 4048, c16=c16)
+    y = pkg.division_decompress_3d(pk, shape, B, b, dtype, c16=c16)
+    torch.cuda.synchronize()
+    assert np.array_equal(pk.cpu().numpy(), ref), pkg.division_kernel_name_3d(0, shape, B, b, dtype, c16=c16)
+    yh, _ = to_host_array(y.cpu())
+    assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt, threads=16), equal_nan=mode != "bf16")

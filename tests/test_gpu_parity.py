@@ -881,3 +881,64 @@ def test_full_size_maps_larger_than_4GiB(shape, B, b):
     torch.cuda.synchronize()
     yr = oracle.decompress(pk.cpu().numpy(), shape, B, b, threads=16)
     assert np.array_equal(y.cpu().numpy(), yr)
+
+
+# ---------------------------------------------------------------- values at the edges of binary32, under every kernel family
+
+SPECIAL_VALUE_SHAPES = [
+    ((3, 4, 56, 56), 8), ((3, 4, 28, 28), 8), ((3, 4, 14, 14), 8), ((6, 2, 7, 7), 8), ((3, 4, 4, 4), 4),
+    ((3, 4, 55, 55), 8), ((2, 6, 17, 17), 4), ((3, 4, 28, 28), 12), ((3, 4, 54, 57), 64), ((3, 4, 56, 56), 64),
+    ((3, 4, 1, 196), 16), ((2, 6, 96, 96), 8), ((3, 4, 150, 150), 18), ((3, 4, 27, 35), 5), ((4, 3, 32, 32), 4),
+    ((3, 4, 13, 13), 8), ((3, 4, 30, 30), 4), ((1, 12, 300, 300), 18), ((3, 4, 56, 56), 12), ((3, 4, 170, 170), 8),
+    ((3, 4, 250, 250), 8), ((3, 4, 60, 60), 8), ((3, 4, 224, 224), 8), ((2, 6, 9, 6), 4), ((3, 4, 1, 3072), 4096),
+]
+
+
+def _special_planes(shape, seed):
+    """Twelve planes (repeated over the tensor) that sit at the edges of the arithmetic: zero and constant planes,
+    an outlier, subnormal values, residual ranges below and just above the degenerate threshold, a residual range
+    that overflows binary32 although every residual is finite, negative zeros, a large offset with small variation."""
+    N, C, H, W = shape
+    g = torch.Generator().manual_seed(seed)
+    r = lambda: torch.randn((H, W), generator=g)
+    half = torch.arange(H * W).view(H, W) * 2 < H * W
+    sign = torch.where(torch.rand((H, W), generator=g) < torch.where(half, 0.25, 0.75), 1.0, -1.0)
+    planes = [
+        torch.zeros(H, W),
+        torch.full((H, W), 3.25),
+        torch.where(torch.arange(H * W).view(H, W) == (H * W) // 3, 1e30, 1.0) * r(),
+        r() * 1e-41,                                   # subnormal values: sums and means stay subnormal
+        r() * 1e-30,                                   # residual range below 2^-90
+        r() * 1e-26,                                   # just above it: scale factors near 2^86
+        sign * 1.6e38,                                 # |residual| <= 3.2e38, range beyond the largest binary32
+        -torch.zeros(H, W),
+        torch.where(r() > 1.0, 1e-45, 1.0) * r(),      # subnormal and ordinary values in one plane
+        1e3 + r() * 1e-2,
+        torch.where(r() > 0, 2.5, -7.0),               # two values only
+        r().clamp_min(0),
+    ]
+    x = torch.stack([planes[i % len(planes)] for i in range(N * C)]).view(shape)
+    return x.contiguous()
+
+
+@pytest.mark.parametrize("shape,B", SPECIAL_VALUE_SHAPES)
+@pytest.mark.parametrize("mode,b", [("f32", 2), ("f32", 8), ("bf16", 4), ("c16", 2)])
+def test_values_at_the_edges_of_binary32(shape, B, mode, b):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    c16 = mode == "c16"
+    dt = oracle.F32_C16 if c16 else (oracle.BF16 if mode == "bf16" else oracle.F32)
+    x = _special_planes(shape, 31 + B).to(dtype)
+    xh, _ = to_host_array(x)
+    ref = oracle.compress(xh, B, b, 2024, dt, threads=16)
+    pk = pkg.division_compress(x.to("cuda:0"), B, b, 2024, c16=c16)
+    y = pkg.division_decompress(pk, shape, B, b, dtype, c16=c16)
+    torch.cuda.synchronize()
+    got = pk.cpu().numpy()
+    if not np.array_equal(got, ref):
+        s, t = oracle.split_packed(got, shape, B, b, dt), oracle.split_packed(ref, shape, B, b, dt)
+        where = {k: sorted({int(i) % 12 for i in np.nonzero(s[k].reshape(s[k].shape[0], -1).view(np.uint8)
+                                                           != t[k].reshape(t[k].shape[0], -1).view(np.uint8))[0]})
+                 for k in ("lfc", "meta", "codes")}
+        raise AssertionError(f"{pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16)}: kinds of plane that differ {where}")
+    yh, _ = to_host_array(y.cpu())
+    assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt), equal_nan=mode != "bf16")

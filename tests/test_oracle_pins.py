@@ -445,3 +445,30 @@ def test_pins_would_catch_a_transposed_or_floor_pooled_oracle():
     xt = np.ascontiguousarray(x.transpose(0, 1, 3, 2))
     lfc_t = oracle.split_packed(oracle.compress(xt, 4, 2, 0), xt.shape, 4, 2)["lfc"][0]
     assert np.array_equal(lfc_t, lfc.T)
+
+
+# ---------------------------------------------------------------- signed zeros
+
+@pytest.mark.parametrize("dt", [oracle.F32, oracle.F32_C16])
+def test_minimum_of_signed_zeros_does_not_depend_on_element_order(dt):
+    # Eq. (quantization): delta = min H^H.  With +0 and -0 both present the reading is IEEE 754-2019 minimum:
+    # -0, wherever it stands in the plane.  One block per plane with mean +0 keeps h = x.
+    import itertools
+    base = [0.0, -0.0, 0.0, -0.0]
+    metas = set()
+    for perm in set(itertools.permutations(base)):
+        x = np.array(perm, dtype=np.float32).reshape(1, 1, 2, 2)
+        s = oracle.split_packed(oracle.compress(x, 4, 2, 1, dt), x.shape, 4, 2, dt)
+        metas.add(s["meta"].tobytes())
+        assert s["lfc"].view(np.uint32 if dt == oracle.F32 else np.uint16).ravel()[0] == 0      # the mean is +0
+    neg_zero = np.float32(-0.0).tobytes()
+    want = neg_zero + np.float32(0).tobytes() if dt == oracle.F32 else neg_zero[2:] + b"\0\0"
+    assert metas == {want}
+    # blocks of one element: the mean of -0 is +0 (a sum that starts at 0), so h = x - mean is -0 exactly where
+    # x is, +0 elsewhere; delta is -0 for every order of the elements, and the round trip gives +0 and 0.75
+    for perm in set(itertools.permutations([0.0, -0.0, 0.75, -0.0])):
+        x = np.array(perm, dtype=np.float32).reshape(1, 1, 1, 4)
+        p = oracle.compress(x, 1, 2, 1, dt)
+        s = oracle.split_packed(p, x.shape, 1, 2, dt)
+        assert s["meta"].tobytes() == want
+        assert oracle.decompress(p, x.shape, 1, 2, dt).tobytes() == np.abs(x).tobytes()
