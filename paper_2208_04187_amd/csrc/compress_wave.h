@@ -21,13 +21,15 @@ struct WaveArgs {
 // 2 ulp of the binary64 quotient, so both round to the same binary32 value
 // unless q lies within a few ulp of a binary32 rounding midpoint (the 29
 // mantissa bits a binary32 drops close to 1000...0); only then, for the whole
-// wavefront, the true division runs.
+// wavefront, the true division runs.  A nonzero q below 2^-126 rounds to a
+// subnormal binary32, which drops more than 29 bits: it takes the division too.
 __device__ __forceinline__ float mean_of(double S, uint32_t cnt) {
     if ((cnt & (cnt - 1)) == 0) return (float)(S * (1.0 / (double)cnt));     // power of two: exact scaling
     const double q = S * (1.0 / (double)cnt);
     const uint32_t low = (uint32_t)__double_as_longlong(q) & 0x1fffffffu;
     const uint32_t dist = low > 0x10000000u ? low - 0x10000000u : 0x10000000u - low;
-    if (__builtin_expect(__any(dist < 16u), 0)) return (float)(S / (double)cnt);
+    const bool subnormal = q != 0.0 && __builtin_fabs(q) < 0x1p-126;
+    if (__builtin_expect(__any(dist < 16u || subnormal), 0)) return (float)(S / (double)cnt);
     return (float)q;
 }
 

@@ -39,6 +39,12 @@ while time.time() - t0 < budget:
     g = torch.Generator().manual_seed(int(rng.integers(0, 2**31)))
     x = torch.randn(shape, generator=g) * float(rng.choice([0.01, 1.0, 300.0]))
     if rng.random() < 0.6: x = torch.relu(x)
+    if rng.random() < 0.3:          # planes at the edges of binary32: zeros of both signs, subnormals, tiny and overflowing ranges
+        xp = x.view(N * C, -1)
+        for p_ in rng.choice(N * C, size=min(N * C, 4), replace=False):
+            r_ = torch.randn(xp.shape[1], generator=g)
+            xp[int(p_)] = [torch.zeros_like(r_), -torch.zeros_like(r_), r_ * 1e-41, r_ * 1e-30, r_ * 1e-26, torch.sign(r_) * 1.6e38,
+                           torch.where(r_ > 2, 1e30, 1.0) * r_, torch.full_like(r_, -2.5), torch.where(r_ > 0, 0.0, -0.0)][int(rng.integers(0, 9))]
     x = x.to(dtype)
     seed = int(rng.integers(0, 2**63))
     ref = oracle.compress(host(x), B, b, seed, dt, threads=16)

@@ -399,6 +399,36 @@ def test_block_mean_on_rounding_midpoints():
     assert st["exact"]
 
 
+# block sizes and ragged edges that give blocks of 98, 196, 198 or 150 elements: counts whose binary64 reciprocal, times the
+# sum, lands beside an exact tie instead of on it
+@pytest.mark.parametrize("shape,B", [((4, 6, 56, 56), 14), ((4, 6, 28, 28), 14), ((4, 6, 14, 14), 16), ((4, 6, 14, 14), 64),
+                                      ((4, 6, 47, 76), 18), ((4, 6, 29, 36), 18), ((4, 6, 7, 14), 16), ((1, 12, 300, 300), 14),
+                                      ((2, 6, 150, 150), 14), ((4, 6, 35, 35), 14), ((4, 6, 17, 17), 14), ((4, 6, 1, 770), 98),
+                                      ((4, 6, 1, 708), 256), ((4, 6, 170, 170), 15), ((8, 6, 13, 14), 6), ((2, 6, 250, 250), 14),
+                                      ((4, 6, 56, 56), 12), ((4, 6, 35, 35), 3), ((2, 6, 203, 200), 28),
+                                      ((2, 6, 7, 7, 4), 8), ((2, 6, 2, 7, 7), 8), ((2, 6, 7, 28, 28), 28), ((1, 12, 14, 30, 34), 14)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_block_mean_that_is_a_subnormal_number(shape, B, dtype):
+    # integers times the smallest subnormal: a block mean is sum / count in units of 2^-149 (2^-133 for bfloat16), so
+    # binary32 rounds it to an integer, and with an even count that is no power of two many means are exact ties
+    g = torch.Generator().manual_seed(sum(shape) + B)
+    unit = 2.0 ** -149 if dtype == torch.float32 else 2.0 ** -133
+    top = 3000 if dtype == torch.float32 else 100
+    x = (torch.randint(-top, top, shape, generator=g).double() * unit).float().to(dtype)
+    xh, dt = to_host_array(x)
+    ref = oracle.compress(xh, B, 2, 5, dt, threads=16)
+    lfc = oracle.split_packed(ref, shape, B, 2, dt)["lfc"]
+    lf = (oracle.bf16_to_f32(lfc) if dtype == torch.bfloat16 else lfc).astype(np.float64)
+    assert np.abs(lf).max() < 2.0 ** -126 and np.count_nonzero(lf) > lf.size // 2          # the means are subnormal
+    three = len(shape) == 5
+    pk = (pkg.division_compress_3d if three else pkg.division_compress)(x.to("cuda:0"), B, 2, 5)
+    torch.cuda.synchronize()
+    got = oracle.split_packed(pk.cpu().numpy(), shape, B, 2, dt)["lfc"]
+    assert np.array_equal(got.view(np.uint8), lfc.view(np.uint8)), \
+        (pkg.division_kernel_name_3d if three else pkg.division_kernel_name)(0, shape, B, 2, dtype)
+    assert np.array_equal(pk.cpu().numpy(), ref)
+
+
 def test_descriptor_array_calls_serve_a_mixed_step():
     """Maps of different shapes, dimensionalities, types and parameters in one call each way; every map
     must come out exactly as its single-map call gives it (and as the oracle does)."""
