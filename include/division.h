@@ -100,7 +100,11 @@ int division_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W,
  * up-sampling of the stored H^L; delta = min H^H, Delta = (max H^H - delta) /
  * (2^b - 1); code = floor(t + u) with t = (H^H - delta) * (2^b - 1)/(max-delta)
  * and u uniform in [0,1) with 16 random bits per element.  A plane whose
- * residual range is below 2^-90 gets Delta = 0 and all-zero codes.
+ * residual range is below 2^-90 (or beyond the largest binary32) gets Delta = 0
+ * and all-zero codes.  Zeros keep a sign: a block of -0 has mean +0, and the
+ * minimum of residuals +0 and -0 is -0 (the order of IEEE 754 minimum), so the
+ * stored bytes do not depend on where in a plane a zero stands.  Subnormal
+ * inputs and means are kept, not flushed.
  * NaN or infinite inputs give unspecified codes (no error is raised).
  */
 int division_compress(const void *x, int64_t N, int64_t C, int64_t H, int64_t W,
