@@ -972,3 +972,31 @@ def test_values_at_the_edges_of_binary32(shape, B, mode, b):
         raise AssertionError(f"{pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16)}: kinds of plane that differ {where}")
     yh, _ = to_host_array(y.cpu())
     assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt), equal_nan=mode != "bf16")
+
+
+@pytest.mark.parametrize("shape,B", SPECIAL_VALUE_SHAPES)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_a_plane_of_nan_and_infinity_leaves_the_other_planes_alone(shape, B, dtype):
+    # what such a plane is compressed to is unspecified; its neighbours (same wavefront, same workgroup) must not see it
+    N, C, H, W = shape
+    x = _relu_normal(shape, 77 + B, dtype)
+    xp = x.view(N * C, -1)
+    bad = [1, N * C // 2, N * C - 1]
+    g = torch.Generator().manual_seed(B)
+    for i, p in enumerate(bad):
+        r = torch.randn(H * W, generator=g)
+        xp[p] = [torch.full_like(r, float("nan")), torch.where(r > 0, float("inf"), -float("inf")),
+                 torch.where(r > 1, float("nan"), r)][i].to(dtype)
+    xh, dt = to_host_array(x)
+    ref = oracle.split_packed(oracle.compress(xh, B, 4, 6, dt, threads=16), shape, B, 4, dt)
+    pk = pkg.division_compress(x.to("cuda:0"), B, 4, 6)
+    y = pkg.division_decompress(pk, shape, B, 4, dtype)
+    torch.cuda.synchronize()
+    got = oracle.split_packed(pk.cpu().numpy(), shape, B, 4, dt)
+    good = np.setdiff1d(np.arange(N * C), bad)
+    for k in ("codes", "meta", "lfc"):
+        a, r_ = got[k].reshape(N * C, -1), ref[k].reshape(N * C, -1)
+        assert np.array_equal(a[good].view(np.uint8), r_[good].view(np.uint8)), k
+    yh, _ = to_host_array(y.cpu())
+    want = oracle.decompress(pk.cpu().numpy(), shape, B, 4, dt).reshape(N * C, -1)
+    assert np.array_equal(yh.reshape(N * C, -1)[good], want[good])
