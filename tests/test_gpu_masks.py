@@ -176,3 +176,27 @@ def test_relu_fused_with_compression_matches_relu_then_compress(shape, B, b, fus
     torch.cuda.synchronize()
     assert torch.equal(pk2, pk) and torch.equal(m2, m) and torch.equal(pk3, pk) and torch.equal(m3, m)
     assert torch.equal(x2.view(torch.int16 if mode == "bf16" else torch.int32), y.view(torch.int16 if mode == "bf16" else torch.int32))
+
+
+@pytest.mark.parametrize("shape,B", [((3, 4, 56, 56), 8), ((2, 6, 112, 112), 8), ((3, 4, 28, 28), 8), ((3, 4, 14, 14), 8),
+                                      ((3, 4, 32, 32), 4), ((3, 4, 4, 4), 4), ((3, 4, 55, 55), 8), ((3, 4, 56, 56), 12)])
+@pytest.mark.parametrize("mode,b", [("f32", 2), ("bf16", 4), ("c16", 8)])
+def test_relu_fused_with_compression_on_values_at_the_edges_of_binary32(shape, B, mode, b):
+    # zero, signed-zero, subnormal, near-degenerate and huge planes (and their negatives) through Relu and the codec
+    from tests.test_gpu_parity import _special_planes
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    c16 = mode == "c16"
+    dt = oracle.F32_C16 if c16 else (oracle.BF16 if mode == "bf16" else oracle.F32)
+    rdt = oracle.BF16 if mode == "bf16" else oracle.F32
+    x = _special_planes(shape, 91 + B)
+    x[shape[0] // 2:] = -x[shape[0] // 2:]
+    x = x.to(dtype)
+    xh = x.view(torch.int16).numpy().view(np.uint16) if mode == "bf16" else x.numpy()
+    y_ref, m_ref = oracle.relu_forward(xh, rdt)
+    p_ref = oracle.compress(y_ref.reshape(shape), B, b, 515, dt)
+    y, m, pk = pkg.division_relu_compress(x.to("cuda:0"), B, b, 515, c16=c16)
+    torch.cuda.synchronize()
+    bits = (torch.int16, np.uint16) if mode == "bf16" else (torch.int32, np.uint32)
+    assert np.array_equal(y.cpu().view(bits[0]).numpy().view(bits[1]), y_ref.reshape(shape).view(bits[1]))
+    assert np.array_equal(m.cpu().numpy().view(np.uint32), m_ref)
+    assert np.array_equal(pk.cpu().numpy(), p_ref)
