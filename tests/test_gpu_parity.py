@@ -1000,3 +1000,25 @@ def test_a_plane_of_nan_and_infinity_leaves_the_other_planes_alone(shape, B, dty
     yh, _ = to_host_array(y.cpu())
     want = oracle.decompress(pk.cpu().numpy(), shape, B, 4, dt).reshape(N * C, -1)
     assert np.array_equal(yh.reshape(N * C, -1)[good], want[good])
+
+
+# planes of 10^5 .. 2 x 10^6 elements and block sizes from 3 to far beyond the map: the general kernels' index arithmetic
+@pytest.mark.parametrize("shape,B", [((2, 3, 1, 100003), 8), ((2, 3, 1, 100003), 1000), ((2, 3, 1, 100003), 1 << 20),
+                                      ((2, 3, 1, 1 << 20), 4096), ((2, 3, 1, 1 << 20), 65536), ((1, 2, 1, 65537 * 4), 100003),
+                                      ((1, 2, 1031, 1033), 8), ((1, 2, 1031, 1033), 2000), ((1, 2, 1024, 1024), 128),
+                                      ((1, 1, 4099, 257), 4099), ((1, 2, 257, 4100), 3), ((1, 1, 2, 500001), 1024),
+                                      ((1, 1, 500001, 2), 8), ((1, 1, 70001, 1), 70000), ((1, 2, 3, 3, 40000), 128),
+                                      ((1, 2, 40000, 3, 3), 2000), ((1, 1, 130, 130, 130), 8), ((1, 1, 130, 130, 130), 4099)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_long_maps_and_blocks_far_larger_than_the_map(shape, B, dtype):
+    three = len(shape) == 5
+    b = 2 if B % 2 == 0 else 4
+    x = _relu_normal(shape, B + sum(shape), dtype)
+    xh, dt = to_host_array(x)
+    ref = oracle.compress(xh, B, b, 9, dt, threads=16)
+    pk = (pkg.division_compress_3d if three else pkg.division_compress)(x.to("cuda:0"), B, b, 9)
+    y = (pkg.division_decompress_3d if three else pkg.division_decompress)(pk, shape, B, b, dtype)
+    torch.cuda.synchronize()
+    assert np.array_equal(pk.cpu().numpy(), ref)
+    yh, _ = to_host_array(y.cpu())
+    assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt, threads=16))
