@@ -1022,3 +1022,29 @@ def test_long_maps_and_blocks_far_larger_than_the_map(shape, B, dtype):
     assert np.array_equal(pk.cpu().numpy(), ref)
     yh, _ = to_host_array(y.cpu())
     assert np.array_equal(yh, oracle.decompress(ref, shape, B, b, dt, threads=16))
+
+
+# maps and outputs that start 1, 2, 3 or 5 elements past a 16-byte boundary, with guard elements on both sides of the output
+@pytest.mark.parametrize("shape,B", SPECIAL_VALUE_SHAPES + [((2, 6, 5, 9, 13), 4), ((1, 12, 4, 28, 28), 8), ((2, 6, 8, 27, 27), 8),
+                                                             ((1, 12, 16, 16, 16), 8)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_unaligned_maps_and_outputs_under_every_kernel_family(shape, B, dtype):
+    three = len(shape) == 5
+    numel, pad, guard = int(np.prod(shape)), 64, 7.0
+    compress = pkg.division_compress_3d if three else pkg.division_compress
+    decompress = pkg.division_decompress_3d if three else pkg.division_decompress
+    for off in (1, 2, 3, 5):
+        x = _relu_normal(shape, B + sum(shape) + off, dtype)
+        xh, dt = to_host_array(x)
+        ref = oracle.compress(xh, B, 2, 9, dt, threads=16)
+        base = torch.zeros(numel + 2 * pad, dtype=dtype, device="cuda:0")
+        base[pad + off: pad + off + numel] = x.flatten().to("cuda:0")
+        pk = compress(base[pad + off: pad + off + numel].view(shape), B, 2, 9)
+        ob = torch.full((numel + 2 * pad,), guard, dtype=dtype, device="cuda:0")
+        decompress(pk, shape, B, 2, dtype, out=ob[pad + off: pad + off + numel].view(shape))
+        torch.cuda.synchronize()
+        assert np.array_equal(pk.cpu().numpy(), ref), off
+        obh = ob.cpu()
+        yh, _ = to_host_array(obh[pad + off: pad + off + numel].contiguous())
+        assert np.array_equal(yh.reshape(shape), oracle.decompress(ref, shape, B, 2, dt, threads=16)), off
+        assert bool((obh[:pad + off] == guard).all()) and bool((obh[pad + off + numel:] == guard).all()), off
