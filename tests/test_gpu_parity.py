@@ -1025,6 +1025,7 @@ def test_long_maps_and_blocks_far_larger_than_the_map(shape, B, dtype):
 
 
 # maps and outputs that start 1, 2, 3 or 5 elements past a 16-byte boundary, with guard elements on both sides of the output
+# and guard bytes behind the packed buffer
 @pytest.mark.parametrize("shape,B", SPECIAL_VALUE_SHAPES + [((2, 6, 5, 9, 13), 4), ((1, 12, 4, 28, 28), 8), ((2, 6, 8, 27, 27), 8),
                                                              ((1, 12, 16, 16, 16), 8)])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
@@ -1039,11 +1040,13 @@ def test_unaligned_maps_and_outputs_under_every_kernel_family(shape, B, dtype):
         ref = oracle.compress(xh, B, 2, 9, dt, threads=16)
         base = torch.zeros(numel + 2 * pad, dtype=dtype, device="cuda:0")
         base[pad + off: pad + off + numel] = x.flatten().to("cuda:0")
-        pk = compress(base[pad + off: pad + off + numel].view(shape), B, 2, 9)
+        big = torch.full((ref.size + 256,), 0x5A, dtype=torch.uint8, device="cuda:0")      # guard bytes behind the packed buffer
+        compress(base[pad + off: pad + off + numel].view(shape), B, 2, 9, packed=big)
+        pk = big[:ref.size]
         ob = torch.full((numel + 2 * pad,), guard, dtype=dtype, device="cuda:0")
         decompress(pk, shape, B, 2, dtype, out=ob[pad + off: pad + off + numel].view(shape))
         torch.cuda.synchronize()
-        assert np.array_equal(pk.cpu().numpy(), ref), off
+        assert np.array_equal(pk.cpu().numpy(), ref) and bool((big[ref.size:] == 0x5A).all()), off
         obh = ob.cpu()
         yh, _ = to_host_array(obh[pad + off: pad + off + numel].contiguous())
         assert np.array_equal(yh.reshape(shape), oracle.decompress(ref, shape, B, 2, dt, threads=16)), off
