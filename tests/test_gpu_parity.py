@@ -1051,3 +1051,18 @@ def test_unaligned_maps_and_outputs_under_every_kernel_family(shape, B, dtype):
         yh, _ = to_host_array(obh[pad + off: pad + off + numel].contiguous())
         assert np.array_equal(yh.reshape(shape), oracle.decompress(ref, shape, B, 2, dt, threads=16)), off
         assert bool((obh[:pad + off] == guard).all()) and bool((obh[pad + off + numel:] == guard).all()), off
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2 ** 32, 2 ** 32 - 1, 2 ** 63 + 5, 2 ** 64 - 1])
+def test_seeds_over_the_whole_64_bit_range(seed):
+    # both halves of the seed reach the stream (Eq. quantization's rounding draws), in single and in batch calls
+    shapes = [((3, 4, 28, 28), 8), ((2, 3, 55, 55), 4), ((5, 2, 7, 7), 8)]
+    for shape, B in shapes:
+        x = _relu_normal(shape, 5 + B)
+        ref = oracle.compress(x.numpy(), B, 4, seed)
+        xd = x.to("cuda:0")
+        pk = pkg.division_compress(xd, B, 4, seed)
+        pb = pkg.division_compress_batch([xd, xd], B, 4, [seed ^ 1, seed])
+        torch.cuda.synchronize()
+        assert np.array_equal(pk.cpu().numpy(), ref)
+        assert torch.equal(pb[1], pk) and not torch.equal(pb[0], pk)
