@@ -472,3 +472,25 @@ def test_minimum_of_signed_zeros_does_not_depend_on_element_order(dt):
         s = oracle.split_packed(p, x.shape, 1, 2, dt)
         assert s["meta"].tobytes() == want
         assert oracle.decompress(p, x.shape, 1, 2, dt).tobytes() == np.abs(x).tobytes()
+
+
+def test_block_mean_in_the_subnormal_range_rounds_ties_to_even():
+    # Sec. 4.1 average pooling: exact sum / count, one rounding to binary32.  With elements k * 2^-149 the mean is
+    # (sum k / count) * 2^-149, and binary32 keeps whole multiples of 2^-149 there: the rounding is that of a rational
+    # to an integer, ties to even (python's round on a Fraction)
+    from fractions import Fraction
+    rng = _rng(41)
+    tiny = 2.0 ** -149
+    for cnt, shape, B in ((6, (1, 1, 2, 3), 4), (98, (1, 1, 7, 14), 16), (198, (1, 1, 11, 18), 18), (10, (1, 1, 1, 10), 16)):
+        ties = 0
+        for _ in range(300):
+            k = rng.integers(-3000, 3000, cnt)
+            if rng.random() < 0.5:                               # force an exact tie
+                k[0] += (cnt // 2 - int(k.sum())) % cnt
+            x = (k.astype(np.float64) * tiny).astype(np.float32).reshape(shape)
+            assert np.array_equal(x.astype(np.float64).ravel() / tiny, k)
+            lfc = oracle.split_packed(oracle.compress(x, B, 2, 3), shape, B, 2)["lfc"].ravel()
+            want = round(Fraction(int(k.sum()), cnt))
+            ties += (2 * int(k.sum())) % cnt == 0 and (2 * int(k.sum()) // cnt) % 2 == 1
+            assert lfc.size == 1 and float(lfc[0]) / tiny == want
+        assert ties > 100
