@@ -102,6 +102,14 @@ def bf16_nearest(fr: Fraction) -> Fraction:
     return lo if (lo / ulp) % 2 == 0 else hi
 
 
+def _range_is_usable(rng: Fraction) -> bool:
+    """Reading of the degenerate plane (Eq. (quantization) divides by the range): a plane is
+    quantised only if its rounded residual range is at least 2^-90 and is a finite binary32
+    number.  A difference of two finite binary32 values whose nearest binary32 would need the
+    exponent 128 has overflowed: f32() above returns 2^128 or more for it."""
+    return Fraction(2) ** -90 <= rng < Fraction(2) ** 128
+
+
 def codec_plane(x, H, W, B, b, seed, plane, c16=False):
     """x: list of H*W Fractions (exact binary32 values), row-major.
     c16: H^L, delta and Delta cached as bfloat16 (delta rounded down, Delta rounded up).
@@ -129,10 +137,11 @@ def codec_plane(x, H, W, B, b, seed, plane, c16=False):
     if c16:
         delta = bf16_floor(delta)
     rng = f32(hmax - delta)
-    if rng >= Fraction(2) ** -90 and c16:
+    usable = _range_is_usable(rng)
+    if usable and c16:
         Delta = bf16_ceil(f32(rng / L))
         inv = f32(1 / Delta)
-    elif rng >= Fraction(2) ** -90:
+    elif usable:
         Delta = f32(rng / L)
         inv = f32(Fraction(L) / rng)
         if f32(rng * inv) < L:
@@ -172,7 +181,7 @@ def codec_volume(x, dims, B, b, seed, plane):
     h = [f32(x[i] - mean_of[key[i]]) for i in range(n)]
     delta, hmax = min(h), max(h)
     rng = f32(hmax - delta)
-    if rng >= Fraction(2) ** -90:
+    if _range_is_usable(rng):
         Delta = f32(rng / L)
         inv = f32(Fraction(L) / rng)
         if f32(rng * inv) < L:
