@@ -316,6 +316,17 @@ int division_decompress_maps(int count, const division_map *maps, void *hip_stre
 int division_kernel_name_3d(int direction, const void *data, int64_t N, int64_t C, int64_t D, int64_t H,
                             int64_t W, division_dtype dt, int B, int b, char *out, size_t cap);
 
+/*
+ * Test aid (host-only, no GPU needed): the block mean of Sec. 4.1 (AveragePooling) as the compress
+ * kernels evaluate it.  The definition is (float)(block_sum / count): the exact sum of the block's
+ * elements, held in binary64, divided in binary64, rounded once to binary32.  The kernels multiply
+ * by the reciprocal of count instead and fall back to the division when the product lies close to
+ * a rounding boundary of binary32 or below the smallest normal binary32; this function runs that
+ * very rule (same source) on the host, so that it can be checked against the definition for every
+ * count.  *divided (may be null) receives 1 when the division was taken.  count == 0 returns 0.
+ */
+float division_block_mean_rule(double block_sum, uint32_t count, int *divided);
+
 /* Version of this ABI (host-only). */
 int division_abi_version(void);
 

@@ -15,21 +15,45 @@ struct WaveArgs {
     FastDiv d_ipr, d_wpp;
 };
 
-// (float)(S / cnt) for a small positive integer cnt, the way the reference
-// definition rounds it (binary64 quotient, then one rounding to binary32),
-// without a binary64 division in the common case: q = S * (1/cnt) is within
-// 2 ulp of the binary64 quotient, so both round to the same binary32 value
-// unless q lies within a few ulp of a binary32 rounding midpoint (the 29
-// mantissa bits a binary32 drops close to 1000...0); only then, for the whole
-// wavefront, the true division runs.  A nonzero q below 2^-126 rounds to a
-// subnormal binary32, which drops more than 29 bits: it takes the division too.
-__device__ __forceinline__ float mean_of(double S, uint32_t cnt) {
-    if ((cnt & (cnt - 1)) == 0) return (float)(S * (1.0 / (double)cnt));     // power of two: exact scaling
-    const double q = S * (1.0 / (double)cnt);
-    const uint32_t low = (uint32_t)__double_as_longlong(q) & 0x1fffffffu;
+// (float)(S / cnt) for a positive integer cnt, the way the reference definition rounds it
+// (binary64 quotient, then one rounding to binary32), without a binary64 division in the common
+// case.  q = fl(S * fl(1/cnt)) carries two roundings of relative size 2^-53 each, so it lies within
+// 2^-52 |S/cnt| <= 2 ulp of the exact quotient, i.e. within 3 ulp of the binary64 quotient
+// d = fl(S/cnt) (half an ulp from the exact one, plus q's own grid).  q and d round to the same
+// binary32 unless a rounding boundary of binary32 lies between them.  For a normal binary32 result
+// those boundaries are the binary64 numbers whose low 29 bits read 1000...0 (and, for d itself to
+// land on the other side, nothing closer than that): if the low 29 bits of q are at least 16 ulp
+// from that pattern, no boundary is within 16 ulp of q, d is within 3, so both round alike.
+// A nonzero q below 2^-126 rounds to a subnormal binary32, which drops more than 29 bits, so the
+// pattern test does not see its boundaries: it takes the division.  (q >= 2^-126 > d cannot
+// disagree: d is then within 3 ulp below 2^-126, q's low bits are near zero, both round to 2^-126.)
+// S is a sum of binary32 values, at least 2^-149 in magnitude when nonzero, so neither q nor d is
+// a subnormal binary64; cnt < 2^32 is exact in binary64.  mean_rule_divides says whether q may
+// stand in for d; it is host code too, so that a test can run the rule without a GPU.
+__host__ __device__ __forceinline__ bool mean_rule_divides(double q) {
+    uint64_t bits;
+    __builtin_memcpy(&bits, &q, sizeof bits);
+    const uint32_t low = (uint32_t)bits & 0x1fffffffu;
     const uint32_t dist = low > 0x10000000u ? low - 0x10000000u : 0x10000000u - low;
     const bool subnormal = q != 0.0 && __builtin_fabs(q) < 0x1p-126;
-    if (__builtin_expect(__any(dist < 16u || subnormal), 0)) return (float)(S / (double)cnt);
+    return dist < 16u || subnormal;
+}
+__host__ __device__ __forceinline__ bool mean_count_is_power_of_two(uint32_t cnt) { return (cnt & (cnt - 1)) == 0; }
+
+// The rule on the device: when any lane of the wavefront needs the division, all take it.
+__device__ __forceinline__ float mean_of(double S, uint32_t cnt) {
+    if (mean_count_is_power_of_two(cnt)) return (float)(S * (1.0 / (double)cnt));     // exact scaling
+    const double q = S * (1.0 / (double)cnt);
+    if (__builtin_expect(__any(mean_rule_divides(q)), 0)) return (float)(S / (double)cnt);
+    return (float)q;
+}
+
+// The rule for one value on the host (what a lane whose neighbours do not ask for the division computes).
+inline float mean_of_host(double S, uint32_t cnt, int* divided) {
+    *divided = 0;
+    if (mean_count_is_power_of_two(cnt)) return (float)(S * (1.0 / (double)cnt));
+    const double q = S * (1.0 / (double)cnt);
+    if (mean_rule_divides(q)) { *divided = 1; return (float)(S / (double)cnt); }
     return (float)q;
 }
 

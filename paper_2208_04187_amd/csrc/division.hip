@@ -319,6 +319,13 @@ int division_kernel_name(int direction, const void* data, int64_t N, int64_t C, 
     return kernel_name_impl(direction, data, N, C, 1, H, W, dt, B, b, out, cap);
 }
 
+float division_block_mean_rule(double block_sum, uint32_t count, int* divided) {
+    int d = 0;
+    const float m = count ? mean_of_host(block_sum, count, &d) : 0.0f;
+    if (divided) *divided = d;
+    return m;
+}
+
 int division_kernel_name_3d(int direction, const void* data, int64_t N, int64_t C, int64_t D, int64_t H, int64_t W,
                             division_dtype dt, int B, int b, char* out, size_t cap) {
     return kernel_name_impl(direction, data, N, C, D, H, W, dt, B, b, out, cap);
