@@ -8,8 +8,11 @@
  *
  * All tensor pointers are DEVICE pointers (HIP global memory) unless a
  * comment says "host".  The library allocates nothing, keeps no state between
- * calls, and never synchronises: every kernel is enqueued on the caller's
- * stream and the call returns at once.  Buffers stay owned by the caller and
+ * calls that any result depends on (it remembers the compute-unit count of each
+ * device it has seen and which kernels it has allowed a large LDS footprint),
+ * and never synchronises: every kernel is enqueued on the caller's stream and
+ * the call returns at once.  Calls act on the current device of the calling
+ * thread.  Buffers stay owned by the caller and
  * must remain valid until the stream has passed the call.
  *
  * Packed buffer layout (little endian; P = N*C planes, one plane = one
@@ -68,9 +71,15 @@ size_t division_packed_bytes(int64_t N, int64_t C, int64_t H, int64_t W,
                              int B, int b, division_dtype dt);
 
 /*
- * Byte offset and size of the three regions of the packed buffer (host-only;
- * out pointers are host pointers, none may be null).  Returns DIVISION_OK or
- * DIVISION_EINVAL.
+ * Byte offset and size of the three regions of the packed buffer, i.e. of the
+ * members of the cached tuple of Sec. 4.1 (last paragraph): codes = V^H packed
+ * at b bits (the N^2 Q/8 bytes per channel of that passage, padded to whole
+ * words), meta = (delta, Delta) of Eq. (quantization) per plane, lfc = H^L,
+ * the pooled map of ceil(H/B) x ceil(W/B) means per plane (Appendix D gives
+ * the pooled shape for B | N; the border windows are the footnote's N < B
+ * rule applied per edge).  The layout itself is stated at the top of this
+ * file.  Host-only; out pointers are host pointers, none may be null.
+ * Returns DIVISION_OK or DIVISION_EINVAL.
  */
 int division_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W,
                            int B, int b, division_dtype dt,

@@ -97,14 +97,10 @@ def _dt(t: torch.dtype, c16: bool = False) -> int:
     raise TypeError(f"unsupported dtype {t}" + (" with c16" if c16 else ""))
 
 
-# the raw handle of torch's current stream without building a torch.cuda.Stream object (8 us per call)
-_raw_current_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
-
-
 def _stream(stream) -> int:
+    """The hipStream_t to launch on, as an integer: the given stream (a torch.cuda.Stream or a raw
+    handle), else torch's current stream through its public accessor."""
     if stream is None:
-        if _raw_current_stream is not None:
-            return int(_raw_current_stream(torch.cuda.current_device()))
         stream = torch.cuda.current_stream()
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 

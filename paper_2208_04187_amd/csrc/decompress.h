@@ -37,12 +37,9 @@ __device__ __forceinline__ float dequant(uint32_t q, float Delta, float delta, f
 // Four reconstructed elements leave with one store.  The map is written once
 // and not read again by this library, so the stores are non-temporal: they do
 // not displace what the neighbouring kernels keep in the caches (3.5 % on the
-// whole compress + decompress step).  Build with -DDIVISION_TEMPORAL_STORE when
-// the consumer of the map runs right behind and should find it in the
-// last-level cache.
+// whole compress + decompress step).
 template <typename T>
 __device__ __forceinline__ void store4(T* dst, size_t i, float a, float b, float c, float d) {
-#ifndef DIVISION_TEMPORAL_STORE
     if constexpr (sizeof(T) == 4) {
         f32x4 v; v.x = a; v.y = b; v.z = c; v.w = d;
         __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst + i));
@@ -53,16 +50,6 @@ __device__ __forceinline__ void store4(T* dst, size_t i, float a, float b, float
         o.y = float_to_bf16_bits(c) | (float_to_bf16_bits(d) << 16);
         __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(dst + i));
     }
-#else
-    if constexpr (sizeof(T) == 4) {
-        *reinterpret_cast<float4*>(dst + i) = make_float4(a, b, c, d);
-    } else {
-        uint2 o;
-        o.x = float_to_bf16_bits(a) | (float_to_bf16_bits(b) << 16);
-        o.y = float_to_bf16_bits(c) | (float_to_bf16_bits(d) << 16);
-        *reinterpret_cast<uint2*>(dst + i) = o;
-    }
-#endif
 }
 
 // Copies this workgroup's slices of the three packed regions (codes, meta, LFC

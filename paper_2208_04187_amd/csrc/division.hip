@@ -47,6 +47,7 @@
 #include <stddef.h>
 #include <stdio.h>
 #include <stdlib.h>
+#include <atomic>
 #include <type_traits>
 #include <vector>
 #include "../../include/division.h"

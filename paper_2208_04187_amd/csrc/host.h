@@ -59,15 +59,18 @@ Regions make_regions(const Layout& L) {
 constexpr uint32_t kWaveChunkLds = 8704u;
 constexpr uint32_t kWavePlaneMax = 17u << 10;
 
+// Compute units of the current device (sizes the grids of the kernels that walk over planes).  Asked
+// once per device and kept: a table of constants of the machine, not state of a call.
 int num_cus() {
-    static int n = [] {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-            v = 256;
-        return v;
-    }();
-    return n;
+    constexpr int kMaxDev = 64;
+    static std::atomic<int> cus[kMaxDev];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return 256;
+    int v = cus[dev].load(std::memory_order_relaxed);
+    if (v > 0) return v;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    cus[dev].store(v, std::memory_order_relaxed);
+    return v;
 }
 
 // dynamic LDS above the default limit needs a one-time opt-in per kernel
