@@ -35,14 +35,16 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> Path:
-    """Compile unconditionally; returns the path of the shared library."""
+def build(verbose: bool = False, extra_flags=(), out: Path | None = None) -> Path:
+    """Compile unconditionally; returns the path of the shared library.  extra_flags are added to every
+    hipcc compile line and out replaces the library's path (both for builds that compare variants)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    lib_path = Path(out) if out is not None else LIB
     objdir = Path(tempfile.mkdtemp(prefix="division_build_"))
     try:
         def compile_unit(unit):
             name, src, extra = unit
-            cmd = [hipcc, *HIPCC_FLAGS, *extra, "-c", "-o", str(objdir / name), str(src)]
+            cmd = [hipcc, *HIPCC_FLAGS, *extra, *extra_flags, "-c", "-o", str(objdir / name), str(src)]
             return name, subprocess.run(cmd, capture_output=True, text=True)
 
         with ThreadPoolExecutor(max_workers=len(UNITS)) as pool:
@@ -57,13 +59,13 @@ def build(verbose: bool = False) -> Path:
             raise RuntimeError("a kernel spills registers to scratch memory (performance guard):\n" + "\n".join(spills[:5]))
         if verbose and log:
             print("\n".join(ln for ln in log.splitlines() if "remark:" not in ln))
-        tmp = LIB.with_name(LIB.name + ".tmp%d" % os.getpid())
+        tmp = lib_path.with_name(lib_path.name + ".tmp%d" % os.getpid())
         link = [hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", str(tmp), *(str(objdir / u[0]) for u in UNITS)]
         res = subprocess.run(link, capture_output=True, text=True)
         if res.returncode != 0:
             tmp.unlink(missing_ok=True)
             raise RuntimeError("link failed:\n" + res.stderr)
-        os.replace(tmp, LIB)
+        os.replace(tmp, lib_path)
     finally:
         shutil.rmtree(objdir, ignore_errors=True)
-    return LIB
+    return lib_path

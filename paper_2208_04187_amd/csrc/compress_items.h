@@ -88,20 +88,20 @@ __device__ __forceinline__ void compress_items_body(const ItemsArgs& a) {
                 const uint32_t vo = fullrows ? base : base + ((uint32_t)rr < nrows ? rr * rowb : 0u);
                 const uint32_t so = fullrows ? rr * rowb : 0u;
                 if constexpr (sizeof(T) == 4 && VEC == 4) {
-                    const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, vo, so, kLoadAux);
+                    const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, vo, so, kLoadReuse);
                     v[rr][0] = __uint_as_float(q.x); v[rr][1] = __uint_as_float(q.y);
                     v[rr][2] = __uint_as_float(q.z); v[rr][3] = __uint_as_float(q.w);
                 } else if constexpr (sizeof(T) == 4 && VEC == 2) {
                     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-                    const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, vo, so, kLoadAux);
+                    const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, vo, so, kLoadReuse);
                     v[rr][0] = __uint_as_float(q.x); v[rr][1] = __uint_as_float(q.y);
                 } else if constexpr (VEC == 4) {
                     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-                    const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, vo, so, kLoadAux);
+                    const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, vo, so, kLoadReuse);
                     v[rr][0] = __uint_as_float(q.x << 16); v[rr][1] = __uint_as_float(q.x & 0xffff0000u);
                     v[rr][2] = __uint_as_float(q.y << 16); v[rr][3] = __uint_as_float(q.y & 0xffff0000u);
                 } else {
-                    const uint32_t q = __builtin_amdgcn_raw_buffer_load_b32(rsrc, vo, so, kLoadAux);
+                    const uint32_t q = __builtin_amdgcn_raw_buffer_load_b32(rsrc, vo, so, kLoadReuse);
                     v[rr][0] = __uint_as_float(q << 16); v[rr][1] = __uint_as_float(q & 0xffff0000u);
                 }
             }

@@ -48,53 +48,63 @@ __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
     float* red = lfcs + ((a.nb + 1 + 3) & ~3u);                        // [2*NW] cross-wave min / max
     double* zsum = reinterpret_cast<double*>(red + 2 * NW + 2);       // [nb*B] (3-D maps) one sum per block and depth slice
 
-    const uint32_t tid = threadIdx.x;
-    const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
-
-    // which block each of the lane's units belongs to (nb = sentinel for units past the plane)
     uint32_t blk[K];
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-        const uint32_t f = tid + NT * k;
-        const uint32_t row = fdiv(f, a.d_w4);          // row, counted over all depth slices
-        const uint32_t c4 = f - row * a.w4;
-        if constexpr (ND == 3) {
-            const uint32_t z = fdiv(row, a.d_H);
-            blk[k] = f < a.q4 ? ((z / B) * a.LH + (row - z * a.H) / B) * a.LW + c4 / UPB : a.nb;
-        } else if constexpr (B != 0) blk[k] = f < a.q4 ? (row / B) * a.LW + c4 / UPB : a.nb;
-        else blk[k] = f < a.q4 ? fdiv(row, a.d_B) * a.LW + fdiv(c4, a.d_upb) : a.nb;
-    }
-    if (tid == 0) lfcs[a.nb] = __builtin_nanf("");
     bool full_blocks = false;
     if constexpr (B != 0) full_blocks = (a.H % B) == 0 && (a.W % B) == 0 && (ND == 2 || (a.D % B) == 0);
+    const uint32_t tid = threadIdx.x;
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
     // rounds of units a plane has (uniform); the one- and four-wavefront instances for B = 4 and 8
     // always run all K (their planes fill at least eight of them)
     auto round_live = [&](int k) -> bool { return (B != 0 && NW != 16 && ND == 2) || (uint32_t)(NT * k) < a.q4; };
 
-    const uint32_t pbeg = blockIdx.x * a.ppw;
-    const uint32_t pend = min(a.P, pbeg + a.ppw);
-    for (uint32_t p = pbeg; p < pend; ++p) {
-        // ---- load the plane: coalesced, bounds-checked (units past the plane read as zero)
+    // One plane per workgroup (more workgroups, better balance than several planes each).  Which
+    // plane: see xcd_run_index.
+    const uint32_t p = xcd_run_index(blockIdx.x, a.P);
+    {
+        // ---- load the plane first of all: coalesced, bounds-checked (units past the plane read as
+        // zero).  Everything the workgroup has to set up (the block of each unit, the sentinel)
+        // runs while the loads are in flight.
         float x[K][4];
         {
             const T* src = static_cast<const T*>(pt.x) + (size_t)p * a.HW;
             const __amdgpu_buffer_rsrc_t rsrc =
                 __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(a.HW * sizeof(T)), 0x00020000);
+            u32x4 q[K];
 #pragma unroll
             for (int k = 0; k < K; ++k) {
-                if (!round_live(k)) {
-                    x[k][0] = x[k][1] = x[k][2] = x[k][3] = 0.0f;
-                    continue;
-                }
+                q[k] = u32x4{0u, 0u, 0u, 0u};
+                if (!round_live(k)) continue;
                 if constexpr (sizeof(T) == 4) {
-                    const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, tid * 16u, k * NT * 16, kLoadAux);
-                    x[k][0] = __uint_as_float(q.x); x[k][1] = __uint_as_float(q.y);
-                    x[k][2] = __uint_as_float(q.z); x[k][3] = __uint_as_float(q.w);
+                    q[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, tid * 16u, k * NT * 16, kLoadAux);
                 } else {
                     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-                    const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, tid * 8u, k * NT * 8, kLoadAux);
-                    x[k][0] = __uint_as_float(q.x << 16); x[k][1] = __uint_as_float(q.x & 0xffff0000u);
-                    x[k][2] = __uint_as_float(q.y << 16); x[k][3] = __uint_as_float(q.y & 0xffff0000u);
+                    const u32x2 h = __builtin_amdgcn_raw_buffer_load_b64(rsrc, tid * 8u, k * NT * 8, kLoadAux);
+                    q[k].x = h.x; q[k].y = h.y;
+                }
+            }
+            // which block each of the lane's units belongs to (nb = sentinel for units past the plane)
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const uint32_t f = tid + NT * k;
+                const uint32_t row = fdiv(f, a.d_w4);          // row, counted over all depth slices
+                const uint32_t c4 = f - row * a.w4;
+                uint32_t bk;
+                if constexpr (ND == 3) {
+                    const uint32_t z = fdiv(row, a.d_H);
+                    bk = ((z / B) * a.LH + (row - z * a.H) / B) * a.LW + c4 / UPB;
+                } else if constexpr (B != 0) bk = (row / B) * a.LW + c4 / UPB;
+                else bk = fdiv(row, a.d_B) * a.LW + fdiv(c4, a.d_upb);
+                blk[k] = f < a.q4 ? bk : a.nb;
+            }
+            if (tid == 0) lfcs[a.nb] = __builtin_nanf("");
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                if constexpr (sizeof(T) == 4) {
+                    x[k][0] = __uint_as_float(q[k].x); x[k][1] = __uint_as_float(q[k].y);
+                    x[k][2] = __uint_as_float(q[k].z); x[k][3] = __uint_as_float(q[k].w);
+                } else {
+                    x[k][0] = __uint_as_float(q[k].x << 16); x[k][1] = __uint_as_float(q[k].x & 0xffff0000u);
+                    x[k][2] = __uint_as_float(q[k].y << 16); x[k][3] = __uint_as_float(q[k].y & 0xffff0000u);
                 }
             }
         }
@@ -285,7 +295,6 @@ __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
             const uint32_t padb = a.WPP * 4 - a.q4 * CB;
             if (tid < padb) cbase[a.q4 * CB + tid] = 0;
         }
-        if constexpr (NW == 1) wave_sync(); else lds_barrier();      // usum, lfcs and red are reused
     }
 }
 

@@ -136,11 +136,7 @@ __device__ __forceinline__ void decompress_rowvec_body(const DecArgs& a) {
                                (float_to_bf16_bits(dequant((hi >> ((2 * e + 1) * BITS)) & Lq, dd.y, dd.x, l1)) << 16);
                 }
                 u32x4 o; o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
-#ifndef DIVISION_TEMPORAL_STORE
                 __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(out + (size_t)vi * 4));
-#else
-                *reinterpret_cast<u32x4*>(out + (size_t)vi * 4) = o;
-#endif
             }
             return;
         }

@@ -87,9 +87,17 @@ constexpr uint32_t kLdsTarget = 40u << 10; // preferred LDS bytes per workgroup 
 constexpr uint32_t kRowsLdsTarget = 40u << 10; // same for compress_rows
 constexpr uint32_t kLdsMax = 156u << 10;   // hard limit per workgroup (160 KB per CU)
 constexpr uint32_t kWeyl = 0x9E3779B9u;
-// cache policy of the loads of x: default.  x is read exactly once, but marking
-// the loads non-temporal (2) measured 4 % slower on the whole step.
-constexpr int kLoadAux = 0;
+// Cache policy of the loads of x (the aux operand of the buffer loads: bit 1 = nt).  A kernel whose
+// wavefronts read whole contiguous runs, every line once, marks its loads non-temporal: a read-only
+// stream of this shape measured 6.4 -> 7.0 TB/s that way, and x no longer displaces the packed
+// buffers from the last-level cache.  A kernel whose lanes read rows of a few bytes each
+// (compress_items) touches every line several times and needs the default policy: it ran 15 %
+// slower with non-temporal loads.
+#ifndef DIVISION_LOAD_AUX
+#define DIVISION_LOAD_AUX 2
+#endif
+constexpr int kLoadAux = DIVISION_LOAD_AUX;
+constexpr int kLoadReuse = 0;
 
 #include "helpers.h"
 #include "compress_tile.h"

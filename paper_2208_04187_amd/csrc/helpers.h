@@ -195,6 +195,22 @@ __device__ __forceinline__ DecPtrs dec_ptrs(const DecTab& tab, const Regions& rg
     return pt;
 }
 
+// Which unit of work (a plane, a chunk of planes) workgroup b of n takes.  Workgroups are dealt to
+// the eight XCDs round-robin by their index, and each XCD has its own L2.  A compress workgroup
+// writes a few hundred bytes into each of three regions (codes, meta, H^L), far less than a cache
+// line per region for small planes, so with the plain order b -> b the lines of those regions are
+// written piecewise from eight L2s.  Here the workgroups of one XCD (equal b % 8) take runs of 64
+// consecutive units instead, so that every line of the packed buffer is completed inside one L2
+// and leaves it whole (a read stream with the writes of compress_regs: 5.63 -> 5.81 TB/s).  The
+// last n % 512 units keep the plain order.
+__device__ __forceinline__ uint32_t xcd_run_index(uint32_t b, uint32_t n) {
+    constexpr uint32_t X = 8, R = 64;
+    const uint32_t full = n - n % (X * R);
+    if (b >= full) return b;
+    const uint32_t x = b % X, j = b / X;
+    return ((j / R) * X + x) * R + (j % R);
+}
+
 struct TileArgs {
     CompTab tab;
     Regions rg;

@@ -594,7 +594,10 @@ constexpr size_t kDecLdsMax = 60u << 10;
 // is the flat optimum (64 KB: 0.5-1 % slower, 12 KB: 4 % slower, 6 KB: 12 %).  A decompress kernel
 // timed on its own, launch after launch, prefers 12 KB by 15 %, but not between other kernels.
 // `mult`: G must be a multiple of it (flat kernel: whole 4-element vectors).
-constexpr uint64_t kDecChunkBytes = 32768;
+#ifndef DIVISION_DEC_CHUNK
+#define DIVISION_DEC_CHUNK 32768
+#endif
+constexpr uint64_t kDecChunkBytes = DIVISION_DEC_CHUNK;
 uint64_t dec_planes(const Layout& L, size_t es, uint64_t mult) {
     const uint64_t target = kDecChunkBytes / es;
     uint64_t G = (target + L.HW / 2) / L.HW;
