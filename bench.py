@@ -346,6 +346,10 @@ def main() -> int:
                     help="cache H^L, delta and Delta as bfloat16 (the paper's format; fp32 workloads only)")
     ap.add_argument("--compare-modes", action="store_true",
                     help="also time the other launch mode (before the reported one) and add its figures to the line")
+    ap.add_argument("--roofline-every", type=int, default=4,
+                    help="bracket the dominant kernel's launches with events on every N-th timed step (default 4). "
+                         "An event pair is two more packets for the command processor and opens a gap of 5-9 us "
+                         "before the launch it brackets; on every step that is 4 %% of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-shape", action="store_true",
                     help="time compress and decompress of every distinct tensor shape of the workload on their own, "
@@ -472,24 +476,33 @@ def main() -> int:
 
     def timed(mode):
         launches = launch_list(mode)
-        # warm-up; its last step times every launch to find the dominant kernel
-        for w in range(max(1, args.warmup) - 1):
+        # preparation (untimed, before the warm-up): a few steps so that buffers, code objects and clocks
+        # are where a running job has them, then one step that times every launch to find the dominant
+        # kernel, and the events the timed region will need (creating one costs the host microseconds)
+        for w in range(8):
             run_step(launches, w % nsets)
         probe = []
-        run_step(launches, (max(1, args.warmup) - 1) % nsets, None, probe)
+        run_step(launches, 0, None, probe)
         torch.cuda.synchronize()
         per_kernel = {}
         for (d, g), e0, e1 in probe:
             per_kernel[kname(d, g)] = per_kernel.get(kname(d, g), 0.0) + e0.elapsed_time(e1)
         dominant = max(per_kernel, key=per_kernel.get)
-        # timed region: exactly K steps; events only around the dominant kernel's launches
         events = []
         n_dom = sum(1 for d, g in launches if kname(d, g) == dominant)
-        pool = [StreamEvent(torch) for _ in range(2 * n_dom * args.steps)]
+        every = max(1, min(args.roofline_every, args.steps))
+        pool = [StreamEvent(torch) for _ in range(2 * n_dom * (args.steps // every + 1))]
+        # W warm-up steps, then exactly K timed steps between two synchronisations; events only around the
+        # dominant kernel's launches, on every `every`-th step
+        for w in range(args.warmup):
+            run_step(launches, w % nsets)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for k in range(args.steps):
-            run_step(launches, k % nsets, dominant, events, pool)
+            if k % every == 0:
+                run_step(launches, k % nsets, dominant, events, pool)
+            else:
+                run_step(launches, k % nsets)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         return (t1 - t0) * 1e3 / args.steps, per_kernel, dominant, events, len(launches)
@@ -529,7 +542,7 @@ def main() -> int:
         "compression_ratio": round(input_bytes / packed_bytes, 3),
         f"{other_mode}_mode_GB_s": round(algo_bytes_step / (other_ms * 1e-3) / 1e9, 1) if other_ms else None,
         f"{other_mode}_mode_ms_per_step": round(other_ms, 4) if other_ms else None,
-        "kernel_ms_last_warmup_step": {k: round(v, 4) for k, v in sorted(per_kernel.items())},
+        "kernel_ms_probe_step": {k: round(v, 4) for k, v in sorted(per_kernel.items())},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(dominant) if args.config == 2 and args.batch is None and not args.c16 else None,

@@ -62,13 +62,14 @@ __device__ __forceinline__ void compress_items_body(const ItemsArgs& a) {
     const uint32_t rowW = (a.W / 2u) * kWeyl;                 // pair counter distance between rows
     const uint32_t rwords = a.ppr * a.WPP;
 
-    const uint32_t rend = min(a.nrounds, (blockIdx.x + 1) * a.rpw);
+    const uint32_t wg = xcd_run_index(blockIdx.x, gridDim.x);   // which run of rpw rounds this workgroup takes
+    const uint32_t rend = min(a.nrounds, (wg + 1) * a.rpw);
     const uint32_t mbits = a.rpw * a.ppr * a.HW;               // RELU: mask bits of a workgroup (a multiple of 32)
     if constexpr (RELU) {
         for (uint32_t w = lane; w < mbits / 32u; w += 64) mw[w] = 0u;
         wave_sync();
     }
-    for (uint32_t round = blockIdx.x * a.rpw; round < rend; ++round) {
+    for (uint32_t round = wg * a.rpw; round < rend; ++round) {
         const uint32_t p0 = round * a.ppr;
         const uint32_t Gc = min(a.ppr, a.P - p0);
         const bool live = g < Gc;
@@ -115,7 +116,7 @@ __device__ __forceinline__ void compress_items_body(const ItemsArgs& a) {
                 __builtin_amdgcn_make_buffer_rsrc(ydst, 0, (int)(Gc * a.HW * sizeof(T)), 0x00020000);
             const uint32_t base = (g * a.HW + off) * (uint32_t)sizeof(T);
             const uint32_t rowb = a.W * (uint32_t)sizeof(T);
-            const uint32_t bit0 = (round - blockIdx.x * a.rpw) * a.ppr * a.HW + g * a.HW + off;    // of the item's first row
+            const uint32_t bit0 = (round - wg * a.rpw) * a.ppr * a.HW + g * a.HW + off;    // of the item's first row
 #pragma unroll
             for (int rr = 0; rr < R; ++rr) {
                 uint32_t bits = 0;
@@ -218,8 +219,8 @@ __device__ __forceinline__ void compress_items_body(const ItemsArgs& a) {
         wave_sync();                                           // the words are cleared again by the next round
     }
     if constexpr (RELU) {
-        // the workgroup's mask words: bits [blockIdx.x * mbits, ...) of the map, as far as the map goes
-        const uint64_t first = (uint64_t)blockIdx.x * mbits;
+        // the workgroup's mask words: bits [wg * mbits, ...) of the map, as far as the map goes
+        const uint64_t first = (uint64_t)wg * mbits;
         const uint64_t total = (uint64_t)a.P * a.HW;
         const uint32_t nbits = (uint32_t)min((uint64_t)mbits, total - first);
         uint32_t* dst = a.mask + first / 32u;

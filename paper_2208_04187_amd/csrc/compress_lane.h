@@ -32,8 +32,9 @@ __global__ void __launch_bounds__(64) compress_lane(LaneArgs a) {
     const uint32_t rscale = 1u << (16 - BITS);
     const float* mine = xs + lane * a.HW;
 
-    const uint32_t rend = min(a.nrounds, (blockIdx.x + 1) * a.rpw);
-    for (uint32_t round = blockIdx.x * a.rpw; round < rend; ++round) {
+    const uint32_t wg = xcd_run_index(blockIdx.x, gridDim.x);   // which run of rpw rounds this workgroup takes
+    const uint32_t rend = min(a.nrounds, (wg + 1) * a.rpw);
+    for (uint32_t round = wg * a.rpw; round < rend; ++round) {
         const uint32_t p0 = round * 64u;
         const uint32_t Gc = min(64u, a.P - p0);
         const uint32_t n = Gc * a.HW;

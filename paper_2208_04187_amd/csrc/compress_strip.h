@@ -1,0 +1,157 @@
+// Part of division.hip (included inside its unnamed namespace, in this order): compress_strip.
+
+// ------------------------------------------------------------------ compress, a strip of 28 elements per lane
+
+struct StripArgs {
+    CompTab tab;
+    Regions rg;
+    uint32_t P, H, HW, WPP, nb;
+    uint32_t nrounds;    // ceil(P / planes per round)
+};
+
+// Planes of width 28 or 14 under B = 8 (the 28 x 28 and 14 x 14 maps of a ResNet): a lane owns a
+// strip of 28 consecutive elements of its plane, i.e. one row of a 28-wide map or two rows of a
+// 14-wide one, seven 16-byte units either way, and keeps it in registers from the pooling to the
+// codes.  The lanes of a plane sit side by side (32 slots for up to 32 rows of width 28, 8 slots
+// for up to 16 rows of width 14; 2 resp. 8 planes per wavefront), the lanes of a block row are an
+// aligned group of 8 resp. 4 lanes, so that the block sums (binary64) and the plane's extremes are
+// DPP reductions and every lane ends up with its own blocks' H^L and its plane's scale: no
+// per-block pass, no lookup.
+//
+// Memory side: the round (all its planes are contiguous) is read with coalesced 16-byte loads that
+// are issued before anything else and land in LDS in the map's own order; each lane then takes its
+// strip out of LDS (a stride of 28 words: eight lanes cover the banks once).  The codes of a unit
+// go back to LDS as one byte / half-word / word and leave as whole coalesced words.
+// One round per workgroup of one wavefront.
+template <typename T, int BITS, int W>
+__global__ void __launch_bounds__(64) compress_strip(StripArgs a) {
+    static_assert(W == 28 || W == 14, "strip widths");
+    constexpr int E = 28;                       // elements per lane
+    constexpr int S = W == 28 ? 32 : 8;         // lane slots per plane
+    constexpr int G = 64 / S;                   // planes per round
+    constexpr int LB = W == 28 ? 8 : 4;         // lanes per block row (8 rows)
+    constexpr int NSEG = (W + 7) / 8;           // blocks per block row = columns of the pooled map
+    constexpr int CB = BITS / 2;                // code bytes per 4-element unit
+    constexpr float Lf = float((1 << BITS) - 1);
+    extern __shared__ float4 smem4[];
+    float* xs = reinterpret_cast<float*>(smem4);                     // [G * HW] the round (at most 7 x 64 units), later its code words
+
+    const uint32_t lane = threadIdx.x;
+    const CompPtrs pt = comp_ptrs(a.tab, a.rg, lane);
+    const uint32_t round = xcd_run_index(blockIdx.x, a.nrounds);
+    const uint32_t p0 = round * G;
+    const uint32_t Gc = min((uint32_t)G, a.P - p0);
+
+    // ---- the round's loads first: coalesced, bounds-checked (units past the round read as zero)
+    u32x4 q[7];
+    {
+        const T* src = static_cast<const T*>(pt.x) + (size_t)p0 * a.HW;
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(Gc * a.HW * sizeof(T)), 0x00020000);
+#pragma unroll
+        for (int k = 0; k < 7; ++k) {
+            if constexpr (sizeof(T) == 4) {
+                q[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane * 16u, k * 1024, kLoadAux);
+            } else {
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                const u32x2 h = __builtin_amdgcn_raw_buffer_load_b64(rsrc, lane * 8u, k * 512, kLoadAux);
+                q[k] = u32x4{h.x << 16, h.x & 0xffff0000u, h.y << 16, h.y & 0xffff0000u};
+            }
+        }
+    }
+    // the lane's place: plane g of the round, strip sl of the plane
+    const uint32_t g = lane / S, sl = lane % S;
+    const bool live = g < Gc;
+    const bool valid = live && sl * E < a.HW;
+    const uint32_t bi = sl / LB;                                       // block row of the strip
+    const uint32_t rows = min(8u, a.H - min(a.H, bi * 8u));            // rows of that block row that exist
+    const uint32_t p = p0 + g;
+    const uint32_t k1 = mix32(p ^ pt.seed_a);
+    const uint32_t k2 = mix32(k1 + pt.seed_c);
+    const uint32_t rscale = 1u << (16 - BITS);
+    const uint32_t xv = G * a.HW / 4u;                                // units of a whole round
+#pragma unroll
+    for (int k = 0; k < 7; ++k)
+        if (lane + 64u * k < xv) reinterpret_cast<u32x4*>(xs)[lane + 64 * k] = q[k];
+    wave_sync();
+
+    // ---- the strip; lanes without one take strip 0 of the round and have their effects masked
+    float x[E];
+    {
+        const float4* sp = reinterpret_cast<const float4*>(xs + (valid ? g * a.HW + sl * E : 0u));
+#pragma unroll
+        for (int u = 0; u < 7; ++u) {
+            const float4 v = sp[u];
+            x[4 * u] = v.x; x[4 * u + 1] = v.y; x[4 * u + 2] = v.z; x[4 * u + 3] = v.w;
+        }
+    }
+
+    // ---- Sec. 4.1 AveragePooling: the strip's share of each block of its block row, then the
+    // block row's lanes together (binary64, fixed order)
+    double Sm[NSEG];
+#pragma unroll
+    for (int s = 0; s < NSEG; ++s) Sm[s] = 0.0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) Sm[(e % W) / 8] += (double)x[e];
+    float lfc[NSEG];
+#pragma unroll
+    for (int s = 0; s < NSEG; ++s) {
+        const double Sb = group_sum<LB>(valid ? Sm[s] : 0.0);
+        const uint32_t cols = (uint32_t)(W - 8 * s < 8 ? W - 8 * s : 8);     // a constant once the loop is unrolled
+        lfc[s] = lfc_round<T>(mean_of(Sb, max(rows, 1u) * cols), kC16<T>);
+    }
+    if (valid && sl % LB == 0) {
+#pragma unroll
+        for (int s = 0; s < NSEG; ++s) lfc_store<T>(pt.lfc, (size_t)p * a.nb + bi * NSEG + s, lfc[s], kC16<T>);
+    }
+
+    // ---- residual H^H = H - UpSampling(H^L) in place, the plane's extremes
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        x[e] = x[e] - lfc[(e % W) / 8];
+        mn = fminf(mn, x[e]);
+        mx = fmaxf(mx, x[e]);
+    }
+    mn = valid ? mn : __builtin_inff();
+    mx = valid ? mx : -__builtin_inff();
+    group_minmax(S, mn, mx);
+
+    // ---- scale of Eq. (quantization): every lane of the plane computes the same values
+    float delta, Delta, inv;
+    plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
+    const float invs = inv * (float)(1u << (32 - BITS));
+    if (live && sl == 0) meta_store(pt.meta, p, delta, Delta, kC16<T>);
+
+    // ---- Quant + packing: a unit's four codes are one byte (b = 2), half-word or word of the plane's
+    // code bytes; they are collected in LDS (over the round, which every lane has taken out by now)
+    wave_sync();
+    uint32_t* cw = reinterpret_cast<uint32_t*>(xs);
+    const uint32_t nwords = Gc * a.WPP;
+    {
+        // pad bytes of a plane's last word stay zero
+        const u32x4 z{0u, 0u, 0u, 0u};
+        for (uint32_t i = lane; i * 4u < nwords; i += 64) reinterpret_cast<u32x4*>(cw)[i] = z;
+    }
+    wave_sync();
+    {
+        uint8_t* cb = reinterpret_cast<uint8_t*>(cw) + g * a.WPP * 4u + sl * (7u * CB);
+        const uint32_t xw0 = k1 + (sl * 14u) * kWeyl;
+#pragma unroll
+        for (int u = 0; u < 7; ++u) {
+            const uint32_t xw = xw0 + (uint32_t)(2 * u) * kWeyl;
+            uint32_t c = push_pair<BITS>(0u, x[4 * u + 2], x[4 * u + 3], delta, invs, xw + kWeyl, k2, rscale);
+            c = push_pair<BITS>(c, x[4 * u], x[4 * u + 1], delta, invs, xw, k2, rscale);
+            if (valid) {
+                if constexpr (CB == 1) cb[u] = (uint8_t)c;
+                else if constexpr (CB == 2) reinterpret_cast<uint16_t*>(cb)[u] = (uint16_t)c;
+                else reinterpret_cast<uint32_t*>(cb)[u] = c;
+            }
+        }
+    }
+    wave_sync();
+    {
+        uint32_t* dst = pt.codes + (size_t)p0 * a.WPP;
+        for (uint32_t w = lane; w < nwords; w += 64) dst[w] = cw[w];
+    }
+}

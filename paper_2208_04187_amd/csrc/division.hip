@@ -19,6 +19,9 @@
 //                    workgroup of one / four / sixteen wavefronts, the plane stays in registers from
 //                    load to codes
 //   compress_lane    one-block planes with an odd element count (7x7): a lane per plane
+//   compress_strip   28 x 28 and 14 x 14 planes (widths 28 and 14, up to 32 resp. 16 rows) under B = 8: a lane per strip
+//                    of 28 consecutive elements (one or two rows), the round read with coalesced loads and
+//                    handed out through LDS, block sums and extremes by DPP
 //   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8: a lane per
 //                    pooling item, loaded straight from global memory, DPP reductions (relu_compress_items:
 //                    the same with a Relu applied to the rows as they arrive)
@@ -103,6 +106,7 @@ constexpr int kLoadReuse = 0;
 #include "compress_tile.h"
 #include "compress_wave.h"
 #include "compress_items.h"
+#include "compress_strip.h"
 #include "compress_lane.h"
 #include "compress_regs.h"
 #include "compress_units.h"

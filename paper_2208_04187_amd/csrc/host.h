@@ -296,6 +296,30 @@ bool plan_items(const Layout& L, int64_t H, int64_t W, int B, size_t es, const v
     return true;
 }
 
+// Fills the strip kernel's plan: 2-D maps of width 28 (at most 32 rows) or 14 (an even number of rows,
+// at most 16) under B = 8; false when the shape is not covered.
+bool plan_strip(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* x,
+                StripArgs* a, uint32_t* grid, size_t* lds, int* width) {
+    if (B != 8 || ((uintptr_t)x % (4 * es)) != 0) return false;
+    uint64_t G;
+    if (W == 28 && H <= 32) G = 2;
+    else if (W == 14 && H % 2 == 0 && H <= 16) G = 8;
+    else return false;
+    a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP; a->nb = (uint32_t)L.nb;
+    a->nrounds = (uint32_t)((L.P + G - 1) / G);
+    *grid = a->nrounds;
+    *lds = 4ull * G * L.HW + 16;
+    *width = (int)W;
+    return true;
+}
+
+template <typename T, int BITS>
+hipError_t launch_strip(int width, const StripArgs& a, dim3 grid, size_t lds, hipStream_t st) {
+    void (*kern)(StripArgs) = width == 28 ? compress_strip<T, BITS, 28> : compress_strip<T, BITS, 14>;
+    hipLaunchKernelGGL(kern, grid, dim3(64), lds, st, a);
+    return hipGetLastError();
+}
+
 template <typename T, int BITS>
 hipError_t launch_items(int B, int vec, const ItemsArgs& a, dim3 grid, size_t lds, hipStream_t st) {
     void (*kern)(ItemsArgs);
@@ -718,7 +742,7 @@ hipError_t with_bits(int b, F&& f) {
                                                                   : f(std::integral_constant<int, 8>{});
 }
 
-enum CompKind { REGS, LANE, LINE, ITEMS, UNITS, WAVE, TILE, ONE, ROWS, PLANE, ANY };
+enum CompKind { REGS, LANE, LINE, STRIP, ITEMS, UNITS, WAVE, TILE, ONE, ROWS, PLANE, ANY };
 
 // everything a compress launch needs once the plan is made (the arguments of the kernel that was picked)
 struct CompLaunch {
@@ -726,7 +750,7 @@ struct CompLaunch {
     uint32_t gx, gy;
     size_t lds;
     hipStream_t st;
-    TileArgs a; WaveArgs wa; RegsArgs ra; ItemsArgs ia; LaneArgs la; RowsArgs wa2; PlaneArgs pa; OneArgs oa; AnyArgs g; UnitsArgs ua;
+    TileArgs a; WaveArgs wa; RegsArgs ra; ItemsArgs ia; LaneArgs la; RowsArgs wa2; PlaneArgs pa; OneArgs oa; AnyArgs g; UnitsArgs ua; StripArgs sa;
 };
 struct DecLaunch {
     int kind, flat, nw;
@@ -746,6 +770,7 @@ hipError_t do_compress(const CompLaunch& c, int b) {
         constexpr int BITS = decltype(bits)::value;
         switch (c.kind) {
             case REGS: return launch_regs<T, BITS>(c.B, c.nw, c.ra, gd, lds, st);
+            case STRIP: return launch_strip<T, BITS>(c.vec, c.sa, gd, lds, st);
             case ITEMS: return launch_items<T, BITS>(c.B, c.vec, c.ia, gd, lds, st);
             case UNITS: return launch_units<T, BITS>(c.nw, c.ua, gd, lds, st);
             case WAVE: return launch_wave<T, BITS>(c.B, c.vec, c.wa, gd, lds, st);
@@ -899,6 +924,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         OneArgs oa{};
         AnyArgs g{};
         UnitsArgs ua{};
+        StripArgs sa{};
         size_t lds = 0;
         uint32_t grid = 0;
         int vec = 1, nt = 64, nw = 1;
@@ -908,6 +934,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         else if (plan_regs(L, D, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
         else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
         else if (plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
+        else if (flat && plan_strip(L, H, W, B, es, xa, &sa, &grid, &lds, &vec)) { kind = STRIP; sa.tab = tab; sa.rg = rg; }
         else if (flat && plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
         else if (!one_shape(L, es, xa) && plan_units(L, D, H, W, B, es, xa, &ua, &grid, &lds, &nw)) { kind = UNITS; ua.tab = tab; ua.rg = rg; }
         else if (flat && plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
@@ -926,7 +953,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         CompLaunch c{};
         c.kind = kind; c.B = B; c.vec = vec; c.nt = nt; c.nw = nw; c.flat = flat;
         c.gx = grid; c.gy = (uint32_t)cnt; c.lds = lds; c.st = st;
-        c.a = a; c.wa = wa; c.ra = ra; c.ia = ia; c.la = la; c.wa2 = wa2; c.pa = pa; c.oa = oa; c.g = g; c.ua = ua;
+        c.sa = sa; c.a = a; c.wa = wa; c.ra = ra; c.ia = ia; c.la = la; c.wa2 = wa2; c.pa = pa; c.oa = oa; c.g = g; c.ua = ua;
         const hipError_t err = bridge_compress(dt, c, b);
         if (err != hipSuccess) return DIVISION_EHIP;
     }
@@ -987,7 +1014,7 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     const char* tn = dt == DIVISION_BF16 ? "bf16_t" : dt == DIVISION_F32_C16 ? "f32c16_t" : "float";
     int n;
     if (direction == 0) {
-        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; OneArgs oa{}; UnitsArgs ua{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
+        TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; OneArgs oa{}; UnitsArgs ua{}; StripArgs sa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (line_first(L, es) && plan_line(L, D, H, B, es, data, &oa, &grid))
             n = snprintf(out, cap, "compress_line<%s, %d>", tn, b);
         else if (plan_regs(L, D, H, W, B, es, data, &ra, &grid, &lds, &nw))
@@ -996,6 +1023,8 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
             n = snprintf(out, cap, "compress_lane<%s, %d>", tn, b);
         else if (plan_line(L, D, H, B, es, data, &oa, &grid))
             n = snprintf(out, cap, "compress_line<%s, %d>", tn, b);
+        else if (flat && plan_strip(L, H, W, B, es, data, &sa, &grid, &lds, &vec))
+            n = snprintf(out, cap, "compress_strip<%s, %d, %d>", tn, b, vec);
         else if (flat && plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_items<%s, %d, %d, %d, %d>", tn, b, B, vec, H == 1 ? 1 : B);
         else if (!one_shape(L, es, data) && plan_units(L, D, H, W, B, es, data, &ua, &grid, &lds, &nw))

@@ -700,6 +700,34 @@ def test_one_row_kernel_matches_oracle(shape, B, b, mode):
     _check_variant(shape, B, b, mode)
 
 
+# planes of width 28 and 14 under B = 8: the strip kernel (a lane per 28 consecutive elements)
+STRIP_CASES = [
+    ((3, 171, 28, 28), 2),              # 513 planes: an odd number, the last round holds one plane
+    ((2, 64, 28, 28), 4),
+    ((1, 33, 28, 28), 8),
+    ((5, 41, 14, 14), 2),               # 205 planes in rounds of 8: the last round holds 5
+    ((2, 100, 14, 14), 4),
+    ((1, 19, 14, 14), 8),
+    ((3, 67, 20, 28), 2),               # ragged last block row (4 of 8 rows), lanes 20..31 of a plane idle
+    ((3, 67, 32, 28), 4),               # every lane slot in use
+    ((3, 67, 3, 28), 2),                # three lanes per plane
+    ((3, 67, 9, 28), 8),
+    ((3, 67, 16, 14), 2),               # every lane slot in use (8 row pairs)
+    ((3, 67, 2, 14), 4),                # one row pair per plane
+    ((3, 67, 10, 14), 2),               # ragged last block row (2 of 8 rows)
+    ((1, 1, 28, 28), 2), ((1, 1, 14, 14), 2),
+    ((9, 600, 14, 14), 2),              # 5400 planes: more than one run of the XCD-aware order and its plain tail
+]
+
+
+@pytest.mark.parametrize("shape,b", STRIP_CASES)
+@pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
+def test_strip_kernel_matches_oracle(shape, b, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    assert pkg.division_kernel_name(0, shape, 8, b, dtype, c16=mode == "c16").startswith("compress_strip<")
+    _check_variant(shape, 8, b, mode)
+
+
 @pytest.mark.parametrize("shape,B,b", ROWS_CASES)
 @pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
 def test_general_block_size_kernel_matches_oracle(shape, B, b, mode):

@@ -153,8 +153,11 @@ DISPATCH = [
     ((64, 256, 56, 56), 8, 2, "compress_regs<float, 2, 8, 1>", "decompress_rowvec<float, 2>"),
     ((64, 64, 112, 112), 8, 2, "compress_regs<float, 2, 8, 4>", "decompress_rowvec<float, 2>"),
     ((2, 3, 224, 224), 8, 2, "compress_regs<float, 2, 8, 16>", "decompress_rowvec<float, 2>"),
-    ((64, 512, 28, 28), 8, 2, "compress_items<float, 2, 8, 4, 8>", "decompress_rowvec<float, 2>"),
-    ((64, 1024, 14, 14), 8, 2, "compress_items<float, 2, 8, 2, 8>", "decompress_table<float, 2>"),
+    ((64, 512, 28, 28), 8, 2, "compress_strip<float, 2, 28>", "decompress_rowvec<float, 2>"),
+    ((64, 1024, 14, 14), 8, 2, "compress_strip<float, 2, 14>", "decompress_table<float, 2>"),
+    ((4, 8, 20, 28), 8, 4, "compress_strip<float, 4, 28>", "decompress_rowvec<float, 4>"),
+    ((4, 8, 28, 28), 4, 2, "compress_items<float, 2, 4, 4, 4>", "decompress_rowvec<float, 2>"),
+    ((4, 8, 15, 14), 8, 2, "compress_items<float, 2, 8, 2, 8>", "decompress_words<float, 2>"),
     ((64, 2048, 7, 7), 8, 2, "compress_lane<float, 2>", "decompress_lane<float, 2>"),
     ((128, 64, 32, 32), 4, 2, "compress_items<float, 2, 4, 4, 4>", "decompress_rowvec<float, 2>"),
     ((64, 256, 56, 56), 12, 2, "compress_regs<float, 2, 0, 1>", "decompress_rowvec<float, 2>"),
