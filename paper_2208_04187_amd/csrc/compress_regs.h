@@ -129,7 +129,8 @@ __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
                     u32x4 o;
                     o.x = __float_as_uint(x[k][0]); o.y = __float_as_uint(x[k][1]);
                     o.z = __float_as_uint(x[k][2]); o.w = __float_as_uint(x[k][3]);
-                    __builtin_amdgcn_raw_buffer_store_b128(o, yrs, tid * 16u, k * NT * 16, 0);
+                    // the whole offset in the vector operand (see store_b128_checked)
+                    store_b128_checked(o, yrs, tid * 16u + (uint32_t)(k * NT * 16), 0);
                 } else {
                     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
                     u32x2 o;

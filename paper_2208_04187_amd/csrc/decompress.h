@@ -164,6 +164,74 @@ __global__ void __launch_bounds__(kThreads) decompress_rowvec(DecArgs a) { decom
 template <typename T, int BITS>
 __global__ void __launch_bounds__(kThreads) decompress_rowvec_3d(DecArgs a) { decompress_rowvec_body<T, BITS, 3>(a); }
 
+// The row-vector case again (W % 4 == 0, B % 4 == 0, 4-byte elements) without staging and without a
+// barrier: a workgroup is ONE wavefront that rebuilds kStreamK * 64 consecutive 16-byte vectors of the
+// map (4 KB for kStreamK = 4), wherever the plane boundaries fall.  Each lane finds the plane, row and
+// block of its vectors, loads their code byte / half-word / word, their plane's (delta, Delta) and their
+// block's H^L straight from the packed buffer (all of its lines are shared by many lanes and rounds, so
+// nearly all of these loads are cache hits), and stores.  All loads of the chunk are issued before the
+// first store.  Short-lived one-wavefront workgroups that write a few KB each are what the memory
+// system takes fastest (a write-only stream: 6.4 - 6.7 TB/s in 4 KB pieces, 5.5 in 32 KB ones), and with
+// no barrier the latency of the packed reads is hidden by the other wavefronts of the CU.
+constexpr int kStreamK = DIVISION_STREAM_K;
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void decompress_stream_body(const DecArgs& a) {
+    static_assert(sizeof(T) == 4, "4-byte elements");
+    constexpr int K = kStreamK;
+    constexpr uint32_t Lq = (1u << BITS) - 1u;
+    constexpr uint32_t CBY = BITS / 2;                                  // code bytes per vector
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
+    const uint32_t lane = threadIdx.x;
+    // first vector of the chunk, counted over the whole map: its plane g0 and its place r0 inside the
+    // plane (uniform; the quotient by a binary64 reciprocal, then put right)
+    const uint64_t v0 = (uint64_t)blockIdx.x * (64u * K);
+    const uint64_t nvec = (uint64_t)a.P * a.q4;
+    uint32_t g0 = (uint32_t)((double)v0 * (1.0 / (double)a.q4));
+    int64_t r0 = (int64_t)(v0 - (uint64_t)g0 * a.q4);
+    if (r0 < 0) { --g0; r0 += a.q4; }
+    if (r0 >= (int64_t)a.q4) { ++g0; r0 -= a.q4; }
+    g0 = __builtin_amdgcn_readfirstlane(g0);
+    const uint32_t t0 = __builtin_amdgcn_readfirstlane((uint32_t)r0);
+
+    uint32_t code[K];
+    float2 dd[K];
+    float lfc[K];
+    const uint8_t* cbase = reinterpret_cast<const uint8_t*>(pt.codes);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t t = t0 + 64u * k + lane;                           // < q4 + 64 K
+        const uint32_t dg = fdiv(t, a.d_q4);
+        const uint32_t fi = t - dg * a.q4;                                // vector inside its plane
+        const uint32_t g = min(g0 + dg, a.P - 1u);                         // vectors past the map re-read its last plane
+        const uint32_t r = fdiv(fi, a.d_w4);
+        const uint32_t c = (fi - r * a.w4) * 4u;
+        const uint32_t blk = lfc_row<ND>(a, r) + fdiv(c, a.d_B);
+        const uint8_t* cp = cbase + (size_t)g * a.WPP * 4u + (size_t)fi * CBY;
+        if constexpr (BITS == 2) code[k] = *cp;
+        else if constexpr (BITS == 4) code[k] = *reinterpret_cast<const uint16_t*>(cp);
+        else code[k] = *reinterpret_cast<const uint32_t*>(cp);
+        dd[k] = meta_load(pt.meta, g, kC16<T>);
+        lfc[k] = lfc_load<T>(pt.lfc, (size_t)g * a.nb + blk, kC16<T>);
+    }
+    T* out = static_cast<T*>(pt.xhat) + v0 * 4u;
+    const uint64_t left = nvec - v0;                                      // vectors from the chunk's start to the map's end
+    const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc(
+        out, 0, (int)(left < 64u * K ? (uint32_t)left * 16u : 64u * K * 16u), 0x00020000);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        u32x4 o;
+        o.x = __float_as_uint(dequant(code[k] & Lq, dd[k].y, dd[k].x, lfc[k]));
+        o.y = __float_as_uint(dequant((code[k] >> BITS) & Lq, dd[k].y, dd[k].x, lfc[k]));
+        o.z = __float_as_uint(dequant((code[k] >> (2 * BITS)) & Lq, dd[k].y, dd[k].x, lfc[k]));
+        o.w = __float_as_uint(dequant((code[k] >> (3 * BITS)) & Lq, dd[k].y, dd[k].x, lfc[k]));
+        store_b128_checked(o, ors, lane * 16u + (uint32_t)(k * 1024), DIVISION_STREAM_STORE_AUX);   // past the map: dropped
+    }
+}
+template <typename T, int BITS>
+__global__ void __launch_bounds__(64) decompress_stream(DecArgs a) { if constexpr (sizeof(T) == 4) decompress_stream_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(64) decompress_stream_3d(DecArgs a) { if constexpr (sizeof(T) == 4) decompress_stream_body<T, BITS, 3>(a); }
+
 // H*W a multiple of 4 and at most 255 blocks per plane: the LFC index of every
 // element of a plane is looked up in a table (one byte per element, four per
 // vector) that the workgroup builds once in LDS, so the streaming loop has no

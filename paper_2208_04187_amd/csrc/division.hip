@@ -101,6 +101,12 @@ constexpr uint32_t kWeyl = 0x9E3779B9u;
 #endif
 constexpr int kLoadAux = DIVISION_LOAD_AUX;
 constexpr int kLoadReuse = 0;
+#ifndef DIVISION_STREAM_K
+#define DIVISION_STREAM_K 4
+#endif
+#ifndef DIVISION_STREAM_STORE_AUX
+#define DIVISION_STREAM_STORE_AUX 2
+#endif
 
 #include "helpers.h"
 #include "compress_tile.h"

@@ -225,6 +225,18 @@ struct TileArgs {
     FastDiv d_ipp, d_ipr, d_wpp;
 };
 
+// A bounds-checked 16-byte buffer store whose offset sits in the vector operand only.  A VALU write to
+// the data registers of a store of more than 8 bytes needs wait states behind the store; the
+// compiler counts them for buffer stores WITHOUT a scalar offset register only.  With the offset
+// split as (lane part in the VGPR, round part in an SGPR) a kernel here stored, now and then, the NEXT
+// vector's first dword for the last four lanes of a row of sixteen: the instruction right behind the
+// store had overwritten the first data register.  Keeping the scalar offset at the constant 0 makes
+// the compiler see the hazard and keep its distance.
+__device__ __forceinline__ void store_b128_checked(u32x4 v, __amdgpu_buffer_rsrc_t rsrc, uint32_t byte_offset, int aux) {
+    if (aux == 2) __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, byte_offset, 0, 2);
+    else __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, byte_offset, 0, 0);
+}
+
 // ------------------------------------------------------------------ synchronisation
 
 // Orders LDS traffic between the lanes of ONE wavefront.  The LDS unit serves

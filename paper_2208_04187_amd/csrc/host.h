@@ -635,7 +635,7 @@ uint64_t dec_planes(const Layout& L, size_t es, uint64_t mult) {
     return G;
 }
 
-// Fills the decompress launch plan; returns 0 (row vectors), 3 (block table), 6 (four consecutive elements
+// Fills the decompress launch plan; returns 7 (row vectors of 4-byte elements, a wavefront per chunk), 0 (row vectors), 3 (block table), 6 (four consecutive elements
 // per lane step, any width), 5 (word by word through LDS), 1 (flat), 4 (lane per plane) or 2 (scalar).
 // Hs = rows of one depth slice, D = depth slices (1 for a 2-D map; the table kernel takes 2-D maps only).
 int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, size_t es, const void* xhat,
@@ -664,6 +664,16 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
     if (W % 4 == 0 && B % 4 == 0 && small_idx && out_vec_aligned) {
         a->q4 = (uint32_t)(L.HW / 4);
         a->w4 = (uint32_t)(W / 4);
+        // 4-byte elements: one wavefront per 64 * kStreamK vectors, no staging
+        const uint64_t chunk = 64ull * kStreamK;
+        const uint64_t nvec = L.P * (L.HW / 4);
+        if (es == 4 && fastdiv_ok(a->q4 + chunk, a->q4) && fastdiv_ok(a->q4, a->w4) && (nvec + chunk - 1) / chunk < (1ull << 31) &&
+            nvec < (1ull << 40)) {
+            a->d_q4 = make_fastdiv(a->q4);
+            a->d_w4 = make_fastdiv(a->w4);
+            *grid = (uint32_t)((nvec + chunk - 1) / chunk);
+            return 7;
+        }
         uint64_t G = dec_planes(L, es, 1);
         while (G > 1 && !fastdiv_ok(G * a->q4 + kThreads, a->q4)) --G;
         if (fastdiv_ok(G * a->q4 + kThreads, a->q4) && fastdiv_ok(a->q4, a->w4) && dec_lds_bytes(L, es, G) <= kDecLdsMax) {
@@ -807,6 +817,11 @@ hipError_t do_decompress(const DecLaunch& c, int b) {
         constexpr int BITS = decltype(bits)::value;
         const int kind = c.kind;
         void (*kern)(DecArgs);
+        if (kind == 7) {
+            kern = c.flat ? decompress_stream<T, BITS> : decompress_stream_3d<T, BITS>;
+            hipLaunchKernelGGL(kern, dim3(c.gx, c.gy), dim3(64), 0, c.st, c.a);
+            return hipGetLastError();
+        }
         if (kind == 6) {
             kern = c.nw == 1 ? decompress_units<T, BITS, 1> : c.nw == 2 ? decompress_units<T, BITS, 2>
                  : c.nw == 4 ? decompress_units<T, BITS, 4> : c.nw == 8 ? decompress_units<T, BITS, 8>
@@ -991,6 +1006,7 @@ int decompress_impl(int count, const void* const* packed, void* const* xhat, siz
         size_t lds = 0;
         if (kind == 4) lds = 4ull * (64ull * L.HW + 4);
         else if (kind == 6) lds = 8ull * ((L.nb + 3) & ~3ull);
+        else if (kind == 7) lds = 0;
         else if (kind == 5) lds = a.out_off + 4ull * ((a.G * L.HW + 3) & ~3ull);
         else if (kind != 2) lds = dec_lds_bytes(L, es, a.G) + (kind == 3 ? 4ull * a.q4 + 16 : 0);
         DecLaunch c{};
@@ -1046,6 +1062,8 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
         const int kind = plan_decompress(L, D, H, W, B, es, data, &a, &grid);
         if (kind == 6)
             n = snprintf(out, cap, "decompress_units<%s, %d, %d>", tn, b, (int)a.G);
+        else if (kind == 7)
+            n = snprintf(out, cap, "decompress_stream%s<%s, %d>", sfx, tn, b);
         else
             n = snprintf(out, cap, "%s%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 3 ? "decompress_table" : kind == 5 ? "decompress_words" : kind == 1 ? "decompress_flat" : kind == 4 ? "decompress_lane" : "decompress_scalar",
                          kind == 4 ? "" : sfx, tn, b);

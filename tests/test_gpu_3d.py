@@ -26,7 +26,8 @@ CASES = [
     ((1, 2, 9, 36, 40), 8, 8),                    # ragged everywhere, 8-bit codes
     ((1, 2, 16, 56, 56), 8, 2),                   # plane beyond LDS: workgroup per plane
     ((1, 3, 20, 30, 34), 12, 4),                  # same, ragged, B = 12
-    ((1, 2, 40, 40, 40), 8, 8),                   # codes of a plane beyond the staged decompress: scalar kernel
+    ((1, 2, 40, 40, 40), 8, 8),                   # codes of a plane beyond the staged decompress: stream kernel (fp32), scalar kernel (bf16)
+    ((1, 2, 41, 41, 41), 8, 8),                   # the same with odd extents: scalar kernel
     ((1, 2, 33, 35, 37), 16, 2),                  # odd extents beyond LDS: the scalar workgroup-per-plane kernel
     ((2, 3, 18, 44, 48), 8, 4),                   # ragged blocks in depth and rows, workgroup-per-plane kernel
     ((1, 2, 24, 40, 64), 16, 2),
@@ -80,11 +81,13 @@ def test_volume_kernels_cover_what_the_cases_claim():
     assert kn(0, (3, 2, 5, 7, 7), 4, 2) == "compress_rows_3d<float, 2>"
     assert kn(0, (1, 2, 24, 40, 64), 16, 2) == "compress_plane_3d<float, 2>"
     assert kn(0, (1, 2, 33, 35, 37), 16, 2) == "compress_any_3d<float, 2>"
-    assert kn(1, (3, 5, 16, 16, 16), 8, 2) == "decompress_rowvec_3d<float, 2>"
+    assert kn(1, (3, 5, 16, 16, 16), 8, 2) == "decompress_stream_3d<float, 2>"
+    assert kn(1, (3, 5, 16, 16, 16), 8, 2, torch.bfloat16) == "decompress_rowvec_3d<bf16_t, 2>"
     assert kn(1, (2, 3, 5, 9, 13), 4, 2) == "decompress_units<float, 2, 1>"
     assert kn(1, (2, 2, 3, 35, 35), 4, 4, torch.bfloat16) == "decompress_units<bf16_t, 4, 2>"
     assert kn(1, (3, 2, 5, 7, 7), 4, 2) == "decompress_words_3d<float, 2>"
-    assert kn(1, (1, 2, 40, 40, 40), 8, 8) == "decompress_scalar_3d<float, 8>"
+    assert kn(1, (1, 2, 40, 40, 40), 8, 8) == "decompress_stream_3d<float, 8>"
+    assert kn(1, (1, 2, 41, 41, 41), 8, 8) == "decompress_scalar_3d<float, 8>"
     assert kn(0, (4, 9, 3, 3, 3), 8, 2) == "compress_lane<float, 2>"
     assert kn(0, (2, 3, 7, 1, 30), 8, 2) == pkg.division_kernel_name(0, (2, 3, 7, 30), 8, 2)
     assert kn(0, (2, 3, 1, 28, 28), 8, 2) == pkg.division_kernel_name(0, (2, 3, 28, 28), 8, 2)

@@ -150,18 +150,18 @@ def test_layout_of_the_bfloat16_cached_mode_matches_oracle():
 # which kernel the host picks for a shape (a host-side decision: no GPU needed to ask)
 DISPATCH = [
     # shape, B, b, compress kernel, decompress kernel (fp32)
-    ((64, 256, 56, 56), 8, 2, "compress_regs<float, 2, 8, 1>", "decompress_rowvec<float, 2>"),
-    ((64, 64, 112, 112), 8, 2, "compress_regs<float, 2, 8, 4>", "decompress_rowvec<float, 2>"),
-    ((2, 3, 224, 224), 8, 2, "compress_regs<float, 2, 8, 16>", "decompress_rowvec<float, 2>"),
-    ((64, 512, 28, 28), 8, 2, "compress_strip<float, 2, 28>", "decompress_rowvec<float, 2>"),
+    ((64, 256, 56, 56), 8, 2, "compress_regs<float, 2, 8, 1>", "decompress_stream<float, 2>"),
+    ((64, 64, 112, 112), 8, 2, "compress_regs<float, 2, 8, 4>", "decompress_stream<float, 2>"),
+    ((2, 3, 224, 224), 8, 2, "compress_regs<float, 2, 8, 16>", "decompress_stream<float, 2>"),
+    ((64, 512, 28, 28), 8, 2, "compress_strip<float, 2, 28>", "decompress_stream<float, 2>"),
     ((64, 1024, 14, 14), 8, 2, "compress_strip<float, 2, 14>", "decompress_table<float, 2>"),
-    ((4, 8, 20, 28), 8, 4, "compress_strip<float, 4, 28>", "decompress_rowvec<float, 4>"),
-    ((4, 8, 28, 28), 4, 2, "compress_items<float, 2, 4, 4, 4>", "decompress_rowvec<float, 2>"),
+    ((4, 8, 20, 28), 8, 4, "compress_strip<float, 4, 28>", "decompress_stream<float, 4>"),
+    ((4, 8, 28, 28), 4, 2, "compress_items<float, 2, 4, 4, 4>", "decompress_stream<float, 2>"),
     ((4, 8, 15, 14), 8, 2, "compress_items<float, 2, 8, 2, 8>", "decompress_words<float, 2>"),
     ((64, 2048, 7, 7), 8, 2, "compress_lane<float, 2>", "decompress_lane<float, 2>"),
-    ((128, 64, 32, 32), 4, 2, "compress_items<float, 2, 4, 4, 4>", "decompress_rowvec<float, 2>"),
-    ((64, 256, 56, 56), 12, 2, "compress_regs<float, 2, 0, 1>", "decompress_rowvec<float, 2>"),
-    ((64, 256, 56, 56), 64, 2, "compress_one<float, 2>", "decompress_rowvec<float, 2>"),
+    ((128, 64, 32, 32), 4, 2, "compress_items<float, 2, 4, 4, 4>", "decompress_stream<float, 2>"),
+    ((64, 256, 56, 56), 12, 2, "compress_regs<float, 2, 0, 1>", "decompress_stream<float, 2>"),
+    ((64, 256, 56, 56), 64, 2, "compress_one<float, 2>", "decompress_stream<float, 2>"),
     ((64, 256, 56, 56), 18, 4, "compress_units<float, 4, 2>", "decompress_table<float, 4>"),
     ((32, 96, 55, 55), 4, 4, "compress_units<float, 4, 2>", "decompress_units<float, 4, 2>"),
     ((8, 8, 27, 27), 8, 2, "compress_units<float, 2, 1>", "decompress_units<float, 2, 1>"),
@@ -169,7 +169,7 @@ DISPATCH = [
     ((8, 8, 13, 13), 8, 2, "compress_wave<float, 2, 8, 1>", "decompress_words<float, 2>"),
     ((4, 4, 147, 147), 8, 2, "compress_units<float, 2, 16>", "decompress_units<float, 2, 16>"),
     ((4, 4, 30, 30), 4, 2, "compress_wave<float, 2, 4, 2>", "decompress_table<float, 2>"),
-    ((2, 2, 1, 768), 8, 4, "compress_line<float, 4>", "decompress_rowvec<float, 4>"),
+    ((2, 2, 1, 768), 8, 4, "compress_line<float, 4>", "decompress_stream<float, 4>"),
     ((5, 33, 14, 14), 12, 4, "compress_rows<float, 4>", "decompress_table<float, 4>"),
     ((1, 1, 300, 300), 18, 2, "compress_any<float, 2>", "decompress_scalar<float, 2>"),
 ]
@@ -184,7 +184,7 @@ def test_kernel_choice_per_shape(shape, B, b, comp, dec):
 def test_kernel_choice_for_3d_maps_and_2_byte_elements():
     import torch
     assert pkg.division_kernel_name_3d(0, (2, 4, 16, 56, 56), 8, 2) == "compress_regs_3d<float, 2, 8, 16>"
-    assert pkg.division_kernel_name_3d(1, (2, 4, 16, 56, 56), 8, 2) == "decompress_rowvec_3d<float, 2>"
+    assert pkg.division_kernel_name_3d(1, (2, 4, 16, 56, 56), 8, 2) == "decompress_stream_3d<float, 2>"
     assert pkg.division_kernel_name(0, (8, 8, 55, 55), 8, 2, torch.bfloat16) == "compress_units<bf16_t, 2, 2>"
     assert pkg.division_kernel_name(1, (8, 8, 55, 55), 8, 2, torch.bfloat16) == "decompress_units<bf16_t, 2, 2>"
     assert pkg.division_kernel_name(0, (8, 8, 56, 56), 8, 2, torch.float32, c16=True) == "compress_regs<f32c16_t, 2, 8, 1>"
