@@ -28,11 +28,29 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# benchmark (each counter scaled by what it reads for a plain 1 GiB copy: x2.000
-# and x1.000), averaged over the kernel's launches in one step of the default
-# workload; profiles/bench_resnet50_set_hbm_traffic.md has the figures.
-MEASURED_TRAFFIC_BYTES = {"decompress_rowvec<float, 2>": 447.8e6}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "bench_resnet50_set_hbm_traffic.md")
+
+
+def recorded_traffic(kernel: str, launches_per_step: int, algorithmic_bytes_per_launch: int):
+    """HBM bytes per launch of `kernel` as the committed rocprofv3 counter summary records them
+    (FETCH_SIZE + WRITE_SIZE, each scaled by what it reads for a plain copy of known size).  A run of this
+    benchmark cannot read the counters itself; the record is used only if it was made for the same kernel,
+    the same number of launches per step and the same algorithmic bytes per launch, otherwise the answer is
+    (None, why)."""
+    try:
+        lines = [ln for ln in open(TRAFFIC_PROFILE) if ln.startswith("bench.py traffic record:")]
+    except OSError:
+        return None, "no traffic profile in profiles/"
+    for ln in lines:
+        f = dict(kv.split("=", 1) for kv in ln[len("bench.py traffic record:"):].split(";") if "=" in kv)
+        f = {k.strip(): v.strip() for k, v in f.items()}
+        if f.get("kernel") != kernel:
+            continue
+        if int(f["launches_per_step"]) != launches_per_step or int(f["algorithmic_bytes_per_launch"]) != algorithmic_bytes_per_launch:
+            return None, "the profile's record for %s is for another launch grouping" % kernel
+        return float(f["traffic_bytes_per_launch"]), "profiles/bench_resnet50_set_hbm_traffic.md (rocprofv3 FETCH_SIZE + WRITE_SIZE of this command)"
+    return None, "the traffic profile has no record for %s" % kernel
+
 
 WORKLOAD_NAMES = {
     0: "single 2x16x32x32 fp32 tensor, B=8 b=2 (configs[0])",
@@ -344,8 +362,8 @@ def main() -> int:
                     help="batch: consecutive same-shape maps share a launch (<= 8 per call); layer: one call per map")
     ap.add_argument("--c16", action="store_true",
                     help="cache H^L, delta and Delta as bfloat16 (the paper's format; fp32 workloads only)")
-    ap.add_argument("--compare-modes", action="store_true",
-                    help="also time the other launch mode (before the reported one) and add its figures to the line")
+    ap.add_argument("--no-compare-modes", dest="compare_modes", action="store_false",
+                    help="do not time the other launch mode (it is timed before the reported one and its figures go into the line)")
     ap.add_argument("--roofline-every", type=int, default=4,
                     help="bracket the dominant kernel's launches with events on every N-th timed step (default 4). "
                          "An event pair is two more packets for the command processor and opens a gap of 5-9 us "
@@ -448,6 +466,8 @@ def main() -> int:
             kname_cache[(d, g)] = pkg.division_kernel_name(d, shapes[i], host[i][1].B, host[i][1].b, dtypes[i], c16=args.c16)
         return kname_cache[(d, g)]
 
+    stream = torch.cuda.current_stream().cuda_stream      # raw handle, fetched once: the per-call lookup costs the host 8 us
+
     def run_step(launches, s: int, timed_group=None, events=None, pool=None):
         for d, g in launches:
             sp = host[g[0]][1]
@@ -461,15 +481,15 @@ def main() -> int:
             if len(g) == 1:
                 i = g[0]
                 if d == 0:
-                    pkg.division_compress(xs[s][i], sp.B, sp.b, seeds[i], packed=packs[s][i], c16=args.c16)
+                    pkg.division_compress(xs[s][i], sp.B, sp.b, seeds[i], packed=packs[s][i], c16=args.c16, stream=stream)
                 else:
-                    pkg.division_decompress(packs[s][i], shapes[i], sp.B, sp.b, dtypes[i], out=outs[s][i], c16=args.c16)
+                    pkg.division_decompress(packs[s][i], shapes[i], sp.B, sp.b, dtypes[i], out=outs[s][i], c16=args.c16, stream=stream)
             elif d == 0:
                 pkg.division_compress_batch([xs[s][i] for i in g], sp.B, sp.b, [seeds[i] for i in g],
-                                            packed=[packs[s][i] for i in g], c16=args.c16)
+                                            packed=[packs[s][i] for i in g], c16=args.c16, stream=stream)
             else:
                 pkg.division_decompress_batch([packs[s][i] for i in g], shapes[g[0]], sp.B, sp.b, dtypes[g[0]],
-                                              out=[outs[s][i] for i in g], c16=args.c16)
+                                              out=[outs[s][i] for i in g], c16=args.c16, stream=stream)
             if rec:
                 e1.record()
                 events.append(((d, g), e0, e1))
@@ -518,6 +538,12 @@ def main() -> int:
     achieved = avg_bytes / (avg_ms * 1e-3) / 1e9
     value = algo_bytes_step / (ms_per_step * 1e-3) / 1e9
 
+    if args.config == 2 and args.batch is None and not args.c16 and args.mode == "batch":
+        n_dom_step = sum(1 for d, g in launch_list(args.mode) if kname(d, g) == dominant)
+        traffic, traffic_src = recorded_traffic(dominant, n_dom_step, round(avg_bytes))
+    else:
+        traffic, traffic_src = None, "counters were profiled for the default workload and launch mode only"
+
     out = {
         "metric": "compress+decompress GB/s of activations and % of HBM peak; compression ratio",
         "value": round(value, 1),
@@ -545,7 +571,7 @@ def main() -> int:
         "kernel_ms_probe_step": {k: round(v, 4) for k, v in sorted(per_kernel.items())},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(dominant) if args.config == 2 and args.batch is None and not args.c16 else None,
+                     "traffic": traffic, "traffic_source": traffic_src,
                      "algorithmic_bytes_per_launch": round(avg_bytes), "avg_launch_ms": round(avg_ms, 5),
                      "launches_timed": len(dom_ms)},
     }
@@ -580,12 +606,13 @@ def main() -> int:
             oracle.decompress(p, tuple(xsub.shape), sp.B, sp.b, dt, threads=1)
             t1c += time.perf_counter() - a0
             frac += 2 * (xsub.numel() * xsub.element_size() + p.size)
-        out["cpu_baseline_single_thread"] = {"value": round(frac / t1c / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        out["cpu_baseline_single_thread"] = {"value": round(frac / t1c / 1e9, 3), "unit": "GB/s", "cores": 1,
+                                             "host_cores": os.cpu_count(), "kind": "oracle",
                                              "sample": f"the first eighth of the samples of every tensor, {t1c:.1f} s wall"}
         out["cpu_baseline"] = {"value": round(algo_bytes_step / tc / 1e9, 3), "unit": "GB/s", "cores": threads,
-                               "kind": "oracle",
+                               "host_cores": os.cpu_count(), "kind": "oracle",
                                "sample": f"one full step ({len(host)} tensors, {elements} elements) through the C oracle, "
-                                         f"{threads} OpenMP threads over planes, {tc:.1f} s wall"}
+                                         f"{threads} OpenMP threads over planes on a host that reports {os.cpu_count()} cores, {tc:.1f} s wall"}
     print(json.dumps(out))
     return 0
 
