@@ -527,8 +527,31 @@ def main() -> int:
         t1 = time.perf_counter()
         return (t1 - t0) * 1e3 / args.steps, per_kernel, dominant, events, len(launches)
 
+    def timed_maps():
+        """The whole step as two library calls (division_compress_maps, division_decompress_maps): what the
+        saved-tensor hook issues when a whole forward pass fits one group.  Same protocol, no events."""
+        order = list(range(len(host)))
+        rev = order[::-1]
+        Bs, bs = [host[i][1].B for i in order], [host[i][1].b for i in order]
+
+        def step(s):
+            pkg.division_compress_maps([xs[s][i] for i in order], Bs, bs, [seeds[i] for i in order],
+                                       packed=[packs[s][i] for i in order], c16=args.c16, stream=stream)
+            pkg.division_decompress_maps([packs[s][i] for i in rev], [shapes[i] for i in rev], [Bs[i] for i in rev],
+                                         [bs[i] for i in rev], [dtypes[i] for i in rev], out=[outs[s][i] for i in rev],
+                                         c16=args.c16, stream=stream)
+        for w in range(8 + args.warmup):
+            step(w % nsets)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            step(k % nsets)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
     other_mode = "layer" if args.mode == "batch" else "batch"
     other_ms = timed(other_mode)[0] if args.compare_modes else None
+    maps_ms = timed_maps() if args.compare_modes else None
     ms_per_step, per_kernel, dominant, events, n_launches = timed(args.mode)
 
     dom_ms = [e0.elapsed_time(e1) for _, e0, e1 in events]
@@ -568,6 +591,8 @@ def main() -> int:
         "compression_ratio": round(input_bytes / packed_bytes, 3),
         f"{other_mode}_mode_GB_s": round(algo_bytes_step / (other_ms * 1e-3) / 1e9, 1) if other_ms else None,
         f"{other_mode}_mode_ms_per_step": round(other_ms, 4) if other_ms else None,
+        "maps_mode_GB_s": round(algo_bytes_step / (maps_ms * 1e-3) / 1e9, 1) if maps_ms else None,
+        "maps_mode_ms_per_step": round(maps_ms, 4) if maps_ms else None,
         "kernel_ms_probe_step": {k: round(v, 4) for k, v in sorted(per_kernel.items())},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),

@@ -454,47 +454,6 @@ def test_descriptor_array_calls_serve_a_mixed_step():
         pkg.division_compress_maps(xs[:2], [8, 8], [2, 3], [1, 2])
 
 
-# ---------------------------------------------------------------- Algorithm 1 through autograd
-
-@pytest.mark.parametrize("c16", [False, True])
-def test_saved_tensor_hook_caches_the_map_and_rebuilds_it_in_backward(c16):
-    shape, B, b, seed = (4, 6, 28, 28), 8, 2, 91
-    odt = oracle.F32_C16 if c16 else oracle.F32
-    x = _relu_normal(shape, 7300).to("cuda:0")
-    w = torch.nn.Parameter(torch.linspace(0.5, 1.5, x.numel(), device="cuda:0").view(shape))
-    h = x.clone().requires_grad_(True)
-    hooks = pkg.division_saved_tensors(B, b, seed, c16=c16)
-    with hooks:
-        y = (h * 1.0) * w            # autograd saves the intermediate map (h * 1.0) for w's gradient
-        loss = y.sum()
-    loss.backward()
-    assert hooks.cached_maps == 1
-    assert hooks.cached_bytes == pkg.division_packed_bytes(*shape, B, b, c16=c16)
-    # dL/dw is the reconstructed map itself, bit for bit what the oracle rebuilds from the oracle's tuple
-    ref = oracle.decompress(oracle.compress(x.cpu().numpy(), B, b, seed, odt), shape, B, b, odt)
-    assert np.array_equal(w.grad.cpu().numpy(), ref)
-    # dL/dh needs only w, which is a parameter and is never cached
-    assert torch.equal(h.grad, w.detach())
-
-
-@pytest.mark.parametrize("shape", [(3, 8, 200), (2, 4, 6, 20, 12)])
-def test_saved_tensor_hook_takes_1d_and_3d_maps(shape):
-    B, b, seed = 8, 4, 17
-    g = torch.Generator().manual_seed(len(shape))
-    x = torch.randn(shape, generator=g).to("cuda:0")
-    w = torch.nn.Parameter(torch.full(shape, 2.0, device="cuda:0"))
-    h = x.clone().requires_grad_(True)
-    hooks = pkg.division_saved_tensors(B, b, seed)
-    with hooks:
-        loss = ((h * 1.0) * w).sum()
-    loss.backward()
-    assert hooks.cached_maps == 1
-    oshape = shape if len(shape) == 5 else (shape[0], shape[1], 1, shape[2])
-    xh = x.cpu().numpy().reshape(oshape)
-    ref = oracle.decompress(oracle.compress(xh, B, b, seed), oshape, B, b).reshape(shape)
-    assert np.array_equal(w.grad.cpu().numpy(), ref)
-
-
 # ---------------------------------------------------------------- HIP graph capture
 
 def test_compress_and_decompress_replay_from_a_hip_graph():
