@@ -260,16 +260,18 @@ __device__ __forceinline__ void lds_barrier() {
 
 // ------------------------------------------------------------------ cross-lane helpers (DPP)
 
-// value of another lane of the same 16-lane row; all lanes must be active
+// value of another lane of the same 16-lane row; all lanes must be active.  bound_ctrl is set: the
+// permutations used here never read outside the row, and with it the compiler need not initialise
+// the destination (two fewer instructions per 64-bit exchange)
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
 }
 template <int CTRL>
 __device__ __forceinline__ double dpp_f64(double v) {
     const uint64_t u = __double_as_longlong(v);
-    const uint32_t lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, CTRL, 0xf, 0xf, false);
-    const uint32_t hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), CTRL, 0xf, 0xf, false);
+    const uint32_t lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, CTRL, 0xf, 0xf, true);
+    const uint32_t hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), CTRL, 0xf, 0xf, true);
     return __longlong_as_double(((uint64_t)hi << 32) | lo);
 }
 constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
