@@ -7,6 +7,8 @@ struct StripArgs {
     Regions rg;
     uint32_t P, H, HW, WPP, nb;
     uint32_t nrounds;    // ceil(P / planes per round)
+    void* y;             // relu_compress_strip: the activation's output map and its 1-bit mask (one map per launch);
+    uint32_t* mask;      // a round's elements are a multiple of 32 then: its mask bits are whole words
 };
 
 // Planes of width 28 or 14 under B = 8 (the 28 x 28 and 14 x 14 maps of a ResNet): a lane owns a
@@ -23,8 +25,13 @@ struct StripArgs {
 // strip out of LDS (a stride of 28 words: eight lanes cover the banks once).  The codes of a unit
 // go back to LDS as one byte / half-word / word and leave as whole coalesced words.
 // One round per workgroup of one wavefront.
-template <typename T, int BITS, int W>
-__global__ void __launch_bounds__(64) compress_strip(StripArgs a) {
+//
+// RELU: x is the input of a Relu operator (Appendix, Relu listing) whose output y is the map to
+// cache.  The operator is applied to the round as it arrives, in the coalesced order of the loads:
+// y leaves from the same registers (16-byte stores), the mask bits of a lane's unit are merged
+// over eight adjacent lanes (DPP OR) and leave as whole words; the codec then runs on y.
+template <typename T, int BITS, int W, bool RELU>
+__device__ __forceinline__ void compress_strip_body(const StripArgs& a) {
     static_assert(W == 28 || W == 14, "strip widths");
     constexpr int E = 28;                       // elements per lane
     constexpr int S = W == 28 ? 32 : 8;         // lane slots per plane
@@ -57,6 +64,43 @@ __global__ void __launch_bounds__(64) compress_strip(StripArgs a) {
                 const u32x2 h = __builtin_amdgcn_raw_buffer_load_b64(rsrc, lane * 8u, k * 512, kLoadAux);
                 q[k] = u32x4{h.x << 16, h.x & 0xffff0000u, h.y << 16, h.y & 0xffff0000u};
             }
+        }
+    }
+    if constexpr (RELU) {
+        T* ydst = static_cast<T*>(a.y) + (size_t)p0 * a.HW;
+        const __amdgpu_buffer_rsrc_t yrs =
+            __builtin_amdgcn_make_buffer_rsrc(ydst, 0, (int)(Gc * a.HW * sizeof(T)), 0x00020000);
+        // G * HW is a multiple of 32, so the round's mask starts at a word; a last, shorter round
+        // ends the mask, whose final word has zero pad bits (elements past the round were read as zero)
+        const uint32_t mwords = (Gc * a.HW + 31u) / 32u;
+        const __amdgpu_buffer_rsrc_t mrs =
+            __builtin_amdgcn_make_buffer_rsrc(a.mask + (size_t)round * (G * a.HW / 32u), 0, (int)(mwords * 4u), 0x00020000);
+#pragma unroll
+        for (int k = 0; k < 7; ++k) {
+            uint32_t nib = 0;
+            uint32_t v[4] = {q[k].x, q[k].y, q[k].z, q[k].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool pos = __uint_as_float(v[e]) > 0.0f;
+                nib |= (pos ? 1u : 0u) << e;
+                v[e] = pos ? v[e] : 0u;
+            }
+            q[k] = u32x4{v[0], v[1], v[2], v[3]};
+            // stores past the round are dropped by the buffer bound
+            if constexpr (sizeof(T) == 4) {
+                store_b128_checked(q[k], yrs, lane * 16u + (uint32_t)(k * 1024), 0);
+            } else {
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                u32x2 o;
+                o.x = (v[0] >> 16) | (v[1] & 0xffff0000u);
+                o.y = (v[2] >> 16) | (v[3] & 0xffff0000u);
+                __builtin_amdgcn_raw_buffer_store_b64(o, yrs, lane * 8u, k * 512, 0);
+            }
+            uint32_t w = nib << (4u * (lane & 7u));
+            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppXor1, 0xf, 0xf, false);
+            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppXor2, 0xf, 0xf, false);
+            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppHalfMirror, 0xf, 0xf, false);
+            if ((lane & 7u) == 0) __builtin_amdgcn_raw_buffer_store_b32(w, mrs, (lane >> 3) * 4u, k * 32, 0);
         }
     }
     // the lane's place: plane g of the round, strip sl of the plane
@@ -155,3 +199,8 @@ __global__ void __launch_bounds__(64) compress_strip(StripArgs a) {
         for (uint32_t w = lane; w < nwords; w += 64) dst[w] = cw[w];
     }
 }
+
+template <typename T, int BITS, int W>
+__global__ void __launch_bounds__(64) compress_strip(StripArgs a) { compress_strip_body<T, BITS, W, false>(a); }
+template <typename T, int BITS, int W>
+__global__ void __launch_bounds__(64) relu_compress_strip(StripArgs a) { compress_strip_body<T, BITS, W, true>(a); }

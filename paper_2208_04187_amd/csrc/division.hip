@@ -21,7 +21,8 @@
 //   compress_lane    one-block planes with an odd element count (7x7): a lane per plane
 //   compress_strip   28 x 28 and 14 x 14 planes (widths 28 and 14, up to 32 resp. 16 rows) under B = 8: a lane per strip
 //                    of 28 consecutive elements (one or two rows), the round read with coalesced loads and
-//                    handed out through LDS, block sums and extremes by DPP
+//                    handed out through LDS, block sums and extremes by DPP (relu_compress_strip: the same
+//                    with a Relu applied to the round as its loads arrive)
 //   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8: a lane per
 //                    pooling item, loaded straight from global memory, DPP reductions (relu_compress_items:
 //                    the same with a Relu applied to the rows as they arrive)
@@ -242,10 +243,25 @@ int division_relu_compress(const void* x, int64_t N, int64_t C, int64_t H, int64
         const hipError_t err = bridge_relu(dt, c, b);
         return err == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
     }
-    // fused too: the small planes of the items kernel (28 x 28, 14 x 14, the CIFAR shapes)
-    ItemsArgs ia{};
+    // fused too: the 28- and 14-wide planes of the strip kernel
+    StripArgs sa{};
     int vec = 1;
     const int Bc = covering_block(L, 1, H, W, B);
+    if (plan_relu_strip(L, H, W, Bc, es, both, &sa, &grid, &lds, &vec)) {
+        sa.tab.x[0] = x;
+        sa.tab.pk[0] = packed;
+        sa.tab.seed_a[0] = mix32((uint32_t)(seed & 0xffffffffu) ^ 0x243F6A88u);
+        sa.tab.seed_c[0] = mix32((uint32_t)(seed >> 32) ^ 0x85A308D3u);
+        sa.rg = make_regions(L);
+        sa.y = y;
+        sa.mask = static_cast<uint32_t*>(mask);
+        CompLaunch c{};
+        c.kind = STRIP; c.B = Bc; c.vec = vec; c.gx = grid; c.gy = 1; c.lds = lds; c.st = st; c.sa = sa;
+        const hipError_t err = bridge_relu(dt, c, b);
+        return err == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
+    }
+    // and the other small planes of the items kernel (the CIFAR shapes)
+    ItemsArgs ia{};
     if ((Bc == 4 || Bc == 8) && plan_relu_items(L, H, W, Bc, es, both, &ia, &grid, &lds, &vec)) {
         ia.tab.x[0] = x;
         ia.tab.pk[0] = packed;
@@ -276,9 +292,11 @@ int division_relu_compress_fused(int64_t N, int64_t C, int64_t H, int64_t W, div
     const size_t es = dt == DIVISION_BF16 ? 2 : 4;
     const void* aligned = reinterpret_cast<const void*>((uintptr_t)16);
     if (L.HW % 32 == 0 && (B == 4 || B == 8) && plan_regs(L, 1, H, W, B, es, aligned, &ra, &grid, &lds, &nw) && nw <= 4) return 1;
-    ItemsArgs ia{};
+    StripArgs sa{};
     int vec = 1;
     const int Bc = covering_block(L, 1, H, W, B);
+    if (plan_relu_strip(L, H, W, Bc, es, aligned, &sa, &grid, &lds, &vec)) return 1;
+    ItemsArgs ia{};
     return (Bc == 4 || Bc == 8) && plan_relu_items(L, H, W, Bc, es, aligned, &ia, &grid, &lds, &vec);
 }
 

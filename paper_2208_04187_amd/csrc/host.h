@@ -320,6 +320,21 @@ hipError_t launch_strip(int width, const StripArgs& a, dim3 grid, size_t lds, hi
     return hipGetLastError();
 }
 
+// The Relu + compress instance of the strip kernel; a round's mask bits must be whole words.
+bool plan_relu_strip(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* xy,
+                     StripArgs* a, uint32_t* grid, size_t* lds, int* width) {
+    if (!plan_strip(L, H, W, B, es, xy, a, grid, lds, width)) return false;
+    const uint64_t G = W == 28 ? 2 : 8;
+    return (G * L.HW) % 32 == 0;
+}
+
+template <typename T, int BITS>
+hipError_t launch_relu_strip(int width, const StripArgs& a, dim3 grid, size_t lds, hipStream_t st) {
+    void (*kern)(StripArgs) = width == 28 ? relu_compress_strip<T, BITS, 28> : relu_compress_strip<T, BITS, 14>;
+    hipLaunchKernelGGL(kern, grid, dim3(64), lds, st, a);
+    return hipGetLastError();
+}
+
 template <typename T, int BITS>
 hipError_t launch_items(int B, int vec, const ItemsArgs& a, dim3 grid, size_t lds, hipStream_t st) {
     void (*kern)(ItemsArgs);
@@ -844,13 +859,14 @@ hipError_t do_decompress(const DecLaunch& c, int b) {
     });
 }
 
-// the Relu + compress kernels: the register kernel's planes (c.ra carries y and mask) or, c.kind == ITEMS,
-// the items kernel's (c.ia); one map per launch
+// the Relu + compress kernels: the register kernel's planes (c.ra carries y and mask), c.kind == STRIP the
+// strip kernel's (c.sa) or, c.kind == ITEMS, the items kernel's (c.ia); one map per launch
 template <typename T>
 hipError_t do_relu(const CompLaunch& c, int b) {
     return with_bits(b, [&](auto bits) -> hipError_t {
         constexpr int BITS = decltype(bits)::value;
         if (c.kind == ITEMS) return launch_relu_items<T, BITS>(c.B, c.vec, c.ia, dim3(c.gx, 1), c.lds, c.st);
+        if (c.kind == STRIP) return launch_relu_strip<T, BITS>(c.vec, c.sa, dim3(c.gx, 1), c.lds, c.st);
         void (*kern)(RegsArgs);
         if (c.nw == 1) kern = c.B == 8 ? relu_compress_regs<T, BITS, 8, 1> : relu_compress_regs<T, BITS, 4, 1>;
         else kern = c.B == 8 ? relu_compress_regs<T, BITS, 8, 4> : relu_compress_regs<T, BITS, 4, 4>;

@@ -136,9 +136,13 @@ def test_maxpool_matches_oracle(shape, k, dtype):
     ((2, 3, 56, 56), 12, 2, False),      # block size outside the fused instances
     ((5, 9, 7, 7), 8, 4, False),         # lane-per-plane kernel -> two kernels
     ((2, 3, 30, 30), 4, 2, False),       # more than 64 pooling items per plane -> two kernels
-    ((4, 7, 28, 28), 8, 2, True),        # small planes: the items kernel, 784 mask bits per plane, two rounds per workgroup
-    ((5, 9, 14, 14), 8, 2, True),        # four planes per round (784 bits), 45 planes: the last round holds one
-    ((130, 3, 14, 14), 8, 4, True),      # 98 rounds
+    ((4, 7, 28, 28), 8, 2, True),        # strip kernel: two planes (1568 mask bits) per round
+    ((3, 7, 28, 28), 8, 8, True),        # 21 planes: the last round holds one, its mask ends in half a word
+    ((5, 9, 14, 14), 8, 2, True),        # eight planes per round, 45 planes: the last round holds five
+    ((130, 3, 14, 14), 8, 4, True),      # 49 rounds
+    ((3, 5, 12, 28), 8, 4, True),        # 28-wide, 12 rows: 672 bits per round
+    ((3, 5, 30, 28), 8, 2, True),        # 28-wide, 30 rows: rounds are not whole mask words -> the items kernel
+    ((7, 3, 6, 14), 8, 2, True),         # 14-wide, 6 rows, 21 planes
     ((6, 5, 32, 32), 4, 2, True),        # CIFAR shapes: whole mask words per plane
     ((3, 7, 16, 16), 4, 8, True),
     ((5, 3, 8, 8), 4, 2, True),
