@@ -49,7 +49,8 @@ def test_relu_forward_and_backward_match_oracle(n, dtype):
     assert _same_bits(gin, oracle.mask_backward(m_ref, gh, dt))
 
 
-@pytest.mark.parametrize("p", [0.0, 0.1, 0.5, 0.9, 1.0])
+# the last two: p * 65536 + 1/2 is 2^-25 below 1 (T = 0: nothing dropped, also where r == 0) and exactly 1 (T = 1)
+@pytest.mark.parametrize("p", [0.0, 0.1, 0.5, 0.9, 1.0, (0.5 - 2.0 ** -25) / 65536, 0.5 / 65536])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_dropout_forward_matches_oracle(p, dtype):
     for n, seed in ((1, 1), (77, 2), (4097, 0xFEDCBA9876543210), ((1 << 19) + 3, 4)):

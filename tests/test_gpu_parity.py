@@ -399,6 +399,44 @@ def test_block_mean_on_rounding_midpoints():
     assert st["exact"]
 
 
+@pytest.mark.parametrize("shape", [(2, 3, 112, 112), (3, 5, 56, 56), (5, 7, 28, 28), (9, 7, 14, 14), (11, 13, 7, 7),
+                                   (2, 3, 24, 40), (2, 2, 55, 55), (2, 3, 64, 64), (1, 2, 224, 224)])
+def test_codes_on_exact_ties_of_the_stochastic_rounding(shape):
+    # maps built so that t + u is exactly an integer, one step of u below it or 2^-25 below it for the random
+    # bits the element really gets (tests/test_oracle_rounding_pins.py derives the expected codes by hand)
+    from tests.test_oracle_rounding_pins import tie_map
+    seed = 0xBEEF
+    xh, expect = tie_map(shape, seed)
+    x = torch.from_numpy(xh)
+    st = check_against_oracle(x, 8, 2, seed=seed, require_exact=True)
+    assert st["exact"]
+    gp, _ = gpu_roundtrip(x, 8, 2, seed)
+    s = oracle.split_packed(gp, shape, 8, 2, oracle.F32)
+    q = oracle.unpack_codes(s["codes"], shape[2] * shape[3], 2)
+    for pl, e in enumerate(expect):
+        for i, c in e.items():
+            assert int(q[pl, i]) == c, (pl, i)
+
+
+def test_bfloat16_map_is_rebuilt_with_round_to_nearest_even():
+    # hand-made packed buffers: H^L = 1, delta = 0, Delta = 2^-9, 8-bit codes 0..255 over 56 x 56 elements, so that
+    # xhat = 1 + code * 2^-9 lands on, just below and just above halfway between neighbouring bfloat16 values
+    shape, B, b = (2, 3, 56, 56), 64, 8
+    p = np.zeros(oracle.packed_bytes(*shape, B, b, oracle.BF16), dtype=np.uint8)
+    s = oracle.split_packed(p, shape, B, b, oracle.BF16)
+    codes = (np.arange(56 * 56, dtype=np.uint32) * 7 + 3) % 256
+    s["codes"][:] = (codes.reshape(-1, 4) << (8 * np.arange(4, dtype=np.uint32))).sum(1).astype(np.uint32)[None, :]
+    s["meta"][:, 0] = 0.0
+    s["meta"][:, 1] = 2.0 ** -9
+    s["lfc"][:] = 0x3F80
+    want = torch.tensor(1.0 + codes.astype(np.float64) * 2.0 ** -9, dtype=torch.float32).to(torch.bfloat16)
+    y = pkg.division_decompress(torch.from_numpy(p).to("cuda:0"), shape, B, b, torch.bfloat16)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().view(torch.int16).numpy().reshape(6, -1), oracle.decompress(p, shape, B, b, oracle.BF16).view(np.int16).reshape(6, -1))
+    for pl in range(6):
+        assert torch.equal(y.cpu().view(torch.int16).reshape(6, -1)[pl], want.view(torch.int16))
+
+
 # block sizes and ragged edges that give blocks of 98, 196, 198 or 150 elements: counts whose binary64 reciprocal, times the
 # sum, lands beside an exact tie instead of on it
 @pytest.mark.parametrize("shape,B", [((4, 6, 56, 56), 14), ((4, 6, 28, 28), 14), ((4, 6, 14, 14), 16), ((4, 6, 14, 14), 64),

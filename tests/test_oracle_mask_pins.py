@@ -82,6 +82,11 @@ def test_dropout_threshold_closed_form():
     for p in np.linspace(0, 1, 97):
         p32 = float(np.float32(p))
         assert oracle.dropout_threshold(p32) == int(Fraction(p32) * 65536 + Fraction(1, 2))   # exact rational floor
+    # p * 65536 + 1/2 a hair below an integer: it must not be rounded up on the way (a binary32 sum would be)
+    for eps in (2.0 ** -25, 2.0 ** -24):
+        p32 = float(np.float32((0.5 - eps) / 65536))
+        assert Fraction(p32) * 65536 + Fraction(1, 2) < 1
+        assert oracle.dropout_threshold(p32) == 0, eps
 
 
 @pytest.mark.parametrize("p", [0.0, 0.1, 0.5, 0.9, 1.0])
