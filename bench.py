@@ -287,6 +287,10 @@ VARIANTS = [
     ("block size 64", (64, 512, 28, 28), 64, 2), ("block size 64", (64, 1024, 14, 14), 64, 2),
     ("block size 12", (64, 512, 28, 28), 12, 2), ("block size 18", (64, 512, 28, 28), 18, 2),
     ("block size 12", (64, 1024, 14, 14), 12, 2),
+    # the sweep of Sec. 5 runs on ResNet-18 / CIFAR-10: these are its maps
+    ("block size 12, CIFAR", (256, 64, 32, 32), 12, 2), ("block size 18, CIFAR", (256, 64, 32, 32), 18, 2),
+    ("block size 12, CIFAR", (256, 128, 16, 16), 12, 2), ("block size 18, CIFAR", (256, 128, 16, 16), 18, 2),
+    ("block size 12, CIFAR", (256, 256, 8, 8), 12, 2),
     ("8-bit codes", (64, 256, 56, 56), 8, 8), ("4-bit codes", (64, 256, 56, 56), 8, 4),
     ("1-D map", (256, 128, 1, 768), 8, 4), ("1-D map", (64, 384, 1, 3136), 8, 4), ("1-D map", (256, 768, 1, 196), 16, 2), ("1-D map", (64, 196, 1, 3072), 64, 2),
     ("3-D map", (32, 64, 16, 56, 56), 8, 2), ("3-D map", (32, 128, 8, 28, 28), 8, 2), ("3-D map", (32, 256, 4, 14, 14), 8, 2),
