@@ -1,6 +1,6 @@
 // Part of division.hip (included inside its unnamed namespace, in this order): compress_strip.
 
-// ------------------------------------------------------------------ compress, a strip of 28 elements per lane
+// ------------------------------------------------------------------ compress, a strip of 28 or 32 elements per lane
 
 struct StripArgs {
     CompTab tab;
@@ -11,37 +11,54 @@ struct StripArgs {
     uint32_t* mask;      // a round's elements are a multiple of 32 then: its mask bits are whole words
 };
 
-// Planes of width 28 or 14 under B = 8 (the 28 x 28 and 14 x 14 maps of a ResNet): a lane owns a
-// strip of 28 consecutive elements of its plane, i.e. one row of a 28-wide map or two rows of a
-// 14-wide one, seven 16-byte units either way, and keeps it in registers from the pooling to the
-// codes.  The lanes of a plane sit side by side (32 slots for up to 32 rows of width 28, 8 slots
-// for up to 16 rows of width 14; 2 resp. 8 planes per wavefront), the lanes of a block row are an
-// aligned group of 8 resp. 4 lanes, so that the block sums (binary64) and the plane's extremes are
-// DPP reductions and every lane ends up with its own blocks' H^L and its plane's scale: no
-// per-block pass, no lookup.
+// Geometry of the strip kernel for planes of width W under block size B (both compile-time).
+template <int W, int B>
+struct StripGeom {
+    static_assert(W == 28 || W == 14 || W == 32 || W == 16, "strip widths");
+    static constexpr int E = (W == 28 || W == 14) ? 28 : 32;   // elements per lane: seven or eight 16-byte units
+    static constexpr int RPL = E / W;                           // rows per lane (1 or 2)
+    static constexpr int S = 32 / (RPL * RPL);                  // lane slots per plane: 32 rows, or 8 x 2 rows
+    static constexpr int G = 64 / S;                            // planes per round
+    static constexpr int NSEG = (W + B - 1) / B;                // blocks per block row = columns of the pooled map
+    static constexpr int LBR = B / RPL;                         // lanes per block row
+    static constexpr bool kDpp = LBR == 2 || LBR == 4 || LBR == 8;   // the lanes of a block row are an aligned DPP group
+    static_assert(B % RPL == 0, "a lane's rows lie in one block row");
+};
+
+// Small planes of a fixed width (28 x 28 and 14 x 14 of a ResNet on ImageNet, 32 x 32 and 16 x 16 on
+// CIFAR) under a fixed block size (8, and the 12, 16 and 18 of the block-size sweep of Sec. 5): a
+// lane owns a strip of 28 or 32 consecutive elements of its plane, i.e. one row of a 28- or 32-wide
+// map or two rows of a 14- or 16-wide one, seven or eight 16-byte units, and keeps it in registers
+// from the pooling to the codes.  Which block each element of the strip belongs to is known at
+// compile time.  The lanes of a plane sit side by side (32 slots for up to 32 rows, 8 slots for up
+// to 16 rows; 2 resp. 8 planes per wavefront).  Block sums (binary64): when the lanes of a block
+// row are an aligned group of 4 or 8 (B = 8) they are DPP reductions and every lane ends up with
+// its own blocks' H^L; for the other block sizes a lane parks its strip's share of each block in
+// LDS, a lane per block adds the shares of the block's rows in row order, and the lanes read the
+// H^L values back.  The plane's extremes are DPP reductions either way: no per-element lookup.
 //
 // Memory side: the round (all its planes are contiguous) is read with coalesced 16-byte loads that
 // are issued before anything else and land in LDS in the map's own order; each lane then takes its
-// strip out of LDS (a stride of 28 words: eight lanes cover the banks once).  The codes of a unit
-// go back to LDS as one byte / half-word / word and leave as whole coalesced words.
+// strip out of LDS (a stride of 28 or 32 words).  The codes of a unit go back to LDS as one byte /
+// half-word / word and leave as whole coalesced words.
 // One round per workgroup of one wavefront.
 //
 // RELU: x is the input of a Relu operator (Appendix, Relu listing) whose output y is the map to
 // cache.  The operator is applied to the round as it arrives, in the coalesced order of the loads:
 // y leaves from the same registers (16-byte stores), the mask bits of a lane's unit are merged
 // over eight adjacent lanes (DPP OR) and leave as whole words; the codec then runs on y.
-template <typename T, int BITS, int W, bool RELU>
+template <typename T, int BITS, int W, int B, bool RELU>
 __device__ __forceinline__ void compress_strip_body(const StripArgs& a) {
-    static_assert(W == 28 || W == 14, "strip widths");
-    constexpr int E = 28;                       // elements per lane
-    constexpr int S = W == 28 ? 32 : 8;         // lane slots per plane
-    constexpr int G = 64 / S;                   // planes per round
-    constexpr int LB = W == 28 ? 8 : 4;         // lanes per block row (8 rows)
-    constexpr int NSEG = (W + 7) / 8;           // blocks per block row = columns of the pooled map
+    using Geo = StripGeom<W, B>;
+    constexpr int E = Geo::E, S = Geo::S, G = Geo::G, NSEG = Geo::NSEG, LBR = Geo::LBR, RPL = Geo::RPL;
+    constexpr int UPL = E / 4;                  // units per lane
     constexpr int CB = BITS / 2;                // code bytes per 4-element unit
     constexpr float Lf = float((1 << BITS) - 1);
     extern __shared__ float4 smem4[];
-    float* xs = reinterpret_cast<float*>(smem4);                     // [G * HW] the round (at most 7 x 64 units), later its code words
+    float* xs = reinterpret_cast<float*>(smem4);                     // [UPL * 64 units] the round, later its code words
+    double* part = reinterpret_cast<double*>(xs + UPL * 64 * 4);      // [64 * NSEG] a strip's share of each block of its block row
+    float* lfcs = reinterpret_cast<float*>(part + 64 * NSEG);        // [G * nb <= 64] H^L of the round
+    (void)part; (void)lfcs; (void)RPL;
 
     const uint32_t lane = threadIdx.x;
     const CompPtrs pt = comp_ptrs(a.tab, a.rg, lane);
@@ -50,13 +67,13 @@ __device__ __forceinline__ void compress_strip_body(const StripArgs& a) {
     const uint32_t Gc = min((uint32_t)G, a.P - p0);
 
     // ---- the round's loads first: coalesced, bounds-checked (units past the round read as zero)
-    u32x4 q[7];
+    u32x4 q[UPL];
     {
         const T* src = static_cast<const T*>(pt.x) + (size_t)p0 * a.HW;
         const __amdgpu_buffer_rsrc_t rsrc =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(Gc * a.HW * sizeof(T)), 0x00020000);
 #pragma unroll
-        for (int k = 0; k < 7; ++k) {
+        for (int k = 0; k < UPL; ++k) {
             if constexpr (sizeof(T) == 4) {
                 q[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane * 16u, k * 1024, kLoadAux);
             } else {
@@ -76,7 +93,7 @@ __device__ __forceinline__ void compress_strip_body(const StripArgs& a) {
         const __amdgpu_buffer_rsrc_t mrs =
             __builtin_amdgcn_make_buffer_rsrc(a.mask + (size_t)round * (G * a.HW / 32u), 0, (int)(mwords * 4u), 0x00020000);
 #pragma unroll
-        for (int k = 0; k < 7; ++k) {
+        for (int k = 0; k < UPL; ++k) {
             uint32_t nib = 0;
             uint32_t v[4] = {q[k].x, q[k].y, q[k].z, q[k].w};
 #pragma unroll
@@ -107,15 +124,15 @@ __device__ __forceinline__ void compress_strip_body(const StripArgs& a) {
     const uint32_t g = lane / S, sl = lane % S;
     const bool live = g < Gc;
     const bool valid = live && sl * E < a.HW;
-    const uint32_t bi = sl / LB;                                       // block row of the strip
-    const uint32_t rows = min(8u, a.H - min(a.H, bi * 8u));            // rows of that block row that exist
+    const uint32_t bi = sl / LBR;                                      // block row of the strip
+    const uint32_t rows = min((uint32_t)B, a.H - min(a.H, bi * (uint32_t)B));   // rows of that block row that exist
     const uint32_t p = p0 + g;
     const uint32_t k1 = mix32(p ^ pt.seed_a);
     const uint32_t k2 = mix32(k1 + pt.seed_c);
     const uint32_t rscale = 1u << (16 - BITS);
     const uint32_t xv = G * a.HW / 4u;                                // units of a whole round
 #pragma unroll
-    for (int k = 0; k < 7; ++k)
+    for (int k = 0; k < UPL; ++k)
         if (lane + 64u * k < xv) reinterpret_cast<u32x4*>(xs)[lane + 64 * k] = q[k];
     wave_sync();
 
@@ -124,7 +141,7 @@ __device__ __forceinline__ void compress_strip_body(const StripArgs& a) {
     {
         const float4* sp = reinterpret_cast<const float4*>(xs + (valid ? g * a.HW + sl * E : 0u));
 #pragma unroll
-        for (int u = 0; u < 7; ++u) {
+        for (int u = 0; u < UPL; ++u) {
             const float4 v = sp[u];
             x[4 * u] = v.x; x[4 * u + 1] = v.y; x[4 * u + 2] = v.z; x[4 * u + 3] = v.w;
         }
@@ -136,24 +153,49 @@ __device__ __forceinline__ void compress_strip_body(const StripArgs& a) {
 #pragma unroll
     for (int s = 0; s < NSEG; ++s) Sm[s] = 0.0;
 #pragma unroll
-    for (int e = 0; e < E; ++e) Sm[(e % W) / 8] += (double)x[e];
+    for (int e = 0; e < E; ++e) Sm[(e % W) / B] += (double)x[e];
     float lfc[NSEG];
+    if constexpr (Geo::kDpp) {
 #pragma unroll
-    for (int s = 0; s < NSEG; ++s) {
-        const double Sb = group_sum<LB>(valid ? Sm[s] : 0.0);
-        const uint32_t cols = (uint32_t)(W - 8 * s < 8 ? W - 8 * s : 8);     // a constant once the loop is unrolled
-        lfc[s] = lfc_round<T>(mean_of(Sb, max(rows, 1u) * cols), kC16<T>);
-    }
-    if (valid && sl % LB == 0) {
+        for (int s = 0; s < NSEG; ++s) {
+            const double Sb = group_sum<LBR>(valid ? Sm[s] : 0.0);
+            const uint32_t cols = (uint32_t)(W - B * s < B ? W - B * s : B);     // a constant once the loop is unrolled
+            lfc[s] = lfc_round<T>(mean_of(Sb, max(rows, 1u) * cols), kC16<T>);
+        }
+        if (valid && sl % LBR == 0) {
 #pragma unroll
-        for (int s = 0; s < NSEG; ++s) lfc_store<T>(pt.lfc, (size_t)p * a.nb + bi * NSEG + s, lfc[s], kC16<T>);
+            for (int s = 0; s < NSEG; ++s) lfc_store<T>(pt.lfc, (size_t)p * a.nb + bi * NSEG + s, lfc[s], kC16<T>);
+        }
+    } else {
+        // the shares of a plane's strips lie one after the other: [plane of the round][strip][block column]
+#pragma unroll
+        for (int s = 0; s < NSEG; ++s) part[lane * NSEG + s] = valid ? Sm[s] : 0.0;
+        wave_sync();
+        // a lane per block of the round adds the shares of the block's strips in row order
+        const uint32_t nbr = Gc * a.nb;                                   // at most 64 (the host checks G * nb)
+        if (lane < nbr) {
+            const uint32_t bg = lane / a.nb, t = lane - bg * a.nb;       // plane of the round, block of the plane
+            const uint32_t tbi = t / NSEG, s = t - tbi * NSEG;
+            const uint32_t brows = min((uint32_t)B, a.H - tbi * (uint32_t)B);    // >= 1: the block exists
+            const uint32_t nstrips = (brows + RPL - 1) / RPL;
+            const double* ps = part + (bg * S + tbi * LBR) * NSEG + s;
+            double Sb = 0.0;
+            for (uint32_t i = 0; i < nstrips; ++i) Sb += ps[i * NSEG];
+            const uint32_t cols = min((uint32_t)B, (uint32_t)W - s * (uint32_t)B);
+            const float m = lfc_round<T>(mean_of(Sb, brows * cols), kC16<T>);
+            lfcs[lane] = m;
+            lfc_store<T>(pt.lfc, (size_t)(p0 + bg) * a.nb + t, m, kC16<T>);
+        }
+        wave_sync();
+#pragma unroll
+        for (int s = 0; s < NSEG; ++s) lfc[s] = lfcs[valid ? g * a.nb + bi * NSEG + s : 0u];
     }
 
     // ---- residual H^H = H - UpSampling(H^L) in place, the plane's extremes
     float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
     for (int e = 0; e < E; ++e) {
-        x[e] = x[e] - lfc[(e % W) / 8];
+        x[e] = x[e] - lfc[(e % W) / B];
         mn = fminf(mn, x[e]);
         mx = fmaxf(mx, x[e]);
     }
@@ -179,10 +221,10 @@ __device__ __forceinline__ void compress_strip_body(const StripArgs& a) {
     }
     wave_sync();
     {
-        uint8_t* cb = reinterpret_cast<uint8_t*>(cw) + g * a.WPP * 4u + sl * (7u * CB);
-        const uint32_t xw0 = k1 + (sl * 14u) * kWeyl;
+        uint8_t* cb = reinterpret_cast<uint8_t*>(cw) + g * a.WPP * 4u + sl * (uint32_t)(UPL * CB);
+        const uint32_t xw0 = k1 + (sl * (uint32_t)(E / 2)) * kWeyl;
 #pragma unroll
-        for (int u = 0; u < 7; ++u) {
+        for (int u = 0; u < UPL; ++u) {
             const uint32_t xw = xw0 + (uint32_t)(2 * u) * kWeyl;
             uint32_t c = push_pair<BITS>(0u, x[4 * u + 2], x[4 * u + 3], delta, invs, xw + kWeyl, k2, rscale);
             c = push_pair<BITS>(c, x[4 * u], x[4 * u + 1], delta, invs, xw, k2, rscale);
@@ -200,7 +242,7 @@ __device__ __forceinline__ void compress_strip_body(const StripArgs& a) {
     }
 }
 
+template <typename T, int BITS, int W, int B>
+__global__ void __launch_bounds__(64) compress_strip(StripArgs a) { compress_strip_body<T, BITS, W, B, false>(a); }
 template <typename T, int BITS, int W>
-__global__ void __launch_bounds__(64) compress_strip(StripArgs a) { compress_strip_body<T, BITS, W, false>(a); }
-template <typename T, int BITS, int W>
-__global__ void __launch_bounds__(64) relu_compress_strip(StripArgs a) { compress_strip_body<T, BITS, W, true>(a); }
+__global__ void __launch_bounds__(64) relu_compress_strip(StripArgs a) { compress_strip_body<T, BITS, W, 8, true>(a); }

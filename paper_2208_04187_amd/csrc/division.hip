@@ -19,10 +19,11 @@
 //                    workgroup of one / four / sixteen wavefronts, the plane stays in registers from
 //                    load to codes
 //   compress_lane    one-block planes with an odd element count (7x7): a lane per plane
-//   compress_strip   28 x 28 and 14 x 14 planes (widths 28 and 14, up to 32 resp. 16 rows) under B = 8: a lane per strip
-//                    of 28 consecutive elements (one or two rows), the round read with coalesced loads and
-//                    handed out through LDS, block sums and extremes by DPP (relu_compress_strip: the same
-//                    with a Relu applied to the round as its loads arrive)
+//   compress_strip   planes of width 28 / 32 (up to 32 rows) or 14 / 16 (up to 16 rows) under B = 8 (28, 14) and the
+//                    12, 16, 18 of the block-size sweep: a lane per strip of 28 or 32 consecutive elements (one
+//                    or two rows), the round read with coalesced loads and handed out through LDS, extremes by
+//                    DPP, block sums by DPP (B = 8) or through LDS (relu_compress_strip: B = 8 with a Relu
+//                    applied to the round as its loads arrive)
 //   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8: a lane per
 //                    pooling item, loaded straight from global memory, DPP reductions (relu_compress_items:
 //                    the same with a Relu applied to the rows as they arrive)

@@ -296,26 +296,60 @@ bool plan_items(const Layout& L, int64_t H, int64_t W, int B, size_t es, const v
     return true;
 }
 
-// Fills the strip kernel's plan: 2-D maps of width 28 (at most 32 rows) or 14 (an even number of rows,
-// at most 16) under B = 8; false when the shape is not covered.
+// Fills the strip kernel's plan: 2-D maps of width 28 or 32 (at most 32 rows) or 14 or 16 (an even number
+// of rows, at most 16), 16-byte aligned, under a block size the kernel has an instance for: 8 on 28 / 14
+// (the items kernel keeps 32 / 16 under B = 8), 12, 16 (where a plane has several blocks) and 18 of the
+// block-size sweep; false when the shape is not covered.  *width = 100 * W + B names the instance.
 bool plan_strip(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* x,
                 StripArgs* a, uint32_t* grid, size_t* lds, int* width) {
-    if (B != 8 || ((uintptr_t)x % (4 * es)) != 0) return false;
-    uint64_t G;
-    if (W == 28 && H <= 32) G = 2;
-    else if (W == 14 && H % 2 == 0 && H <= 16) G = 8;
+    if (((uintptr_t)x % (4 * es)) != 0) return false;
+    uint64_t G, upl;
+    if ((W == 28 || W == 32) && H <= 32) { G = 2; upl = W == 28 ? 7 : 8; }
+    else if ((W == 14 || W == 16) && H % 2 == 0 && H <= 16) { G = 8; upl = W == 14 ? 7 : 8; }
     else return false;
+    const bool wide = W == 28 || W == 32;
+    bool have;
+    switch (B) {
+        case 4: have = W == 32 || W == 16; break;
+        case 8: have = true; break;
+        case 12: have = true; break;
+        case 16: have = wide; break;
+        case 18: have = wide; break;
+        default: have = false;
+    }
+    if (!have) return false;
+    const uint64_t nseg = ((uint64_t)W + B - 1) / B;
+    const bool dpp = B == 4 || B == 8;
+    if (L.LW != nseg || (!dpp && G * L.nb > 64)) return false;
     a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP; a->nb = (uint32_t)L.nb;
     a->nrounds = (uint32_t)((L.P + G - 1) / G);
     *grid = a->nrounds;
-    *lds = 4ull * G * L.HW + 16;
-    *width = (int)W;
+    // the round; for the block sizes whose block rows are no DPP group also the strips' shares and the round's H^L
+    *lds = dpp ? 4ull * G * L.HW + 16 : upl * 1024 + 64 * nseg * 8 + 256 + 16;
+    *width = (int)(100 * W + B);
     return true;
 }
 
 template <typename T, int BITS>
 hipError_t launch_strip(int width, const StripArgs& a, dim3 grid, size_t lds, hipStream_t st) {
-    void (*kern)(StripArgs) = width == 28 ? compress_strip<T, BITS, 28> : compress_strip<T, BITS, 14>;
+    void (*kern)(StripArgs);
+    switch (width) {
+        case 2808: kern = compress_strip<T, BITS, 28, 8>; break;
+        case 1408: kern = compress_strip<T, BITS, 14, 8>; break;
+        case 3208: kern = compress_strip<T, BITS, 32, 8>; break;
+        case 1608: kern = compress_strip<T, BITS, 16, 8>; break;
+        case 3204: kern = compress_strip<T, BITS, 32, 4>; break;
+        case 1604: kern = compress_strip<T, BITS, 16, 4>; break;
+        case 2812: kern = compress_strip<T, BITS, 28, 12>; break;
+        case 2816: kern = compress_strip<T, BITS, 28, 16>; break;
+        case 2818: kern = compress_strip<T, BITS, 28, 18>; break;
+        case 3212: kern = compress_strip<T, BITS, 32, 12>; break;
+        case 3216: kern = compress_strip<T, BITS, 32, 16>; break;
+        case 3218: kern = compress_strip<T, BITS, 32, 18>; break;
+        case 1412: kern = compress_strip<T, BITS, 14, 12>; break;
+        case 1612: kern = compress_strip<T, BITS, 16, 12>; break;
+        default: return hipErrorInvalidValue;
+    }
     hipLaunchKernelGGL(kern, grid, dim3(64), lds, st, a);
     return hipGetLastError();
 }
@@ -323,14 +357,14 @@ hipError_t launch_strip(int width, const StripArgs& a, dim3 grid, size_t lds, hi
 // The Relu + compress instance of the strip kernel; a round's mask bits must be whole words.
 bool plan_relu_strip(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* xy,
                      StripArgs* a, uint32_t* grid, size_t* lds, int* width) {
-    if (!plan_strip(L, H, W, B, es, xy, a, grid, lds, width)) return false;
+    if (B != 8 || (W != 28 && W != 14) || !plan_strip(L, H, W, B, es, xy, a, grid, lds, width)) return false;
     const uint64_t G = W == 28 ? 2 : 8;
     return (G * L.HW) % 32 == 0;
 }
 
 template <typename T, int BITS>
 hipError_t launch_relu_strip(int width, const StripArgs& a, dim3 grid, size_t lds, hipStream_t st) {
-    void (*kern)(StripArgs) = width == 28 ? relu_compress_strip<T, BITS, 28> : relu_compress_strip<T, BITS, 14>;
+    void (*kern)(StripArgs) = width == 2808 ? relu_compress_strip<T, BITS, 28> : relu_compress_strip<T, BITS, 14>;
     hipLaunchKernelGGL(kern, grid, dim3(64), lds, st, a);
     return hipGetLastError();
 }
@@ -1056,7 +1090,7 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
         else if (plan_line(L, D, H, B, es, data, &oa, &grid))
             n = snprintf(out, cap, "compress_line<%s, %d>", tn, b);
         else if (flat && plan_strip(L, H, W, B, es, data, &sa, &grid, &lds, &vec))
-            n = snprintf(out, cap, "compress_strip<%s, %d, %d>", tn, b, vec);
+            n = snprintf(out, cap, "compress_strip<%s, %d, %d, %d>", tn, b, vec / 100, vec % 100);
         else if (flat && plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_items<%s, %d, %d, %d, %d>", tn, b, B, vec, H == 1 ? 1 : B);
         else if (!one_shape(L, es, data) && plan_units(L, D, H, W, B, es, data, &ua, &grid, &lds, &nw))

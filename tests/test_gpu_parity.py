@@ -725,6 +725,46 @@ def test_strip_kernel_matches_oracle(shape, b, mode):
     _check_variant(shape, 8, b, mode)
 
 
+# the block sizes of the sweep of Sec. 5 (12, 16, 18) on the small maps of a ResNet (28, 14 wide on ImageNet, 32, 16 on CIFAR):
+# block rows of 12 or 18 rows are no DPP group, the strips' shares of a block meet in LDS
+STRIP_SWEEP_CASES = [
+    ((3, 171, 28, 28), 12, 2),          # 12 + 12 + 4 rows and columns, an odd number of planes
+    ((2, 33, 28, 28), 18, 4),           # 18 + 10
+    ((2, 33, 28, 28), 16, 8),           # 16 + 12: block rows of 16 lanes
+    ((3, 67, 32, 32), 12, 2),           # 12 + 12 + 8, every lane slot in use
+    ((3, 67, 32, 32), 18, 4),           # 18 + 14
+    ((2, 33, 32, 32), 16, 2),
+    ((5, 41, 16, 16), 12, 2),           # 12 + 4, two rows per lane, 205 planes in rounds of 8
+    ((5, 41, 14, 14), 12, 8),           # 12 + 2
+    ((3, 67, 20, 28), 12, 2),           # 12 + 8 rows
+    ((3, 67, 13, 32), 12, 4),           # 12 + 1 rows
+    ((3, 67, 30, 32), 18, 2),           # 18 + 12 rows
+    ((3, 67, 19, 28), 18, 2),           # 18 + 1 rows
+    ((3, 67, 6, 16), 12, 2),            # one block row of 6 rows
+    ((3, 67, 14, 16), 12, 4),           # 12 + 2 rows, two per lane
+    ((1, 1, 32, 32), 18, 2), ((1, 1, 16, 16), 12, 2),
+    ((9, 600, 16, 16), 12, 2),          # 5400 planes: more than one run of the XCD-aware order and its plain tail
+    # B = 4 and 8 on the CIFAR widths: block rows of 4 / 8 rows are DPP groups of 4, 2 (two rows per lane) or 8 lanes
+    ((3, 67, 32, 32), 4, 2),            # 8 x 8 blocks: eight block columns per strip
+    ((3, 67, 32, 32), 8, 4),
+    ((5, 41, 16, 16), 4, 8),            # groups of two lanes
+    ((5, 41, 16, 16), 8, 2),
+    ((3, 67, 30, 32), 4, 2),            # ragged last block row (2 of 4 rows)
+    ((3, 67, 27, 32), 8, 2),            # 3 of 8 rows
+    ((3, 67, 10, 16), 4, 4),            # 2 of 4 rows, two rows per lane
+    ((3, 67, 12, 16), 8, 2),
+]
+
+
+@pytest.mark.parametrize("shape,B,b", STRIP_SWEEP_CASES)
+@pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
+def test_strip_kernel_under_the_block_sizes_of_the_sweep(shape, B, b, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    name = pkg.division_kernel_name(0, shape, B, b, dtype, c16=mode == "c16")
+    assert name.startswith("compress_strip<") and name.endswith(", %d, %d>" % (shape[3], B)), name
+    _check_variant(shape, B, b, mode)
+
+
 @pytest.mark.parametrize("shape,B,b", ROWS_CASES)
 @pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
 def test_general_block_size_kernel_matches_oracle(shape, B, b, mode):
@@ -735,7 +775,7 @@ def test_general_block_size_kernel_matches_oracle(shape, B, b, mode):
     # (1-D maps with power-of-two blocks the one-row kernel), other planes of 256 elements and more
     # the register kernel for any width
     units = shape[2] > 1 and shape[2] * shape[3] >= 256
-    assert (name.startswith(("compress_rows<", "compress_line<")) or (name.startswith("compress_regs<") and ", 0, " in name)
+    assert (name.startswith(("compress_rows<", "compress_line<", "compress_strip<")) or (name.startswith("compress_regs<") and ", 0, " in name)
             or (units and name.startswith("compress_units<")))
     _check_variant(shape, B, b, mode)
 

@@ -153,13 +153,20 @@ DISPATCH = [
     ((64, 256, 56, 56), 8, 2, "compress_regs<float, 2, 8, 1>", "decompress_stream<float, 2>"),
     ((64, 64, 112, 112), 8, 2, "compress_regs<float, 2, 8, 4>", "decompress_stream<float, 2>"),
     ((2, 3, 224, 224), 8, 2, "compress_regs<float, 2, 8, 16>", "decompress_stream<float, 2>"),
-    ((64, 512, 28, 28), 8, 2, "compress_strip<float, 2, 28>", "decompress_stream<float, 2>"),
-    ((64, 1024, 14, 14), 8, 2, "compress_strip<float, 2, 14>", "decompress_table<float, 2>"),
-    ((4, 8, 20, 28), 8, 4, "compress_strip<float, 4, 28>", "decompress_stream<float, 4>"),
+    ((64, 512, 28, 28), 8, 2, "compress_strip<float, 2, 28, 8>", "decompress_stream<float, 2>"),
+    ((64, 1024, 14, 14), 8, 2, "compress_strip<float, 2, 14, 8>", "decompress_table<float, 2>"),
+    ((4, 8, 20, 28), 8, 4, "compress_strip<float, 4, 28, 8>", "decompress_stream<float, 4>"),
+    ((256, 64, 32, 32), 12, 2, "compress_strip<float, 2, 32, 12>", "decompress_stream<float, 2>"),     # the block-size sweep on CIFAR maps
+    ((256, 64, 32, 32), 18, 2, "compress_strip<float, 2, 32, 18>", "decompress_table<float, 2>"),
+    ((256, 128, 16, 16), 12, 2, "compress_strip<float, 2, 16, 12>", "decompress_stream<float, 2>"),
+    ((64, 512, 28, 28), 18, 2, "compress_strip<float, 2, 28, 18>", "decompress_table<float, 2>"),
+    ((64, 1024, 14, 14), 12, 2, "compress_strip<float, 2, 14, 12>", "decompress_table<float, 2>"),
     ((4, 8, 28, 28), 4, 2, "compress_items<float, 2, 4, 4, 4>", "decompress_stream<float, 2>"),
     ((4, 8, 15, 14), 8, 2, "compress_items<float, 2, 8, 2, 8>", "decompress_words<float, 2>"),
     ((64, 2048, 7, 7), 8, 2, "compress_lane<float, 2>", "decompress_lane<float, 2>"),
-    ((128, 64, 32, 32), 4, 2, "compress_items<float, 2, 4, 4, 4>", "decompress_stream<float, 2>"),
+    ((128, 64, 32, 32), 4, 2, "compress_strip<float, 2, 32, 4>", "decompress_stream<float, 2>"),
+    ((128, 128, 16, 16), 4, 2, "compress_strip<float, 2, 16, 4>", "decompress_stream<float, 2>"),
+    ((128, 256, 8, 8), 4, 2, "compress_items<float, 2, 4, 4, 4>", "decompress_stream<float, 2>"),
     ((64, 256, 56, 56), 12, 2, "compress_regs<float, 2, 0, 1>", "decompress_stream<float, 2>"),
     ((64, 256, 56, 56), 64, 2, "compress_one<float, 2>", "decompress_stream<float, 2>"),
     ((64, 256, 56, 56), 18, 4, "compress_units<float, 4, 2>", "decompress_table<float, 4>"),
@@ -170,7 +177,8 @@ DISPATCH = [
     ((4, 4, 147, 147), 8, 2, "compress_units<float, 2, 16>", "decompress_units<float, 2, 16>"),
     ((4, 4, 30, 30), 4, 2, "compress_wave<float, 2, 4, 2>", "decompress_table<float, 2>"),
     ((2, 2, 1, 768), 8, 4, "compress_line<float, 4>", "decompress_stream<float, 4>"),
-    ((5, 33, 14, 14), 12, 4, "compress_rows<float, 4>", "decompress_table<float, 4>"),
+    ((5, 33, 14, 14), 12, 4, "compress_strip<float, 4, 14, 12>", "decompress_table<float, 4>"),
+    ((5, 33, 24, 24), 18, 4, "compress_rows<float, 4>", "decompress_table<float, 4>"),
     ((1, 1, 300, 300), 18, 2, "compress_any<float, 2>", "decompress_scalar<float, 2>"),
 ]
 
