@@ -137,28 +137,44 @@ __global__ void __launch_bounds__(64) compress_one(OneArgs a) {
 // transformer layers) whose block is a power-of-two number of 16-byte vectors (B = 4, 8, 16, 32, 64
 // for fp32): laid out like compress_one, the `upb` vectors of a block sit in neighbouring lanes of
 // one round, so a block's sum is a DPP reduction over those lanes and its LFC stays in a register.
-// No LDS.
+// No LDS.  The planes of a wavefront are contiguous: their vectors are read through one bounds-checked
+// buffer (a lane whose vector lies past its plane reads its neighbour's data or zero and is masked in
+// the arithmetic), codes and H^L leave through bounds-checked buffer stores with the offset pushed out
+// of range where nothing is to be written: no branch depends on a lane, loads and rounds are
+// straight-line code that the compiler is free to interleave.
+constexpr int kLineUnits = 13;
 template <typename T, int BITS>
 __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
-    constexpr int K = kOneUnits;
+    constexpr int K = kLineUnits;
     constexpr uint32_t EPV = 16 / sizeof(T);
     constexpr uint32_t CBV = EPV * BITS / 8;
     constexpr float Lf = float((1 << BITS) - 1);
+    constexpr uint32_t kDrop = 0x80000000u;              // an offset past every buffer here (and no wrap when a round's offset is added): the access is dropped
     const uint32_t tid = threadIdx.x;
     const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
-    const uint32_t sub = tid & (a.S - 1u);
-    const uint32_t p = blockIdx.x * a.ppw + (tid >> a.S_log2);
-    const bool live = p < a.P;
-    const uint32_t pc = live ? p : a.P - 1u;          // lanes past the last plane redo it; their stores are masked
-    const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const T*>(pt.x) + (size_t)pc * a.HW);
+    const uint32_t sub = tid & (a.S - 1u), pl = tid >> a.S_log2;
+    const uint32_t p0 = blockIdx.x * a.ppw;
+    const uint32_t Gc = min(a.ppw, a.P - p0);
+    const uint32_t p = p0 + pl;
+    const bool live = pl < Gc;
 
     u32x4 q[K];
+    {
+        const T* src = static_cast<const T*>(pt.x) + (size_t)p0 * a.HW;
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(Gc * a.HW * sizeof(T)), 0x00020000);
+        const uint32_t off0 = live ? (pl * a.qv + sub) * 16u : kDrop;
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-        const uint32_t u = sub + (uint32_t)k * a.S;
-        if (u < a.qv) q[k] = __builtin_nontemporal_load(src + u);
+        for (int k = 0; k < K; ++k) {
+            // rounds past the plane (uniform) are not loaded; a lane past the plane's end inside a round is
+            q[k] = u32x4{0u, 0u, 0u, 0u};
+            if ((uint32_t)k * a.S < a.qv) q[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off0 + (uint32_t)k * a.S * 16u, 0, kLoadAux);
+        }
     }
     // ---- AveragePooling1D: block sums over the lanes of a block, residual extremes of the plane
+    // every block but the plane's last has upb vectors: their reciprocals are taken once, not per round
+    const uint32_t cnt_full = a.upb * EPV, cnt_last = (a.qv - (a.nb - 1u) * a.upb) * EPV;
+    const double rcp_full = 1.0 / (double)cnt_full, rcp_last = 1.0 / (double)cnt_last;
     float lfcv[K];
     float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
@@ -167,69 +183,77 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
         const uint32_t u = sub + (uint32_t)k * a.S;
         const bool valid = u < a.qv;
         float f[EPV];
-        double s4 = 0.0;
-        if (valid) {
-            unpack_vec<T>(q[k], f);
-            s4 = ((double)f[0] + (double)f[1]) + ((double)f[2] + (double)f[3]);
-            if constexpr (EPV == 8) s4 += ((double)f[4] + (double)f[5]) + ((double)f[6] + (double)f[7]);
-            s4 += 0.0;                                    // a block of negative zeros sums to +0, as a sum from 0 does
-        }
+        unpack_vec<T>(q[k], f);
+        double s4 = ((double)f[0] + (double)f[1]) + ((double)f[2] + (double)f[3]);
+        if constexpr (EPV == 8) s4 += ((double)f[4] + (double)f[5]) + ((double)f[6] + (double)f[7]);
+        s4 = valid ? s4 + 0.0 : 0.0;                  // a block of negative zeros sums to +0, as a sum from 0 does
         const double Sb = group_sum_any(a.upb, s4);
         const uint32_t ustart = u & ~(a.upb - 1u);
-        const uint32_t nvec = valid ? min(a.upb, a.qv - ustart) : 1u;           // the last block may be short
-        const float lfc = lfc_round<T>(mean_of(Sb, nvec * EPV), kC16<T>);
+        const bool last = ustart + a.upb >= a.qv;                              // the last block may be short
+        const float lfc = lfc_round<T>(mean_with_rcp(Sb, last ? cnt_last : cnt_full, last ? rcp_last : rcp_full), kC16<T>);
         lfcv[k] = lfc;
-        if (valid) {
+        float hmn = __builtin_inff(), hmx = -__builtin_inff();
 #pragma unroll
-            for (uint32_t e = 0; e < EPV; ++e) {
-                const float h = f[e] - lfc;
-                mn = fminf(mn, h);
-                mx = fmaxf(mx, h);
-            }
-            if (live && u == ustart) lfc_store<T>(pt.lfc, (size_t)p * a.nb + (u >> a.upb_log2), lfc, kC16<T>);
+        for (uint32_t e = 0; e < EPV; ++e) {
+            const float h = f[e] - lfc;
+            hmn = fminf(hmn, h);
+            hmx = fmaxf(hmx, h);
         }
+        mn = fminf(mn, valid ? hmn : __builtin_inff());
+        mx = fmaxf(mx, valid ? hmx : -__builtin_inff());
     }
     group_minmax(a.S, mn, mx);
     float delta, Delta, inv;
     plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
     const float invs = inv * (float)(1u << (32 - BITS));
-    const uint32_t k1 = mix32(pc ^ pt.seed_a);
+    const uint32_t k1 = mix32(p ^ pt.seed_a);
     const uint32_t k2 = mix32(k1 + pt.seed_c);
-    uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)pc * a.WPP * 4;
+    uint8_t* cwave = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)p0 * a.WPP * 4;
     if (live && sub == 0) {
         meta_store(pt.meta, p, delta, Delta, kC16<T>);
+        uint8_t* cbase = cwave + (size_t)pl * a.WPP * 4;
         const uint32_t padb = a.WPP * 4 - a.qv * CBV;                 // pad bytes of the last word are zero
         for (uint32_t t = 0; t < padb; ++t) cbase[a.qv * CBV + t] = 0;
     }
     // ---- residual, Quant, packing
+    const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(cwave, 0, (int)(Gc * a.WPP * 4u), 0x00020000);
+    constexpr uint32_t LB = (sizeof(T) == 2 || kC16<T>) ? 2u : 4u;          // bytes of a cached H^L value
+    const __amdgpu_buffer_rsrc_t lrs = __builtin_amdgcn_make_buffer_rsrc(
+        static_cast<uint8_t*>(pt.lfc) + (size_t)p0 * a.nb * LB, 0, (int)(Gc * a.nb * LB), 0x00020000);
     const uint32_t rscale = 1u << (16 - BITS);
 #pragma unroll
     for (int k = 0; k < K; ++k) {
+        if ((uint32_t)k * a.S >= a.qv) continue;                                 // uniform
         const uint32_t u = sub + (uint32_t)k * a.S;
-        if (live && u < a.qv) {
-            float h[EPV];
-            unpack_vec<T>(q[k], h);
+        const bool wr = live && u < a.qv;
+        {
+            // H^L of the block whose first vector this is
+            const uint32_t lo = wr && (u & (a.upb - 1u)) == 0 ? (pl * a.nb + (u >> a.upb_log2)) * LB : kDrop;
+            if constexpr (LB == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)float_to_bf16_bits(lfcv[k]), lrs, lo, 0, 0);
+            else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(lfcv[k]), lrs, lo, 0, 0);
+        }
+        float h[EPV];
+        unpack_vec<T>(q[k], h);
 #pragma unroll
-            for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lfcv[k];
-            const uint32_t xw0 = k1 + (u * (EPV / 2)) * kWeyl;
-            uint8_t* dst = cbase + u * CBV;
-            if constexpr (CBV <= 4) {
-                uint32_t c = 0;
+        for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lfcv[k];
+        const uint32_t xw0 = k1 + (u * (EPV / 2)) * kWeyl;
+        const uint32_t co = wr ? pl * a.WPP * 4u + u * CBV : kDrop;
+        if constexpr (CBV <= 4) {
+            uint32_t c = 0;
 #pragma unroll
-                for (int j = EPV / 2 - 1; j >= 0; --j)
-                    c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
-                if constexpr (CBV == 1) *dst = (uint8_t)c;
-                else if constexpr (CBV == 2) *reinterpret_cast<uint16_t*>(dst) = (uint16_t)c;
-                else *reinterpret_cast<uint32_t*>(dst) = c;
-            } else {
-                uint32_t lo = 0, hi = 0;
-                hi = push_pair<BITS>(hi, h[6], h[7], delta, invs, xw0 + 3u * kWeyl, k2, rscale);
-                hi = push_pair<BITS>(hi, h[4], h[5], delta, invs, xw0 + 2u * kWeyl, k2, rscale);
-                lo = push_pair<BITS>(lo, h[2], h[3], delta, invs, xw0 + kWeyl, k2, rscale);
-                lo = push_pair<BITS>(lo, h[0], h[1], delta, invs, xw0, k2, rscale);
-                reinterpret_cast<uint32_t*>(dst)[0] = lo;
-                reinterpret_cast<uint32_t*>(dst)[1] = hi;
-            }
+            for (int j = EPV / 2 - 1; j >= 0; --j)
+                c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+            if constexpr (CBV == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, co, 0, 0);
+            else if constexpr (CBV == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c, crs, co, 0, 0);
+            else __builtin_amdgcn_raw_buffer_store_b32(c, crs, co, 0, 0);
+        } else {
+            uint32_t lo = 0, hi = 0;
+            hi = push_pair<BITS>(hi, h[6], h[7], delta, invs, xw0 + 3u * kWeyl, k2, rscale);
+            hi = push_pair<BITS>(hi, h[4], h[5], delta, invs, xw0 + 2u * kWeyl, k2, rscale);
+            lo = push_pair<BITS>(lo, h[2], h[3], delta, invs, xw0 + kWeyl, k2, rscale);
+            lo = push_pair<BITS>(lo, h[0], h[1], delta, invs, xw0, k2, rscale);
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            __builtin_amdgcn_raw_buffer_store_b64(u32x2{lo, hi}, crs, co, 0, 0);
         }
     }
 }

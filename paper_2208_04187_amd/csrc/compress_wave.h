@@ -41,12 +41,15 @@ __host__ __device__ __forceinline__ bool mean_rule_divides(double q) {
 __host__ __device__ __forceinline__ bool mean_count_is_power_of_two(uint32_t cnt) { return (cnt & (cnt - 1)) == 0; }
 
 // The rule on the device: when any lane of the wavefront needs the division, all take it.
-__device__ __forceinline__ float mean_of(double S, uint32_t cnt) {
-    if (mean_count_is_power_of_two(cnt)) return (float)(S * (1.0 / (double)cnt));     // exact scaling
-    const double q = S * (1.0 / (double)cnt);
+// rcp must be the binary64 quotient 1.0 / cnt (a kernel that needs the mean of many blocks of one size
+// divides once and passes it in).
+__device__ __forceinline__ float mean_with_rcp(double S, uint32_t cnt, double rcp) {
+    if (mean_count_is_power_of_two(cnt)) return (float)(S * rcp);     // exact scaling
+    const double q = S * rcp;
     if (__builtin_expect(__any(mean_rule_divides(q)), 0)) return (float)(S / (double)cnt);
     return (float)q;
 }
+__device__ __forceinline__ float mean_of(double S, uint32_t cnt) { return mean_with_rcp(S, cnt, 1.0 / (double)cnt); }
 
 // The rule for one value on the host (what a lane whose neighbours do not ask for the division computes).
 inline float mean_of_host(double S, uint32_t cnt, int* divided) {

@@ -471,7 +471,7 @@ bool plan_one(const Layout& L, size_t es, const void* x, OneArgs* a, uint32_t* g
     uint32_t best_S = 0, best_log = 0;
     for (uint32_t lg = 3; lg <= 6; ++lg) {
         const uint64_t S = 1ull << lg;
-        if ((qv + S - 1) / S <= (uint64_t)kOneUnits) { best_S = (uint32_t)S; best_log = lg; break; }
+        if ((qv + S - 1) / S <= (uint64_t)kLineUnits) { best_S = (uint32_t)S; best_log = lg; break; }
     }
     a->P = (uint32_t)L.P; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP;
     a->qv = (uint32_t)qv;
@@ -494,7 +494,7 @@ bool plan_line(const Layout& L, int64_t D, int64_t H, int B, size_t es, const vo
     const uint64_t epv = 16 / es;
     if (D != 1 || H != 1 || L.nb < 2 || ((uintptr_t)x % 16) != 0 || L.HW % epv != 0 || (uint64_t)B % epv != 0) return false;
     const uint64_t qv = L.HW / epv, upb = (uint64_t)B / epv;
-    if ((upb & (upb - 1)) != 0 || upb > 64 || qv > (uint64_t)kOneUnits * 64) return false;
+    if ((upb & (upb - 1)) != 0 || upb > 64 || qv > (uint64_t)kLineUnits * 64) return false;
     uint32_t upb_log = 0;
     while ((1ull << upb_log) < upb) ++upb_log;
     // lanes per plane: the smallest power of two that is a block, at least 8 (a plane's lanes then read
@@ -504,7 +504,7 @@ bool plan_line(const Layout& L, int64_t D, int64_t H, int B, size_t es, const vo
     uint32_t best_S = 0, best_log = 0;
     for (uint32_t lg = upb_log > 3 ? upb_log : 3; lg <= 6; ++lg) {
         const uint64_t S = 1ull << lg;
-        if ((qv + S - 1) / S <= (uint64_t)kOneUnits) { best_S = (uint32_t)S; best_log = lg; break; }
+        if ((qv + S - 1) / S <= (uint64_t)kLineUnits) { best_S = (uint32_t)S; best_log = lg; break; }
     }
     if (best_S == 0) return false;
     a->P = (uint32_t)L.P; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP;
