@@ -11,6 +11,7 @@ struct OneArgs {
     uint32_t ppw;        // planes per wavefront = 64 / S
     uint32_t upb, upb_log2;  // compress_line: vectors per block (power of two, at most S); nb = blocks per plane
     uint32_t nb;
+    uint32_t K;          // rounds of the instance to launch (3, 6 or 13): not read by the kernels
 };
 
 constexpr int kOneUnits = 13;     // vectors per lane: planes of up to 13 * 64 vectors
@@ -42,45 +43,59 @@ __device__ __forceinline__ double group_sum_any(uint32_t S, double v) {
 // 64 / S planes; the S lanes of a plane keep its vectors in registers (vector u in lane u mod S),
 // sums and extremes are reductions over those lanes, the codes leave as one to eight bytes per
 // vector.  LDS is not used.
-template <typename T, int BITS>
+// K: rounds the instance runs (3, 6 or 13; the host picks lanes per plane and K so that a plane has at
+// most K rounds of vectors and few of the K * S lane slots stay empty).  No round is tested at run time:
+// a uniform test per round splits the code into blocks that each wait for every load (measured: 50 ->
+// 40 us on 64 x 256 x 56 x 56); a round past the plane loads nothing (its offsets are out of range) and
+// works on zeros that are masked.
+template <typename T, int BITS, int K>
 __global__ void __launch_bounds__(64) compress_one(OneArgs a) {
-    constexpr int K = kOneUnits;
     constexpr uint32_t EPV = 16 / sizeof(T);
     constexpr uint32_t CBV = EPV * BITS / 8;
     constexpr float Lf = float((1 << BITS) - 1);
+    constexpr uint32_t kDrop = 0x80000000u;              // an offset past every buffer here: the access is dropped
     const uint32_t tid = threadIdx.x;
     const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
-    const uint32_t sub = tid & (a.S - 1u);
-    const uint32_t p = blockIdx.x * a.ppw + (tid >> a.S_log2);
-    const bool live = p < a.P;
-    const uint32_t pc = live ? p : a.P - 1u;          // lanes past the last plane redo it; their stores are masked
-    const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const T*>(pt.x) + (size_t)pc * a.HW);
+    const uint32_t sub = tid & (a.S - 1u), pl = tid >> a.S_log2;
+    const uint32_t p0 = xcd_run_index(blockIdx.x, gridDim.x) * a.ppw;
+    const uint32_t Gc = min(a.ppw, a.P - p0);
+    const uint32_t p = p0 + pl;
+    const bool live = pl < Gc;
 
+    // the planes of a wavefront are contiguous: one bounds-checked buffer, no branch that depends on a
+    // lane (a vector past its plane's end reads the neighbour's data or zero and is masked below)
     u32x4 q[K];
+    {
+        const T* src = static_cast<const T*>(pt.x) + (size_t)p0 * a.HW;
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(Gc * a.HW * sizeof(T)), 0x00020000);
+        const uint32_t off0 = live ? (pl * a.qv + sub) * 16u : kDrop;
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-        const uint32_t u = sub + (uint32_t)k * a.S;
-        if (u < a.qv) q[k] = __builtin_nontemporal_load(src + u);
+        for (int k = 0; k < K; ++k) {
+            // a vector past the plane's end is not fetched (offset out of range: it reads as zero)
+            const uint32_t u = sub + (uint32_t)k * a.S;
+            q[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, u < a.qv ? off0 + (uint32_t)k * a.S * 16u : kDrop, 0, kLoadAux);
+        }
     }
     // ---- Sec. 4.1 AveragePooling with one window: the mean of the plane
     double S = 0.0;
     float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        const uint32_t u = sub + (uint32_t)k * a.S;
-        if (u < a.qv) {
-            float f[EPV];
-            unpack_vec<T>(q[k], f);
-            double s4 = ((double)f[0] + (double)f[1]) + ((double)f[2] + (double)f[3]);
-            mn = fminf(mn, fminf(fminf(f[0], f[1]), fminf(f[2], f[3])));
-            mx = fmaxf(mx, fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])));
-            if constexpr (EPV == 8) {
-                s4 += ((double)f[4] + (double)f[5]) + ((double)f[6] + (double)f[7]);
-                mn = fminf(mn, fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
-                mx = fmaxf(mx, fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
-            }
-            S += s4;
+        const bool valid = sub + (uint32_t)k * a.S < a.qv;
+        float f[EPV];
+        unpack_vec<T>(q[k], f);
+        double s4 = ((double)f[0] + (double)f[1]) + ((double)f[2] + (double)f[3]);
+        float vmn = fminf(fminf(f[0], f[1]), fminf(f[2], f[3]));
+        float vmx = fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3]));
+        if constexpr (EPV == 8) {
+            s4 += ((double)f[4] + (double)f[5]) + ((double)f[6] + (double)f[7]);
+            vmn = fminf(vmn, fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
+            vmx = fmaxf(vmx, fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
         }
+        S += valid ? s4 : 0.0;
+        mn = fminf(mn, valid ? vmn : __builtin_inff());
+        mx = fmaxf(mx, valid ? vmx : -__builtin_inff());
     }
     S = group_sum_any(a.S, S);
     const float lfc = lfc_round<T>(mean_of(S, a.HW), kC16<T>);
@@ -91,44 +106,44 @@ __global__ void __launch_bounds__(64) compress_one(OneArgs a) {
     float delta, Delta, inv;
     plane_scale_any(mn, mx, Lf, kC16<T>, delta, Delta, inv);
     const float invs = inv * (float)(1u << (32 - BITS));
-    const uint32_t k1 = mix32(pc ^ pt.seed_a);
+    const uint32_t k1 = mix32(p ^ pt.seed_a);
     const uint32_t k2 = mix32(k1 + pt.seed_c);
-    uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)pc * a.WPP * 4;
+    uint8_t* cwave = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)p0 * a.WPP * 4;
     if (live && sub == 0) {
         meta_store(pt.meta, p, delta, Delta, kC16<T>);
         lfc_store<T>(pt.lfc, (size_t)p, lfc, kC16<T>);
+        uint8_t* cbase = cwave + (size_t)pl * a.WPP * 4;
         const uint32_t padb = a.WPP * 4 - a.qv * CBV;                 // pad bytes of the last word are zero
         for (uint32_t t = 0; t < padb; ++t) cbase[a.qv * CBV + t] = 0;
     }
     // ---- residual, Quant, packing
+    const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(cwave, 0, (int)(Gc * a.WPP * 4u), 0x00020000);
     const uint32_t rscale = 1u << (16 - BITS);
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const uint32_t u = sub + (uint32_t)k * a.S;
-        if (live && u < a.qv) {
-            float h[EPV];
-            unpack_vec<T>(q[k], h);
+        const uint32_t co = live && u < a.qv ? pl * a.WPP * 4u + u * CBV : kDrop;
+        float h[EPV];
+        unpack_vec<T>(q[k], h);
 #pragma unroll
-            for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lfc;
-            const uint32_t xw0 = k1 + (u * (EPV / 2)) * kWeyl;
-            uint8_t* dst = cbase + u * CBV;
-            if constexpr (CBV <= 4) {
-                uint32_t c = 0;
+        for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lfc;
+        const uint32_t xw0 = k1 + (u * (EPV / 2)) * kWeyl;
+        if constexpr (CBV <= 4) {
+            uint32_t c = 0;
 #pragma unroll
-                for (int j = EPV / 2 - 1; j >= 0; --j)
-                    c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
-                if constexpr (CBV == 1) *dst = (uint8_t)c;
-                else if constexpr (CBV == 2) *reinterpret_cast<uint16_t*>(dst) = (uint16_t)c;
-                else *reinterpret_cast<uint32_t*>(dst) = c;
-            } else {
-                uint32_t lo = 0, hi = 0;
-                hi = push_pair<BITS>(hi, h[6], h[7], delta, invs, xw0 + 3u * kWeyl, k2, rscale);
-                hi = push_pair<BITS>(hi, h[4], h[5], delta, invs, xw0 + 2u * kWeyl, k2, rscale);
-                lo = push_pair<BITS>(lo, h[2], h[3], delta, invs, xw0 + kWeyl, k2, rscale);
-                lo = push_pair<BITS>(lo, h[0], h[1], delta, invs, xw0, k2, rscale);
-                reinterpret_cast<uint32_t*>(dst)[0] = lo;
-                reinterpret_cast<uint32_t*>(dst)[1] = hi;
-            }
+            for (int j = EPV / 2 - 1; j >= 0; --j)
+                c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
+            if constexpr (CBV == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, co, 0, 0);
+            else if constexpr (CBV == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c, crs, co, 0, 0);
+            else __builtin_amdgcn_raw_buffer_store_b32(c, crs, co, 0, 0);
+        } else {
+            uint32_t lo = 0, hi = 0;
+            hi = push_pair<BITS>(hi, h[6], h[7], delta, invs, xw0 + 3u * kWeyl, k2, rscale);
+            hi = push_pair<BITS>(hi, h[4], h[5], delta, invs, xw0 + 2u * kWeyl, k2, rscale);
+            lo = push_pair<BITS>(lo, h[2], h[3], delta, invs, xw0 + kWeyl, k2, rscale);
+            lo = push_pair<BITS>(lo, h[0], h[1], delta, invs, xw0, k2, rscale);
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            __builtin_amdgcn_raw_buffer_store_b64(u32x2{lo, hi}, crs, co, 0, 0);
         }
     }
 }
@@ -140,12 +155,11 @@ __global__ void __launch_bounds__(64) compress_one(OneArgs a) {
 // No LDS.  The planes of a wavefront are contiguous: their vectors are read through one bounds-checked
 // buffer (a lane whose vector lies past its plane reads its neighbour's data or zero and is masked in
 // the arithmetic), codes and H^L leave through bounds-checked buffer stores with the offset pushed out
-// of range where nothing is to be written: no branch depends on a lane, loads and rounds are
-// straight-line code that the compiler is free to interleave.
+// of range where nothing is to be written: no branch depends on a lane or on the round, loads and
+// rounds are straight-line code that the compiler is free to interleave.  K as in compress_one.
 constexpr int kLineUnits = 13;
-template <typename T, int BITS>
+template <typename T, int BITS, int K>
 __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
-    constexpr int K = kLineUnits;
     constexpr uint32_t EPV = 16 / sizeof(T);
     constexpr uint32_t CBV = EPV * BITS / 8;
     constexpr float Lf = float((1 << BITS) - 1);
@@ -153,7 +167,7 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
     const uint32_t tid = threadIdx.x;
     const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
     const uint32_t sub = tid & (a.S - 1u), pl = tid >> a.S_log2;
-    const uint32_t p0 = blockIdx.x * a.ppw;
+    const uint32_t p0 = xcd_run_index(blockIdx.x, gridDim.x) * a.ppw;
     const uint32_t Gc = min(a.ppw, a.P - p0);
     const uint32_t p = p0 + pl;
     const bool live = pl < Gc;
@@ -166,9 +180,9 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
         const uint32_t off0 = live ? (pl * a.qv + sub) * 16u : kDrop;
 #pragma unroll
         for (int k = 0; k < K; ++k) {
-            // rounds past the plane (uniform) are not loaded; a lane past the plane's end inside a round is
-            q[k] = u32x4{0u, 0u, 0u, 0u};
-            if ((uint32_t)k * a.S < a.qv) q[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off0 + (uint32_t)k * a.S * 16u, 0, kLoadAux);
+            // no round is tested (see compress_one); a vector past the plane's end is not fetched
+            const uint32_t u = sub + (uint32_t)k * a.S;
+            q[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, u < a.qv ? off0 + (uint32_t)k * a.S * 16u : kDrop, 0, kLoadAux);
         }
     }
     // ---- AveragePooling1D: block sums over the lanes of a block, residual extremes of the plane
@@ -179,7 +193,6 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
     float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        if ((uint32_t)k * a.S >= a.qv) { lfcv[k] = 0.0f; continue; }          // uniform: no vector of this round exists
         const uint32_t u = sub + (uint32_t)k * a.S;
         const bool valid = u < a.qv;
         float f[EPV];
@@ -223,7 +236,6 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
     const uint32_t rscale = 1u << (16 - BITS);
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        if ((uint32_t)k * a.S >= a.qv) continue;                                 // uniform
         const uint32_t u = sub + (uint32_t)k * a.S;
         const bool wr = live && u < a.qv;
         {

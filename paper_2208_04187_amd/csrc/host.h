@@ -459,6 +459,21 @@ bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
     return true;
 }
 
+// Lanes per plane S (a power of two from min_log up) and rounds K of the instance (3, 6 or 13) for
+// planes of qv vectors: the pair that leaves the fewest of the K * S lane slots empty; among equals
+// the one with more rounds (fewer, longer-lived lanes per plane measured better than many short ones).
+bool pick_lanes_and_rounds(uint64_t qv, uint32_t min_log, uint32_t* S_out, uint32_t* log_out, uint32_t* K_out) {
+    uint64_t best = 0;
+    for (uint32_t lg = min_log; lg <= 6; ++lg) {
+        const uint64_t S = 1ull << lg, R = (qv + S - 1) / S;
+        if (R > 13) continue;
+        const uint64_t K = R <= 3 ? 3 : R <= 6 ? 6 : 13;
+        const uint64_t slots = K * S;
+        if (best == 0 || slots < best || (slots == best && K > *K_out)) { best = slots; *S_out = (uint32_t)S; *log_out = lg; *K_out = (uint32_t)K; }
+    }
+    return best != 0;
+}
+
 // Fills the one-block plan: the block covers the plane, which is whole 16-byte vectors, at most
 // kOneUnits per lane of a wavefront.
 bool plan_one(const Layout& L, size_t es, const void* x, OneArgs* a, uint32_t* grid) {
@@ -466,17 +481,14 @@ bool plan_one(const Layout& L, size_t es, const void* x, OneArgs* a, uint32_t* g
     if (L.nb != 1 || ((uintptr_t)x % 16) != 0 || L.HW % epv != 0) return false;
     const uint64_t qv = L.HW / epv;
     if (qv > (uint64_t)kOneUnits * 64) return false;
-    // lanes per plane: the smallest power of two from 8 up (a plane's lanes then read 128 contiguous
-    // bytes per round) that keeps the plane within kOneUnits rounds
-    uint32_t best_S = 0, best_log = 0;
-    for (uint32_t lg = 3; lg <= 6; ++lg) {
-        const uint64_t S = 1ull << lg;
-        if ((qv + S - 1) / S <= (uint64_t)kLineUnits) { best_S = (uint32_t)S; best_log = lg; break; }
-    }
+    // lanes per plane: a power of two from 4 up (a plane's lanes then read 64 contiguous bytes per round)
+    uint32_t best_S = 0, best_log = 0, K = 0;
+    if (!pick_lanes_and_rounds(qv, 2, &best_S, &best_log, &K)) return false;
     a->P = (uint32_t)L.P; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP;
     a->qv = (uint32_t)qv;
     a->S = best_S; a->S_log2 = best_log;
     a->ppw = 64u / best_S;
+    a->K = K;
     *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
     return true;
 }
@@ -497,16 +509,11 @@ bool plan_line(const Layout& L, int64_t D, int64_t H, int B, size_t es, const vo
     if ((upb & (upb - 1)) != 0 || upb > 64 || qv > (uint64_t)kLineUnits * 64) return false;
     uint32_t upb_log = 0;
     while ((1ull << upb_log) < upb) ++upb_log;
-    // lanes per plane: the smallest power of two that is a block, at least 8 (a plane's lanes then read
-    // 128 contiguous bytes per round) and keeps the plane within kOneUnits rounds: few lanes per plane
-    // mean many planes per wavefront to share its fixed costs (measured: 8 or 16 lanes beat both the
-    // choice with the fewest idle lane slots and wider ones)
-    uint32_t best_S = 0, best_log = 0;
-    for (uint32_t lg = upb_log > 3 ? upb_log : 3; lg <= 6; ++lg) {
-        const uint64_t S = 1ull << lg;
-        if ((qv + S - 1) / S <= (uint64_t)kLineUnits) { best_S = (uint32_t)S; best_log = lg; break; }
-    }
-    if (best_S == 0) return false;
+    // lanes per plane: a power of two that holds a block, at least 8 (a plane's lanes then read 128
+    // contiguous bytes per round)
+    uint32_t best_S = 0, best_log = 0, K = 0;
+    if (!pick_lanes_and_rounds(qv, upb_log > 3 ? upb_log : 3, &best_S, &best_log, &K)) return false;
+    a->K = K;
     a->P = (uint32_t)L.P; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP;
     a->qv = (uint32_t)qv;
     a->S = best_S; a->S_log2 = best_log;
@@ -835,8 +842,16 @@ hipError_t do_compress(const CompLaunch& c, int b) {
             case WAVE: return launch_wave<T, BITS>(c.B, c.vec, c.wa, gd, lds, st);
             case TILE: return launch_tile<T, BITS>(c.B, c.vec, c.a, gd, lds, st);
             case LANE: hipLaunchKernelGGL((compress_lane<T, BITS>), gd, dim3(64), lds, st, c.la); return hipGetLastError();
-            case ONE: hipLaunchKernelGGL((compress_one<T, BITS>), gd, dim3(64), 0, st, c.oa); return hipGetLastError();
-            case LINE: hipLaunchKernelGGL((compress_line<T, BITS>), gd, dim3(64), 0, st, c.oa); return hipGetLastError();
+            case ONE: {
+                void (*kern)(OneArgs) = c.oa.K == 3 ? compress_one<T, BITS, 3> : c.oa.K == 6 ? compress_one<T, BITS, 6> : compress_one<T, BITS, 13>;
+                hipLaunchKernelGGL(kern, gd, dim3(64), 0, st, c.oa);
+                return hipGetLastError();
+            }
+            case LINE: {
+                void (*kern)(OneArgs) = c.oa.K == 3 ? compress_line<T, BITS, 3> : c.oa.K == 6 ? compress_line<T, BITS, 6> : compress_line<T, BITS, 13>;
+                hipLaunchKernelGGL(kern, gd, dim3(64), 0, st, c.oa);
+                return hipGetLastError();
+            }
             case ROWS: {
                 void (*kern)(RowsArgs) = flat ? compress_rows<T, BITS> : compress_rows_3d<T, BITS>;
                 const hipError_t e = allow_large_lds(kern, lds);
@@ -1082,13 +1097,13 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     if (direction == 0) {
         TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; OneArgs oa{}; UnitsArgs ua{}; StripArgs sa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (line_first(L, es) && plan_line(L, D, H, B, es, data, &oa, &grid))
-            n = snprintf(out, cap, "compress_line<%s, %d>", tn, b);
+            n = snprintf(out, cap, "compress_line<%s, %d, %u>", tn, b, oa.K);
         else if (plan_regs(L, D, H, W, B, es, data, &ra, &grid, &lds, &nw))
             n = snprintf(out, cap, "compress_regs%s<%s, %d, %d, %d>", sfx, tn, b, (B == 4 || B == 8) ? B : 0, nw);
         else if (plan_lane(L, es, data, &la, &grid, &lds))
             n = snprintf(out, cap, "compress_lane<%s, %d>", tn, b);
         else if (plan_line(L, D, H, B, es, data, &oa, &grid))
-            n = snprintf(out, cap, "compress_line<%s, %d>", tn, b);
+            n = snprintf(out, cap, "compress_line<%s, %d, %u>", tn, b, oa.K);
         else if (flat && plan_strip(L, H, W, B, es, data, &sa, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_strip<%s, %d, %d, %d>", tn, b, vec / 100, vec % 100);
         else if (flat && plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
@@ -1100,7 +1115,7 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
         else if (flat && plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
             n = snprintf(out, cap, "compress_tile<%s, %d, %d, %d, %d>", tn, b, B, vec, nt);
         else if (plan_one(L, es, data, &oa, &grid))
-            n = snprintf(out, cap, "compress_one<%s, %d>", tn, b);
+            n = snprintf(out, cap, "compress_one<%s, %d, %u>", tn, b, oa.K);
         else if (plan_rows(L, D, H, W, B, b, es, data, &wa2, &grid, &lds))
             n = snprintf(out, cap, "compress_rows%s<%s, %d>", sfx, tn, b);
         else if (plan_plane(L, D, H, W, B, es, data, &pa, &grid, &lds))
