@@ -36,7 +36,10 @@ constexpr int kRegUnits = 13;     // units per lane: planes of up to 13 * (threa
 // what gets compressed, without a second trip through HBM.
 // ND = 3: planes of D x H x W elements with blocks of B x B x B (Appendix D); a unit's block and the
 // units of a block are found with the depth as a third coordinate, everything else is the same.
-template <typename T, int BITS, int B, int NW, bool RELU, int ND = 2>
+// FULL: every one of the K rounds holds units of the plane, so no round is tested (a uniform test per
+// round puts each round into a basic block of its own that waits for every load; the instances that
+// must test because their planes may be short get a second copy of the body for planes that are not).
+template <typename T, int BITS, int B, int NW, bool RELU, int ND = 2, bool FULL = false>
 __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
     constexpr int NT = 64 * NW;
     constexpr int K = kRegUnits;
@@ -55,7 +58,7 @@ __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
     const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
     // rounds of units a plane has (uniform); the one- and four-wavefront instances for B = 4 and 8
     // always run all K (their planes fill at least eight of them)
-    auto round_live = [&](int k) -> bool { return (B != 0 && NW != 16 && ND == 2) || (uint32_t)(NT * k) < a.q4; };
+    auto round_live = [&](int k) -> bool { return FULL || (B != 0 && NW != 16 && ND == 2) || (uint32_t)(NT * k) < a.q4; };
 
     // One plane per workgroup (more workgroups, better balance than several planes each).  Which
     // plane: see xcd_run_index.
@@ -300,8 +303,18 @@ __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
 }
 
 template <typename T, int BITS, int B, int NW>
-__global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) { compress_regs_body<T, BITS, B, NW, false>(a); }
+__global__ void __launch_bounds__(64 * NW) compress_regs(RegsArgs a) {
+    if constexpr (B == 0 || NW == 16) {
+        if ((uint32_t)(64 * NW * (kRegUnits - 1)) < a.q4) compress_regs_body<T, BITS, B, NW, false, 2, true>(a);
+        else compress_regs_body<T, BITS, B, NW, false, 2, false>(a);
+    } else {
+        compress_regs_body<T, BITS, B, NW, false>(a);
+    }
+}
 template <typename T, int BITS, int B, int NW>
 __global__ void __launch_bounds__(64 * NW) relu_compress_regs(RegsArgs a) { compress_regs_body<T, BITS, B, NW, true>(a); }
 template <typename T, int BITS, int B, int NW>
-__global__ void __launch_bounds__(64 * NW) compress_regs_3d(RegsArgs a) { compress_regs_body<T, BITS, B, NW, false, 3>(a); }
+__global__ void __launch_bounds__(64 * NW) compress_regs_3d(RegsArgs a) {
+    if ((uint32_t)(64 * NW * (kRegUnits - 1)) < a.q4) compress_regs_body<T, BITS, B, NW, false, 3, true>(a);
+    else compress_regs_body<T, BITS, B, NW, false, 3, false>(a);
+}
