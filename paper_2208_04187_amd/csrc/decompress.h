@@ -61,24 +61,37 @@ __device__ __forceinline__ void stage_packed(const DecArgs& a, const DecPtrs& pt
                                              float2* s_meta, T* s_lfc, uint32_t tid) {
     const uint32_t nw = Gc * a.WPP;
     const uint32_t* src = pt.codes + (size_t)p0 * a.WPP;
-    if ((((size_t)p0 * a.WPP) & 3u) == 0) {
-        const uint32_t nq = nw >> 2;
-        for (uint32_t i = tid; i < nq; i += kThreads)
-            reinterpret_cast<u32x4*>(s_codes)[i] = reinterpret_cast<const u32x4*>(src)[i];
-        for (uint32_t i = (nq << 2) + tid; i < nw; i += kThreads) s_codes[i] = src[i];
-    } else {
-        for (uint32_t i = tid; i < nw; i += kThreads) s_codes[i] = src[i];
-    }
-    for (uint32_t i = tid; i < Gc; i += kThreads) s_meta[i] = meta_load(pt.meta, p0 + i, kC16<T>);
+    const uint32_t nq = (((size_t)p0 * a.WPP) & 3u) == 0 ? nw >> 2 : 0u;       // 16-byte vectors of code words
     const uint32_t nl = Gc * a.nb;
-    if (sizeof(T) == 4 && kC16<T>) {
-        // bfloat16 H^L of an fp32 map: widened here, so that the streaming loops read floats as ever
-        const uint16_t* lsrc = static_cast<const uint16_t*>(pt.lfc) + (size_t)p0 * a.nb;
-        for (uint32_t i = tid; i < nl; i += kThreads) reinterpret_cast<float*>(s_lfc)[i] = bf16_bits_to_float(lsrc[i]);
-    } else {
-        const T* lsrc = static_cast<const T*>(pt.lfc) + (size_t)p0 * a.nb;
-        for (uint32_t i = tid; i < nl; i += kThreads) s_lfc[i] = lsrc[i];
-    }
+    constexpr bool widen = sizeof(T) == 4 && kC16<T>;      // bfloat16 H^L of an fp32 map: widened here, the streaming loops read floats
+    typedef typename std::conditional<widen, uint16_t, T>::type LT;
+    const LT* lsrc = static_cast<const LT*>(pt.lfc) + (size_t)p0 * a.nb;
+    auto put_lfc = [&](uint32_t i, LT v) {
+        if constexpr (widen) reinterpret_cast<float*>(s_lfc)[i] = bf16_bits_to_float(v);
+        else s_lfc[i] = v;
+    };
+    // the first piece of each of the four slices is fetched before any of them is waited for (one
+    // latency instead of four: a loop that loads and parks, then the next, waits once per loop)
+    const uint32_t iw = (nq << 2) + tid;
+    const bool hq = tid < nq, hw = iw < nw, hm = tid < Gc, hl = tid < nl;
+    u32x4 q0{0u, 0u, 0u, 0u};
+    uint32_t w0 = 0;
+    float2 m0 = make_float2(0.0f, 0.0f);
+    LT l0{};
+    if (hq) q0 = reinterpret_cast<const u32x4*>(src)[tid];
+    if (hw) w0 = src[iw];
+    if (hm) m0 = meta_load(pt.meta, p0 + tid, kC16<T>);
+    if (hl) l0 = lsrc[tid];
+    if (hq) reinterpret_cast<u32x4*>(s_codes)[tid] = q0;
+    if (hw) s_codes[iw] = w0;
+    if (hm) s_meta[tid] = m0;
+    if (hl) put_lfc(tid, l0);
+    // what is left of larger slices
+    for (uint32_t i = tid + kThreads; i < nq; i += kThreads)
+        reinterpret_cast<u32x4*>(s_codes)[i] = reinterpret_cast<const u32x4*>(src)[i];
+    for (uint32_t i = iw + kThreads; i < nw; i += kThreads) s_codes[i] = src[i];
+    for (uint32_t i = tid + kThreads; i < Gc; i += kThreads) s_meta[i] = meta_load(pt.meta, p0 + i, kC16<T>);
+    for (uint32_t i = tid + kThreads; i < nl; i += kThreads) put_lfc(i, lsrc[i]);
     lds_barrier();
 }
 
