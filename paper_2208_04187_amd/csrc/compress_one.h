@@ -11,7 +11,8 @@ struct OneArgs {
     uint32_t ppw;        // planes per wavefront = 64 / S
     uint32_t upb, upb_log2;  // compress_line: vectors per block (power of two, at most S); nb = blocks per plane
     uint32_t nb;
-    uint32_t K;          // rounds of the instance to launch (3, 6 or 13): not read by the kernels
+    uint32_t K;          // rounds of the instance to launch (3, 6, 12 or 13): not read by the kernels
+    uint32_t NG;         // compress_line: groups of 64 / S planes per wavefront (1, or 12 / rounds per plane for tiny planes)
 };
 
 constexpr int kOneUnits = 13;     // vectors per lane: planes of up to 13 * 64 vectors
@@ -158,45 +159,64 @@ __global__ void __launch_bounds__(64) compress_one(OneArgs a) {
 // of range where nothing is to be written: no branch depends on a lane or on the round, loads and
 // rounds are straight-line code that the compiler is free to interleave.  K as in compress_one.
 constexpr int kLineUnits = 13;
-template <typename T, int BITS, int K>
+// NG > 1: planes of at most R = K / NG rounds (a few hundred bytes each): a wavefront takes NG groups of
+// 64 / S planes one after the other, all their loads issued first, so that it has K vectors per lane in
+// flight like the instances for larger planes (two or three would not cover the memory latency).
+template <typename T, int BITS, int K, int NG = 1>
 __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
+    constexpr int R = K / NG;
+    static_assert(R * NG == K, "whole groups");
     constexpr uint32_t EPV = 16 / sizeof(T);
     constexpr uint32_t CBV = EPV * BITS / 8;
     constexpr float Lf = float((1 << BITS) - 1);
     constexpr uint32_t kDrop = 0x80000000u;              // an offset past every buffer here (and no wrap when a round's offset is added): the access is dropped
     const uint32_t tid = threadIdx.x;
     const CompPtrs pt = comp_ptrs(a.tab, a.rg, tid);
-    const uint32_t sub = tid & (a.S - 1u), pl = tid >> a.S_log2;
-    const uint32_t p0 = xcd_run_index(blockIdx.x, gridDim.x) * a.ppw;
-    const uint32_t Gc = min(a.ppw, a.P - p0);
-    const uint32_t p = p0 + pl;
-    const bool live = pl < Gc;
+    const uint32_t sub = tid & (a.S - 1u);
+    const uint32_t ppw = a.ppw * NG;                     // planes of the wavefront
+    const uint32_t p0 = xcd_run_index(blockIdx.x, gridDim.x) * ppw;
+    const uint32_t Gc = min(ppw, a.P - p0);
 
     u32x4 q[K];
     {
         const T* src = static_cast<const T*>(pt.x) + (size_t)p0 * a.HW;
         const __amdgpu_buffer_rsrc_t rsrc =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)(Gc * a.HW * sizeof(T)), 0x00020000);
-        const uint32_t off0 = live ? (pl * a.qv + sub) * 16u : kDrop;
 #pragma unroll
-        for (int k = 0; k < K; ++k) {
-            // no round is tested (see compress_one); a vector past the plane's end is not fetched
-            const uint32_t u = sub + (uint32_t)k * a.S;
-            q[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, u < a.qv ? off0 + (uint32_t)k * a.S * 16u : kDrop, 0, kLoadAux);
+        for (int g = 0; g < NG; ++g) {
+            const uint32_t pl = (uint32_t)g * a.ppw + (tid >> a.S_log2);
+            const uint32_t off0 = pl < Gc ? (pl * a.qv + sub) * 16u : kDrop;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                // no round is tested (see compress_one); a vector past the plane's end is not fetched
+                const uint32_t u = sub + (uint32_t)r * a.S;
+                q[g * R + r] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, u < a.qv ? off0 + (uint32_t)r * a.S * 16u : kDrop, 0, kLoadAux);
+            }
         }
     }
-    // ---- AveragePooling1D: block sums over the lanes of a block, residual extremes of the plane
     // every block but the plane's last has upb vectors: their reciprocals are taken once, not per round
     const uint32_t cnt_full = a.upb * EPV, cnt_last = (a.qv - (a.nb - 1u) * a.upb) * EPV;
     const double rcp_full = 1.0 / (double)cnt_full, rcp_last = 1.0 / (double)cnt_last;
-    float lfcv[K];
+    uint8_t* cwave = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)p0 * a.WPP * 4;
+    const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(cwave, 0, (int)(Gc * a.WPP * 4u), 0x00020000);
+    constexpr uint32_t LB = (sizeof(T) == 2 || kC16<T>) ? 2u : 4u;          // bytes of a cached H^L value
+    const __amdgpu_buffer_rsrc_t lrs = __builtin_amdgcn_make_buffer_rsrc(
+        static_cast<uint8_t*>(pt.lfc) + (size_t)p0 * a.nb * LB, 0, (int)(Gc * a.nb * LB), 0x00020000);
+    const uint32_t rscale = 1u << (16 - BITS);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+    const uint32_t pl = (uint32_t)g * a.ppw + (tid >> a.S_log2);
+    const uint32_t p = p0 + pl;
+    const bool live = pl < Gc;
+    // ---- AveragePooling1D: block sums over the lanes of a block, residual extremes of the plane
+    float lfcv[R];
     float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
+    for (int k = 0; k < R; ++k) {
         const uint32_t u = sub + (uint32_t)k * a.S;
         const bool valid = u < a.qv;
         float f[EPV];
-        unpack_vec<T>(q[k], f);
+        unpack_vec<T>(q[g * R + k], f);
         double s4 = ((double)f[0] + (double)f[1]) + ((double)f[2] + (double)f[3]);
         if constexpr (EPV == 8) s4 += ((double)f[4] + (double)f[5]) + ((double)f[6] + (double)f[7]);
         s4 = valid ? s4 + 0.0 : 0.0;                  // a block of negative zeros sums to +0, as a sum from 0 does
@@ -221,7 +241,6 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
     const float invs = inv * (float)(1u << (32 - BITS));
     const uint32_t k1 = mix32(p ^ pt.seed_a);
     const uint32_t k2 = mix32(k1 + pt.seed_c);
-    uint8_t* cwave = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)p0 * a.WPP * 4;
     if (live && sub == 0) {
         meta_store(pt.meta, p, delta, Delta, kC16<T>);
         uint8_t* cbase = cwave + (size_t)pl * a.WPP * 4;
@@ -229,13 +248,8 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
         for (uint32_t t = 0; t < padb; ++t) cbase[a.qv * CBV + t] = 0;
     }
     // ---- residual, Quant, packing
-    const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(cwave, 0, (int)(Gc * a.WPP * 4u), 0x00020000);
-    constexpr uint32_t LB = (sizeof(T) == 2 || kC16<T>) ? 2u : 4u;          // bytes of a cached H^L value
-    const __amdgpu_buffer_rsrc_t lrs = __builtin_amdgcn_make_buffer_rsrc(
-        static_cast<uint8_t*>(pt.lfc) + (size_t)p0 * a.nb * LB, 0, (int)(Gc * a.nb * LB), 0x00020000);
-    const uint32_t rscale = 1u << (16 - BITS);
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
+    for (int k = 0; k < R; ++k) {
         const uint32_t u = sub + (uint32_t)k * a.S;
         const bool wr = live && u < a.qv;
         {
@@ -245,7 +259,7 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
             else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(lfcv[k]), lrs, lo, 0, 0);
         }
         float h[EPV];
-        unpack_vec<T>(q[k], h);
+        unpack_vec<T>(q[g * R + k], h);
 #pragma unroll
         for (uint32_t e = 0; e < EPV; ++e) h[e] = h[e] - lfcv[k];
         const uint32_t xw0 = k1 + (u * (EPV / 2)) * kWeyl;
@@ -267,5 +281,6 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
             typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
             __builtin_amdgcn_raw_buffer_store_b64(u32x2{lo, hi}, crs, co, 0, 0);
         }
+    }
     }
 }

@@ -489,6 +489,7 @@ bool plan_one(const Layout& L, size_t es, const void* x, OneArgs* a, uint32_t* g
     a->S = best_S; a->S_log2 = best_log;
     a->ppw = 64u / best_S;
     a->K = K;
+    a->NG = 1;
     *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
     return true;
 }
@@ -513,14 +514,17 @@ bool plan_line(const Layout& L, int64_t D, int64_t H, int B, size_t es, const vo
     // contiguous bytes per round)
     uint32_t best_S = 0, best_log = 0, K = 0;
     if (!pick_lanes_and_rounds(qv, upb_log > 3 ? upb_log : 3, &best_S, &best_log, &K)) return false;
-    a->K = K;
+    // planes of at most three rounds: twelve rounds of several plane groups per wavefront
+    const uint32_t R = (uint32_t)((qv + best_S - 1) / best_S);
+    a->NG = K == 3 ? 12u / R : 1u;
+    a->K = K == 3 ? 12u : K;
     a->P = (uint32_t)L.P; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP;
     a->qv = (uint32_t)qv;
     a->S = best_S; a->S_log2 = best_log;
     a->ppw = 64u / best_S;
     a->upb = (uint32_t)upb; a->upb_log2 = upb_log;
     a->nb = (uint32_t)L.nb;
-    *grid = (uint32_t)((L.P + a->ppw - 1) / a->ppw);
+    *grid = (uint32_t)((L.P + (uint64_t)a->ppw * a->NG - 1) / ((uint64_t)a->ppw * a->NG));
     return true;
 }
 
@@ -848,7 +852,8 @@ hipError_t do_compress(const CompLaunch& c, int b) {
                 return hipGetLastError();
             }
             case LINE: {
-                void (*kern)(OneArgs) = c.oa.K == 3 ? compress_line<T, BITS, 3> : c.oa.K == 6 ? compress_line<T, BITS, 6> : compress_line<T, BITS, 13>;
+                void (*kern)(OneArgs) = c.oa.K == 12 ? (c.oa.NG == 12 ? compress_line<T, BITS, 12, 12> : c.oa.NG == 6 ? compress_line<T, BITS, 12, 6> : compress_line<T, BITS, 12, 4>)
+                                      : c.oa.K == 6 ? compress_line<T, BITS, 6> : compress_line<T, BITS, 13>;
                 hipLaunchKernelGGL(kern, gd, dim3(64), 0, st, c.oa);
                 return hipGetLastError();
             }
@@ -1097,13 +1102,13 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     if (direction == 0) {
         TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; OneArgs oa{}; UnitsArgs ua{}; StripArgs sa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (line_first(L, es) && plan_line(L, D, H, B, es, data, &oa, &grid))
-            n = snprintf(out, cap, "compress_line<%s, %d, %u>", tn, b, oa.K);
+            n = snprintf(out, cap, "compress_line<%s, %d, %u, %u>", tn, b, oa.K, oa.NG);
         else if (plan_regs(L, D, H, W, B, es, data, &ra, &grid, &lds, &nw))
             n = snprintf(out, cap, "compress_regs%s<%s, %d, %d, %d>", sfx, tn, b, (B == 4 || B == 8) ? B : 0, nw);
         else if (plan_lane(L, es, data, &la, &grid, &lds))
             n = snprintf(out, cap, "compress_lane<%s, %d>", tn, b);
         else if (plan_line(L, D, H, B, es, data, &oa, &grid))
-            n = snprintf(out, cap, "compress_line<%s, %d, %u>", tn, b, oa.K);
+            n = snprintf(out, cap, "compress_line<%s, %d, %u, %u>", tn, b, oa.K, oa.NG);
         else if (flat && plan_strip(L, H, W, B, es, data, &sa, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_strip<%s, %d, %d, %d>", tn, b, vec / 100, vec % 100);
         else if (flat && plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))

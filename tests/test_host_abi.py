@@ -176,7 +176,7 @@ DISPATCH = [
     ((8, 8, 13, 13), 8, 2, "compress_wave<float, 2, 8, 1>", "decompress_words<float, 2>"),
     ((4, 4, 147, 147), 8, 2, "compress_units<float, 2, 16>", "decompress_units<float, 2, 16>"),
     ((4, 4, 30, 30), 4, 2, "compress_wave<float, 2, 4, 2>", "decompress_table<float, 2>"),
-    ((2, 2, 1, 768), 8, 4, "compress_line<float, 4, 6>", "decompress_stream<float, 4>"),
+    ((2, 2, 1, 768), 8, 4, "compress_line<float, 4, 6, 1>", "decompress_stream<float, 4>"),
     ((5, 33, 14, 14), 12, 4, "compress_strip<float, 4, 14, 12>", "decompress_table<float, 4>"),
     ((5, 33, 24, 24), 18, 4, "compress_rows<float, 4>", "decompress_table<float, 4>"),
     ((1, 1, 300, 300), 18, 2, "compress_any<float, 2>", "decompress_scalar<float, 2>"),
