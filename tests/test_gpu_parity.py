@@ -685,6 +685,13 @@ LINE_CASES = [
     ((5, 3, 1, 200), 8, 2),             # 50 vectors
     ((70, 3, 1, 24), 4, 4),             # tiny planes: 6 vectors, 8 lanes per plane, ragged last wavefront
     ((4, 4, 1, 1024), 64, 4),
+    # token vectors of a Swin-T under its B = 64: 96 / 192 wide (two / three rounds, several plane groups per
+    # wavefront, 9408 planes: XCD-aware order and its tail), 384 / 768 wide (six rounds)
+    ((3, 3136, 1, 96), 64, 2),
+    ((5, 157, 1, 192), 64, 4),
+    ((7, 13, 1, 384), 64, 2),
+    ((5, 49, 1, 768), 64, 8),
+    ((3, 7, 1, 1536), 64, 2),
 ]
 
 
