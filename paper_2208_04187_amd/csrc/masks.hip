@@ -311,6 +311,85 @@ __global__ void __launch_bounds__(kThreads) maxpool_forward_kernel(PoolArgs a) {
     }
 }
 
+// Forward, k = 2 on rows of whole 8-element pieces (W % 8 == 0, H * W a multiple of 32, 16-byte aligned
+// x): a thread takes four adjacent windows, i.e. eight consecutive elements of two rows (two 16-byte loads
+// per row for 4-byte elements, one for 2-byte ones), writes their four maxima with one store and the eight
+// location bits of each row as one byte of the LDS image of the band's mask slice: bytes have one owner, so
+// there is no atomic, and a band of an even number of output rows is whole mask words, so the slice leaves
+// with plain stores and the mask needs no clearing beforehand.  The last band of a plane also writes the
+// (zero) bits of an odd last row.
+template <typename T>
+__global__ void __launch_bounds__(kThreads) maxpool2_forward_fast(PoolArgs a) {
+    extern __shared__ uint32_t words[];
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    constexpr uint32_t EPV = 16 / sizeof(T);             // elements per 16-byte load
+    const uint32_t tid = threadIdx.x;
+    const uint32_t p = blockIdx.x / a.bands;
+    const uint32_t bnd = blockIdx.x - p * a.bands;
+    const uint32_t oi0 = bnd * a.band;
+    const uint32_t oi1 = min(a.OH, oi0 + a.band);
+    const uint32_t r0 = 2u * oi0;
+    const uint32_t r1 = bnd + 1 == a.bands ? a.H : 2u * oi1;                 // input rows [r0, r1) belong to this band
+    const uint64_t w0 = ((uint64_t)p * a.HW + (uint64_t)r0 * a.W) >> 5;      // first word of the slice (whole words)
+    const uint32_t nwords = (r1 - r0) * a.W / 32u;
+    for (uint32_t w = tid; w < nwords; w += kThreads) words[w] = 0u;
+    __syncthreads();
+    uint8_t* bytes = reinterpret_cast<uint8_t*>(words);
+    const T* xp = static_cast<const T*>(a.in) + (size_t)p * a.HW;
+    T* yp = static_cast<T*>(a.out) + (size_t)p * a.OH * a.OW;
+    const uint32_t ow4 = a.OW / 4u;
+    const uint32_t n4 = (oi1 - oi0) * ow4;
+    for (uint32_t o4 = tid; o4 < n4; o4 += kThreads) {
+        const uint32_t r = o4 / ow4;
+        const uint32_t oj4 = o4 - r * ow4;
+        const uint32_t oi = oi0 + r;
+        const uint32_t base = 2u * oi * a.W + oj4 * 8u;                    // first of the eight elements, upper row
+        uint32_t e0[8], e1[8];                                              // the two rows as fp32 bit patterns
+        if constexpr (sizeof(T) == 4) {
+            const u32x4 a0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xp + base));
+            const u32x4 a1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xp + base + 4));
+            const u32x4 b0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xp + base + a.W));
+            const u32x4 b1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xp + base + a.W + 4));
+            e0[0] = a0.x; e0[1] = a0.y; e0[2] = a0.z; e0[3] = a0.w; e0[4] = a1.x; e0[5] = a1.y; e0[6] = a1.z; e0[7] = a1.w;
+            e1[0] = b0.x; e1[1] = b0.y; e1[2] = b0.z; e1[3] = b0.w; e1[4] = b1.x; e1[5] = b1.y; e1[6] = b1.z; e1[7] = b1.w;
+        } else {
+            const u32x4 a0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xp + base));
+            const u32x4 b0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xp + base + a.W));
+            const uint32_t wa[4] = {a0.x, a0.y, a0.z, a0.w}, wb[4] = {b0.x, b0.y, b0.z, b0.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                e0[2 * j] = wa[j] << 16; e0[2 * j + 1] = wa[j] & 0xffff0000u;
+                e1[2 * j] = wb[j] << 16; e1[2 * j + 1] = wb[j] & 0xffff0000u;
+            }
+        }
+        (void)EPV;
+        uint32_t m[4], byte0 = 0, byte1 = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            // first maximum in row-major order: a later element wins only if it compares greater
+            uint32_t best = e0[2 * j], loc = 0;
+            if (__uint_as_float(e0[2 * j + 1]) > __uint_as_float(best)) { best = e0[2 * j + 1]; loc = 1; }
+            if (__uint_as_float(e1[2 * j]) > __uint_as_float(best)) { best = e1[2 * j]; loc = 2; }
+            if (__uint_as_float(e1[2 * j + 1]) > __uint_as_float(best)) { best = e1[2 * j + 1]; loc = 3; }
+            m[j] = best;
+            byte0 |= (loc < 2 ? 1u << loc : 0u) << (2 * j);
+            byte1 |= (loc >= 2 ? 1u << (loc - 2) : 0u) << (2 * j);
+        }
+        if constexpr (sizeof(T) == 4) {
+            __builtin_nontemporal_store(u32x4{m[0], m[1], m[2], m[3]}, reinterpret_cast<u32x4*>(yp + oi * a.OW + oj4 * 4u));
+        } else {
+            __builtin_nontemporal_store(u32x2{(m[0] >> 16) | (m[1] & 0xffff0000u), (m[2] >> 16) | (m[3] & 0xffff0000u)},
+                                        reinterpret_cast<u32x2*>(yp + oi * a.OW + oj4 * 4u));
+        }
+        const uint32_t b0i = (2u * r * a.W + oj4 * 8u) >> 3;               // byte of the slice that holds the upper row's eight bits
+        bytes[b0i] = (uint8_t)byte0;
+        bytes[b0i + (a.W >> 3)] = (uint8_t)byte1;
+    }
+    __syncthreads();
+    for (uint32_t w = tid; w < nwords; w += kThreads) a.mask[w0 + w] = words[w];
+}
+
 // Backward: grad_in = V (.) (1_{k x k} (x) grad_out).  VEC = 4: a thread takes four consecutive
 // elements of one row per step (W % 4 == 0, grad_in 16-byte resp. 8-byte aligned): one 16-byte
 // store, one mask word read.  VEC = 1: element by element.
@@ -345,6 +424,40 @@ __global__ void __launch_bounds__(kThreads) maxpool_backward_kernel(PoolArgs a) 
             op[i] = v[0];
         }
     }
+}
+
+// Backward, k = 2 on rows of whole 4-element pieces (W % 4 == 0, 16-byte aligned grad_in, 8-byte aligned
+// grad_out): a thread rebuilds four consecutive elements of one row, which lie under two adjacent windows:
+// one mask word, one load of the two output gradients, one non-temporal 16-byte store; a workgroup of
+// one... four wavefronts writes 4 KB and ends (what a write stream wants here).
+template <typename T>
+__global__ void __launch_bounds__(kThreads) maxpool2_backward_fast(PoolArgs a) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const uint32_t p = blockIdx.y;
+    const T* gp = static_cast<const T*>(a.in) + (size_t)p * a.OH * a.OW;
+    T* op = static_cast<T*>(a.out) + (size_t)p * a.HW;
+    const uint32_t vi = blockIdx.x * kThreads + threadIdx.x;
+    if (vi >= a.HW / 4u) return;
+    const uint32_t w4 = a.W / 4u;
+    const uint32_t r = vi / w4;
+    const uint32_t c = (vi - r * w4) * 4u;
+    const uint64_t bit = (uint64_t)p * a.HW + (uint64_t)vi * 4u;
+    const uint32_t bits = (a.mask[bit >> 5] >> (uint32_t)(bit & 31u)) & 15u;
+    // a row past the last whole window has no bits set: any row's gradients will do for the address
+    const uint32_t oi = min(r >> 1, a.OH - 1u);
+    const T* g = gp + oi * a.OW + (c >> 1);
+    uint32_t g0, g1;                                   // the two gradients as raw element bits
+    if constexpr (sizeof(T) == 4) {
+        const u32x2 v = *reinterpret_cast<const u32x2*>(g);
+        g0 = v.x; g1 = v.y;
+    } else {
+        const uint32_t v = *reinterpret_cast<const uint32_t*>(g);
+        g0 = v & 0xffffu; g1 = v >> 16;
+    }
+    const uint32_t o0 = bits & 1u ? g0 : 0u, o1 = bits & 2u ? g0 : 0u, o2 = bits & 4u ? g1 : 0u, o3 = bits & 8u ? g1 : 0u;
+    if constexpr (sizeof(T) == 4) __builtin_nontemporal_store(u32x4{o0, o1, o2, o3}, reinterpret_cast<u32x4*>(op + (size_t)vi * 4u));
+    else __builtin_nontemporal_store(u32x2{o0 | (o1 << 16), o2 | (o3 << 16)}, reinterpret_cast<u32x2*>(op + (size_t)vi * 4u));
 }
 
 int pool_args(bool forward, const void* in, void* out, const void* mask, int64_t N, int64_t C, int64_t H, int64_t W,
@@ -393,6 +506,30 @@ int division_maxpool_forward(const void* x, int64_t N, int64_t C, int64_t H, int
     const int rc = pool_args(true, x, y, mask, N, C, H, W, dt, k, mask_capacity, &a);
     if (rc != DIVISION_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const size_t esz = dt == DIVISION_BF16 ? 2 : 4;
+    if (k == 2 && a.OH > 0 && a.W % 8 == 0 && a.HW % 32 == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)y % (4 * esz)) == 0) {
+        // bands of an even number of output rows (whole mask words), at most 64 Ki bits, enough of them to fill the machine
+#ifndef DIVISION_POOL_WG_BYTES
+#define DIVISION_POOL_WG_BYTES 8192
+#endif
+        // about 8 KB of x per workgroup (short-lived workgroups, many of them), at most 64 Ki mask bits
+        uint32_t band = (uint32_t)(DIVISION_POOL_WG_BYTES / (2ull * a.W * esz)) & ~1u;
+        if (band < 2) band = 2;
+        if (2ull * band * a.W > 65536) band = (uint32_t)(65536 / (2ull * a.W)) & ~1u;
+        if (band < 2) band = 0;
+        if (band >= 2) {
+            a.band = band;
+            a.bands = (a.OH + band - 1) / band;
+            const uint64_t grid = (uint64_t)a.P * a.bands;
+            // the last band of a plane also holds an odd last row
+            const size_t lds = ((size_t)(band + 1) * 2 * a.W) / 8 + 16;
+            if (grid <= 0x7fffffffull) {
+                void (*kern)(PoolArgs) = dt == DIVISION_F32 ? maxpool2_forward_fast<float> : maxpool2_forward_fast<uint16_t>;
+                hipLaunchKernelGGL(kern, dim3((uint32_t)grid), dim3(kThreads), lds, st, a);
+                return hipGetLastError() == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
+            }
+        }
+    }
     const uint64_t nwords = ((uint64_t)a.P * a.HW + 31) / 32;
     const uint32_t zgrid = (uint32_t)((nwords + kThreads * 8ull - 1) / (kThreads * 8ull));
     hipLaunchKernelGGL(zero_words, dim3(zgrid < 1 ? 1 : zgrid), dim3(kThreads), 0, st, a.mask, nwords);
@@ -426,6 +563,12 @@ int division_maxpool_backward(const void* mask, size_t mask_bytes, const void* g
     if (rc != DIVISION_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const size_t esz = dt == DIVISION_BF16 ? 2 : 4;
+    if (k == 2 && a.OH > 0 && a.OW > 0 && a.W % 4 == 0 && ((uintptr_t)grad_in % (4 * esz)) == 0 && ((uintptr_t)grad_out % (2 * esz)) == 0 &&
+        a.P <= 65535u) {
+        void (*fast)(PoolArgs) = dt == DIVISION_F32 ? maxpool2_backward_fast<float> : maxpool2_backward_fast<uint16_t>;
+        hipLaunchKernelGGL(fast, dim3((a.HW / 4 + kThreads - 1) / kThreads, a.P), dim3(kThreads), 0, st, a);
+        return hipGetLastError() == hipSuccess ? DIVISION_OK : DIVISION_EHIP;
+    }
     const bool vec4 = a.W % 4 == 0 && ((uintptr_t)grad_in % (4 * esz)) == 0;
     void (*kern)(PoolArgs);
     if (dt == DIVISION_F32) kern = vec4 ? maxpool_backward_kernel<float, 4> : maxpool_backward_kernel<float, 1>;

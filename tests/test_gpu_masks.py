@@ -101,7 +101,11 @@ def test_mask_errors_and_empty_input():
 
 MP_CASES = [((2, 3, 8, 8), 2), ((1, 2, 9, 7), 2), ((2, 2, 12, 9), 3), ((1, 1, 5, 5), 1), ((3, 1, 4, 6), 4),
             ((2, 5, 112, 112), 2), ((2, 1, 7, 7), 7), ((1, 1, 10, 13), 5), ((70, 33, 14, 14), 2),
-            ((1, 1, 3, 3), 4), ((1, 2, 600, 300), 2), ((2, 3, 56, 56), 3)]
+            ((1, 1, 3, 3), 4), ((1, 2, 600, 300), 2), ((2, 3, 56, 56), 3),
+            # k = 2 on rows of whole 8-element pieces: four windows per thread, mask bytes with one owner
+            ((5, 7, 56, 56), 2), ((3, 2, 11, 32), 2),      # the second: an odd last row, written (as zeros) by the last band
+            ((4, 3, 4, 8), 2), ((2, 2, 64, 40), 2), ((1, 2, 600, 304), 2), ((300, 9, 8, 16), 2),
+            ((2, 3, 30, 24), 2), ((3, 2, 9, 16), 2)]        # H * W no multiple of 32: the general forward kernel, the fast backward one
 
 
 @pytest.mark.parametrize("shape,k", MP_CASES)
