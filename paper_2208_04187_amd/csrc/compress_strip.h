@@ -244,5 +244,5 @@ __device__ __forceinline__ void compress_strip_body(const StripArgs& a) {
 
 template <typename T, int BITS, int W, int B>
 __global__ void __launch_bounds__(64) compress_strip(StripArgs a) { compress_strip_body<T, BITS, W, B, false>(a); }
-template <typename T, int BITS, int W>
-__global__ void __launch_bounds__(64) relu_compress_strip(StripArgs a) { compress_strip_body<T, BITS, W, 8, true>(a); }
+template <typename T, int BITS, int W, int B>
+__global__ void __launch_bounds__(64) relu_compress_strip(StripArgs a) { compress_strip_body<T, BITS, W, B, true>(a); }

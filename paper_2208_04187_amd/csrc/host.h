@@ -357,14 +357,24 @@ hipError_t launch_strip(int width, const StripArgs& a, dim3 grid, size_t lds, hi
 // The Relu + compress instance of the strip kernel; a round's mask bits must be whole words.
 bool plan_relu_strip(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* xy,
                      StripArgs* a, uint32_t* grid, size_t* lds, int* width) {
-    if (B != 8 || (W != 28 && W != 14) || !plan_strip(L, H, W, B, es, xy, a, grid, lds, width)) return false;
-    const uint64_t G = W == 28 ? 2 : 8;
+    // the instances whose block sums are DPP reductions: B = 8 on every strip width, B = 4 on 32 / 16
+    if ((B != 8 && B != 4) || !plan_strip(L, H, W, B, es, xy, a, grid, lds, width)) return false;
+    const uint64_t G = (W == 28 || W == 32) ? 2 : 8;
     return (G * L.HW) % 32 == 0;
 }
 
 template <typename T, int BITS>
 hipError_t launch_relu_strip(int width, const StripArgs& a, dim3 grid, size_t lds, hipStream_t st) {
-    void (*kern)(StripArgs) = width == 2808 ? relu_compress_strip<T, BITS, 28> : relu_compress_strip<T, BITS, 14>;
+    void (*kern)(StripArgs);
+    switch (width) {
+        case 2808: kern = relu_compress_strip<T, BITS, 28, 8>; break;
+        case 1408: kern = relu_compress_strip<T, BITS, 14, 8>; break;
+        case 3208: kern = relu_compress_strip<T, BITS, 32, 8>; break;
+        case 1608: kern = relu_compress_strip<T, BITS, 16, 8>; break;
+        case 3204: kern = relu_compress_strip<T, BITS, 32, 4>; break;
+        case 1604: kern = relu_compress_strip<T, BITS, 16, 4>; break;
+        default: return hipErrorInvalidValue;
+    }
     hipLaunchKernelGGL(kern, grid, dim3(64), lds, st, a);
     return hipGetLastError();
 }

@@ -148,6 +148,10 @@ def test_maxpool_matches_oracle(shape, k, dtype):
     ((3, 5, 12, 28), 8, 4, True),        # 28-wide, 12 rows: 672 bits per round
     ((3, 5, 30, 28), 8, 2, True),        # 28-wide, 30 rows: rounds are not whole mask words -> the items kernel
     ((7, 3, 6, 14), 8, 2, True),         # 14-wide, 6 rows, 21 planes
+    ((3, 5, 32, 32), 8, 2, True),        # the CIFAR widths in the strip kernel: B = 8 and B = 4
+    ((5, 3, 16, 16), 8, 4, True),
+    ((3, 5, 20, 32), 4, 2, True),        # ragged: 20 rows
+    ((3, 5, 10, 16), 4, 8, True),
     ((6, 5, 32, 32), 4, 2, True),        # CIFAR shapes: whole mask words per plane
     ((3, 7, 16, 16), 4, 8, True),
     ((5, 3, 8, 8), 4, 2, True),
