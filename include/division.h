@@ -275,9 +275,9 @@ int division_decompress_3d(const void *packed, size_t packed_bytes, int64_t N, i
  * next layer's: Appendix, Relu listing, and Sec. 4.1).  Equivalent to division_relu_forward(x -> y,
  * mask) followed by division_compress(y -> packed), with the same outputs bit for bit; for the
  * shapes division_relu_compress_fused reports (B = 4 or 8, 16-byte aligned x and y; planes of
- * 2048-3328 or 8192-13312 elements in whole 32-element mask words, the 28- and 14-wide planes
- * of at most 32 resp. 16 rows under B = 8, and the small planes of at most 64 pooling items of
- * B rows by 2 or 4 columns: the CIFAR shapes) one kernel does both and y does not travel through HBM a second time.  Other shapes run the two
+ * 2048-3328 or 8192-13312 elements in whole 32-element mask words, the 28- / 32-wide planes of
+ * at most 32 rows and the 14- / 16-wide ones of at most 16 under B = 8 (32, 16: also B = 4), and
+ * the other small planes of at most 64 pooling items of B rows by 2 or 4 columns) one kernel does both and y does not travel through HBM a second time.  Other shapes run the two
  * kernels one after the other.  y may be x itself (in place); arguments as for the two calls it replaces.
  */
 int division_relu_compress(const void *x, int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt,
