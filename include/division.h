@@ -54,7 +54,7 @@ typedef enum { DIVISION_F32 = 0, DIVISION_BF16 = 1, DIVISION_F32_C16 = 2 } divis
 /* Return codes of every int-returning entry point. */
 enum {
     DIVISION_OK     = 0,
-    DIVISION_EINVAL = 1,  /* null pointer, N/C/H/W <= 0, B < 1, b not in {2,4,8}, unknown dtype */
+    DIVISION_EINVAL = 1,  /* null pointer, N/C/H/W <= 0, B < 1, b not in {1,2,4,8}, unknown dtype */
     DIVISION_ESIZE  = 2,  /* packed buffer smaller than division_packed_bytes(...)             */
     DIVISION_EALIGN = 3,  /* x / xhat not aligned to the element size, packed not to 16 bytes  */
     DIVISION_ERANGE = 4,  /* N*C or H*W above 2^31-1, or N*C*H*W above 2^40                    */
@@ -96,7 +96,7 @@ int division_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W,
  *           smaller than B are pooled to 1x1 (footnote of Sec. 4.1); when B
  *           does not divide H or W the border windows average their valid
  *           elements only.
- *   b       bits per HFC code (the paper's Q): 2, 4 or 8.
+ *   b       bits per HFC code (the paper's Q): 2, 4 or 8 in the fast kernels; 1 is served by the general kernels only (slow).
  *   seed    selects the stochastic-rounding stream of Eq. (quantization); the
  *           output is a pure function of (x, shape, dt, B, b, seed) and does
  *           not depend on the launch geometry or the device.

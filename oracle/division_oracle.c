@@ -194,7 +194,7 @@ typedef struct {
 /* A plane is D x H x W (Appendix D, 3-D maps); D = 1 is the 2-D map of Sec. 4.1, D = H = 1 the 1-D one. */
 static int make_layout(int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int B, int b, int dt, layout_t *L)
 {
-    if (N <= 0 || C <= 0 || D <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4 && b != 8))
+    if (N <= 0 || C <= 0 || D <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 1 && b != 2 && b != 4 && b != 8))
         return 1;
     if (dt != ORACLE_F32 && dt != ORACLE_BF16 && dt != ORACLE_F32_C16)
         return 1;

@@ -231,7 +231,7 @@ int division_relu_compress(const void* x, int64_t N, int64_t C, int64_t H, int64
     size_t lds = 0;
     int nw = 1;
     const void* both = reinterpret_cast<const void*>((uintptr_t)x | (uintptr_t)y);
-    if (L.HW % 32 == 0 && (B == 4 || B == 8) && plan_regs(L, 1, H, W, B, es, both, &ra, &grid, &lds, &nw) && nw <= 4) {
+    if (b != 1 && L.HW % 32 == 0 && (B == 4 || B == 8) && plan_regs(L, 1, H, W, B, es, both, &ra, &grid, &lds, &nw) && nw <= 4) {
         ra.tab.x[0] = x;
         ra.tab.pk[0] = packed;
         ra.tab.seed_a[0] = mix32((uint32_t)(seed & 0xffffffffu) ^ 0x243F6A88u);
@@ -248,7 +248,7 @@ int division_relu_compress(const void* x, int64_t N, int64_t C, int64_t H, int64
     StripArgs sa{};
     int vec = 1;
     const int Bc = covering_block(L, 1, H, W, B);
-    if (plan_relu_strip(L, H, W, Bc, es, both, &sa, &grid, &lds, &vec)) {
+    if (b != 1 && plan_relu_strip(L, H, W, Bc, es, both, &sa, &grid, &lds, &vec)) {
         sa.tab.x[0] = x;
         sa.tab.pk[0] = packed;
         sa.tab.seed_a[0] = mix32((uint32_t)(seed & 0xffffffffu) ^ 0x243F6A88u);
@@ -263,7 +263,7 @@ int division_relu_compress(const void* x, int64_t N, int64_t C, int64_t H, int64
     }
     // and the other small planes of the items kernel (the CIFAR shapes)
     ItemsArgs ia{};
-    if ((Bc == 4 || Bc == 8) && plan_relu_items(L, H, W, Bc, es, both, &ia, &grid, &lds, &vec)) {
+    if (b != 1 && (Bc == 4 || Bc == 8) && plan_relu_items(L, H, W, Bc, es, both, &ia, &grid, &lds, &vec)) {
         ia.tab.x[0] = x;
         ia.tab.pk[0] = packed;
         ia.tab.seed_a[0] = mix32((uint32_t)(seed & 0xffffffffu) ^ 0x243F6A88u);
@@ -285,7 +285,7 @@ int division_relu_compress(const void* x, int64_t N, int64_t C, int64_t H, int64
 
 int division_relu_compress_fused(int64_t N, int64_t C, int64_t H, int64_t W, division_dtype dt, int B, int b) {
     Layout L;
-    if (make_layout(N, C, 1, H, W, B, b, (int)dt, &L) != DIVISION_OK) return 0;
+    if (make_layout(N, C, 1, H, W, B, b, (int)dt, &L) != DIVISION_OK || b == 1) return 0;
     RegsArgs ra{};
     uint32_t grid = 0;
     size_t lds = 0;

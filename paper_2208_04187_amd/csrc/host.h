@@ -11,7 +11,7 @@ size_t align16(size_t v) { return (v + 15u) & ~(size_t)15u; }
 
 // A plane is D x H x W elements (Appendix D: 3-D maps); D = 1 for the 2-D maps of Sec. 4.1.
 int make_layout(int64_t N, int64_t C, int64_t D, int64_t H, int64_t W, int B, int b, int dt, Layout* L) {
-    if (N <= 0 || C <= 0 || D <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 2 && b != 4 && b != 8)) return DIVISION_EINVAL;
+    if (N <= 0 || C <= 0 || D <= 0 || H <= 0 || W <= 0 || B < 1 || (b != 1 && b != 2 && b != 4 && b != 8)) return DIVISION_EINVAL;
     if (dt != DIVISION_F32 && dt != DIVISION_BF16 && dt != DIVISION_F32_C16) return DIVISION_EINVAL;
     const uint64_t lim31 = 0x7fffffffull;
     if ((uint64_t)N > lim31 || (uint64_t)C > lim31 || (uint64_t)D > lim31 || (uint64_t)H > lim31 || (uint64_t)W > lim31)
@@ -846,6 +846,12 @@ hipError_t do_compress(const CompLaunch& c, int b) {
     hipStream_t st = c.st;
     const size_t lds = c.lds;
     const bool flat = c.flat != 0;
+    if (b == 1) {
+        // 1-bit codes: the general kernel only (the planner picks nothing else)
+        void (*kern)(AnyArgs) = flat ? compress_any<T, 1> : compress_any_3d<T, 1>;
+        hipLaunchKernelGGL(kern, gd, dim3(kThreads), 0, st, c.g);
+        return hipGetLastError();
+    }
     return with_bits(b, [&](auto bits) -> hipError_t {
         constexpr int BITS = decltype(bits)::value;
         switch (c.kind) {
@@ -892,6 +898,11 @@ hipError_t do_compress(const CompLaunch& c, int b) {
 
 template <typename T>
 hipError_t do_decompress(const DecLaunch& c, int b) {
+    if (b == 1) {
+        void (*kern)(DecArgs) = c.flat ? decompress_scalar<T, 1> : decompress_scalar_3d<T, 1>;
+        hipLaunchKernelGGL(kern, dim3(c.gx, c.gy), dim3(kThreads), 0, c.st, c.a);
+        return hipGetLastError();
+    }
     return with_bits(b, [&](auto bits) -> hipError_t {
         constexpr int BITS = decltype(bits)::value;
         const int kind = c.kind;
@@ -1025,7 +1036,15 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         int vec = 1, nt = 64, nw = 1;
         CompKind kind;
         const bool flat = D == 1;               // the register, item, wavefront and tile kernels take 2-D maps
-        if (line_first(L, es) && plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
+        auto use_any = [&]() {
+            kind = ANY;
+            g.tab = tab; g.rg = rg;
+            g.P = (uint32_t)L.P; g.H = (uint32_t)H; g.W = (uint32_t)W; g.HW = (uint32_t)L.HW; g.D = (uint32_t)D;
+            g.LH = (uint32_t)L.LH; g.LW = (uint32_t)L.LW; g.nb = (uint32_t)L.nb; g.WPP = (uint32_t)L.WPP; g.B = (uint32_t)B;
+            grid = (uint32_t)L.P;
+        };
+        if (b == 1) use_any();                  // 1-bit codes (Q = 1): the general kernel, whatever the shape
+        else if (line_first(L, es) && plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
         else if (plan_regs(L, D, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
         else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
         else if (plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
@@ -1038,13 +1057,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         else if (plan_one(L, es, xa, &oa, &grid)) { kind = ONE; oa.tab = tab; oa.rg = rg; lds = 0; }
         else if (plan_rows(L, D, H, W, B, b, es, xa, &wa2, &grid, &lds)) { kind = ROWS; wa2.tab = tab; wa2.rg = rg; }
         else if (plan_plane(L, D, H, W, B, es, xa, &pa, &grid, &lds)) { kind = PLANE; pa.tab = tab; pa.rg = rg; }
-        else {
-            kind = ANY;
-            g.tab = tab; g.rg = rg;
-            g.P = (uint32_t)L.P; g.H = (uint32_t)H; g.W = (uint32_t)W; g.HW = (uint32_t)L.HW; g.D = (uint32_t)D;
-            g.LH = (uint32_t)L.LH; g.LW = (uint32_t)L.LW; g.nb = (uint32_t)L.nb; g.WPP = (uint32_t)L.WPP; g.B = (uint32_t)B;
-            grid = (uint32_t)L.P;
-        }
+        else use_any();
         CompLaunch c{};
         c.kind = kind; c.B = B; c.vec = vec; c.nt = nt; c.nw = nw; c.flat = flat;
         c.gx = grid; c.gy = (uint32_t)cnt; c.lds = lds; c.st = st;
@@ -1079,7 +1092,8 @@ int decompress_impl(int count, const void* const* packed, void* const* xhat, siz
         const int cnt = count - i0 < kMaxBatch ? count - i0 : kMaxBatch;
         DecArgs a{};
         uint32_t grid = 0;
-        const int kind = plan_decompress(L, D, H, W, B, es, reinterpret_cast<const void*>(all_out ? all_out : 16), &a, &grid);
+        int kind = plan_decompress(L, D, H, W, B, es, reinterpret_cast<const void*>(all_out ? all_out : 16), &a, &grid);
+        if (b == 1) { kind = 2; a.G = 1; grid = (uint32_t)L.P; }      // 1-bit codes: the element-per-thread kernel
         for (int i = 0; i < cnt; ++i) { a.tab.pk[i] = packed[i0 + i]; a.tab.xhat[i] = xhat[i0 + i]; }
         a.rg = rg;
         // LDS of the streaming kernels: staged codes, meta and LFC of G planes (+ the block table)
@@ -1109,7 +1123,9 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     const size_t es = dt == DIVISION_BF16 ? 2 : 4;
     const char* tn = dt == DIVISION_BF16 ? "bf16_t" : dt == DIVISION_F32_C16 ? "f32c16_t" : "float";
     int n;
-    if (direction == 0) {
+    if (b == 1)
+        n = snprintf(out, cap, "%s%s<%s, 1>", direction == 0 ? "compress_any" : "decompress_scalar", sfx, tn);
+    else if (direction == 0) {
         TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; OneArgs oa{}; UnitsArgs ua{}; StripArgs sa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (line_first(L, es) && plan_line(L, D, H, B, es, data, &oa, &grid))
             n = snprintf(out, cap, "compress_line<%s, %d, %u, %u>", tn, b, oa.K, oa.NG);

@@ -437,6 +437,21 @@ def test_bfloat16_map_is_rebuilt_with_round_to_nearest_even():
         assert torch.equal(y.cpu().view(torch.int16).reshape(6, -1)[pl], want.view(torch.int16))
 
 
+# 1-bit codes (Q = 1): served by the general kernels whatever the shape
+@pytest.mark.parametrize("shape,B", [((3, 5, 56, 56), 8), ((2, 3, 28, 28), 8), ((5, 7, 7, 7), 8), ((2, 9, 1, 96), 64),
+                                     ((2, 3, 55, 55), 4), ((3, 2, 33, 17), 12), ((1, 1, 1, 1), 8), ((2, 2, 100, 37), 8)])
+@pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
+def test_one_bit_codes_match_oracle(shape, B, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    assert pkg.division_kernel_name(0, shape, B, 1, dtype, c16=mode == "c16").startswith("compress_any<")
+    assert pkg.division_kernel_name(1, shape, B, 1, dtype, c16=mode == "c16").startswith("decompress_scalar<")
+    _check_variant(shape, B, 1, mode)
+    # and the ratio the codec was asked for: one bit per element + H^L + scale
+    n = shape[0] * shape[1] * shape[2] * shape[3]
+    if n >= 1024:
+        assert pkg.division_packed_bytes(*shape, B, 1, dtype, mode == "c16") < n * (2 if mode == "bf16" else 4) / 4
+
+
 # block sizes and ragged edges that give blocks of 98, 196, 198 or 150 elements: counts whose binary64 reciprocal, times the
 # sum, lands beside an exact tie instead of on it
 @pytest.mark.parametrize("shape,B", [((4, 6, 56, 56), 14), ((4, 6, 28, 28), 14), ((4, 6, 14, 14), 16), ((4, 6, 14, 14), 64),

@@ -47,6 +47,29 @@ def test_worked_example_2x2_b2():
         assert np.array_equal(xh, x)
 
 
+def test_worked_example_1bit_codes():
+    # Q = 1: L = 1, the two codes are the plane's extremes.  A 2 x 4 plane that is one block holding
+    # {0, 4} only: mean 2, h = -+2, delta = -2, range 4, Delta = 4, t in {0, 1}: fixed points of the
+    # rounding, so code = (x == 4) for every seed, 8 codes in the low byte of one word, and xhat = x.
+    x = np.array([[[[0, 4, 4, 0], [4, 0, 0, 4]]]], np.float32)
+    for seed in (0, 3, 2 ** 40 + 1):
+        p, xh = _roundtrip(x, 4, 1, seed)
+        s = oracle.split_packed(p, x.shape, 4, 1)
+        assert s["codes"].tolist() == [[0b10010110]]
+        assert s["meta"].tolist() == [[-2.0, 4.0]]
+        assert s["lfc"].tolist() == [[[2.0]]]
+        assert np.array_equal(xh, x)
+    # a value a quarter of the way up is coded 1 with probability 1/4 (u uniform on 65536 steps)
+    y = np.array([[[[0, 4, 1, 3]]]], np.float32)              # mean 2, h = [-2, 2, -1, 1], t = [0, 1, 1/4, 3/4]
+    ones = np.zeros(4)
+    n = 4000
+    for seed in range(n):
+        q = oracle.unpack_codes(oracle.split_packed(oracle.compress(y, 4, 1, seed), y.shape, 4, 1)["codes"], 4, 1)[0]
+        ones += q
+    assert ones[0] == 0 and ones[1] == n
+    assert abs(ones[2] / n - 0.25) < 0.03 and abs(ones[3] / n - 0.75) < 0.03
+
+
 def test_worked_example_4x4_b4():
     # one 4x4 block holding the ramp 0..15: mean 7.5, range 15, Delta 1, codes 0..15
     x = np.arange(16, dtype=np.float32).reshape(1, 1, 4, 4)
@@ -97,7 +120,7 @@ def test_block_constant_gives_zero_hfc(shape, B):
     assert np.array_equal(oracle.decompress(p, shape, B, 2), x)
 
 
-@pytest.mark.parametrize("b", [2, 4, 8])
+@pytest.mark.parametrize("b", [1, 2, 4, 8])
 @pytest.mark.parametrize("shape,B", [((2, 4, 16, 16), 8), ((1, 5, 7, 7), 8), ((2, 3, 14, 14), 8), ((1, 2, 55, 55), 4)])
 def test_reconstruction_error_bounded_by_one_step(shape, B, b):
     x = np.maximum(_rng(3).standard_normal(shape), 0).astype(np.float32)
@@ -255,7 +278,7 @@ def test_decompress_is_dequant_plus_upsampled_lfc():
 
 # ---------------------------------------------------------------- X2 exact-rational brute force
 
-@pytest.mark.parametrize("H,W,B,b", [(2, 2, 2, 2), (3, 5, 2, 2), (5, 7, 3, 4), (4, 4, 1, 2), (5, 7, 8, 2),
+@pytest.mark.parametrize("H,W,B,b", [(2, 2, 2, 2), (3, 5, 2, 2), (5, 7, 3, 4), (4, 4, 1, 2), (5, 7, 8, 2), (5, 7, 3, 1), (6, 11, 4, 1),
                                      (6, 6, 4, 4), (7, 7, 8, 4), (3, 9, 4, 2), (5, 6, 4, 8), (7, 7, 8, 8)])
 def test_brute_force_exact_rational(H, W, B, b):
     rng = _rng(100 + H * 31 + W * 7 + B)
@@ -316,7 +339,7 @@ def test_layout_closed_form_and_config_sizes():
         return a16(a16(a16(4 * P * WPP) + 8 * P) + es * P * (-(-H // B)) * (-(-W // B)))
     cases = [(2, 16, 32, 32, 8, 2, 4), (64, 256, 56, 56, 8, 2, 4), (64, 2048, 7, 7, 8, 2, 4), (3, 5, 55, 55, 4, 4, 4),
              (256, 256, 56, 56, 8, 2, 2), (1, 1, 1, 1, 1, 2, 4), (7, 3, 13, 29, 5, 4, 2),
-             (64, 256, 56, 56, 8, 8, 4), (5, 3, 7, 7, 8, 8, 2)]
+             (64, 256, 56, 56, 8, 8, 4), (5, 3, 7, 7, 8, 8, 2), (3, 5, 7, 9, 4, 1, 4), (2, 2, 56, 56, 8, 1, 2)]
     for N, C, H, W, B, b, es in cases:
         dt = oracle.BF16 if es == 2 else oracle.F32
         assert oracle.packed_bytes(N, C, H, W, B, b, dt) == closed(N, C, H, W, B, b, es)
@@ -325,7 +348,7 @@ def test_layout_closed_form_and_config_sizes():
     for hw, total in [(112, 3928), (56, 988), (28, 268), (14, 76), (7, 28)]:
         lay = oracle.packed_layout(16, 1, hw, hw, 8, 2)
         assert (lay["codes_bytes"] + lay["meta_bytes"] + lay["lfc_bytes"]) // 16 == total
-    for bad in [(0, 1, 4, 4, 2, 2), (1, 1, 4, 4, 0, 2), (1, 1, 4, 4, 2, 3), (1, 1, 4, 4, 2, 1), (1, 1, 4, 4, 2, 16)]:
+    for bad in [(0, 1, 4, 4, 2, 2), (1, 1, 4, 4, 0, 2), (1, 1, 4, 4, 2, 3), (1, 1, 4, 4, 2, 0), (1, 1, 4, 4, 2, 16)]:
         assert oracle.packed_bytes(*bad) == 0
 
 
