@@ -279,10 +279,11 @@ __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
         // ---- Quant + packing: a unit is two element pairs = 4 codes (one byte for b = 2, a word for b = 8)
         {
             const uint32_t rscale = 1u << (16 - BITS);
-            constexpr uint32_t CB = BITS / 2;                         // code bytes per unit (1, 2 or 4)
+            constexpr uint32_t CB = BITS / 2;                         // code bytes per unit (1, 2 or 4; 1-bit codes: half a byte)
+            const uint32_t cbytes = BITS == 1 ? (a.q4 + 1u) / 2u : a.q4 * CB;    // code bytes of the plane
             uint8_t* cbase = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)p * a.WPP * 4;
             const __amdgpu_buffer_rsrc_t crs =
-                __builtin_amdgcn_make_buffer_rsrc(cbase, 0, (int)(a.q4 * CB), 0x00020000);
+                __builtin_amdgcn_make_buffer_rsrc(cbase, 0, (int)cbytes, 0x00020000);
             const uint32_t xw0 = k1 + (2u * tid) * kWeyl;
 #pragma unroll
             for (int k = 0; k < K; ++k) {
@@ -291,13 +292,19 @@ __device__ __forceinline__ void compress_regs_body(const RegsArgs& a) {
                 uint32_t c = push_pair<BITS>(0u, x[k][2], x[k][3], delta, invs, xw + kWeyl, k2, rscale);
                 c = push_pair<BITS>(c, x[k][0], x[k][1], delta, invs, xw, k2, rscale);
                 // stores past the plane's code bytes are dropped by the buffer bound
-                if constexpr (CB == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, tid, k * NT, 0);
+                if constexpr (BITS == 1) {
+                    // the four codes of a unit are half a byte: the even lane of a pair stores the byte of
+                    // both units (the odd lane's store is dropped; a unit past the plane contributes zeros)
+                    c = tid + (uint32_t)(k * NT) < a.q4 ? c : 0u;
+                    const uint32_t up = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)c, 0xB1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
+                    __builtin_amdgcn_raw_buffer_store_b8((uint8_t)(c | (up << 4)), crs, (tid & 1u) ? 0x80000000u : (tid >> 1) + (uint32_t)(k * (NT / 2)), 0, 0);
+                } else if constexpr (CB == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, tid, k * NT, 0);
                 else if constexpr (CB == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c, crs, tid * 2u, k * NT * 2, 0);
                 else __builtin_amdgcn_raw_buffer_store_b32(c, crs, tid * 4u, k * NT * 4, 0);
             }
             // pad bytes of the plane's last word are zero
-            const uint32_t padb = a.WPP * 4 - a.q4 * CB;
-            if (tid < padb) cbase[a.q4 * CB + tid] = 0;
+            const uint32_t padb = a.WPP * 4 - cbytes;
+            if (tid < padb) cbase[cbytes + tid] = 0;
         }
     }
 }

@@ -223,15 +223,29 @@ __device__ __forceinline__ void compress_strip_body(const StripArgs& a) {
     {
         uint8_t* cb = reinterpret_cast<uint8_t*>(cw) + g * a.WPP * 4u + sl * (uint32_t)(UPL * CB);
         const uint32_t xw0 = k1 + (sl * (uint32_t)(E / 2)) * kWeyl;
+        uint32_t strip_bits = 0;                                       // 1-bit codes: the strip's E codes
+        (void)cb; (void)strip_bits;
 #pragma unroll
         for (int u = 0; u < UPL; ++u) {
             const uint32_t xw = xw0 + (uint32_t)(2 * u) * kWeyl;
             uint32_t c = push_pair<BITS>(0u, x[4 * u + 2], x[4 * u + 3], delta, invs, xw + kWeyl, k2, rscale);
             c = push_pair<BITS>(c, x[4 * u], x[4 * u + 1], delta, invs, xw, k2, rscale);
-            if (valid) {
+            if constexpr (BITS == 1) strip_bits |= c << (4 * u);
+            else if (valid) {
                 if constexpr (CB == 1) cb[u] = (uint8_t)c;
                 else if constexpr (CB == 2) reinterpret_cast<uint16_t*>(cb)[u] = (uint16_t)c;
                 else reinterpret_cast<uint32_t*>(cb)[u] = c;
+            }
+        }
+        if constexpr (BITS == 1) {
+            // a strip's E bits start at bit sl * E of the plane's code words, for E = 28 in the middle of a
+            // byte: the lanes OR their bits into the (cleared) words, one or two words per strip
+            if (valid) {
+                uint32_t* pw = cw + g * a.WPP;
+                const uint32_t bit = sl * (uint32_t)E, sh = bit & 31u;
+                __hip_atomic_fetch_or(pw + (bit >> 5), strip_bits << sh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (sh + (uint32_t)E > 32u)
+                    __hip_atomic_fetch_or(pw + (bit >> 5) + 1u, strip_bits >> (32u - sh), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
     }

@@ -126,7 +126,10 @@ __device__ __forceinline__ void decompress_rowvec_body(const DecArgs& a) {
                 const uint32_t fi = vi - g * a.q4;                     // even
                 const float2 dd = s_meta[g];
                 uint32_t lo, hi;                                       // codes of elements 0-3 and 4-7
-                if constexpr (BITS == 2) {
+                if constexpr (BITS == 1) {
+                    lo = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + (fi >> 1)];
+                    hi = lo >> 4;
+                } else if constexpr (BITS == 2) {
                     lo = reinterpret_cast<const uint16_t*>(s_codes)[(g * a.WPP * 4 + fi) >> 1];
                     hi = lo >> 8;
                 } else if constexpr (BITS == 4) {
@@ -159,7 +162,8 @@ __device__ __forceinline__ void decompress_rowvec_body(const DecArgs& a) {
         const uint32_t fi = vi - g * a.q4;        // vector index inside the plane
         const float2 dd = s_meta[g];
         uint32_t c4;                               // the four codes, BITS apart from bit 0
-        if constexpr (BITS == 2) c4 = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + fi];
+        if constexpr (BITS == 1) c4 = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + (fi >> 1)] >> ((fi & 1u) * 4u);
+        else if constexpr (BITS == 2) c4 = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + fi];
         else if constexpr (BITS == 4) c4 = reinterpret_cast<const uint16_t*>(s_codes)[g * a.WPP * 2 + fi];
         else c4 = s_codes[g * a.WPP + fi];
         const uint32_t r = fdiv(fi, a.d_w4);
@@ -219,8 +223,9 @@ __device__ __forceinline__ void decompress_stream_body(const DecArgs& a) {
         const uint32_t r = fdiv(fi, a.d_w4);
         const uint32_t c = (fi - r * a.w4) * 4u;
         const uint32_t blk = lfc_row<ND>(a, r) + fdiv(c, a.d_B);
-        const uint8_t* cp = cbase + (size_t)g * a.WPP * 4u + (size_t)fi * CBY;
-        if constexpr (BITS == 2) code[k] = *cp;
+        const uint8_t* cp = cbase + (size_t)g * a.WPP * 4u + (BITS == 1 ? (size_t)(fi >> 1) : (size_t)fi * CBY);
+        if constexpr (BITS == 1) code[k] = (uint32_t)*cp >> ((fi & 1u) * 4u);     // four 1-bit codes: half a byte
+        else if constexpr (BITS == 2) code[k] = *cp;
         else if constexpr (BITS == 4) code[k] = *reinterpret_cast<const uint16_t*>(cp);
         else code[k] = *reinterpret_cast<const uint32_t*>(cp);
         dd[k] = meta_load(pt.meta, g, kC16<T>);
@@ -278,7 +283,8 @@ __global__ void __launch_bounds__(kThreads) decompress_table(DecArgs a) {
         const uint32_t fi = vi - g * a.q4;
         const float2 dd = s_meta[g];
         uint32_t c4;
-        if constexpr (BITS == 2) c4 = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + fi];
+        if constexpr (BITS == 1) c4 = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + (fi >> 1)] >> ((fi & 1u) * 4u);
+        else if constexpr (BITS == 2) c4 = reinterpret_cast<const uint8_t*>(s_codes)[g * a.WPP * 4 + fi];
         else if constexpr (BITS == 4) c4 = reinterpret_cast<const uint16_t*>(s_codes)[g * a.WPP * 2 + fi];
         else c4 = s_codes[g * a.WPP + fi];
         const uint32_t t = s_tab[fi];

@@ -11,6 +11,7 @@ pytestmark = pytest.mark.gpu
 
 CASES = [
     ((2, 3, 4, 14, 14), 8, 1), ((2, 2, 3, 9, 11), 4, 1),     # 1-bit codes: the general kernels
+    ((2, 3, 16, 28, 28), 8, 1), ((2, 3, 4, 28, 28), 8, 1), ((1, 2, 20, 44, 48), 8, 1), ((1, 2, 9, 36, 40), 8, 1),   # and the register kernel
     # shape (N, C, D, H, W), B, b                 what it exercises
     ((2, 3, 8, 8, 8), 4, 2),                      # cubes of 4: LDS kernel, vector rows
     ((3, 5, 16, 16, 16), 8, 2),                   # 4096-element planes, several per chunk

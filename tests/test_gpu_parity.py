@@ -437,19 +437,71 @@ def test_bfloat16_map_is_rebuilt_with_round_to_nearest_even():
         assert torch.equal(y.cpu().view(torch.int16).reshape(6, -1)[pl], want.view(torch.int16))
 
 
-# 1-bit codes (Q = 1): served by the general kernels whatever the shape
-@pytest.mark.parametrize("shape,B", [((3, 5, 56, 56), 8), ((2, 3, 28, 28), 8), ((5, 7, 7, 7), 8), ((2, 9, 1, 96), 64),
-                                     ((2, 3, 55, 55), 4), ((3, 2, 33, 17), 12), ((1, 1, 1, 1), 8), ((2, 2, 100, 37), 8)])
+# 1-bit codes (Q = 1): the register, strip and lane kernels on the shapes they take, the general kernels elsewhere
+ONE_BIT_CASES = [
+    # shape, B, compress kernel, decompress kernel (of fp32 maps)
+    ((3, 5, 56, 56), 8, "compress_regs<float, 1, 8, 1>", "decompress_stream"),
+    ((3, 5, 56, 56), 4, "compress_regs<float, 1, 4, 1>", "decompress_stream"),
+    ((3, 5, 56, 56), 12, "compress_regs<float, 1, 0, 1>", "decompress_stream"),
+    ((2, 3, 48, 48), 8, "compress_regs<float, 1, 8, 1>", "decompress_stream"),      # rounds past the plane
+    ((2, 3, 47, 44), 8, "compress_regs<float, 1, 8, 1>", "decompress_stream"),      # 517 units: the last byte holds one unit
+    ((2, 3, 51, 60), 4, "compress_regs<float, 1, 4, 1>", "decompress_stream"),      # 765 units
+    ((2, 3, 112, 112), 8, "compress_regs<float, 1, 8, 4>", "decompress_stream"),
+    ((2, 3, 96, 96), 8, "compress_regs<float, 1, 8, 4>", "decompress_stream"),
+    ((1, 3, 97, 92), 8, "compress_regs<float, 1, 8, 4>", "decompress_stream"),      # 2231 units
+    ((1, 2, 224, 224), 8, "compress_regs<float, 1, 8, 16>", "decompress_stream"),
+    ((2, 3, 160, 160), 8, "compress_regs<float, 1, 8, 16>", "decompress_stream"),
+    ((2, 3, 1, 3136), 8, "compress_regs<float, 1, 8, 1>", "decompress_stream"),
+    ((2, 3, 28, 28), 8, "compress_strip<float, 1, 28, 8>", "decompress_stream"),
+    ((1, 5, 28, 28), 8, "compress_strip<float, 1, 28, 8>", "decompress_stream"),    # a ragged last round
+    ((2, 3, 20, 28), 8, "compress_strip<float, 1, 28, 8>", "decompress_stream"),
+    ((2, 3, 27, 28), 8, "compress_strip<float, 1, 28, 8>", "decompress_stream"),    # 756 bits: strips end inside a word
+    ((2, 3, 28, 28), 12, "compress_strip<float, 1, 28, 12>", "decompress_stream"),
+    ((2, 3, 28, 28), 18, "compress_strip<float, 1, 28, 18>", "decompress_table"),
+    ((4, 6, 14, 14), 8, "compress_strip<float, 1, 14, 8>", "decompress_table"),
+    ((1, 7, 14, 14), 8, "compress_strip<float, 1, 14, 8>", "decompress_table"),
+    ((2, 3, 10, 14), 8, "compress_strip<float, 1, 14, 8>", "decompress_table"),
+    ((2, 5, 14, 14), 12, "compress_strip<float, 1, 14, 12>", "decompress_table"),
+    ((3, 5, 32, 32), 4, "compress_strip<float, 1, 32, 4>", "decompress_stream"),
+    ((1, 1, 32, 32), 8, "compress_strip<float, 1, 32, 8>", "decompress_stream"),
+    ((2, 3, 32, 32), 16, "compress_strip<float, 1, 32, 16>", "decompress_stream"),
+    ((3, 5, 16, 16), 8, "compress_strip<float, 1, 16, 8>", "decompress_stream"),
+    ((3, 5, 16, 16), 4, "compress_strip<float, 1, 16, 4>", "decompress_stream"),
+    ((2, 5, 16, 16), 12, "compress_strip<float, 1, 16, 12>", "decompress_stream"),
+    ((5, 7, 7, 7), 8, "compress_lane<float, 1>", "decompress_lane"),
+    ((3, 67, 7, 7), 8, "compress_lane<float, 1>", "decompress_lane"),
+    ((2, 3, 5, 5), 8, "compress_lane<float, 1>", "decompress_lane"),
+    ((1, 1, 1, 1), 8, "compress_lane<float, 1>", "decompress_lane"),
+    ((2, 9, 1, 96), 64, "compress_any<float, 1>", "decompress_stream"),
+    ((2, 3, 64, 64), 8, "compress_any<float, 1>", "decompress_stream"),
+    ((2, 2, 100, 37), 8, "compress_any<float, 1>", "decompress_table"),
+    ((2, 3, 55, 55), 4, "compress_any<float, 1>", "decompress_scalar"),
+    ((3, 2, 33, 17), 12, "compress_any<float, 1>", "decompress_scalar"),
+]
+
+
+@pytest.mark.parametrize("shape,B,ckern,dkern", ONE_BIT_CASES)
 @pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
-def test_one_bit_codes_match_oracle(shape, B, mode):
+def test_one_bit_codes_match_oracle(shape, B, ckern, dkern, mode):
     dtype = torch.bfloat16 if mode == "bf16" else torch.float32
-    assert pkg.division_kernel_name(0, shape, B, 1, dtype, c16=mode == "c16").startswith("compress_any<")
-    assert pkg.division_kernel_name(1, shape, B, 1, dtype, c16=mode == "c16").startswith("decompress_scalar<")
+    c16 = mode == "c16"
+    tn = {"f32": "float", "bf16": "bf16_t", "c16": "f32c16_t"}[mode]
+    assert pkg.division_kernel_name(0, shape, B, 1, dtype, c16=c16) == ckern.replace("float", tn)
+    if mode == "f32":
+        assert pkg.division_kernel_name(1, shape, B, 1, dtype).startswith(dkern + "<float, 1>")
     _check_variant(shape, B, 1, mode)
+    # pad bits and bytes of a buffer that held something else before
+    dt = oracle.F32_C16 if c16 else (oracle.BF16 if mode == "bf16" else oracle.F32)
+    x = _relu_normal(shape, 5 + B, dtype)
+    xh, _ = to_host_array(x)
+    pk = torch.full((pkg.division_packed_bytes(*shape, B, 1, dtype, c16),), 0xFF, dtype=torch.uint8, device="cuda:0")
+    pkg.division_compress(x.to("cuda:0"), B, 1, 99, packed=pk, c16=c16)
+    torch.cuda.synchronize()
+    assert np.array_equal(pk.cpu().numpy(), oracle.compress(xh, B, 1, 99, dt, threads=16))
     # and the ratio the codec was asked for: one bit per element + H^L + scale
     n = shape[0] * shape[1] * shape[2] * shape[3]
     if n >= 1024:
-        assert pkg.division_packed_bytes(*shape, B, 1, dtype, mode == "c16") < n * (2 if mode == "bf16" else 4) / 4
+        assert pkg.division_packed_bytes(*shape, B, 1, dtype, c16) < n * (2 if mode == "bf16" else 4) / 4
 
 
 # block sizes and ragged edges that give blocks of 98, 196, 198 or 150 elements: counts whose binary64 reciprocal, times the
@@ -1039,7 +1091,7 @@ def _special_planes(shape, seed):
 
 
 @pytest.mark.parametrize("shape,B", SPECIAL_VALUE_SHAPES)
-@pytest.mark.parametrize("mode,b", [("f32", 2), ("f32", 8), ("bf16", 4), ("c16", 2)])
+@pytest.mark.parametrize("mode,b", [("f32", 2), ("f32", 8), ("bf16", 4), ("c16", 2), ("f32", 1), ("bf16", 1)])
 def test_values_at_the_edges_of_binary32(shape, B, mode, b):
     dtype = torch.bfloat16 if mode == "bf16" else torch.float32
     c16 = mode == "c16"

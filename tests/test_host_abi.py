@@ -151,6 +151,14 @@ def test_layout_of_the_bfloat16_cached_mode_matches_oracle():
 DISPATCH = [
     # shape, B, b, compress kernel, decompress kernel (fp32)
     ((64, 256, 56, 56), 8, 2, "compress_regs<float, 2, 8, 1>", "decompress_stream<float, 2>"),
+    # 1-bit codes: the ResNet-50 shapes in the fast kernels, the rest in the general ones
+    ((64, 256, 56, 56), 8, 1, "compress_regs<float, 1, 8, 1>", "decompress_stream<float, 1>"),
+    ((64, 64, 112, 112), 8, 1, "compress_regs<float, 1, 8, 4>", "decompress_stream<float, 1>"),
+    ((64, 512, 28, 28), 8, 1, "compress_strip<float, 1, 28, 8>", "decompress_stream<float, 1>"),
+    ((64, 1024, 14, 14), 8, 1, "compress_strip<float, 1, 14, 8>", "decompress_table<float, 1>"),
+    ((64, 2048, 7, 7), 8, 1, "compress_lane<float, 1>", "decompress_lane<float, 1>"),
+    ((256, 96, 55, 55), 8, 1, "compress_any<float, 1>", "decompress_scalar<float, 1>"),
+    ((64, 96, 64, 64), 8, 1, "compress_any<float, 1>", "decompress_stream<float, 1>"),
     ((64, 64, 112, 112), 8, 2, "compress_regs<float, 2, 8, 4>", "decompress_stream<float, 2>"),
     ((2, 3, 224, 224), 8, 2, "compress_regs<float, 2, 8, 16>", "decompress_stream<float, 2>"),
     ((64, 512, 28, 28), 8, 2, "compress_strip<float, 2, 28, 8>", "decompress_stream<float, 2>"),
