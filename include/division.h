@@ -96,10 +96,10 @@ int division_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W,
  *           smaller than B are pooled to 1x1 (footnote of Sec. 4.1); when B
  *           does not divide H or W the border windows average their valid
  *           elements only.
- *   b       bits per HFC code (the paper's Q): 1, 2, 4 or 8.  2, 4 and 8 have fast kernels for every
- *           shape; 1 has them for planes of 2048 elements and more with W % 4 == 0, for the 28 / 32 and
- *           14 / 16 wide planes of the strip kernel and for one-block planes of odd size, and is served by
- *           the general kernels (slow) elsewhere.
+ *   b       bits per HFC code (the paper's Q): 1, 2, 4 or 8.  2, 4 and 8 have fast compress kernels
+ *           for every shape; 1 has them for the shapes of the register, strip, lane, items and units
+ *           kernels (the ResNet-50 and CIFAR maps, odd widths) and is compressed by the general kernel
+ *           (slow) elsewhere.  Decompression is fast for every b.
  *   seed    selects the stochastic-rounding stream of Eq. (quantization); the
  *           output is a pure function of (x, shape, dt, B, b, seed) and does
  *           not depend on the launch geometry or the device.

@@ -326,7 +326,9 @@ static void plane_scale(const float *h, size_t HW, int b, float *delta, float *D
  * must use the very values the decoder will see, and every residual must stay inside their code
  * range, so delta is the plane minimum rounded DOWN to bfloat16 and Delta is
  * fl(fl(max - delta) / L) rounded UP to bfloat16; the scale is inv = fl(1 / Delta).  The top code
- * need not be reached.  A plane with fl(max - delta) below 2^-90 is degenerate (Delta = 0). */
+ * need not be reached.  A plane with fl(max - delta) below 2^-90 is degenerate (Delta = 0), and so
+ * is one whose Delta, rounded up, is beyond the largest bfloat16: the decoder could not multiply by
+ * it (with L = 1 and a range between the largest bfloat16 and the largest binary32). */
 static void plane_scale_c16(const float *h, size_t HW, int b, float *delta, float *Delta, float *inv)
 {
     float lo, hi;
@@ -338,9 +340,14 @@ static void plane_scale_c16(const float *h, size_t HW, int b, float *delta, floa
     if (range >= 0x1p-90f && range <= 3.4028234663852886e38f) {
         volatile float q = range / Lf;              /* fp32 div */
         const float D = bf16_ceil(q);
-        volatile float s = 1.0f / D;                /* fp32 div */
-        *Delta = D;
-        *inv = s;
+        if (D <= 3.3895313892515355e38f) {          /* the largest bfloat16 */
+            volatile float s = 1.0f / D;            /* fp32 div */
+            *Delta = D;
+            *inv = s;
+        } else {                                    /* Delta has no finite bfloat16 (1-bit codes only) */
+            *Delta = 0.0f;
+            *inv = 0.0f;
+        }
     } else {
         *Delta = 0.0f;
         *inv = 0.0f;

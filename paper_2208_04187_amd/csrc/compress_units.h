@@ -227,14 +227,17 @@ __global__ void __launch_bounds__(NW ? 64 * NW : 64) compress_units(UnitsArgs a)
         // ---- Quant + packing: a unit is two element pairs = 4 codes; a lane reads back the residuals it wrote
         {
             const uint32_t rscale = 1u << (16 - BITS);
-            constexpr uint32_t CB = BITS / 2;                         // code bytes per unit (1, 2 or 4)
+            constexpr uint32_t CB = BITS / 2;                         // code bytes per unit (1, 2 or 4; 1-bit codes: half a byte)
+            const uint32_t cbytes = BITS == 1 ? (a.q4 + 1u) / 2u : a.q4 * CB;    // code bytes of a plane
             // NW >= 1: the buffer ends with the plane's last unit, so that stores of units past the plane
             // are dropped; NW = 0: it ends with the round's last plane, units past a plane are skipped
             const uint32_t pf = rd * G;
             uint8_t* cround = reinterpret_cast<uint8_t*>(pt.codes) + (size_t)pf * a.WPP * 4;
             const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(
-                cround, 0, (int)(SUB ? min(G, a.P - pf) * a.WPP * 4u : a.q4 * CB), 0x00020000);
+                cround, 0, (int)(SUB ? min(G, a.P - pf) * a.WPP * 4u : cbytes), 0x00020000);
             const uint32_t cvoff = g * a.WPP * 4u + l * CB;
+            const uint32_t cvoff1 = (l & 1u) ? 0x80000000u : g * a.WPP * 4u + (l >> 1);     // 1-bit codes: the odd lane stores nothing
+            (void)cvoff1;
             const uint32_t xw0 = k1 + (2u * l) * kWeyl;
             const uint32_t tailmask = tail ? (1u << (tail * BITS)) - 1u : 0xffffffffu;
 #pragma unroll
@@ -246,14 +249,23 @@ __global__ void __launch_bounds__(NW ? 64 * NW : 64) compress_units(UnitsArgs a)
                 c = push_pair<BITS>(c, v.x, v.y, delta, invs, xw, k2, rscale);
                 // the last unit's elements past the plane leave zero bits
                 if (l + S * k + 1 == a.q4) c &= tailmask;
+                if constexpr (BITS == 1) {
+                    // the four codes of a unit are half a byte: the even lane of a pair stores the byte of both
+                    // units (a unit past the plane contributes zeros, the odd lane's store is dropped)
+                    const bool in = l + S * k < a.q4;
+                    c = in ? c : 0u;
+                    c |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)c, 0xB1, 0xf, 0xf, true) << 4;   // quad_perm [1,0,3,2]
+                    __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, in ? cvoff1 + (uint32_t)(S * k / 2) : 0x80000000u, 0, 0);
+                    continue;
+                }
                 if (SUB && l + S * k >= a.q4) continue;
                 if constexpr (CB == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, cvoff, (int)(S * k), 0);
                 else if constexpr (CB == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c, crs, cvoff, (int)(S * k * 2), 0);
                 else __builtin_amdgcn_raw_buffer_store_b32(c, crs, cvoff, (int)(S * k * 4), 0);
             }
             // pad bytes of the plane's last word are zero
-            const uint32_t padb = a.WPP * 4 - a.q4 * CB;
-            if (l < padb && pv) cround[(size_t)g * a.WPP * 4 + a.q4 * CB + l] = 0;
+            const uint32_t padb = a.WPP * 4 - cbytes;
+            if (l < padb && pv) cround[(size_t)g * a.WPP * 4 + cbytes + l] = 0;
         }
         sync();      // xs, rsum, lfcs and red are reused
     }

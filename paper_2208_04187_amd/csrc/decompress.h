@@ -525,7 +525,8 @@ __global__ void __launch_bounds__(64 * NW) decompress_units(DecArgs a) {
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             if (!round_live(k) || shift) continue;
-            if constexpr (CB == 1) wide[k].x = __builtin_amdgcn_raw_buffer_load_b8(crs, tid, k * NT, 0);
+            if constexpr (BITS == 1) wide[k].x = __builtin_amdgcn_raw_buffer_load_b8(crs, (tid + (uint32_t)(NT * k)) >> 1, 0, 0);   // two units per byte
+            else if constexpr (CB == 1) wide[k].x = __builtin_amdgcn_raw_buffer_load_b8(crs, tid, k * NT, 0);
             else if constexpr (CB == 2) wide[k].x = __builtin_amdgcn_raw_buffer_load_b16(crs, tid * 2u, k * NT * 2, 0);
             else wide[k].x = __builtin_amdgcn_raw_buffer_load_b32(crs, tid * 4u, k * NT * 4, 0);
         }
@@ -558,7 +559,7 @@ __global__ void __launch_bounds__(64 * NW) decompress_units(DecArgs a) {
                 c4[k] = f ? c : c << (shift * BITS);       // unit 0: the slots before the plane, then its first elements
                 continue;
             }
-            c4[k] = wide[k].x;
+            c4[k] = BITS == 1 ? wide[k].x >> ((tid & 1u) * 4u) : wide[k].x;
         }
         const float2 sc = dd;
         if (p + gridDim.x < a.P) issue_loads(p + gridDim.x);

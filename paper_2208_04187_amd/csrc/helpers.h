@@ -95,7 +95,8 @@ __device__ __forceinline__ float bf16_ceil_f(float f) {
 // Scale of one plane from its residual extremes.  Plain: delta = min, Delta, inv as plane_scale.
 // c16: the quantiser has to use the very values the decoder will read and every residual has to
 // stay inside their code range, so delta = min rounded DOWN to bfloat16, Delta =
-// fl(fl(max - delta) / L) rounded UP to bfloat16, inv = fl(1 / Delta).
+// fl(fl(max - delta) / L) rounded UP to bfloat16, inv = fl(1 / Delta); Delta = inv = 0 when the
+// range is below 2^-90, not finite, or Delta would not be a finite bfloat16.
 __device__ __forceinline__ void plane_scale_any(float mn, float mx, float Lf, uint32_t c16,
                                                 float& delta, float& Delta, float& inv) {
     if (!c16) {
@@ -107,7 +108,10 @@ __device__ __forceinline__ void plane_scale_any(float mn, float mx, float Lf, ui
     const float range = mx - delta;
     if (range >= 0x1p-90f && range <= 3.4028234663852886e38f) {
         Delta = bf16_ceil_f(range / Lf);
-        inv = 1.0f / Delta;
+        // L = 1 and a range beyond the largest bfloat16: no finite step to cache, the plane is degenerate
+        const bool finite = Delta <= 3.3895313892515355e38f;
+        inv = finite ? 1.0f / Delta : 0.0f;
+        Delta = finite ? Delta : 0.0f;
     } else {
         Delta = 0.0f;
         inv = 0.0f;

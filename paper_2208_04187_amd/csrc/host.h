@@ -242,7 +242,11 @@ template <typename T, int BITS>
 hipError_t launch_units(int nw, const UnitsArgs& a, dim3 grid, size_t lds, hipStream_t st) {
     void (*kern)(UnitsArgs) = nw == 0 ? compress_units<T, BITS, 0> : nw == 1 ? compress_units<T, BITS, 1>
                             : nw == 2 ? compress_units<T, BITS, 2> : nw == 4 ? compress_units<T, BITS, 4>
-                            : nw == 8 ? compress_units<T, BITS, 8> : compress_units<T, BITS, 16>;
+                                                                             : compress_units<T, BITS, 8>;
+    // 1-bit codes have no instance of sixteen wavefronts (its lane pairing does not fit the 128 registers
+    // a lane of 1024 threads has): the planner sends those planes elsewhere
+    if constexpr (BITS != 1) { if (nw == 16) kern = compress_units<T, BITS, 16>; }
+    else if (nw == 16) return hipErrorInvalidValue;
     const hipError_t e = allow_large_lds(kern, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, dim3(nw ? 64 * nw : 64), lds, st, a);
@@ -822,10 +826,6 @@ hipError_t with_bits(int b, F&& f) {
                                                                   : f(std::integral_constant<int, 8>{});
 }
 
-// the decompress kernels (by the kind plan_decompress returns) that have a 1-bit instance: row vectors,
-// table, lane, stream; the other shapes take the element-per-thread kernel (kind 2) under 1-bit codes
-inline bool one_bit_decompress_kind(int kind) { return kind == 0 || kind == 3 || kind == 4 || kind == 7; }
-
 enum CompKind { REGS, LANE, LINE, STRIP, ITEMS, UNITS, WAVE, TILE, ONE, ROWS, PLANE, ANY };
 
 // everything a compress launch needs once the plan is made (the arguments of the kernel that was picked)
@@ -851,11 +851,13 @@ hipError_t do_compress(const CompLaunch& c, int b) {
     const size_t lds = c.lds;
     const bool flat = c.flat != 0;
     if (b == 1) {
-        // 1-bit codes: the register, strip and lane kernels, else the general one (the planner picks nothing else)
+        // 1-bit codes: the register, strip, lane, items and units kernels, else the general one (the planner picks nothing else)
         switch (c.kind) {
             case REGS: return launch_regs<T, 1>(c.B, c.nw, c.ra, gd, lds, st);
             case STRIP: return launch_strip<T, 1>(c.vec, c.sa, gd, lds, st);
             case LANE: hipLaunchKernelGGL((compress_lane<T, 1>), gd, dim3(64), lds, st, c.la); return hipGetLastError();
+            case ITEMS: return launch_items<T, 1>(c.B, c.vec, c.ia, gd, lds, st);
+            case UNITS: return launch_units<T, 1>(c.nw, c.ua, gd, lds, st);
             default: {
                 void (*kern)(AnyArgs) = flat ? compress_any<T, 1> : compress_any_3d<T, 1>;
                 hipLaunchKernelGGL(kern, gd, dim3(kThreads), 0, st, c.g);
@@ -909,24 +911,8 @@ hipError_t do_compress(const CompLaunch& c, int b) {
 
 template <typename T>
 hipError_t do_decompress(const DecLaunch& c, int b) {
-    if (b == 1) {
-        // 1-bit codes: the kinds one_bit_decompress_kind leaves
-        void (*kern)(DecArgs);
-        if (c.kind == 7) {
-            kern = c.flat ? decompress_stream<T, 1> : decompress_stream_3d<T, 1>;
-            hipLaunchKernelGGL(kern, dim3(c.gx, c.gy), dim3(64), 0, c.st, c.a);
-            return hipGetLastError();
-        }
-        if (c.kind == 0) kern = c.flat ? decompress_rowvec<T, 1> : decompress_rowvec_3d<T, 1>;
-        else if (c.kind == 3) kern = decompress_table<T, 1>;
-        else if (c.kind == 4) kern = decompress_lane<T, 1>;
-        else kern = c.flat ? decompress_scalar<T, 1> : decompress_scalar_3d<T, 1>;
-        const hipError_t e = allow_large_lds(kern, c.lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, dim3(c.gx, c.gy), dim3(c.kind == 4 ? 64 : kThreads), c.lds, c.st, c.a);
-        return hipGetLastError();
-    }
-    return with_bits(b, [&](auto bits) -> hipError_t {
+    // every decompress kernel has an instance for 1-bit codes too
+    auto launch = [&](auto bits) -> hipError_t {
         constexpr int BITS = decltype(bits)::value;
         const int kind = c.kind;
         void (*kern)(DecArgs);
@@ -954,7 +940,8 @@ hipError_t do_decompress(const DecLaunch& c, int b) {
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3(c.gx, c.gy), dim3(kind == 4 ? 64 : kThreads), c.lds, c.st, c.a);
         return hipGetLastError();
-    });
+    };
+    return b == 1 ? launch(std::integral_constant<int, 1>{}) : with_bits(b, launch);
 }
 
 // the Relu + compress kernels: the register kernel's planes (c.ra carries y and mask), c.kind == STRIP the
@@ -1071,6 +1058,8 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
             if (plan_regs(L, D, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
             else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
             else if (flat && plan_strip(L, H, W, B, es, xa, &sa, &grid, &lds, &vec)) { kind = STRIP; sa.tab = tab; sa.rg = rg; }
+            else if (flat && plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
+            else if (plan_units(L, D, H, W, B, es, xa, &ua, &grid, &lds, &nw) && nw != 16) { kind = UNITS; ua.tab = tab; ua.rg = rg; }
             else use_any();
         }
         else if (line_first(L, es) && plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
@@ -1121,8 +1110,7 @@ int decompress_impl(int count, const void* const* packed, void* const* xhat, siz
         const int cnt = count - i0 < kMaxBatch ? count - i0 : kMaxBatch;
         DecArgs a{};
         uint32_t grid = 0;
-        int kind = plan_decompress(L, D, H, W, B, es, reinterpret_cast<const void*>(all_out ? all_out : 16), &a, &grid);
-        if (b == 1 && !one_bit_decompress_kind(kind)) { kind = 2; a.G = 1; grid = (uint32_t)L.P; }      // the element-per-thread kernel
+        const int kind = plan_decompress(L, D, H, W, B, es, reinterpret_cast<const void*>(all_out ? all_out : 16), &a, &grid);
         for (int i = 0; i < cnt; ++i) { a.tab.pk[i] = packed[i0 + i]; a.tab.xhat[i] = xhat[i0 + i]; }
         a.rg = rg;
         // LDS of the streaming kernels: staged codes, meta and LFC of G planes (+ the block table)
@@ -1153,13 +1141,17 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     const char* tn = dt == DIVISION_BF16 ? "bf16_t" : dt == DIVISION_F32_C16 ? "f32c16_t" : "float";
     int n;
     if (b == 1 && direction == 0) {
-        RegsArgs ra{}; LaneArgs la{}; StripArgs sa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nw = 1;
+        RegsArgs ra{}; LaneArgs la{}; StripArgs sa{}; ItemsArgs ia{}; UnitsArgs ua{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nw = 1;
         if (plan_regs(L, D, H, W, B, es, data, &ra, &grid, &lds, &nw))
             n = snprintf(out, cap, "compress_regs%s<%s, 1, %d, %d>", sfx, tn, (B == 4 || B == 8) ? B : 0, nw);
         else if (plan_lane(L, es, data, &la, &grid, &lds))
             n = snprintf(out, cap, "compress_lane<%s, 1>", tn);
         else if (flat && plan_strip(L, H, W, B, es, data, &sa, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_strip<%s, 1, %d, %d>", tn, vec / 100, vec % 100);
+        else if (flat && plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
+            n = snprintf(out, cap, "compress_items<%s, 1, %d, %d, %d>", tn, B, vec, H == 1 ? 1 : B);
+        else if (plan_units(L, D, H, W, B, es, data, &ua, &grid, &lds, &nw) && nw != 16)
+            n = snprintf(out, cap, "compress_units<%s, 1, %d>", tn, nw);
         else
             n = snprintf(out, cap, "compress_any%s<%s, 1>", sfx, tn);
     } else if (direction == 0) {
@@ -1192,8 +1184,7 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
             n = snprintf(out, cap, "compress_any%s<%s, %d>", sfx, tn, b);
     } else {
         DecArgs a{}; uint32_t grid = 0;
-        int kind = plan_decompress(L, D, H, W, B, es, data, &a, &grid);
-        if (b == 1 && !one_bit_decompress_kind(kind)) kind = 2;
+        const int kind = plan_decompress(L, D, H, W, B, es, data, &a, &grid);
         if (kind == 6)
             n = snprintf(out, cap, "decompress_units<%s, %d, %d>", tn, b, (int)a.G);
         else if (kind == 7)

@@ -138,6 +138,8 @@ def codec_plane(x, H, W, B, b, seed, plane, c16=False):
         delta = bf16_floor(delta)
     rng = f32(hmax - delta)
     usable = _range_is_usable(rng)
+    if usable and c16 and bf16_ceil(f32(rng / L)) >= Fraction(2) ** 128:
+        usable = False               # the step has no finite bfloat16 to be cached as (1-bit codes only)
     if usable and c16:
         Delta = bf16_ceil(f32(rng / L))
         inv = f32(1 / Delta)

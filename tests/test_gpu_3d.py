@@ -10,7 +10,8 @@ from tests.parity import to_host_array
 pytestmark = pytest.mark.gpu
 
 CASES = [
-    ((2, 3, 4, 14, 14), 8, 1), ((2, 2, 3, 9, 11), 4, 1),     # 1-bit codes: the general kernels
+    ((2, 3, 4, 14, 14), 8, 1), ((2, 2, 3, 9, 11), 4, 1), ((2, 2, 3, 35, 35), 4, 1), ((2, 2, 8, 27, 27), 8, 1), ((5, 3, 4, 9, 9), 8, 1),     # 1-bit codes: the units kernels
+    ((1, 2, 33, 35, 37), 16, 1), ((3, 4, 2, 4, 6), 8, 1), ((4, 9, 3, 3, 3), 8, 1),     # and the general, one-block and lane kernels
     ((2, 3, 16, 28, 28), 8, 1), ((2, 3, 4, 28, 28), 8, 1), ((1, 2, 20, 44, 48), 8, 1), ((1, 2, 9, 36, 40), 8, 1),   # and the register kernel
     # shape (N, C, D, H, W), B, b                 what it exercises
     ((2, 3, 8, 8, 8), 4, 2),                      # cubes of 4: LDS kernel, vector rows

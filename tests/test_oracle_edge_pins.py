@@ -49,7 +49,7 @@ def _one_plane(values, H, W, B, b, dt, seed=7):
 # ---------------------------------------------------------------- lower edge: residual range around 2^-90
 
 @pytest.mark.parametrize("dt", [oracle.F32, C16])
-@pytest.mark.parametrize("b", [2, 4, 8])
+@pytest.mark.parametrize("b", [1, 2, 4, 8])
 def test_residual_range_just_below_at_and_just_above_the_lower_edge(dt, b):
     """A 1 x 2 plane (0, v) under B = 2 is one block with mean v/2 (exact: a halving), so the
     residuals are -v/2 and v - v/2 and their range is v, up to the one rounding of the subtraction
@@ -107,7 +107,7 @@ def test_a_larger_plane_whose_range_sits_on_the_lower_edge(dt):
 # ---------------------------------------------------------------- upper edge: ranges beyond binary32
 
 @pytest.mark.parametrize("dt", [oracle.F32, C16])
-@pytest.mark.parametrize("b", [2, 4])
+@pytest.mark.parametrize("b", [1, 2, 4])
 def test_residual_range_that_overflows_binary32_is_degenerate(dt, b):
     """(-a, a) with a = 2^127 (a bfloat16 number too): mean 0, residuals -a and a, both finite, but
     a - (-a) = 2^128 is not a binary32 number.  The plane is not quantised: Delta = 0, codes 0,
@@ -119,7 +119,7 @@ def test_residual_range_that_overflows_binary32_is_degenerate(dt, b):
     assert xh.tolist() == [-a, -a]
 
 
-@pytest.mark.parametrize("b", [2, 4])
+@pytest.mark.parametrize("b", [1, 2, 4])
 def test_largest_finite_residual_range_is_still_quantised(b):
     """(-m/2, m/2) with m the largest binary32: the range is m itself, finite, so the plane is
     quantised: Delta = fl(m / L) > 0, the extremes take the end codes."""
@@ -138,6 +138,30 @@ def test_largest_finite_residual_range_in_the_bfloat16_cached_format():
     big = float(oracle.bf16_to_f32(np.array([0x7F7F], dtype=np.uint16))[0])
     delta, Delta, q, xh = _one_plane([-big / 2, big / 2], 1, 2, 2, 2, C16)
     assert delta == -big / 2 and Delta > 0 and q[0] == 0 and q[1] >= 2
+
+
+def test_a_step_beyond_the_largest_bfloat16_makes_the_plane_degenerate_in_the_cached_format():
+    """1-bit codes, bfloat16-cached tuple: (-a, a) with a = 1.99609375 * 2^126 (nine significant bits, not a
+    bfloat16).  delta = -a rounded down to bfloat16 = -2^127, the range a + 2^127 = 1.998046875 * 2^127 is a finite
+    binary32 number, but Delta = range / 1 rounded up to bfloat16 would be 2^128: there is no finite step to cache.
+    The plane is not quantised: Delta = 0, codes 0, xhat = H^L + delta = -2^127 (finite, not NaN).  In the fp32
+    format the same plane is quantised: Delta = 2a, codes 0 and 1, rebuilt exactly."""
+    a = 1.99609375 * 2.0 ** 126
+    delta, Delta, q, xh = _one_plane([-a, a], 1, 2, 2, 1, C16)
+    assert delta == -(2.0 ** 127) and Delta == 0.0
+    assert q.tolist() == [0, 0]
+    assert xh.tolist() == [-(2.0 ** 127)] * 2 and np.isfinite(xh).all()
+    delta, Delta, q, xh = _one_plane([-a, a], 1, 2, 2, 1, oracle.F32)
+    assert delta == -a and Delta == 2 * a and q.tolist() == [0, 1] and xh.tolist() == [-a, a]
+
+
+def test_the_largest_step_that_is_a_bfloat16_is_still_used():
+    """1-bit codes, cached format: (-a, a) with a = 1.9921875 * 2^126 (a bfloat16): range = largest bfloat16 exactly,
+    Delta = range, the extremes take codes 0 and 1 and are rebuilt exactly."""
+    big = float(oracle.bf16_to_f32(np.array([0x7F7F], dtype=np.uint16))[0])
+    delta, Delta, q, xh = _one_plane([-big / 2, big / 2], 1, 2, 2, 1, C16)
+    assert delta == -big / 2 and Delta == big
+    assert q.tolist() == [0, 1] and xh.tolist() == [-big / 2, big / 2]
 
 
 # ---------------------------------------------------------------- Dropout: the element whose bits equal the threshold
