@@ -293,6 +293,7 @@ VARIANTS = [
     ("block size 12, CIFAR", (256, 256, 8, 8), 12, 2),
     ("8-bit codes", (64, 256, 56, 56), 8, 8), ("4-bit codes", (64, 256, 56, 56), 8, 4), ("1-bit codes", (64, 256, 56, 56), 8, 1),
     ("1-bit codes", (64, 64, 112, 112), 8, 1), ("1-bit codes", (64, 512, 28, 28), 8, 1), ("1-bit codes", (64, 1024, 14, 14), 8, 1), ("1-bit codes", (64, 2048, 7, 7), 8, 1),
+    ("1-bit codes, 1-D map", (256, 128, 1, 768), 8, 1), ("1-bit codes, odd width", (256, 96, 55, 55), 8, 1),
     ("1-D map", (256, 128, 1, 768), 8, 4), ("1-D map", (64, 384, 1, 3136), 8, 4), ("1-D map", (256, 768, 1, 196), 16, 2), ("1-D map", (64, 196, 1, 3072), 64, 2),
     ("3-D map", (32, 64, 16, 56, 56), 8, 2), ("3-D map", (32, 128, 8, 28, 28), 8, 2), ("3-D map", (32, 256, 4, 14, 14), 8, 2),
     ("3-D map", (32, 512, 2, 7, 7), 8, 2), ("3-D map", (64, 64, 16, 16, 16), 8, 2), ("3-D map", (64, 64, 16, 16, 16), 4, 2),

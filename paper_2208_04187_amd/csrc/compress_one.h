@@ -53,6 +53,7 @@ template <typename T, int BITS, int K>
 __global__ void __launch_bounds__(64) compress_one(OneArgs a) {
     constexpr uint32_t EPV = 16 / sizeof(T);
     constexpr uint32_t CBV = EPV * BITS / 8;
+    constexpr bool HALF = EPV * BITS == 4;                // 1-bit codes of a 4-element vector: half a byte
     constexpr float Lf = float((1 << BITS) - 1);
     constexpr uint32_t kDrop = 0x80000000u;              // an offset past every buffer here: the access is dropped
     const uint32_t tid = threadIdx.x;
@@ -114,8 +115,9 @@ __global__ void __launch_bounds__(64) compress_one(OneArgs a) {
         meta_store(pt.meta, p, delta, Delta, kC16<T>);
         lfc_store<T>(pt.lfc, (size_t)p, lfc, kC16<T>);
         uint8_t* cbase = cwave + (size_t)pl * a.WPP * 4;
-        const uint32_t padb = a.WPP * 4 - a.qv * CBV;                 // pad bytes of the last word are zero
-        for (uint32_t t = 0; t < padb; ++t) cbase[a.qv * CBV + t] = 0;
+        const uint32_t cbytes = HALF ? (a.qv + 1u) / 2u : a.qv * CBV;
+        const uint32_t padb = a.WPP * 4 - cbytes;                     // pad bytes of the last word are zero
+        for (uint32_t t = 0; t < padb; ++t) cbase[cbytes + t] = 0;
     }
     // ---- residual, Quant, packing
     const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(cwave, 0, (int)(Gc * a.WPP * 4u), 0x00020000);
@@ -134,7 +136,12 @@ __global__ void __launch_bounds__(64) compress_one(OneArgs a) {
 #pragma unroll
             for (int j = EPV / 2 - 1; j >= 0; --j)
                 c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
-            if constexpr (CBV == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, co, 0, 0);
+            if constexpr (HALF) {
+                // the even lane of a pair stores the byte of both vectors (a vector past the plane gives zeros)
+                c = co != kDrop ? c : 0u;
+                c |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)c, 0xB1, 0xf, 0xf, true) << 4;     // quad_perm [1,0,3,2]
+                __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, co != kDrop && (sub & 1u) == 0 ? pl * a.WPP * 4u + (u >> 1) : kDrop, 0, 0);
+            } else if constexpr (CBV == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, co, 0, 0);
             else if constexpr (CBV == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c, crs, co, 0, 0);
             else __builtin_amdgcn_raw_buffer_store_b32(c, crs, co, 0, 0);
         } else {
@@ -168,6 +175,7 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
     static_assert(R * NG == K, "whole groups");
     constexpr uint32_t EPV = 16 / sizeof(T);
     constexpr uint32_t CBV = EPV * BITS / 8;
+    constexpr bool HALF = EPV * BITS == 4;                // 1-bit codes of a 4-element vector: half a byte
     constexpr float Lf = float((1 << BITS) - 1);
     constexpr uint32_t kDrop = 0x80000000u;              // an offset past every buffer here (and no wrap when a round's offset is added): the access is dropped
     const uint32_t tid = threadIdx.x;
@@ -244,8 +252,9 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
     if (live && sub == 0) {
         meta_store(pt.meta, p, delta, Delta, kC16<T>);
         uint8_t* cbase = cwave + (size_t)pl * a.WPP * 4;
-        const uint32_t padb = a.WPP * 4 - a.qv * CBV;                 // pad bytes of the last word are zero
-        for (uint32_t t = 0; t < padb; ++t) cbase[a.qv * CBV + t] = 0;
+        const uint32_t cbytes = HALF ? (a.qv + 1u) / 2u : a.qv * CBV;
+        const uint32_t padb = a.WPP * 4 - cbytes;                     // pad bytes of the last word are zero
+        for (uint32_t t = 0; t < padb; ++t) cbase[cbytes + t] = 0;
     }
     // ---- residual, Quant, packing
 #pragma unroll
@@ -269,7 +278,11 @@ __global__ void __launch_bounds__(64) compress_line(OneArgs a) {
 #pragma unroll
             for (int j = EPV / 2 - 1; j >= 0; --j)
                 c = push_pair<BITS>(c, h[2 * j], h[2 * j + 1], delta, invs, xw0 + (uint32_t)j * kWeyl, k2, rscale);
-            if constexpr (CBV == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, co, 0, 0);
+            if constexpr (HALF) {
+                c = wr ? c : 0u;
+                c |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)c, 0xB1, 0xf, 0xf, true) << 4;     // quad_perm [1,0,3,2]
+                __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, wr && (sub & 1u) == 0 ? pl * a.WPP * 4u + (u >> 1) : kDrop, 0, 0);
+            } else if constexpr (CBV == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)c, crs, co, 0, 0);
             else if constexpr (CBV == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c, crs, co, 0, 0);
             else __builtin_amdgcn_raw_buffer_store_b32(c, crs, co, 0, 0);
         } else {

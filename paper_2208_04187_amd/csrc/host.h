@@ -844,6 +844,20 @@ struct DecLaunch {
     DecArgs a;
 };
 
+template <typename T, int BITS>
+hipError_t launch_one(const OneArgs& a, dim3 gd, hipStream_t st) {
+    void (*kern)(OneArgs) = a.K == 3 ? compress_one<T, BITS, 3> : a.K == 6 ? compress_one<T, BITS, 6> : compress_one<T, BITS, 13>;
+    hipLaunchKernelGGL(kern, gd, dim3(64), 0, st, a);
+    return hipGetLastError();
+}
+template <typename T, int BITS>
+hipError_t launch_line(const OneArgs& a, dim3 gd, hipStream_t st) {
+    void (*kern)(OneArgs) = a.K == 12 ? (a.NG == 12 ? compress_line<T, BITS, 12, 12> : a.NG == 6 ? compress_line<T, BITS, 12, 6> : compress_line<T, BITS, 12, 4>)
+                          : a.K == 6 ? compress_line<T, BITS, 6> : compress_line<T, BITS, 13>;
+    hipLaunchKernelGGL(kern, gd, dim3(64), 0, st, a);
+    return hipGetLastError();
+}
+
 template <typename T>
 hipError_t do_compress(const CompLaunch& c, int b) {
     const dim3 gd(c.gx, c.gy);
@@ -851,13 +865,15 @@ hipError_t do_compress(const CompLaunch& c, int b) {
     const size_t lds = c.lds;
     const bool flat = c.flat != 0;
     if (b == 1) {
-        // 1-bit codes: the register, strip, lane, items and units kernels, else the general one (the planner picks nothing else)
+        // 1-bit codes: the kernels that have an instance for them (the planner picks nothing else)
         switch (c.kind) {
             case REGS: return launch_regs<T, 1>(c.B, c.nw, c.ra, gd, lds, st);
             case STRIP: return launch_strip<T, 1>(c.vec, c.sa, gd, lds, st);
             case LANE: hipLaunchKernelGGL((compress_lane<T, 1>), gd, dim3(64), lds, st, c.la); return hipGetLastError();
             case ITEMS: return launch_items<T, 1>(c.B, c.vec, c.ia, gd, lds, st);
             case UNITS: return launch_units<T, 1>(c.nw, c.ua, gd, lds, st);
+            case ONE: return launch_one<T, 1>(c.oa, gd, st);
+            case LINE: return launch_line<T, 1>(c.oa, gd, st);
             default: {
                 void (*kern)(AnyArgs) = flat ? compress_any<T, 1> : compress_any_3d<T, 1>;
                 hipLaunchKernelGGL(kern, gd, dim3(kThreads), 0, st, c.g);
@@ -875,17 +891,8 @@ hipError_t do_compress(const CompLaunch& c, int b) {
             case WAVE: return launch_wave<T, BITS>(c.B, c.vec, c.wa, gd, lds, st);
             case TILE: return launch_tile<T, BITS>(c.B, c.vec, c.a, gd, lds, st);
             case LANE: hipLaunchKernelGGL((compress_lane<T, BITS>), gd, dim3(64), lds, st, c.la); return hipGetLastError();
-            case ONE: {
-                void (*kern)(OneArgs) = c.oa.K == 3 ? compress_one<T, BITS, 3> : c.oa.K == 6 ? compress_one<T, BITS, 6> : compress_one<T, BITS, 13>;
-                hipLaunchKernelGGL(kern, gd, dim3(64), 0, st, c.oa);
-                return hipGetLastError();
-            }
-            case LINE: {
-                void (*kern)(OneArgs) = c.oa.K == 12 ? (c.oa.NG == 12 ? compress_line<T, BITS, 12, 12> : c.oa.NG == 6 ? compress_line<T, BITS, 12, 6> : compress_line<T, BITS, 12, 4>)
-                                      : c.oa.K == 6 ? compress_line<T, BITS, 6> : compress_line<T, BITS, 13>;
-                hipLaunchKernelGGL(kern, gd, dim3(64), 0, st, c.oa);
-                return hipGetLastError();
-            }
+            case ONE: return launch_one<T, BITS>(c.oa, gd, st);
+            case LINE: return launch_line<T, BITS>(c.oa, gd, st);
             case ROWS: {
                 void (*kern)(RowsArgs) = flat ? compress_rows<T, BITS> : compress_rows_3d<T, BITS>;
                 const hipError_t e = allow_large_lds(kern, lds);
@@ -1053,28 +1060,22 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
             g.LH = (uint32_t)L.LH; g.LW = (uint32_t)L.LW; g.nb = (uint32_t)L.nb; g.WPP = (uint32_t)L.WPP; g.B = (uint32_t)B;
             grid = (uint32_t)L.P;
         };
-        if (b == 1) {
-            // 1-bit codes (Q = 1): the kernels of the large shapes, else the general kernel
-            if (plan_regs(L, D, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
-            else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
-            else if (flat && plan_strip(L, H, W, B, es, xa, &sa, &grid, &lds, &vec)) { kind = STRIP; sa.tab = tab; sa.rg = rg; }
-            else if (flat && plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
-            else if (plan_units(L, D, H, W, B, es, xa, &ua, &grid, &lds, &nw) && nw != 16) { kind = UNITS; ua.tab = tab; ua.rg = rg; }
-            else use_any();
-        }
-        else if (line_first(L, es) && plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
+        // 1-bit codes (Q = 1) have no instance of the wave, tile, rows and plane kernels, nor of the units kernel
+        // with sixteen wavefronts: those shapes go to the general kernel
+        const bool wide = b != 1;
+        if (line_first(L, es) && plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
         else if (plan_regs(L, D, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
         else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
         else if (plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
         else if (flat && plan_strip(L, H, W, B, es, xa, &sa, &grid, &lds, &vec)) { kind = STRIP; sa.tab = tab; sa.rg = rg; }
         else if (flat && plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
-        else if (!one_shape(L, es, xa) && plan_units(L, D, H, W, B, es, xa, &ua, &grid, &lds, &nw)) { kind = UNITS; ua.tab = tab; ua.rg = rg; }
-        else if (flat && plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
+        else if (!one_shape(L, es, xa) && plan_units(L, D, H, W, B, es, xa, &ua, &grid, &lds, &nw) && (wide || nw != 16)) { kind = UNITS; ua.tab = tab; ua.rg = rg; }
+        else if (wide && flat && plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
             kind = WAVE; wa.tab = tab; wa.rg = rg;
-        } else if (flat && plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) { kind = TILE; a.tab = tab; a.rg = rg; }
+        } else if (wide && flat && plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) { kind = TILE; a.tab = tab; a.rg = rg; }
         else if (plan_one(L, es, xa, &oa, &grid)) { kind = ONE; oa.tab = tab; oa.rg = rg; lds = 0; }
-        else if (plan_rows(L, D, H, W, B, b, es, xa, &wa2, &grid, &lds)) { kind = ROWS; wa2.tab = tab; wa2.rg = rg; }
-        else if (plan_plane(L, D, H, W, B, es, xa, &pa, &grid, &lds)) { kind = PLANE; pa.tab = tab; pa.rg = rg; }
+        else if (wide && plan_rows(L, D, H, W, B, b, es, xa, &wa2, &grid, &lds)) { kind = ROWS; wa2.tab = tab; wa2.rg = rg; }
+        else if (wide && plan_plane(L, D, H, W, B, es, xa, &pa, &grid, &lds)) { kind = PLANE; pa.tab = tab; pa.rg = rg; }
         else use_any();
         CompLaunch c{};
         c.kind = kind; c.B = B; c.vec = vec; c.nt = nt; c.nw = nw; c.flat = flat;
@@ -1140,21 +1141,8 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
     const size_t es = dt == DIVISION_BF16 ? 2 : 4;
     const char* tn = dt == DIVISION_BF16 ? "bf16_t" : dt == DIVISION_F32_C16 ? "f32c16_t" : "float";
     int n;
-    if (b == 1 && direction == 0) {
-        RegsArgs ra{}; LaneArgs la{}; StripArgs sa{}; ItemsArgs ia{}; UnitsArgs ua{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nw = 1;
-        if (plan_regs(L, D, H, W, B, es, data, &ra, &grid, &lds, &nw))
-            n = snprintf(out, cap, "compress_regs%s<%s, 1, %d, %d>", sfx, tn, (B == 4 || B == 8) ? B : 0, nw);
-        else if (plan_lane(L, es, data, &la, &grid, &lds))
-            n = snprintf(out, cap, "compress_lane<%s, 1>", tn);
-        else if (flat && plan_strip(L, H, W, B, es, data, &sa, &grid, &lds, &vec))
-            n = snprintf(out, cap, "compress_strip<%s, 1, %d, %d>", tn, vec / 100, vec % 100);
-        else if (flat && plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
-            n = snprintf(out, cap, "compress_items<%s, 1, %d, %d, %d>", tn, B, vec, H == 1 ? 1 : B);
-        else if (plan_units(L, D, H, W, B, es, data, &ua, &grid, &lds, &nw) && nw != 16)
-            n = snprintf(out, cap, "compress_units<%s, 1, %d>", tn, nw);
-        else
-            n = snprintf(out, cap, "compress_any%s<%s, 1>", sfx, tn);
-    } else if (direction == 0) {
+    if (direction == 0) {
+        const bool wide = b != 1;        // as in compress_impl
         TileArgs a{}; WaveArgs wa{}; RegsArgs ra{}; ItemsArgs ia{}; LaneArgs la{}; RowsArgs wa2{}; PlaneArgs pa{}; OneArgs oa{}; UnitsArgs ua{}; StripArgs sa{}; size_t lds = 0; uint32_t grid = 0; int vec = 1, nt = 64, nw = 1;
         if (line_first(L, es) && plan_line(L, D, H, B, es, data, &oa, &grid))
             n = snprintf(out, cap, "compress_line<%s, %d, %u, %u>", tn, b, oa.K, oa.NG);
@@ -1168,17 +1156,17 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
             n = snprintf(out, cap, "compress_strip<%s, %d, %d, %d>", tn, b, vec / 100, vec % 100);
         else if (flat && plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_items<%s, %d, %d, %d, %d>", tn, b, B, vec, H == 1 ? 1 : B);
-        else if (!one_shape(L, es, data) && plan_units(L, D, H, W, B, es, data, &ua, &grid, &lds, &nw))
+        else if (!one_shape(L, es, data) && plan_units(L, D, H, W, B, es, data, &ua, &grid, &lds, &nw) && (wide || nw != 16))
             n = snprintf(out, cap, "compress_units<%s, %d, %d>", tn, b, nw);
-        else if (flat && plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))
+        else if (wide && flat && plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_wave<%s, %d, %d, %d>", tn, b, B, vec);
-        else if (flat && plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
+        else if (wide && flat && plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
             n = snprintf(out, cap, "compress_tile<%s, %d, %d, %d, %d>", tn, b, B, vec, nt);
         else if (plan_one(L, es, data, &oa, &grid))
             n = snprintf(out, cap, "compress_one<%s, %d, %u>", tn, b, oa.K);
-        else if (plan_rows(L, D, H, W, B, b, es, data, &wa2, &grid, &lds))
+        else if (wide && plan_rows(L, D, H, W, B, b, es, data, &wa2, &grid, &lds))
             n = snprintf(out, cap, "compress_rows%s<%s, %d>", sfx, tn, b);
-        else if (plan_plane(L, D, H, W, B, es, data, &pa, &grid, &lds))
+        else if (wide && plan_plane(L, D, H, W, B, es, data, &pa, &grid, &lds))
             n = snprintf(out, cap, "compress_plane%s<%s, %d>", sfx, tn, b);
         else
             n = snprintf(out, cap, "compress_any%s<%s, %d>", sfx, tn, b);
