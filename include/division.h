@@ -97,9 +97,9 @@ int division_packed_layout(int64_t N, int64_t C, int64_t H, int64_t W,
  *           does not divide H or W the border windows average their valid
  *           elements only.
  *   b       bits per HFC code (the paper's Q): 1, 2, 4 or 8.  2, 4 and 8 have fast compress kernels
- *           for every shape; 1 has them for the shapes of the register, strip, lane, items, units,
- *           one-block and 1-D kernels (the ResNet-50 and CIFAR maps, odd widths, token maps) and is
- *           compressed by the general kernel (slow) elsewhere.  Decompression is fast for every b.
+ *           for every shape; 1 has them under B = 4 and 8 (and for the ResNet-50, CIFAR and token
+ *           maps under any B) and is compressed by the general kernel (slow) for other block sizes on
+ *           small planes, planes beyond LDS and small 3-D maps.  Decompression is fast for every b.
  *   seed    selects the stochastic-rounding stream of Eq. (quantization); the
  *           output is a pure function of (x, shape, dt, B, b, seed) and does
  *           not depend on the launch geometry or the device.

@@ -46,7 +46,7 @@
 //                    plane's codes and LFC in flight
 // Code widths: 2, 4 and 8 bits in every kernel; 1 bit (four codes of a unit = half a byte) in compress_regs,
 // compress_strip, compress_lane, compress_items, compress_units (up to 8 wavefronts), compress_one, compress_line,
-// compress_any and in
+// compress_tile, compress_any and in
 // every decompress kernel.
 // The kernels with a _3d twin take N x C x D x H x W maps with B x B x B blocks (Appendix D).
 // Every kernel takes a table of up to 8 maps of one shape (blockIdx.y picks the map).

@@ -874,6 +874,7 @@ hipError_t do_compress(const CompLaunch& c, int b) {
             case UNITS: return launch_units<T, 1>(c.nw, c.ua, gd, lds, st);
             case ONE: return launch_one<T, 1>(c.oa, gd, st);
             case LINE: return launch_line<T, 1>(c.oa, gd, st);
+            case TILE: return launch_tile<T, 1>(c.B, c.vec, c.a, gd, lds, st);
             default: {
                 void (*kern)(AnyArgs) = flat ? compress_any<T, 1> : compress_any_3d<T, 1>;
                 hipLaunchKernelGGL(kern, gd, dim3(kThreads), 0, st, c.g);
@@ -1060,8 +1061,8 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
             g.LH = (uint32_t)L.LH; g.LW = (uint32_t)L.LW; g.nb = (uint32_t)L.nb; g.WPP = (uint32_t)L.WPP; g.B = (uint32_t)B;
             grid = (uint32_t)L.P;
         };
-        // 1-bit codes (Q = 1) have no instance of the wave, tile, rows and plane kernels, nor of the units kernel
-        // with sixteen wavefronts: those shapes go to the general kernel
+        // 1-bit codes (Q = 1) have no instance of the wave, rows and plane kernels, nor of the units kernel with
+        // sixteen wavefronts: the wave kernel's shapes go to the tile kernel, the others to the general kernel
         const bool wide = b != 1;
         if (line_first(L, es) && plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
         else if (plan_regs(L, D, H, W, B, es, xa, &ra, &grid, &lds, &nw)) { kind = REGS; ra.tab = tab; ra.rg = rg; }
@@ -1072,7 +1073,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         else if (!one_shape(L, es, xa) && plan_units(L, D, H, W, B, es, xa, &ua, &grid, &lds, &nw) && (wide || nw != 16)) { kind = UNITS; ua.tab = tab; ua.rg = rg; }
         else if (wide && flat && plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
             kind = WAVE; wa.tab = tab; wa.rg = rg;
-        } else if (wide && flat && plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) { kind = TILE; a.tab = tab; a.rg = rg; }
+        } else if (flat && plan_tile(L, H, W, B, b, es, xa, &a, &grid, &lds, &vec, &nt)) { kind = TILE; a.tab = tab; a.rg = rg; }
         else if (plan_one(L, es, xa, &oa, &grid)) { kind = ONE; oa.tab = tab; oa.rg = rg; lds = 0; }
         else if (wide && plan_rows(L, D, H, W, B, b, es, xa, &wa2, &grid, &lds)) { kind = ROWS; wa2.tab = tab; wa2.rg = rg; }
         else if (wide && plan_plane(L, D, H, W, B, es, xa, &pa, &grid, &lds)) { kind = PLANE; pa.tab = tab; pa.rg = rg; }
@@ -1160,7 +1161,7 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
             n = snprintf(out, cap, "compress_units<%s, %d, %d>", tn, b, nw);
         else if (wide && flat && plan_wave(L, H, W, B, b, es, data, &wa, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_wave<%s, %d, %d, %d>", tn, b, B, vec);
-        else if (wide && flat && plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
+        else if (flat && plan_tile(L, H, W, B, b, es, data, &a, &grid, &lds, &vec, &nt))
             n = snprintf(out, cap, "compress_tile<%s, %d, %d, %d, %d>", tn, b, B, vec, nt);
         else if (plan_one(L, es, data, &oa, &grid))
             n = snprintf(out, cap, "compress_one<%s, %d, %u>", tn, b, oa.K);

@@ -487,7 +487,12 @@ ONE_BIT_CASES = [
     ((3, 5, 12, 12), 64, "compress_one<float, 1, ", "decompress_"),                   # 36 vectors
     ((3, 5, 6, 10), 32, "compress_one<float, 1, ", "decompress_"),                    # 15 vectors
     ((3, 5, 54, 57), 64, "compress_units<float, 1, 2>", "decompress_"),
-    ((2, 3, 64, 64), 8, "compress_any<float, 1>", "decompress_stream"),
+    ((2, 3, 64, 64), 8, "compress_tile<float, 1, 8, 4, 256>", "decompress_stream"),
+    ((2, 3, 40, 40), 4, "compress_tile<float, 1, 4, 4, 256>", "decompress_stream"),
+    ((2, 3, 20, 30), 4, "compress_tile<float, 1, 4, 2, 256>", "decompress_"),
+    ((5, 7, 15, 15), 4, "compress_tile<float, 1, 4, 1, 256>", "decompress_words"),
+    ((2, 3, 44, 46), 8, "compress_tile<float, 1, 8, 2, 256>", "decompress_"),
+    ((1, 2, 300, 300), 8, "compress_any<float, 1>", "decompress_"),
     ((2, 3, 28, 28), 3, "compress_any<float, 1>", "decompress_table"),
     ((2, 2, 100, 37), 8, "compress_units<float, 1, 2>", "decompress_table"),
     ((2, 3, 55, 55), 4, "compress_units<float, 1, 2>", "decompress_units"),
@@ -497,10 +502,11 @@ ONE_BIT_CASES = [
     ((2, 3, 35, 35), 8, "compress_units<float, 1, 1>", "decompress_units"),
     ((2, 3, 73, 73), 8, "compress_units<float, 1, 4>", "decompress_units"),
     ((1, 3, 125, 125), 8, "compress_units<float, 1, 8>", "decompress_units"),
-    ((1, 2, 147, 147), 8, "compress_any<float, 1>", "decompress_units"),          # sixteen wavefronts per plane: no 1-bit instance
+    ((1, 2, 147, 147), 8, "compress_tile<float, 1, 8, 1, 256>", "decompress_units"),   # sixteen wavefronts per plane: no 1-bit instance of the units kernel
+    ((1, 2, 147, 147), 18, "compress_any<float, 1>", "decompress_units"),
     ((5, 7, 17, 17), 8, "compress_units<float, 1, 0>", "decompress_words"),        # 32 lanes per plane
     ((5, 7, 18, 17), 4, "compress_units<float, 1, 0>", "decompress_words"),
-    ((5, 7, 13, 13), 8, "compress_any<float, 1>", "decompress_words"),
+    ((5, 7, 13, 13), 8, "compress_tile<float, 1, 8, 1, 256>", "decompress_words"),
     ((3, 5, 9, 6), 4, "compress_items<float, 1, 4, 2, 4>", "decompress_"),
     ((4, 8, 8, 8), 4, "compress_items<float, 1, 4, 4, 4>", "decompress_stream"),
     ((4, 8, 8, 8), 8, "compress_items<float, 1, 8, 4, 8>", "decompress_stream"),

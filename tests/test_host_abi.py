@@ -160,8 +160,12 @@ DISPATCH = [
     ((256, 96, 55, 55), 8, 1, "compress_units<float, 1, 2>", "decompress_units<float, 1, 2>"),
     ((128, 768, 17, 17), 8, 1, "compress_units<float, 1, 0>", "decompress_words<float, 1>"),
     ((256, 256, 8, 8), 4, 1, "compress_items<float, 1, 4, 4, 4>", "decompress_stream<float, 1>"),
-    ((64, 64, 147, 147), 8, 1, "compress_any<float, 1>", "decompress_units<float, 1, 16>"),
-    ((64, 96, 64, 64), 8, 1, "compress_any<float, 1>", "decompress_stream<float, 1>"),
+    ((64, 64, 147, 147), 8, 1, "compress_tile<float, 1, 8, 1, 256>", "decompress_units<float, 1, 16>"),
+    ((64, 64, 147, 147), 18, 1, "compress_any<float, 1>", "decompress_units<float, 1, 16>"),
+    ((64, 96, 64, 64), 8, 1, "compress_tile<float, 1, 8, 4, 256>", "decompress_stream<float, 1>"),
+    ((256, 128, 1, 768), 8, 1, "compress_line<float, 1, 6, 1>", "decompress_stream<float, 1>"),
+    ((64, 256, 56, 56), 64, 1, "compress_one<float, 1, 13>", "decompress_stream<float, 1>"),
+    ((64, 512, 28, 28), 3, 1, "compress_any<float, 1>", "decompress_table<float, 1>"),
     ((64, 64, 112, 112), 8, 2, "compress_regs<float, 2, 8, 4>", "decompress_stream<float, 2>"),
     ((2, 3, 224, 224), 8, 2, "compress_regs<float, 2, 8, 16>", "decompress_stream<float, 2>"),
     ((64, 512, 28, 28), 8, 2, "compress_strip<float, 2, 28, 8>", "decompress_stream<float, 2>"),
