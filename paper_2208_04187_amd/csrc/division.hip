@@ -24,6 +24,9 @@
 //                    or two rows), the round read with coalesced loads and handed out through LDS, extremes by
 //                    DPP, block sums by DPP (B = 8) or through LDS (relu_compress_strip: B = 8 with a Relu
 //                    applied to the round as its loads arrive)
+//   compress_rowstrip  planes of an odd width with an instance (13, 15, 17, 27, 35, 55) under B = 8 (4): the strip
+//                    kernel with a row per lane; rows start in the middle of an element pair every other time, so a
+//                    lane quantises the pairs its row touches and ORs its code bits into the plane's words in LDS
 //   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8: a lane per
 //                    pooling item, loaded straight from global memory, DPP reductions (relu_compress_items:
 //                    the same with a Relu applied to the rows as they arrive)
@@ -45,8 +48,8 @@
 //                    consecutive elements per lane step, block table made once per workgroup, the next
 //                    plane's codes and LFC in flight
 // Code widths: 2, 4 and 8 bits in every kernel; 1 bit (four codes of a unit = half a byte) in compress_regs,
-// compress_strip, compress_lane, compress_items, compress_units (up to 8 wavefronts), compress_one, compress_line,
-// compress_tile, compress_any and in
+// compress_strip, compress_rowstrip, compress_lane, compress_items, compress_units (up to 8 wavefronts), compress_one,
+// compress_line, compress_tile, compress_any and in
 // every decompress kernel.
 // The kernels with a _3d twin take N x C x D x H x W maps with B x B x B blocks (Appendix D).
 // Every kernel takes a table of up to 8 maps of one shape (blockIdx.y picks the map).
@@ -119,6 +122,7 @@ constexpr int kLoadReuse = 0;
 #include "compress_wave.h"
 #include "compress_items.h"
 #include "compress_strip.h"
+#include "compress_rowstrip.h"
 #include "compress_lane.h"
 #include "compress_regs.h"
 #include "compress_units.h"

@@ -358,6 +358,48 @@ hipError_t launch_strip(int width, const StripArgs& a, dim3 grid, size_t lds, hi
     return hipGetLastError();
 }
 
+// Fills the plan of the row-per-lane strip kernel: 2-D maps of an odd width it has an instance for (13, 15,
+// 17, 27, 35, 55) with at most 16 (13, 15), 32 (17, 27) or 64 rows, under B = 8 (B = 4 too on 13, 15 and 55),
+// 16-byte aligned.
+// *width = 100 * W + B names the instance.
+bool plan_rowstrip(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* x,
+                   StripArgs* a, uint32_t* grid, size_t* lds, int* width) {
+    if (((uintptr_t)x % 16) != 0) return false;
+    uint64_t S;
+    if (W == 13 || W == 15) S = 16;
+    else if (W == 17 || W == 27) S = 32;
+    else if (W == 35 || W == 55) S = 64;
+    else return false;
+    if (!(B == 8 || (B == 4 && (S == 16 || W == 55))) || H < 2 || (uint64_t)H > S) return false;
+    const uint64_t G = 64 / S;
+    if (L.LW != ((uint64_t)W + B - 1) / B) return false;
+    a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP; a->nb = (uint32_t)L.nb;
+    a->nrounds = (uint32_t)((L.P + G - 1) / G);
+    *grid = a->nrounds;
+    *lds = 16ull * ((G * L.HW + 3) / 4) + 16;          // the round in whole 16-byte units
+    *width = (int)(100 * W + B);
+    return true;
+}
+
+template <typename T, int BITS>
+hipError_t launch_rowstrip(int width, const StripArgs& a, dim3 grid, size_t lds, hipStream_t st) {
+    void (*kern)(StripArgs);
+    switch (width) {
+        case 1308: kern = compress_rowstrip<T, BITS, 13, 8>; break;
+        case 1304: kern = compress_rowstrip<T, BITS, 13, 4>; break;
+        case 1508: kern = compress_rowstrip<T, BITS, 15, 8>; break;
+        case 1504: kern = compress_rowstrip<T, BITS, 15, 4>; break;
+        case 1708: kern = compress_rowstrip<T, BITS, 17, 8>; break;
+        case 2708: kern = compress_rowstrip<T, BITS, 27, 8>; break;
+        case 3508: kern = compress_rowstrip<T, BITS, 35, 8>; break;
+        case 5508: kern = compress_rowstrip<T, BITS, 55, 8>; break;
+        case 5504: kern = compress_rowstrip<T, BITS, 55, 4>; break;
+        default: return hipErrorInvalidValue;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(64), lds, st, a);
+    return hipGetLastError();
+}
+
 // The Relu + compress instance of the strip kernel; a round's mask bits must be whole words.
 bool plan_relu_strip(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* xy,
                      StripArgs* a, uint32_t* grid, size_t* lds, int* width) {
@@ -826,7 +868,7 @@ hipError_t with_bits(int b, F&& f) {
                                                                   : f(std::integral_constant<int, 8>{});
 }
 
-enum CompKind { REGS, LANE, LINE, STRIP, ITEMS, UNITS, WAVE, TILE, ONE, ROWS, PLANE, ANY };
+enum CompKind { REGS, LANE, LINE, STRIP, ROWSTRIP, ITEMS, UNITS, WAVE, TILE, ONE, ROWS, PLANE, ANY };
 
 // everything a compress launch needs once the plan is made (the arguments of the kernel that was picked)
 struct CompLaunch {
@@ -869,6 +911,7 @@ hipError_t do_compress(const CompLaunch& c, int b) {
         switch (c.kind) {
             case REGS: return launch_regs<T, 1>(c.B, c.nw, c.ra, gd, lds, st);
             case STRIP: return launch_strip<T, 1>(c.vec, c.sa, gd, lds, st);
+            case ROWSTRIP: return launch_rowstrip<T, 1>(c.vec, c.sa, gd, lds, st);
             case LANE: hipLaunchKernelGGL((compress_lane<T, 1>), gd, dim3(64), lds, st, c.la); return hipGetLastError();
             case ITEMS: return launch_items<T, 1>(c.B, c.vec, c.ia, gd, lds, st);
             case UNITS: return launch_units<T, 1>(c.nw, c.ua, gd, lds, st);
@@ -887,6 +930,7 @@ hipError_t do_compress(const CompLaunch& c, int b) {
         switch (c.kind) {
             case REGS: return launch_regs<T, BITS>(c.B, c.nw, c.ra, gd, lds, st);
             case STRIP: return launch_strip<T, BITS>(c.vec, c.sa, gd, lds, st);
+            case ROWSTRIP: return launch_rowstrip<T, BITS>(c.vec, c.sa, gd, lds, st);
             case ITEMS: return launch_items<T, BITS>(c.B, c.vec, c.ia, gd, lds, st);
             case UNITS: return launch_units<T, BITS>(c.nw, c.ua, gd, lds, st);
             case WAVE: return launch_wave<T, BITS>(c.B, c.vec, c.wa, gd, lds, st);
@@ -1069,6 +1113,7 @@ int compress_impl(int count, const void* const* x, void* const* packed, const ui
         else if (plan_lane(L, es, xa, &la, &grid, &lds)) { kind = LANE; la.tab = tab; la.rg = rg; }
         else if (plan_line(L, D, H, B, es, xa, &oa, &grid)) { kind = LINE; oa.tab = tab; oa.rg = rg; lds = 0; }
         else if (flat && plan_strip(L, H, W, B, es, xa, &sa, &grid, &lds, &vec)) { kind = STRIP; sa.tab = tab; sa.rg = rg; }
+        else if (flat && plan_rowstrip(L, H, W, B, es, xa, &sa, &grid, &lds, &vec)) { kind = ROWSTRIP; sa.tab = tab; sa.rg = rg; }
         else if (flat && plan_items(L, H, W, B, es, xa, &ia, &grid, &lds, &vec)) { kind = ITEMS; ia.tab = tab; ia.rg = rg; }
         else if (!one_shape(L, es, xa) && plan_units(L, D, H, W, B, es, xa, &ua, &grid, &lds, &nw) && (wide || nw != 16)) { kind = UNITS; ua.tab = tab; ua.rg = rg; }
         else if (wide && flat && plan_wave(L, H, W, B, b, es, xa, &wa, &grid, &lds, &vec)) {
@@ -1155,6 +1200,8 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
             n = snprintf(out, cap, "compress_line<%s, %d, %u, %u>", tn, b, oa.K, oa.NG);
         else if (flat && plan_strip(L, H, W, B, es, data, &sa, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_strip<%s, %d, %d, %d>", tn, b, vec / 100, vec % 100);
+        else if (flat && plan_rowstrip(L, H, W, B, es, data, &sa, &grid, &lds, &vec))
+            n = snprintf(out, cap, "compress_rowstrip<%s, %d, %d, %d>", tn, b, vec / 100, vec % 100);
         else if (flat && plan_items(L, H, W, B, es, data, &ia, &grid, &lds, &vec))
             n = snprintf(out, cap, "compress_items<%s, %d, %d, %d, %d>", tn, b, B, vec, H == 1 ? 1 : B);
         else if (!one_shape(L, es, data) && plan_units(L, D, H, W, B, es, data, &ua, &grid, &lds, &nw) && (wide || nw != 16))

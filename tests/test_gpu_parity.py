@@ -490,23 +490,25 @@ ONE_BIT_CASES = [
     ((2, 3, 64, 64), 8, "compress_tile<float, 1, 8, 4, 256>", "decompress_stream"),
     ((2, 3, 40, 40), 4, "compress_tile<float, 1, 4, 4, 256>", "decompress_stream"),
     ((2, 3, 20, 30), 4, "compress_tile<float, 1, 4, 2, 256>", "decompress_"),
-    ((5, 7, 15, 15), 4, "compress_tile<float, 1, 4, 1, 256>", "decompress_words"),
+    ((5, 7, 11, 15), 4, "compress_rowstrip<float, 1, 15, 4>", "decompress_words"),
+    ((5, 7, 15, 11), 4, "compress_tile<float, 1, 4, 1, 256>", "decompress_words"),
     ((2, 3, 44, 46), 8, "compress_tile<float, 1, 8, 2, 256>", "decompress_"),
     ((1, 2, 300, 300), 8, "compress_any<float, 1>", "decompress_"),
     ((2, 3, 28, 28), 3, "compress_any<float, 1>", "decompress_table"),
     ((2, 2, 100, 37), 8, "compress_units<float, 1, 2>", "decompress_table"),
-    ((2, 3, 55, 55), 4, "compress_units<float, 1, 2>", "decompress_units"),
-    ((2, 3, 55, 55), 8, "compress_units<float, 1, 2>", "decompress_units"),
+    ((2, 3, 53, 53), 4, "compress_units<float, 1, 2>", "decompress_units"),
+    ((2, 3, 57, 57), 8, "compress_units<float, 1, 2>", "decompress_units"),
+    ((2, 3, 55, 55), 8, "compress_rowstrip<float, 1, 55, 8>", "decompress_units"),
     ((3, 2, 33, 17), 12, "compress_units<float, 1, 1>", "decompress_units"),
-    ((2, 3, 27, 27), 8, "compress_units<float, 1, 1>", "decompress_units"),       # 729 elements: a lone unit in the last byte
-    ((2, 3, 35, 35), 8, "compress_units<float, 1, 1>", "decompress_units"),
+    ((2, 3, 29, 29), 8, "compress_units<float, 1, 1>", "decompress_units"),       # 841 elements: a lone unit in the last byte
+    ((2, 3, 37, 37), 8, "compress_units<float, 1, 1>", "decompress_units"),
     ((2, 3, 73, 73), 8, "compress_units<float, 1, 4>", "decompress_units"),
     ((1, 3, 125, 125), 8, "compress_units<float, 1, 8>", "decompress_units"),
     ((1, 2, 147, 147), 8, "compress_tile<float, 1, 8, 1, 256>", "decompress_units"),   # sixteen wavefronts per plane: no 1-bit instance of the units kernel
     ((1, 2, 147, 147), 18, "compress_any<float, 1>", "decompress_units"),
-    ((5, 7, 17, 17), 8, "compress_units<float, 1, 0>", "decompress_words"),        # 32 lanes per plane
+    ((5, 7, 19, 19), 8, "compress_units<float, 1, 0>", "decompress_words"),        # 16 lanes per plane
     ((5, 7, 18, 17), 4, "compress_units<float, 1, 0>", "decompress_words"),
-    ((5, 7, 13, 13), 8, "compress_tile<float, 1, 8, 1, 256>", "decompress_words"),
+    ((5, 7, 11, 11), 8, "compress_tile<float, 1, 8, 1, 256>", "decompress_words"),
     ((3, 5, 9, 6), 4, "compress_items<float, 1, 4, 2, 4>", "decompress_"),
     ((4, 8, 8, 8), 4, "compress_items<float, 1, 4, 4, 4>", "decompress_stream"),
     ((4, 8, 8, 8), 8, "compress_items<float, 1, 8, 4, 8>", "decompress_stream"),
@@ -875,6 +877,41 @@ def test_strip_kernel_under_the_block_sizes_of_the_sweep(shape, B, b, mode):
     _check_variant(shape, B, b, mode)
 
 
+# planes of an odd width (13, 15, 17, 27, 35, 55): a row per lane, rows that start in the middle of an element pair
+ROWSTRIP_CASES = [
+    ((3, 5, 13, 13), 8), ((7, 9, 13, 13), 4), ((5, 3, 15, 15), 8), ((5, 3, 15, 15), 4), ((3, 5, 17, 17), 8), ((2, 3, 27, 27), 8),
+    ((3, 5, 9, 13), 8),                  # 8 + 1 rows
+    ((3, 5, 16, 13), 4),                 # every lane slot in use
+    ((3, 5, 2, 15), 8), ((3, 5, 3, 17), 8),
+    ((3, 5, 32, 27), 8),                 # every lane slot in use, 32 rows
+    ((3, 5, 31, 17), 8),
+    ((1, 1, 13, 13), 8), ((1, 1, 27, 27), 8),
+    ((1, 7, 27, 27), 8), ((3, 67, 13, 13), 8),     # rounds that end before their last plane slot
+    ((2, 3, 35, 35), 8), ((2, 3, 55, 55), 8), ((2, 3, 55, 55), 4),       # a plane per wavefront
+    ((1, 3, 64, 35), 8), ((1, 2, 40, 55), 4), ((1, 1, 55, 55), 8), ((1, 2, 5, 55), 8),
+    ((9, 600, 15, 15), 8),               # 5400 planes: more than one run of the XCD-aware order and its plain tail
+]
+
+
+@pytest.mark.parametrize("shape,B", ROWSTRIP_CASES)
+@pytest.mark.parametrize("b", [1, 2, 4, 8])
+@pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
+def test_row_per_lane_kernel_on_odd_widths(shape, B, b, mode):
+    dtype = torch.bfloat16 if mode == "bf16" else torch.float32
+    c16 = mode == "c16"
+    name = pkg.division_kernel_name(0, shape, B, b, dtype, c16=c16)
+    assert name.startswith("compress_rowstrip<") and name.endswith(", %d, %d, %d>" % (b, shape[3], B)), name
+    _check_variant(shape, B, b, mode)
+    # code words of a buffer that held something else before: every bit is written, pad bits are zero
+    dt = oracle.F32_C16 if c16 else (oracle.BF16 if mode == "bf16" else oracle.F32)
+    x = _relu_normal(shape, 11 + B + b, dtype)
+    xh, _ = to_host_array(x)
+    pk = torch.full((pkg.division_packed_bytes(*shape, B, b, dtype, c16),), 0xFF, dtype=torch.uint8, device="cuda:0")
+    pkg.division_compress(x.to("cuda:0"), B, b, 4242, packed=pk, c16=c16)
+    torch.cuda.synchronize()
+    assert np.array_equal(pk.cpu().numpy(), oracle.compress(xh, B, b, 4242, dt, threads=16))
+
+
 @pytest.mark.parametrize("shape,B,b", ROWS_CASES)
 @pytest.mark.parametrize("mode", ["f32", "bf16", "c16"])
 def test_general_block_size_kernel_matches_oracle(shape, B, b, mode):
@@ -937,9 +974,9 @@ def test_register_kernel_any_block_size_matches_oracle(shape, B, b, mode):
 
 # planes whose rows or blocks are not whole 16-byte vectors: the register kernel with a block per element
 UNITS_CASES = [
-    ((2, 3, 55, 55), 8, 2),             # 757 units (the last one holds one element), two wavefronts
-    ((3, 2, 55, 55), 4, 4),             # 784 row segments of 4 (3 at the right edge)
-    ((3, 5, 27, 27), 8, 2),             # 183 units: one wavefront, three rounds
+    ((2, 3, 57, 57), 8, 2),             # 813 units (the last one holds one element), two wavefronts
+    ((3, 2, 53, 53), 4, 4),             # 742 row segments of 4 (1 at the right edge)
+    ((3, 5, 29, 29), 8, 2),             # 211 units: one wavefront, four rounds
     ((2, 3, 27, 27), 4, 8),
     ((2, 2, 147, 147), 8, 2),           # 5403 units: sixteen wavefronts
     ((1, 3, 149, 149), 4, 4),           # 5476 row segments
@@ -953,12 +990,12 @@ UNITS_CASES = [
     ((4, 3, 23, 23), 64, 2),            # one block per plane with an odd element count
     ((3, 3, 26, 45), 8, 2),             # odd width, even element count: 2-byte planes start on 4-byte boundaries
     ((2, 3, 38, 75), 4, 4),             # H*W % 4 == 2: the last unit holds two elements
-    ((6, 5, 17, 17), 8, 2),             # planes below 512 elements: 16 lanes per plane, four planes per wavefront;
+    ((6, 5, 19, 19), 8, 2),             # planes below 512 elements: 16 lanes per plane, four planes per wavefront;
     ((5, 7, 19, 19), 4, 4),             # 30 planes: the last round has two
     ((3, 3, 21, 21), 2, 8),             # 242 row segments: 32 lanes per plane
     ((4, 6, 17, 17), 18, 2),            # one block per plane
     ((7, 3, 17, 23), 6, 2),
-    ((1, 1, 55, 55), 8, 2),             # a single plane
+    ((1, 1, 57, 57), 8, 2),             # a single plane
     ((2, 2, 2, 1001), 8, 4),            # two long rows: 126 blocks in one block row
     ((1, 3, 127, 129), 8, 2),           # 16383 elements: eight wavefronts
     ((3, 1, 3, 4099), 8, 2),            # 513 blocks of 3 rows: 4104 row segments
@@ -978,8 +1015,8 @@ def test_register_kernel_any_width_matches_oracle(shape, B, b, mode):
 
 
 # more planes than workgroups: a workgroup takes every grid-th plane, the next one's loads in flight
-@pytest.mark.parametrize("shape,B,b", [((21, 100, 55, 55), 8, 2), ((3, 100, 147, 147), 8, 2), ((42, 100, 27, 27), 4, 4),
-                                        ((3, 1001, 35, 35), 8, 2), ((5, 4001, 17, 17), 8, 2)])
+@pytest.mark.parametrize("shape,B,b", [((21, 100, 57, 57), 8, 2), ((3, 100, 147, 147), 8, 2), ((42, 100, 27, 27), 4, 4),
+                                        ((3, 1001, 37, 37), 8, 2), ((5, 4001, 19, 19), 8, 2)])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_register_kernel_any_width_many_planes(shape, B, b, dtype):
     assert pkg.division_kernel_name(0, shape, B, b, dtype).startswith("compress_units<")
@@ -1096,6 +1133,7 @@ SPECIAL_VALUE_SHAPES = [
     ((3, 4, 1, 196), 16), ((2, 6, 96, 96), 8), ((3, 4, 150, 150), 18), ((3, 4, 27, 35), 5), ((4, 3, 32, 32), 4),
     ((3, 4, 13, 13), 8), ((3, 4, 30, 30), 4), ((1, 12, 300, 300), 18), ((3, 4, 56, 56), 12), ((3, 4, 170, 170), 8),
     ((3, 4, 250, 250), 8), ((3, 4, 60, 60), 8), ((3, 4, 224, 224), 8), ((2, 6, 9, 6), 4), ((3, 4, 1, 3072), 4096),
+    ((3, 4, 27, 27), 8), ((3, 4, 17, 17), 8), ((3, 4, 15, 15), 4),
 ]
 
 
