@@ -250,6 +250,149 @@ __global__ void __launch_bounds__(64) decompress_stream(DecArgs a) { if constexp
 template <typename T, int BITS>
 __global__ void __launch_bounds__(64) decompress_stream_3d(DecArgs a) { if constexpr (sizeof(T) == 4) decompress_stream_body<T, BITS, 3>(a); }
 
+// The stream kernel for maps whose rows, blocks or planes are not whole vectors (odd widths, any B; 4-byte
+// elements): a workgroup is again ONE wavefront that rebuilds kStreamK * 64 consecutive, aligned 16-byte
+// vectors of the map wherever rows and planes end, without LDS or barrier.  A vector's four elements may
+// lie in two rows and in two planes (planes have at least 4 elements): each element finds its own plane,
+// row, column and block; the vector's codes are the 4 * BITS bits from its first element's place in its
+// plane's code words (two words, funnel-shifted), continued with the first bits of the next plane where
+// the plane ends inside the vector; (delta, Delta) of both planes and the H^L of each element's block come
+// straight from the packed buffer (cache hits: all lanes of a chunk share a few lines).  Vectors past the
+// map re-read its last plane and their stores are dropped by the buffer bound, dword by dword, so a map
+// whose element count is not a multiple of 4 ends with a partly stored vector.
+// quotient by a divisor of at least 2 (the host checks it, and that numerator * divisor < 2^32): no test for the
+// divisor 1 that fdiv carries, which the compiler turns into a branch per division
+__device__ __forceinline__ uint32_t udiv2(uint32_t n, FastDiv f) { return __umulhi(n, f.m); }
+// offset of row r's first block among a plane's H^L values (r counts the rows of all depth slices)
+template <int ND>
+__device__ __forceinline__ uint32_t lfc_row2(const DecArgs& a, uint32_t r) {
+    if constexpr (ND == 3) {
+        const uint32_t z = udiv2(r, a.d_Hs);
+        return (udiv2(z, a.d_B) * a.LHs + udiv2(r - z * a.Hs, a.d_B)) * a.LW;
+    } else {
+        return udiv2(r, a.d_B) * a.LW;
+    }
+}
+template <typename T, int BITS, int ND>
+__device__ __forceinline__ void decompress_stream_any_body(const DecArgs& a) {
+    static_assert(sizeof(T) == 4, "4-byte elements");
+    constexpr int K = kStreamK;
+    constexpr uint32_t Lq = (1u << BITS) - 1u;
+    constexpr uint32_t LB = kC16<T> ? 2u : 4u, MB = kC16<T> ? 4u : 8u;     // bytes of one H^L value, of one (delta, Delta)
+    const DecPtrs pt = dec_ptrs(a.tab, a.rg);
+    const uint32_t lane = threadIdx.x;
+    // first element of the chunk, counted over the whole map: its plane g0 and its place t0 inside the plane
+    const uint64_t e0 = (uint64_t)blockIdx.x * (256u * K);
+    const uint64_t ntot = (uint64_t)a.P * a.HW;
+    uint32_t g0 = (uint32_t)((double)e0 * (1.0 / (double)a.HW));
+    int64_t r0 = (int64_t)(e0 - (uint64_t)g0 * a.HW);
+    if (r0 < 0) { --g0; r0 += a.HW; }
+    if (r0 >= (int64_t)a.HW) { ++g0; r0 -= a.HW; }
+    g0 = __builtin_amdgcn_readfirstlane(g0);
+    const uint32_t t0 = __builtin_amdgcn_readfirstlane((uint32_t)r0);
+    // the three regions of the packed buffer through bounds-checked buffers with 32-bit offsets (the host
+    // checks that each is below 4 GiB); the word behind the last plane's code words reads as zero
+    const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(pt.codes), 0, (int)(a.P * a.WPP * 4u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t mrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(pt.meta), 0, (int)(a.P * MB), 0x00020000);
+    const __amdgpu_buffer_rsrc_t lrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(pt.lfc), 0, (int)(a.P * a.nb * LB), 0x00020000);
+
+    uint32_t lo[K], hi[K], nx[K], sh[K], n0[K], lw[K][4];
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+    u32x2 ma[K], mb[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        // (products of two numbers below 2^24 use the full-rate 24-bit multiply; the host checks the sizes)
+        const uint32_t t = t0 + 4u * (64u * k + lane);                    // < HW + 256 K
+        const uint32_t dg = udiv2(t, a.d_HW);
+        const uint32_t i = t - __umul24(dg, a.HW);                        // the vector's first element inside its plane
+        const uint32_t g = min(g0 + dg, a.P - 1u);                         // vectors past the map re-read its last plane
+        const uint32_t g1 = min(g + 1u, a.P - 1u);
+        n0[k] = min(4u, a.HW - i);                                        // elements of the vector that lie in plane g
+        const uint32_t bit = i * BITS;
+        sh[k] = bit & 31u;
+        // One load of three words: the two the vector's codes may lie in and the one behind them.  Where the plane
+        // ends inside the vector its codes end in the plane's last word, and the next plane's first word is the
+        // second or the third of the three.  (Behind the map's last plane the words read as zero and are not used.)
+        const uint32_t wi = bit >> 5;
+        const u32x3 cw3 = __builtin_amdgcn_raw_buffer_load_b96(crs, (__umul24(g, a.WPP) + wi) * 4u, 0, 0);
+        lo[k] = cw3.x;
+        hi[k] = cw3.y;
+        nx[k] = wi + 1u == a.WPP ? cw3.y : cw3.z;
+        // (delta, Delta) of the plane and of the next one lie side by side (the last plane has no next one: zeros)
+        if constexpr (kC16<T>) {
+            const u32x2 m2 = __builtin_amdgcn_raw_buffer_load_b64(mrs, g * 4u, 0, 0);
+            ma[k].x = m2.x; mb[k].x = m2.y;
+        } else {
+            const u32x4 m4 = __builtin_amdgcn_raw_buffer_load_b128(mrs, g * 8u, 0, 0);
+            ma[k] = u32x2{m4.x, m4.y}; mb[k] = u32x2{m4.z, m4.w};
+        }
+        // Row r and column c of the first element.  W >= 4: the vector leaves its row at most once; B >= 4: what
+        // lies behind the row's end (columns 0-2 of the next row, or of row 0 of the next plane) is in block
+        // column 0, and inside the row the block column grows by at most one.  Byte offsets of the H^L values:
+        // oa (the first element's block), ob (block column 0 of the next row), oc (block 0 of the next plane).
+        const uint32_t r = udiv2(i, a.d_W);
+        const uint32_t c = i - __umul24(r, a.W);
+        const uint32_t bc = udiv2(c, a.d_B);
+        const uint32_t crem = c - __umul24(bc, a.B);                      // column inside its block
+        uint32_t rt0, rt1;
+        if constexpr (ND == 2) {
+            const uint32_t rb = udiv2(r, a.d_B);
+            const uint32_t rrem = r - __umul24(rb, a.B);
+            rt0 = __umul24(rb, a.LW);
+            rt1 = rt0 + (rrem + 1u >= a.B ? a.LW : 0u);
+        } else {
+            rt0 = lfc_row2<ND>(a, r);
+            rt1 = lfc_row2<ND>(a, r + 1u);
+        }
+        const uint32_t pg = __umul24(g, a.nb);
+        const uint32_t oa = (pg + rt0 + bc) * LB, ob = (pg + rt1) * LB, oc = __umul24(g1, a.nb) * LB;
+        // (three loads instead of four, the middle elements picking among them, measured 5-15 % slower: the
+        // selects cost more than the load)
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) {
+            const bool first = j < n0[k];
+            const bool wrap = c + j >= a.W;
+            const uint32_t in_row = oa + (crem + j >= a.B ? LB : 0u);
+            const uint32_t off = first ? (wrap ? ob : in_row) : oc;
+            if constexpr (kC16<T>) lw[k][j] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(lrs, off, 0, 0) << 16;
+            else lw[k][j] = __builtin_amdgcn_raw_buffer_load_b32(lrs, off, 0, 0);
+        }
+    }
+    T* out = static_cast<T*>(pt.xhat) + e0;
+    const uint64_t left = ntot - e0;                                      // elements from the chunk's start to the map's end
+    const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc(
+        out, 0, (int)(left < 256u * K ? (uint32_t)left * 4u : 256u * K * 4u), 0x00020000);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        uint32_t c = __builtin_amdgcn_alignbit(hi[k], lo[k], sh[k]);
+        // the plane's last n0 codes, then the next plane's first ones: 64-bit shifts, so that n0 = 4 (a shift by the
+        // whole word) needs no test (a test would let the compiler move the load of nx behind it, after a wait)
+        const uint32_t nb0 = n0[k] * BITS;
+        c = (c & (uint32_t)((1ull << nb0) - 1ull)) | (uint32_t)((uint64_t)nx[k] << nb0);
+        float2 da, db;
+        if constexpr (kC16<T>) {
+            da = make_float2(__uint_as_float(ma[k].x << 16), __uint_as_float(ma[k].x & 0xffff0000u));
+            db = make_float2(__uint_as_float(mb[k].x << 16), __uint_as_float(mb[k].x & 0xffff0000u));
+        } else {
+            da = make_float2(__uint_as_float(ma[k].x), __uint_as_float(ma[k].y));
+            db = make_float2(__uint_as_float(mb[k].x), __uint_as_float(mb[k].y));
+        }
+        uint32_t ov[4];
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) {
+            const bool first = j < n0[k];
+            ov[j] = __float_as_uint(dequant((c >> (j * BITS)) & Lq, first ? da.y : db.y, first ? da.x : db.x, __uint_as_float(lw[k][j])));
+        }
+        u32x4 o; o.x = ov[0]; o.y = ov[1]; o.z = ov[2]; o.w = ov[3];
+        store_b128_checked(o, ors, lane * 16u + (uint32_t)(k * 1024), DIVISION_STREAM_STORE_AUX);   // past the map: dropped
+    }
+}
+template <typename T, int BITS>
+__global__ void __launch_bounds__(64) decompress_stream_any(DecArgs a) { if constexpr (sizeof(T) == 4) decompress_stream_any_body<T, BITS, 2>(a); }
+template <typename T, int BITS>
+__global__ void __launch_bounds__(64) decompress_stream_any_3d(DecArgs a) { if constexpr (sizeof(T) == 4) decompress_stream_any_body<T, BITS, 3>(a); }
+
 // H*W a multiple of 4 and at most 255 blocks per plane: the LFC index of every
 // element of a plane is looked up in a table (one byte per element, four per
 // vector) that the workgroup builds once in LDS, so the streaming loop has no

@@ -751,7 +751,8 @@ uint64_t dec_planes(const Layout& L, size_t es, uint64_t mult) {
     return G;
 }
 
-// Fills the decompress launch plan; returns 7 (row vectors of 4-byte elements, a wavefront per chunk), 0 (row vectors), 3 (block table), 6 (four consecutive elements
+// Fills the decompress launch plan; returns 7 (row vectors of 4-byte elements, a wavefront per chunk), 0 (row vectors), 3 (block table),
+// 8 (4-byte elements of any width, a wavefront per chunk), 6 (four consecutive elements
 // per lane step, any width), 5 (word by word through LDS), 1 (flat), 4 (lane per plane) or 2 (scalar).
 // Hs = rows of one depth slice, D = depth slices (1 for a 2-D map; the table kernel takes 2-D maps only).
 int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, size_t es, const void* xhat,
@@ -811,6 +812,20 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
             a->d_q4 = make_fastdiv(a->q4);
             *grid = (uint32_t)((L.P + G - 1) / G);
             return 3;
+        }
+    }
+    // 4-byte elements, rows, blocks or planes that are not whole vectors: a wavefront per chunk of aligned vectors,
+    // every element finds its own plane and block
+    // (several blocks per plane: one-block planes are the flat kernel's, measured faster there; B >= 4 and W >= 4: a
+    // vector then leaves its row and its block column at most once, and no division is by 1; plane and plane count
+    // below 2^24 for the 24-bit multiplies; the three regions of the packed buffer within 32-bit byte offsets)
+    if (es == 4 && L.nb > 1 && W >= 4 && B >= 4 && (D == 1 || Hs >= 2) && L.HW < (1ull << 24) && L.P < (1ull << 24) && small_idx && out_vec_aligned && fastdiv_ok(L.HW, (uint64_t)W) &&
+        fastdiv_ok((uint64_t)H + 1, (uint64_t)B) && L.P * L.WPP * 4 < (1ull << 31) && L.P * L.nb * 4 < (1ull << 31) && L.P * 8 < (1ull << 31)) {
+        const uint64_t chunk = 256ull * kStreamK;                       // elements
+        const uint64_t ntot = L.P * L.HW;
+        if (fastdiv_ok(L.HW + chunk + 4, L.HW) && (ntot + chunk - 1) / chunk < (1ull << 31) && ntot < (1ull << 42)) {
+            *grid = (uint32_t)((ntot + chunk - 1) / chunk);
+            return 8;
         }
     }
     // planes (2-D or 3-D) of 512 elements and more whose rows or blocks are not whole vectors: four consecutive
@@ -968,8 +983,9 @@ hipError_t do_decompress(const DecLaunch& c, int b) {
         constexpr int BITS = decltype(bits)::value;
         const int kind = c.kind;
         void (*kern)(DecArgs);
-        if (kind == 7) {
-            kern = c.flat ? decompress_stream<T, BITS> : decompress_stream_3d<T, BITS>;
+        if (kind == 7 || kind == 8) {
+            if (kind == 7) kern = c.flat ? decompress_stream<T, BITS> : decompress_stream_3d<T, BITS>;
+            else kern = c.flat ? decompress_stream_any<T, BITS> : decompress_stream_any_3d<T, BITS>;
             hipLaunchKernelGGL(kern, dim3(c.gx, c.gy), dim3(64), 0, c.st, c.a);
             return hipGetLastError();
         }
@@ -1164,7 +1180,7 @@ int decompress_impl(int count, const void* const* packed, void* const* xhat, siz
         size_t lds = 0;
         if (kind == 4) lds = 4ull * (64ull * L.HW + 4);
         else if (kind == 6) lds = 8ull * ((L.nb + 3) & ~3ull);
-        else if (kind == 7) lds = 0;
+        else if (kind == 7 || kind == 8) lds = 0;
         else if (kind == 5) lds = a.out_off + 4ull * ((a.G * L.HW + 3) & ~3ull);
         else if (kind != 2) lds = dec_lds_bytes(L, es, a.G) + (kind == 3 ? 4ull * a.q4 + 16 : 0);
         DecLaunch c{};
@@ -1225,6 +1241,8 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
             n = snprintf(out, cap, "decompress_units<%s, %d, %d>", tn, b, (int)a.G);
         else if (kind == 7)
             n = snprintf(out, cap, "decompress_stream%s<%s, %d>", sfx, tn, b);
+        else if (kind == 8)
+            n = snprintf(out, cap, "decompress_stream_any%s<%s, %d>", sfx, tn, b);
         else
             n = snprintf(out, cap, "%s%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 3 ? "decompress_table" : kind == 5 ? "decompress_words" : kind == 1 ? "decompress_flat" : kind == 4 ? "decompress_lane" : "decompress_scalar",
                          kind == 4 ? "" : sfx, tn, b);

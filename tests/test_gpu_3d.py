@@ -86,9 +86,12 @@ def test_volume_kernels_cover_what_the_cases_claim():
     assert kn(0, (1, 2, 33, 35, 37), 16, 2) == "compress_any_3d<float, 2>"
     assert kn(1, (3, 5, 16, 16, 16), 8, 2) == "decompress_stream_3d<float, 2>"
     assert kn(1, (3, 5, 16, 16, 16), 8, 2, torch.bfloat16) == "decompress_rowvec_3d<bf16_t, 2>"
-    assert kn(1, (2, 3, 5, 9, 13), 4, 2) == "decompress_units<float, 2, 1>"
+    assert kn(1, (2, 3, 5, 9, 13), 4, 2) == "decompress_stream_any_3d<float, 2>"
+    assert kn(1, (2, 3, 5, 9, 13), 4, 2, torch.bfloat16) == "decompress_units<bf16_t, 2, 1>"
     assert kn(1, (2, 2, 3, 35, 35), 4, 4, torch.bfloat16) == "decompress_units<bf16_t, 4, 2>"
-    assert kn(1, (3, 2, 5, 7, 7), 4, 2) == "decompress_words_3d<float, 2>"
+    assert kn(1, (3, 2, 5, 7, 7), 4, 2) == "decompress_stream_any_3d<float, 2>"
+    assert kn(1, (3, 2, 5, 7, 7), 4, 2, torch.bfloat16) == "decompress_words_3d<bf16_t, 2>"
+    assert kn(1, (2, 2, 6, 10, 7), 3, 4) == "decompress_words_3d<float, 4>"
     assert kn(1, (1, 2, 40, 40, 40), 8, 8) == "decompress_stream_3d<float, 8>"
     assert kn(1, (1, 2, 41, 41, 41), 8, 8) == "decompress_scalar_3d<float, 8>"
     assert kn(0, (4, 9, 3, 3, 3), 8, 2) == "compress_lane<float, 2>"

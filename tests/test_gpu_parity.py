@@ -490,25 +490,25 @@ ONE_BIT_CASES = [
     ((2, 3, 64, 64), 8, "compress_tile<float, 1, 8, 4, 256>", "decompress_stream"),
     ((2, 3, 40, 40), 4, "compress_tile<float, 1, 4, 4, 256>", "decompress_stream"),
     ((2, 3, 20, 30), 4, "compress_tile<float, 1, 4, 2, 256>", "decompress_"),
-    ((5, 7, 11, 15), 4, "compress_rowstrip<float, 1, 15, 4>", "decompress_words"),
-    ((5, 7, 15, 11), 4, "compress_tile<float, 1, 4, 1, 256>", "decompress_words"),
+    ((5, 7, 11, 15), 4, "compress_rowstrip<float, 1, 15, 4>", "decompress_stream_any"),
+    ((5, 7, 15, 11), 4, "compress_tile<float, 1, 4, 1, 256>", "decompress_stream_any"),
     ((2, 3, 44, 46), 8, "compress_tile<float, 1, 8, 2, 256>", "decompress_"),
     ((1, 2, 300, 300), 8, "compress_any<float, 1>", "decompress_"),
     ((2, 3, 28, 28), 3, "compress_any<float, 1>", "decompress_table"),
     ((2, 2, 100, 37), 8, "compress_units<float, 1, 2>", "decompress_table"),
-    ((2, 3, 53, 53), 4, "compress_units<float, 1, 2>", "decompress_units"),
-    ((2, 3, 57, 57), 8, "compress_units<float, 1, 2>", "decompress_units"),
-    ((2, 3, 55, 55), 8, "compress_rowstrip<float, 1, 55, 8>", "decompress_units"),
-    ((3, 2, 33, 17), 12, "compress_units<float, 1, 1>", "decompress_units"),
-    ((2, 3, 29, 29), 8, "compress_units<float, 1, 1>", "decompress_units"),       # 841 elements: a lone unit in the last byte
-    ((2, 3, 37, 37), 8, "compress_units<float, 1, 1>", "decompress_units"),
-    ((2, 3, 73, 73), 8, "compress_units<float, 1, 4>", "decompress_units"),
-    ((1, 3, 125, 125), 8, "compress_units<float, 1, 8>", "decompress_units"),
-    ((1, 2, 147, 147), 8, "compress_tile<float, 1, 8, 1, 256>", "decompress_units"),   # sixteen wavefronts per plane: no 1-bit instance of the units kernel
-    ((1, 2, 147, 147), 18, "compress_any<float, 1>", "decompress_units"),
-    ((5, 7, 19, 19), 8, "compress_units<float, 1, 0>", "decompress_words"),        # 16 lanes per plane
-    ((5, 7, 18, 17), 4, "compress_units<float, 1, 0>", "decompress_words"),
-    ((5, 7, 11, 11), 8, "compress_tile<float, 1, 8, 1, 256>", "decompress_words"),
+    ((2, 3, 53, 53), 4, "compress_units<float, 1, 2>", "decompress_stream_any"),
+    ((2, 3, 57, 57), 8, "compress_units<float, 1, 2>", "decompress_stream_any"),
+    ((2, 3, 55, 55), 8, "compress_rowstrip<float, 1, 55, 8>", "decompress_stream_any"),
+    ((3, 2, 33, 17), 12, "compress_units<float, 1, 1>", "decompress_stream_any"),
+    ((2, 3, 29, 29), 8, "compress_units<float, 1, 1>", "decompress_stream_any"),       # 841 elements: a lone unit in the last byte
+    ((2, 3, 37, 37), 8, "compress_units<float, 1, 1>", "decompress_stream_any"),
+    ((2, 3, 73, 73), 8, "compress_units<float, 1, 4>", "decompress_stream_any"),
+    ((1, 3, 125, 125), 8, "compress_units<float, 1, 8>", "decompress_stream_any"),
+    ((1, 2, 147, 147), 8, "compress_tile<float, 1, 8, 1, 256>", "decompress_stream_any"),   # sixteen wavefronts per plane: no 1-bit instance of the units kernel
+    ((1, 2, 147, 147), 18, "compress_any<float, 1>", "decompress_stream_any"),
+    ((5, 7, 19, 19), 8, "compress_units<float, 1, 0>", "decompress_stream_any"),        # 16 lanes per plane
+    ((5, 7, 18, 17), 4, "compress_units<float, 1, 0>", "decompress_stream_any"),
+    ((5, 7, 11, 11), 8, "compress_tile<float, 1, 8, 1, 256>", "decompress_stream_any"),
     ((3, 5, 9, 6), 4, "compress_items<float, 1, 4, 2, 4>", "decompress_"),
     ((4, 8, 8, 8), 4, "compress_items<float, 1, 4, 4, 4>", "decompress_stream"),
     ((4, 8, 8, 8), 8, "compress_items<float, 1, 8, 4, 8>", "decompress_stream"),
@@ -1010,7 +1010,8 @@ def test_register_kernel_any_width_matches_oracle(shape, B, b, mode):
     dtype = torch.bfloat16 if mode == "bf16" else torch.float32
     assert pkg.division_kernel_name(0, shape, B, b, dtype, c16=mode == "c16").startswith("compress_units<")
     if shape[3] % 2 == 1 and shape[2] * shape[3] >= 512:      # (smaller planes are rebuilt chunk-wise in LDS)
-        assert pkg.division_kernel_name(1, shape, B, b, dtype, c16=mode == "c16").startswith("decompress_units<")
+        # (4-byte elements: the wavefront-per-chunk kernel for any width where a plane has several blocks of 4 and more)
+        assert pkg.division_kernel_name(1, shape, B, b, dtype, c16=mode == "c16").startswith(("decompress_units<", "decompress_stream_any<"))
     _check_variant(shape, B, b, mode)
 
 
@@ -1267,6 +1268,37 @@ def test_unaligned_maps_and_outputs_under_every_kernel_family(shape, B, dtype):
         yh, _ = to_host_array(obh[pad + off: pad + off + numel].contiguous())
         assert np.array_equal(yh.reshape(shape), oracle.decompress(ref, shape, B, 2, dt, threads=16)), off
         assert bool((obh[:pad + off] == guard).all()) and bool((obh[pad + off + numel:] == guard).all()), off
+
+
+# fp32 maps whose rows and planes are not whole 16-byte vectors, rebuilt by the wavefront-per-chunk kernel: the element
+# count of the map leaves 1, 2 or 3 elements in its last vector, planes end inside vectors, chunks end inside planes
+STREAM_ANY_CASES = [
+    ((1, 1, 13, 13), 8, 2), ((1, 2, 13, 13), 8, 4), ((1, 3, 13, 13), 4, 8), ((3, 5, 17, 17), 8, 2), ((2, 3, 55, 55), 8, 2),
+    ((7, 11, 27, 27), 8, 1), ((2, 3, 147, 147), 8, 2), ((5, 7, 3, 5), 4, 2), ((9, 9, 1, 9), 4, 4), ((3, 7, 2, 5), 4, 2),
+    ((2, 3, 30, 35), 5, 2), ((3, 5, 1, 197), 8, 2), ((2, 2, 1, 4099), 64, 2), ((40, 25, 5, 7), 4, 2), ((2, 3, 57, 57), 7, 2),
+    ((2, 2, 3, 9, 11), 4, 2), ((2, 2, 3, 35, 35), 4, 4), ((5, 3, 4, 9, 9), 8, 2), ((3, 2, 5, 7, 7), 4, 1), ((2, 3, 7, 5, 30), 5, 2),
+]
+
+
+@pytest.mark.parametrize("shape,B,b", STREAM_ANY_CASES)
+@pytest.mark.parametrize("mode", ["f32", "c16"])
+def test_wavefront_per_chunk_decompress_of_any_width(shape, B, b, mode):
+    three = len(shape) == 5
+    c16 = mode == "c16"
+    dt = oracle.F32_C16 if c16 else oracle.F32
+    name = (pkg.division_kernel_name_3d if three else pkg.division_kernel_name)(1, shape, B, b, torch.float32, c16=c16)
+    assert name.startswith("decompress_stream_any"), name
+    numel, guard = int(np.prod(shape)), -777.0
+    g = torch.Generator().manual_seed(sum(shape) + B + b)
+    x = (torch.randn(shape, generator=g) * 1.5 + 0.2)
+    ref = oracle.compress(x.numpy(), B, b, 31337, dt, threads=16)
+    ob = torch.full((numel + 64,), guard, dtype=torch.float32, device="cuda:0")           # guard elements behind the map
+    out = ob[:numel].view(shape)
+    (pkg.division_decompress_3d if three else pkg.division_decompress)(torch.from_numpy(ref).to("cuda:0"), shape, B, b, torch.float32, out=out, c16=c16)
+    torch.cuda.synchronize()
+    obh = ob.cpu().numpy()
+    assert np.array_equal(obh[:numel].reshape(shape), oracle.decompress(ref, shape, B, b, dt, threads=16))
+    assert (obh[numel:] == guard).all()
 
 
 @pytest.mark.parametrize("seed", [0, 1, 2 ** 32, 2 ** 32 - 1, 2 ** 63 + 5, 2 ** 64 - 1])

@@ -157,11 +157,11 @@ DISPATCH = [
     ((64, 512, 28, 28), 8, 1, "compress_strip<float, 1, 28, 8>", "decompress_stream<float, 1>"),
     ((64, 1024, 14, 14), 8, 1, "compress_strip<float, 1, 14, 8>", "decompress_table<float, 1>"),
     ((64, 2048, 7, 7), 8, 1, "compress_lane<float, 1>", "decompress_lane<float, 1>"),
-    ((256, 96, 55, 55), 8, 1, "compress_rowstrip<float, 1, 55, 8>", "decompress_units<float, 1, 2>"),
-    ((128, 768, 17, 17), 8, 1, "compress_rowstrip<float, 1, 17, 8>", "decompress_words<float, 1>"),
+    ((256, 96, 55, 55), 8, 1, "compress_rowstrip<float, 1, 55, 8>", "decompress_stream_any<float, 1>"),
+    ((128, 768, 17, 17), 8, 1, "compress_rowstrip<float, 1, 17, 8>", "decompress_stream_any<float, 1>"),
     ((256, 256, 8, 8), 4, 1, "compress_items<float, 1, 4, 4, 4>", "decompress_stream<float, 1>"),
-    ((64, 64, 147, 147), 8, 1, "compress_tile<float, 1, 8, 1, 256>", "decompress_units<float, 1, 16>"),
-    ((64, 64, 147, 147), 18, 1, "compress_any<float, 1>", "decompress_units<float, 1, 16>"),
+    ((64, 64, 147, 147), 8, 1, "compress_tile<float, 1, 8, 1, 256>", "decompress_stream_any<float, 1>"),
+    ((64, 64, 147, 147), 18, 1, "compress_any<float, 1>", "decompress_stream_any<float, 1>"),
     ((64, 96, 64, 64), 8, 1, "compress_tile<float, 1, 8, 4, 256>", "decompress_stream<float, 1>"),
     ((256, 128, 1, 768), 8, 1, "compress_line<float, 1, 6, 1>", "decompress_stream<float, 1>"),
     ((64, 256, 56, 56), 64, 1, "compress_one<float, 1, 13>", "decompress_stream<float, 1>"),
@@ -177,7 +177,7 @@ DISPATCH = [
     ((64, 512, 28, 28), 18, 2, "compress_strip<float, 2, 28, 18>", "decompress_table<float, 2>"),
     ((64, 1024, 14, 14), 12, 2, "compress_strip<float, 2, 14, 12>", "decompress_table<float, 2>"),
     ((4, 8, 28, 28), 4, 2, "compress_items<float, 2, 4, 4, 4>", "decompress_stream<float, 2>"),
-    ((4, 8, 15, 14), 8, 2, "compress_items<float, 2, 8, 2, 8>", "decompress_words<float, 2>"),
+    ((4, 8, 15, 14), 8, 2, "compress_items<float, 2, 8, 2, 8>", "decompress_stream_any<float, 2>"),
     ((64, 2048, 7, 7), 8, 2, "compress_lane<float, 2>", "decompress_lane<float, 2>"),
     ((128, 64, 32, 32), 4, 2, "compress_strip<float, 2, 32, 4>", "decompress_stream<float, 2>"),
     ((128, 128, 16, 16), 4, 2, "compress_strip<float, 2, 16, 4>", "decompress_stream<float, 2>"),
@@ -185,16 +185,16 @@ DISPATCH = [
     ((64, 256, 56, 56), 12, 2, "compress_regs<float, 2, 0, 1>", "decompress_stream<float, 2>"),
     ((64, 256, 56, 56), 64, 2, "compress_one<float, 2, 13>", "decompress_stream<float, 2>"),
     ((64, 256, 56, 56), 18, 4, "compress_units<float, 4, 2>", "decompress_table<float, 4>"),
-    ((32, 96, 55, 55), 4, 4, "compress_rowstrip<float, 4, 55, 4>", "decompress_units<float, 4, 2>"),
-    ((8, 8, 27, 27), 8, 2, "compress_rowstrip<float, 2, 27, 8>", "decompress_units<float, 2, 1>"),
-    ((8, 8, 17, 17), 8, 2, "compress_rowstrip<float, 2, 17, 8>", "decompress_words<float, 2>"),
-    ((8, 8, 13, 13), 8, 2, "compress_rowstrip<float, 2, 13, 8>", "decompress_words<float, 2>"),
-    ((8, 8, 27, 27), 4, 2, "compress_units<float, 2, 1>", "decompress_units<float, 2, 1>"),
-    ((8, 8, 19, 19), 8, 2, "compress_units<float, 2, 0>", "decompress_words<float, 2>"),
-    ((8, 8, 11, 11), 8, 2, "compress_wave<float, 2, 8, 1>", "decompress_words<float, 2>"),
-    ((8, 8, 35, 35), 8, 2, "compress_rowstrip<float, 2, 35, 8>", "decompress_units<float, 2, 1>"),
-    ((8, 8, 73, 73), 8, 2, "compress_units<float, 2, 4>", "decompress_units<float, 2, 4>"),
-    ((4, 4, 147, 147), 8, 2, "compress_units<float, 2, 16>", "decompress_units<float, 2, 16>"),
+    ((32, 96, 55, 55), 4, 4, "compress_rowstrip<float, 4, 55, 4>", "decompress_stream_any<float, 4>"),
+    ((8, 8, 27, 27), 8, 2, "compress_rowstrip<float, 2, 27, 8>", "decompress_stream_any<float, 2>"),
+    ((8, 8, 17, 17), 8, 2, "compress_rowstrip<float, 2, 17, 8>", "decompress_stream_any<float, 2>"),
+    ((8, 8, 13, 13), 8, 2, "compress_rowstrip<float, 2, 13, 8>", "decompress_stream_any<float, 2>"),
+    ((8, 8, 27, 27), 4, 2, "compress_units<float, 2, 1>", "decompress_stream_any<float, 2>"),
+    ((8, 8, 19, 19), 8, 2, "compress_units<float, 2, 0>", "decompress_stream_any<float, 2>"),
+    ((8, 8, 11, 11), 8, 2, "compress_wave<float, 2, 8, 1>", "decompress_stream_any<float, 2>"),
+    ((8, 8, 35, 35), 8, 2, "compress_rowstrip<float, 2, 35, 8>", "decompress_stream_any<float, 2>"),
+    ((8, 8, 73, 73), 8, 2, "compress_units<float, 2, 4>", "decompress_stream_any<float, 2>"),
+    ((4, 4, 147, 147), 8, 2, "compress_units<float, 2, 16>", "decompress_stream_any<float, 2>"),
     ((4, 4, 30, 30), 4, 2, "compress_wave<float, 2, 4, 2>", "decompress_table<float, 2>"),
     ((2, 2, 1, 768), 8, 4, "compress_line<float, 4, 6, 1>", "decompress_stream<float, 4>"),
     ((5, 33, 14, 14), 12, 4, "compress_strip<float, 4, 14, 12>", "decompress_table<float, 4>"),
