@@ -44,7 +44,7 @@ __device__ __forceinline__ double group_sum_any(uint32_t S, double v) {
 // 64 / S planes; the S lanes of a plane keep its vectors in registers (vector u in lane u mod S),
 // sums and extremes are reductions over those lanes, the codes leave as one to eight bytes per
 // vector.  LDS is not used.
-// K: rounds the instance runs (3, 6 or 13; the host picks lanes per plane and K so that a plane has at
+// K: rounds the instance runs (3, 4, 6 or 13; the host picks lanes per plane and K so that a plane has at
 // most K rounds of vectors and few of the K * S lane slots stay empty).  No round is tested at run time:
 // a uniform test per round splits the code into blocks that each wait for every load (measured: 50 ->
 // 40 us on 64 x 256 x 56 x 56); a round past the plane loads nothing (its offsets are out of range) and

@@ -515,7 +515,7 @@ bool plan_wave(const Layout& L, int64_t H, int64_t W, int B, int b, size_t es, c
     return true;
 }
 
-// Lanes per plane S (a power of two from min_log up) and rounds K of the instance (3, 6 or 13) for
+// Lanes per plane S (a power of two from min_log up) and rounds K of the instance (3, 4, 6 or 13) for
 // planes of qv vectors: the pair that leaves the fewest of the K * S lane slots empty; among equals
 // the one with more rounds (fewer, longer-lived lanes per plane measured better than many short ones).
 bool pick_lanes_and_rounds(uint64_t qv, uint32_t min_log, uint32_t* S_out, uint32_t* log_out, uint32_t* K_out) {
@@ -523,7 +523,7 @@ bool pick_lanes_and_rounds(uint64_t qv, uint32_t min_log, uint32_t* S_out, uint3
     for (uint32_t lg = min_log; lg <= 6; ++lg) {
         const uint64_t S = 1ull << lg, R = (qv + S - 1) / S;
         if (R > 13) continue;
-        const uint64_t K = R <= 3 ? 3 : R <= 6 ? 6 : 13;
+        const uint64_t K = R <= 3 ? 3 : R <= 4 ? 4 : R <= 6 ? 6 : 13;
         const uint64_t slots = K * S;
         if (best == 0 || slots < best || (slots == best && K > *K_out)) { best = slots; *S_out = (uint32_t)S; *log_out = lg; *K_out = (uint32_t)K; }
     }
@@ -903,14 +903,14 @@ struct DecLaunch {
 
 template <typename T, int BITS>
 hipError_t launch_one(const OneArgs& a, dim3 gd, hipStream_t st) {
-    void (*kern)(OneArgs) = a.K == 3 ? compress_one<T, BITS, 3> : a.K == 6 ? compress_one<T, BITS, 6> : compress_one<T, BITS, 13>;
+    void (*kern)(OneArgs) = a.K == 3 ? compress_one<T, BITS, 3> : a.K == 4 ? compress_one<T, BITS, 4> : a.K == 6 ? compress_one<T, BITS, 6> : compress_one<T, BITS, 13>;
     hipLaunchKernelGGL(kern, gd, dim3(64), 0, st, a);
     return hipGetLastError();
 }
 template <typename T, int BITS>
 hipError_t launch_line(const OneArgs& a, dim3 gd, hipStream_t st) {
     void (*kern)(OneArgs) = a.K == 12 ? (a.NG == 12 ? compress_line<T, BITS, 12, 12> : a.NG == 6 ? compress_line<T, BITS, 12, 6> : compress_line<T, BITS, 12, 4>)
-                          : a.K == 6 ? compress_line<T, BITS, 6> : compress_line<T, BITS, 13>;
+                          : a.K == 4 ? compress_line<T, BITS, 4> : a.K == 6 ? compress_line<T, BITS, 6> : compress_line<T, BITS, 13>;
     hipLaunchKernelGGL(kern, gd, dim3(64), 0, st, a);
     return hipGetLastError();
 }

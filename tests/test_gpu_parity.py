@@ -475,8 +475,8 @@ ONE_BIT_CASES = [
     ((2, 9, 1, 96), 64, "compress_line<float, 1, 12, 6>", "decompress_stream"),
     ((2, 9, 1, 768), 8, "compress_line<float, 1, 6, 1>", "decompress_stream"),
     ((2, 9, 1, 768), 64, "compress_line<float, 1, 6, 1>", "decompress_stream"),
-    ((5, 9, 1, 196), 16, "compress_line<float, 1, 6, 1>", "decompress_stream"),      # 49 vectors: the last byte holds one
-    ((3, 7, 1, 100), 8, "compress_line<float, 1, 6, 1>", "decompress_stream"),       # 25 vectors
+    ((5, 9, 1, 196), 16, "compress_line<float, 1, 4, 1>", "decompress_stream"),      # 49 vectors: the last byte holds one
+    ((3, 7, 1, 100), 8, "compress_line<float, 1, 4, 1>", "decompress_stream"),       # 25 vectors
     ((7, 9, 1, 24), 8, "compress_line<float, 1, 12, 12>", "decompress_stream"),
     ((2, 3, 1, 3072), 64, "compress_regs<float, 1, 0, 1>", "decompress_stream"),
     ((2, 3, 1, 3072), 4096, "compress_one<float, 1, 13>", "decompress_stream"),
