@@ -368,6 +368,8 @@ def main() -> int:
                     help="batch: consecutive same-shape maps share a launch (<= 8 per call); layer: one call per map")
     ap.add_argument("--c16", action="store_true",
                     help="cache H^L, delta and Delta as bfloat16 (the paper's format; fp32 workloads only)")
+    ap.add_argument("--bf16", action="store_true",
+                    help="every map of the workload as bfloat16 (mixed-precision training; not the headline workload)")
     ap.add_argument("--no-compare-modes", dest="compare_modes", action="store_false",
                     help="do not time the other launch mode (it is timed before the reported one and its figures go into the line)")
     ap.add_argument("--roofline-every", type=int, default=4,
@@ -428,7 +430,7 @@ def main() -> int:
     _, specs = config(args.config)
     host = []
     for k, spec, x in draw_config(args.config, args.batch):
-        if spec.dtype == "bf16":
+        if spec.dtype == "bf16" or args.bf16:
             x = x.to(torch.bfloat16)
         host.append((k, spec, x))
     nsets = max(1, args.sets)
@@ -567,7 +569,7 @@ def main() -> int:
     achieved = avg_bytes / (avg_ms * 1e-3) / 1e9
     value = algo_bytes_step / (ms_per_step * 1e-3) / 1e9
 
-    if args.config == 2 and args.batch is None and not args.c16 and args.mode == "batch":
+    if args.config == 2 and args.batch is None and not args.c16 and not args.bf16 and args.mode == "batch":
         n_dom_step = sum(1 for d, g in launch_list(args.mode) if kname(d, g) == dominant)
         traffic, traffic_src = recorded_traffic(dominant, n_dom_step, round(avg_bytes))
     else:
@@ -591,7 +593,7 @@ def main() -> int:
                    "B": host[0][1].B, "b": host[0][1].b, "buffer_sets": nsets,
                    "launch_mode": args.mode, "launches_per_step": n_launches,
                    "cache_format": "bf16 H^L, delta, Delta (Sec. 4.1)" if args.c16 else "H^L in the map's type, fp32 delta, Delta",
-                   "batch_override": args.batch},
+                   "batch_override": args.batch, "all_maps_bfloat16": bool(args.bf16)},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "activation_GB_s": round(2 * input_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "compression_ratio": round(input_bytes / packed_bytes, 3),
