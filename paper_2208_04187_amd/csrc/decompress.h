@@ -327,6 +327,17 @@ __device__ __forceinline__ void decompress_stream_any_body(const DecArgs& a) {
             const u32x4 m4 = __builtin_amdgcn_raw_buffer_load_b128(mrs, g * 8u, 0, 0);
             ma[k] = u32x2{m4.x, m4.y}; mb[k] = u32x2{m4.z, m4.w};
         }
+        if constexpr (ND == 0) {
+            // one block per plane: H^L of the plane and of the next one lie side by side, one load
+            if constexpr (kC16<T>) {
+                lw[k][0] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(lrs, g * 2u, 0, 0) << 16;     // (2-byte values: a 4-byte load
+                lw[k][1] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(lrs, g * 2u + 2u, 0, 0) << 16; // of both would not be aligned)
+            } else {
+                const u32x2 l2 = __builtin_amdgcn_raw_buffer_load_b64(lrs, g * 4u, 0, 0);
+                lw[k][0] = l2.x; lw[k][1] = l2.y;
+            }
+            continue;
+        }
         // Row r and column c of the first element.  W >= 4: the vector leaves its row at most once; B >= 4: what
         // lies behind the row's end (columns 0-2 of the next row, or of row 0 of the next plane) is in block
         // column 0, and inside the row the block column grows by at most one.  Byte offsets of the H^L values:
@@ -382,7 +393,8 @@ __device__ __forceinline__ void decompress_stream_any_body(const DecArgs& a) {
 #pragma unroll
         for (uint32_t j = 0; j < 4; ++j) {
             const bool first = j < n0[k];
-            ov[j] = __float_as_uint(dequant((c >> (j * BITS)) & Lq, first ? da.y : db.y, first ? da.x : db.x, __uint_as_float(lw[k][j])));
+            const uint32_t lfcw = ND == 0 ? (first ? lw[k][0] : lw[k][1]) : lw[k][j];
+            ov[j] = __float_as_uint(dequant((c >> (j * BITS)) & Lq, first ? da.y : db.y, first ? da.x : db.x, __uint_as_float(lfcw)));
         }
         u32x4 o; o.x = ov[0]; o.y = ov[1]; o.z = ov[2]; o.w = ov[3];
         store_b128_checked(o, ors, lane * 16u + (uint32_t)(k * 1024), DIVISION_STREAM_STORE_AUX);   // past the map: dropped
@@ -392,6 +404,9 @@ template <typename T, int BITS>
 __global__ void __launch_bounds__(64) decompress_stream_any(DecArgs a) { if constexpr (sizeof(T) == 4) decompress_stream_any_body<T, BITS, 2>(a); }
 template <typename T, int BITS>
 __global__ void __launch_bounds__(64) decompress_stream_any_3d(DecArgs a) { if constexpr (sizeof(T) == 4) decompress_stream_any_body<T, BITS, 3>(a); }
+// planes that are one block (any number of map dimensions): no rows or columns, H^L is the plane's
+template <typename T, int BITS>
+__global__ void __launch_bounds__(64) decompress_stream_one(DecArgs a) { if constexpr (sizeof(T) == 4) decompress_stream_any_body<T, BITS, 0>(a); }
 
 // H*W a multiple of 4 and at most 255 blocks per plane: the LFC index of every
 // element of a plane is looked up in a table (one byte per element, four per

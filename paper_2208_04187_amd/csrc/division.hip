@@ -41,9 +41,10 @@
 //   compress_plane   planes beyond LDS with vector rows and blocks (video volumes, image-sized maps):
 //                    a workgroup per plane, two vector passes over x
 //   compress_any     everything else (giant planes with odd extents): scalar, slow
-//   decompress_stream / decompress_stream_any: 4-byte elements, one wavefront per 4 KB chunk of aligned vectors, no LDS:
+//   decompress_stream / decompress_stream_any / decompress_stream_one: 4-byte elements, one wavefront per 4 KB chunk of aligned vectors, no LDS:
 //                    rows of whole vectors inside one block (_stream), or any width where a vector may span two rows
-//                    and two planes (_stream_any: each element finds its plane and block, six loads per vector)
+//                    and two planes (_stream_any: each element finds its plane and block, six loads per vector;
+//                    _stream_one: planes that are one block)
 //   decompress_rowvec / _table / _words / _flat / _lane / _scalar: streaming, the packed slice of a
 //                    workgroup staged in LDS, one 16-byte non-temporal store per lane step (_words:
 //                    small planes of odd width, the chunk rebuilt in LDS word by word first)

@@ -777,6 +777,17 @@ int plan_decompress(const Layout& L, int64_t D, int64_t Hs, int64_t W, int B, si
         *grid = (nrounds + rpw - 1) / rpw;
         return 4;
     }
+    // 4-byte elements, one block per plane (not those of the lane kernel above, which measured the same on 7 x 7, nor those of the row-vector stream kernel below): a wavefront per
+    // chunk of aligned vectors, H^L is the plane's
+    if (es == 4 && L.nb == 1 && !(W % 4 == 0 && B % 4 == 0) && L.HW >= 4 && L.HW < (1ull << 24) && L.P < (1ull << 24) && out_vec_aligned &&
+        L.P * L.WPP * 4 < (1ull << 31) && L.P * 8 < (1ull << 31)) {
+        const uint64_t chunk = 256ull * kStreamK;                       // elements
+        const uint64_t ntot = L.P * L.HW;
+        if (fastdiv_ok(L.HW + chunk + 4, L.HW) && (ntot + chunk - 1) / chunk < (1ull << 31) && ntot < (1ull << 42)) {
+            *grid = (uint32_t)((ntot + chunk - 1) / chunk);
+            return 9;
+        }
+    }
     // fast path: rows are whole vectors that sit inside one block
     if (W % 4 == 0 && B % 4 == 0 && small_idx && out_vec_aligned) {
         a->q4 = (uint32_t)(L.HW / 4);
@@ -983,8 +994,9 @@ hipError_t do_decompress(const DecLaunch& c, int b) {
         constexpr int BITS = decltype(bits)::value;
         const int kind = c.kind;
         void (*kern)(DecArgs);
-        if (kind == 7 || kind == 8) {
+        if (kind == 7 || kind == 8 || kind == 9) {
             if (kind == 7) kern = c.flat ? decompress_stream<T, BITS> : decompress_stream_3d<T, BITS>;
+            else if (kind == 9) kern = decompress_stream_one<T, BITS>;
             else kern = c.flat ? decompress_stream_any<T, BITS> : decompress_stream_any_3d<T, BITS>;
             hipLaunchKernelGGL(kern, dim3(c.gx, c.gy), dim3(64), 0, c.st, c.a);
             return hipGetLastError();
@@ -1180,7 +1192,7 @@ int decompress_impl(int count, const void* const* packed, void* const* xhat, siz
         size_t lds = 0;
         if (kind == 4) lds = 4ull * (64ull * L.HW + 4);
         else if (kind == 6) lds = 8ull * ((L.nb + 3) & ~3ull);
-        else if (kind == 7 || kind == 8) lds = 0;
+        else if (kind == 7 || kind == 8 || kind == 9) lds = 0;
         else if (kind == 5) lds = a.out_off + 4ull * ((a.G * L.HW + 3) & ~3ull);
         else if (kind != 2) lds = dec_lds_bytes(L, es, a.G) + (kind == 3 ? 4ull * a.q4 + 16 : 0);
         DecLaunch c{};
@@ -1243,6 +1255,8 @@ int kernel_name_impl(int direction, const void* data, int64_t N, int64_t C, int6
             n = snprintf(out, cap, "decompress_stream%s<%s, %d>", sfx, tn, b);
         else if (kind == 8)
             n = snprintf(out, cap, "decompress_stream_any%s<%s, %d>", sfx, tn, b);
+        else if (kind == 9)
+            n = snprintf(out, cap, "decompress_stream_one<%s, %d>", tn, b);
         else
             n = snprintf(out, cap, "%s%s<%s, %d>", kind == 0 ? "decompress_rowvec" : kind == 3 ? "decompress_table" : kind == 5 ? "decompress_words" : kind == 1 ? "decompress_flat" : kind == 4 ? "decompress_lane" : "decompress_scalar",
                          kind == 4 ? "" : sfx, tn, b);

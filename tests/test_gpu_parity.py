@@ -1011,7 +1011,7 @@ def test_register_kernel_any_width_matches_oracle(shape, B, b, mode):
     assert pkg.division_kernel_name(0, shape, B, b, dtype, c16=mode == "c16").startswith("compress_units<")
     if shape[3] % 2 == 1 and shape[2] * shape[3] >= 512:      # (smaller planes are rebuilt chunk-wise in LDS)
         # (4-byte elements: the wavefront-per-chunk kernel for any width where a plane has several blocks of 4 and more)
-        assert pkg.division_kernel_name(1, shape, B, b, dtype, c16=mode == "c16").startswith(("decompress_units<", "decompress_stream_any<"))
+        assert pkg.division_kernel_name(1, shape, B, b, dtype, c16=mode == "c16").startswith(("decompress_units<", "decompress_stream_any<", "decompress_stream_one<"))
     _check_variant(shape, B, b, mode)
 
 
@@ -1280,14 +1280,22 @@ STREAM_ANY_CASES = [
 ]
 
 
-@pytest.mark.parametrize("shape,B,b", STREAM_ANY_CASES)
+# the same for planes that are one block: H^L is the plane's
+STREAM_ONE_CASES = [
+    ((5, 7, 9, 9), 16, 2), ((3, 67, 7, 10), 16, 4), ((37, 9, 11, 11), 64, 1), ((2, 3, 14, 14), 64, 2), ((3, 5, 16, 16), 18, 8),
+    ((4, 3, 23, 23), 64, 2), ((2, 3, 2, 2), 8, 2), ((9, 5, 1, 50), 64, 4), ((1, 1, 1, 6), 8, 2), ((1, 3, 1, 70), 128, 2),
+    ((7, 9, 5, 6), 8, 2), ((4, 9, 3, 3, 6), 8, 2), ((3, 4, 2, 4, 6), 8, 4),
+]
+
+
+@pytest.mark.parametrize("shape,B,b", STREAM_ANY_CASES + STREAM_ONE_CASES)
 @pytest.mark.parametrize("mode", ["f32", "c16"])
 def test_wavefront_per_chunk_decompress_of_any_width(shape, B, b, mode):
     three = len(shape) == 5
     c16 = mode == "c16"
     dt = oracle.F32_C16 if c16 else oracle.F32
     name = (pkg.division_kernel_name_3d if three else pkg.division_kernel_name)(1, shape, B, b, torch.float32, c16=c16)
-    assert name.startswith("decompress_stream_any"), name
+    assert name.startswith("decompress_stream_one" if (shape, B, b) in STREAM_ONE_CASES else "decompress_stream_any"), name
     numel, guard = int(np.prod(shape)), -777.0
     g = torch.Generator().manual_seed(sum(shape) + B + b)
     x = (torch.randn(shape, generator=g) * 1.5 + 0.2)
