@@ -24,7 +24,7 @@
 //                    or two rows), the round read with coalesced loads and handed out through LDS, extremes by
 //                    DPP, block sums by DPP (B = 8) or through LDS (relu_compress_strip: B = 8 with a Relu
 //                    applied to the round as its loads arrive)
-//   compress_rowstrip  planes of an odd width with an instance (13, 15, 17, 27, 35, 55) under B = 8 (4): the strip
+//   compress_rowstrip  planes of an odd width with an instance (13, 15, 17, 27, 35, 55) under B = 8 or 4: the strip
 //                    kernel with a row per lane; rows start in the middle of an element pair every other time, so a
 //                    lane quantises the pairs its row touches and ORs its code bits into the plane's words in LDS
 //   compress_items   planes of at most 64 pooling items (28x28, 14x14, CIFAR shapes), B = 4, 8: a lane per

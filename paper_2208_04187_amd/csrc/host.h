@@ -359,8 +359,7 @@ hipError_t launch_strip(int width, const StripArgs& a, dim3 grid, size_t lds, hi
 }
 
 // Fills the plan of the row-per-lane strip kernel: 2-D maps of an odd width it has an instance for (13, 15,
-// 17, 27, 35, 55) with at most 16 (13, 15), 32 (17, 27) or 64 rows, under B = 8 (B = 4 too on 13, 15 and 55),
-// 16-byte aligned.
+// 17, 27, 35, 55) with at most 16 (13, 15), 32 (17, 27) or 64 rows, under B = 8 or 4, 16-byte aligned.
 // *width = 100 * W + B names the instance.
 bool plan_rowstrip(const Layout& L, int64_t H, int64_t W, int B, size_t es, const void* x,
                    StripArgs* a, uint32_t* grid, size_t* lds, int* width) {
@@ -370,7 +369,7 @@ bool plan_rowstrip(const Layout& L, int64_t H, int64_t W, int B, size_t es, cons
     else if (W == 17 || W == 27) S = 32;
     else if (W == 35 || W == 55) S = 64;
     else return false;
-    if (!(B == 8 || (B == 4 && (S == 16 || W == 55))) || H < 2 || (uint64_t)H > S) return false;
+    if ((B != 8 && B != 4) || H < 2 || (uint64_t)H > S) return false;
     const uint64_t G = 64 / S;
     if (L.LW != ((uint64_t)W + B - 1) / B) return false;
     a->P = (uint32_t)L.P; a->H = (uint32_t)H; a->HW = (uint32_t)L.HW; a->WPP = (uint32_t)L.WPP; a->nb = (uint32_t)L.nb;
@@ -390,8 +389,11 @@ hipError_t launch_rowstrip(int width, const StripArgs& a, dim3 grid, size_t lds,
         case 1508: kern = compress_rowstrip<T, BITS, 15, 8>; break;
         case 1504: kern = compress_rowstrip<T, BITS, 15, 4>; break;
         case 1708: kern = compress_rowstrip<T, BITS, 17, 8>; break;
+        case 1704: kern = compress_rowstrip<T, BITS, 17, 4>; break;
         case 2708: kern = compress_rowstrip<T, BITS, 27, 8>; break;
+        case 2704: kern = compress_rowstrip<T, BITS, 27, 4>; break;
         case 3508: kern = compress_rowstrip<T, BITS, 35, 8>; break;
+        case 3504: kern = compress_rowstrip<T, BITS, 35, 4>; break;
         case 5508: kern = compress_rowstrip<T, BITS, 55, 8>; break;
         case 5504: kern = compress_rowstrip<T, BITS, 55, 4>; break;
         default: return hipErrorInvalidValue;

@@ -189,7 +189,8 @@ DISPATCH = [
     ((8, 8, 27, 27), 8, 2, "compress_rowstrip<float, 2, 27, 8>", "decompress_stream_any<float, 2>"),
     ((8, 8, 17, 17), 8, 2, "compress_rowstrip<float, 2, 17, 8>", "decompress_stream_any<float, 2>"),
     ((8, 8, 13, 13), 8, 2, "compress_rowstrip<float, 2, 13, 8>", "decompress_stream_any<float, 2>"),
-    ((8, 8, 27, 27), 4, 2, "compress_units<float, 2, 1>", "decompress_stream_any<float, 2>"),
+    ((8, 8, 27, 27), 4, 2, "compress_rowstrip<float, 2, 27, 4>", "decompress_stream_any<float, 2>"),
+    ((8, 8, 29, 29), 4, 2, "compress_units<float, 2, 1>", "decompress_stream_any<float, 2>"),
     ((8, 8, 19, 19), 8, 2, "compress_units<float, 2, 0>", "decompress_stream_any<float, 2>"),
     ((8, 8, 11, 11), 8, 2, "compress_wave<float, 2, 8, 1>", "decompress_stream_any<float, 2>"),
     ((8, 8, 35, 35), 8, 2, "compress_rowstrip<float, 2, 35, 8>", "decompress_stream_any<float, 2>"),
