@@ -56,10 +56,16 @@ __device__ __forceinline__ uint32_t pair_word(uint32_t xw, uint32_t k2) {
 }
 
 // n / d for n*d < 2^32 with m = floor(2^32/d)+1 (m == 0 encodes d == 1)
-struct FastDiv { uint32_t d, m; };
-__device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f) { return f.m ? __umulhi(n, f.m) : n; }
+// Quotient by a runtime divisor d through one multiply-high: exact while numerator * d < 2^32 (the host checks it
+// with fastdiv_ok).  The divisor 1 has no 32-bit multiplier: its m is 0 and `one` is all ones, so that the quotient
+// needs no test (a test on m, uniform as it is, became a scalar branch per division: 13 in decompress_stream, 228
+// in compress_units, each ending a basic block in the middle of the loads; without them decompress_stream runs
+// 1.5-2.5 % faster).  fdiv_tested is the form with the test, kept for the one loop that measured faster with it.
+struct FastDiv { uint32_t one, m; };
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f) { return __umulhi(n, f.m) | (n & f.one); }
+__device__ __forceinline__ uint32_t fdiv_tested(uint32_t n, FastDiv f) { return f.m ? __umulhi(n, f.m) : n; }
 static FastDiv make_fastdiv(uint32_t d) {
-    FastDiv f; f.d = d; f.m = d <= 1 ? 0u : (uint32_t)((1ull << 32) / d) + 1u; return f;
+    FastDiv f; f.one = d <= 1 ? 0xffffffffu : 0u; f.m = d <= 1 ? 0u : (uint32_t)((1ull << 32) / d) + 1u; return f;
 }
 
 // per-plane scale of Eq. (quantization): delta = min, Delta = range/L,
