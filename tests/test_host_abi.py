@@ -147,6 +147,63 @@ def test_layout_of_the_bfloat16_cached_mode_matches_oracle():
     assert pkg.lib().division_packed_bytes(1, 1, 4, 4, 2, 2, 3) == 0           # unknown dtype code
 
 
+def test_layout_matches_oracle_over_a_seeded_grid_of_shapes():
+    """The two layouts are typed independently (csrc/host.h, oracle/division_oracle.c): 2-D and 3-D maps, every code
+    width incl. 1 bit, the three cache formats, block sizes below, at and above the extents."""
+    import numpy as np
+    import torch
+    rng = np.random.default_rng(20220808)
+    fmts = [(torch.float32, False, oracle.F32), (torch.bfloat16, False, oracle.BF16), (torch.float32, True, oracle.F32_C16)]
+    for _ in range(1500):
+        N, C = int(rng.integers(1, 70)), int(rng.integers(1, 300))
+        H, W = int(rng.integers(1, 240)), int(rng.integers(1, 240))
+        B = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 18, 64, 300]))
+        b = int(rng.choice([1, 2, 4, 8]))
+        tdt, c16, odt = fmts[int(rng.integers(0, 3))]
+        if rng.random() < 0.3:
+            D = int(rng.integers(2, 20))
+            assert pkg.division_packed_bytes_3d(N, C, D, H, W, B, b, tdt, c16) == oracle.packed_bytes_3d(N, C, D, H, W, B, b, odt)
+            assert pkg.division_packed_layout_3d(N, C, D, H, W, B, b, tdt, c16) == oracle.packed_layout_3d(N, C, D, H, W, B, b, odt)
+        else:
+            assert pkg.division_packed_bytes(N, C, H, W, B, b, tdt, c16) == oracle.packed_bytes(N, C, H, W, B, b, odt)
+            assert pkg.division_packed_layout(N, C, H, W, B, b, tdt, c16) == oracle.packed_layout(N, C, H, W, B, b, odt)
+
+
+def test_the_planner_names_a_kernel_for_every_shape_of_a_seeded_grid():
+    """Host-side only: for every valid shape, code width, format and pointer alignment the planner answers with a
+    kernel of a known family whose template arguments carry the code width asked for."""
+    import numpy as np
+    import torch
+    rng = np.random.default_rng(4187)
+    comp = {"compress_regs", "compress_regs_3d", "compress_lane", "compress_line", "compress_strip", "compress_rowstrip",
+            "compress_items", "compress_units", "compress_wave", "compress_tile", "compress_one", "compress_rows",
+            "compress_rows_3d", "compress_plane", "compress_plane_3d", "compress_any", "compress_any_3d"}
+    dec = {"decompress_stream", "decompress_stream_3d", "decompress_stream_any", "decompress_stream_any_3d",
+           "decompress_stream_one", "decompress_rowvec", "decompress_rowvec_3d", "decompress_table", "decompress_units",
+           "decompress_words", "decompress_words_3d", "decompress_flat", "decompress_flat_3d", "decompress_lane",
+           "decompress_scalar", "decompress_scalar_3d"}
+    seen = set()
+    for _ in range(4000):
+        N, C = int(rng.integers(1, 40)), int(rng.integers(1, 100))
+        H, W = int(rng.integers(1, 200)), int(rng.integers(1, 200))
+        if rng.random() < 0.3:
+            H = W = int(rng.choice([4, 7, 8, 13, 14, 16, 17, 27, 28, 32, 35, 55, 56, 73, 112, 147]))
+        B = int(rng.choice([1, 2, 3, 4, 8, 8, 12, 16, 18, 64]))
+        b = int(rng.choice([1, 2, 4, 8]))
+        tdt, c16 = [(torch.float32, False), (torch.bfloat16, False), (torch.float32, True)][int(rng.integers(0, 3))]
+        ptr = int(rng.choice([0, 256, 260, 258])) if tdt == torch.bfloat16 else int(rng.choice([0, 256, 260]))
+        three = rng.random() < 0.25
+        shape = (N, C, int(rng.integers(2, 12)), H, W) if three else (N, C, H, W)
+        kn = pkg.division_kernel_name_3d if three else pkg.division_kernel_name
+        for direction, families in ((0, comp), (1, dec)):
+            name = kn(direction, shape, B, b, tdt, data_ptr=ptr, c16=c16)
+            family, args = name.split("<", 1)
+            assert family in families, name
+            assert args.split(", ")[1].rstrip(">") == str(b), name
+            seen.add(family)
+    assert len(seen) >= 28, sorted(seen)
+
+
 # which kernel the host picks for a shape (a host-side decision: no GPU needed to ask)
 DISPATCH = [
     # shape, B, b, compress kernel, decompress kernel (fp32)
